@@ -1,0 +1,123 @@
+/*
+ * mcnconv -- the convolution block of the MatConvNet manual (arXiv 1412.4564,
+ * function vl_nnconv) for AMD MI355X (gfx950): forward and backward.
+ *
+ * Conventions shared by every entry point
+ * ---------------------------------------
+ * Arrays.  The manual's 4-D arrays are stored FIRST INDEX FASTEST (the vec()
+ * order of Sec. 2.3.1), fp32:
+ *     x    : H  x W  x D  x N     x[i,j,d,n]   at  i + H *(j + W *(d + D *n))
+ *     w    : H' x W' x D' x D''   w[i',j',d',k] at i'+ H'*(j'+ W'*(d'+ D'*k))
+ *     y    : H''x W''x D''x N     (same rule; D'' is called K below)
+ *     b    : K values
+ * Derivative arrays (dzdx, dzdw, dzdb, dzdy) have the shape of what they
+ * differentiate (Sec. 4, introduction).
+ *
+ * Geometry (Sec. 4.1).  stride = (S_h, S_w) vertical then horizontal; pads =
+ * (top, bottom, left, right), any value >= 0; H'' = floor((H - H' + top +
+ * bottom)/S_h) + 1 and likewise W''.  Filter groups: D' must divide D, giving
+ * g = D/D' groups; K must be a multiple of g; filters m*K/g .. (m+1)*K/g - 1
+ * form group m and read input channels m*D' .. (m+1)*D' - 1.
+ *
+ * Pointers.  EVERY data pointer (x, w, b, y, dzdy, dzdx, dzdw, dzdb, ws) is a
+ * DEVICE pointer owned by the caller, 16-byte aligned (any hipMalloc or
+ * PyTorch allocation is).  The descriptor and the int32 out-parameters are
+ * HOST pointers.  `stream` is a hipStream_t passed as void* (NULL = the null
+ * stream).  The library allocates no device memory, keeps no state between
+ * calls, never synchronises, and launches all work on `stream`.
+ *
+ * Workspace.  Each operation may need scratch memory: ask
+ * mcn_conv_workspace_size() and pass a buffer of at least that many bytes
+ * (ws may be NULL when the size is 0).  Its contents are garbage afterwards.
+ *
+ * Results are WRITTEN, never accumulated into (the manual's blocks return
+ * derivatives; summing them along a network is the caller's business,
+ * Sec. 2.3.3).  Inputs are not modified.  Outputs must not overlap inputs.
+ *
+ * Errors.  Every function returns an mcn_status; 0 is success.  All argument
+ * and geometry checks happen on the host before anything is launched, so a
+ * failed call has done no GPU work.  Nothing prints, throws or aborts.
+ */
+#ifndef MCNCONV_H
+#define MCNCONV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct mcn_conv_desc {
+    int32_t H, W, D, N;         /* x : H x W x D x N                               */
+    int32_t Hf, Wf, Df, K;      /* w : H' x W' x D' x K;  groups g = D / Df         */
+    int32_t stride_h, stride_w; /* S_h, S_w >= 1                                    */
+    int32_t pad_top, pad_bottom, pad_left, pad_right; /* P_h^-, P_h^+, P_w^-, P_w^+ */
+    int32_t precision;          /* MCN_PREC_FP32 or MCN_PREC_BF16                   */
+} mcn_conv_desc;
+
+enum { MCN_PREC_FP32 = 0,   /* fp32 operands, fp32 accumulation                        */
+       MCN_PREC_BF16 = 1 }; /* operands rounded to bf16 on chip, fp32 accumulation;
+                               arrays in memory stay fp32                              */
+
+typedef enum mcn_status {
+    MCN_OK = 0,
+    MCN_BAD_ARG = 1,             /* NULL descriptor/pointer, dim < 1, stride < 1, pad < 0,
+                                    unknown precision or operation                      */
+    MCN_BAD_GROUPS = 2,          /* Df does not divide D, or D/Df does not divide K     */
+    MCN_FILTER_TOO_LARGE = 3,    /* H + top + bottom < H'  or  W + left + right < W'
+                                    (Sec. 4.1: "otherwise an error is thrown")          */
+    MCN_WORKSPACE_TOO_SMALL = 4,
+    MCN_UNSUPPORTED = 5,         /* an array has 2^31 elements or more                  */
+    MCN_HIP_ERROR = 6            /* a launch failed; see mcn_last_hip_error()           */
+} mcn_status;
+
+enum { MCN_OP_FORWARD = 0, MCN_OP_BACKWARD_DATA = 1, MCN_OP_BACKWARD_FILTER = 2, MCN_OP_BACKWARD_BIAS = 3 };
+
+/* Sec. 4.1 "Output size" (derived in Sec. 5.2): writes H'' and W''.
+ * Validates the whole descriptor; Ho / Wo may be NULL.  Host only. */
+int mcn_conv_output_size(const mcn_conv_desc *desc, int32_t *Ho, int32_t *Wo);
+
+/* Bytes of scratch that operation `op` (MCN_OP_*) needs for this descriptor.
+ * Returns an mcn_status; the size is written to *bytes.  Host only. */
+int mcn_conv_workspace_size(const mcn_conv_desc *desc, int op, size_t *bytes);
+
+/* Sec. 4.1, "Padding and stride":
+ *   y[i'',j'',k,n] = b[k] + sum_{i',j',d'} w[i',j',d',k] *
+ *                    x[S_h(i''-1)+i'-top, S_w(j''-1)+j'-left, group(k)*D'+d', n]
+ * with x read as zero outside its support.  b == NULL means no bias
+ * (the manual's vl_nnconv(x,f,[])).  Writes all of y. */
+int mcn_conv_forward(const mcn_conv_desc *desc, const float *x, const float *w, const float *b,
+                     float *y, void *ws, size_t ws_bytes, void *stream);
+
+/* Sec. 2.3.2 eq. (projected) applied to the sum above; Sec. 6.1 boxed formula
+ * dz/dX = phi*(dz/dY F^T):  dzdx = d<dzdy, y>/dx.  Samples of x that no filter
+ * window reads get exactly 0.  Writes all of dzdx. */
+int mcn_conv_backward_data(const mcn_conv_desc *desc, const float *w, const float *dzdy,
+                           float *dzdx, void *ws, size_t ws_bytes, void *stream);
+
+/* Sec. 6.1 boxed formula dz/dF = phi(x)^T dz/dY, summed over the batch:
+ * dzdw = d<dzdy, y>/dw.  Writes all of dzdw. */
+int mcn_conv_backward_filter(const mcn_conv_desc *desc, const float *x, const float *dzdy,
+                             float *dzdw, void *ws, size_t ws_bytes, void *stream);
+
+/* y is affine in b with coefficient one, so
+ * dzdb[k] = sum_{i'',j'',n} dzdy[i'',j'',k,n].  Writes K values. */
+int mcn_conv_backward_bias(const mcn_conv_desc *desc, const float *dzdy, float *dzdb,
+                           void *ws, size_t ws_bytes, void *stream);
+
+/* Static description of a status code. */
+const char *mcn_status_string(int status);
+
+/* The hipError_t (as int) behind the most recent MCN_HIP_ERROR of this thread, else 0. */
+int mcn_last_hip_error(void);
+
+/* Name of the kernel family the dispatcher picks for this descriptor and
+ * operation ("direct", "igemm", ...); for reports and tests.  Returns NULL on a bad
+ * descriptor.  Host only. */
+const char *mcn_conv_kernel_name(const mcn_conv_desc *desc, int op);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MCNCONV_H */

@@ -147,10 +147,11 @@ int orc_forward_at(const orc_geom *g, const double *x, const double *f,
     return ORC_OK;
 }
 
-/* dzdx = d<dzdy, y>/dx.  The same loops as the forward sum; each product
- * f * x in y[io,jo,k,n] contributes f * dzdy[io,jo,k,n] to that x's
- * derivative.  Samples of x that no window reaches stay exactly zero.
- * Threads split the batch, so no two write one element. */
+/* dzdx = d<dzdy, y>/dx.  The same terms as the forward sum: each product
+ * f * x inside y[io,jo,k,n] contributes f * dzdy[io,jo,k,n] to the derivative
+ * of that x (scatter form).  Samples of x that no window reaches stay exactly
+ * zero.  The loops are ordered so that one thread owns one (channel, image)
+ * plane of dzdx, so no two threads write one element. */
 int orc_backward_data(const orc_geom *g, const double *f, const double *dzdy,
                       double *dzdx) {
     int32_t Ho, Wo;
@@ -159,23 +160,24 @@ int orc_backward_data(const orc_geom *g, const double *f, const double *dzdy,
     if (!f || !dzdy || !dzdx) return ORC_BAD_ARG;
     const int Kg = g->K / (g->D / g->Df);
     memset(dzdx, 0, sizeof(double) * (size_t)g->H * g->W * g->D * g->N);
+    const int64_t planes = (int64_t)g->N * g->D;
 #pragma omp parallel for schedule(dynamic, 1)
-    for (int n = 0; n < g->N; ++n)
-        for (int k = 0; k < g->K; ++k) {
-            const int grp = k / Kg;
+    for (int64_t t = 0; t < planes; ++t) {
+        const int n = (int)(t / g->D), d = (int)(t % g->D);
+        const int grp = d / g->Df, fd = d % g->Df;   /* d = grp * Df + fd */
+        for (int k = grp * Kg; k < (grp + 1) * Kg; ++k)   /* the filters that read channel d */
             for (int jo = 0; jo < Wo; ++jo)
                 for (int io = 0; io < Ho; ++io) {
                     const double p = dzdy[YADDR(io, jo, k, n)];
-                    for (int fd = 0; fd < g->Df; ++fd)
-                        for (int fj = 0; fj < g->Wf; ++fj)
-                            for (int fi = 0; fi < g->Hf; ++fi) {
-                                int i = g->Sh * io + fi - g->Pt;
-                                int j = g->Sw * jo + fj - g->Pl;
-                                if (i < 0 || i >= g->H || j < 0 || j >= g->W) continue;
-                                dzdx[XADDR(i, j, grp * g->Df + fd, n)] += f[FADDR(fi, fj, fd, k)] * p;
-                            }
+                    for (int fj = 0; fj < g->Wf; ++fj)
+                        for (int fi = 0; fi < g->Hf; ++fi) {
+                            int i = g->Sh * io + fi - g->Pt;
+                            int j = g->Sw * jo + fj - g->Pl;
+                            if (i < 0 || i >= g->H || j < 0 || j >= g->W) continue;
+                            dzdx[XADDR(i, j, d, n)] += f[FADDR(fi, fj, fd, k)] * p;
+                        }
                 }
-        }
+    }
     return ORC_OK;
 }
 

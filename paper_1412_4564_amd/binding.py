@@ -1,0 +1,217 @@
+"""ctypes binding of libmcnconv.so: the same names as include/mcnconv.h.
+
+Argument marshalling only -- every step of the convolution runs in the HIP
+kernels behind the C ABI.  There is no CPU fallback: if the library is not
+built, importing this module's functions raises.
+
+Tensor convention: the manual's H x W x D x N arrays are first-index-fastest,
+which is the memory order of a contiguous torch tensor of shape (N, D, W, H).
+So x is (N,D,W,H), w is (K,Df,Wf,Hf), y and dzdy are (N,K,Wo,Ho), b is (K,).
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmcnconv.so")
+
+MCN_OK, MCN_BAD_ARG, MCN_BAD_GROUPS, MCN_FILTER_TOO_LARGE = 0, 1, 2, 3
+MCN_WORKSPACE_TOO_SMALL, MCN_UNSUPPORTED, MCN_HIP_ERROR = 4, 5, 6
+MCN_OP_FORWARD, MCN_OP_BACKWARD_DATA, MCN_OP_BACKWARD_FILTER, MCN_OP_BACKWARD_BIAS = 0, 1, 2, 3
+MCN_PREC_FP32, MCN_PREC_BF16 = 0, 1
+
+EXPORTS = (
+    "mcn_conv_output_size", "mcn_conv_workspace_size", "mcn_conv_forward", "mcn_conv_backward_data",
+    "mcn_conv_backward_filter", "mcn_conv_backward_bias", "mcn_status_string", "mcn_last_hip_error",
+    "mcn_conv_kernel_name",
+)
+
+
+class mcn_conv_desc(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in (
+        "H", "W", "D", "N", "Hf", "Wf", "Df", "K", "stride_h", "stride_w",
+        "pad_top", "pad_bottom", "pad_left", "pad_right", "precision")]
+
+
+class McnError(RuntimeError):
+    def __init__(self, status, where=""):
+        self.status = int(status)
+        msg = lib().mcn_status_string(self.status).decode()
+        if self.status == MCN_HIP_ERROR:
+            msg += " (hipError %d)" % lib().mcn_last_hip_error()
+        super().__init__("%s: %s" % (where, msg) if where else msg)
+
+
+_lib = None
+
+
+def lib():
+    """Load libmcnconv.so (built by paper_1412_4564_amd.build); fails loudly if absent."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError("%s is not built: run `python -m paper_1412_4564_amd.build`" % LIB_PATH)
+        # PyTorch bundles its own HIP runtime under the same soname.  Import it first so that
+        # this library binds to the runtime that owns the tensors and streams it is handed;
+        # the other order leaves two runtimes in the process and launches fail with "no device".
+        import torch  # noqa: F401
+        L = ctypes.CDLL(LIB_PATH)
+        D = ctypes.POINTER(mcn_conv_desc)
+        P, SZ, I32P = ctypes.c_void_p, ctypes.c_size_t, ctypes.POINTER(ctypes.c_int32)
+        L.mcn_conv_output_size.argtypes = [D, I32P, I32P]
+        L.mcn_conv_workspace_size.argtypes = [D, ctypes.c_int, ctypes.POINTER(SZ)]
+        L.mcn_conv_forward.argtypes = [D, P, P, P, P, P, SZ, P]
+        L.mcn_conv_backward_data.argtypes = [D, P, P, P, P, SZ, P]
+        L.mcn_conv_backward_filter.argtypes = [D, P, P, P, P, SZ, P]
+        L.mcn_conv_backward_bias.argtypes = [D, P, P, P, SZ, P]
+        L.mcn_status_string.argtypes = [ctypes.c_int]
+        L.mcn_status_string.restype = ctypes.c_char_p
+        L.mcn_last_hip_error.restype = ctypes.c_int
+        L.mcn_conv_kernel_name.argtypes = [D, ctypes.c_int]
+        L.mcn_conv_kernel_name.restype = ctypes.c_char_p
+        for f in ("mcn_conv_output_size", "mcn_conv_workspace_size", "mcn_conv_forward",
+                  "mcn_conv_backward_data", "mcn_conv_backward_filter", "mcn_conv_backward_bias"):
+            getattr(L, f).restype = ctypes.c_int
+        _lib = L
+    return _lib
+
+
+def make_desc(xshape, wshape, stride=(1, 1), pad=(0, 0, 0, 0), precision=MCN_PREC_FP32):
+    """Descriptor from tensor shapes x (N,D,W,H), w (K,Df,Wf,Hf), stride (Sh,Sw), pad (t,b,l,r)."""
+    N, D, W, H = (int(v) for v in xshape)
+    K, Df, Wf, Hf = (int(v) for v in wshape)
+    return mcn_conv_desc(H, W, D, N, Hf, Wf, Df, K, int(stride[0]), int(stride[1]),
+                         int(pad[0]), int(pad[1]), int(pad[2]), int(pad[3]), int(precision))
+
+
+# ---- raw calls: same names and argument order as the C header; pointers are ints ----
+def mcn_conv_output_size(desc):
+    ho, wo = ctypes.c_int32(0), ctypes.c_int32(0)
+    st = lib().mcn_conv_output_size(ctypes.byref(desc), ctypes.byref(ho), ctypes.byref(wo))
+    if st:
+        raise McnError(st, "mcn_conv_output_size")
+    return ho.value, wo.value
+
+
+def mcn_conv_workspace_size(desc, op):
+    n = ctypes.c_size_t(0)
+    st = lib().mcn_conv_workspace_size(ctypes.byref(desc), int(op), ctypes.byref(n))
+    if st:
+        raise McnError(st, "mcn_conv_workspace_size")
+    return int(n.value)
+
+
+def mcn_conv_kernel_name(desc, op):
+    s = lib().mcn_conv_kernel_name(ctypes.byref(desc), int(op))
+    return None if s is None else s.decode()
+
+
+def mcn_conv_forward(desc, x, w, b, y, ws, ws_bytes, stream):
+    return lib().mcn_conv_forward(ctypes.byref(desc), x, w, b, y, ws, ws_bytes, stream)
+
+
+def mcn_conv_backward_data(desc, w, dzdy, dzdx, ws, ws_bytes, stream):
+    return lib().mcn_conv_backward_data(ctypes.byref(desc), w, dzdy, dzdx, ws, ws_bytes, stream)
+
+
+def mcn_conv_backward_filter(desc, x, dzdy, dzdw, ws, ws_bytes, stream):
+    return lib().mcn_conv_backward_filter(ctypes.byref(desc), x, dzdy, dzdw, ws, ws_bytes, stream)
+
+
+def mcn_conv_backward_bias(desc, dzdy, dzdb, ws, ws_bytes, stream):
+    return lib().mcn_conv_backward_bias(ctypes.byref(desc), dzdy, dzdb, ws, ws_bytes, stream)
+
+
+# ---- tensor-level helpers: allocate outputs / workspace with torch, pass pointers ----
+def _check(t, shape, name):
+    import torch
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == torch.float32 and t.is_contiguous()):
+        raise TypeError("%s must be a contiguous fp32 CUDA tensor" % name)
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise ValueError("%s has shape %r, expected %r" % (name, tuple(t.shape), tuple(shape)))
+
+
+def _stream():
+    import torch
+    return torch.cuda.current_stream().cuda_stream
+
+
+class Workspace:
+    """A reusable device scratch buffer (grown on demand, never shrunk)."""
+
+    def __init__(self):
+        self.buf = None
+
+    def get(self, nbytes, device):
+        import torch
+        if nbytes == 0:
+            return None, 0
+        if self.buf is None or self.buf.numel() < nbytes or self.buf.device != device:
+            self.buf = torch.empty(nbytes, dtype=torch.uint8, device=device)
+        return self.buf.data_ptr(), self.buf.numel()
+
+
+_default_ws = Workspace()
+
+
+def conv_forward(x, w, b=None, stride=(1, 1), pad=(0, 0, 0, 0), precision=MCN_PREC_FP32, out=None, workspace=None):
+    import torch
+    _check(x, None, "x"); _check(w, None, "w")
+    desc = make_desc(x.shape, w.shape, stride, pad, precision)
+    ho, wo = mcn_conv_output_size(desc)
+    if b is not None:
+        _check(b, (w.shape[0],), "b")
+    ysh = (x.shape[0], w.shape[0], wo, ho)
+    y = out if out is not None else torch.empty(ysh, dtype=torch.float32, device=x.device)
+    _check(y, ysh, "out")
+    wsp, wsn = (workspace or _default_ws).get(mcn_conv_workspace_size(desc, MCN_OP_FORWARD), x.device)
+    st = mcn_conv_forward(desc, x.data_ptr(), w.data_ptr(), None if b is None else b.data_ptr(), y.data_ptr(),
+                          wsp, wsn, _stream())
+    if st:
+        raise McnError(st, "mcn_conv_forward")
+    return y
+
+
+def conv_backward_data(xshape, w, dzdy, stride=(1, 1), pad=(0, 0, 0, 0), precision=MCN_PREC_FP32, out=None, workspace=None):
+    import torch
+    _check(w, None, "w")
+    desc = make_desc(xshape, w.shape, stride, pad, precision)
+    ho, wo = mcn_conv_output_size(desc)
+    _check(dzdy, (xshape[0], w.shape[0], wo, ho), "dzdy")
+    dzdx = out if out is not None else torch.empty(tuple(xshape), dtype=torch.float32, device=w.device)
+    _check(dzdx, tuple(xshape), "out")
+    wsp, wsn = (workspace or _default_ws).get(mcn_conv_workspace_size(desc, MCN_OP_BACKWARD_DATA), w.device)
+    st = mcn_conv_backward_data(desc, w.data_ptr(), dzdy.data_ptr(), dzdx.data_ptr(), wsp, wsn, _stream())
+    if st:
+        raise McnError(st, "mcn_conv_backward_data")
+    return dzdx
+
+
+def conv_backward_filter(x, wshape, dzdy, stride=(1, 1), pad=(0, 0, 0, 0), precision=MCN_PREC_FP32, out=None, workspace=None):
+    import torch
+    _check(x, None, "x")
+    desc = make_desc(x.shape, wshape, stride, pad, precision)
+    ho, wo = mcn_conv_output_size(desc)
+    _check(dzdy, (x.shape[0], wshape[0], wo, ho), "dzdy")
+    dzdw = out if out is not None else torch.empty(tuple(wshape), dtype=torch.float32, device=x.device)
+    _check(dzdw, tuple(wshape), "out")
+    wsp, wsn = (workspace or _default_ws).get(mcn_conv_workspace_size(desc, MCN_OP_BACKWARD_FILTER), x.device)
+    st = mcn_conv_backward_filter(desc, x.data_ptr(), dzdy.data_ptr(), dzdw.data_ptr(), wsp, wsn, _stream())
+    if st:
+        raise McnError(st, "mcn_conv_backward_filter")
+    return dzdw
+
+
+def conv_backward_bias(xshape, wshape, dzdy, stride=(1, 1), pad=(0, 0, 0, 0), out=None, workspace=None):
+    import torch
+    desc = make_desc(xshape, wshape, stride, pad)
+    ho, wo = mcn_conv_output_size(desc)
+    _check(dzdy, (xshape[0], wshape[0], wo, ho), "dzdy")
+    dzdb = out if out is not None else torch.empty((wshape[0],), dtype=torch.float32, device=dzdy.device)
+    _check(dzdb, (wshape[0],), "out")
+    wsp, wsn = (workspace or _default_ws).get(mcn_conv_workspace_size(desc, MCN_OP_BACKWARD_BIAS), dzdy.device)
+    st = mcn_conv_backward_bias(desc, dzdy.data_ptr(), dzdb.data_ptr(), wsp, wsn, _stream())
+    if st:
+        raise McnError(st, "mcn_conv_backward_bias")
+    return dzdb

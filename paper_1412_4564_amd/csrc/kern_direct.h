@@ -1,0 +1,155 @@
+// Direct (one result per thread / per wave) kernels: the general fallback that
+// accepts every geometry.  They evaluate the sums of Sec. 4.1 of the MatConvNet
+// manual (arXiv 1412.4564) and their adjoints (Sec. 2.3.2, Sec. 6.1) term by
+// term in fp32.  Lanes run along the first (fastest) array index so that global
+// accesses are coalesced.
+#pragma once
+#include <hip/hip_runtime.h>
+#include "geom.h"
+
+namespace mcn {
+
+// y[io,jo,k,n] = b[k] + sum w[fi,fj,fd,k] * x[Sh*io+fi-Pt, Sw*jo+fj-Pl, grp*Df+fd, n]
+__global__ __launch_bounds__(256) void direct_forward_kernel(Geom g, const float *__restrict__ x,
+                                                             const float *__restrict__ w,
+                                                             const float *__restrict__ b,
+                                                             float *__restrict__ y, int total) {
+    int idx = blockIdx.x * 256 + threadIdx.x;
+    if (idx >= total) return;
+    int io = idx % g.Ho;
+    int t = idx / g.Ho;
+    int jo = t % g.Wo;
+    t /= g.Wo;
+    int k = t % g.K;
+    int n = t / g.K;
+    const int grp = k / g.Kg;
+    const float *wk = w + (size_t)k * g.Hf * g.Wf * g.Df;
+    const float *xn = x + ((size_t)n * g.D + (size_t)grp * g.Df) * g.H * g.W;
+    const int i0 = g.Sh * io - g.Pt, j0 = g.Sw * jo - g.Pl;
+    float acc = b ? b[k] : 0.f;
+    for (int fd = 0; fd < g.Df; ++fd) {
+        for (int fj = 0; fj < g.Wf; ++fj) {
+            int j = j0 + fj;
+            if (j < 0 || j >= g.W) continue;
+            for (int fi = 0; fi < g.Hf; ++fi) {
+                int i = i0 + fi;
+                if (i < 0 || i >= g.H) continue;
+                acc = fmaf(wk[fi + g.Hf * (fj + g.Wf * fd)], xn[i + g.H * (j + (size_t)g.W * fd)], acc);
+            }
+        }
+    }
+    y[idx] = acc;
+}
+
+// dzdx[i,j,d,n] = sum over k in group(d), and all (io,fi), (jo,fj) with
+// Sh*io+fi-Pt = i, Sw*jo+fj-Pl = j, of w[fi,fj,fd,k] * dzdy[io,jo,k,n].
+__global__ __launch_bounds__(256) void direct_backward_data_kernel(Geom g, const float *__restrict__ w,
+                                                                   const float *__restrict__ dzdy,
+                                                                   float *__restrict__ dzdx, int total) {
+    int idx = blockIdx.x * 256 + threadIdx.x;
+    if (idx >= total) return;
+    int i = idx % g.H;
+    int t = idx / g.H;
+    int j = t % g.W;
+    t /= g.W;
+    int d = t % g.D;
+    int n = t / g.D;
+    const int grp = d / g.Df, fd = d % g.Df;
+    const size_t ysz = (size_t)g.Ho * g.Wo;
+    float acc = 0.f;
+    for (int kk = 0; kk < g.Kg; ++kk) {
+        const int k = grp * g.Kg + kk;
+        const float *wk = w + ((size_t)k * g.Df + fd) * g.Hf * g.Wf;
+        const float *pk = dzdy + ((size_t)n * g.K + k) * ysz;
+        for (int fj = 0; fj < g.Wf; ++fj) {
+            int tj = j + g.Pl - fj;
+            if (tj < 0) break;            // tj only decreases with fj
+            int jo = tj / g.Sw;
+            if (tj - jo * g.Sw != 0 || jo >= g.Wo) continue;
+            for (int fi = 0; fi < g.Hf; ++fi) {
+                int ti = i + g.Pt - fi;
+                if (ti < 0) break;
+                int io = ti / g.Sh;
+                if (ti - io * g.Sh != 0 || io >= g.Ho) continue;
+                acc = fmaf(wk[fi + g.Hf * fj], pk[io + (size_t)g.Ho * jo], acc);
+            }
+        }
+    }
+    dzdx[idx] = acc;
+}
+
+__device__ inline float wave_sum(float v) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, 64);
+    return v;
+}
+
+// One wavefront per filter coefficient:
+// dzdw[fi,fj,fd,k] = sum_{n,jo,io} x[Sh*io+fi-Pt, Sw*jo+fj-Pl, grp*Df+fd, n] * dzdy[io,jo,k,n]
+__global__ __launch_bounds__(256) void direct_backward_filter_kernel(Geom g, const float *__restrict__ x,
+                                                                     const float *__restrict__ dzdy,
+                                                                     float *__restrict__ dzdw, int total) {
+    const int lane = threadIdx.x & 63;
+    int e = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (e >= total) return;                 // whole wave leaves together
+    int fi = e % g.Hf;
+    int t = e / g.Hf;
+    int fj = t % g.Wf;
+    t /= g.Wf;
+    int fd = t % g.Df;
+    int k = t / g.Df;
+    const int grp = k / g.Kg;
+    // valid io range: 0 <= Sh*io + fi - Pt < H
+    int lo_i = g.Pt - fi;  lo_i = lo_i > 0 ? (lo_i + g.Sh - 1) / g.Sh : 0;
+    int hi_i = g.H - 1 + g.Pt - fi;  hi_i = hi_i < 0 ? -1 : hi_i / g.Sh;  if (hi_i > g.Ho - 1) hi_i = g.Ho - 1;
+    int lo_j = g.Pl - fj;  lo_j = lo_j > 0 ? (lo_j + g.Sw - 1) / g.Sw : 0;
+    int hi_j = g.W - 1 + g.Pl - fj;  hi_j = hi_j < 0 ? -1 : hi_j / g.Sw;  if (hi_j > g.Wo - 1) hi_j = g.Wo - 1;
+    float acc = 0.f;
+    for (int n = 0; n < g.N; ++n) {
+        const float *xc = x + ((size_t)n * g.D + (size_t)grp * g.Df + fd) * g.H * g.W;
+        const float *pc = dzdy + ((size_t)n * g.K + k) * g.Ho * g.Wo;
+        for (int jo = lo_j; jo <= hi_j; ++jo) {
+            const float *xr = xc + (size_t)g.H * (g.Sw * jo + fj - g.Pl) + (fi - g.Pt);
+            const float *pr = pc + (size_t)g.Ho * jo;
+            for (int io = lo_i + lane; io <= hi_i; io += 64) acc = fmaf(xr[g.Sh * io], pr[io], acc);
+        }
+    }
+    acc = wave_sum(acc);
+    if (lane == 0) dzdw[e] = acc;
+}
+
+// ---- bias derivative: dzdb[k] = sum_{n,jo,io} dzdy[io,jo,k,n] ------------------
+// Stage 1: block (k, s) sums the units u = s, s+S, ... where unit u = (n, chunk c)
+// covers dzdy[c*CH .. min((c+1)*CH, HoWo)) of image n, filter k.  Stage 2 adds the S
+// partials of each k in a fixed order, so the result does not depend on scheduling.
+constexpr int BIAS_CHUNK = 4096;
+
+__global__ __launch_bounds__(256) void bias_partial_kernel(const float *__restrict__ dzdy, float *__restrict__ part,
+                                                           int HoWo, int K, int N, int chunks, int S) {
+    const int k = blockIdx.x, s = blockIdx.y;
+    const int units = N * chunks;
+    float acc = 0.f;
+    for (int u = s; u < units; u += S) {
+        const int n = u / chunks, c = u - n * chunks;
+        const float *p = dzdy + ((size_t)n * K + k) * HoWo;
+        const int lo = c * BIAS_CHUNK;
+        const int hi = min(lo + BIAS_CHUNK, HoWo);
+        for (int e = lo + threadIdx.x; e < hi; e += 256) acc += p[e];
+    }
+    __shared__ float red[4];
+    acc = wave_sum(acc);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) part[(size_t)k * S + s] = (red[0] + red[1]) + (red[2] + red[3]);
+}
+
+__global__ __launch_bounds__(256) void bias_final_kernel(const float *__restrict__ part, float *__restrict__ dzdb,
+                                                         int K, int S) {
+    int k = blockIdx.x * 256 + threadIdx.x;
+    if (k >= K) return;
+    float acc = 0.f;
+    for (int s = 0; s < S; ++s) acc += part[(size_t)k * S + s];
+    dzdb[k] = acc;
+}
+
+}  // namespace mcn

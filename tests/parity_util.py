@@ -1,0 +1,119 @@
+"""Shared helpers for the GPU-vs-oracle parity tests (test code only)."""
+import numpy as np
+import torch
+
+import oracle
+from paper_1412_4564_amd import binding as B
+from paper_1412_4564_amd import synth
+
+TOL_FWD = 1e-4      # fp32 forward
+TOL_BWD = 1e-3      # fp32 backward passes
+TOL_BF16 = 1e-2     # bf16-operand variant
+
+
+def norm_err(got, ref, den):
+    """max |got-ref| / den, where den is the same operator applied to absolute
+    values (the sum of |w||x| over each result's receptive field).  Where den is 0 the
+    result is structurally zero and must match exactly."""
+    got = np.asarray(got, dtype=np.float64).ravel()
+    ref = np.asarray(ref, dtype=np.float64).ravel()
+    den = np.asarray(den, dtype=np.float64).ravel()
+    assert got.shape == ref.shape == den.shape
+    assert np.all(np.isfinite(got)), "non-finite values in GPU result"
+    zero = den == 0
+    if zero.any():
+        assert np.all(got[zero] == 0.0), "structurally-zero results must be exactly 0"
+    nz = ~zero
+    if not nz.any():
+        return 0.0
+    return float(np.max(np.abs(got[nz] - ref[nz]) / den[nz]))
+
+
+def layer_args(L):
+    return dict(stride=L["stride"], pad=L["pad"])
+
+
+def gpu(t):
+    return t.cuda()
+
+
+def np64(t):
+    return t.numpy().astype(np.float64)
+
+
+def sample_idx(total, count, seed):
+    rng = np.random.default_rng(seed)
+    if total <= count:
+        return np.arange(total, dtype=np.int64)
+    idx = rng.choice(total, size=count, replace=False).astype(np.int64)
+    # always include the very first and last elements (tile corners / ragged tails)
+    idx[0], idx[1] = 0, total - 1
+    return idx
+
+
+def run_layer_full(L, precision=B.MCN_PREC_FP32, with_bias=True, seed=0):
+    """All four operations on layer L, every element compared.  Returns dict of errors."""
+    st, pad = L["stride"], L["pad"]
+    x, w, b = synth.make_x(L, seed), synth.make_w(L, seed), synth.make_b(L, seed)
+    ho, wo = oracle.output_size(x.shape, w.shape, st, pad)
+    p = synth.make_dzdy(L, ho, wo, seed)
+    xd, wd, bd, pd = np64(x), np64(w), np64(b), np64(p)
+    bb = bd if with_bias else None
+    out = {}
+    xg, wg, bg, pg = gpu(x), gpu(w), gpu(b), gpu(p)
+    y = B.conv_forward(xg, wg, bg if with_bias else None, st, pad, precision)
+    dx = B.conv_backward_data(x.shape, wg, pg, st, pad, precision)
+    dw = B.conv_backward_filter(xg, w.shape, pg, st, pad, precision)
+    db = B.conv_backward_bias(x.shape, w.shape, pg, st, pad)
+    torch.cuda.synchronize()
+    assert tuple(y.shape) == (L["N"], L["K"], wo, ho)
+    out["forward"] = norm_err(y.cpu().numpy(), oracle.forward(xd, wd, bb, st, pad),
+                              oracle.forward(np.abs(xd), np.abs(wd), None if bb is None else np.abs(bb), st, pad))
+    out["backward_data"] = norm_err(dx.cpu().numpy(), oracle.backward_data(x.shape, wd, pd, st, pad),
+                                    oracle.backward_data(x.shape, np.abs(wd), np.abs(pd), st, pad))
+    out["backward_filter"] = norm_err(dw.cpu().numpy(), oracle.backward_filter(xd, w.shape, pd, st, pad),
+                                      oracle.backward_filter(np.abs(xd), w.shape, np.abs(pd), st, pad))
+    out["backward_bias"] = norm_err(db.cpu().numpy(), oracle.backward_bias(x.shape, w.shape, pd, st, pad),
+                                    oracle.backward_bias(x.shape, w.shape, np.abs(pd), st, pad))
+    return out
+
+
+def run_layer_sampled(L, n_out=4000, n_filt=96, precision=B.MCN_PREC_FP32, seed=0):
+    """All four operations at full size; results compared at sampled places that the
+    oracle computes one by one (bias derivative: all K)."""
+    st, pad = L["stride"], L["pad"]
+    x, w, b = synth.make_x(L, seed), synth.make_w(L, seed), synth.make_b(L, seed)
+    ho, wo = oracle.output_size(x.shape, w.shape, st, pad)
+    p = synth.make_dzdy(L, ho, wo, seed)
+    xg, wg, bg, pg = gpu(x), gpu(w), gpu(b), gpu(p)
+    y = B.conv_forward(xg, wg, bg, st, pad, precision)
+    dx = B.conv_backward_data(x.shape, wg, pg, st, pad, precision)
+    dw = B.conv_backward_filter(xg, w.shape, pg, st, pad, precision)
+    db = B.conv_backward_bias(x.shape, w.shape, pg, st, pad)
+    torch.cuda.synchronize()
+    y, dx, dw, db = (t.cpu().numpy().ravel() for t in (y, dx, dw, db))
+    del xg, wg, pg
+    xd, wd, bd, pd = np64(x), np64(w), np64(b), np64(p)
+    out = {}
+    iy = sample_idx(y.size, n_out, 1)
+    out["forward"] = norm_err(y[iy], oracle.forward_at(xd, wd, bd, iy, st, pad),
+                              oracle.forward_at(np.abs(xd), np.abs(wd), np.abs(bd), iy, st, pad))
+    ix = sample_idx(dx.size, n_out, 2)
+    out["backward_data"] = norm_err(dx[ix], oracle.backward_data_at(x.shape, wd, pd, ix, st, pad),
+                                    oracle.backward_data_at(x.shape, np.abs(wd), np.abs(pd), ix, st, pad))
+    iw = sample_idx(dw.size, n_filt, 3)
+    out["backward_filter"] = norm_err(dw[iw], oracle.backward_filter_at(xd, w.shape, pd, iw, st, pad),
+                                      oracle.backward_filter_at(np.abs(xd), w.shape, np.abs(pd), iw, st, pad))
+    out["backward_bias"] = norm_err(db, oracle.backward_bias(x.shape, w.shape, pd, st, pad),
+                                    oracle.backward_bias(x.shape, w.shape, np.abs(pd), st, pad))
+    return out
+
+
+def assert_errors(errs, precision=B.MCN_PREC_FP32, label=""):
+    tol_f = TOL_BF16 if precision == B.MCN_PREC_BF16 else TOL_FWD
+    tol_b = TOL_BF16 if precision == B.MCN_PREC_BF16 else TOL_BWD
+    print(label, {k: "%.2e" % v for k, v in errs.items()}, flush=True)
+    assert errs["forward"] <= tol_f, (label, errs)
+    assert errs["backward_data"] <= tol_b, (label, errs)
+    assert errs["backward_filter"] <= tol_b, (label, errs)
+    assert errs["backward_bias"] <= TOL_BWD, (label, errs)

@@ -1,0 +1,110 @@
+"""Host-side checks of the C-ABI library: it loads, exports every function the
+header declares, and turns every bad geometry into a status code before any GPU
+work (so these run without a GPU)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_1412_4564_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    names = []
+    inc = os.path.join(ROOT, "include")
+    for fn in sorted(os.listdir(inc)):
+        if not fn.endswith(".h"):
+            continue
+        text = open(os.path.join(inc, fn)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names += re.findall(r"\b(mcn_[a-z0-9_]+)\s*\(", text)
+    return sorted(set(names))
+
+
+def test_library_exports_every_declared_function():
+    names = declared_functions()
+    assert set(names) == set(B.EXPORTS), names
+    L = ctypes.CDLL(B.LIB_PATH)
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def desc(**kw):
+    base = dict(xshape=(2, 4, 9, 8), wshape=(6, 2, 3, 3), stride=(1, 1), pad=(0, 0, 0, 0))
+    base.update(kw)
+    return B.make_desc(**base)
+
+
+def test_output_size_closed_form():
+    # Sec. 4.1 "Output size": floor((H - H' + Pt + Pb)/Sh) + 1
+    assert B.mcn_conv_output_size(desc()) == (6, 7)
+    assert B.mcn_conv_output_size(desc(stride=(2, 3), pad=(1, 0, 2, 1))) == ((8 - 3 + 1) // 2 + 1, (9 - 3 + 3) // 3 + 1)
+    assert B.mcn_conv_output_size(B.make_desc((4, 16, 53, 37), (24, 16, 5, 3), (2, 3), (1, 0, 2, 1))) == (18, 18)
+    assert B.mcn_conv_output_size(B.make_desc((128, 3, 227, 227), (96, 3, 11, 11), (4, 4))) == (55, 55)
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(stride=(0, 1)), B.MCN_BAD_ARG),
+    (dict(stride=(1, -1)), B.MCN_BAD_ARG),
+    (dict(pad=(0, -1, 0, 0)), B.MCN_BAD_ARG),
+    (dict(xshape=(0, 4, 9, 8)), B.MCN_BAD_ARG),
+    (dict(wshape=(6, 2, 3, 0)), B.MCN_BAD_ARG),
+    (dict(precision=7), B.MCN_BAD_ARG),
+    (dict(wshape=(6, 3, 3, 3)), B.MCN_BAD_GROUPS),       # D' = 3 does not divide D = 4
+    (dict(wshape=(5, 2, 3, 3)), B.MCN_BAD_GROUPS),       # 2 groups do not divide 5 filters
+    (dict(wshape=(6, 2, 3, 9)), B.MCN_FILTER_TOO_LARGE),  # H = 8 < H' = 9
+    (dict(wshape=(6, 2, 11, 3), pad=(0, 0, 1, 0)), B.MCN_FILTER_TOO_LARGE),
+    (dict(xshape=(1 << 20, 64, 9, 8), wshape=(6, 64, 3, 3)), B.MCN_UNSUPPORTED),   # x has >= 2^31 elements
+])
+def test_bad_geometry_is_a_status_code_everywhere(kw, code):
+    d = desc(**kw)
+    L = B.lib()
+    assert L.mcn_conv_output_size(ctypes.byref(d), None, None) == code
+    n = ctypes.c_size_t(0)
+    assert L.mcn_conv_workspace_size(ctypes.byref(d), 0, ctypes.byref(n)) == code
+    # non-null dummy pointers: validation must reject before touching them
+    p = 4096
+    assert B.mcn_conv_forward(d, p, p, p, p, None, 0, None) == code
+    assert B.mcn_conv_backward_data(d, p, p, p, None, 0, None) == code
+    assert B.mcn_conv_backward_filter(d, p, p, p, None, 0, None) == code
+    assert B.mcn_conv_backward_bias(d, p, p, None, 0, None) == code
+    assert B.mcn_conv_kernel_name(d, 0) is None
+
+
+def test_null_pointers_and_small_workspace_are_rejected():
+    d = desc()
+    p = 4096
+    L = B.lib()
+    assert L.mcn_conv_output_size(None, None, None) == B.MCN_BAD_ARG
+    assert L.mcn_conv_workspace_size(ctypes.byref(d), 9, ctypes.byref(ctypes.c_size_t(0))) == B.MCN_BAD_ARG
+    assert L.mcn_conv_workspace_size(ctypes.byref(d), 0, None) == B.MCN_BAD_ARG
+    assert B.mcn_conv_forward(d, None, p, p, p, None, 0, None) == B.MCN_BAD_ARG
+    assert B.mcn_conv_forward(d, p, None, p, p, None, 0, None) == B.MCN_BAD_ARG
+    assert B.mcn_conv_forward(d, p, p, p, None, None, 0, None) == B.MCN_BAD_ARG
+    assert B.mcn_conv_backward_data(d, p, None, p, None, 0, None) == B.MCN_BAD_ARG
+    assert B.mcn_conv_backward_filter(d, p, p, None, None, 0, None) == B.MCN_BAD_ARG
+    assert B.mcn_conv_backward_bias(d, None, p, None, 0, None) == B.MCN_BAD_ARG
+    for op, call in [(B.MCN_OP_BACKWARD_BIAS, lambda ws, n: B.mcn_conv_backward_bias(d, p, p, ws, n, None)),
+                     (B.MCN_OP_FORWARD, lambda ws, n: B.mcn_conv_forward(d, p, p, p, p, ws, n, None)),
+                     (B.MCN_OP_BACKWARD_DATA, lambda ws, n: B.mcn_conv_backward_data(d, p, p, p, ws, n, None)),
+                     (B.MCN_OP_BACKWARD_FILTER, lambda ws, n: B.mcn_conv_backward_filter(d, p, p, p, ws, n, None))]:
+        need = B.mcn_conv_workspace_size(d, op)
+        if need:
+            assert call(p, need - 1) == B.MCN_WORKSPACE_TOO_SMALL
+            assert call(None, need) == B.MCN_WORKSPACE_TOO_SMALL
+
+
+def test_status_strings():
+    L = B.lib()
+    seen = set()
+    for code in range(0, 7):
+        s = L.mcn_status_string(code).decode()
+        assert s and s not in seen
+        seen.add(s)
+    assert "unknown" in L.mcn_status_string(99).decode()
+    for op in range(4):
+        assert B.mcn_conv_kernel_name(desc(), op)
+    assert B.mcn_conv_kernel_name(desc(), 17) is None

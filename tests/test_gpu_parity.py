@@ -1,0 +1,131 @@
+"""GPU-vs-oracle parity, through the C ABI.  Error bar: normalised error
+(|gpu - oracle| / the same sum taken over absolute values) <= 1e-4 forward,
+<= 1e-3 backward in fp32; structurally-zero results exactly zero."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_1412_4564_amd import binding as B
+from paper_1412_4564_amd import synth
+
+import parity_util as U
+
+pytestmark = pytest.mark.gpu
+
+
+def custom_layer(H, W, D, N, Hf, Wf, Df, K, stride=(1, 1), pad=(0, 0, 0, 0), idx=0):
+    return dict(H=H, W=W, D=D, N=N, Hf=Hf, Wf=Wf, Df=Df, K=K, stride=tuple(stride), pad=tuple(pad),
+                config=9, index=idx)
+
+
+# ---- small layers of the workloads: every element ---------------------------------
+@pytest.mark.parametrize("name", ["1", "5c", "2c"])
+def test_small_workload_layers_full(name):
+    L = synth.LAYERS[name]
+    U.assert_errors(U.run_layer_full(L), label="layer " + name)
+    U.assert_errors(U.run_layer_full(L, with_bias=False, seed=1), label="layer %s, no bias" % name)
+
+
+@pytest.mark.parametrize("name,nb", [("2a", 6), ("2b", 5), ("3a", 2), ("3b", 3), ("4a", 1), ("4b", 2), ("4c", 5),
+                                     ("5a", 9), ("5b", 3)])
+def test_workload_layers_reduced_batch_full(name, nb):
+    """Real spatial/channel shape, small batch: every element compared."""
+    L = synth.with_batch(synth.LAYERS[name], nb)
+    U.assert_errors(U.run_layer_full(L), label="layer %s at N=%d" % (name, nb))
+
+
+# ---- full-size workloads, in the configuration the benchmark times: sampled -------
+@pytest.mark.parametrize("name", ["2a", "2b", "3a", "3b", "4a", "4b", "4c", "5a", "5b"])
+def test_workload_layers_full_size_sampled(name):
+    L = synth.LAYERS[name]
+    U.assert_errors(U.run_layer_sampled(L), label="layer %s full size" % name)
+
+
+# ---- irregular geometry sweep: strides, four pads, groups, non-square everything ---
+SWEEP = [
+    # H  W  D  N  Hf Wf Df K   stride   pad
+    (13, 9, 4, 3, 3, 2, 2, 6, (1, 1), (0, 0, 0, 0)),
+    (13, 9, 4, 3, 3, 2, 2, 6, (2, 1), (1, 2, 0, 1)),
+    (9, 13, 6, 2, 2, 4, 2, 9, (1, 3), (3, 0, 1, 2)),
+    (33, 35, 5, 2, 5, 3, 5, 7, (3, 2), (2, 1, 0, 2)),
+    (70, 40, 8, 2, 3, 3, 8, 40, (1, 1), (1, 1, 1, 1)),      # several 32-pixel tiles + ragged tail
+    (67, 5, 3, 3, 7, 5, 3, 33, (1, 1), (3, 3, 2, 2)),
+    (16, 16, 12, 2, 1, 1, 4, 9, (1, 1), (0, 0, 0, 0)),       # 1x1, 3 groups
+    (16, 16, 12, 2, 1, 1, 12, 5, (2, 2), (0, 0, 0, 0)),      # 1x1 with stride: unread samples
+    (10, 11, 2, 2, 4, 4, 2, 3, (5, 6), (0, 0, 0, 0)),        # stride > filter: unread rows/cols
+    (4, 5, 3, 4, 4, 5, 3, 10, (1, 1), (0, 0, 0, 0)),         # fully connected: 1x1 output
+    (3, 3, 2, 2, 2, 2, 2, 2, (1, 1), (4, 4, 4, 4)),          # pad larger than the filter
+    (1, 1, 1, 1, 1, 1, 1, 1, (1, 1), (0, 0, 0, 0)),          # the smallest problem
+    (2, 40, 1, 1, 2, 3, 1, 1, (1, 1), (0, 0, 1, 1)),         # single channel, single filter
+    (40, 2, 64, 1, 3, 2, 64, 64, (1, 1), (1, 1, 0, 0)),      # deep reduction
+    (31, 29, 6, 5, 3, 3, 3, 130, (1, 1), (1, 1, 1, 1)),      # K = 2 groups x 65: ragged filter tiles
+    (21, 17, 7, 2, 6, 6, 7, 3, (2, 2), (0, 5, 5, 0)),
+]
+
+
+@pytest.mark.parametrize("case", range(len(SWEEP)))
+def test_geometry_sweep(case):
+    H, W, D, N, Hf, Wf, Df, K, st, pad = SWEEP[case]
+    L = custom_layer(H, W, D, N, Hf, Wf, Df, K, st, pad, idx=case)
+    U.assert_errors(U.run_layer_full(L, with_bias=(case % 2 == 0)), label="sweep %d" % case)
+
+
+def test_random_geometries():
+    rng = np.random.default_rng(31415)
+    for t in range(40):
+        g = int(rng.choice([1, 1, 2, 3]))
+        Df, Kg = int(rng.integers(1, 9)), int(rng.integers(1, 40))
+        Hf, Wf = int(rng.integers(1, 6)), int(rng.integers(1, 6))
+        H, W = int(rng.integers(1, 40)), int(rng.integers(1, 40))
+        pad = [int(v) for v in rng.integers(0, 4, size=4)]
+        while H + pad[0] + pad[1] < Hf:
+            pad[1] += 1
+        while W + pad[2] + pad[3] < Wf:
+            pad[3] += 1
+        st = (int(rng.integers(1, 4)), int(rng.integers(1, 4)))
+        L = custom_layer(H, W, g * Df, int(rng.integers(1, 5)), Hf, Wf, Df, g * Kg, st, pad, idx=100 + t)
+        U.assert_errors(U.run_layer_full(L, with_bias=bool(t % 2), seed=t), label="random %d %r" % (t, L))
+
+
+# ---- semantics of the boundary ---------------------------------------------------
+def test_outputs_are_overwritten_and_runs_are_bit_identical():
+    L = synth.with_batch(synth.LAYERS["2b"], 4)
+    st, pad = L["stride"], L["pad"]
+    x, w, b = (U.gpu(t) for t in (synth.make_x(L), synth.make_w(L), synth.make_b(L)))
+    ho, wo = B.mcn_conv_output_size(B.make_desc(x.shape, w.shape, st, pad))
+    p = U.gpu(synth.make_dzdy(L, ho, wo))
+    outs1 = [B.conv_forward(x, w, b, st, pad), B.conv_backward_data(x.shape, w, p, st, pad),
+             B.conv_backward_filter(x, w.shape, p, st, pad), B.conv_backward_bias(x.shape, w.shape, p, st, pad)]
+    # second run into buffers pre-filled with NaN / large values: nothing may leak through
+    bufs = [torch.full_like(o, float("nan")) for o in outs1]
+    bufs[2].fill_(1e30)
+    B.conv_forward(x, w, b, st, pad, out=bufs[0])
+    B.conv_backward_data(x.shape, w, p, st, pad, out=bufs[1])
+    B.conv_backward_filter(x, w.shape, p, st, pad, out=bufs[2])
+    B.conv_backward_bias(x.shape, w.shape, p, st, pad, out=bufs[3])
+    torch.cuda.synchronize()
+    for a, c in zip(outs1, bufs):
+        assert torch.equal(a, c)
+
+
+def test_null_bias_equals_zero_bias():
+    L = synth.LAYERS["5c"]
+    st, pad = L["stride"], L["pad"]
+    x, w = U.gpu(synth.make_x(L)), U.gpu(synth.make_w(L))
+    y0 = B.conv_forward(x, w, None, st, pad)
+    y1 = B.conv_forward(x, w, torch.zeros(L["K"], device="cuda"), st, pad)
+    assert torch.equal(y0, y1)
+
+
+def test_runs_on_a_side_stream():
+    L = synth.LAYERS["1"]
+    st, pad = L["stride"], L["pad"]
+    x, w, b = U.gpu(synth.make_x(L)), U.gpu(synth.make_w(L)), U.gpu(synth.make_b(L))
+    ref = B.conv_forward(x, w, b, st, pad)
+    torch.cuda.synchronize()
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        y = B.conv_forward(x, w, b, st, pad)
+    s.synchronize()
+    assert torch.equal(ref, y)
