@@ -1,0 +1,200 @@
+#!/usr/bin/env python3
+"""Benchmark of the convolution block on one MI355X.
+
+A "step" is one pass of the whole hot path -- forward, input derivative, filter
+derivative and bias derivative -- over every layer of the workload, with all
+operands already resident in HBM.  The default workload is the deep 3x3 stack
+(224x224x64->64, 56x56x256->256, 14x14x512->512; stride 1, pad 1, N=32, fp32)
+on which the headline metric is quoted.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload vgg3x3|<layer names>]
+"""
+import argparse
+import json
+import sys
+import time
+
+import numpy as np
+import torch
+
+from paper_1412_4564_amd import binding as B
+from paper_1412_4564_amd import synth
+
+FP32_MFMA_PEAK_TFLOPS = 157.3     # 256 CU x 256 flop/clk x 2.4 GHz
+HBM_PEAK_GBS = 8000.0
+
+WORKLOADS = {"vgg3x3": ["4a", "4b", "4c"]}
+OPS = ["forward", "backward_data", "backward_filter", "backward_bias"]
+
+
+def layer_macs(L, ho, wo):
+    return ho * wo * L["K"] * L["N"] * L["Hf"] * L["Wf"] * L["Df"]
+
+
+class LayerState:
+    def __init__(self, name, L, precision):
+        self.name, self.L = name, L
+        self.st, self.pad, self.prec = L["stride"], L["pad"], precision
+        self.x = synth.make_x(L).cuda()
+        self.w = synth.make_w(L).cuda()
+        self.b = synth.make_b(L).cuda()
+        desc = B.make_desc(self.x.shape, self.w.shape, self.st, self.pad, precision)
+        self.desc = desc
+        self.ho, self.wo = B.mcn_conv_output_size(desc)
+        self.p = synth.make_dzdy(L, self.ho, self.wo).cuda()
+        self.y = torch.empty_like(self.p)
+        self.dx = torch.empty_like(self.x)
+        self.dw = torch.empty_like(self.w)
+        self.db = torch.empty_like(self.b)
+        self.macs = layer_macs(L, self.ho, self.wo)
+        self.kernels = [B.mcn_conv_kernel_name(desc, op) for op in range(4)]
+        ws = max(B.mcn_conv_workspace_size(desc, op) for op in range(4))
+        self.ws = torch.empty(max(ws, 16), dtype=torch.uint8, device="cuda")
+        # algorithmic bytes per operation: each operand once
+        nx, nw, ny = self.x.numel(), self.w.numel(), self.p.numel()
+        self.bytes = [4 * (nx + nw + ny), 4 * (ny + nw + nx), 4 * (nx + ny + nw), 4 * (ny + L["K"])]
+
+    def run(self, op, stream):
+        d, ws, n = self.desc, self.ws.data_ptr(), self.ws.numel()
+        if op == 0:
+            st = B.mcn_conv_forward(d, self.x.data_ptr(), self.w.data_ptr(), self.b.data_ptr(), self.y.data_ptr(), ws, n, stream)
+        elif op == 1:
+            st = B.mcn_conv_backward_data(d, self.w.data_ptr(), self.p.data_ptr(), self.dx.data_ptr(), ws, n, stream)
+        elif op == 2:
+            st = B.mcn_conv_backward_filter(d, self.x.data_ptr(), self.p.data_ptr(), self.dw.data_ptr(), ws, n, stream)
+        else:
+            st = B.mcn_conv_backward_bias(d, self.p.data_ptr(), self.db.data_ptr(), ws, n, stream)
+        if st:
+            raise B.McnError(st, OPS[op])
+
+
+def cpu_baseline(names):
+    """The oracle as it stands, timed on this machine's host cores on a bounded sample
+    of the same workload: the same layers at a reduced batch."""
+    import oracle
+    sample_n = {"4a": 1, "4b": 1, "4c": 2}
+    flops, secs, desc = 0.0, 0.0, []
+    for name in names:
+        L = synth.with_batch(synth.LAYERS[name], sample_n.get(name, 1))
+        st, pad = L["stride"], L["pad"]
+        x = synth.make_x(L).numpy().astype(np.float64)
+        w = synth.make_w(L).numpy().astype(np.float64)
+        b = synth.make_b(L).numpy().astype(np.float64)
+        ho, wo = oracle.output_size(x.shape, w.shape, st, pad)
+        p = synth.make_dzdy(L, ho, wo).numpy().astype(np.float64)
+        t0 = time.perf_counter()
+        oracle.forward(x, w, b, st, pad)
+        oracle.backward_data(x.shape, w, p, st, pad)
+        oracle.backward_filter(x, w.shape, p, st, pad)
+        oracle.backward_bias(x.shape, w.shape, p, st, pad)
+        secs += time.perf_counter() - t0
+        flops += 3 * 2.0 * layer_macs(L, ho, wo)
+        desc.append("%s at N=%d" % (name, L["N"]))
+    return {"value": flops / secs / 1e12, "unit": "TFLOP/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": "fwd+bwd of layers " + ", ".join(desc) + " (fp64 loop nest, %.1f s)" % secs}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="vgg3x3", help="vgg3x3 or comma-separated layer names (e.g. 2b,3b)")
+    ap.add_argument("--precision", default="fp32", choices=["fp32", "bf16"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU; --gpus %d is not supported (the path shards over the batch, "
+                 "see DESIGN.md)" % args.gpus)
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    torch.cuda.set_device(0)
+    names = WORKLOADS.get(args.workload) or args.workload.split(",")
+    prec = B.MCN_PREC_BF16 if args.precision == "bf16" else B.MCN_PREC_FP32
+    layers = [LayerState(n, synth.LAYERS[n], prec) for n in names]
+    stream_obj = torch.cuda.current_stream()
+    stream = stream_obj.cuda_stream
+
+    def step(events=None):
+        for li, Ls in enumerate(layers):
+            for op in range(4):
+                Ls.run(op, stream)
+                if events is not None:
+                    ev = torch.cuda.Event(enable_timing=True)
+                    ev.record(stream_obj)
+                    events.append(ev)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    # timed region: exactly --steps steps
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+
+    # per-call durations with events on the launch stream (a second, separately timed pass of the same steps,
+    # so that the event records do not perturb the headline number)
+    per = np.zeros((len(layers), 4))
+    for _ in range(args.steps):
+        start = torch.cuda.Event(enable_timing=True)
+        start.record(stream_obj)
+        evs = []
+        step(evs)
+        torch.cuda.synchronize()
+        prev = start
+        for i, ev in enumerate(evs):
+            per[i // 4, i % 4] += prev.elapsed_time(ev)
+            prev = ev
+    per /= args.steps     # ms per call
+
+    flops_step = sum(3 * 2.0 * Ls.macs for Ls in layers)
+    ms_per_step = 1e3 * elapsed / args.steps
+    value = flops_step / (elapsed / args.steps) / 1e12
+
+    # dominant kernel: the call that takes the most time per step
+    li, op = np.unravel_index(np.argmax(per), per.shape)
+    dom = layers[li]
+    detail = {}
+    for i, Ls in enumerate(layers):
+        for o in range(4):
+            ms = per[i, o]
+            e = {"kernel": Ls.kernels[o], "ms": round(float(ms), 4),
+                 "GBps": round(Ls.bytes[o] / ms / 1e6, 1)}
+            if o < 3:
+                e["TFLOPs"] = round(2.0 * Ls.macs / ms / 1e9, 2)
+            detail["%s.%s" % (Ls.name, OPS[o])] = e
+    if op < 3:
+        ach = 2.0 * dom.macs / per[li, op] / 1e9
+        roof = {"bound": "mfma", "achieved": round(ach, 2), "peak": FP32_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                "frac": round(ach / FP32_MFMA_PEAK_TFLOPS, 4), "traffic": None,
+                "kernel": "%s.%s (%s)" % (dom.name, OPS[op], dom.kernels[op])}
+    else:
+        ach = dom.bytes[op] / per[li, op] / 1e6
+        roof = {"bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": None,
+                "kernel": "%s.%s (%s)" % (dom.name, OPS[op], dom.kernels[op])}
+
+    out = {
+        "metric": "conv fwd+bwd TFLOP/s (fp32) on VGG-style 3x3 layers",
+        "value": round(value, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32" if prec == B.MCN_PREC_FP32 else "bf16-in/f32-acc", "data": "synthetic",
+        "config": {"workload": "conv fwd+bwd (dzdx, dzdw, dzdb) of layers " + ",".join(names) +
+                               " (3x3 stride 1 pad 1, N=32)" if args.workload == "vgg3x3" else
+                               "conv fwd+bwd of layers " + ",".join(names),
+                   "layers": {Ls.name: {"x_HWDN": [Ls.L["H"], Ls.L["W"], Ls.L["D"], Ls.L["N"]],
+                                        "w_HWDK": [Ls.L["Hf"], Ls.L["Wf"], Ls.L["Df"], Ls.L["K"]]} for Ls in layers}},
+        "frac_of_fp32_mfma_peak": round(value / FP32_MFMA_PEAK_TFLOPS, 4),
+        "roofline": roof,
+        "calls": detail,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(names)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

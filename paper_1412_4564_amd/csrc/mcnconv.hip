@@ -9,6 +9,8 @@
 #include "../../include/mcnconv.h"
 #include "geom.h"
 #include "kern_direct.h"
+#include "kern_igemm.h"
+#include "igemm_plan.h"
 
 using namespace mcn;
 
@@ -46,11 +48,68 @@ BiasPlan plan_bias(const Geom &g) {
     return p;
 }
 
+// ---- implicit-GEMM dispatch -------------------------------------------------
+bool igemm_enabled() {
+    static const bool off = getenv("MCN_FORCE_DIRECT") != nullptr;   // benchmarking / debugging override
+    return !off;
+}
+
+// which view (if any) of this operation runs on the implicit-GEMM kernel
+bool igemm_plan_for(const Geom &g, int op, IgemmPlan *pl) {
+    if (!igemm_enabled()) return false;
+    if (op == MCN_OP_FORWARD) return plan_igemm(forward_view(g), pl);
+    if (op == MCN_OP_BACKWARD_DATA && g.Sh == 1 && g.Sw == 1) return plan_igemm(backward_data_view(g), pl);
+    return false;
+}
+
+template <int WK, int WP, int MK, int MP, int DC, int HF, int WF, int TMAX>
+int launch_igemm_inst(const IgemmPlan &pl, const float *in, const float *wpk, const float *bias, float *out,
+                      hipStream_t s) {
+    auto kern = igemm_conv_kernel<WK, WP, MK, MP, DC, HF, WF, TMAX, IGEMM_EPT>;
+    if (pl.lds_bytes > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           (int)pl.lds_bytes);
+        if (e != hipSuccess) { g_last_hip_error = (int)e; return MCN_HIP_ERROR; }
+    }
+    hipLaunchKernelGGL(kern, dim3(pl.blocks), dim3(64 * WK * WP), pl.lds_bytes, s, pl.P, in, wpk, bias, out);
+    return check_launch();
+}
+
+int launch_igemm(const IgemmPlan &pl, const ConvView &v, const float *in, const float *w, const float *bias,
+                 float *out, float *packed, hipStream_t s) {
+    const int total = (int)pl.packed_floats;
+    // for the packing kernel the weight array is always the caller's w : Hf x Wf x Df x K
+    const int Df = v.pack_mode == 0 ? v.Cg : v.Kg;
+    hipLaunchKernelGGL(igemm_pack_weights_kernel, dim3(cdiv(total, 256)), dim3(256), 0, s, w, packed, v.Hf, v.Wf, Df,
+                       v.Kg, v.Cg, v.G, pl.P.KT, pl.P.NCH, pl.TK, pl.DC, v.pack_mode, total);
+    int st = check_launch();
+    if (st) return st;
+    switch (pl.shape) {
+        case IG_128x256:
+            return pl.fixed33 ? launch_igemm_inst<2, 4, 2, 2, 8, 3, 3, 9>(pl, in, packed, bias, out, s)
+                              : launch_igemm_inst<2, 4, 2, 2, 4, 0, 0, IGEMM_TMAX>(pl, in, packed, bias, out, s);
+        case IG_64x512:
+            return pl.fixed33 ? launch_igemm_inst<1, 8, 2, 2, 8, 3, 3, 9>(pl, in, packed, bias, out, s)
+                              : launch_igemm_inst<1, 8, 2, 2, 4, 0, 0, IGEMM_TMAX>(pl, in, packed, bias, out, s);
+        case IG_32x256:
+            return pl.fixed33 ? launch_igemm_inst<1, 4, 1, 2, 8, 3, 3, 9>(pl, in, packed, bias, out, s)
+                              : launch_igemm_inst<1, 4, 1, 2, 4, 0, 0, IGEMM_TMAX>(pl, in, packed, bias, out, s);
+        default:
+            return MCN_BAD_ARG;
+    }
+}
+
 size_t workspace_bytes(const Geom &g, int op) {
     switch (op) {
         case MCN_OP_BACKWARD_BIAS: {
             BiasPlan p = plan_bias(g);
             return (size_t)g.K * p.S * sizeof(float);
+        }
+        case MCN_OP_FORWARD:
+        case MCN_OP_BACKWARD_DATA: {
+            IgemmPlan pl;
+            if (igemm_plan_for(g, op, &pl)) return pl.packed_floats * sizeof(float);
+            return 0;
         }
         default:
             return 0;
@@ -83,8 +142,11 @@ const char *mcn_conv_kernel_name(const mcn_conv_desc *desc, int op) {
     Geom g;
     if (make_geom(desc, &g)) return NULL;
     switch (op) {
-        case MCN_OP_FORWARD: return "direct";
-        case MCN_OP_BACKWARD_DATA: return "direct";
+        case MCN_OP_FORWARD:
+        case MCN_OP_BACKWARD_DATA: {
+            IgemmPlan pl;
+            return igemm_plan_for(g, op, &pl) ? "igemm" : "direct";
+        }
         case MCN_OP_BACKWARD_FILTER: return "direct";
         case MCN_OP_BACKWARD_BIAS: return "reduce2";
         default: return NULL;
@@ -100,6 +162,8 @@ int mcn_conv_forward(const mcn_conv_desc *desc, const float *x, const float *w, 
     if (ws_bytes < workspace_bytes(g, MCN_OP_FORWARD) || (!ws && workspace_bytes(g, MCN_OP_FORWARD)))
         return MCN_WORKSPACE_TOO_SMALL;
     hipStream_t s = (hipStream_t)stream;
+    IgemmPlan pl;
+    if (igemm_plan_for(g, MCN_OP_FORWARD, &pl)) return launch_igemm(pl, forward_view(g), x, w, b, y, (float *)ws, s);
     const int total = (int)numel_y(g);
     hipLaunchKernelGGL(direct_forward_kernel, dim3(cdiv(total, 256)), dim3(256), 0, s, g, x, w, b, y, total);
     return check_launch();
@@ -114,6 +178,9 @@ int mcn_conv_backward_data(const mcn_conv_desc *desc, const float *w, const floa
     if (ws_bytes < workspace_bytes(g, MCN_OP_BACKWARD_DATA) || (!ws && workspace_bytes(g, MCN_OP_BACKWARD_DATA)))
         return MCN_WORKSPACE_TOO_SMALL;
     hipStream_t s = (hipStream_t)stream;
+    IgemmPlan pl;
+    if (igemm_plan_for(g, MCN_OP_BACKWARD_DATA, &pl))
+        return launch_igemm(pl, backward_data_view(g), dzdy, w, nullptr, dzdx, (float *)ws, s);
     const int total = (int)numel_x(g);
     hipLaunchKernelGGL(direct_backward_data_kernel, dim3(cdiv(total, 256)), dim3(256), 0, s, g, w, dzdy, dzdx, total);
     return check_launch();
