@@ -133,3 +133,108 @@ inline bool plan_igemm(const ConvView &v, IgemmPlan *pl) {
 }
 
 }  // namespace mcn
+
+// ---- filter derivative (kern_wgrad.h) ---------------------------------------------------
+#include "kern_wgrad.h"
+namespace mcn {
+
+enum WgradShape { WG_128x128 = 0, WG_64x192 = 1, WG_32x256 = 2 };
+
+struct WgradPlan {
+    int shape;
+    int PCH;             // pixels per chunk
+    int TK, TR, NT;
+    WgradParams P;
+    size_t lds_bytes;
+    int splits;          // RB * SPR
+    size_t partial_floats;
+    int blocks;
+};
+
+inline bool plan_wgrad(const Geom &g, WgradPlan *pl) {
+    ConvView v = forward_view(g);
+    const int T = v.Hf * v.Wf;
+    const int R = T * v.Cg;
+    if ((double)numel_x(g) * 4 >= 2147483647.0 || (double)numel_y(g) * 4 >= 2147483647.0) return false;
+    int shape, WK, WR, MK, MR, EPT, NCHMAX, WGRAD_PCH;
+    if (v.Kg > 64) { shape = WG_128x128; WK = 2; WR = 2; MK = 2; MR = 2; EPT = 2; NCHMAX = 16; WGRAD_PCH = 32; }
+    else if (v.Kg > 32) { shape = WG_64x192; WK = 2; WR = 2; MK = 1; MR = 3; EPT = 2; NCHMAX = 24; WGRAD_PCH = 64; }
+    else { shape = WG_32x256; WK = 1; WR = 4; MK = 1; MR = 2; EPT = 2; NCHMAX = 32; WGRAD_PCH = 32; }
+    const int TK = WK * MK * 32, TR = WR * MR * 32, NT = 64 * WK * WR;
+    const int RT = (R + TR - 1) / TR;
+    int nch_max = 0;
+    for (int rt = 0; rt < RT; ++rt) {
+        const int lo = rt * TR, hi = (lo + TR < R ? lo + TR : R);
+        const int n = (hi - 1) / T - lo / T + 1;
+        if (n > nch_max) nch_max = n;
+    }
+    if (nch_max > NCHMAX) return false;
+    const int Wp = (v.Wo - 1) * v.Sw + v.Wf;
+
+    int cand[40];
+    int nc = 0;
+    cand[nc++] = v.Ho;
+    for (int parts = 2; parts <= 16; ++parts) cand[nc++] = (v.Ho + parts - 1) / parts;
+    for (int t = 32; t <= 256; t += 32) cand[nc++] = t;
+    double best = 1e30;
+    int bestTI = 0, bestSC = 0;
+    for (int a = 0; a < nc; ++a) {
+        const int TI = cand[a];
+        if (TI < 1 || TI > v.Ho) continue;
+        const int64_t SR = (int64_t)(TI - 1) * v.Sh + v.Hf;
+        if (SR > 4096) continue;
+        const int64_t QN = (int64_t)TI * v.Wo * v.N;
+        if (QN >= ((int64_t)1 << 30)) continue;
+        const int SC = slab_columns(v, TI, WGRAD_PCH, Wp);
+        if (SC > 2 * Wp) continue;                       // at most two image crossings per chunk
+        if (SR * SC > (int64_t)EPT * NT) continue;
+        const int RB = (v.Ho + TI - 1) / TI;
+        const double chunks = (double)RB * (double)((QN + WGRAD_PCH - 1) / WGRAD_PCH);
+        const double score = chunks * (1.0 + 0.002 * (double)(SR * SC));
+        if (score < best) { best = score; bestTI = TI; bestSC = SC; }
+    }
+    if (!bestTI) return false;
+
+    WgradParams &P = pl->P;
+    P.H = v.H; P.W = v.W; P.N = v.N; P.Ctot = v.Ctot; P.Cg = v.Cg;
+    P.Ho = v.Ho; P.Wo = v.Wo; P.Ktot = v.Ktot; P.Kg = v.Kg; P.G = v.G;
+    P.Hf = v.Hf; P.Wf = v.Wf; P.Sh = v.Sh; P.Sw = v.Sw; P.Pt = v.Pt; P.Pl = v.Pl;
+    P.TI = bestTI; P.RB = (v.Ho + bestTI - 1) / bestTI;
+    P.Wp = Wp;
+    P.SR = (bestTI - 1) * v.Sh + v.Hf;
+    P.SC = bestSC;
+    // pitches chosen so that the 32 coefficients a half-wave reads fall in 32 different LDS banks:
+    // bank(r) = fi + SRP*fj + CP*c  ==  r  (mod 32)
+    int SRP = P.SR;
+    while (SRP % 32 != v.Hf % 32) ++SRP;
+    int CP = SRP * bestSC;
+    while (CP % 32 != T % 32) ++CP;
+    P.SRP = SRP; P.CP = CP;
+    P.KT = (v.Kg + TK - 1) / TK; P.RT = RT;
+    P.QN = bestTI * v.Wo * v.N;
+    P.R = R;
+    P.XS = nch_max * CP;
+    P.EPTU = (P.SR * bestSC + NT - 1) / NT;
+    pl->PCH = WGRAD_PCH;
+    const int64_t base_blocks = (int64_t)v.G * P.KT * RT * P.RB;
+    const int64_t chunks = (P.QN + WGRAD_PCH - 1) / WGRAD_PCH;
+    int64_t spr = (768 + base_blocks - 1) / base_blocks;
+    if (spr > chunks) spr = chunks;
+    if (spr < 1) spr = 1;
+    int64_t qs = ((chunks + spr - 1) / spr) * WGRAD_PCH;
+    spr = (P.QN + qs - 1) / qs;
+    P.QS = (int)qs; P.SPR = (int)spr;
+    pl->splits = (int)(P.RB * spr);
+    P.direct_out = pl->splits == 1;
+    pl->partial_floats = pl->splits > 1 ? (size_t)pl->splits * (size_t)numel_w(g) : 0;
+    if (pl->partial_floats * 4 > ((size_t)3 << 30)) return false;
+    const int64_t blocks = base_blocks * spr;
+    if (blocks >= ((int64_t)1 << 31)) return false;
+    pl->blocks = (int)blocks;
+    pl->shape = shape; pl->TK = TK; pl->TR = TR; pl->NT = NT;
+    pl->lds_bytes = (size_t)(2 * TK * (WGRAD_PCH + 1) + 2 * WGRAD_PCH + 2 * P.XS) * sizeof(float);
+    if (pl->lds_bytes > IGEMM_LDS_LIMIT) return false;
+    return true;
+}
+
+}  // namespace mcn

@@ -99,6 +99,40 @@ int launch_igemm(const IgemmPlan &pl, const ConvView &v, const float *in, const 
     }
 }
 
+bool wgrad_plan_for(const Geom &g, WgradPlan *pl) {
+    if (!igemm_enabled()) return false;
+    return plan_wgrad(g, pl);
+}
+
+template <int WK, int WR, int MK, int MR, int PCH, int EPT, int NCHMAX>
+int launch_wgrad_inst(const WgradPlan &pl, const float *x, const float *dzdy, float *outp, hipStream_t s) {
+    if (pl.PCH != PCH) return MCN_BAD_ARG;
+    auto kern = wgrad_kernel<WK, WR, MK, MR, PCH, EPT, NCHMAX>;
+    if (pl.lds_bytes > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           (int)pl.lds_bytes);
+        if (e != hipSuccess) { g_last_hip_error = (int)e; return MCN_HIP_ERROR; }
+    }
+    hipLaunchKernelGGL(kern, dim3(pl.blocks), dim3(64 * WK * WR), pl.lds_bytes, s, pl.P, x, dzdy, outp);
+    return check_launch();
+}
+
+int launch_wgrad(const WgradPlan &pl, const Geom &g, const float *x, const float *dzdy, float *dzdw, float *ws,
+                 hipStream_t s) {
+    float *outp = pl.splits > 1 ? ws : dzdw;
+    int st;
+    switch (pl.shape) {
+        case WG_128x128: st = launch_wgrad_inst<2, 2, 2, 2, 32, 2, 16>(pl, x, dzdy, outp, s); break;
+        case WG_64x192: st = launch_wgrad_inst<2, 2, 1, 3, 64, 2, 24>(pl, x, dzdy, outp, s); break;
+        case WG_32x256: st = launch_wgrad_inst<1, 4, 1, 2, 32, 2, 32>(pl, x, dzdy, outp, s); break;
+        default: return MCN_BAD_ARG;
+    }
+    if (st || pl.splits == 1) return st;
+    const int total = (int)numel_w(g);
+    hipLaunchKernelGGL(wgrad_reduce_kernel, dim3(cdiv(total, 256)), dim3(256), 0, s, ws, dzdw, total, pl.splits);
+    return check_launch();
+}
+
 size_t workspace_bytes(const Geom &g, int op) {
     switch (op) {
         case MCN_OP_BACKWARD_BIAS: {
@@ -109,6 +143,11 @@ size_t workspace_bytes(const Geom &g, int op) {
         case MCN_OP_BACKWARD_DATA: {
             IgemmPlan pl;
             if (igemm_plan_for(g, op, &pl)) return pl.packed_floats * sizeof(float);
+            return 0;
+        }
+        case MCN_OP_BACKWARD_FILTER: {
+            WgradPlan pl;
+            if (wgrad_plan_for(g, &pl)) return pl.partial_floats * sizeof(float);
             return 0;
         }
         default:
@@ -147,7 +186,10 @@ const char *mcn_conv_kernel_name(const mcn_conv_desc *desc, int op) {
             IgemmPlan pl;
             return igemm_plan_for(g, op, &pl) ? "igemm" : "direct";
         }
-        case MCN_OP_BACKWARD_FILTER: return "direct";
+        case MCN_OP_BACKWARD_FILTER: {
+            WgradPlan pl;
+            return wgrad_plan_for(g, &pl) ? "wgrad_igemm" : "direct";
+        }
         case MCN_OP_BACKWARD_BIAS: return "reduce2";
         default: return NULL;
     }
@@ -195,6 +237,8 @@ int mcn_conv_backward_filter(const mcn_conv_desc *desc, const float *x, const fl
     if (ws_bytes < workspace_bytes(g, MCN_OP_BACKWARD_FILTER) || (!ws && workspace_bytes(g, MCN_OP_BACKWARD_FILTER)))
         return MCN_WORKSPACE_TOO_SMALL;
     hipStream_t s = (hipStream_t)stream;
+    WgradPlan wp;
+    if (wgrad_plan_for(g, &wp)) return launch_wgrad(wp, g, x, dzdy, dzdw, (float *)ws, s);
     const int total = (int)numel_w(g);
     hipLaunchKernelGGL(direct_backward_filter_kernel, dim3(cdiv(total, 4)), dim3(256), 0, s, g, x, dzdy, dzdw, total);
     return check_launch();
