@@ -90,7 +90,6 @@ __global__ __launch_bounds__(64 * WK * WP) void igemm_conv_kernel(IgemmParams P,
     constexpr int NT = 64 * WK * WP;
     constexpr int TK = WK * MK * 32;
     constexpr int TQ = WP * MP * 32;
-    constexpr int UNROLL_FJ = HF ? WF : 1, UNROLL_FI = HF ? HF : 1;
     constexpr int WPT = (DC * TMAX * TK / 4 + NT - 1) / NT;   // float4 weight loads per thread per chunk
     const int Hf = HF ? HF : P.Hf;
     const int Wf = WF ? WF : P.Wf;
@@ -163,13 +162,17 @@ __global__ __launch_bounds__(64 * WK * WP) void igemm_conv_kernel(IgemmParams P,
         ooff[mp] = ok ? io + P.Ho * (jo + P.Wo * (P.Ktot * n)) : -1;
     }
 
+    // accumulators start at the bias of their filter (lane holds 16 filters of each filter tile)
     floatx16 acc[MK][MP];
 #pragma unroll
     for (int mk = 0; mk < MK; ++mk)
 #pragma unroll
-        for (int mp = 0; mp < MP; ++mp)
+        for (int v = 0; v < 16; ++v) {
+            const int kl = kt * TK + (wk * MK + mk) * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
+            const float bv = (bias && kl < P.Kg) ? bias[g * P.Kg + kl] : 0.f;
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc[mk][mp][v] = 0.f;
+            for (int mp = 0; mp < MP; ++mp) acc[mk][mp][v] = bv;
+        }
 
     const float *wsrc = wpk + ((size_t)(g * P.KT + kt) * P.NCH) * wchunk;
     floatx4 wreg[WPT];
@@ -220,23 +223,49 @@ __global__ __launch_bounds__(64 * WK * WP) void igemm_conv_kernel(IgemmParams P,
         if (more) load_chunk(ch + 1);
         const float *wl = ((ch & 1) ? wbuf1 : wbuf0) + aoff;
         const float *xl = (ch & 1) ? xbuf1 : xbuf0;
+        if constexpr (HF > 0) {
+            // filter size known: the (channel pair, tap) steps of a chunk form one flat, fully unrolled
+            // list; the LDS reads of step s+1 are issued before the MFMAs of step s.
+            constexpr int TT = HF * WF;
+            constexpr int NSTEP = (DC / 2) * TT;
+            float a[2][MK], bb[2][MP];
+            auto fetch = [&](int s, int slot) {
+                const int dp = s / TT, tap = s % TT;
+                const int fj = tap / HF, fi = tap % HF;
 #pragma unroll
-        for (int dp = 0; dp < DC / 2; ++dp) {
-#pragma unroll UNROLL_FJ
-            for (int fj = 0; fj < Wf; ++fj) {
-#pragma unroll UNROLL_FI
-                for (int fi = 0; fi < Hf; ++fi) {
-                    const int tap = fi + Hf * fj;
-                    float a[MK], bb[MP];
+                for (int mk = 0; mk < MK; ++mk) a[slot][mk] = wl[((dp * TT + tap) * 2) * TK + mk * 32];
 #pragma unroll
-                    for (int mk = 0; mk < MK; ++mk) a[mk] = wl[((dp * T + tap) * 2) * TK + mk * 32];
+                for (int mp = 0; mp < MP; ++mp) bb[slot][mp] = xl[bbase[mp] + dp * 2 * CP + fj * SRP + fi];
+            };
+            fetch(0, 0);
 #pragma unroll
-                    for (int mp = 0; mp < MP; ++mp) bb[mp] = xl[bbase[mp] + dp * 2 * CP + fj * SRP + fi];
+            for (int s = 0; s < NSTEP; ++s) {
+                if (s + 1 < NSTEP) fetch(s + 1, (s + 1) & 1);
+                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                    for (int mk = 0; mk < MK; ++mk)
+                for (int mk = 0; mk < MK; ++mk)
 #pragma unroll
-                        for (int mp = 0; mp < MP; ++mp)
-                            acc[mk][mp] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[mk], bb[mp], acc[mk][mp], 0, 0, 0);
+                    for (int mp = 0; mp < MP; ++mp)
+                        acc[mk][mp] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[s & 1][mk], bb[s & 1][mp], acc[mk][mp], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        } else {
+#pragma unroll
+            for (int dp = 0; dp < DC / 2; ++dp) {
+                for (int fj = 0; fj < Wf; ++fj) {
+                    for (int fi = 0; fi < Hf; ++fi) {
+                        const int tap = fi + Hf * fj;
+                        float a[MK], bb[MP];
+#pragma unroll
+                        for (int mk = 0; mk < MK; ++mk) a[mk] = wl[((dp * T + tap) * 2) * TK + mk * 32];
+#pragma unroll
+                        for (int mp = 0; mp < MP; ++mp) bb[mp] = xl[bbase[mp] + dp * 2 * CP + fj * SRP + fi];
+#pragma unroll
+                        for (int mk = 0; mk < MK; ++mk)
+#pragma unroll
+                            for (int mp = 0; mp < MP; ++mp)
+                                acc[mk][mp] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[mk], bb[mp], acc[mk][mp], 0, 0, 0);
+                    }
                 }
             }
         }
@@ -253,10 +282,9 @@ __global__ __launch_bounds__(64 * WK * WP) void igemm_conv_kernel(IgemmParams P,
             const int kl = kt * TK + (wk * MK + mk) * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
             if (kl < P.Kg) {
                 const int k = g * P.Kg + kl;
-                const float bv = bias ? bias[k] : 0.f;
 #pragma unroll
                 for (int mp = 0; mp < MP; ++mp)
-                    if (ooff[mp] >= 0) out[(size_t)ooff[mp] + (size_t)HoWo * k] = acc[mk][mp][v] + bv;
+                    if (ooff[mp] >= 0) out[(size_t)ooff[mp] + (size_t)HoWo * k] = acc[mk][mp][v];
             }
         }
     }

@@ -207,18 +207,25 @@ __global__ __launch_bounds__(64 * WK * WR) void wgrad_kernel(WgradParams P, cons
         int tab[STEPS];
 #pragma unroll
         for (int t = 0; t < STEPS; ++t) tab[t] = tb[t];
+        // LDS reads of step t+1 are issued before the MFMAs of step t
+        float a[2][MK], bb[2][MR];
+        auto fetch = [&](int t, int slot) {
+#pragma unroll
+            for (int mk = 0; mk < MK; ++mk) a[slot][mk] = yb[mk * 32 * PCHP + 2 * t];
+#pragma unroll
+            for (int mr = 0; mr < MR; ++mr) bb[slot][mr] = xb[roff[mr] + tab[t]];
+        };
+        fetch(0, 0);
 #pragma unroll
         for (int t = 0; t < STEPS; ++t) {
-            float a[MK], bb[MR];
-#pragma unroll
-            for (int mk = 0; mk < MK; ++mk) a[mk] = yb[mk * 32 * PCHP + 2 * t];
-#pragma unroll
-            for (int mr = 0; mr < MR; ++mr) bb[mr] = xb[roff[mr] + tab[t]];
+            if (t + 1 < STEPS) fetch(t + 1, (t + 1) & 1);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int mk = 0; mk < MK; ++mk)
 #pragma unroll
                 for (int mr = 0; mr < MR; ++mr)
-                    acc[mk][mr] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[mk], bb[mr], acc[mk][mr], 0, 0, 0);
+                    acc[mk][mr] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[t & 1][mk], bb[t & 1][mr], acc[mk][mr], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
         }
         if (more) store_chunk(buf ^ 1);
         __syncthreads();

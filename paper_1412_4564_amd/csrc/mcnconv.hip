@@ -54,12 +54,31 @@ bool igemm_enabled() {
     return !off;
 }
 
-// which view (if any) of this operation runs on the implicit-GEMM kernel
-bool igemm_plan_for(const Geom &g, int op, IgemmPlan *pl) {
-    if (!igemm_enabled()) return false;
-    if (op == MCN_OP_FORWARD) return plan_igemm(forward_view(g), pl);
-    if (op == MCN_OP_BACKWARD_DATA && g.Sh == 1 && g.Sw == 1) return plan_igemm(backward_data_view(g), pl);
-    return false;
+// Plans depend only on the descriptor; planning walks candidate tilings, so the last few
+// descriptors' plans are remembered per host thread (host memory only, no device state).
+struct PlanEntry {
+    mcn_conv_desc d;
+    bool used;
+    bool fwd_ok, bwd_ok, wg_ok;
+    IgemmPlan fwd, bwd;
+    WgradPlan wg;
+};
+constexpr int PLAN_CACHE = 16;
+thread_local PlanEntry g_plans[PLAN_CACHE];
+thread_local int g_plan_next = 0;
+
+const PlanEntry *plans_for(const mcn_conv_desc *d, const Geom &g) {
+    for (int i = 0; i < PLAN_CACHE; ++i)
+        if (g_plans[i].used && memcmp(&g_plans[i].d, d, sizeof(*d)) == 0) return &g_plans[i];
+    PlanEntry &e = g_plans[g_plan_next];
+    g_plan_next = (g_plan_next + 1) % PLAN_CACHE;
+    e.d = *d;
+    e.used = true;
+    const bool on = igemm_enabled();
+    e.fwd_ok = on && plan_igemm(forward_view(g), &e.fwd);
+    e.bwd_ok = on && g.Sh == 1 && g.Sw == 1 && plan_igemm(backward_data_view(g), &e.bwd);
+    e.wg_ok = on && plan_wgrad(g, &e.wg);
+    return &e;
 }
 
 template <int WK, int WP, int MK, int MP, int DC, int HF, int WF, int TMAX>
@@ -99,11 +118,6 @@ int launch_igemm(const IgemmPlan &pl, const ConvView &v, const float *in, const 
     }
 }
 
-bool wgrad_plan_for(const Geom &g, WgradPlan *pl) {
-    if (!igemm_enabled()) return false;
-    return plan_wgrad(g, pl);
-}
-
 template <int WK, int WR, int MK, int MR, int PCH, int EPT, int NCHMAX>
 int launch_wgrad_inst(const WgradPlan &pl, const float *x, const float *dzdy, float *outp, hipStream_t s) {
     if (pl.PCH != PCH) return MCN_BAD_ARG;
@@ -133,23 +147,16 @@ int launch_wgrad(const WgradPlan &pl, const Geom &g, const float *x, const float
     return check_launch();
 }
 
-size_t workspace_bytes(const Geom &g, int op) {
+size_t workspace_bytes(const mcn_conv_desc *d, const Geom &g, int op) {
+    const PlanEntry *e = plans_for(d, g);
     switch (op) {
         case MCN_OP_BACKWARD_BIAS: {
             BiasPlan p = plan_bias(g);
             return (size_t)g.K * p.S * sizeof(float);
         }
-        case MCN_OP_FORWARD:
-        case MCN_OP_BACKWARD_DATA: {
-            IgemmPlan pl;
-            if (igemm_plan_for(g, op, &pl)) return pl.packed_floats * sizeof(float);
-            return 0;
-        }
-        case MCN_OP_BACKWARD_FILTER: {
-            WgradPlan pl;
-            if (wgrad_plan_for(g, &pl)) return pl.partial_floats * sizeof(float);
-            return 0;
-        }
+        case MCN_OP_FORWARD: return e->fwd_ok ? e->fwd.packed_floats * sizeof(float) : 0;
+        case MCN_OP_BACKWARD_DATA: return e->bwd_ok ? e->bwd.packed_floats * sizeof(float) : 0;
+        case MCN_OP_BACKWARD_FILTER: return e->wg_ok ? e->wg.partial_floats * sizeof(float) : 0;
         default:
             return 0;
     }
@@ -173,23 +180,18 @@ int mcn_conv_workspace_size(const mcn_conv_desc *desc, int op, size_t *bytes) {
     int st = make_geom(desc, &g);
     if (st) return st;
     if (!bytes || op < MCN_OP_FORWARD || op > MCN_OP_BACKWARD_BIAS) return MCN_BAD_ARG;
-    *bytes = workspace_bytes(g, op);
+    *bytes = workspace_bytes(desc, g, op);
     return MCN_OK;
 }
 
 const char *mcn_conv_kernel_name(const mcn_conv_desc *desc, int op) {
     Geom g;
     if (make_geom(desc, &g)) return NULL;
+    const PlanEntry *e = plans_for(desc, g);
     switch (op) {
-        case MCN_OP_FORWARD:
-        case MCN_OP_BACKWARD_DATA: {
-            IgemmPlan pl;
-            return igemm_plan_for(g, op, &pl) ? "igemm" : "direct";
-        }
-        case MCN_OP_BACKWARD_FILTER: {
-            WgradPlan pl;
-            return wgrad_plan_for(g, &pl) ? "wgrad_igemm" : "direct";
-        }
+        case MCN_OP_FORWARD: return e->fwd_ok ? "igemm" : "direct";
+        case MCN_OP_BACKWARD_DATA: return e->bwd_ok ? "igemm" : "direct";
+        case MCN_OP_BACKWARD_FILTER: return e->wg_ok ? "wgrad_igemm" : "direct";
         case MCN_OP_BACKWARD_BIAS: return "reduce2";
         default: return NULL;
     }
@@ -201,11 +203,11 @@ int mcn_conv_forward(const mcn_conv_desc *desc, const float *x, const float *w, 
     int st = make_geom(desc, &g);
     if (st) return st;
     if (!x || !w || !y) return MCN_BAD_ARG;
-    if (ws_bytes < workspace_bytes(g, MCN_OP_FORWARD) || (!ws && workspace_bytes(g, MCN_OP_FORWARD)))
-        return MCN_WORKSPACE_TOO_SMALL;
+    const size_t need = workspace_bytes(desc, g, MCN_OP_FORWARD);
+    if (ws_bytes < need || (!ws && need)) return MCN_WORKSPACE_TOO_SMALL;
+    const PlanEntry *pe = plans_for(desc, g);
     hipStream_t s = (hipStream_t)stream;
-    IgemmPlan pl;
-    if (igemm_plan_for(g, MCN_OP_FORWARD, &pl)) return launch_igemm(pl, forward_view(g), x, w, b, y, (float *)ws, s);
+    if (pe->fwd_ok) return launch_igemm(pe->fwd, forward_view(g), x, w, b, y, (float *)ws, s);
     const int total = (int)numel_y(g);
     hipLaunchKernelGGL(direct_forward_kernel, dim3(cdiv(total, 256)), dim3(256), 0, s, g, x, w, b, y, total);
     return check_launch();
@@ -217,12 +219,11 @@ int mcn_conv_backward_data(const mcn_conv_desc *desc, const float *w, const floa
     int st = make_geom(desc, &g);
     if (st) return st;
     if (!w || !dzdy || !dzdx) return MCN_BAD_ARG;
-    if (ws_bytes < workspace_bytes(g, MCN_OP_BACKWARD_DATA) || (!ws && workspace_bytes(g, MCN_OP_BACKWARD_DATA)))
-        return MCN_WORKSPACE_TOO_SMALL;
+    const size_t need = workspace_bytes(desc, g, MCN_OP_BACKWARD_DATA);
+    if (ws_bytes < need || (!ws && need)) return MCN_WORKSPACE_TOO_SMALL;
+    const PlanEntry *pe = plans_for(desc, g);
     hipStream_t s = (hipStream_t)stream;
-    IgemmPlan pl;
-    if (igemm_plan_for(g, MCN_OP_BACKWARD_DATA, &pl))
-        return launch_igemm(pl, backward_data_view(g), dzdy, w, nullptr, dzdx, (float *)ws, s);
+    if (pe->bwd_ok) return launch_igemm(pe->bwd, backward_data_view(g), dzdy, w, nullptr, dzdx, (float *)ws, s);
     const int total = (int)numel_x(g);
     hipLaunchKernelGGL(direct_backward_data_kernel, dim3(cdiv(total, 256)), dim3(256), 0, s, g, w, dzdy, dzdx, total);
     return check_launch();
@@ -234,11 +235,11 @@ int mcn_conv_backward_filter(const mcn_conv_desc *desc, const float *x, const fl
     int st = make_geom(desc, &g);
     if (st) return st;
     if (!x || !dzdy || !dzdw) return MCN_BAD_ARG;
-    if (ws_bytes < workspace_bytes(g, MCN_OP_BACKWARD_FILTER) || (!ws && workspace_bytes(g, MCN_OP_BACKWARD_FILTER)))
-        return MCN_WORKSPACE_TOO_SMALL;
+    const size_t need = workspace_bytes(desc, g, MCN_OP_BACKWARD_FILTER);
+    if (ws_bytes < need || (!ws && need)) return MCN_WORKSPACE_TOO_SMALL;
+    const PlanEntry *pe = plans_for(desc, g);
     hipStream_t s = (hipStream_t)stream;
-    WgradPlan wp;
-    if (wgrad_plan_for(g, &wp)) return launch_wgrad(wp, g, x, dzdy, dzdw, (float *)ws, s);
+    if (pe->wg_ok) return launch_wgrad(pe->wg, g, x, dzdy, dzdw, (float *)ws, s);
     const int total = (int)numel_w(g);
     hipLaunchKernelGGL(direct_backward_filter_kernel, dim3(cdiv(total, 4)), dim3(256), 0, s, g, x, dzdy, dzdw, total);
     return check_launch();
@@ -250,7 +251,7 @@ int mcn_conv_backward_bias(const mcn_conv_desc *desc, const float *dzdy, float *
     int st = make_geom(desc, &g);
     if (st) return st;
     if (!dzdy || !dzdb) return MCN_BAD_ARG;
-    const size_t need = workspace_bytes(g, MCN_OP_BACKWARD_BIAS);
+    const size_t need = workspace_bytes(desc, g, MCN_OP_BACKWARD_BIAS);
     if (ws_bytes < need || (!ws && need)) return MCN_WORKSPACE_TOO_SMALL;
     hipStream_t s = (hipStream_t)stream;
     BiasPlan p = plan_bias(g);
