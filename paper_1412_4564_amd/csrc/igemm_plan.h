@@ -1,5 +1,6 @@
 // Host-side planning for the implicit-GEMM kernel: which instantiation, how the
-// pixels are cut into row blocks and tiles, how large the LDS slab is.
+// pixels are cut into row blocks and tiles, how the reduction is cut into units,
+// how large the LDS buffers are, and how many resident blocks share the work.
 #pragma once
 #include <stdint.h>
 #include <stddef.h>
@@ -10,30 +11,47 @@ namespace mcn {
 
 // One convolution "view": the sum the kernel evaluates (see kern_igemm.h).
 struct ConvView {
-    int H, W, N, Ctot, Cg;
-    int Ho, Wo, Ktot, Kg, G;
+    int H, W, N, Ctot, Cg;          // input array of the view
+    int Ho, Wo, Ktot, Kg, G;        // output pixels computed, output channels
     int Hf, Wf, Sh, Sw, Pt, Pl;
-    int pack_mode;   // 0 forward, 1 input derivative (flipped, transposed filters)
+    int OH, OW, oi0, osi, oj0, osj; // placement of the view's output pixels in the output array
+    // weight packing (PackParams): mode, shape of the caller's filter array, stride phase
+    int pack_mode, HfA, WfA, DfA, pSh, pSw, pi, pj, ldk;
 };
 
 inline ConvView forward_view(const Geom &g) {
-    ConvView v;
+    ConvView v = {};
     v.H = g.H; v.W = g.W; v.N = g.N; v.Ctot = g.D; v.Cg = g.Df;
     v.Ho = g.Ho; v.Wo = g.Wo; v.Ktot = g.K; v.Kg = g.Kg; v.G = g.G;
     v.Hf = g.Hf; v.Wf = g.Wf; v.Sh = g.Sh; v.Sw = g.Sw; v.Pt = g.Pt; v.Pl = g.Pl;
-    v.pack_mode = 0;
+    v.OH = g.Ho; v.OW = g.Wo; v.oi0 = 0; v.osi = 1; v.oj0 = 0; v.osj = 1;
+    v.pack_mode = 0; v.HfA = g.Hf; v.WfA = g.Wf; v.DfA = g.Df;
     return v;
 }
 
-// Stride-1 only: dzdx[i,j] = sum_{fi,fj,k} w[fi,fj,.,k] dzdy[i+Pt-fi, j+Pl-fj, k]; substituting
-// fi' = Hf-1-fi turns it into the forward sum over dzdy with top pad Hf-1-Pt (Sec. 6.1, dz/dX).
-inline ConvView backward_data_view(const Geom &g) {
-    ConvView v;
+// Input derivative, one stride phase (pi, pj), 0 <= pi < Sh, 0 <= pj < Sw  (Sec. 6.1 dz/dX, in the
+// gather form of Sec. 6.2):  dzdx[i,j] = sum_{fi,fj,k} w[fi,fj,.,k] dzdy[(i+Pt-fi)/Sh, (j+Pl-fj)/Sw, k]
+// over the taps for which the divisions are exact.  Rows i = i0 + Sh*m with i0 = (pi-Pt) mod Sh
+// only see taps fi = pi + Sh*a; with t = A-1-a this is a stride-1 sum over dzdy with A taps and top
+// pad A-1-b0, b0 = (i0+Pt-pi)/Sh.  Returns false if the phase has no taps or no rows (nothing to do:
+// those samples of dzdx are zero).
+inline bool backward_data_view(const Geom &g, int pi, int pj, ConvView *out) {
+    const int A = pi < g.Hf ? (g.Hf - pi + g.Sh - 1) / g.Sh : 0;
+    const int Bt = pj < g.Wf ? (g.Wf - pj + g.Sw - 1) / g.Sw : 0;
+    const int i0 = ((pi - g.Pt) % g.Sh + g.Sh) % g.Sh;
+    const int j0 = ((pj - g.Pl) % g.Sw + g.Sw) % g.Sw;
+    const int Mi = i0 < g.H ? (g.H - i0 + g.Sh - 1) / g.Sh : 0;
+    const int Mj = j0 < g.W ? (g.W - j0 + g.Sw - 1) / g.Sw : 0;
+    if (A == 0 || Bt == 0 || Mi == 0 || Mj == 0) return false;
+    const int b0 = (i0 + g.Pt - pi) / g.Sh, d0 = (j0 + g.Pl - pj) / g.Sw;   // exact divisions
+    ConvView v = {};
     v.H = g.Ho; v.W = g.Wo; v.N = g.N; v.Ctot = g.K; v.Cg = g.Kg;
-    v.Ho = g.H; v.Wo = g.W; v.Ktot = g.D; v.Kg = g.Df; v.G = g.G;
-    v.Hf = g.Hf; v.Wf = g.Wf; v.Sh = 1; v.Sw = 1; v.Pt = g.Hf - 1 - g.Pt; v.Pl = g.Wf - 1 - g.Pl;
-    v.pack_mode = 1;
-    return v;
+    v.Ho = Mi; v.Wo = Mj; v.Ktot = g.D; v.Kg = g.Df; v.G = g.G;
+    v.Hf = A; v.Wf = Bt; v.Sh = 1; v.Sw = 1; v.Pt = A - 1 - b0; v.Pl = Bt - 1 - d0;
+    v.OH = g.H; v.OW = g.W; v.oi0 = i0; v.osi = g.Sh; v.oj0 = j0; v.osj = g.Sw;
+    v.pack_mode = 1; v.HfA = g.Hf; v.WfA = g.Wf; v.DfA = g.Df; v.pSh = g.Sh; v.pSw = g.Sw; v.pi = pi; v.pj = pj;
+    *out = v;
+    return true;
 }
 
 enum IgemmShape { IG_128x256 = 0, IG_64x512 = 1, IG_32x256 = 2, IG_NONE = -1 };
@@ -41,17 +59,16 @@ enum IgemmShape { IG_128x256 = 0, IG_64x512 = 1, IG_32x256 = 2, IG_NONE = -1 };
 struct IgemmPlan {
     int shape;          // IgemmShape
     bool fixed33;       // 3x3 filter instantiation
-    int DC;             // channels per chunk
     int TK, TQ, NT;
     IgemmParams P;
+    PackParams Q;
     size_t lds_bytes;
     size_t packed_floats;
-    int blocks;
+    size_t partial_floats;   // 2 slots of TK*TQ per resident block
 };
 
-constexpr int IGEMM_EPT = 2;
-constexpr int IGEMM_TMAX = 25;
 constexpr size_t IGEMM_LDS_LIMIT = 160 * 1024;
+constexpr int IGEMM_FIXED_DC = 8;
 
 // exact number of slab columns the worst pixel tile needs
 inline int slab_columns(const ConvView &v, int TI, int TQ, int Wp) {
@@ -69,49 +86,96 @@ inline int slab_columns(const ConvView &v, int TI, int TQ, int Wp) {
     return best;
 }
 
-inline bool plan_igemm(const ConvView &v, IgemmPlan *pl) {
+// How a tile's reduction is cut into units.  Returns false if nothing fits.
+struct UnitCut { int pair_mode, DC, TC, NTR, NS; };
+
+inline bool cut_units(const ConvView &v, int TK, int64_t CP, size_t lds_left, UnitCut *uc) {
     const int T = v.Hf * v.Wf;
-    if (T > IGEMM_TMAX) return false;
+    double best = 1e30;
+    bool found = false;
+    for (int mode = 0; mode < 2; ++mode) {
+        for (int NTR = 1; NTR <= T; ++NTR) {
+            int TC = (T + NTR - 1) / NTR;
+            if (mode == 1) TC += TC & 1;                         // tap pairs: even capacity
+            if ((int64_t)(NTR - 1) * TC >= T) continue;          // an empty last range
+            for (int DC = 1; DC <= 64; ++DC) {
+                if (mode == 0 && (DC & 1)) continue;
+                if (DC > 1 && DC - (mode == 0 ? 2 : 1) >= v.Cg) break;   // more padding channels than needed
+                int NS = mode == 0 ? (DC / 2) * TC : DC * (TC / 2);
+                NS += NS & 1;
+                if (NS > 80) continue;
+                const size_t lds = (2 * (size_t)NS * 2 * TK + 2 * (size_t)DC * CP) * 4;
+                if (lds > lds_left) continue;
+                // work actually issued per tile / useful work
+                const int NCG = (v.Cg + DC - 1) / DC;
+                const double issued = (double)NCG * NTR * NS * 2;
+                const double useful = (double)v.Cg * T;
+                // prefer little padding, then ~40 steps per unit, then few slab reloads (NTR small)
+                const double score = issued / useful * (1.0 + 0.002 * (NS > 40 ? NS - 40 : 40 - NS)) *
+                                     (1.0 + 0.01 * (NTR - 1));
+                if (score < best) { best = score; found = true; uc->pair_mode = mode; uc->DC = DC; uc->TC = TC; uc->NTR = NTR; uc->NS = NS; }
+            }
+        }
+    }
+    return found;
+}
+
+inline bool plan_igemm(const ConvView &v, int n_cu, IgemmPlan *pl) {
+    const int T = v.Hf * v.Wf;
     int shape, WK, WP, MK, MP;
     if (v.Kg > 64) { shape = IG_128x256; WK = 2; WP = 4; MK = 2; MP = 2; }
     else if (v.Kg > 32) { shape = IG_64x512; WK = 1; WP = 8; MK = 2; MP = 2; }
     else { shape = IG_32x256; WK = 1; WP = 4; MK = 1; MP = 2; }
     const int TK = WK * MK * 32, TQ = WP * MP * 32, NT = 64 * WK * WP;
-    const bool fixed33 = (v.Hf == 3 && v.Wf == 3);
-    int DC = fixed33 ? 8 : 4;
-    if (!fixed33 && T > 16 && TK == 128) DC = 4;
+    const bool fixed33 = (v.Hf == 3 && v.Wf == 3 && v.Cg >= 2 * IGEMM_FIXED_DC);
     const int Wp = (v.Wo - 1) * v.Sw + v.Wf;
-    const size_t wchunk = (size_t)DC * T * TK;
-
     // candidates for the row-block height
-    int cand[40];
+    int cand[48];
     int nc = 0;
     cand[nc++] = v.Ho;
     for (int parts = 2; parts <= 16; ++parts) cand[nc++] = (v.Ho + parts - 1) / parts;
     for (int t = 32; t <= 256; t += 32) cand[nc++] = t;
+    for (int t = 1; t <= 16; t *= 2) cand[nc++] = t;
     double best_score = 1e30;
     int bestTI = 0, bestSC = 0;
+    UnitCut best_uc = {};
     for (int a = 0; a < nc; ++a) {
         const int TI = cand[a];
         if (TI < 1 || TI > v.Ho) continue;
         const int64_t SR = (int64_t)(TI - 1) * v.Sh + v.Hf;
-        if (SR > 4096) continue;
+        if (SR > 8192) continue;
         if ((int64_t)TI * v.Wo * v.N >= ((int64_t)1 << 30)) continue;
         const int SC = slab_columns(v, TI, TQ, Wp);
         const int64_t CP = SR * SC;
-        if (CP > (int64_t)IGEMM_EPT * NT) continue;
-        const size_t lds = (2 * wchunk + 2 * (size_t)DC * CP) * sizeof(float);
-        if (lds > IGEMM_LDS_LIMIT) continue;
+        if (CP > 16 * NT) continue;
+        // an image crossing inside a tile moves the window by whole images: keep offsets in range
+        const int64_t span = (int64_t)SC / Wp + 2;
+        if ((double)span * v.Ctot * v.H * v.W * 4.0 >= 2147483647.0) continue;
+        const int EPT = (int)((CP + NT - 1) / NT);
+        const size_t fixed_lds = ((size_t)EPT * NT + 4) * 4;
+        UnitCut uc;
+        if (fixed33) {
+            uc.pair_mode = 0; uc.DC = IGEMM_FIXED_DC; uc.TC = 9; uc.NTR = 1; uc.NS = (IGEMM_FIXED_DC / 2) * 9;
+            if ((2 * (size_t)uc.NS * 2 * TK + 2 * (size_t)uc.DC * CP) * 4 + fixed_lds > IGEMM_LDS_LIMIT) continue;
+        } else {
+            if (fixed_lds + 4096 > IGEMM_LDS_LIMIT) continue;
+            // the offset table needs NTR*NS*2 ints: reserve 16 KB for it up front
+            if (!cut_units(v, TK, CP, IGEMM_LDS_LIMIT - fixed_lds - 16384, &uc)) continue;
+            if ((size_t)uc.NTR * uc.NS * 2 * 4 > 16384) continue;
+        }
         const int RB = (v.Ho + TI - 1) / TI;
         const int64_t QN = (int64_t)TI * v.Wo * v.N;
         const int64_t PT = (QN + TQ - 1) / TQ;
         const double mfma_waste = (double)RB * PT * TQ / ((double)v.Ho * v.Wo * v.N);
-        const double score = mfma_waste * (1.0 + 0.05 * (double)CP / TQ);
-        if (score < best_score) { best_score = score; bestTI = TI; bestSC = SC; }
+        const int NCG = (v.Cg + uc.DC - 1) / uc.DC;
+        const double red_waste = (double)NCG * uc.NTR * uc.NS * 2 / ((double)v.Cg * T);
+        const double score = mfma_waste * red_waste * (1.0 + 0.05 * (double)CP / TQ);
+        if (score < best_score) { best_score = score; bestTI = TI; bestSC = SC; best_uc = uc; }
     }
     if (!bestTI) return false;
 
     IgemmParams &P = pl->P;
+    P = IgemmParams{};
     P.H = v.H; P.W = v.W; P.N = v.N; P.Ctot = v.Ctot; P.Cg = v.Cg;
     P.Ho = v.Ho; P.Wo = v.Wo; P.Ktot = v.Ktot; P.Kg = v.Kg; P.G = v.G;
     P.Hf = v.Hf; P.Wf = v.Wf; P.Sh = v.Sh; P.Sw = v.Sw; P.Pt = v.Pt; P.Pl = v.Pl;
@@ -119,16 +183,35 @@ inline bool plan_igemm(const ConvView &v, IgemmPlan *pl) {
     P.Wp = Wp;
     P.SR = (bestTI - 1) * v.Sh + v.Hf; P.SRP = P.SR;
     P.CP = P.SRP * bestSC;
+    P.EPT = (P.CP + NT - 1) / NT;
     P.KT = (v.Kg + TK - 1) / TK;
-    P.NCH = (v.Cg + DC - 1) / DC;
     P.QN = bestTI * v.Wo * v.N;
     P.PT = (P.QN + TQ - 1) / TQ;
-    const int64_t blocks = (int64_t)v.G * P.RB * P.PT * P.KT;
-    if (blocks >= ((int64_t)1 << 31)) return false;
-    pl->shape = shape; pl->fixed33 = fixed33; pl->DC = DC; pl->TK = TK; pl->TQ = TQ; pl->NT = NT;
-    pl->lds_bytes = (2 * wchunk + 2 * (size_t)DC * P.CP) * sizeof(float);
-    pl->packed_floats = (size_t)v.G * P.KT * P.NCH * wchunk;
-    pl->blocks = (int)blocks;
+    P.DC = best_uc.DC; P.TC = best_uc.TC; P.NTR = best_uc.NTR; P.NS = best_uc.NS; P.pair_mode = best_uc.pair_mode;
+    P.NU = ((v.Cg + P.DC - 1) / P.DC) * P.NTR;
+    const int64_t tiles = (int64_t)v.G * P.RB * P.PT * P.KT;
+    if (tiles >= ((int64_t)1 << 30)) return false;
+    P.tiles = (int)tiles;
+    const int64_t total = tiles * P.NU;
+    P.nblocks = (int)(total < n_cu ? total : n_cu);
+    P.OH = v.OH; P.OW = v.OW; P.oi0 = v.oi0; P.osi = v.osi; P.oj0 = v.oj0; P.osj = v.osj;
+    const size_t wsz = (size_t)P.NS * 2 * TK;
+    pl->packed_floats = (size_t)v.G * P.KT * P.NU * wsz;
+    if (pl->packed_floats * 4 >= 2147483647ull) return false;
+    P.packed_bytes = (unsigned)(pl->packed_floats * 4);
+    pl->partial_floats = P.nblocks > 1 ? (size_t)2 * P.nblocks * TK * TQ : 0;
+    pl->shape = shape; pl->fixed33 = fixed33; pl->TK = TK; pl->TQ = TQ; pl->NT = NT;
+    pl->lds_bytes = (2 * wsz + 2 * (size_t)P.DC * P.CP + (size_t)P.EPT * NT +
+                     (fixed33 ? 0 : (size_t)P.NTR * P.NS * 2) + 4) * sizeof(float);
+    if (pl->lds_bytes > IGEMM_LDS_LIMIT) return false;
+
+    PackParams &Q = pl->Q;
+    Q = PackParams{};
+    Q.Hf = v.Hf; Q.Wf = v.Wf; Q.HfA = v.HfA; Q.WfA = v.WfA; Q.DfA = v.DfA;
+    Q.Kg = v.Kg; Q.Cg = v.Cg; Q.G = v.G; Q.KT = P.KT; Q.NU = P.NU; Q.NTR = P.NTR; Q.NS = P.NS; Q.TK = TK;
+    Q.DC = P.DC; Q.TC = P.TC; Q.pair_mode = P.pair_mode; Q.mode = v.pack_mode;
+    Q.Sh = v.pSh; Q.Sw = v.pSw; Q.pi = v.pi; Q.pj = v.pj; Q.ldk = v.ldk;
+    Q.total = (int)pl->packed_floats;
     return true;
 }
 

@@ -78,6 +78,12 @@ __global__ __launch_bounds__(256) void direct_backward_data_kernel(Geom g, const
     dzdx[idx] = acc;
 }
 
+// out[0..total) = 0  (samples of dzdx that no filter tap reaches when a stride exceeds the filter)
+__global__ __launch_bounds__(256) void zero_fill_kernel(float *__restrict__ out, int total) {
+    const long long lo = (long long)blockIdx.x * 1024, hi = lo + 1024 < total ? lo + 1024 : total;
+    for (long long e = lo + threadIdx.x; e < hi; e += 256) out[e] = 0.f;
+}
+
 __device__ inline float wave_sum(float v) {
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, 64);

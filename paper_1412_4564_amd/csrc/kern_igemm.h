@@ -1,26 +1,38 @@
-// Implicit-GEMM convolution on the fp32 matrix cores (v_mfma_f32_32x32x2_f32).
+// Implicit-GEMM convolution on the fp32 matrix cores (v_mfma_f32_32x32x2_f32),
+// as a persistent kernel that shares the reduction between blocks ("stream-K").
 //
 // Computes the sum of Sec. 4.1 of the MatConvNet manual (arXiv 1412.4564),
 //   out[io,jo,k,n] = bias[k] + sum_{fi,fj,c} wt(k,c,fi,fj) * in[Sh*io+fi-Pt, Sw*jo+fj-Pl, g*Cg+c, n],
 // for one "view" of a convolution.  The forward pass uses it directly; the
-// derivative with respect to the input (Sec. 6.1, dz/dX = phi*(dz/dY F^T)) of a
-// stride-1 convolution is the same sum over dzdy with the filter flipped and the
-// roles of input channels and filters exchanged, so it runs on this kernel too with
-// a different weight packing (Pt, Pl may then be negative = cropping).
+// derivative with respect to the input (Sec. 6.1, dz/dX = phi*(dz/dY F^T)) is the
+// same kind of sum over dzdy with the filter flipped and the roles of input
+// channels and filters exchanged (one such sum per stride phase), and the passes
+// of a fully-connected layer are 1x1 views; all of them run here with a
+// different weight packing.
 //
 // Mapping to the GEMM  OUT[k][pixel] = sum_r WT[k][r] * PATCH[r][pixel]:
-//  * matrix A (32 filters x 2 channels) comes from a packed copy of the weights,
-//    matrix B (2 channels x 32 pixels) from an LDS copy of the input ("slab") --
-//    never from an im2row buffer in HBM.  Lanes run along pixels, which are
-//    contiguous in memory (first array index), so B reads and the final stores
-//    are coalesced.
-//  * pixels of one block: rows are cut into row blocks of TI rows; inside a row
+//  * matrix A (32 filters x 2 reduction elements) comes from a packed copy of the
+//    weights, matrix B (2 reduction elements x 32 pixels) from an LDS copy of the
+//    input ("slab") -- never from an im2row buffer in HBM.  Lanes run along pixels,
+//    which are contiguous in memory (first array index), so slab loads, B reads and
+//    the final stores are coalesced.
+//  * pixels of one tile: rows are cut into row blocks of TI rows; inside a row
 //    block the pixels are numbered q = ii + TI*(jo + Wo*n), i.e. columns of all
-//    images are chained, and a block takes TQ consecutive q.  The slab holds, per
+//    images are chained, and a tile takes TQ consecutive q.  The slab holds, per
 //    channel, every input column/row those pixels read, so filter tap (fi,fj) of
 //    pixel q is the slab element at  base(q) + fi + SRP*fj.
-//  * reduction: channels in chunks of DC, double-buffered in LDS; inside a chunk
-//    all taps; one MFMA consumes two channels of one tap.
+//  * reduction: a tile's reduction is cut into NU units of DC channels x TC taps.
+//    One unit = NS steps of one MFMA per accumulator; a step consumes either two
+//    channels of one tap (pair_mode 0) or two taps of one channel (pair_mode 1).
+//  * scheduling: the list of all (tile, unit) pairs is cut into nblocks equal
+//    contiguous ranges, one per resident block, so every compute unit gets the same
+//    amount of matrix work whatever the number of tiles.  A block that owns a whole
+//    tile writes it to `out`; pieces of a tile shared between blocks go to a
+//    workspace and are summed in block order by igemm_fixup_kernel (no float
+//    atomics: results do not depend on scheduling).
+//  * staging: global -> LDS loads bypass the registers (buffer_load ... lds),
+//    double-buffered one unit ahead; padding is produced by the out-of-range rule of
+//    buffer loads (reads as zero).
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -30,10 +42,16 @@ namespace mcn {
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
+#define MCN_LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
+
+constexpr unsigned SLAB_INVALID = 0x80000000u;   // >= any buffer size used here: reads as 0
+constexpr int BUFFER_FLAGS = 0x00020000;         // raw buffer, 32-bit elements
+constexpr int WAIT_VMCNT0 = 0x0F70;              // s_waitcnt vmcnt(0) only
+
 struct IgemmParams {
     int H, W, N;        // input plane size, batch
     int Ctot, Cg;       // channels in the input array / per group (reduction depth)
-    int Ho, Wo;         // output plane size
+    int Ho, Wo;         // output plane size of this view (rows/columns actually computed)
     int Ktot, Kg, G;    // channels in the output array / per group, groups
     int Hf, Wf, Sh, Sw;
     int Pt, Pl;         // top/left pad (negative = crop)
@@ -41,199 +59,262 @@ struct IgemmParams {
     int Wp;             // columns reserved per image in the chained padded-column index
     int SR, SRP;        // slab rows used / row pitch
     int CP;             // slab channel pitch (floats)
-    int KT, NCH, PT;    // filter tiles per group, channel chunks, pixel tiles per row block
+    int EPT;            // slab elements per thread: ceil(CP / threads)
+    int KT, PT;         // filter tiles per group, pixel tiles per row block
     int QN;             // TI*Wo*N: chained pixels per row block
+    int DC, TC, NTR;    // channels per unit, taps per unit, tap ranges
+    int NU;             // units per tile = ceil(Cg/DC) * NTR
+    int NS;             // steps per unit (even)
+    int pair_mode;      // 0: a step pairs two channels, 1: a step pairs two taps
+    int tiles;          // G*RB*PT*KT
+    int nblocks;        // resident blocks sharing tiles*NU units
+    // where output pixel (io, jo) of this view lands in the output array (stride phases of dzdx)
+    int OH, OW;         // plane size of the output array
+    int oi0, osi, oj0, osj;   // row = oi0 + osi*io, column = oj0 + osj*jo
+    unsigned packed_bytes;    // size of the packed weights of this view
 };
 
-constexpr unsigned SLAB_INVALID = 0x80000000u;   // >= any per-block buffer size: reads as 0
+// Blocks on consecutive hardware ids land on different XCDs; give each XCD a contiguous
+// share of the work so that neighbouring tiles (shared halo, same weights) meet in one L2.
+__device__ __host__ inline int sk_virtual_block(int b, int nblocks) {
+    return (nblocks % 8 == 0) ? (b % 8) * (nblocks / 8) + b / 8 : b;
+}
+__device__ __host__ inline long long sk_begin(long long total, int nblocks, int vb) {
+    return total * vb / nblocks;
+}
+
+// ---- reduction order of a unit ------------------------------------------------------------
+// element (s, h) of tap range tr: local channel cl and tap, or tap = -1 if it is padding
+__device__ inline void unit_element(int pair_mode, int DC, int TC, int T, int tr, int s, int h, int *cl, int *tap) {
+    int c, t;
+    if (pair_mode == 0) {
+        const int dp = s / TC;
+        c = 2 * dp + h;
+        t = tr * TC + (s - dp * TC);
+    } else {
+        const int hp = TC / 2;
+        c = s / hp;
+        t = tr * TC + 2 * (s - c * hp) + h;
+    }
+    if (c >= DC || t >= T || t >= (tr + 1) * TC) t = -1;
+    *cl = c;
+    *tap = t;
+}
 
 // ---- weight packing ------------------------------------------------------------------
-// packed[g][kt][ch][dp][tap][half][kk] = wt(k = kt*TK+kk, c = ch*DC + 2*dp + half, tap), 0 outside.
+// packed[g][kt][unit][s][h][kk] = wt(k = kt*TK+kk, c = cg*DC + cl, tap), 0 where padded.
 // mode 0 (forward):        wt(k,c,fi,fj) = w[fi, fj, c, g*Kg + k]
-// mode 1 (input derivative of a stride-1 convolution, Kg = D', Cg = K/G):
-//                          wt(k,c,fi,fj) = w[Hf-1-fi, Wf-1-fj, k, g*Cg + c]
+// mode 1 (input derivative, Kg = D', Cg = K/G; one call per stride phase (pi, pj)):
+//     view tap (ti,tj) is filter tap fi = pi + Sh*(Hfv-1-ti), fj = pj + Sw*(Wfv-1-tj):
+//                          wt(k,c,ti,tj) = w[fi, fj, k, g*Cg + c]
+// mode 2 (1x1 view whose weights are a transposed matrix, used for the filter derivative of a
+//     fully-connected layer):  wt(k,c) = w[k + ldk*c]
+struct PackParams {
+    int Hf, Wf;            // taps of the view
+    int HfA, WfA, DfA;     // shape of the caller's filter array (modes 0, 1)
+    int Kg, Cg, G, KT, NU, NTR, NS, TK, DC, TC, pair_mode, mode;
+    int Sh, Sw, pi, pj;    // mode 1
+    int ldk;               // mode 2
+    int total;
+};
+
 __global__ __launch_bounds__(256) void igemm_pack_weights_kernel(const float *__restrict__ w, float *__restrict__ packed,
-                                                                 int Hf, int Wf, int Df, int Kg, int Cg, int G, int KT,
-                                                                 int NCH, int TK, int DC, int mode, int total) {
+                                                                 PackParams Q) {
     int p = blockIdx.x * 256 + threadIdx.x;
-    if (p >= total) return;
-    const int T = Hf * Wf;
+    if (p >= Q.total) return;
     int t = p;
-    const int kk = t % TK; t /= TK;
-    const int half = t & 1; t >>= 1;
-    const int tap = t % T; t /= T;
-    const int dp = t % (DC / 2); t /= (DC / 2);
-    const int ch = t % NCH; t /= NCH;
-    const int kt = t % KT;
-    const int g = t / KT;
-    const int k = kt * TK + kk;
-    const int c = ch * DC + 2 * dp + half;
+    const int kk = t % Q.TK; t /= Q.TK;
+    const int h = t & 1; t >>= 1;
+    const int s = t % Q.NS; t /= Q.NS;
+    const int uu = t % Q.NU; t /= Q.NU;
+    const int kt = t % Q.KT;
+    const int g = t / Q.KT;
+    const int cg = uu / Q.NTR, tr = uu - cg * Q.NTR;
+    int cl, tap;
+    unit_element(Q.pair_mode, Q.DC, Q.TC, Q.Hf * Q.Wf, tr, s, h, &cl, &tap);
+    const int k = kt * Q.TK + kk;
+    const int c = cg * Q.DC + cl;
     float v = 0.f;
-    if (k < Kg && c < Cg) {
-        const int fi = tap % Hf, fj = tap / Hf;
-        if (mode == 0)
-            v = w[fi + Hf * (fj + Wf * (c + (size_t)Df * (g * Kg + k)))];
-        else
-            v = w[(Hf - 1 - fi) + Hf * ((Wf - 1 - fj) + Wf * (k + (size_t)Df * (g * Cg + c)))];
+    if (tap >= 0 && k < Q.Kg && c < Q.Cg) {
+        const int ti = tap % Q.Hf, tj = tap / Q.Hf;
+        if (Q.mode == 0) {
+            v = w[ti + Q.HfA * (tj + Q.WfA * (c + (size_t)Q.DfA * (g * Q.Kg + k)))];
+        } else if (Q.mode == 1) {
+            const int fi = Q.pi + Q.Sh * (Q.Hf - 1 - ti), fj = Q.pj + Q.Sw * (Q.Wf - 1 - tj);
+            v = w[fi + Q.HfA * (fj + Q.WfA * (k + (size_t)Q.DfA * (g * Q.Cg + c)))];
+        } else {
+            v = w[k + (size_t)Q.ldk * c];
+        }
     }
     packed[p] = v;
 }
 
 // ---- main kernel -----------------------------------------------------------------------
 // WK x WP waves; each wave owns MK x MP tiles of 32 filters x 32 pixels.
-// HF, WF > 0: filter size known at compile time; 0: read from the parameters (T <= TMAX).
-template <int WK, int WP, int MK, int MP, int DC, int HF, int WF, int TMAX, int EPT>
-__global__ __launch_bounds__(64 * WK * WP) void igemm_conv_kernel(IgemmParams P, const float *__restrict__ in,
-                                                                  const float *__restrict__ wpk,
-                                                                  const float *__restrict__ bias,
-                                                                  float *__restrict__ out) {
+// HF, WF > 0: filter size and DCF channels per unit known at compile time (pair_mode 0, one tap
+// range, fully unrolled); HF = 0: everything read from the parameters, offsets from a table.
+// WPE: waves per SIMD the register allocation must allow.
+template <int WK, int WP, int MK, int MP, int HF, int WF, int DCF, int WPE>
+__global__ __launch_bounds__(64 * WK * WP, WPE) void igemm_sk_kernel(IgemmParams P, const float *__restrict__ in,
+                                                                     const float *__restrict__ wpk,
+                                                                     const float *__restrict__ bias,
+                                                                     float *__restrict__ out,
+                                                                     float *__restrict__ part) {
     constexpr int NT = 64 * WK * WP;
     constexpr int TK = WK * MK * 32;
     constexpr int TQ = WP * MP * 32;
-    constexpr int WPT = (DC * TMAX * TK / 4 + NT - 1) / NT;   // float4 weight loads per thread per chunk
-    const int Hf = HF ? HF : P.Hf;
-    const int Wf = WF ? WF : P.Wf;
-    const int T = Hf * Wf;
-    const int wchunk = DC * T * TK;        // floats of packed weights per chunk
-    const int wchunk4 = wchunk / 4;
+    constexpr bool FIXED = HF > 0;
+    const int DC = FIXED ? DCF : P.DC;
+    const int NS = FIXED ? (DCF / 2) * HF * WF : P.NS;
+    const int NU = P.NU;
+    const int WSZ = NS * 2 * TK;               // floats of packed weights per unit
     const int CP = P.CP, SRP = P.SRP;
+    const int XSZ = DC * CP;
 
     extern __shared__ __align__(16) float lds[];
-    float *wbuf0 = lds;
-    float *wbuf1 = lds + wchunk;
-    float *xbuf0 = lds + 2 * wchunk;
-    float *xbuf1 = xbuf0 + DC * CP;
+    float *wbuf = lds;                                   // [2][WSZ]
+    float *xbuf = lds + 2 * WSZ;                         // [2][DC*CP]
+    int *gtab = reinterpret_cast<int *>(xbuf + 2 * XSZ); // [EPT][NT]: entry (s, tid) is private to thread tid
+    int *otab = gtab + P.EPT * NT;                       // table mode: [NTR][NS][2] slab offsets
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = tid >> 6;
+    const int half = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wk = wave % WK, wp = wave / WK;
-
-    int b = blockIdx.x;
-    const int kt = b % P.KT; b /= P.KT;
-    const int pt = b % P.PT; b /= P.PT;
-    const int rb = b % P.RB;
-    const int g = b / P.RB;
-
-    const int q0 = pt * TQ;
-    const int qend = min(q0 + TQ, P.QN);
-    const int c_first = q0 / P.TI;
-    const int n_first = c_first / P.Wo;
-    const int u0 = (c_first - n_first * P.Wo) * P.Sw;      // chained column of the slab's first column, relative to image n_first
-    const int row0 = rb * P.TI * P.Sh - P.Pt;              // input row of slab row 0
     const int HW = P.H * P.W;
+    const int OHW = P.OH * P.OW;
 
-    // input window of this block: images n_first.. ; channel 0 of group g
-    const size_t in_base = ((size_t)n_first * P.Ctot + (size_t)g * P.Cg) * HW;
-    const size_t in_total = (size_t)P.N * P.Ctot * HW;
-    size_t in_left = (in_total - in_base) * 4;
-    if (in_left > 0x7fffffffull) in_left = 0x7fffffffull;
-    __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)(in + in_base), 0, (int)in_left, 0x00020000);
+    const int vb = sk_virtual_block(blockIdx.x, P.nblocks);
+    const long long total = (long long)P.tiles * NU;
+    const long long ub = sk_begin(total, P.nblocks, vb), ue = sk_begin(total, P.nblocks, vb + 1);
+    if (ub >= ue) return;
 
-    // slab elements of this thread: byte offset (channel 0) or SLAB_INVALID
-    unsigned goff[EPT];
-#pragma unroll
-    for (int s = 0; s < EPT; ++s) {
-        const int e = tid + NT * s;
-        const int col = e / SRP;
-        const int r = e - col * SRP;
-        const int U = u0 + col;
-        const int ni = U / P.Wp;                 // image relative to n_first
-        const int j = U - ni * P.Wp - P.Pl;
-        const int i = row0 + r;
-        const bool ok = e < CP && r < P.SR && i >= 0 && i < P.H && j >= 0 && j < P.W && (n_first + ni) < P.N;
-        goff[s] = ok ? 4u * (unsigned)(i + P.H * j + ni * P.Ctot * HW) : SLAB_INVALID;
+    if constexpr (!FIXED) {
+        const int T = P.Hf * P.Wf;
+        for (int idx = tid; idx < P.NTR * NS * 2; idx += NT) {
+            const int h = idx & 1;
+            const int s = (idx >> 1) % NS;
+            const int tr = (idx >> 1) / NS;
+            int cl, tap;
+            unit_element(P.pair_mode, DC, P.TC, T, tr, s, h, &cl, &tap);
+            otab[idx] = tap >= 0 ? cl * CP + (tap / P.Hf) * SRP + tap % P.Hf : 0;
+        }
     }
 
-    // pixels of this lane
-    int bbase[MP];   // slab offset (floats) of the pixel's window origin, plus this lane's channel half
+    __amdgpu_buffer_rsrc_t wrs = __builtin_amdgcn_make_buffer_rsrc((void *)wpk, 0, (int)P.packed_bytes, BUFFER_FLAGS);
+
+    // ---- load side: tile whose units are being fetched ------------------------------------
+    __amdgpu_buffer_rsrc_t xrs = wrs;
+    unsigned wtile_off = 0;        // byte offset of the tile's packed weights
+    auto setup_load = [&](int t) {
+        const int kt = t % P.KT; t /= P.KT;
+        const int pt = t % P.PT; t /= P.PT;
+        const int rb = t % P.RB;
+        const int g = t / P.RB;
+        const int q0 = pt * TQ;
+        const int c_first = q0 / P.TI;
+        const int n_first = c_first / P.Wo;
+        const int u0 = (c_first - n_first * P.Wo) * P.Sw;   // chained column of the slab's first column
+        const int row0 = rb * P.TI * P.Sh - P.Pt;           // input row of slab row 0
+        const size_t in_base = ((size_t)n_first * P.Ctot + (size_t)g * P.Cg) * HW;
+        size_t in_left = ((size_t)P.N * P.Ctot * HW - in_base) * 4;
+        if (in_left > 0x7fffffffull) in_left = 0x7fffffffull;
+        xrs = __builtin_amdgcn_make_buffer_rsrc((void *)(in + in_base), 0, (int)in_left, BUFFER_FLAGS);
+        wtile_off = (unsigned)((size_t)(g * P.KT + kt) * NU * WSZ * 4);
+        for (int s = 0; s < P.EPT; ++s) {
+            const int e = tid + NT * s;
+            const int col = e / SRP;
+            const int r = e - col * SRP;
+            const int U = u0 + col;
+            const int ni = U / P.Wp;                 // image relative to n_first
+            const int j = U - ni * P.Wp - P.Pl;
+            const int i = row0 + r;
+            const bool ok = e < CP && r < P.SR && i >= 0 && i < P.H && j >= 0 && j < P.W && (n_first + ni) < P.N;
+            gtab[s * NT + tid] = ok ? (int)(4u * (unsigned)(i + P.H * j + ni * P.Ctot * HW)) : (int)SLAB_INVALID;
+        }
+    };
+    // fetch unit uu of the load-side tile into buffer b
+    auto issue_loads = [&](int uu, int b) {
+        float *wb = wbuf + b * WSZ;
+        float *xb = xbuf + b * XSZ;
+        const unsigned woff = wtile_off + (unsigned)uu * (unsigned)WSZ * 4u;
+        for (int e0 = wave * 256; e0 < WSZ; e0 += NT * 4) {       // 16 bytes per lane
+            if (e0 + lane * 4 < WSZ)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(wrs, MCN_LDS_PTR(wb + e0), 16, (unsigned)(e0 + lane * 4) * 4u,
+                                                         woff, 0, 0);
+        }
+        const int cg = FIXED ? uu : uu / P.NTR;
+        const int c0 = cg * DC;
+        for (int s = 0; s < P.EPT; ++s) {
+            const int e0 = wave * 64 + NT * s;
+            if (e0 >= CP) break;
+            const unsigned go = (unsigned)gtab[s * NT + tid];
+            if (e0 + lane < CP) {
+                for (int d = 0; d < DC; ++d) {
+                    const int c = c0 + d;
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(xrs, MCN_LDS_PTR(xb + d * CP + e0), 4,
+                                                             c < P.Cg ? go : SLAB_INVALID,
+                                                             (unsigned)c * (unsigned)HW * 4u, 0, 0);
+                }
+            }
+        }
+    };
+
+    // ---- compute side: tile whose accumulators are live -----------------------------------
+    int bbase[MP];   // slab offset (floats) of the pixel's window origin (+ channel half when FIXED)
     int ooff[MP];    // output offset of (io, jo, k=0 of the array, n), or -1
-#pragma unroll
-    for (int mp = 0; mp < MP; ++mp) {
-        const int q = q0 + (wp * MP + mp) * 32 + (lane & 31);
-        const int ii = q % P.TI;
-        const int c = q / P.TI;
-        const int n = c / P.Wo;
-        const int jo = c - n * P.Wo;
-        const int io = rb * P.TI + ii;
-        const bool ok = q < qend && io < P.Ho;
-        const int ucol = jo * P.Sw + (n - n_first) * P.Wp - u0;
-        bbase[mp] = (ok ? ii * P.Sh + SRP * ucol : 0) + (lane >> 5) * CP;
-        ooff[mp] = ok ? io + P.Ho * (jo + P.Wo * (P.Ktot * n)) : -1;
-    }
-
-    // accumulators start at the bias of their filter (lane holds 16 filters of each filter tile)
+    int c_kt = 0, c_g = 0;
     floatx16 acc[MK][MP];
+    auto setup_compute = [&](int t, bool with_bias) {
+        const int kt = t % P.KT; t /= P.KT;
+        const int pt = t % P.PT; t /= P.PT;
+        const int rb = t % P.RB;
+        const int g = t / P.RB;
+        c_kt = kt; c_g = g;
+        const int q0 = pt * TQ;
+        const int qend = min(q0 + TQ, P.QN);
+        const int c_first = q0 / P.TI;
+        const int n_first = c_first / P.Wo;
+        const int u0 = (c_first - n_first * P.Wo) * P.Sw;
 #pragma unroll
-    for (int mk = 0; mk < MK; ++mk)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int kl = kt * TK + (wk * MK + mk) * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
-            const float bv = (bias && kl < P.Kg) ? bias[g * P.Kg + kl] : 0.f;
-#pragma unroll
-            for (int mp = 0; mp < MP; ++mp) acc[mk][mp][v] = bv;
-        }
-
-    const float *wsrc = wpk + ((size_t)(g * P.KT + kt) * P.NCH) * wchunk;
-    floatx4 wreg[WPT];
-    float xreg[DC][EPT];
-
-    auto load_chunk = [&](int ch) {
-        const floatx4 *src = reinterpret_cast<const floatx4 *>(wsrc + (size_t)ch * wchunk);
-#pragma unroll
-        for (int s = 0; s < WPT; ++s) {
-            const int idx = tid + NT * s;
-            if (idx < wchunk4) wreg[s] = src[idx];
-        }
-#pragma unroll
-        for (int d = 0; d < DC; ++d) {
-            const int c = ch * DC + d;
-            const unsigned soff = (unsigned)c * (unsigned)HW * 4u;
-#pragma unroll
-            for (int s = 0; s < EPT; ++s) {
-                float v = 0.f;
-                if (c < P.Cg) v = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rsrc, goff[s], soff, 0));
-                xreg[d][s] = v;
-            }
-        }
-    };
-    auto store_chunk = [&](float *wb, float *xb) {
-        floatx4 *dst = reinterpret_cast<floatx4 *>(wb);
-#pragma unroll
-        for (int s = 0; s < WPT; ++s) {
-            const int idx = tid + NT * s;
-            if (idx < wchunk4) dst[idx] = wreg[s];
+        for (int mp = 0; mp < MP; ++mp) {
+            const int q = q0 + (wp * MP + mp) * 32 + (lane & 31);
+            const int ii = q % P.TI;
+            const int c = q / P.TI;
+            const int n = c / P.Wo;
+            const int jo = c - n * P.Wo;
+            const int io = rb * P.TI + ii;
+            const bool ok = q < qend && io < P.Ho;
+            const int ucol = jo * P.Sw + (n - n_first) * P.Wp - u0;
+            bbase[mp] = (ok ? ii * P.Sh + SRP * ucol : 0) + (FIXED ? half * CP : 0);
+            ooff[mp] = ok ? (P.oi0 + P.osi * io) + P.OH * ((P.oj0 + P.osj * jo) + P.OW * (P.Ktot * n)) : -1;
         }
 #pragma unroll
-        for (int d = 0; d < DC; ++d)
+        for (int mk = 0; mk < MK; ++mk)
 #pragma unroll
-            for (int s = 0; s < EPT; ++s) {
-                const int e = tid + NT * s;
-                if (e < CP) xb[d * CP + e] = xreg[d][s];
+            for (int v = 0; v < 16; ++v) {
+                const int kl = kt * TK + (wk * MK + mk) * 32 + (v >> 2) * 8 + half * 4 + (v & 3);
+                const float bv = (with_bias && bias && kl < P.Kg) ? bias[g * P.Kg + kl] : 0.f;
+#pragma unroll
+                for (int mp = 0; mp < MP; ++mp) acc[mk][mp][v] = bv;
             }
     };
-
-    load_chunk(0);
-    store_chunk(wbuf0, xbuf0);
-    __syncthreads();
-
-    const int aoff = (lane >> 5) * TK + wk * MK * 32 + (lane & 31);
-    for (int ch = 0; ch < P.NCH; ++ch) {
-        const bool more = ch + 1 < P.NCH;
-        if (more) load_chunk(ch + 1);
-        const float *wl = ((ch & 1) ? wbuf1 : wbuf0) + aoff;
-        const float *xl = (ch & 1) ? xbuf1 : xbuf0;
-        if constexpr (HF > 0) {
-            // filter size known: the (channel pair, tap) steps of a chunk form one flat, fully unrolled
-            // list; the LDS reads of step s+1 are issued before the MFMAs of step s.
+    const int aoff = half * TK + wk * MK * 32 + (lane & 31);
+    auto compute = [&](int uu, int b) {
+        const float *wl = wbuf + b * WSZ + aoff;
+        const float *xl = xbuf + b * XSZ;
+        if constexpr (FIXED) {
+            // the (channel pair, tap) steps of a unit form one flat, fully unrolled list; the LDS
+            // reads of step s+1 are issued before the MFMAs of step s.
             constexpr int TT = HF * WF;
-            constexpr int NSTEP = (DC / 2) * TT;
+            constexpr int NSTEP = (DCF / 2) * TT;
             float a[2][MK], bb[2][MP];
             auto fetch = [&](int s, int slot) {
                 const int dp = s / TT, tap = s % TT;
                 const int fj = tap / HF, fi = tap % HF;
 #pragma unroll
-                for (int mk = 0; mk < MK; ++mk) a[slot][mk] = wl[((dp * TT + tap) * 2) * TK + mk * 32];
+                for (int mk = 0; mk < MK; ++mk) a[slot][mk] = wl[s * 2 * TK + mk * 32];
 #pragma unroll
                 for (int mp = 0; mp < MP; ++mp) bb[slot][mp] = xl[bbase[mp] + dp * 2 * CP + fj * SRP + fi];
             };
@@ -250,43 +331,145 @@ __global__ __launch_bounds__(64 * WK * WP) void igemm_conv_kernel(IgemmParams P,
                 __builtin_amdgcn_sched_barrier(0);
             }
         } else {
+            const int tr = uu % P.NTR;
+            const int *ot = otab + tr * NS * 2 + half;
+            float a0[MK], b0[MP], a1[MK], b1[MP];
+            int o0 = ot[0], o1 = ot[2];
+            auto fetch = [&](float *a, float *bq, int s, int o) {
 #pragma unroll
-            for (int dp = 0; dp < DC / 2; ++dp) {
-                for (int fj = 0; fj < Wf; ++fj) {
-                    for (int fi = 0; fi < Hf; ++fi) {
-                        const int tap = fi + Hf * fj;
-                        float a[MK], bb[MP];
+                for (int mk = 0; mk < MK; ++mk) a[mk] = wl[s * 2 * TK + mk * 32];
 #pragma unroll
-                        for (int mk = 0; mk < MK; ++mk) a[mk] = wl[((dp * T + tap) * 2) * TK + mk * 32];
+                for (int mp = 0; mp < MP; ++mp) bq[mp] = xl[bbase[mp] + o];
+            };
+            auto mma = [&](const float *a, const float *bq) {
 #pragma unroll
-                        for (int mp = 0; mp < MP; ++mp) bb[mp] = xl[bbase[mp] + dp * 2 * CP + fj * SRP + fi];
+                for (int mk = 0; mk < MK; ++mk)
 #pragma unroll
-                        for (int mk = 0; mk < MK; ++mk)
+                    for (int mp = 0; mp < MP; ++mp)
+                        acc[mk][mp] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[mk], bq[mp], acc[mk][mp], 0, 0, 0);
+            };
+            fetch(a0, b0, 0, o0);
+            for (int s = 0; s < NS; s += 2) {
+                const int o0n = ot[2 * min(s + 2, NS - 1)];
+                const int o1n = ot[2 * min(s + 3, NS - 1)];
+                fetch(a1, b1, s + 1, o1);
+                __builtin_amdgcn_sched_barrier(0);
+                mma(a0, b0);
+                __builtin_amdgcn_sched_barrier(0);
+                if (s + 2 < NS) fetch(a0, b0, s + 2, o0n);
+                __builtin_amdgcn_sched_barrier(0);
+                mma(a1, b1);
+                __builtin_amdgcn_sched_barrier(0);
+                o0 = o0n; o1 = o1n;
+            }
+            (void)o0;
+        }
+    };
+    // lane holds pixel (lane&31) of each pixel tile and 16 filters of each filter tile
+    auto store_tile = [&]() {
 #pragma unroll
-                            for (int mp = 0; mp < MP; ++mp)
-                                acc[mk][mp] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[mk], bb[mp], acc[mk][mp], 0, 0, 0);
-                    }
+        for (int mk = 0; mk < MK; ++mk) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int kl = c_kt * TK + (wk * MK + mk) * 32 + (v >> 2) * 8 + half * 4 + (v & 3);
+                if (kl < P.Kg) {
+                    const int k = c_g * P.Kg + kl;
+#pragma unroll
+                    for (int mp = 0; mp < MP; ++mp)
+                        if (ooff[mp] >= 0) out[(size_t)ooff[mp] + (size_t)OHW * k] = acc[mk][mp][v];
                 }
             }
         }
-        if (more) store_chunk((ch & 1) ? wbuf0 : wbuf1, (ch & 1) ? xbuf0 : xbuf1);
-        __syncthreads();
-    }
-
-    // epilogue: lane holds pixel (lane&31) of each pixel tile and 16 filters of each filter tile
-    const int HoWo = P.Ho * P.Wo;
+    };
+    auto store_partial = [&](int slot) {
+        float *dst = part + (size_t)slot * (TK * TQ);
 #pragma unroll
-    for (int mk = 0; mk < MK; ++mk) {
+        for (int mk = 0; mk < MK; ++mk)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int kl = kt * TK + (wk * MK + mk) * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
-            if (kl < P.Kg) {
-                const int k = g * P.Kg + kl;
+            for (int v = 0; v < 16; ++v) {
+                const int kloc = (wk * MK + mk) * 32 + (v >> 2) * 8 + half * 4 + (v & 3);
 #pragma unroll
                 for (int mp = 0; mp < MP; ++mp)
-                    if (ooff[mp] >= 0) out[(size_t)ooff[mp] + (size_t)HoWo * k] = acc[mk][mp][v];
+                    dst[kloc * TQ + (wp * MP + mp) * 32 + (lane & 31)] = acc[mk][mp][v];
             }
+    };
+
+    // ---- the block's range of units --------------------------------------------------------
+    int t_c = (int)(ub / NU);             // compute-side tile and unit
+    int uu_c = (int)(ub - (long long)t_c * NU);
+    int t_l = t_c, uu_l = uu_c;           // the load side runs one unit ahead
+    bool first_segment = true;
+    // the segment starting at unit uu of tile t covers the tile iff it starts at 0 and the
+    // block's range reaches the tile's end
+    auto segment_is_whole = [&](int t, int uu) { return uu == 0 && (long long)(t + 1) * NU <= ue; };
+    setup_load(t_l);
+    issue_loads(uu_l, 0);
+    bool whole = segment_is_whole(t_c, uu_c);
+    setup_compute(t_c, whole);
+
+    const int nunits = (int)(ue - ub);
+    for (int it = 0; it < nunits; ++it) {
+        __builtin_amdgcn_s_waitcnt(WAIT_VMCNT0);   // this wave's LDS-direct loads have landed
+        __syncthreads();                           // everyone's have, and the other buffer is free
+        if (it + 1 < nunits) {
+            if (++uu_l == NU) { uu_l = 0; ++t_l; setup_load(t_l); }
+            issue_loads(uu_l, (it + 1) & 1);
         }
+        compute(uu_c, it & 1);
+        const bool last = it + 1 == nunits;
+        if (uu_c + 1 == NU || last) {
+            if (whole) store_tile();
+            else store_partial(2 * vb + (first_segment ? 0 : 1));
+            first_segment = false;
+            if (!last) {
+                ++t_c; uu_c = 0;
+                whole = segment_is_whole(t_c, 0);
+                setup_compute(t_c, whole);
+            }
+        } else {
+            ++uu_c;
+        }
+    }
+}
+
+// Sum the pieces of every tile that was shared between blocks, in block order, add the bias,
+// and write the tile.  One thread group per (block boundary, slice of the tile); a boundary
+// handles its tile only if it is the first boundary inside that tile.
+template <int TK, int TQ>
+__global__ __launch_bounds__(256) void igemm_fixup_kernel(IgemmParams P, const float *__restrict__ part,
+                                                          const float *__restrict__ bias, float *__restrict__ out) {
+    const int j = blockIdx.x + 1;                    // boundary between virtual blocks j-1 and j
+    const long long total = (long long)P.tiles * P.NU;
+    const long long B = sk_begin(total, P.nblocks, j);
+    const int t = (int)(B / P.NU);
+    const long long t_lo = (long long)t * P.NU, t_hi = t_lo + P.NU;
+    if (B == t_lo) return;                                        // boundary on a tile edge: nothing shared
+    if (sk_begin(total, P.nblocks, j - 1) > t_lo) return;         // an earlier boundary owns this tile
+    int tt = t;
+    const int kt = tt % P.KT; tt /= P.KT;
+    const int pt = tt % P.PT; tt /= P.PT;
+    const int rb = tt % P.RB;
+    const int g = tt / P.RB;
+    const int OHW = P.OH * P.OW;
+    for (int e = blockIdx.y * 256 + threadIdx.x; e < TK * TQ; e += gridDim.y * 256) {
+        const int kloc = e / TQ, ql = e - kloc * TQ;
+        const int kl = kt * TK + kloc;
+        const int q = pt * TQ + ql;
+        const int ii = q % P.TI;
+        const int c = q / P.TI;
+        const int n = c / P.Wo;
+        const int jo = c - n * P.Wo;
+        const int io = rb * P.TI + ii;
+        if (kl >= P.Kg || q >= P.QN || io >= P.Ho) continue;
+        float acc = bias ? bias[g * P.Kg + kl] : 0.f;
+        for (int b = j - 1; b < P.nblocks; ++b) {
+            const long long bb = sk_begin(total, P.nblocks, b);
+            if (bb >= t_hi) break;
+            const int slot = 2 * b + (bb >= t_lo ? 0 : 1);
+            acc += part[(size_t)slot * (TK * TQ) + e];
+        }
+        out[(size_t)((P.oi0 + P.osi * io) + P.OH * ((P.oj0 + P.osj * jo) + P.OW * (P.Ktot * n))) +
+            (size_t)OHW * (g * P.Kg + kl)] = acc;
     }
 }
 

@@ -54,18 +54,42 @@ bool igemm_enabled() {
     return !off;
 }
 
+// Number of compute units of the current device (the persistent kernels run one block per
+// unit).  Falls back to the MI355X figure when no device can be asked, so that size queries
+// work on a machine without a GPU.
+int compute_units() {
+    static int n = 0;
+    if (n == 0) {
+        int dev = 0, v = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
+            n = v;
+        else
+            n = 256;
+        (void)hipGetLastError();
+    }
+    return n;
+}
+
+constexpr int MAX_PHASES = 64;
+
 // Plans depend only on the descriptor; planning walks candidate tilings, so the last few
 // descriptors' plans are remembered per host thread (host memory only, no device state).
 struct PlanEntry {
     mcn_conv_desc d;
     bool used;
     bool fwd_ok, bwd_ok, wg_ok;
-    IgemmPlan fwd, bwd;
+    IgemmPlan fwd;
+    int n_bwd;                 // stride phases of the input derivative that have work
+    bool bwd_fill;             // some samples of dzdx belong to no phase with work: zero-fill first
+    IgemmPlan bwd[MAX_PHASES];
     WgradPlan wg;
 };
-constexpr int PLAN_CACHE = 16;
+constexpr int PLAN_CACHE = 8;
 thread_local PlanEntry g_plans[PLAN_CACHE];
 thread_local int g_plan_next = 0;
+
+inline size_t align256(size_t n) { return (n + 255) & ~(size_t)255; }
 
 const PlanEntry *plans_for(const mcn_conv_desc *d, const Geom &g) {
     for (int i = 0; i < PLAN_CACHE; ++i)
@@ -75,44 +99,66 @@ const PlanEntry *plans_for(const mcn_conv_desc *d, const Geom &g) {
     e.d = *d;
     e.used = true;
     const bool on = igemm_enabled();
-    e.fwd_ok = on && plan_igemm(forward_view(g), &e.fwd);
-    e.bwd_ok = on && g.Sh == 1 && g.Sw == 1 && plan_igemm(backward_data_view(g), &e.bwd);
+    const int ncu = compute_units();
+    e.fwd_ok = on && plan_igemm(forward_view(g), ncu, &e.fwd);
+    e.bwd_ok = on && g.Sh * g.Sw <= MAX_PHASES;
+    e.n_bwd = 0;
+    e.bwd_fill = false;
+    if (e.bwd_ok) {
+        for (int pj = 0; pj < g.Sw && e.bwd_ok; ++pj)
+            for (int pi = 0; pi < g.Sh && e.bwd_ok; ++pi) {
+                ConvView v;
+                if (!backward_data_view(g, pi, pj, &v)) {
+                    // no taps in this phase: its samples (if it has any) are zero
+                    e.bwd_fill = true;
+                    continue;
+                }
+                e.bwd_ok = plan_igemm(v, ncu, &e.bwd[e.n_bwd++]);
+            }
+    }
     e.wg_ok = on && plan_wgrad(g, &e.wg);
     return &e;
 }
 
-template <int WK, int WP, int MK, int MP, int DC, int HF, int WF, int TMAX>
+template <int WK, int WP, int MK, int MP, int HF, int WF, int DCF>
 int launch_igemm_inst(const IgemmPlan &pl, const float *in, const float *wpk, const float *bias, float *out,
-                      hipStream_t s) {
-    auto kern = igemm_conv_kernel<WK, WP, MK, MP, DC, HF, WF, TMAX, IGEMM_EPT>;
+                      float *part, hipStream_t s) {
+    auto kern = igemm_sk_kernel<WK, WP, MK, MP, HF, WF, DCF, 2>;
     if (pl.lds_bytes > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
                                            (int)pl.lds_bytes);
         if (e != hipSuccess) { g_last_hip_error = (int)e; return MCN_HIP_ERROR; }
     }
-    hipLaunchKernelGGL(kern, dim3(pl.blocks), dim3(64 * WK * WP), pl.lds_bytes, s, pl.P, in, wpk, bias, out);
+    hipLaunchKernelGGL(kern, dim3(pl.P.nblocks), dim3(64 * WK * WP), pl.lds_bytes, s, pl.P, in, wpk, bias, out, part);
+    int st = check_launch();
+    if (st || pl.P.nblocks < 2) return st;
+    constexpr int TK = WK * MK * 32, TQ = WP * MP * 32;
+    hipLaunchKernelGGL((igemm_fixup_kernel<TK, TQ>), dim3(pl.P.nblocks - 1, 16), dim3(256), 0, s, pl.P, part, bias, out);
     return check_launch();
 }
 
-int launch_igemm(const IgemmPlan &pl, const ConvView &v, const float *in, const float *w, const float *bias,
-                 float *out, float *packed, hipStream_t s) {
-    const int total = (int)pl.packed_floats;
-    // for the packing kernel the weight array is always the caller's w : Hf x Wf x Df x K
-    const int Df = v.pack_mode == 0 ? v.Cg : v.Kg;
-    hipLaunchKernelGGL(igemm_pack_weights_kernel, dim3(cdiv(total, 256)), dim3(256), 0, s, w, packed, v.Hf, v.Wf, Df,
-                       v.Kg, v.Cg, v.G, pl.P.KT, pl.P.NCH, pl.TK, pl.DC, v.pack_mode, total);
+// workspace of one view: [packed weights][partial tiles]
+size_t igemm_ws_bytes(const IgemmPlan &pl) {
+    return align256(pl.packed_floats * sizeof(float)) + pl.partial_floats * sizeof(float);
+}
+
+int launch_igemm(const IgemmPlan &pl, const float *in, const float *w, const float *bias, float *out, void *ws,
+                 hipStream_t s) {
+    float *packed = (float *)ws;
+    float *part = (float *)((char *)ws + align256(pl.packed_floats * sizeof(float)));
+    hipLaunchKernelGGL(igemm_pack_weights_kernel, dim3(cdiv(pl.Q.total, 256)), dim3(256), 0, s, w, packed, pl.Q);
     int st = check_launch();
     if (st) return st;
     switch (pl.shape) {
         case IG_128x256:
-            return pl.fixed33 ? launch_igemm_inst<2, 4, 2, 2, 8, 3, 3, 9>(pl, in, packed, bias, out, s)
-                              : launch_igemm_inst<2, 4, 2, 2, 4, 0, 0, IGEMM_TMAX>(pl, in, packed, bias, out, s);
+            return pl.fixed33 ? launch_igemm_inst<2, 4, 2, 2, 3, 3, IGEMM_FIXED_DC>(pl, in, packed, bias, out, part, s)
+                              : launch_igemm_inst<2, 4, 2, 2, 0, 0, 0>(pl, in, packed, bias, out, part, s);
         case IG_64x512:
-            return pl.fixed33 ? launch_igemm_inst<1, 8, 2, 2, 8, 3, 3, 9>(pl, in, packed, bias, out, s)
-                              : launch_igemm_inst<1, 8, 2, 2, 4, 0, 0, IGEMM_TMAX>(pl, in, packed, bias, out, s);
+            return pl.fixed33 ? launch_igemm_inst<1, 8, 2, 2, 3, 3, IGEMM_FIXED_DC>(pl, in, packed, bias, out, part, s)
+                              : launch_igemm_inst<1, 8, 2, 2, 0, 0, 0>(pl, in, packed, bias, out, part, s);
         case IG_32x256:
-            return pl.fixed33 ? launch_igemm_inst<1, 4, 1, 2, 8, 3, 3, 9>(pl, in, packed, bias, out, s)
-                              : launch_igemm_inst<1, 4, 1, 2, 4, 0, 0, IGEMM_TMAX>(pl, in, packed, bias, out, s);
+            return pl.fixed33 ? launch_igemm_inst<1, 4, 1, 2, 3, 3, IGEMM_FIXED_DC>(pl, in, packed, bias, out, part, s)
+                              : launch_igemm_inst<1, 4, 1, 2, 0, 0, 0>(pl, in, packed, bias, out, part, s);
         default:
             return MCN_BAD_ARG;
     }
@@ -154,8 +200,14 @@ size_t workspace_bytes(const mcn_conv_desc *d, const Geom &g, int op) {
             BiasPlan p = plan_bias(g);
             return (size_t)g.K * p.S * sizeof(float);
         }
-        case MCN_OP_FORWARD: return e->fwd_ok ? e->fwd.packed_floats * sizeof(float) : 0;
-        case MCN_OP_BACKWARD_DATA: return e->bwd_ok ? e->bwd.packed_floats * sizeof(float) : 0;
+        case MCN_OP_FORWARD: return e->fwd_ok ? igemm_ws_bytes(e->fwd) : 0;
+        case MCN_OP_BACKWARD_DATA: {
+            // the phases run one after the other on the stream and share one region
+            size_t m = 0;
+            if (e->bwd_ok)
+                for (int i = 0; i < e->n_bwd; ++i) { size_t b = igemm_ws_bytes(e->bwd[i]); if (b > m) m = b; }
+            return m;
+        }
         case MCN_OP_BACKWARD_FILTER: return e->wg_ok ? e->wg.partial_floats * sizeof(float) : 0;
         default:
             return 0;
@@ -207,7 +259,7 @@ int mcn_conv_forward(const mcn_conv_desc *desc, const float *x, const float *w, 
     if (ws_bytes < need || (!ws && need)) return MCN_WORKSPACE_TOO_SMALL;
     const PlanEntry *pe = plans_for(desc, g);
     hipStream_t s = (hipStream_t)stream;
-    if (pe->fwd_ok) return launch_igemm(pe->fwd, forward_view(g), x, w, b, y, (float *)ws, s);
+    if (pe->fwd_ok) return launch_igemm(pe->fwd, x, w, b, y, ws, s);
     const int total = (int)numel_y(g);
     hipLaunchKernelGGL(direct_forward_kernel, dim3(cdiv(total, 256)), dim3(256), 0, s, g, x, w, b, y, total);
     return check_launch();
@@ -223,7 +275,19 @@ int mcn_conv_backward_data(const mcn_conv_desc *desc, const float *w, const floa
     if (ws_bytes < need || (!ws && need)) return MCN_WORKSPACE_TOO_SMALL;
     const PlanEntry *pe = plans_for(desc, g);
     hipStream_t s = (hipStream_t)stream;
-    if (pe->bwd_ok) return launch_igemm(pe->bwd, backward_data_view(g), dzdy, w, nullptr, dzdx, (float *)ws, s);
+    if (pe->bwd_ok) {
+        if (pe->bwd_fill) {
+            const int total = (int)numel_x(g);
+            hipLaunchKernelGGL(zero_fill_kernel, dim3(cdiv(total, 1024)), dim3(256), 0, s, dzdx, total);
+            st = check_launch();
+            if (st) return st;
+        }
+        for (int i = 0; i < pe->n_bwd; ++i) {
+            st = launch_igemm(pe->bwd[i], dzdy, w, nullptr, dzdx, ws, s);
+            if (st) return st;
+        }
+        return MCN_OK;
+    }
     const int total = (int)numel_x(g);
     hipLaunchKernelGGL(direct_backward_data_kernel, dim3(cdiv(total, 256)), dim3(256), 0, s, g, w, dzdy, dzdx, total);
     return check_launch();
