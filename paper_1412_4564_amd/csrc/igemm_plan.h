@@ -225,25 +225,40 @@ enum WgradShape { WG_128x128 = 0, WG_64x192 = 1, WG_32x256 = 2 };
 
 struct WgradPlan {
     int shape;
-    int PCH;             // pixels per chunk
     int TK, TR, NT;
     WgradParams P;
     size_t lds_bytes;
-    int splits;          // RB * SPR
-    size_t partial_floats;
-    int blocks;
+    int occupancy;           // resident blocks per compute unit
+    size_t partial_floats;   // 2 slots of TK*TR per resident block
 };
 
-inline bool plan_wgrad(const Geom &g, WgradPlan *pl) {
-    ConvView v = forward_view(g);
+// columns of the slab that PCH consecutive chained pixels can touch: exact if the walk is short,
+// otherwise a bound (never too small)
+inline int wgrad_slab_columns(const ConvView &v, int TI, int PCH, int Wp) {
+    const int64_t QN = (int64_t)TI * v.Wo * v.N;
+    int64_t cols = ((int64_t)PCH - 1 + TI - 1) / TI + 1;
+    if (cols > (int64_t)v.Wo * v.N) cols = (int64_t)v.Wo * v.N;
+    const int64_t D = cols - 1;
+    const int64_t cross = v.Wf >= v.Sw ? (D + v.Wo - 1) / v.Wo : D / v.Wo;
+    const int64_t bound = D * v.Sw + cross * (v.Wf - v.Sw) + v.Wf;
+    if ((QN + PCH - 1) / PCH > 50000) return (int)bound;
+    const int exact = slab_columns(v, TI, PCH, Wp);
+    return exact;
+}
+
+inline bool plan_wgrad(const ConvView &v, int n_cu, WgradPlan *pl) {
     const int T = v.Hf * v.Wf;
-    const int R = T * v.Cg;
-    if ((double)numel_x(g) * 4 >= 2147483647.0 || (double)numel_y(g) * 4 >= 2147483647.0) return false;
-    int shape, WK, WR, MK, MR, EPT, NCHMAX, WGRAD_PCH;
-    if (v.Kg > 64) { shape = WG_128x128; WK = 2; WR = 2; MK = 2; MR = 2; EPT = 2; NCHMAX = 16; WGRAD_PCH = 32; }
-    else if (v.Kg > 32) { shape = WG_64x192; WK = 2; WR = 2; MK = 1; MR = 3; EPT = 2; NCHMAX = 24; WGRAD_PCH = 64; }
-    else { shape = WG_32x256; WK = 1; WR = 4; MK = 1; MR = 2; EPT = 2; NCHMAX = 32; WGRAD_PCH = 32; }
-    const int TK = WK * MK * 32, TR = WR * MR * 32, NT = 64 * WK * WR;
+    const int64_t R64 = (int64_t)T * v.Cg;
+    if (R64 >= ((int64_t)1 << 30)) return false;
+    const int R = (int)R64;
+    // byte offsets into x and dzdy are 32-bit
+    if ((double)v.H * v.W * v.Ctot * v.N * 4 >= 2147483647.0) return false;
+    if ((double)v.Ho * v.Wo * v.Ktot * v.N * 4 >= 2147483647.0) return false;
+    int shape, WK, WR, MK, MR;
+    if (v.Kg > 64) { shape = WG_128x128; WK = 2; WR = 2; MK = 2; MR = 2; }
+    else if (v.Kg > 32) { shape = WG_64x192; WK = 2; WR = 2; MK = 1; MR = 3; }
+    else { shape = WG_32x256; WK = 1; WR = 4; MK = 1; MR = 2; }
+    const int TK = WK * MK * 32, TR = WR * MR * 32, NT = 64 * WK * WR, NW = WK * WR;
     const int RT = (R + TR - 1) / TR;
     int nch_max = 0;
     for (int rt = 0; rt < RT; ++rt) {
@@ -251,72 +266,96 @@ inline bool plan_wgrad(const Geom &g, WgradPlan *pl) {
         const int n = (hi - 1) / T - lo / T + 1;
         if (n > nch_max) nch_max = n;
     }
-    if (nch_max > NCHMAX) return false;
     const int Wp = (v.Wo - 1) * v.Sw + v.Wf;
+    const int klim = v.Kg < TK ? v.Kg : TK;
 
-    int cand[40];
+    int cand[48];
     int nc = 0;
     cand[nc++] = v.Ho;
     for (int parts = 2; parts <= 16; ++parts) cand[nc++] = (v.Ho + parts - 1) / parts;
-    for (int t = 32; t <= 256; t += 32) cand[nc++] = t;
+    for (int t = 32; t <= 128; t += 32) cand[nc++] = t;
+    for (int t = 1; t <= 16; t *= 2) cand[nc++] = t;
     double best = 1e30;
-    int bestTI = 0, bestSC = 0;
+    int bestTI = 0, bestPCH = 0, bestSC = 0, bestSRP = 0, bestCP = 0, bestOcc = 0;
+    size_t bestLds = 0;
     for (int a = 0; a < nc; ++a) {
         const int TI = cand[a];
         if (TI < 1 || TI > v.Ho) continue;
+        bool dup = false;
+        for (int b = 0; b < a; ++b) dup = dup || cand[b] == TI;
+        if (dup) continue;
         const int64_t SR = (int64_t)(TI - 1) * v.Sh + v.Hf;
-        if (SR > 4096) continue;
+        if (SR > 16384) continue;
         const int64_t QN = (int64_t)TI * v.Wo * v.N;
         if (QN >= ((int64_t)1 << 30)) continue;
-        const int SC = slab_columns(v, TI, WGRAD_PCH, Wp);
-        if (SC > 2 * Wp) continue;                       // at most two image crossings per chunk
-        if (SR * SC > (int64_t)EPT * NT) continue;
-        const int RB = (v.Ho + TI - 1) / TI;
-        const double chunks = (double)RB * (double)((QN + WGRAD_PCH - 1) / WGRAD_PCH);
-        const double score = chunks * (1.0 + 0.002 * (double)(SR * SC));
-        if (score < best) { best = score; bestTI = TI; bestSC = SC; }
+        // pitches chosen so that the 32 coefficients a half-wave reads fall in 32 different LDS banks:
+        // bank(r) = fi + SRP*fj + CP*c  ==  r  (mod 32)
+        int SRP = (int)SR;
+        while (SRP % 32 != v.Hf % 32) ++SRP;
+        int pch_cand[16];
+        int np = 0;
+        for (int m = 1; m <= 4; ++m) pch_cand[np++] = TI * m;
+        for (int m = 2; m <= 4; ++m) pch_cand[np++] = (TI + m - 1) / m;
+        pch_cand[np++] = 32; pch_cand[np++] = 64; pch_cand[np++] = 96; pch_cand[np++] = 128;
+        for (int b = 0; b < np; ++b) {
+            int PCH = (pch_cand[b] + 3) & ~3;
+            if (PCH < 8) PCH = 8;
+            if (PCH > 128) continue;
+            const int SC = wgrad_slab_columns(v, TI, PCH, Wp);
+            if (SC >= 32768) continue;
+            int64_t CP = (int64_t)SRP * SC;
+            while (CP % 32 != T % 32) ++CP;
+            const int64_t XS = (int64_t)nch_max * CP;
+            const int NSEG = (PCH + 63) / 64;
+            const int PCHP = PCH | 1;
+            const int EPT = (int)(((int64_t)SRP * SC + NT - 1) / NT);
+            const int64_t lds = (2 * (int64_t)TK * PCHP + 2 * XS + 2 * NSEG * 64 + (int64_t)EPT * NT + 4) * 4;
+            if (lds > (int64_t)IGEMM_LDS_LIMIT) continue;
+            int occ = (int)((int64_t)IGEMM_LDS_LIMIT / lds);
+            if (occ > 2) occ = 2;   // the kernels are compiled for two waves per SIMD
+            const int RB = (v.Ho + TI - 1) / TI;
+            const double units = (double)RB * (double)((QN + PCH - 1) / PCH);
+            const double mfma = (double)(PCH / 2) * MK * MR * 64.0;
+            const double loads = ((double)klim * NSEG + (double)nch_max * (double)((SRP * SC + 63) / 64)) / NW;
+            const double ovh = 900.0 + 24.0 * loads;
+            const double score = units * (mfma + ovh / (occ >= 2 ? 2.0 : 1.0));
+            if (score < best) {
+                best = score; bestTI = TI; bestPCH = PCH; bestSC = SC; bestSRP = SRP; bestCP = (int)CP; bestOcc = occ;
+                bestLds = (size_t)lds;
+            }
+        }
     }
     if (!bestTI) return false;
 
     WgradParams &P = pl->P;
+    P = WgradParams{};
     P.H = v.H; P.W = v.W; P.N = v.N; P.Ctot = v.Ctot; P.Cg = v.Cg;
     P.Ho = v.Ho; P.Wo = v.Wo; P.Ktot = v.Ktot; P.Kg = v.Kg; P.G = v.G;
     P.Hf = v.Hf; P.Wf = v.Wf; P.Sh = v.Sh; P.Sw = v.Sw; P.Pt = v.Pt; P.Pl = v.Pl;
     P.TI = bestTI; P.RB = (v.Ho + bestTI - 1) / bestTI;
     P.Wp = Wp;
     P.SR = (bestTI - 1) * v.Sh + v.Hf;
-    P.SC = bestSC;
-    // pitches chosen so that the 32 coefficients a half-wave reads fall in 32 different LDS banks:
-    // bank(r) = fi + SRP*fj + CP*c  ==  r  (mod 32)
-    int SRP = P.SR;
-    while (SRP % 32 != v.Hf % 32) ++SRP;
-    int CP = SRP * bestSC;
-    while (CP % 32 != T % 32) ++CP;
-    P.SRP = SRP; P.CP = CP;
+    P.SRP = bestSRP; P.SC = bestSC; P.CP = bestCP;
+    P.EPT = (bestSRP * bestSC + NT - 1) / NT;
     P.KT = (v.Kg + TK - 1) / TK; P.RT = RT;
     P.QN = bestTI * v.Wo * v.N;
+    P.PCH = bestPCH; P.PCHP = bestPCH | 1;
+    P.CPR = (P.QN + bestPCH - 1) / bestPCH;
+    const int64_t NU = (int64_t)P.RB * P.CPR;
+    if (NU >= ((int64_t)1 << 30)) return false;
+    P.NU = (int)NU;
     P.R = R;
-    P.XS = nch_max * CP;
-    P.EPTU = (P.SR * bestSC + NT - 1) / NT;
-    pl->PCH = WGRAD_PCH;
-    const int64_t base_blocks = (int64_t)v.G * P.KT * RT * P.RB;
-    const int64_t chunks = (P.QN + WGRAD_PCH - 1) / WGRAD_PCH;
-    int64_t spr = (768 + base_blocks - 1) / base_blocks;
-    if (spr > chunks) spr = chunks;
-    if (spr < 1) spr = 1;
-    int64_t qs = ((chunks + spr - 1) / spr) * WGRAD_PCH;
-    spr = (P.QN + qs - 1) / qs;
-    P.QS = (int)qs; P.SPR = (int)spr;
-    pl->splits = (int)(P.RB * spr);
-    P.direct_out = pl->splits == 1;
-    pl->partial_floats = pl->splits > 1 ? (size_t)pl->splits * (size_t)numel_w(g) : 0;
-    if (pl->partial_floats * 4 > ((size_t)3 << 30)) return false;
-    const int64_t blocks = base_blocks * spr;
-    if (blocks >= ((int64_t)1 << 31)) return false;
-    pl->blocks = (int)blocks;
+    P.XS = nch_max * bestCP;
+    const int64_t tiles = (int64_t)v.G * P.KT * RT;
+    if (tiles >= ((int64_t)1 << 30)) return false;
+    P.tiles = (int)tiles;
+    const int64_t total = tiles * NU;
+    const int64_t want = (int64_t)n_cu * bestOcc;
+    P.nblocks = (int)(total < want ? total : want);
+    pl->occupancy = bestOcc;
+    pl->partial_floats = P.nblocks > 1 ? (size_t)2 * P.nblocks * TK * TR : 0;
     pl->shape = shape; pl->TK = TK; pl->TR = TR; pl->NT = NT;
-    pl->lds_bytes = (size_t)(2 * TK * (WGRAD_PCH + 1) + 2 * WGRAD_PCH + 2 * P.XS) * sizeof(float);
-    if (pl->lds_bytes > IGEMM_LDS_LIMIT) return false;
+    pl->lds_bytes = bestLds;
     return true;
 }
 

@@ -116,7 +116,7 @@ const PlanEntry *plans_for(const mcn_conv_desc *d, const Geom &g) {
                 e.bwd_ok = plan_igemm(v, ncu, &e.bwd[e.n_bwd++]);
             }
     }
-    e.wg_ok = on && plan_wgrad(g, &e.wg);
+    e.wg_ok = on && plan_wgrad(forward_view(g), ncu, &e.wg);
     return &e;
 }
 
@@ -164,33 +164,33 @@ int launch_igemm(const IgemmPlan &pl, const float *in, const float *w, const flo
     }
 }
 
-template <int WK, int WR, int MK, int MR, int PCH, int EPT, int NCHMAX>
-int launch_wgrad_inst(const WgradPlan &pl, const float *x, const float *dzdy, float *outp, hipStream_t s) {
-    if (pl.PCH != PCH) return MCN_BAD_ARG;
-    auto kern = wgrad_kernel<WK, WR, MK, MR, PCH, EPT, NCHMAX>;
+template <int WK, int WR, int MK, int MR>
+int launch_wgrad_inst(const WgradPlan &pl, const float *x, const float *dzdy, const float *rbias, float *out,
+                      float *part, hipStream_t s) {
+    auto kern = wgrad_sk_kernel<WK, WR, MK, MR, 2>;
     if (pl.lds_bytes > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
                                            (int)pl.lds_bytes);
         if (e != hipSuccess) { g_last_hip_error = (int)e; return MCN_HIP_ERROR; }
     }
-    hipLaunchKernelGGL(kern, dim3(pl.blocks), dim3(64 * WK * WR), pl.lds_bytes, s, pl.P, x, dzdy, outp);
+    hipLaunchKernelGGL(kern, dim3(pl.P.nblocks), dim3(64 * WK * WR), pl.lds_bytes, s, pl.P, x, dzdy, rbias, out, part);
+    int st = check_launch();
+    if (st || pl.P.nblocks < 2) return st;
+    constexpr int TK = WK * MK * 32, TR = WR * MR * 32;
+    hipLaunchKernelGGL((wgrad_fixup_kernel<TK, TR>), dim3(pl.P.nblocks - 1, TK * TR / 256), dim3(256), 0, s, pl.P, part,
+                       rbias, out);
     return check_launch();
 }
 
-int launch_wgrad(const WgradPlan &pl, const Geom &g, const float *x, const float *dzdy, float *dzdw, float *ws,
+int launch_wgrad(const WgradPlan &pl, const float *x, const float *dzdy, const float *rbias, float *out, void *ws,
                  hipStream_t s) {
-    float *outp = pl.splits > 1 ? ws : dzdw;
-    int st;
+    float *part = (float *)ws;
     switch (pl.shape) {
-        case WG_128x128: st = launch_wgrad_inst<2, 2, 2, 2, 32, 2, 16>(pl, x, dzdy, outp, s); break;
-        case WG_64x192: st = launch_wgrad_inst<2, 2, 1, 3, 64, 2, 24>(pl, x, dzdy, outp, s); break;
-        case WG_32x256: st = launch_wgrad_inst<1, 4, 1, 2, 32, 2, 32>(pl, x, dzdy, outp, s); break;
+        case WG_128x128: return launch_wgrad_inst<2, 2, 2, 2>(pl, x, dzdy, rbias, out, part, s);
+        case WG_64x192: return launch_wgrad_inst<2, 2, 1, 3>(pl, x, dzdy, rbias, out, part, s);
+        case WG_32x256: return launch_wgrad_inst<1, 4, 1, 2>(pl, x, dzdy, rbias, out, part, s);
         default: return MCN_BAD_ARG;
     }
-    if (st || pl.splits == 1) return st;
-    const int total = (int)numel_w(g);
-    hipLaunchKernelGGL(wgrad_reduce_kernel, dim3(cdiv(total, 256)), dim3(256), 0, s, ws, dzdw, total, pl.splits);
-    return check_launch();
 }
 
 size_t workspace_bytes(const mcn_conv_desc *d, const Geom &g, int op) {
@@ -303,7 +303,7 @@ int mcn_conv_backward_filter(const mcn_conv_desc *desc, const float *x, const fl
     if (ws_bytes < need || (!ws && need)) return MCN_WORKSPACE_TOO_SMALL;
     const PlanEntry *pe = plans_for(desc, g);
     hipStream_t s = (hipStream_t)stream;
-    if (pe->wg_ok) return launch_wgrad(pe->wg, g, x, dzdy, dzdw, (float *)ws, s);
+    if (pe->wg_ok) return launch_wgrad(pe->wg, x, dzdy, nullptr, dzdw, ws, s);
     const int total = (int)numel_w(g);
     hipLaunchKernelGGL(direct_backward_filter_kernel, dim3(cdiv(total, 4)), dim3(256), 0, s, g, x, dzdy, dzdw, total);
     return check_launch();
