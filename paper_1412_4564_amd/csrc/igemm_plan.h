@@ -54,6 +54,36 @@ inline bool backward_data_view(const Geom &g, int pi, int pj, ConvView *out) {
     return true;
 }
 
+// Fully-connected case (Sec. 4.1: a filter as large as the input, one output sample per image,
+// no padding, one group).  With R = H*W*D the three passes are plain matrix products of
+// X (R x N), F (R x K) and dY (K x N), all stored with their first index fastest:
+//   Y = F^T X + b,   dX = F dY,   dF = X dY^T.
+inline bool is_fully_connected(const Geom &g) {
+    return g.G == 1 && g.H == g.Hf && g.W == g.Wf && g.Pt == 0 && g.Pb == 0 && g.Pl == 0 && g.Pr == 0;
+}
+inline ConvView fc_view_1x1(int64_t R, int C, int K) {
+    ConvView v = {};
+    v.H = (int)R; v.W = 1; v.N = 1; v.Ctot = C; v.Cg = C;
+    v.Ho = (int)R; v.Wo = 1; v.Ktot = K; v.Kg = K; v.G = 1;
+    v.Hf = 1; v.Wf = 1; v.Sh = 1; v.Sw = 1; v.Pt = 0; v.Pl = 0;
+    v.OH = (int)R; v.OW = 1; v.oi0 = 0; v.osi = 1; v.oj0 = 0; v.osj = 1;
+    v.pack_mode = 0; v.HfA = 1; v.WfA = 1; v.DfA = C;
+    return v;
+}
+// Y[k][n] = sum_r F[r][k] X[r][n]: the split-K kernel with the coefficients r as "pixels", the
+// images as "filters" and the filters as "channels" (both operands contiguous along r).
+inline ConvView fc_forward_view(const Geom &g) { return fc_view_1x1((int64_t)g.H * g.W * g.D, g.K, g.N); }
+// dX[r][n] = sum_k F[r][k] dY[k][n]: a 1x1 convolution over the "image" F with R pixels and K
+// channels, whose N filters are the columns of dY.
+inline ConvView fc_backward_data_view(const Geom &g) { return fc_view_1x1((int64_t)g.H * g.W * g.D, g.K, g.N); }
+// dF[r][k] = sum_n X[r][n] dY[k][n]: a 1x1 convolution over the "image" X with R pixels and N
+// channels, whose K filters are the rows of dY (read transposed by the packing pass).
+inline ConvView fc_backward_filter_view(const Geom &g) {
+    ConvView v = fc_view_1x1((int64_t)g.H * g.W * g.D, g.N, g.K);
+    v.pack_mode = 2; v.ldk = g.K;
+    return v;
+}
+
 enum IgemmShape { IG_128x256 = 0, IG_64x512 = 1, IG_32x256 = 2, IG_NONE = -1 };
 
 struct IgemmPlan {

@@ -84,6 +84,9 @@ struct PlanEntry {
     bool bwd_fill;             // some samples of dzdx belong to no phase with work: zero-fill first
     IgemmPlan bwd[MAX_PHASES];
     WgradPlan wg;
+    bool fc;                   // fully-connected layer: the three passes run as plain matrix products
+    WgradPlan fc_fwd;
+    IgemmPlan fc_bwd, fc_wg;
 };
 constexpr int PLAN_CACHE = 8;
 thread_local PlanEntry g_plans[PLAN_CACHE];
@@ -117,6 +120,9 @@ const PlanEntry *plans_for(const mcn_conv_desc *d, const Geom &g) {
             }
     }
     e.wg_ok = on && plan_wgrad(forward_view(g), ncu, &e.wg);
+    e.fc = on && is_fully_connected(g) && (int64_t)g.H * g.W * g.D < ((int64_t)1 << 30) &&
+           plan_wgrad(fc_forward_view(g), ncu, &e.fc_fwd) && plan_igemm(fc_backward_data_view(g), ncu, &e.fc_bwd) &&
+           plan_igemm(fc_backward_filter_view(g), ncu, &e.fc_wg);
     return &e;
 }
 
@@ -200,15 +206,20 @@ size_t workspace_bytes(const mcn_conv_desc *d, const Geom &g, int op) {
             BiasPlan p = plan_bias(g);
             return (size_t)g.K * p.S * sizeof(float);
         }
-        case MCN_OP_FORWARD: return e->fwd_ok ? igemm_ws_bytes(e->fwd) : 0;
+        case MCN_OP_FORWARD:
+            if (e->fc) return e->fc_fwd.partial_floats * sizeof(float);
+            return e->fwd_ok ? igemm_ws_bytes(e->fwd) : 0;
         case MCN_OP_BACKWARD_DATA: {
+            if (e->fc) return igemm_ws_bytes(e->fc_bwd);
             // the phases run one after the other on the stream and share one region
             size_t m = 0;
             if (e->bwd_ok)
                 for (int i = 0; i < e->n_bwd; ++i) { size_t b = igemm_ws_bytes(e->bwd[i]); if (b > m) m = b; }
             return m;
         }
-        case MCN_OP_BACKWARD_FILTER: return e->wg_ok ? e->wg.partial_floats * sizeof(float) : 0;
+        case MCN_OP_BACKWARD_FILTER:
+            if (e->fc) return igemm_ws_bytes(e->fc_wg);
+            return e->wg_ok ? e->wg.partial_floats * sizeof(float) : 0;
         default:
             return 0;
     }
@@ -241,9 +252,9 @@ const char *mcn_conv_kernel_name(const mcn_conv_desc *desc, int op) {
     if (make_geom(desc, &g)) return NULL;
     const PlanEntry *e = plans_for(desc, g);
     switch (op) {
-        case MCN_OP_FORWARD: return e->fwd_ok ? "igemm" : "direct";
-        case MCN_OP_BACKWARD_DATA: return e->bwd_ok ? "igemm" : "direct";
-        case MCN_OP_BACKWARD_FILTER: return e->wg_ok ? "wgrad_igemm" : "direct";
+        case MCN_OP_FORWARD: return e->fc ? "fc_gemm" : e->fwd_ok ? "igemm" : "direct";
+        case MCN_OP_BACKWARD_DATA: return e->fc ? "fc_gemm" : e->bwd_ok ? "igemm" : "direct";
+        case MCN_OP_BACKWARD_FILTER: return e->fc ? "fc_gemm" : e->wg_ok ? "wgrad_igemm" : "direct";
         case MCN_OP_BACKWARD_BIAS: return "reduce2";
         default: return NULL;
     }
@@ -259,6 +270,7 @@ int mcn_conv_forward(const mcn_conv_desc *desc, const float *x, const float *w, 
     if (ws_bytes < need || (!ws && need)) return MCN_WORKSPACE_TOO_SMALL;
     const PlanEntry *pe = plans_for(desc, g);
     hipStream_t s = (hipStream_t)stream;
+    if (pe->fc) return launch_wgrad(pe->fc_fwd, w, x, b, y, ws, s);
     if (pe->fwd_ok) return launch_igemm(pe->fwd, x, w, b, y, ws, s);
     const int total = (int)numel_y(g);
     hipLaunchKernelGGL(direct_forward_kernel, dim3(cdiv(total, 256)), dim3(256), 0, s, g, x, w, b, y, total);
@@ -275,6 +287,7 @@ int mcn_conv_backward_data(const mcn_conv_desc *desc, const float *w, const floa
     if (ws_bytes < need || (!ws && need)) return MCN_WORKSPACE_TOO_SMALL;
     const PlanEntry *pe = plans_for(desc, g);
     hipStream_t s = (hipStream_t)stream;
+    if (pe->fc) return launch_igemm(pe->fc_bwd, w, dzdy, nullptr, dzdx, ws, s);
     if (pe->bwd_ok) {
         if (pe->bwd_fill) {
             const int total = (int)numel_x(g);
@@ -303,6 +316,7 @@ int mcn_conv_backward_filter(const mcn_conv_desc *desc, const float *x, const fl
     if (ws_bytes < need || (!ws && need)) return MCN_WORKSPACE_TOO_SMALL;
     const PlanEntry *pe = plans_for(desc, g);
     hipStream_t s = (hipStream_t)stream;
+    if (pe->fc) return launch_igemm(pe->fc_wg, x, dzdy, nullptr, dzdw, ws, s);
     if (pe->wg_ok) return launch_wgrad(pe->wg, x, dzdy, nullptr, dzdw, ws, s);
     const int total = (int)numel_w(g);
     hipLaunchKernelGGL(direct_backward_filter_kernel, dim3(cdiv(total, 4)), dim3(256), 0, s, g, x, dzdy, dzdw, total);
