@@ -102,6 +102,9 @@ def main():
     ap.add_argument("--workload", default="vgg3x3", help="vgg3x3 or comma-separated layer names (e.g. 2b,3b)")
     ap.add_argument("--precision", default="fp32", choices=["fp32", "bf16"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 256 MiB elementwise copy three times, so that a counter run "
+                         "(rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE) holds a kernel of known traffic to scale by")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU; --gpus %d is not supported (the path shards over the batch, "
@@ -191,6 +194,12 @@ def main():
         "roofline": roof,
         "calls": detail,
     }
+    if args.copy_calibration:
+        src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.mul(src, 1.0, out=dst)      # reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(names)
     print(json.dumps(out), flush=True)

@@ -182,7 +182,7 @@ inline bool plan_igemm(const ConvView &v, int n_cu, IgemmPlan *pl) {
         const int64_t span = (int64_t)SC / Wp + 2;
         if ((double)span * v.Ctot * v.H * v.W * 4.0 >= 2147483647.0) continue;
         const int EPT = (int)((CP + NT - 1) / NT);
-        const size_t fixed_lds = ((size_t)EPT * NT + 4) * 4;
+        const size_t fixed_lds = ((size_t)EPT * NT + 2 * TK + 4) * 4;
         UnitCut uc;
         if (fixed33) {
             uc.pair_mode = 0; uc.DC = IGEMM_FIXED_DC; uc.TC = 9; uc.NTR = 1; uc.NS = (IGEMM_FIXED_DC / 2) * 9;
@@ -231,7 +231,7 @@ inline bool plan_igemm(const ConvView &v, int n_cu, IgemmPlan *pl) {
     P.packed_bytes = (unsigned)(pl->packed_floats * 4);
     pl->partial_floats = P.nblocks > 1 ? (size_t)2 * P.nblocks * TK * TQ : 0;
     pl->shape = shape; pl->fixed33 = fixed33; pl->TK = TK; pl->TQ = TQ; pl->NT = NT;
-    pl->lds_bytes = (2 * wsz + 2 * (size_t)P.DC * P.CP + (size_t)P.EPT * NT +
+    pl->lds_bytes = (2 * wsz + 2 * (size_t)P.DC * P.CP + (size_t)P.EPT * NT + 2 * TK +
                      (fixed33 ? 0 : (size_t)P.NTR * P.NS * 2) + 4) * sizeof(float);
     if (pl->lds_bytes > IGEMM_LDS_LIMIT) return false;
 

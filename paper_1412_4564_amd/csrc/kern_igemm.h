@@ -36,6 +36,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <type_traits>
 
 namespace mcn {
 
@@ -47,6 +48,11 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 constexpr unsigned SLAB_INVALID = 0x80000000u;   // >= any buffer size used here: reads as 0
 constexpr int BUFFER_FLAGS = 0x00020000;         // raw buffer, 32-bit elements
 constexpr int WAIT_VMCNT0 = 0x0F70;              // s_waitcnt vmcnt(0) only
+
+// Workgroup barrier that orders LDS traffic only: unlike __syncthreads() it does not wait for
+// this wave's outstanding global stores, so a finished tile drains to memory while the next one
+// is computed.  Loads into LDS are waited for explicitly (vmcnt) where they are consumed.
+__device__ inline void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
 struct IgemmParams {
     int H, W, N;        // input plane size, batch
@@ -81,6 +87,16 @@ __device__ __host__ inline int sk_virtual_block(int b, int nblocks) {
 }
 __device__ __host__ inline long long sk_begin(long long total, int nblocks, int vb) {
     return total * vb / nblocks;
+}
+
+// Tile order: filter tiles fastest (they share the slab), then the row blocks of one strip of
+// columns (vertically adjacent tiles share the cache lines their halo rows touch), then the
+// strips, then the groups.
+__device__ inline void decode_tile(const IgemmParams &P, int t, int *kt, int *pt, int *rb, int *g) {
+    *kt = t % P.KT; t /= P.KT;
+    *rb = t % P.RB; t /= P.RB;
+    *pt = t % P.PT;
+    *g = t / P.PT;
 }
 
 // ---- reduction order of a unit ------------------------------------------------------------
@@ -175,7 +191,8 @@ __global__ __launch_bounds__(64 * WK * WP, WPE) void igemm_sk_kernel(IgemmParams
     float *wbuf = lds;                                   // [2][WSZ]
     float *xbuf = lds + 2 * WSZ;                         // [2][DC*CP]
     int *gtab = reinterpret_cast<int *>(xbuf + 2 * XSZ); // [EPT][NT]: entry (s, tid) is private to thread tid
-    int *otab = gtab + P.EPT * NT;                       // table mode: [NTR][NS][2] slab offsets
+    float *blds = reinterpret_cast<float *>(gtab + P.EPT * NT);   // [2][TK] bias of the tile, by tile parity
+    int *otab = reinterpret_cast<int *>(blds + 2 * TK);           // table mode: [NTR][NS][2] slab offsets
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -203,15 +220,16 @@ __global__ __launch_bounds__(64 * WK * WP, WPE) void igemm_sk_kernel(IgemmParams
     }
 
     __amdgpu_buffer_rsrc_t wrs = __builtin_amdgcn_make_buffer_rsrc((void *)wpk, 0, (int)P.packed_bytes, BUFFER_FLAGS);
+    __amdgpu_buffer_rsrc_t brs = __builtin_amdgcn_make_buffer_rsrc((void *)bias, 0, bias ? P.Ktot * 4 : 0, BUFFER_FLAGS);
 
     // ---- load side: tile whose units are being fetched ------------------------------------
     __amdgpu_buffer_rsrc_t xrs = wrs;
     unsigned wtile_off = 0;        // byte offset of the tile's packed weights
+    int l_t = 0, l_kt = 0, l_g = 0;
     auto setup_load = [&](int t) {
-        const int kt = t % P.KT; t /= P.KT;
-        const int pt = t % P.PT; t /= P.PT;
-        const int rb = t % P.RB;
-        const int g = t / P.RB;
+        l_t = t;
+        int kt, pt, rb, g;
+        decode_tile(P, t, &kt, &pt, &rb, &g);
         const int q0 = pt * TQ;
         const int c_first = q0 / P.TI;
         const int n_first = c_first / P.Wo;
@@ -222,6 +240,7 @@ __global__ __launch_bounds__(64 * WK * WP, WPE) void igemm_sk_kernel(IgemmParams
         if (in_left > 0x7fffffffull) in_left = 0x7fffffffull;
         xrs = __builtin_amdgcn_make_buffer_rsrc((void *)(in + in_base), 0, (int)in_left, BUFFER_FLAGS);
         wtile_off = (unsigned)((size_t)(g * P.KT + kt) * NU * WSZ * 4);
+        l_kt = kt; l_g = g;
         for (int s = 0; s < P.EPT; ++s) {
             const int e = tid + NT * s;
             const int col = e / SRP;
@@ -244,6 +263,13 @@ __global__ __launch_bounds__(64 * WK * WP, WPE) void igemm_sk_kernel(IgemmParams
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(wrs, MCN_LDS_PTR(wb + e0), 16, (unsigned)(e0 + lane * 4) * 4u,
                                                          woff, 0, 0);
         }
+        if (bias && uu == NU - 1 && wave * 64 < TK) {
+            // the tile's bias, for the epilogue of a tile this block owns entirely
+            const int kl = l_kt * TK + wave * 64 + lane;
+            if (wave * 64 + lane < TK)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(brs, MCN_LDS_PTR(blds + (l_t & 1) * TK + wave * 64), 4,
+                                                         kl < P.Kg ? (unsigned)(l_g * P.Kg + kl) * 4u : SLAB_INVALID, 0, 0, 0);
+        }
         const int cg = FIXED ? uu : uu / P.NTR;
         const int c0 = cg * DC;
         for (int s = 0; s < P.EPT; ++s) {
@@ -264,13 +290,12 @@ __global__ __launch_bounds__(64 * WK * WP, WPE) void igemm_sk_kernel(IgemmParams
     // ---- compute side: tile whose accumulators are live -----------------------------------
     int bbase[MP];   // slab offset (floats) of the pixel's window origin (+ channel half when FIXED)
     int ooff[MP];    // output offset of (io, jo, k=0 of the array, n), or -1
-    int c_kt = 0, c_g = 0;
+    int c_t = 0, c_kt = 0, c_g = 0;
     floatx16 acc[MK][MP];
-    auto setup_compute = [&](int t, bool with_bias) {
-        const int kt = t % P.KT; t /= P.KT;
-        const int pt = t % P.PT; t /= P.PT;
-        const int rb = t % P.RB;
-        const int g = t / P.RB;
+    auto setup_compute = [&](int t) {
+        c_t = t;
+        int kt, pt, rb, g;
+        decode_tile(P, t, &kt, &pt, &rb, &g);
         c_kt = kt; c_g = g;
         const int q0 = pt * TQ;
         const int qend = min(q0 + TQ, P.QN);
@@ -293,15 +318,14 @@ __global__ __launch_bounds__(64 * WK * WP, WPE) void igemm_sk_kernel(IgemmParams
 #pragma unroll
         for (int mk = 0; mk < MK; ++mk)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int kl = kt * TK + (wk * MK + mk) * 32 + (v >> 2) * 8 + half * 4 + (v & 3);
-                const float bv = (with_bias && bias && kl < P.Kg) ? bias[g * P.Kg + kl] : 0.f;
+            for (int mp = 0; mp < MP; ++mp)
 #pragma unroll
-                for (int mp = 0; mp < MP; ++mp) acc[mk][mp][v] = bv;
-            }
+                for (int v = 0; v < 16; ++v) acc[mk][mp][v] = 0.f;
     };
     const int aoff = half * TK + wk * MK * 32 + (lane & 31);
-    auto compute = [&](int uu, int b) {
+    // steps [part*NS/2, (part+1)*NS/2) of unit uu, operands in buffer b
+    auto compute = [&](auto PART, int uu, int b) {
+        constexpr int part = decltype(PART)::value;
         const float *wl = wbuf + b * WSZ + aoff;
         const float *xl = xbuf + b * XSZ;
         if constexpr (FIXED) {
@@ -309,6 +333,7 @@ __global__ __launch_bounds__(64 * WK * WP, WPE) void igemm_sk_kernel(IgemmParams
             // reads of step s+1 are issued before the MFMAs of step s.
             constexpr int TT = HF * WF;
             constexpr int NSTEP = (DCF / 2) * TT;
+            constexpr int S0 = part * (NSTEP / 2), S1 = part ? NSTEP : NSTEP / 2;
             float a[2][MK], bb[2][MP];
             auto fetch = [&](int s, int slot) {
                 const int dp = s / TT, tap = s % TT;
@@ -318,10 +343,10 @@ __global__ __launch_bounds__(64 * WK * WP, WPE) void igemm_sk_kernel(IgemmParams
 #pragma unroll
                 for (int mp = 0; mp < MP; ++mp) bb[slot][mp] = xl[bbase[mp] + dp * 2 * CP + fj * SRP + fi];
             };
-            fetch(0, 0);
+            fetch(S0, S0 & 1);
 #pragma unroll
-            for (int s = 0; s < NSTEP; ++s) {
-                if (s + 1 < NSTEP) fetch(s + 1, (s + 1) & 1);
+            for (int s = S0; s < S1; ++s) {
+                if (s + 1 < S1) fetch(s + 1, (s + 1) & 1);
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int mk = 0; mk < MK; ++mk)
@@ -333,8 +358,11 @@ __global__ __launch_bounds__(64 * WK * WP, WPE) void igemm_sk_kernel(IgemmParams
         } else {
             const int tr = uu % P.NTR;
             const int *ot = otab + tr * NS * 2 + half;
+            const int mid = (NS >> 2) << 1;                 // even
+            const int s0 = part ? mid : 0, s1 = part ? NS : mid;
+            if (s0 >= s1) return;
             float a0[MK], b0[MP], a1[MK], b1[MP];
-            int o0 = ot[0], o1 = ot[2];
+            int o0 = ot[2 * s0], o1 = ot[2 * s0 + 2];
             auto fetch = [&](float *a, float *bq, int s, int o) {
 #pragma unroll
                 for (int mk = 0; mk < MK; ++mk) a[mk] = wl[s * 2 * TK + mk * 32];
@@ -348,15 +376,15 @@ __global__ __launch_bounds__(64 * WK * WP, WPE) void igemm_sk_kernel(IgemmParams
                     for (int mp = 0; mp < MP; ++mp)
                         acc[mk][mp] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[mk], bq[mp], acc[mk][mp], 0, 0, 0);
             };
-            fetch(a0, b0, 0, o0);
-            for (int s = 0; s < NS; s += 2) {
+            fetch(a0, b0, s0, o0);
+            for (int s = s0; s < s1; s += 2) {
                 const int o0n = ot[2 * min(s + 2, NS - 1)];
                 const int o1n = ot[2 * min(s + 3, NS - 1)];
                 fetch(a1, b1, s + 1, o1);
                 __builtin_amdgcn_sched_barrier(0);
                 mma(a0, b0);
                 __builtin_amdgcn_sched_barrier(0);
-                if (s + 2 < NS) fetch(a0, b0, s + 2, o0n);
+                if (s + 2 < s1) fetch(a0, b0, s + 2, o0n);
                 __builtin_amdgcn_sched_barrier(0);
                 mma(a1, b1);
                 __builtin_amdgcn_sched_barrier(0);
@@ -367,16 +395,19 @@ __global__ __launch_bounds__(64 * WK * WP, WPE) void igemm_sk_kernel(IgemmParams
     };
     // lane holds pixel (lane&31) of each pixel tile and 16 filters of each filter tile
     auto store_tile = [&]() {
+        const float *bl = blds + (c_t & 1) * TK;
 #pragma unroll
         for (int mk = 0; mk < MK; ++mk) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                const int kl = c_kt * TK + (wk * MK + mk) * 32 + (v >> 2) * 8 + half * 4 + (v & 3);
+                const int kloc = (wk * MK + mk) * 32 + (v >> 2) * 8 + half * 4 + (v & 3);
+                const int kl = c_kt * TK + kloc;
                 if (kl < P.Kg) {
                     const int k = c_g * P.Kg + kl;
+                    const float bv = bias ? bl[kloc] : 0.f;
 #pragma unroll
                     for (int mp = 0; mp < MP; ++mp)
-                        if (ooff[mp] >= 0) out[(size_t)ooff[mp] + (size_t)OHW * k] = acc[mk][mp][v];
+                        if (ooff[mp] >= 0) out[(size_t)ooff[mp] + (size_t)OHW * k] = acc[mk][mp][v] + bv;
                 }
             }
         }
@@ -405,26 +436,39 @@ __global__ __launch_bounds__(64 * WK * WP, WPE) void igemm_sk_kernel(IgemmParams
     setup_load(t_l);
     issue_loads(uu_l, 0);
     bool whole = segment_is_whole(t_c, uu_c);
-    setup_compute(t_c, whole);
+    setup_compute(t_c);
 
+    // The two waves that share a SIMD fetch the next unit at different times (one before its
+    // MFMAs, the other half-way through), so that one of them always feeds the matrix core.
+    const bool late_fetch = NT == 512 && ((wave >> 2) & 1);
     const int nunits = (int)(ue - ub);
+    bool loads_waited = false;
     for (int it = 0; it < nunits; ++it) {
-        __builtin_amdgcn_s_waitcnt(WAIT_VMCNT0);   // this wave's LDS-direct loads have landed
-        __syncthreads();                           // everyone's have, and the other buffer is free
-        if (it + 1 < nunits) {
+        if (!loads_waited) __builtin_amdgcn_s_waitcnt(WAIT_VMCNT0);   // this wave's LDS-direct loads have landed
+        loads_waited = false;
+        lds_barrier();                             // everyone's have, and the other buffer is free
+        const bool more = it + 1 < nunits;
+        auto fetch_next = [&]() {
             if (++uu_l == NU) { uu_l = 0; ++t_l; setup_load(t_l); }
             issue_loads(uu_l, (it + 1) & 1);
-        }
-        compute(uu_c, it & 1);
-        const bool last = it + 1 == nunits;
+        };
+        if (more && !late_fetch) fetch_next();
+        compute(std::integral_constant<int, 0>{}, uu_c, it & 1);
+        if (more && late_fetch) fetch_next();
+        compute(std::integral_constant<int, 1>{}, uu_c, it & 1);
+        const bool last = !more;
         if (uu_c + 1 == NU || last) {
+            // wait for the next unit's loads now, so that the stores below need not be waited for at
+            // the top of the next iteration and drain while it computes
+            __builtin_amdgcn_s_waitcnt(WAIT_VMCNT0);
+            loads_waited = true;
             if (whole) store_tile();
             else store_partial(2 * vb + (first_segment ? 0 : 1));
             first_segment = false;
             if (!last) {
                 ++t_c; uu_c = 0;
                 whole = segment_is_whole(t_c, 0);
-                setup_compute(t_c, whole);
+                setup_compute(t_c);
             }
         } else {
             ++uu_c;
@@ -445,11 +489,8 @@ __global__ __launch_bounds__(256) void igemm_fixup_kernel(IgemmParams P, const f
     const long long t_lo = (long long)t * P.NU, t_hi = t_lo + P.NU;
     if (B == t_lo) return;                                        // boundary on a tile edge: nothing shared
     if (sk_begin(total, P.nblocks, j - 1) > t_lo) return;         // an earlier boundary owns this tile
-    int tt = t;
-    const int kt = tt % P.KT; tt /= P.KT;
-    const int pt = tt % P.PT; tt /= P.PT;
-    const int rb = tt % P.RB;
-    const int g = tt / P.RB;
+    int kt, pt, rb, g;
+    decode_tile(P, t, &kt, &pt, &rb, &g);
     const int OHW = P.OH * P.OW;
     for (int e = blockIdx.y * 256 + threadIdx.x; e < TK * TQ; e += gridDim.y * 256) {
         const int kloc = e / TQ, ql = e - kloc * TQ;
