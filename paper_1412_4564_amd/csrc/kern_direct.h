@@ -149,6 +149,33 @@ __global__ __launch_bounds__(256) void bias_partial_kernel(const float *__restri
     if (threadIdx.x == 0) part[(size_t)k * S + s] = (red[0] + red[1]) + (red[2] + red[3]);
 }
 
+// Small output planes (down to the 1x1 output of a fully-connected layer): one image of dzdy is
+// a contiguous row of K*HoWo values, so threads run along that row and step over the images.
+// Stage 1: part[s][e] = sum over images n = s, s+S, ... of dzdy[e + K*HoWo*n], e = p + HoWo*k.
+__global__ __launch_bounds__(256) void bias_rows_partial_kernel(const float *__restrict__ dzdy, float *__restrict__ part,
+                                                                int KHoWo, int N, int S) {
+    const int e = blockIdx.x * 256 + threadIdx.x, s = blockIdx.y;
+    if (e >= KHoWo) return;
+    float acc = 0.f;
+    for (int n = s; n < N; n += S) acc += dzdy[(size_t)n * KHoWo + e];
+    part[(size_t)s * KHoWo + e] = acc;
+}
+// Stage 2: one wavefront per filter adds its S*HoWo partials in a fixed order.
+__global__ __launch_bounds__(256) void bias_rows_final_kernel(const float *__restrict__ part, float *__restrict__ dzdb,
+                                                              int HoWo, int K, int S) {
+    const int lane = threadIdx.x & 63;
+    const int k = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (k >= K) return;                 // whole wave leaves together
+    const int KHoWo = K * HoWo, total = S * HoWo;
+    float acc = 0.f;
+    for (int u = lane; u < total; u += 64) {
+        const int s = u / HoWo, p = u - s * HoWo;
+        acc += part[(size_t)s * KHoWo + (size_t)k * HoWo + p];
+    }
+    acc = wave_sum(acc);
+    if (lane == 0) dzdb[k] = acc;
+}
+
 __global__ __launch_bounds__(256) void bias_final_kernel(const float *__restrict__ part, float *__restrict__ dzdb,
                                                          int K, int S) {
     int k = blockIdx.x * 256 + threadIdx.x;

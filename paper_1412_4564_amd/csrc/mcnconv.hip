@@ -31,13 +31,26 @@ inline unsigned cdiv(int64_t a, int64_t b) { return (unsigned)((a + b - 1) / b);
 
 // ---- bias derivative plan --------------------------------------------------
 struct BiasPlan {
+    bool rows;   // small output plane: threads run along the K*HoWo values of one image
     int chunks;  // chunks of BIAS_CHUNK samples per (n, k) plane
-    int S;       // partial sums per filter
+    int S;       // partial sums per filter (rows: per value of the image row)
+    size_t ws_floats;
 };
 
 BiasPlan plan_bias(const Geom &g) {
     BiasPlan p;
     const int64_t HoWo = (int64_t)g.Ho * g.Wo;
+    p.rows = HoWo < 64;
+    if (p.rows) {
+        const int64_t row = HoWo * g.K;
+        int64_t want = 1024 / ((row + 255) / 256);     // aim for ~1024 blocks in all
+        if (want > g.N) want = g.N;
+        if (want < 1) want = 1;
+        p.chunks = 0;
+        p.S = (int)want;
+        p.ws_floats = (size_t)p.S * (size_t)row;
+        return p;
+    }
     p.chunks = (int)((HoWo + BIAS_CHUNK - 1) / BIAS_CHUNK);
     const int64_t units = (int64_t)g.N * p.chunks;
     int64_t want = (2048 + g.K - 1) / g.K;   // aim for ~2048 blocks in all
@@ -45,6 +58,7 @@ BiasPlan plan_bias(const Geom &g) {
     if (want < 1) want = 1;
     if (want > 65535) want = 65535;
     p.S = (int)want;
+    p.ws_floats = (size_t)g.K * p.S;
     return p;
 }
 
@@ -203,8 +217,7 @@ size_t workspace_bytes(const mcn_conv_desc *d, const Geom &g, int op) {
     const PlanEntry *e = plans_for(d, g);
     switch (op) {
         case MCN_OP_BACKWARD_BIAS: {
-            BiasPlan p = plan_bias(g);
-            return (size_t)g.K * p.S * sizeof(float);
+            return plan_bias(g).ws_floats * sizeof(float);
         }
         case MCN_OP_FORWARD:
             if (e->fc) return e->fc_fwd.partial_floats * sizeof(float);
@@ -255,7 +268,7 @@ const char *mcn_conv_kernel_name(const mcn_conv_desc *desc, int op) {
         case MCN_OP_FORWARD: return e->fc ? "fc_gemm" : e->fwd_ok ? "igemm" : "direct";
         case MCN_OP_BACKWARD_DATA: return e->fc ? "fc_gemm" : e->bwd_ok ? "igemm" : "direct";
         case MCN_OP_BACKWARD_FILTER: return e->fc ? "fc_gemm" : e->wg_ok ? "wgrad_igemm" : "direct";
-        case MCN_OP_BACKWARD_BIAS: return "reduce2";
+        case MCN_OP_BACKWARD_BIAS: return plan_bias(g).rows ? "reduce_rows" : "reduce2";
         default: return NULL;
     }
 }
@@ -334,6 +347,14 @@ int mcn_conv_backward_bias(const mcn_conv_desc *desc, const float *dzdy, float *
     hipStream_t s = (hipStream_t)stream;
     BiasPlan p = plan_bias(g);
     float *part = (float *)ws;
+    if (p.rows) {
+        const int row = g.K * g.Ho * g.Wo;
+        hipLaunchKernelGGL(bias_rows_partial_kernel, dim3(cdiv(row, 256), p.S), dim3(256), 0, s, dzdy, part, row, g.N, p.S);
+        st = check_launch();
+        if (st) return st;
+        hipLaunchKernelGGL(bias_rows_final_kernel, dim3(cdiv(g.K, 4)), dim3(256), 0, s, part, dzdb, g.Ho * g.Wo, g.K, p.S);
+        return check_launch();
+    }
     hipLaunchKernelGGL(bias_partial_kernel, dim3(g.K, p.S), dim3(256), 0, s, dzdy, part, g.Ho * g.Wo, g.K, g.N,
                        p.chunks, p.S);
     st = check_launch();
