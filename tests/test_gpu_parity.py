@@ -88,6 +88,65 @@ def test_random_geometries():
         U.assert_errors(U.run_layer_full(L, with_bias=bool(t % 2), seed=t), label="random %d %r" % (t, L))
 
 
+# ---- which kernels the dispatcher picks ----------------------------------------------
+def test_workload_layers_run_on_the_matrix_core_kernels():
+    """No layer of the workloads may fall back to the one-result-per-thread kernels."""
+    for name, L in synth.LAYERS.items():
+        d = B.make_desc(synth.x_shape(L), synth.w_shape(L), L["stride"], L["pad"])
+        names = [B.mcn_conv_kernel_name(d, op) for op in range(4)]
+        assert "direct" not in names, (name, names)
+    d = B.make_desc(synth.x_shape(synth.LAYERS["5a"]), synth.w_shape(synth.LAYERS["5a"]))
+    assert [B.mcn_conv_kernel_name(d, op) for op in range(3)] == ["fc_gemm"] * 3
+
+
+# ---- fully-connected case (Sec. 4.1): matrix-product path, ragged sizes --------------
+FC_CASES = [
+    # H  W  D   N   K
+    (6, 6, 8, 5, 7),          # everything smaller than one tile
+    (3, 5, 33, 130, 70),      # N and K ragged against 128-wide tiles, R = 495 not a multiple of anything
+    (1, 1, 300, 40, 129),     # 1x1 input: a plain matrix product
+    (7, 2, 16, 257, 33),
+]
+
+
+@pytest.mark.parametrize("case", range(len(FC_CASES)))
+def test_fully_connected_layers(case):
+    H, W, D, N, K = FC_CASES[case]
+    L = custom_layer(H, W, D, N, H, W, D, K, idx=40 + case)
+    d = B.make_desc(synth.x_shape(L), synth.w_shape(L))
+    assert B.mcn_conv_kernel_name(d, 0) == "fc_gemm"
+    U.assert_errors(U.run_layer_full(L, with_bias=(case % 2 == 0)), label="fc %d" % case)
+
+
+# ---- strided input derivative: every stride phase, phases without taps ------------------
+STRIDED = [
+    # H  W  D  N  Hf Wf Df K   stride   pad
+    (23, 19, 8, 3, 5, 4, 8, 12, (2, 3), (2, 1, 0, 3)),
+    (31, 31, 3, 2, 11, 11, 3, 20, (4, 4), (0, 0, 0, 0)),     # first layer of the Krizhevsky-style network, small
+    (20, 18, 4, 2, 2, 3, 4, 6, (4, 5), (1, 0, 2, 2)),        # stride larger than the filter: rows/columns no tap reaches
+    (17, 9, 6, 2, 3, 3, 3, 8, (3, 1), (1, 1, 1, 1)),         # two groups
+    (12, 40, 5, 3, 1, 7, 5, 9, (2, 2), (0, 0, 3, 3)),
+]
+
+
+@pytest.mark.parametrize("case", range(len(STRIDED)))
+def test_strided_layers(case):
+    H, W, D, N, Hf, Wf, Df, K, st, pad = STRIDED[case]
+    L = custom_layer(H, W, D, N, Hf, Wf, Df, K, st, pad, idx=60 + case)
+    d = B.make_desc(synth.x_shape(L), synth.w_shape(L), st, pad)
+    assert B.mcn_conv_kernel_name(d, 1) == "igemm"
+    U.assert_errors(U.run_layer_full(L, with_bias=(case % 2 == 1)), label="strided %d" % case)
+
+
+# ---- work sharing between blocks: many tiles, few tiles, shared tiles -------------------
+def test_tiles_shared_between_blocks_match_whole_tiles():
+    """Same layer at batch sizes that give fewer tiles than compute units (every tile is
+    shared), about as many, and many more; every element compared."""
+    base = custom_layer(20, 20, 32, 1, 3, 3, 32, 160, (1, 1), (1, 1, 1, 1), idx=80)
+    for nb in (1, 3, 40):
+        U.assert_errors(U.run_layer_full(synth.with_batch(base, nb)), label="sharing N=%d" % nb)
+
+
 # ---- semantics of the boundary ---------------------------------------------------
 def test_outputs_are_overwritten_and_runs_are_bit_identical():
     L = synth.with_batch(synth.LAYERS["2b"], 4)
