@@ -134,7 +134,7 @@ inline bool cut_units(const ConvView &v, int TK, int64_t CP, size_t lds_left, Un
                 int NS = mode == 0 ? (DC / 2) * TC : DC * (TC / 2);
                 NS += NS & 1;
                 if (NS > 80) continue;
-                const size_t lds = (2 * (size_t)NS * 2 * TK + 2 * (size_t)DC * CP) * 4;
+                const size_t lds = (2 * ((size_t)NS * 2 * TK + 255) + 2 * (size_t)DC * CP) * 4;
                 if (lds > lds_left) continue;
                 // work actually issued per tile / useful work
                 const int NCG = (v.Cg + DC - 1) / DC;
@@ -157,7 +157,7 @@ inline bool plan_igemm(const ConvView &v, int n_cu, IgemmPlan *pl) {
     else if (v.Kg > 32) { shape = IG_64x512; WK = 1; WP = 8; MK = 2; MP = 2; }
     else { shape = IG_32x256; WK = 1; WP = 4; MK = 1; MP = 2; }
     const int TK = WK * MK * 32, TQ = WP * MP * 32, NT = 64 * WK * WP;
-    const bool fixed33 = (v.Hf == 3 && v.Wf == 3 && v.Cg >= 2 * IGEMM_FIXED_DC);
+    const bool fixed33 = (v.Hf == 3 && v.Wf == 3 && v.Cg >= 2 * IGEMM_FIXED_DC && v.Cg % IGEMM_FIXED_DC == 0);
     const int Wp = (v.Wo - 1) * v.Sw + v.Wf;
     // candidates for the row-block height
     int cand[48];
@@ -176,17 +176,18 @@ inline bool plan_igemm(const ConvView &v, int n_cu, IgemmPlan *pl) {
         if (SR > 8192) continue;
         if ((int64_t)TI * v.Wo * v.N >= ((int64_t)1 << 30)) continue;
         const int SC = slab_columns(v, TI, TQ, Wp);
-        const int64_t CP = SR * SC;
+        const int64_t CP = (SR * SC + 63) / 64 * 64;
         if (CP > 16 * NT) continue;
         // an image crossing inside a tile moves the window by whole images: keep offsets in range
         const int64_t span = (int64_t)SC / Wp + 2;
         if ((double)span * v.Ctot * v.H * v.W * 4.0 >= 2147483647.0) continue;
+        if ((double)(span + 1) * v.Ktot * v.OH * v.OW * 4.0 >= 2147483647.0) continue;   // and inside its output window
         const int EPT = (int)((CP + NT - 1) / NT);
         const size_t fixed_lds = ((size_t)EPT * NT + 2 * TK + 4) * 4;
         UnitCut uc;
         if (fixed33) {
             uc.pair_mode = 0; uc.DC = IGEMM_FIXED_DC; uc.TC = 9; uc.NTR = 1; uc.NS = (IGEMM_FIXED_DC / 2) * 9;
-            if ((2 * (size_t)uc.NS * 2 * TK + 2 * (size_t)uc.DC * CP) * 4 + fixed_lds > IGEMM_LDS_LIMIT) continue;
+            if ((2 * ((size_t)uc.NS * 2 * TK + 255) + 2 * (size_t)uc.DC * CP) * 4 + fixed_lds > IGEMM_LDS_LIMIT) continue;
         } else {
             if (fixed_lds + 4096 > IGEMM_LDS_LIMIT) continue;
             // the offset table needs NTR*NS*2 ints: reserve 16 KB for it up front
@@ -212,7 +213,7 @@ inline bool plan_igemm(const ConvView &v, int n_cu, IgemmPlan *pl) {
     P.TI = bestTI; P.RB = (v.Ho + bestTI - 1) / bestTI;
     P.Wp = Wp;
     P.SR = (bestTI - 1) * v.Sh + v.Hf; P.SRP = P.SR;
-    P.CP = P.SRP * bestSC;
+    P.CP = (P.SRP * bestSC + 63) / 64 * 64;
     P.EPT = (P.CP + NT - 1) / NT;
     P.KT = (v.Kg + TK - 1) / TK;
     P.QN = bestTI * v.Wo * v.N;
@@ -225,7 +226,8 @@ inline bool plan_igemm(const ConvView &v, int n_cu, IgemmPlan *pl) {
     const int64_t total = tiles * P.NU;
     P.nblocks = (int)(total < n_cu ? total : n_cu);
     P.OH = v.OH; P.OW = v.OW; P.oi0 = v.oi0; P.osi = v.osi; P.oj0 = v.oj0; P.osj = v.osj;
-    const size_t wsz = (size_t)P.NS * 2 * TK;
+    const size_t wsz = ((size_t)P.NS * 2 * TK + 255) / 256 * 256;
+    P.WSZ = (int)wsz;
     pl->packed_floats = (size_t)v.G * P.KT * P.NU * wsz;
     if (pl->packed_floats * 4 >= 2147483647ull) return false;
     P.packed_bytes = (unsigned)(pl->packed_floats * 4);
@@ -238,7 +240,7 @@ inline bool plan_igemm(const ConvView &v, int n_cu, IgemmPlan *pl) {
     PackParams &Q = pl->Q;
     Q = PackParams{};
     Q.Hf = v.Hf; Q.Wf = v.Wf; Q.HfA = v.HfA; Q.WfA = v.WfA; Q.DfA = v.DfA;
-    Q.Kg = v.Kg; Q.Cg = v.Cg; Q.G = v.G; Q.KT = P.KT; Q.NU = P.NU; Q.NTR = P.NTR; Q.NS = P.NS; Q.TK = TK;
+    Q.Kg = v.Kg; Q.Cg = v.Cg; Q.G = v.G; Q.KT = P.KT; Q.NU = P.NU; Q.NTR = P.NTR; Q.NS = P.NS; Q.WSZ = P.WSZ; Q.TK = TK;
     Q.DC = P.DC; Q.TC = P.TC; Q.pair_mode = P.pair_mode; Q.mode = v.pack_mode;
     Q.Sh = v.pSh; Q.Sw = v.pSw; Q.pi = v.pi; Q.pj = v.pj; Q.ldk = v.ldk;
     Q.total = (int)pl->packed_floats;

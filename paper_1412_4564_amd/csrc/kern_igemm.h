@@ -64,13 +64,14 @@ struct IgemmParams {
     int TI, RB;         // rows per row block, number of row blocks
     int Wp;             // columns reserved per image in the chained padded-column index
     int SR, SRP;        // slab rows used / row pitch
-    int CP;             // slab channel pitch (floats)
+    int CP;             // slab channel pitch (floats), a multiple of 64
     int EPT;            // slab elements per thread: ceil(CP / threads)
     int KT, PT;         // filter tiles per group, pixel tiles per row block
     int QN;             // TI*Wo*N: chained pixels per row block
     int DC, TC, NTR;    // channels per unit, taps per unit, tap ranges
     int NU;             // units per tile = ceil(Cg/DC) * NTR
     int NS;             // steps per unit (even)
+    int WSZ;            // floats of packed weights per unit: NS*2*TK rounded up to a multiple of 256
     int pair_mode;      // 0: a step pairs two channels, 1: a step pairs two taps
     int tiles;          // G*RB*PT*KT
     int nblocks;        // resident blocks sharing tiles*NU units
@@ -118,7 +119,8 @@ __device__ inline void unit_element(int pair_mode, int DC, int TC, int T, int tr
 }
 
 // ---- weight packing ------------------------------------------------------------------
-// packed[g][kt][unit][s][h][kk] = wt(k = kt*TK+kk, c = cg*DC + cl, tap), 0 where padded.
+// packed[g][kt][unit][s][h][kk] = wt(k = kt*TK+kk, c = cg*DC + cl, tap), 0 where padded; one unit
+// takes WSZ floats.
 // mode 0 (forward):        wt(k,c,fi,fj) = w[fi, fj, c, g*Kg + k]
 // mode 1 (input derivative, Kg = D', Cg = K/G; one call per stride phase (pi, pj)):
 //     view tap (ti,tj) is filter tap fi = pi + Sh*(Hfv-1-ti), fj = pj + Sw*(Wfv-1-tj):
@@ -128,7 +130,7 @@ __device__ inline void unit_element(int pair_mode, int DC, int TC, int T, int tr
 struct PackParams {
     int Hf, Wf;            // taps of the view
     int HfA, WfA, DfA;     // shape of the caller's filter array (modes 0, 1)
-    int Kg, Cg, G, KT, NU, NTR, NS, TK, DC, TC, pair_mode, mode;
+    int Kg, Cg, G, KT, NU, NTR, NS, WSZ, TK, DC, TC, pair_mode, mode;
     int Sh, Sw, pi, pj;    // mode 1
     int ldk;               // mode 2
     int total;
@@ -138,10 +140,12 @@ __global__ __launch_bounds__(256) void igemm_pack_weights_kernel(const float *__
                                                                  PackParams Q) {
     int p = blockIdx.x * 256 + threadIdx.x;
     if (p >= Q.total) return;
-    int t = p;
-    const int kk = t % Q.TK; t /= Q.TK;
-    const int h = t & 1; t >>= 1;
-    const int s = t % Q.NS; t /= Q.NS;
+    int t = p / Q.WSZ;
+    int within = p - t * Q.WSZ;
+    if (within >= Q.NS * 2 * Q.TK) { packed[p] = 0.f; return; }     // pitch padding
+    const int kk = within % Q.TK; within /= Q.TK;
+    const int h = within & 1;
+    const int s = within >> 1;
     const int uu = t % Q.NU; t /= Q.NU;
     const int kt = t % Q.KT;
     const int g = t / Q.KT;
@@ -183,7 +187,8 @@ __global__ __launch_bounds__(64 * WK * WP, WPE) void igemm_sk_kernel(IgemmParams
     const int DC = FIXED ? DCF : P.DC;
     const int NS = FIXED ? (DCF / 2) * HF * WF : P.NS;
     const int NU = P.NU;
-    const int WSZ = NS * 2 * TK;               // floats of packed weights per unit
+    const int WSZ = FIXED ? (((DCF / 2) * HF * WF * 2 * TK + 255) & ~255) : P.WSZ;   // floats of packed weights per unit
+    constexpr int NW = WK * WP;
     const int CP = P.CP, SRP = P.SRP;
     const int XSZ = DC * CP;
 
@@ -221,6 +226,8 @@ __global__ __launch_bounds__(64 * WK * WP, WPE) void igemm_sk_kernel(IgemmParams
 
     __amdgpu_buffer_rsrc_t wrs = __builtin_amdgcn_make_buffer_rsrc((void *)wpk, 0, (int)P.packed_bytes, BUFFER_FLAGS);
     __amdgpu_buffer_rsrc_t brs = __builtin_amdgcn_make_buffer_rsrc((void *)bias, 0, bias ? P.Ktot * 4 : 0, BUFFER_FLAGS);
+    const __amdgpu_buffer_rsrc_t zrs = __builtin_amdgcn_make_buffer_rsrc((void *)in, 0, 0, BUFFER_FLAGS);   // reads as zero
+    const unsigned lane16 = (unsigned)lane * 16u;
 
     // ---- load side: tile whose units are being fetched ------------------------------------
     __amdgpu_buffer_rsrc_t xrs = wrs;
@@ -258,13 +265,10 @@ __global__ __launch_bounds__(64 * WK * WP, WPE) void igemm_sk_kernel(IgemmParams
         float *wb = wbuf + b * WSZ;
         float *xb = xbuf + b * XSZ;
         const unsigned woff = wtile_off + (unsigned)uu * (unsigned)WSZ * 4u;
-        for (int e0 = wave * 256; e0 < WSZ; e0 += NT * 4) {       // 16 bytes per lane
-            if (e0 + lane * 4 < WSZ)
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(wrs, MCN_LDS_PTR(wb + e0), 16, (unsigned)(e0 + lane * 4) * 4u,
-                                                         woff, 0, 0);
-        }
-        if (bias && uu == NU - 1 && wave * 64 < TK) {
-            // the tile's bias, for the epilogue of a tile this block owns entirely
+        for (int e0 = wave * 256; e0 < WSZ; e0 += NW * 256)       // one wave instruction = 256 floats, 16 bytes per lane
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(wrs, MCN_LDS_PTR(wb + e0), 16, lane16, woff + (unsigned)e0 * 4u, 0, 0);
+        if (bias && uu == 0 && wave * 64 < TK) {
+            // the tile's bias: start value of the accumulators of a tile this block owns entirely
             const int kl = l_kt * TK + wave * 64 + lane;
             if (wave * 64 + lane < TK)
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(brs, MCN_LDS_PTR(blds + (l_t & 1) * TK + wave * 64), 4,
@@ -276,21 +280,23 @@ __global__ __launch_bounds__(64 * WK * WP, WPE) void igemm_sk_kernel(IgemmParams
             const int e0 = wave * 64 + NT * s;
             if (e0 >= CP) break;
             const unsigned go = (unsigned)gtab[s * NT + tid];
-            if (e0 + lane < CP) {
-                for (int d = 0; d < DC; ++d) {
-                    const int c = c0 + d;
-                    __builtin_amdgcn_raw_ptr_buffer_load_lds(xrs, MCN_LDS_PTR(xb + d * CP + e0), 4,
-                                                             c < P.Cg ? go : SLAB_INVALID,
-                                                             (unsigned)c * (unsigned)HW * 4u, 0, 0);
-                }
+            for (int d = 0; d < DC; ++d) {
+                const int c = c0 + d;
+                // channels past the group's last one read as zero (their weights are zero too)
+                const __amdgpu_buffer_rsrc_t rs = (FIXED || c < P.Cg) ? xrs : zrs;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, MCN_LDS_PTR(xb + d * CP + e0), 4, go,
+                                                         (unsigned)c * (unsigned)HW * 4u, 0, 0);
             }
         }
     };
 
     // ---- compute side: tile whose accumulators are live -----------------------------------
     int bbase[MP];   // slab offset (floats) of the pixel's window origin (+ channel half when FIXED)
-    int ooff[MP];    // output offset of (io, jo, k=0 of the array, n), or -1
+    unsigned ooff[MP];   // byte offset of the lane's first result of the tile relative to the tile's output
+                         // window (filter k0 + 4*half of image n_first), or SLAB_INVALID
+    __amdgpu_buffer_rsrc_t ors = wrs;   // the tile's output window
     int c_t = 0, c_kt = 0, c_g = 0;
+    bool need_init = true;
     floatx16 acc[MK][MP];
     auto setup_compute = [&](int t) {
         c_t = t;
@@ -313,14 +319,29 @@ __global__ __launch_bounds__(64 * WK * WP, WPE) void igemm_sk_kernel(IgemmParams
             const bool ok = q < qend && io < P.Ho;
             const int ucol = jo * P.Sw + (n - n_first) * P.Wp - u0;
             bbase[mp] = (ok ? ii * P.Sh + SRP * ucol : 0) + (FIXED ? half * CP : 0);
-            ooff[mp] = ok ? (P.oi0 + P.osi * io) + P.OH * ((P.oj0 + P.osj * jo) + P.OW * (P.Ktot * n)) : -1;
+            ooff[mp] = ok ? 4u * (unsigned)((P.oi0 + P.osi * io) + P.OH * (P.oj0 + P.osj * jo) +
+                                            OHW * (P.Ktot * (n - n_first) + 4 * half))
+                          : SLAB_INVALID;
         }
+        const size_t out_base = (size_t)n_first * P.Ktot * OHW;
+        size_t out_left = ((size_t)P.N * P.Ktot * OHW - out_base) * 4;
+        if (out_left > 0x7fffffffull) out_left = 0x7fffffffull;
+        ors = __builtin_amdgcn_make_buffer_rsrc((void *)(out + out_base), 0, (int)out_left, BUFFER_FLAGS);
+        need_init = true;
+    };
+    // start value of the accumulators: the bias for a tile this block owns entirely (staged in LDS with the
+    // tile's first unit), zero for a piece of a shared tile (the fix-up pass adds the bias)
+    auto init_acc = [&](bool with_bias) {
+        const float *bl = blds + (c_t & 1) * TK;
 #pragma unroll
         for (int mk = 0; mk < MK; ++mk)
 #pragma unroll
-            for (int mp = 0; mp < MP; ++mp)
+            for (int v = 0; v < 16; ++v) {
+                const int kloc = (wk * MK + mk) * 32 + (v >> 2) * 8 + half * 4 + (v & 3);
+                const float bv = with_bias ? bl[kloc] : 0.f;
 #pragma unroll
-                for (int v = 0; v < 16; ++v) acc[mk][mp][v] = 0.f;
+                for (int mp = 0; mp < MP; ++mp) acc[mk][mp][v] = bv;
+            }
     };
     const int aoff = half * TK + wk * MK * 32 + (lane & 31);
     // steps [part*NS/2, (part+1)*NS/2) of unit uu, operands in buffer b
@@ -394,20 +415,23 @@ __global__ __launch_bounds__(64 * WK * WP, WPE) void igemm_sk_kernel(IgemmParams
         }
     };
     // lane holds pixel (lane&31) of each pixel tile and 16 filters of each filter tile
+    // Buffer stores: the filter part of the address is a scalar offset, pixels that do not exist
+    // carry an out-of-range offset and are dropped by the hardware, so no per-store vector arithmetic.
     auto store_tile = [&]() {
-        const float *bl = blds + (c_t & 1) * TK;
 #pragma unroll
         for (int mk = 0; mk < MK; ++mk) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                const int kloc = (wk * MK + mk) * 32 + (v >> 2) * 8 + half * 4 + (v & 3);
-                const int kl = c_kt * TK + kloc;
-                if (kl < P.Kg) {
-                    const int k = c_g * P.Kg + kl;
-                    const float bv = bias ? bl[kloc] : 0.f;
+                const int kl0 = c_kt * TK + (wk * MK + mk) * 32 + (v >> 2) * 8 + (v & 3);   // filter of the lower half-wave
+                const int left = P.Kg - kl0;
+                if (left <= 0) continue;
+                const unsigned soff = (unsigned)(c_g * P.Kg + kl0) * (unsigned)OHW * 4u;
 #pragma unroll
-                    for (int mp = 0; mp < MP; ++mp)
-                        if (ooff[mp] >= 0) out[(size_t)ooff[mp] + (size_t)OHW * k] = acc[mk][mp][v] + bv;
+                for (int mp = 0; mp < MP; ++mp) {
+                    // the upper half-wave holds filter kl0 + 4
+                    const unsigned vo = (left > 4 || half == 0) ? ooff[mp] : SLAB_INVALID;
+                    const float val = acc[mk][mp][v];
+                    __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(val), ors, vo, soff, 0);
                 }
             }
         }
@@ -447,6 +471,7 @@ __global__ __launch_bounds__(64 * WK * WP, WPE) void igemm_sk_kernel(IgemmParams
         if (!loads_waited) __builtin_amdgcn_s_waitcnt(WAIT_VMCNT0);   // this wave's LDS-direct loads have landed
         loads_waited = false;
         lds_barrier();                             // everyone's have, and the other buffer is free
+        if (need_init) { init_acc(whole && bias != nullptr); need_init = false; }
         const bool more = it + 1 < nunits;
         auto fetch_next = [&]() {
             if (++uu_l == NU) { uu_l = 0; ++t_l; setup_load(t_l); }

@@ -145,6 +145,11 @@ def test_tiles_shared_between_blocks_match_whole_tiles():
     base = custom_layer(20, 20, 32, 1, 3, 3, 32, 160, (1, 1), (1, 1, 1, 1), idx=80)
     for nb in (1, 3, 40):
         U.assert_errors(U.run_layer_full(synth.with_batch(base, nb)), label="sharing N=%d" % nb)
+    # enough pixels that most tiles are computed by one block alone (the direct store path)
+    big = custom_layer(40, 40, 16, 200, 3, 3, 16, 64, (1, 1), (1, 1, 1, 1), idx=81)
+    U.assert_errors(U.run_layer_full(big), label="whole tiles, 3x3")
+    big5 = custom_layer(24, 24, 6, 150, 5, 5, 6, 20, (1, 1), (2, 2, 2, 2), idx=82)
+    U.assert_errors(U.run_layer_full(big5), label="whole tiles, 5x5, ragged filters")
 
 
 # ---- semantics of the boundary ---------------------------------------------------
