@@ -4,6 +4,7 @@
 #pragma once
 #include <stdint.h>
 #include <stddef.h>
+#include <stdlib.h>
 #include "geom.h"
 #include "kern_igemm.h"
 
@@ -264,20 +265,6 @@ struct WgradPlan {
     size_t partial_floats;   // 2 slots of TK*TR per resident block
 };
 
-// columns of the slab that PCH consecutive chained pixels can touch: exact if the walk is short,
-// otherwise a bound (never too small)
-inline int wgrad_slab_columns(const ConvView &v, int TI, int PCH, int Wp) {
-    const int64_t QN = (int64_t)TI * v.Wo * v.N;
-    int64_t cols = ((int64_t)PCH - 1 + TI - 1) / TI + 1;
-    if (cols > (int64_t)v.Wo * v.N) cols = (int64_t)v.Wo * v.N;
-    const int64_t D = cols - 1;
-    const int64_t cross = v.Wf >= v.Sw ? (D + v.Wo - 1) / v.Wo : D / v.Wo;
-    const int64_t bound = D * v.Sw + cross * (v.Wf - v.Sw) + v.Wf;
-    if ((QN + PCH - 1) / PCH > 50000) return (int)bound;
-    const int exact = slab_columns(v, TI, PCH, Wp);
-    return exact;
-}
-
 inline bool plan_wgrad(const ConvView &v, int n_cu, WgradPlan *pl) {
     const int T = v.Hf * v.Wf;
     const int64_t R64 = (int64_t)T * v.Cg;
@@ -290,7 +277,7 @@ inline bool plan_wgrad(const ConvView &v, int n_cu, WgradPlan *pl) {
     if (v.Kg > 64) { shape = WG_128x128; WK = 2; WR = 2; MK = 2; MR = 2; }
     else if (v.Kg > 32) { shape = WG_64x192; WK = 2; WR = 2; MK = 1; MR = 3; }
     else { shape = WG_32x256; WK = 1; WR = 4; MK = 1; MR = 2; }
-    const int TK = WK * MK * 32, TR = WR * MR * 32, NT = 64 * WK * WR, NW = WK * WR;
+    const int TK = WK * MK * 32, TR = WR * MR * 32, NT = 64 * WK * WR;
     const int RT = (R + TR - 1) / TR;
     int nch_max = 0;
     for (int rt = 0; rt < RT; ++rt) {
@@ -298,61 +285,50 @@ inline bool plan_wgrad(const ConvView &v, int n_cu, WgradPlan *pl) {
         const int n = (hi - 1) / T - lo / T + 1;
         if (n > nch_max) nch_max = n;
     }
-    const int Wp = (v.Wo - 1) * v.Sw + v.Wf;
     const int klim = v.Kg < TK ? v.Kg : TK;
 
-    int cand[48];
-    int nc = 0;
-    cand[nc++] = v.Ho;
-    for (int parts = 2; parts <= 16; ++parts) cand[nc++] = (v.Ho + parts - 1) / parts;
-    for (int t = 32; t <= 128; t += 32) cand[nc++] = t;
-    for (int t = 1; t <= 16; t *= 2) cand[nc++] = t;
+    // a unit is a patch of TI rows x MC columns of one image's output plane, at most 128 pixels
     double best = 1e30;
-    int bestTI = 0, bestPCH = 0, bestSC = 0, bestSRP = 0, bestCP = 0, bestOcc = 0;
+    int bestTI = 0, bestMC = 0, bestSRP = 0, bestCP = 0, bestOcc = 0;
     size_t bestLds = 0;
-    for (int a = 0; a < nc; ++a) {
-        const int TI = cand[a];
-        if (TI < 1 || TI > v.Ho) continue;
-        bool dup = false;
-        for (int b = 0; b < a; ++b) dup = dup || cand[b] == TI;
-        if (dup) continue;
-        const int64_t SR = (int64_t)(TI - 1) * v.Sh + v.Hf;
+    for (int TI = 1; TI <= v.Ho && TI <= 128; ++TI) {
+        const int RB = (v.Ho + TI - 1) / TI;
+        if (TI > 1 && TI < v.Ho && (v.Ho + TI - 2) / (TI - 1) == RB) continue;   // a smaller TI gives the same row blocks
+        const int TIE = (TI + 1) & ~1;
+        const int64_t SR = (int64_t)(TIE - 1) * v.Sh + v.Hf;     // rows the padding pixel of an odd TI reads are staged too
         if (SR > 16384) continue;
-        const int64_t QN = (int64_t)TI * v.Wo * v.N;
-        if (QN >= ((int64_t)1 << 30)) continue;
         // pitches chosen so that the 32 coefficients a half-wave reads fall in 32 different LDS banks:
         // bank(r) = fi + SRP*fj + CP*c  ==  r  (mod 32)
         int SRP = (int)SR;
         while (SRP % 32 != v.Hf % 32) ++SRP;
-        int pch_cand[16];
-        int np = 0;
-        for (int m = 1; m <= 4; ++m) pch_cand[np++] = TI * m;
-        for (int m = 2; m <= 4; ++m) pch_cand[np++] = (TI + m - 1) / m;
-        pch_cand[np++] = 32; pch_cand[np++] = 64; pch_cand[np++] = 96; pch_cand[np++] = 128;
-        for (int b = 0; b < np; ++b) {
-            int PCH = (pch_cand[b] + 3) & ~3;
-            if (PCH < 8) PCH = 8;
-            if (PCH > 128) continue;
-            const int SC = wgrad_slab_columns(v, TI, PCH, Wp);
+        for (int MC = 1; MC <= v.Wo && TIE * MC <= 128; ++MC) {
+            const int CC = (v.Wo + MC - 1) / MC;
+            if (MC > 1 && MC < v.Wo && (v.Wo + MC - 2) / (MC - 1) == CC) continue;
+            const int PCH = TIE * MC;
+            const int64_t SC = (int64_t)(MC - 1) * v.Sw + v.Wf;
             if (SC >= 32768) continue;
             int64_t CP = (int64_t)SRP * SC;
             while (CP % 32 != T % 32) ++CP;
             const int64_t XS = (int64_t)nch_max * CP;
-            const int NSEG = (PCH + 63) / 64;
             const int PCHP = PCH | 1;
             const int EPT = (int)(((int64_t)SRP * SC + NT - 1) / NT);
-            const int64_t lds = (2 * (int64_t)TK * PCHP + 2 * XS + 2 * NSEG * 64 + (int64_t)EPT * NT + 4) * 4;
+            const int64_t lds = (2 * (int64_t)TK * PCHP + 2 * XS + (int64_t)EPT * NT + 4) * 4;
             if (lds > (int64_t)IGEMM_LDS_LIMIT) continue;
             int occ = (int)((int64_t)IGEMM_LDS_LIMIT / lds);
             if (occ > 2) occ = 2;   // the kernels are compiled for two waves per SIMD
-            const int RB = (v.Ho + TI - 1) / TI;
-            const double units = (double)RB * (double)((QN + PCH - 1) / PCH);
+            // cost of a unit in matrix-core cycles: its MFMAs plus what staging it costs beside them
+            // (fitted to measurements: a fixed part and a part per staged element, about twice as
+            // much when only one block fits a compute unit and nothing else hides it)
+            const double units = (double)v.N * RB * CC;
             const double mfma = (double)(PCH / 2) * MK * MR * 64.0;
-            const double loads = ((double)klim * NSEG + (double)nch_max * (double)((SRP * SC + 63) / 64)) / NW;
-            const double ovh = 900.0 + 24.0 * loads;
-            const double score = units * (mfma + ovh / (occ >= 2 ? 2.0 : 1.0));
+            const double elems = (double)klim * PCH + (double)nch_max * (double)(SRP * SC);
+            // row runs that do not start on 128-byte lines cost extra memory transactions (a patch of whole
+            // columns is one contiguous run of dzdy)
+            const bool aligned = TI == v.Ho || (TI * 4) % 128 == 0;
+            const double ovh = (1700.0 + 0.18 * elems) * (occ >= 2 ? 1.0 : 2.0) * (aligned ? 1.0 : 1.25);
+            const double score = units * (mfma + ovh);
             if (score < best) {
-                best = score; bestTI = TI; bestPCH = PCH; bestSC = SC; bestSRP = SRP; bestCP = (int)CP; bestOcc = occ;
+                best = score; bestTI = TI; bestMC = MC; bestSRP = SRP; bestCP = (int)CP; bestOcc = occ;
                 bestLds = (size_t)lds;
             }
         }
@@ -365,15 +341,14 @@ inline bool plan_wgrad(const ConvView &v, int n_cu, WgradPlan *pl) {
     P.Ho = v.Ho; P.Wo = v.Wo; P.Ktot = v.Ktot; P.Kg = v.Kg; P.G = v.G;
     P.Hf = v.Hf; P.Wf = v.Wf; P.Sh = v.Sh; P.Sw = v.Sw; P.Pt = v.Pt; P.Pl = v.Pl;
     P.TI = bestTI; P.RB = (v.Ho + bestTI - 1) / bestTI;
-    P.Wp = Wp;
-    P.SR = (bestTI - 1) * v.Sh + v.Hf;
-    P.SRP = bestSRP; P.SC = bestSC; P.CP = bestCP;
-    P.EPT = (bestSRP * bestSC + NT - 1) / NT;
+    P.MC = bestMC; P.CC = (v.Wo + bestMC - 1) / bestMC;
+    P.TIE = (bestTI + 1) & ~1;
+    P.SR = (P.TIE - 1) * v.Sh + v.Hf;
+    P.SRP = bestSRP; P.SC = (bestMC - 1) * v.Sw + v.Wf; P.CP = bestCP;
+    P.EPT = (bestSRP * P.SC + NT - 1) / NT;
     P.KT = (v.Kg + TK - 1) / TK; P.RT = RT;
-    P.QN = bestTI * v.Wo * v.N;
-    P.PCH = bestPCH; P.PCHP = bestPCH | 1;
-    P.CPR = (P.QN + bestPCH - 1) / bestPCH;
-    const int64_t NU = (int64_t)P.RB * P.CPR;
+    P.PCH = P.TIE * bestMC; P.PCHP = P.PCH | 1;
+    const int64_t NU = (int64_t)v.N * P.RB * P.CC;
     if (NU >= ((int64_t)1 << 30)) return false;
     P.NU = (int)NU;
     P.R = R;

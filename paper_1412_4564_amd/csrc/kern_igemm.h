@@ -47,7 +47,36 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 constexpr unsigned SLAB_INVALID = 0x80000000u;   // >= any buffer size used here: reads as 0
 constexpr int BUFFER_FLAGS = 0x00020000;         // raw buffer, 32-bit elements
+constexpr int BUFFER_FLAGS_WORD3 = 0x00020000;
 constexpr int WAIT_VMCNT0 = 0x0F70;              // s_waitcnt vmcnt(0) only
+
+// ---- global -> LDS loads that bypass the registers ------------------------------------------
+// buffer_load ... lds writes lane l's element at LDS address M0 + 4*l (16*l for the 128-bit
+// form); out-of-range lanes write zero; lanes that are switched off write nothing.  They are
+// issued through inline assembly so that the compiler's wait-count insertion does not know about
+// them (it would otherwise wait for them before unrelated LDS reads and serialise the
+// prefetch); the kernels wait for them explicitly with s_waitcnt vmcnt(0) before the barrier
+// that publishes the buffer.
+typedef int buffer_rsrc __attribute__((ext_vector_type(4)));
+__device__ inline buffer_rsrc make_rsrc(const void *base, unsigned bytes) {
+    const unsigned long long a = (unsigned long long)base;
+    buffer_rsrc r = {(int)(unsigned)a, (int)((a >> 32) & 0xffffu), (int)bytes, BUFFER_FLAGS_WORD3};
+    // the resource must live in scalar registers
+    r.x = __builtin_amdgcn_readfirstlane(r.x); r.y = __builtin_amdgcn_readfirstlane(r.y);
+    r.z = __builtin_amdgcn_readfirstlane(r.z); r.w = __builtin_amdgcn_readfirstlane(r.w);
+    return r;
+}
+__device__ inline unsigned lds_address(const void *p) { return (unsigned)(size_t)MCN_LDS_PTR(p); }
+// lds_addr: wave-uniform LDS byte address of lane 0's element
+__device__ inline void load_to_lds_b32(unsigned lds_addr, unsigned voffset, buffer_rsrc rsrc, unsigned soffset) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, %3 offen lds"
+                 :: "s"(lds_addr), "v"(voffset), "s"(rsrc), "s"(soffset) : "memory");
+}
+__device__ inline void load_to_lds_b128(unsigned lds_addr, unsigned voffset, buffer_rsrc rsrc, unsigned soffset) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                 :: "s"(lds_addr), "v"(voffset), "s"(rsrc), "s"(soffset) : "memory");
+}
+
 
 // Workgroup barrier that orders LDS traffic only: unlike __syncthreads() it does not wait for
 // this wave's outstanding global stores, so a finished tile drains to memory while the next one
@@ -224,13 +253,13 @@ __global__ __launch_bounds__(64 * WK * WP, WPE) void igemm_sk_kernel(IgemmParams
         }
     }
 
-    __amdgpu_buffer_rsrc_t wrs = __builtin_amdgcn_make_buffer_rsrc((void *)wpk, 0, (int)P.packed_bytes, BUFFER_FLAGS);
-    __amdgpu_buffer_rsrc_t brs = __builtin_amdgcn_make_buffer_rsrc((void *)bias, 0, bias ? P.Ktot * 4 : 0, BUFFER_FLAGS);
-    const __amdgpu_buffer_rsrc_t zrs = __builtin_amdgcn_make_buffer_rsrc((void *)in, 0, 0, BUFFER_FLAGS);   // reads as zero
+    const buffer_rsrc wrs = make_rsrc(wpk, P.packed_bytes);
+    const buffer_rsrc brs = make_rsrc(bias, bias ? (unsigned)P.Ktot * 4u : 0u);
+    const buffer_rsrc zrs = make_rsrc(in, 0);   // reads as zero
     const unsigned lane16 = (unsigned)lane * 16u;
 
     // ---- load side: tile whose units are being fetched ------------------------------------
-    __amdgpu_buffer_rsrc_t xrs = wrs;
+    buffer_rsrc xrs = wrs;
     unsigned wtile_off = 0;        // byte offset of the tile's packed weights
     int l_t = 0, l_kt = 0, l_g = 0;
     auto setup_load = [&](int t) {
@@ -245,7 +274,7 @@ __global__ __launch_bounds__(64 * WK * WP, WPE) void igemm_sk_kernel(IgemmParams
         const size_t in_base = ((size_t)n_first * P.Ctot + (size_t)g * P.Cg) * HW;
         size_t in_left = ((size_t)P.N * P.Ctot * HW - in_base) * 4;
         if (in_left > 0x7fffffffull) in_left = 0x7fffffffull;
-        xrs = __builtin_amdgcn_make_buffer_rsrc((void *)(in + in_base), 0, (int)in_left, BUFFER_FLAGS);
+        xrs = make_rsrc(in + in_base, (unsigned)in_left);
         wtile_off = (unsigned)((size_t)(g * P.KT + kt) * NU * WSZ * 4);
         l_kt = kt; l_g = g;
         for (int s = 0; s < P.EPT; ++s) {
@@ -266,13 +295,13 @@ __global__ __launch_bounds__(64 * WK * WP, WPE) void igemm_sk_kernel(IgemmParams
         float *xb = xbuf + b * XSZ;
         const unsigned woff = wtile_off + (unsigned)uu * (unsigned)WSZ * 4u;
         for (int e0 = wave * 256; e0 < WSZ; e0 += NW * 256)       // one wave instruction = 256 floats, 16 bytes per lane
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(wrs, MCN_LDS_PTR(wb + e0), 16, lane16, woff + (unsigned)e0 * 4u, 0, 0);
+            load_to_lds_b128(lds_address(wb + e0), lane16, wrs, woff + (unsigned)e0 * 4u);
         if (bias && uu == 0 && wave * 64 < TK) {
             // the tile's bias: start value of the accumulators of a tile this block owns entirely
             const int kl = l_kt * TK + wave * 64 + lane;
             if (wave * 64 + lane < TK)
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(brs, MCN_LDS_PTR(blds + (l_t & 1) * TK + wave * 64), 4,
-                                                         kl < P.Kg ? (unsigned)(l_g * P.Kg + kl) * 4u : SLAB_INVALID, 0, 0, 0);
+                load_to_lds_b32(lds_address(blds + (l_t & 1) * TK + wave * 64),
+                                kl < P.Kg ? (unsigned)(l_g * P.Kg + kl) * 4u : SLAB_INVALID, brs, 0);
         }
         const int cg = FIXED ? uu : uu / P.NTR;
         const int c0 = cg * DC;
@@ -283,9 +312,8 @@ __global__ __launch_bounds__(64 * WK * WP, WPE) void igemm_sk_kernel(IgemmParams
             for (int d = 0; d < DC; ++d) {
                 const int c = c0 + d;
                 // channels past the group's last one read as zero (their weights are zero too)
-                const __amdgpu_buffer_rsrc_t rs = (FIXED || c < P.Cg) ? xrs : zrs;
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, MCN_LDS_PTR(xb + d * CP + e0), 4, go,
-                                                         (unsigned)c * (unsigned)HW * 4u, 0, 0);
+                const buffer_rsrc rs = (FIXED || c < P.Cg) ? xrs : zrs;
+                load_to_lds_b32(lds_address(xb + d * CP + e0), go, rs, (unsigned)c * (unsigned)HW * 4u);
             }
         }
     };
@@ -294,7 +322,7 @@ __global__ __launch_bounds__(64 * WK * WP, WPE) void igemm_sk_kernel(IgemmParams
     int bbase[MP];   // slab offset (floats) of the pixel's window origin (+ channel half when FIXED)
     unsigned ooff[MP];   // byte offset of the lane's first result of the tile relative to the tile's output
                          // window (filter k0 + 4*half of image n_first), or SLAB_INVALID
-    __amdgpu_buffer_rsrc_t ors = wrs;   // the tile's output window
+    __amdgpu_buffer_rsrc_t ors = __builtin_amdgcn_make_buffer_rsrc((void *)out, 0, 0, BUFFER_FLAGS);   // the tile's output window
     int c_t = 0, c_kt = 0, c_g = 0;
     bool need_init = true;
     floatx16 acc[MK][MP];

@@ -6,10 +6,14 @@
 // GEMM view:  OUT[k][r] = sum_p DY[k][p] * PATCH[r][p],  r = fi + Hf*(fj + Wf*c)  (the memory order
 // of one filter), p = output pixel.  The reduction runs over pixels, two per
 // v_mfma_f32_32x32x2_f32.  A tile is TK filters x TR coefficients; its reduction is cut into
-// units of PCH pixels.  For a unit the block stages in LDS the dzdy tile [k][pixel] and, per
-// input channel of the tile's r range, the slab of x that those pixels read (no im2row
-// buffer), plus a table pixel -> slab offset.  Lanes run along r, so the final stores are
-// coalesced.
+// units.  A unit is a patch of TI rows x MC columns of one image's output plane (pixel
+// p = ii + TIE*dc of the patch, TIE = TI rounded up to even so that the two pixels of an MFMA
+// step lie in one column), so everything that depends on the lane -- which pixel, which slab
+// element -- is the same for every unit, and only scalar base offsets change from unit to
+// unit; inside a column both operands advance by a constant stride from step to step, so the
+// MFMA loop addresses LDS with immediate offsets.  For a unit the block stages in LDS the dzdy tile [k][pixel] and, per input
+// channel of the tile's r range, the slab of x that the patch reads (no im2row buffer).  Lanes
+// run along r, so the final stores are coalesced.
 //
 // Scheduling is the same as in the forward kernel: all (tile, unit) pairs are cut into
 // nblocks equal contiguous ranges, one per resident block; a block writes its piece of a
@@ -17,8 +21,9 @@
 // so results do not depend on scheduling (no float atomics).  Global -> LDS loads bypass the
 // registers and run one unit ahead.
 //
-// Pixels are numbered as in the forward kernel: rows are cut into row blocks of TI rows,
-// and inside a row block q = ii + TI*(jo + Wo*n).
+// The matrix core and the vector ALU share issue cycles, so the code around the MFMA loop is
+// written to need few vector instructions: per-lane quantities are precomputed once per block,
+// unit-dependent quantities are scalar.
 //
 // With a 1x1 view this kernel is a plain GEMM  OUT[k][c] = sum_p A[k][p] B[c][p]  with both
 // operands contiguous along the reduction, which is what the forward pass of a
@@ -35,22 +40,22 @@ struct WgradParams {
     int H, W, N, Ctot, Cg;
     int Ho, Wo, Ktot, Kg, G;
     int Hf, Wf, Sh, Sw, Pt, Pl;
-    int TI, RB;          // rows per row block, row blocks
-    int Wp;              // chained-column pitch of one image
+    int TI, RB;          // rows per patch, patches per column (row blocks)
+    int TIE;             // TI rounded up to even: pixel pitch of a patch column
+    int MC, CC;          // columns per patch, patches per row of patches: ceil(Wo / MC)
     int SR, SRP, SC;     // slab rows, padded row pitch, columns
     int CP;              // slab channel pitch
     int EPT;             // slab positions per thread: ceil(SRP*SC / threads)
     int KT, RT;          // filter tiles per group, r tiles
-    int QN;              // TI*Wo*N
-    int PCH, PCHP;       // pixels per unit (multiple of 4), LDS pitch of a dzdy row (odd)
-    int CPR;             // units per row block: ceil(QN / PCH)
-    int NU;              // units per tile = RB * CPR
+    int PCH, PCHP;       // pixels per unit = TIE*MC, LDS pitch of a dzdy row (odd)
+    int NU;              // units per tile = N * RB * CC
     int R;               // Hf*Wf*Cg
     int XS;              // floats per slab buffer (max channels of an r tile * CP)
     int tiles, nblocks;
 };
 
-template <int WK, int WR, int MK, int MR, int WPE>
+// S1: vertical stride 1 (the slab rows of consecutive pixels are adjacent)
+template <int WK, int WR, int MK, int MR, bool S1, int WPE>
 __global__ __launch_bounds__(64 * WK * WR, WPE) void wgrad_sk_kernel(WgradParams P, const float *__restrict__ x,
                                                                      const float *__restrict__ dzdy,
                                                                      const float *__restrict__ rbias,
@@ -60,6 +65,7 @@ __global__ __launch_bounds__(64 * WK * WR, WPE) void wgrad_sk_kernel(WgradParams
     constexpr int NW = WK * WR;
     constexpr int TK = WK * MK * 32;
     constexpr int TR = WR * MR * 32;
+    constexpr int NSEGMAX = 2;                 // PCH <= 128
     const int PCH = P.PCH, PCHP = P.PCHP;
     const int NSEG = (PCH + 63) >> 6;
     const int YS = TK * PCHP;
@@ -69,8 +75,7 @@ __global__ __launch_bounds__(64 * WK * WR, WPE) void wgrad_sk_kernel(WgradParams
     extern __shared__ __align__(16) float lds[];
     float *ybuf = lds;                                        // [2][TK*PCHP]
     float *xbuf = lds + 2 * YS;                               // [2][XS]
-    int *tabbuf = reinterpret_cast<int *>(xbuf + 2 * P.XS);   // [2][NSEG*64] pixel -> slab offset
-    int *etab = tabbuf + 2 * NSEG * 64;                       // [EPT][NT] slab position -> (col, row), private per thread
+    int *etab = reinterpret_cast<int *>(xbuf + 2 * P.XS);     // [EPT][NT] slab position -> (row | column << 16); private per thread
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -83,17 +88,32 @@ __global__ __launch_bounds__(64 * WK * WR, WPE) void wgrad_sk_kernel(WgradParams
     const long long ub = sk_begin(total, P.nblocks, vb), ue = sk_begin(total, P.nblocks, vb + 1);
     if (ub >= ue) return;
 
-    // slab position e = col*SRP + r  ->  (col, r); r >= SR is pitch padding
+    // ---- per-lane quantities that hold for every unit ------------------------------------------
+    // slab position e = col*SRP + r
     for (int s = 0; s < P.EPT; ++s) {
         const int e = tid + NT * s;
         const int col = e / SRP;
         const int r = e - col * SRP;
-        etab[s * NT + tid] = (col < P.SC && r < P.SR) ? (col << 16 | r) : -1;
+        const bool ok = col < P.SC && r < P.SR;
+        etab[s * NT + tid] = ok ? (r | col << 16) : 0x7fff;       // pitch padding: any row will do, it is never read
+    }
+    // pixel p = ii + TIE*dc of the patch
+    int p_ii[NSEGMAX], p_dc[NSEGMAX];
+    unsigned p_off[NSEGMAX];
+#pragma unroll
+    for (int seg = 0; seg < NSEGMAX; ++seg) {
+        const int p = seg * 64 + lane;
+        const int dc = p / P.TIE;
+        const int ii = p - dc * P.TIE;
+        const bool ok = ii < P.TI && dc < P.MC;
+        p_ii[seg] = ok ? ii : 0x40000000;
+        p_dc[seg] = dc;
+        p_off[seg] = 4u * (unsigned)(ii + P.Ho * dc);
     }
 
     // ---- load side -------------------------------------------------------------------------
-    __amdgpu_buffer_rsrc_t xrs = __builtin_amdgcn_make_buffer_rsrc((void *)x, 0, 0x7fffffff, BUFFER_FLAGS);
-    __amdgpu_buffer_rsrc_t yrs = xrs;
+    buffer_rsrc xrs = make_rsrc(x, 0x7fffffffu);
+    buffer_rsrc yrs = xrs;
     int l_klim = 0, l_nch = 0;
     auto setup_load = [&](int t) {
         const int rt = t % P.RT; t /= P.RT;
@@ -104,58 +124,45 @@ __global__ __launch_bounds__(64 * WK * WR, WPE) void wgrad_sk_kernel(WgradParams
         const int c_lo = r_lo / T;
         l_nch = (r_hi - 1) / T - c_lo + 1;
         l_klim = min(P.Kg - kt * TK, TK);
-        xrs = __builtin_amdgcn_make_buffer_rsrc((void *)(x + ((size_t)g * P.Cg + c_lo) * HW), 0, 0x7fffffff, BUFFER_FLAGS);
-        yrs = __builtin_amdgcn_make_buffer_rsrc((void *)(dzdy + ((size_t)g * P.Kg + (size_t)kt * TK) * HoWo), 0,
-                                                0x7fffffff, BUFFER_FLAGS);
+        xrs = make_rsrc(x + ((size_t)g * P.Cg + c_lo) * HW, 0x7fffffffu);
+        yrs = make_rsrc(dzdy + ((size_t)g * P.Kg + (size_t)kt * TK) * HoWo, 0x7fffffffu);
     };
     auto issue_loads = [&](int uu, int b) {
         float *yb = ybuf + b * YS;
         float *xb = xbuf + b * P.XS;
-        int *tb = tabbuf + b * NSEG * 64;
-        const int rb = uu / P.CPR;
-        const int qa = (uu - rb * P.CPR) * PCH;
-        const int q_hi = min(qa + PCH, P.QN);
-        // unit geometry (uniform)
-        const int c_first = qa / P.TI;
-        const int n_first = c_first / P.Wo;
-        const int u0 = (c_first - n_first * P.Wo) * P.Sw;
+        // unit -> image, patch (all scalar)
+        const int per_image = P.RB * P.CC;
+        const int n = uu / per_image;
+        const int rem = uu - n * per_image;
+        const int jc = rem / P.RB, rb = rem - jc * P.RB;
+        const int io0 = rb * P.TI, jo0 = jc * P.MC;
+        const int rows = min(P.TI, P.Ho - io0), cols = min(P.MC, P.Wo - jo0);
         // dzdy tile: one wave instruction = 64 pixels of one filter
+        const unsigned ybase = 4u * (unsigned)(io0 + P.Ho * jo0 + n * (P.Ktot * HoWo));
         for (int seg = 0; seg < NSEG; ++seg) {
-            const int pl = seg * 64 + lane;
-            const int q = qa + pl;
-            const int c = q / P.TI;
-            const int ii = q - c * P.TI;
-            const int n = c / P.Wo;
-            const int jo = c - n * P.Wo;
-            const int io = rb * P.TI + ii;
-            const bool pok = q < q_hi && io < P.Ho;
-            const unsigned yoff = pok ? 4u * (unsigned)(io + P.Ho * jo + n * (P.Ktot * HoWo)) : SLAB_INVALID;
-            if (wave == 0) tb[pl] = pok ? ii * P.Sh + SRP * (jo * P.Sw + (n - n_first) * P.Wp - u0) : 0;
-            if (pl < PCH) {
+            const unsigned yoff = (p_ii[seg] < rows && p_dc[seg] < cols) ? p_off[seg] + ybase : SLAB_INVALID;
+            if (seg * 64 + lane < PCH) {
                 for (int k = wave; k < l_klim; k += NW)
-                    __builtin_amdgcn_raw_ptr_buffer_load_lds(yrs, MCN_LDS_PTR(yb + k * PCHP + seg * 64), 4, yoff,
-                                                             (unsigned)k * (unsigned)HoWo * 4u, 0, 0);
+                    load_to_lds_b32(lds_address(yb + k * PCHP + seg * 64), yoff, yrs, (unsigned)k * (unsigned)HoWo * 4u);
             }
         }
-        // x slab of the tile's channels
-        const int row0 = rb * P.TI * P.Sh - P.Pt;
+        // x slab of the tile's channels: rows i0 + r, columns j0 + col of image n
+        const int i0 = io0 * P.Sh - P.Pt, j0 = jo0 * P.Sw - P.Pl;
+        const int xbase = 4 * (i0 + P.H * j0 + n * (P.Ctot * HW));
         const int ntot = SRP * P.SC;
         for (int s = 0; s < P.EPT; ++s) {
             const int e0 = wave * 64 + NT * s;
             if (e0 >= ntot) break;
-            const int cr = etab[s * NT + tid];
-            const int col = cr >> 16, r = cr & 0xffff;
-            const int U = u0 + col;
-            const int ni = U / P.Wp;
-            const int j = U - ni * P.Wp - P.Pl;
-            const int i = row0 + r;
-            const bool ok = cr >= 0 && i >= 0 && i < P.H && j >= 0 && j < P.W && (n_first + ni) < P.N;
-            const unsigned go = ok ? 4u * (unsigned)(i + P.H * j + (n_first + ni) * (P.Ctot * HW)) : SLAB_INVALID;
+            const int rc = etab[s * NT + tid];
+            const int r = rc & 0xffff, col = rc >> 16;
+            const int rel = 4 * (r + P.H * col);
+            const bool ok = (unsigned)(r + i0) < (unsigned)P.H && (unsigned)(col + j0) < (unsigned)P.W;
+            const unsigned go = ok ? (unsigned)(rel + xbase) : SLAB_INVALID;
             if (e0 + lane < ntot) {
                 for (int d = 0; d < l_nch; ++d)
-                    __builtin_amdgcn_raw_ptr_buffer_load_lds(xrs, MCN_LDS_PTR(xb + d * CP + e0), 4, go,
-                                                             (unsigned)d * (unsigned)HW * 4u, 0, 0);
+                    load_to_lds_b32(lds_address(xb + d * CP + e0), go, xrs, (unsigned)d * (unsigned)HW * 4u);
             }
+
         }
     };
 
@@ -181,7 +188,7 @@ __global__ __launch_bounds__(64 * WK * WR, WPE) void wgrad_sk_kernel(WgradParams
                 const int fi = tap - fj * P.Hf;
                 o = (c - c_lo) * CP + fj * SRP + fi;
             }
-            roff[mr] = o;
+            roff[mr] = o + half * P.Sh;             // the upper half-wave takes the odd pixel of a step
         }
 #pragma unroll
         for (int mk = 0; mk < MK; ++mk)
@@ -191,18 +198,17 @@ __global__ __launch_bounds__(64 * WK * WR, WPE) void wgrad_sk_kernel(WgradParams
                 for (int v = 0; v < 16; ++v) acc[mk][mr][v] = 0.f;
     };
     const int aoff = (wk * MK * 32 + l32) * PCHP + half;
+    // all steps of the unit in buffer b: columns of the patch, two pixels per step
     auto compute = [&](int b) {
-        const float *yb = ybuf + b * YS + aoff;
-        const float *xb = xbuf + b * P.XS;
-        const int *tb = tabbuf + b * NSEG * 64 + half;
-        const int steps = PCH >> 1;             // even
-        float a0[MK], b0[MR], a1[MK], b1[MR];
-        auto fetch = [&](float *a, float *bq, int t, int tv) {
+        // running LDS indices (floats) of the lane's operands
+        int ya[MK], xr[MR];
 #pragma unroll
-            for (int mk = 0; mk < MK; ++mk) a[mk] = yb[mk * 32 * PCHP + 2 * t];
+        for (int mk = 0; mk < MK; ++mk) ya[mk] = b * YS + aoff + mk * 32 * PCHP;
 #pragma unroll
-            for (int mr = 0; mr < MR; ++mr) bq[mr] = xb[roff[mr] + tv];
-        };
+        for (int mr = 0; mr < MR; ++mr) xr[mr] = b * P.XS + roff[mr];
+        const int steps_col = P.TIE >> 1;
+        const int xstep = 2 * P.Sh;                                   // floats between the slab rows of steps t and t+1
+        const int xcol = SRP * P.Sw - P.TIE * P.Sh;                   // from the end of a column to the start of the next
         auto mma = [&](const float *a, const float *bq) {
 #pragma unroll
             for (int mk = 0; mk < MK; ++mk)
@@ -210,22 +216,36 @@ __global__ __launch_bounds__(64 * WK * WR, WPE) void wgrad_sk_kernel(WgradParams
                 for (int mr = 0; mr < MR; ++mr)
                     acc[mk][mr] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[mk], bq[mr], acc[mk][mr], 0, 0, 0);
         };
-        int t0 = tb[0], t1 = tb[2];
-        fetch(a0, b0, 0, t0);
-        for (int t = 0; t < steps; t += 2) {
-            const int t0n = tb[2 * min(t + 2, steps - 1)];
-            const int t1n = tb[2 * min(t + 3, steps - 1)];
-            fetch(a1, b1, t + 1, t1);
-            __builtin_amdgcn_sched_barrier(0);
-            mma(a0, b0);
-            __builtin_amdgcn_sched_barrier(0);
-            if (t + 2 < steps) fetch(a0, b0, t + 2, t0n);
-            __builtin_amdgcn_sched_barrier(0);
-            mma(a1, b1);
-            __builtin_amdgcn_sched_barrier(0);
-            t0 = t0n; t1 = t1n;
+        for (int dc = 0; dc < P.MC; ++dc) {
+            int t = 0;
+            for (; t + 4 <= steps_col; t += 4) {
+                float a[4][MK], bq[4][MR];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+#pragma unroll
+                    for (int mk = 0; mk < MK; ++mk) a[j][mk] = ybuf[ya[mk] + 2 * j];
+#pragma unroll
+                    for (int mr = 0; mr < MR; ++mr)
+                        bq[j][mr] = xbuf[xr[mr] + (S1 ? 2 * j : xstep * j)];
+                }
+#pragma unroll
+                for (int mk = 0; mk < MK; ++mk) ya[mk] += 8;
+#pragma unroll
+                for (int mr = 0; mr < MR; ++mr) xr[mr] += S1 ? 8 : 4 * xstep;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) mma(a[j], bq[j]);
+            }
+            for (; t < steps_col; ++t) {
+                float a[MK], bq[MR];
+#pragma unroll
+                for (int mk = 0; mk < MK; ++mk) { a[mk] = ybuf[ya[mk]]; ya[mk] += 2; }
+#pragma unroll
+                for (int mr = 0; mr < MR; ++mr) { bq[mr] = xbuf[xr[mr]]; xr[mr] += S1 ? 2 : xstep; }
+                mma(a, bq);
+            }
+#pragma unroll
+            for (int mr = 0; mr < MR; ++mr) xr[mr] += xcol;
         }
-        (void)t0;
     };
     // lane holds coefficient r (lane&31) of each r tile and 16 filters of each filter tile
     auto store_tile = [&]() {
@@ -273,13 +293,15 @@ __global__ __launch_bounds__(64 * WK * WR, WPE) void wgrad_sk_kernel(WgradParams
     const int nunits = (int)(ue - ub);
     for (int it = 0; it < nunits; ++it) {
         __builtin_amdgcn_s_waitcnt(WAIT_VMCNT0);
-        __syncthreads();
-        if (it + 1 < nunits) {
+        lds_barrier();
+        const bool more = it + 1 < nunits;
+        auto fetch_next = [&]() {
             if (++uu_l == NU) { uu_l = 0; ++t_l; setup_load(t_l); }
             issue_loads(uu_l, (it + 1) & 1);
-        }
+        };
+        if (more) fetch_next();
         compute(it & 1);
-        const bool last = it + 1 == nunits;
+        const bool last = !more;
         if (uu_c + 1 == NU || last) {
             if (whole) store_tile();
             else store_partial(2 * vb + (first_segment ? 0 : 1));

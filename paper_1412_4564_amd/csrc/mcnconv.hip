@@ -184,10 +184,10 @@ int launch_igemm(const IgemmPlan &pl, const float *in, const float *w, const flo
     }
 }
 
-template <int WK, int WR, int MK, int MR>
-int launch_wgrad_inst(const WgradPlan &pl, const float *x, const float *dzdy, const float *rbias, float *out,
-                      float *part, hipStream_t s) {
-    auto kern = wgrad_sk_kernel<WK, WR, MK, MR, 2>;
+template <int WK, int WR, int MK, int MR, bool S1>
+int launch_wgrad_inst2(const WgradPlan &pl, const float *x, const float *dzdy, const float *rbias, float *out,
+                       float *part, hipStream_t s) {
+    auto kern = wgrad_sk_kernel<WK, WR, MK, MR, S1, 2>;
     if (pl.lds_bytes > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
                                            (int)pl.lds_bytes);
@@ -200,6 +200,13 @@ int launch_wgrad_inst(const WgradPlan &pl, const float *x, const float *dzdy, co
     hipLaunchKernelGGL((wgrad_fixup_kernel<TK, TR>), dim3(pl.P.nblocks - 1, TK * TR / 256), dim3(256), 0, s, pl.P, part,
                        rbias, out);
     return check_launch();
+}
+
+template <int WK, int WR, int MK, int MR>
+int launch_wgrad_inst(const WgradPlan &pl, const float *x, const float *dzdy, const float *rbias, float *out,
+                      float *part, hipStream_t s) {
+    return pl.P.Sh == 1 ? launch_wgrad_inst2<WK, WR, MK, MR, true>(pl, x, dzdy, rbias, out, part, s)
+                        : launch_wgrad_inst2<WK, WR, MK, MR, false>(pl, x, dzdy, rbias, out, part, s);
 }
 
 int launch_wgrad(const WgradPlan &pl, const float *x, const float *dzdy, const float *rbias, float *out, void *ws,
