@@ -11,6 +11,7 @@ on which the headline metric is quoted.  Prints ONE JSON line.
 """
 import argparse
 import json
+import os
 import sys
 import time
 
@@ -24,6 +25,22 @@ FP32_MFMA_PEAK_TFLOPS = 157.3     # 256 CU x 256 flop/clk x 2.4 GHz
 HBM_PEAK_GBS = 8000.0
 
 WORKLOADS = {"vgg3x3": ["4a", "4b", "4c"]}
+TRAFFIC_FILE = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "vgg3x3_hbm_traffic.txt")
+
+
+def measured_traffic(call):
+    """HBM bytes (fetch + write) of one call, from the committed summary of the two rocprofv3 --pmc
+    runs of this benchmark (lines 'TOTAL <layer>.<operation> <fetch bytes> <write bytes>'); None if
+    the summary does not hold the call."""
+    try:
+        with open(TRAFFIC_FILE) as f:
+            for line in f:
+                t = line.split()
+                if len(t) == 4 and t[0] == "TOTAL" and t[1] == call:
+                    return int(float(t[2]) + float(t[3]))
+    except OSError:
+        pass
+    return None
 OPS = ["forward", "backward_data", "backward_filter", "backward_bias"]
 
 
@@ -72,7 +89,7 @@ def cpu_baseline(names):
     """The oracle as it stands, timed on this machine's host cores on a bounded sample
     of the same workload: the same layers at a reduced batch."""
     import oracle
-    sample_n = {"4a": 1, "4b": 1, "4c": 2}
+    sample_n = {"4a": 12, "4b": 12, "4c": 24}      # about 10-20 s of host time in all
     flops, secs, desc = 0.0, 0.0, []
     for name in names:
         L = synth.with_batch(synth.LAYERS[name], sample_n.get(name, 1))
@@ -172,12 +189,14 @@ def main():
     if op < 3:
         ach = 2.0 * dom.macs / per[li, op] / 1e9
         roof = {"bound": "mfma", "achieved": round(ach, 2), "peak": FP32_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-                "frac": round(ach / FP32_MFMA_PEAK_TFLOPS, 4), "traffic": None,
+                "frac": round(ach / FP32_MFMA_PEAK_TFLOPS, 4),
+                "traffic": measured_traffic("%s.%s" % (dom.name, OPS[op])) if args.workload == "vgg3x3" else None,
                 "kernel": "%s.%s (%s)" % (dom.name, OPS[op], dom.kernels[op])}
     else:
         ach = dom.bytes[op] / per[li, op] / 1e6
         roof = {"bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": None,
+                "frac": round(ach / HBM_PEAK_GBS, 4),
+                "traffic": measured_traffic("%s.%s" % (dom.name, OPS[op])) if args.workload == "vgg3x3" else None,
                 "kernel": "%s.%s (%s)" % (dom.name, OPS[op], dom.kernels[op])}
 
     out = {

@@ -317,34 +317,53 @@ __global__ __launch_bounds__(64 * WK * WR, WPE) void wgrad_sk_kernel(WgradParams
     }
 }
 
-// Sum the pieces of every tile shared between blocks, in block order, and write the tile.
+// Sum the pieces of every tile shared between blocks and write the tile.  The order of the
+// additions is fixed: piece i goes to partial sum i mod 8, the partial sums are added as a
+// balanced tree.  blockIdx.x = tile; one block = 64 results x 8 partial sums.
 template <int TK, int TR>
-__global__ __launch_bounds__(256) void wgrad_fixup_kernel(WgradParams P, const float *__restrict__ part,
+__global__ __launch_bounds__(512) void wgrad_fixup_kernel(WgradParams P, const float *__restrict__ part,
                                                           const float *__restrict__ rbias, float *__restrict__ out) {
-    const int j = blockIdx.x + 1;
+    const int t = blockIdx.x;
     const long long total = (long long)P.tiles * P.NU;
-    const long long B = sk_begin(total, P.nblocks, j);
-    const int t = (int)(B / P.NU);
     const long long t_lo = (long long)t * P.NU, t_hi = t_lo + P.NU;
-    if (B == t_lo) return;
-    if (sk_begin(total, P.nblocks, j - 1) > t_lo) return;
+    // first block with units of this tile
+    int b0 = (int)(t_lo * P.nblocks / total);
+    while (b0 + 1 < P.nblocks && sk_begin(total, P.nblocks, b0 + 1) <= t_lo) ++b0;
+    while (b0 > 0 && sk_begin(total, P.nblocks, b0) > t_lo) --b0;
+    const long long b0_lo = sk_begin(total, P.nblocks, b0);
+    if (sk_begin(total, P.nblocks, b0 + 1) >= t_hi) return;      // computed by one block alone: already written
+    int b_last = b0 + 1;
+    while (b_last + 1 < P.nblocks && sk_begin(total, P.nblocks, b_last + 1) < t_hi) ++b_last;
+    const int npieces = b_last - b0 + 1;
+    // block b0's piece is its first one if it starts with this tile, else its last; the others start inside the tile
+    const int slot0 = 2 * b0 + (b0_lo >= t_lo ? 0 : 1);
     int tt = t;
     const int rt = tt % P.RT; tt /= P.RT;
     const int kt = tt % P.KT;
     const int g = tt / P.KT;
     const int klim = min(P.Kg - kt * TK, TK);
-    // blocks that hold a piece of this tile: j-1 .. b_last
-    int b_last = j;
-    while (b_last + 1 < P.nblocks && sk_begin(total, P.nblocks, b_last + 1) < t_hi) ++b_last;
-    const bool first_is_head = sk_begin(total, P.nblocks, j - 1) >= t_lo;
-    for (int e = blockIdx.y * 256 + threadIdx.x; e < TK * TR; e += gridDim.y * 256) {
-        const int kloc = e / TR, rl = e - kloc * TR;
-        const int r = rt * TR + rl;
-        if (kloc >= klim || r >= P.R) continue;
-        float acc = part[(size_t)(2 * (j - 1) + (first_is_head ? 0 : 1)) * (TK * TR) + e];
-        for (int b = j; b <= b_last; ++b) acc += part[(size_t)(2 * b) * (TK * TR) + e];
-        if (rbias) acc += rbias[r];
-        out[(size_t)(g * P.Kg + kt * TK + kloc) * P.R + r] = acc;
+    __shared__ float red[8][64];
+    const int el = threadIdx.x & 63, pg = threadIdx.x >> 6;
+    for (int e0 = blockIdx.y * 64; e0 < TK * TR; e0 += gridDim.y * 64) {
+        const int e = e0 + el;
+        float acc = 0.f;
+        for (int i = pg; i < npieces; i += 8) {
+            const int slot = i == 0 ? slot0 : 2 * (b0 + i);
+            acc += part[(size_t)slot * (TK * TR) + e];
+        }
+        red[pg][el] = acc;
+        __syncthreads();
+        if (pg == 0) {
+            const int kloc = e / TR, rl = e - kloc * TR;
+            const int r = rt * TR + rl;
+            if (kloc < klim && r < P.R) {
+                float v = ((red[0][el] + red[1][el]) + (red[2][el] + red[3][el])) +
+                          ((red[4][el] + red[5][el]) + (red[6][el] + red[7][el]));
+                if (rbias) v += rbias[r];
+                out[(size_t)(g * P.Kg + kt * TK + kloc) * P.R + r] = v;
+            }
+        }
+        __syncthreads();
     }
 }
 

@@ -197,8 +197,11 @@ int launch_wgrad_inst2(const WgradPlan &pl, const float *x, const float *dzdy, c
     int st = check_launch();
     if (st || pl.P.nblocks < 2) return st;
     constexpr int TK = WK * MK * 32, TR = WR * MR * 32;
-    hipLaunchKernelGGL((wgrad_fixup_kernel<TK, TR>), dim3(pl.P.nblocks - 1, TK * TR / 256), dim3(256), 0, s, pl.P, part,
-                       rbias, out);
+    // at most nblocks - 1 tiles are shared, but which ones is cheaper to find per tile
+    int fy = 2048 / pl.P.tiles;          // about 2048 blocks in all
+    if (fy < 1) fy = 1;
+    if (fy > TK * TR / 64) fy = TK * TR / 64;
+    hipLaunchKernelGGL((wgrad_fixup_kernel<TK, TR>), dim3(pl.P.tiles, fy), dim3(512), 0, s, pl.P, part, rbias, out);
     return check_launch();
 }
 
