@@ -49,7 +49,7 @@ def layer_macs(L, ho, wo):
 
 
 class LayerState:
-    def __init__(self, name, L, precision):
+    def __init__(self, name, L, precision, rotate_mb=0):
         self.name, self.L = name, L
         self.st, self.pad, self.prec = L["stride"], L["pad"], precision
         self.x = synth.make_x(L).cuda()
@@ -63,6 +63,15 @@ class LayerState:
         self.dx = torch.empty_like(self.x)
         self.dw = torch.empty_like(self.w)
         self.db = torch.empty_like(self.b)
+        # optional rotation through several copies of the activations, so that repeated launches are
+        # not served from the 256 MB last-level cache (for the memory-bound layers)
+        self.sets = [(self.x, self.p, self.y, self.dx)]
+        if rotate_mb > 0:
+            per_set = 4 * (2 * self.x.numel() + 2 * self.p.numel())
+            n_sets = min(256, max(1, -(-rotate_mb * (1 << 20) // per_set)))
+            for _ in range(n_sets - 1):
+                self.sets.append((self.x.clone(), self.p.clone(), torch.empty_like(self.p), torch.empty_like(self.x)))
+        self.turn = 0
         self.macs = layer_macs(L, self.ho, self.wo)
         self.kernels = [B.mcn_conv_kernel_name(desc, op) for op in range(4)]
         ws = max(B.mcn_conv_workspace_size(desc, op) for op in range(4))
@@ -73,14 +82,17 @@ class LayerState:
 
     def run(self, op, stream):
         d, ws, n = self.desc, self.ws.data_ptr(), self.ws.numel()
+        x, p, y, dx = self.sets[self.turn % len(self.sets)]
+        if op == 3:
+            self.turn += 1
         if op == 0:
-            st = B.mcn_conv_forward(d, self.x.data_ptr(), self.w.data_ptr(), self.b.data_ptr(), self.y.data_ptr(), ws, n, stream)
+            st = B.mcn_conv_forward(d, x.data_ptr(), self.w.data_ptr(), self.b.data_ptr(), y.data_ptr(), ws, n, stream)
         elif op == 1:
-            st = B.mcn_conv_backward_data(d, self.w.data_ptr(), self.p.data_ptr(), self.dx.data_ptr(), ws, n, stream)
+            st = B.mcn_conv_backward_data(d, self.w.data_ptr(), p.data_ptr(), dx.data_ptr(), ws, n, stream)
         elif op == 2:
-            st = B.mcn_conv_backward_filter(d, self.x.data_ptr(), self.p.data_ptr(), self.dw.data_ptr(), ws, n, stream)
+            st = B.mcn_conv_backward_filter(d, x.data_ptr(), p.data_ptr(), self.dw.data_ptr(), ws, n, stream)
         else:
-            st = B.mcn_conv_backward_bias(d, self.p.data_ptr(), self.db.data_ptr(), ws, n, stream)
+            st = B.mcn_conv_backward_bias(d, p.data_ptr(), self.db.data_ptr(), ws, n, stream)
         if st:
             raise B.McnError(st, OPS[op])
 
@@ -119,6 +131,9 @@ def main():
     ap.add_argument("--workload", default="vgg3x3", help="vgg3x3 or comma-separated layer names (e.g. 2b,3b)")
     ap.add_argument("--precision", default="fp32", choices=["fp32", "bf16"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--rotate-mb", type=int, default=0,
+                    help="rotate each layer's activations through copies totalling at least this many MiB "
+                         "(cold-cache timing of the memory-bound layers)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 256 MiB elementwise copy three times, so that a counter run "
                          "(rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE) holds a kernel of known traffic to scale by")
@@ -131,7 +146,7 @@ def main():
     torch.cuda.set_device(0)
     names = WORKLOADS.get(args.workload) or args.workload.split(",")
     prec = B.MCN_PREC_BF16 if args.precision == "bf16" else B.MCN_PREC_FP32
-    layers = [LayerState(n, synth.LAYERS[n], prec) for n in names]
+    layers = [LayerState(n, synth.LAYERS[n], prec, args.rotate_mb) for n in names]
     stream_obj = torch.cuda.current_stream()
     stream = stream_obj.cuda_stream
 
