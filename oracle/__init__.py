@@ -14,9 +14,10 @@ from __future__ import annotations
 
 import ctypes
 import os
-import subprocess
 
 import numpy as np
+
+from ._cbuild import compile_shared
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "conv_oracle.c")
@@ -37,13 +38,10 @@ class _Geom(ctypes.Structure):
 
 
 def build(force: bool = False) -> str:
-    """Compile conv_oracle.c into a shared library beside it (gcc, OpenMP)."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        tmp = _LIB + ".tmp%d" % os.getpid()
-        subprocess.check_call(["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared",
-                               "-Wall", "-Wextra", "-o", tmp, _SRC])
-        os.replace(tmp, _LIB)
-    return _LIB
+    """Compile every C file of the oracle (this block's and the convolution transpose's)."""
+    from . import convt
+    convt.build(force)
+    return compile_shared(_SRC, _LIB, force)
 
 
 _lib = None
