@@ -1,6 +1,7 @@
 /*
- * mcnconv -- the convolution block of the MatConvNet manual (arXiv 1412.4564,
- * function vl_nnconv) for AMD MI355X (gfx950): forward and backward.
+ * mcnconv -- the convolution block (function vl_nnconv) and the convolution
+ * transpose block (vl_nnconvt) of the MatConvNet manual (arXiv 1412.4564) for
+ * AMD MI355X (gfx950): forward and backward.
  *
  * Conventions shared by every entry point
  * ---------------------------------------
@@ -69,7 +70,8 @@ typedef enum mcn_status {
                                     (Sec. 4.1: "otherwise an error is thrown")          */
     MCN_WORKSPACE_TOO_SMALL = 4,
     MCN_UNSUPPORTED = 5,         /* an array has 2^31 elements or more                  */
-    MCN_HIP_ERROR = 6            /* a launch failed; see mcn_last_hip_error()           */
+    MCN_HIP_ERROR = 6,           /* a launch failed; see mcn_last_hip_error()           */
+    MCN_CROP_TOO_LARGE = 7       /* convolution transpose: the crops leave no output     */
 } mcn_status;
 
 enum { MCN_OP_FORWARD = 0, MCN_OP_BACKWARD_DATA = 1, MCN_OP_BACKWARD_FILTER = 2, MCN_OP_BACKWARD_BIAS = 3 };
@@ -105,6 +107,68 @@ int mcn_conv_backward_filter(const mcn_conv_desc *desc, const float *x, const fl
  * dzdb[k] = sum_{i'',j'',n} dzdy[i'',j'',k,n].  Writes K values. */
 int mcn_conv_backward_bias(const mcn_conv_desc *desc, const float *dzdy, float *dzdb,
                            void *ws, size_t ws_bytes, void *stream);
+
+/* ------------------------------------------------------------------------
+ * Convolution transpose (Sec. 4.2; derivation Sec. 6.2; output size Sec. 5.3)
+ * ------------------------------------------------------------------------
+ * Arrays (first index fastest, fp32, device pointers, as above):
+ *     x : H  x W  x D x N
+ *     f : H' x W' x K' x D       filter k is the slice f[:,:,k,:] (Sec. 4.2): the
+ *                                 THIRD index runs over output channels of a
+ *                                 group, the FOURTH over all input channels
+ *     y : H''x W''x (groups*K') x N,    b : groups*K' values
+ * Geometry: up = (S_h, S_w) input upsampling factors, crops = (top, bottom,
+ * left, right) >= 0 removed from the output;
+ *     H'' = S_h (H - 1) + H' - top - bottom,   W'' likewise,
+ * the smallest size whose convolution (filter H' x W', stride = up, pads =
+ * crops) has size H x W.  MCN_CROP_TOO_LARGE if H'' < 1 or W'' < 1.
+ * Groups (the manual is silent; this is the transpose of the grouped
+ * convolution of Sec. 4.1 run from y's shape to x's): `groups` must divide D;
+ * input channels m*D/groups .. (m+1)*D/groups - 1 feed output channels
+ * m*K' .. (m+1)*K' - 1.
+ * Workspace, stream, results-are-written and error rules are those of the
+ * convolution block; `op` is the same MCN_OP_* enumeration. */
+typedef struct mcn_convt_desc {
+    int32_t H, W, D, N;          /* x : H x W x D x N                                  */
+    int32_t Hf, Wf, Kf, groups;  /* f : H' x W' x K' x D;  y has groups*K' channels    */
+    int32_t up_h, up_w;          /* S_h, S_w >= 1                                      */
+    int32_t crop_top, crop_bottom, crop_left, crop_right;
+    int32_t precision;           /* MCN_PREC_*                                         */
+} mcn_convt_desc;
+
+/* Sec. 4.2 / Sec. 5.3: writes H'' and W''.  Validates the whole descriptor;
+ * Ho / Wo may be NULL.  Host only. */
+int mcn_convt_output_size(const mcn_convt_desc *desc, int32_t *Ho, int32_t *Wo);
+
+/* Bytes of scratch that operation `op` needs for this descriptor.  Host only. */
+int mcn_convt_workspace_size(const mcn_convt_desc *desc, int op, size_t *bytes);
+
+/* Sec. 4.2: vec y = M^T vec x (+ b), M being the matrix of the convolution
+ * block that maps y's shape to x's shape with bank f, stride = up, pads =
+ * crops.  Sample by sample (Sec. 6.2 in two dimensions, 1-based):
+ *   y[i'',j'',m*K'+k,n] = b[m*K'+k] + sum_{i,j,d in group m}
+ *        f[i''-S_h(i-1)+top, j''-S_w(j-1)+left, k, d] * x[i,j,d,n]
+ * with f read as zero outside its support.  b == NULL means no bias.
+ * Writes all of y. */
+int mcn_convt_forward(const mcn_convt_desc *desc, const float *x, const float *f, const float *b,
+                      float *y, void *ws, size_t ws_bytes, void *stream);
+
+/* dzdx = d<dzdy, y>/dx = M dzdy: the convolution of dzdy with the bank f
+ * (Sec. 4.2: the block is the transpose of convolution).  Writes all of dzdx. */
+int mcn_convt_backward_data(const mcn_convt_desc *desc, const float *f, const float *dzdy,
+                            float *dzdx, void *ws, size_t ws_bytes, void *stream);
+
+/* dzdf = d<dzdy, y>/df, summed over the batch (Sec. 2.3.2 eq. (projected)
+ * applied to the sum above).  Writes all of dzdf. */
+int mcn_convt_backward_filter(const mcn_convt_desc *desc, const float *x, const float *dzdy,
+                              float *dzdf, void *ws, size_t ws_bytes, void *stream);
+
+/* dzdb[c] = sum_{i'',j'',n} dzdy[i'',j'',c,n].  Writes groups*K' values. */
+int mcn_convt_backward_bias(const mcn_convt_desc *desc, const float *dzdy, float *dzdb,
+                            void *ws, size_t ws_bytes, void *stream);
+
+/* Name of the kernel family the dispatcher picks; NULL on a bad descriptor. */
+const char *mcn_convt_kernel_name(const mcn_convt_desc *desc, int op);
 
 /* Static description of a status code. */
 const char *mcn_status_string(int status);

@@ -7,6 +7,8 @@ built, importing this module's functions raises.
 Tensor convention: the manual's H x W x D x N arrays are first-index-fastest,
 which is the memory order of a contiguous torch tensor of shape (N, D, W, H).
 So x is (N,D,W,H), w is (K,Df,Wf,Hf), y and dzdy are (N,K,Wo,Ho), b is (K,).
+For the convolution transpose the filter bank H' x W' x K' x D is (D,Kf,Wf,Hf) and y has
+groups*Kf channels.
 """
 from __future__ import annotations
 
@@ -17,7 +19,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libmcnconv.so")
 
 MCN_OK, MCN_BAD_ARG, MCN_BAD_GROUPS, MCN_FILTER_TOO_LARGE = 0, 1, 2, 3
-MCN_WORKSPACE_TOO_SMALL, MCN_UNSUPPORTED, MCN_HIP_ERROR = 4, 5, 6
+MCN_WORKSPACE_TOO_SMALL, MCN_UNSUPPORTED, MCN_HIP_ERROR, MCN_CROP_TOO_LARGE = 4, 5, 6, 7
 MCN_OP_FORWARD, MCN_OP_BACKWARD_DATA, MCN_OP_BACKWARD_FILTER, MCN_OP_BACKWARD_BIAS = 0, 1, 2, 3
 MCN_PREC_FP32, MCN_PREC_BF16 = 0, 1
 
@@ -25,6 +27,8 @@ EXPORTS = (
     "mcn_conv_output_size", "mcn_conv_workspace_size", "mcn_conv_forward", "mcn_conv_backward_data",
     "mcn_conv_backward_filter", "mcn_conv_backward_bias", "mcn_status_string", "mcn_last_hip_error",
     "mcn_conv_kernel_name",
+    "mcn_convt_output_size", "mcn_convt_workspace_size", "mcn_convt_forward", "mcn_convt_backward_data",
+    "mcn_convt_backward_filter", "mcn_convt_backward_bias", "mcn_convt_kernel_name",
 )
 
 
@@ -32,6 +36,12 @@ class mcn_conv_desc(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in (
         "H", "W", "D", "N", "Hf", "Wf", "Df", "K", "stride_h", "stride_w",
         "pad_top", "pad_bottom", "pad_left", "pad_right", "precision")]
+
+
+class mcn_convt_desc(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in (
+        "H", "W", "D", "N", "Hf", "Wf", "Kf", "groups", "up_h", "up_w",
+        "crop_top", "crop_bottom", "crop_left", "crop_right", "precision")]
 
 
 class McnError(RuntimeError):
@@ -70,8 +80,19 @@ def lib():
         L.mcn_last_hip_error.restype = ctypes.c_int
         L.mcn_conv_kernel_name.argtypes = [D, ctypes.c_int]
         L.mcn_conv_kernel_name.restype = ctypes.c_char_p
+        T = ctypes.POINTER(mcn_convt_desc)
+        L.mcn_convt_output_size.argtypes = [T, I32P, I32P]
+        L.mcn_convt_workspace_size.argtypes = [T, ctypes.c_int, ctypes.POINTER(SZ)]
+        L.mcn_convt_forward.argtypes = [T, P, P, P, P, P, SZ, P]
+        L.mcn_convt_backward_data.argtypes = [T, P, P, P, P, SZ, P]
+        L.mcn_convt_backward_filter.argtypes = [T, P, P, P, P, SZ, P]
+        L.mcn_convt_backward_bias.argtypes = [T, P, P, P, SZ, P]
+        L.mcn_convt_kernel_name.argtypes = [T, ctypes.c_int]
+        L.mcn_convt_kernel_name.restype = ctypes.c_char_p
         for f in ("mcn_conv_output_size", "mcn_conv_workspace_size", "mcn_conv_forward",
-                  "mcn_conv_backward_data", "mcn_conv_backward_filter", "mcn_conv_backward_bias"):
+                  "mcn_conv_backward_data", "mcn_conv_backward_filter", "mcn_conv_backward_bias",
+                  "mcn_convt_output_size", "mcn_convt_workspace_size", "mcn_convt_forward",
+                  "mcn_convt_backward_data", "mcn_convt_backward_filter", "mcn_convt_backward_bias"):
             getattr(L, f).restype = ctypes.c_int
         _lib = L
     return _lib
@@ -121,6 +142,53 @@ def mcn_conv_backward_filter(desc, x, dzdy, dzdw, ws, ws_bytes, stream):
 
 def mcn_conv_backward_bias(desc, dzdy, dzdb, ws, ws_bytes, stream):
     return lib().mcn_conv_backward_bias(ctypes.byref(desc), dzdy, dzdb, ws, ws_bytes, stream)
+
+
+def make_convt_desc(xshape, fshape, upsample=(1, 1), crop=(0, 0, 0, 0), groups=1, precision=MCN_PREC_FP32):
+    """Descriptor from tensor shapes x (N,D,W,H), f (D,Kf,Wf,Hf), upsample (Sh,Sw), crop (t,b,l,r)."""
+    N, D, W, H = (int(v) for v in xshape)
+    Df, Kf, Wf, Hf = (int(v) for v in fshape)
+    if Df != D:
+        raise ValueError("the filter bank's last axis (%d) must equal the input depth (%d)" % (Df, D))
+    return mcn_convt_desc(H, W, D, N, Hf, Wf, Kf, int(groups), int(upsample[0]), int(upsample[1]),
+                          int(crop[0]), int(crop[1]), int(crop[2]), int(crop[3]), int(precision))
+
+
+def mcn_convt_output_size(desc):
+    ho, wo = ctypes.c_int32(0), ctypes.c_int32(0)
+    st = lib().mcn_convt_output_size(ctypes.byref(desc), ctypes.byref(ho), ctypes.byref(wo))
+    if st:
+        raise McnError(st, "mcn_convt_output_size")
+    return ho.value, wo.value
+
+
+def mcn_convt_workspace_size(desc, op):
+    n = ctypes.c_size_t(0)
+    st = lib().mcn_convt_workspace_size(ctypes.byref(desc), int(op), ctypes.byref(n))
+    if st:
+        raise McnError(st, "mcn_convt_workspace_size")
+    return int(n.value)
+
+
+def mcn_convt_kernel_name(desc, op):
+    s = lib().mcn_convt_kernel_name(ctypes.byref(desc), int(op))
+    return None if s is None else s.decode()
+
+
+def mcn_convt_forward(desc, x, f, b, y, ws, ws_bytes, stream):
+    return lib().mcn_convt_forward(ctypes.byref(desc), x, f, b, y, ws, ws_bytes, stream)
+
+
+def mcn_convt_backward_data(desc, f, dzdy, dzdx, ws, ws_bytes, stream):
+    return lib().mcn_convt_backward_data(ctypes.byref(desc), f, dzdy, dzdx, ws, ws_bytes, stream)
+
+
+def mcn_convt_backward_filter(desc, x, dzdy, dzdf, ws, ws_bytes, stream):
+    return lib().mcn_convt_backward_filter(ctypes.byref(desc), x, dzdy, dzdf, ws, ws_bytes, stream)
+
+
+def mcn_convt_backward_bias(desc, dzdy, dzdb, ws, ws_bytes, stream):
+    return lib().mcn_convt_backward_bias(ctypes.byref(desc), dzdy, dzdb, ws, ws_bytes, stream)
 
 
 # ---- tensor-level helpers: allocate outputs / workspace with torch, pass pointers ----
@@ -214,4 +282,71 @@ def conv_backward_bias(xshape, wshape, dzdy, stride=(1, 1), pad=(0, 0, 0, 0), ou
     st = mcn_conv_backward_bias(desc, dzdy.data_ptr(), dzdb.data_ptr(), wsp, wsn, _stream())
     if st:
         raise McnError(st, "mcn_conv_backward_bias")
+    return dzdb
+
+
+# ---- convolution transpose ----
+def _convt_shapes(xshape, fshape, upsample, crop, groups, precision=MCN_PREC_FP32):
+    desc = make_convt_desc(xshape, fshape, upsample, crop, groups, precision)
+    ho, wo = mcn_convt_output_size(desc)
+    return desc, (int(xshape[0]), int(groups) * int(fshape[1]), wo, ho)
+
+
+def convt_forward(x, f, b=None, upsample=(1, 1), crop=(0, 0, 0, 0), groups=1, precision=MCN_PREC_FP32, out=None,
+                  workspace=None):
+    import torch
+    _check(x, None, "x"); _check(f, None, "f")
+    desc, ysh = _convt_shapes(x.shape, f.shape, upsample, crop, groups, precision)
+    if b is not None:
+        _check(b, (ysh[1],), "b")
+    y = out if out is not None else torch.empty(ysh, dtype=torch.float32, device=x.device)
+    _check(y, ysh, "out")
+    wsp, wsn = (workspace or _default_ws).get(mcn_convt_workspace_size(desc, MCN_OP_FORWARD), x.device)
+    st = mcn_convt_forward(desc, x.data_ptr(), f.data_ptr(), None if b is None else b.data_ptr(), y.data_ptr(),
+                           wsp, wsn, _stream())
+    if st:
+        raise McnError(st, "mcn_convt_forward")
+    return y
+
+
+def convt_backward_data(xshape, f, dzdy, upsample=(1, 1), crop=(0, 0, 0, 0), groups=1, precision=MCN_PREC_FP32,
+                        out=None, workspace=None):
+    import torch
+    _check(f, None, "f")
+    desc, ysh = _convt_shapes(xshape, f.shape, upsample, crop, groups, precision)
+    _check(dzdy, ysh, "dzdy")
+    dzdx = out if out is not None else torch.empty(tuple(xshape), dtype=torch.float32, device=f.device)
+    _check(dzdx, tuple(xshape), "out")
+    wsp, wsn = (workspace or _default_ws).get(mcn_convt_workspace_size(desc, MCN_OP_BACKWARD_DATA), f.device)
+    st = mcn_convt_backward_data(desc, f.data_ptr(), dzdy.data_ptr(), dzdx.data_ptr(), wsp, wsn, _stream())
+    if st:
+        raise McnError(st, "mcn_convt_backward_data")
+    return dzdx
+
+
+def convt_backward_filter(x, fshape, dzdy, upsample=(1, 1), crop=(0, 0, 0, 0), groups=1, precision=MCN_PREC_FP32,
+                          out=None, workspace=None):
+    import torch
+    _check(x, None, "x")
+    desc, ysh = _convt_shapes(x.shape, fshape, upsample, crop, groups, precision)
+    _check(dzdy, ysh, "dzdy")
+    dzdf = out if out is not None else torch.empty(tuple(fshape), dtype=torch.float32, device=x.device)
+    _check(dzdf, tuple(fshape), "out")
+    wsp, wsn = (workspace or _default_ws).get(mcn_convt_workspace_size(desc, MCN_OP_BACKWARD_FILTER), x.device)
+    st = mcn_convt_backward_filter(desc, x.data_ptr(), dzdy.data_ptr(), dzdf.data_ptr(), wsp, wsn, _stream())
+    if st:
+        raise McnError(st, "mcn_convt_backward_filter")
+    return dzdf
+
+
+def convt_backward_bias(xshape, fshape, dzdy, upsample=(1, 1), crop=(0, 0, 0, 0), groups=1, out=None, workspace=None):
+    import torch
+    desc, ysh = _convt_shapes(xshape, fshape, upsample, crop, groups)
+    _check(dzdy, ysh, "dzdy")
+    dzdb = out if out is not None else torch.empty((ysh[1],), dtype=torch.float32, device=dzdy.device)
+    _check(dzdb, (ysh[1],), "out")
+    wsp, wsn = (workspace or _default_ws).get(mcn_convt_workspace_size(desc, MCN_OP_BACKWARD_BIAS), dzdy.device)
+    st = mcn_convt_backward_bias(desc, dzdy.data_ptr(), dzdb.data_ptr(), wsp, wsn, _stream())
+    if st:
+        raise McnError(st, "mcn_convt_backward_bias")
     return dzdb

@@ -84,6 +84,21 @@ __global__ __launch_bounds__(256) void zero_fill_kernel(float *__restrict__ out,
     for (long long e = lo + threadIdx.x; e < hi; e += 256) out[e] = 0.f;
 }
 
+// out[p + plane*(c + C*n)] = bias[c]  (start value of an output whose contributions are written,
+// or left out, per stride phase: the convolution transpose with a bias)
+__global__ __launch_bounds__(256) void bias_fill_kernel(float *__restrict__ out, const float *__restrict__ bias,
+                                                        int plane, int C, int total) {
+    const long long lo = (long long)blockIdx.x * 1024, hi = lo + 1024 < total ? lo + 1024 : total;
+    for (long long e = lo + threadIdx.x; e < hi; e += 256) out[e] = bias[(e / plane) % C];
+}
+
+// out[p + plane*(c + C*n)] += bias[c]
+__global__ __launch_bounds__(256) void bias_add_kernel(float *__restrict__ out, const float *__restrict__ bias,
+                                                       int plane, int C, int total) {
+    const long long lo = (long long)blockIdx.x * 1024, hi = lo + 1024 < total ? lo + 1024 : total;
+    for (long long e = lo + threadIdx.x; e < hi; e += 256) out[e] += bias[(e / plane) % C];
+}
+
 __device__ inline float wave_sum(float v) {
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, 64);

@@ -37,14 +37,14 @@ struct BiasPlan {
     size_t ws_floats;
 };
 
-BiasPlan plan_bias(const Geom &g) {
+// dzdy is HoWo x K x N (plane, channels, images)
+BiasPlan plan_bias(int64_t HoWo, int K, int N) {
     BiasPlan p;
-    const int64_t HoWo = (int64_t)g.Ho * g.Wo;
     p.rows = HoWo < 64;
     if (p.rows) {
-        const int64_t row = HoWo * g.K;
+        const int64_t row = HoWo * K;
         int64_t want = 1024 / ((row + 255) / 256);     // aim for ~1024 blocks in all
-        if (want > g.N) want = g.N;
+        if (want > N) want = N;
         if (want < 1) want = 1;
         p.chunks = 0;
         p.S = (int)want;
@@ -52,15 +52,16 @@ BiasPlan plan_bias(const Geom &g) {
         return p;
     }
     p.chunks = (int)((HoWo + BIAS_CHUNK - 1) / BIAS_CHUNK);
-    const int64_t units = (int64_t)g.N * p.chunks;
-    int64_t want = (2048 + g.K - 1) / g.K;   // aim for ~2048 blocks in all
+    const int64_t units = (int64_t)N * p.chunks;
+    int64_t want = (2048 + K - 1) / K;   // aim for ~2048 blocks in all
     if (want > units) want = units;
     if (want < 1) want = 1;
     if (want > 65535) want = 65535;
     p.S = (int)want;
-    p.ws_floats = (size_t)g.K * p.S;
+    p.ws_floats = (size_t)K * p.S;
     return p;
 }
+BiasPlan plan_bias(const Geom &g) { return plan_bias((int64_t)g.Ho * g.Wo, g.K, g.N); }
 
 // ---- implicit-GEMM dispatch -------------------------------------------------
 bool igemm_enabled() {
@@ -248,6 +249,120 @@ size_t workspace_bytes(const mcn_conv_desc *d, const Geom &g, int op) {
     }
 }
 
+// ---- the four passes on a validated geometry ---------------------------------------------
+
+int run_forward(const mcn_conv_desc *desc, const Geom &g, const float *x, const float *w, const float *b, float *y,
+                void *ws, size_t ws_bytes, hipStream_t s) {
+    if (!x || !w || !y) return MCN_BAD_ARG;
+    const size_t need = workspace_bytes(desc, g, MCN_OP_FORWARD);
+    if (ws_bytes < need || (!ws && need)) return MCN_WORKSPACE_TOO_SMALL;
+    const PlanEntry *pe = plans_for(desc, g);
+    if (pe->fc) return launch_wgrad(pe->fc_fwd, w, x, b, y, ws, s);
+    if (pe->fwd_ok) return launch_igemm(pe->fwd, x, w, b, y, ws, s);
+    const int total = (int)numel_y(g);
+    hipLaunchKernelGGL(direct_forward_kernel, dim3(cdiv(total, 256)), dim3(256), 0, s, g, x, w, b, y, total);
+    return check_launch();
+}
+
+// dzdx = (input derivative) + bias[channel of x]; the bias (may be NULL) is what turns this pass
+// into the forward pass of the convolution transpose.
+int run_backward_data(const mcn_conv_desc *desc, const Geom &g, const float *w, const float *dzdy, const float *bias,
+                      float *dzdx, void *ws, size_t ws_bytes, hipStream_t s) {
+    if (!w || !dzdy || !dzdx) return MCN_BAD_ARG;
+    const size_t need = workspace_bytes(desc, g, MCN_OP_BACKWARD_DATA);
+    if (ws_bytes < need || (!ws && need)) return MCN_WORKSPACE_TOO_SMALL;
+    const PlanEntry *pe = plans_for(desc, g);
+    const int total = (int)numel_x(g);
+    int st;
+    if (pe->bwd_ok && !pe->fc) {
+        if (pe->bwd_fill) {
+            if (bias)
+                hipLaunchKernelGGL(bias_fill_kernel, dim3(cdiv(total, 1024)), dim3(256), 0, s, dzdx, bias, g.H * g.W, g.D, total);
+            else
+                hipLaunchKernelGGL(zero_fill_kernel, dim3(cdiv(total, 1024)), dim3(256), 0, s, dzdx, total);
+            st = check_launch();
+            if (st) return st;
+        }
+        for (int i = 0; i < pe->n_bwd; ++i) {
+            st = launch_igemm(pe->bwd[i], dzdy, w, bias, dzdx, ws, s);
+            if (st) return st;
+        }
+        return MCN_OK;
+    }
+    if (pe->fc) {
+        st = launch_igemm(pe->fc_bwd, w, dzdy, nullptr, dzdx, ws, s);
+    } else {
+        hipLaunchKernelGGL(direct_backward_data_kernel, dim3(cdiv(total, 256)), dim3(256), 0, s, g, w, dzdy, dzdx, total);
+        st = check_launch();
+    }
+    if (st || !bias) return st;
+    hipLaunchKernelGGL(bias_add_kernel, dim3(cdiv(total, 1024)), dim3(256), 0, s, dzdx, bias, g.H * g.W, g.D, total);
+    return check_launch();
+}
+
+int run_backward_filter(const mcn_conv_desc *desc, const Geom &g, const float *x, const float *dzdy, float *dzdw,
+                        void *ws, size_t ws_bytes, hipStream_t s) {
+    if (!x || !dzdy || !dzdw) return MCN_BAD_ARG;
+    const size_t need = workspace_bytes(desc, g, MCN_OP_BACKWARD_FILTER);
+    if (ws_bytes < need || (!ws && need)) return MCN_WORKSPACE_TOO_SMALL;
+    const PlanEntry *pe = plans_for(desc, g);
+    if (pe->fc) return launch_igemm(pe->fc_wg, x, dzdy, nullptr, dzdw, ws, s);
+    if (pe->wg_ok) return launch_wgrad(pe->wg, x, dzdy, nullptr, dzdw, ws, s);
+    const int total = (int)numel_w(g);
+    hipLaunchKernelGGL(direct_backward_filter_kernel, dim3(cdiv(total, 4)), dim3(256), 0, s, g, x, dzdy, dzdw, total);
+    return check_launch();
+}
+
+// dzdb[k] = sum of the plane x K x N array dzdy over its plane and its images
+int run_backward_bias(int plane, int K, int N, const float *dzdy, float *dzdb, void *ws, size_t ws_bytes,
+                      hipStream_t s) {
+    if (!dzdy || !dzdb) return MCN_BAD_ARG;
+    const BiasPlan p = plan_bias(plane, K, N);
+    const size_t need = p.ws_floats * sizeof(float);
+    if (ws_bytes < need || (!ws && need)) return MCN_WORKSPACE_TOO_SMALL;
+    float *part = (float *)ws;
+    int st;
+    if (p.rows) {
+        const int row = K * plane;
+        hipLaunchKernelGGL(bias_rows_partial_kernel, dim3(cdiv(row, 256), p.S), dim3(256), 0, s, dzdy, part, row, N, p.S);
+        st = check_launch();
+        if (st) return st;
+        hipLaunchKernelGGL(bias_rows_final_kernel, dim3(cdiv(K, 4)), dim3(256), 0, s, part, dzdb, plane, K, p.S);
+        return check_launch();
+    }
+    hipLaunchKernelGGL(bias_partial_kernel, dim3(K, p.S), dim3(256), 0, s, dzdy, part, plane, K, N, p.chunks, p.S);
+    st = check_launch();
+    if (st) return st;
+    hipLaunchKernelGGL(bias_final_kernel, dim3(cdiv(K, 256)), dim3(256), 0, s, part, dzdb, K, p.S);
+    return check_launch();
+}
+
+// Convolution transpose (Sec. 4.2): validate the descriptor and write the "conjugate"
+// convolution, the one that maps an array of y's shape to one of x's shape with the same bank
+// (stride = upsampling, pads = crops).  In the conjugate's terms its input is H'' x W'' x
+// groups*K', its bank has D filters of depth K', and its output is H x W x D.
+int conjugate_convolution(const mcn_convt_desc *t, mcn_conv_desc *c, Geom *g) {
+    if (!t) return MCN_BAD_ARG;
+    if (t->H < 1 || t->W < 1 || t->D < 1 || t->N < 1) return MCN_BAD_ARG;
+    if (t->Hf < 1 || t->Wf < 1 || t->Kf < 1 || t->groups < 1) return MCN_BAD_ARG;
+    if (t->up_h < 1 || t->up_w < 1) return MCN_BAD_ARG;
+    if (t->crop_top < 0 || t->crop_bottom < 0 || t->crop_left < 0 || t->crop_right < 0) return MCN_BAD_ARG;
+    if (t->precision != MCN_PREC_FP32 && t->precision != MCN_PREC_BF16) return MCN_BAD_ARG;
+    if (t->D % t->groups != 0) return MCN_BAD_GROUPS;
+    const int64_t lim = (int64_t)1 << 31;
+    const int64_t Ho = (int64_t)t->up_h * (t->H - 1) + t->Hf - t->crop_top - t->crop_bottom;
+    const int64_t Wo = (int64_t)t->up_w * (t->W - 1) + t->Wf - t->crop_left - t->crop_right;
+    if (Ho < 1 || Wo < 1) return MCN_CROP_TOO_LARGE;
+    if (Ho >= lim || Wo >= lim || (int64_t)t->groups * t->Kf >= lim) return MCN_UNSUPPORTED;
+    memset(c, 0, sizeof(*c));
+    c->H = (int32_t)Ho; c->W = (int32_t)Wo; c->D = t->groups * t->Kf; c->N = t->N;
+    c->Hf = t->Hf; c->Wf = t->Wf; c->Df = t->Kf; c->K = t->D;
+    c->stride_h = t->up_h; c->stride_w = t->up_w;
+    c->pad_top = t->crop_top; c->pad_bottom = t->crop_bottom; c->pad_left = t->crop_left; c->pad_right = t->crop_right;
+    c->precision = t->precision;
+    return make_geom(c, g);
+}
+
 }  // namespace
 
 extern "C" {
@@ -288,16 +403,7 @@ int mcn_conv_forward(const mcn_conv_desc *desc, const float *x, const float *w, 
     Geom g;
     int st = make_geom(desc, &g);
     if (st) return st;
-    if (!x || !w || !y) return MCN_BAD_ARG;
-    const size_t need = workspace_bytes(desc, g, MCN_OP_FORWARD);
-    if (ws_bytes < need || (!ws && need)) return MCN_WORKSPACE_TOO_SMALL;
-    const PlanEntry *pe = plans_for(desc, g);
-    hipStream_t s = (hipStream_t)stream;
-    if (pe->fc) return launch_wgrad(pe->fc_fwd, w, x, b, y, ws, s);
-    if (pe->fwd_ok) return launch_igemm(pe->fwd, x, w, b, y, ws, s);
-    const int total = (int)numel_y(g);
-    hipLaunchKernelGGL(direct_forward_kernel, dim3(cdiv(total, 256)), dim3(256), 0, s, g, x, w, b, y, total);
-    return check_launch();
+    return run_forward(desc, g, x, w, b, y, ws, ws_bytes, (hipStream_t)stream);
 }
 
 int mcn_conv_backward_data(const mcn_conv_desc *desc, const float *w, const float *dzdy, float *dzdx,
@@ -305,28 +411,7 @@ int mcn_conv_backward_data(const mcn_conv_desc *desc, const float *w, const floa
     Geom g;
     int st = make_geom(desc, &g);
     if (st) return st;
-    if (!w || !dzdy || !dzdx) return MCN_BAD_ARG;
-    const size_t need = workspace_bytes(desc, g, MCN_OP_BACKWARD_DATA);
-    if (ws_bytes < need || (!ws && need)) return MCN_WORKSPACE_TOO_SMALL;
-    const PlanEntry *pe = plans_for(desc, g);
-    hipStream_t s = (hipStream_t)stream;
-    if (pe->fc) return launch_igemm(pe->fc_bwd, w, dzdy, nullptr, dzdx, ws, s);
-    if (pe->bwd_ok) {
-        if (pe->bwd_fill) {
-            const int total = (int)numel_x(g);
-            hipLaunchKernelGGL(zero_fill_kernel, dim3(cdiv(total, 1024)), dim3(256), 0, s, dzdx, total);
-            st = check_launch();
-            if (st) return st;
-        }
-        for (int i = 0; i < pe->n_bwd; ++i) {
-            st = launch_igemm(pe->bwd[i], dzdy, w, nullptr, dzdx, ws, s);
-            if (st) return st;
-        }
-        return MCN_OK;
-    }
-    const int total = (int)numel_x(g);
-    hipLaunchKernelGGL(direct_backward_data_kernel, dim3(cdiv(total, 256)), dim3(256), 0, s, g, w, dzdy, dzdx, total);
-    return check_launch();
+    return run_backward_data(desc, g, w, dzdy, nullptr, dzdx, ws, ws_bytes, (hipStream_t)stream);
 }
 
 int mcn_conv_backward_filter(const mcn_conv_desc *desc, const float *x, const float *dzdy, float *dzdw,
@@ -334,16 +419,7 @@ int mcn_conv_backward_filter(const mcn_conv_desc *desc, const float *x, const fl
     Geom g;
     int st = make_geom(desc, &g);
     if (st) return st;
-    if (!x || !dzdy || !dzdw) return MCN_BAD_ARG;
-    const size_t need = workspace_bytes(desc, g, MCN_OP_BACKWARD_FILTER);
-    if (ws_bytes < need || (!ws && need)) return MCN_WORKSPACE_TOO_SMALL;
-    const PlanEntry *pe = plans_for(desc, g);
-    hipStream_t s = (hipStream_t)stream;
-    if (pe->fc) return launch_igemm(pe->fc_wg, x, dzdy, nullptr, dzdw, ws, s);
-    if (pe->wg_ok) return launch_wgrad(pe->wg, x, dzdy, nullptr, dzdw, ws, s);
-    const int total = (int)numel_w(g);
-    hipLaunchKernelGGL(direct_backward_filter_kernel, dim3(cdiv(total, 4)), dim3(256), 0, s, g, x, dzdy, dzdw, total);
-    return check_launch();
+    return run_backward_filter(desc, g, x, dzdy, dzdw, ws, ws_bytes, (hipStream_t)stream);
 }
 
 int mcn_conv_backward_bias(const mcn_conv_desc *desc, const float *dzdy, float *dzdb, void *ws, size_t ws_bytes,
@@ -351,26 +427,87 @@ int mcn_conv_backward_bias(const mcn_conv_desc *desc, const float *dzdy, float *
     Geom g;
     int st = make_geom(desc, &g);
     if (st) return st;
-    if (!dzdy || !dzdb) return MCN_BAD_ARG;
-    const size_t need = workspace_bytes(desc, g, MCN_OP_BACKWARD_BIAS);
-    if (ws_bytes < need || (!ws && need)) return MCN_WORKSPACE_TOO_SMALL;
-    hipStream_t s = (hipStream_t)stream;
-    BiasPlan p = plan_bias(g);
-    float *part = (float *)ws;
-    if (p.rows) {
-        const int row = g.K * g.Ho * g.Wo;
-        hipLaunchKernelGGL(bias_rows_partial_kernel, dim3(cdiv(row, 256), p.S), dim3(256), 0, s, dzdy, part, row, g.N, p.S);
-        st = check_launch();
-        if (st) return st;
-        hipLaunchKernelGGL(bias_rows_final_kernel, dim3(cdiv(g.K, 4)), dim3(256), 0, s, part, dzdb, g.Ho * g.Wo, g.K, p.S);
-        return check_launch();
-    }
-    hipLaunchKernelGGL(bias_partial_kernel, dim3(g.K, p.S), dim3(256), 0, s, dzdy, part, g.Ho * g.Wo, g.K, g.N,
-                       p.chunks, p.S);
-    st = check_launch();
+    return run_backward_bias(g.Ho * g.Wo, g.K, g.N, dzdy, dzdb, ws, ws_bytes, (hipStream_t)stream);
+}
+
+// ---- convolution transpose: the same kernels with the roles of the arrays exchanged ----------
+
+int mcn_convt_output_size(const mcn_convt_desc *desc, int32_t *Ho, int32_t *Wo) {
+    mcn_conv_desc c;
+    Geom g;
+    int st = conjugate_convolution(desc, &c, &g);
     if (st) return st;
-    hipLaunchKernelGGL(bias_final_kernel, dim3(cdiv(g.K, 256)), dim3(256), 0, s, part, dzdb, g.K, p.S);
-    return check_launch();
+    if (Ho) *Ho = c.H;
+    if (Wo) *Wo = c.W;
+    return MCN_OK;
+}
+
+int mcn_convt_workspace_size(const mcn_convt_desc *desc, int op, size_t *bytes) {
+    mcn_conv_desc c;
+    Geom g;
+    int st = conjugate_convolution(desc, &c, &g);
+    if (st) return st;
+    if (!bytes || op < MCN_OP_FORWARD || op > MCN_OP_BACKWARD_BIAS) return MCN_BAD_ARG;
+    switch (op) {
+        case MCN_OP_FORWARD: *bytes = workspace_bytes(&c, g, MCN_OP_BACKWARD_DATA); break;
+        case MCN_OP_BACKWARD_DATA: *bytes = workspace_bytes(&c, g, MCN_OP_FORWARD); break;
+        case MCN_OP_BACKWARD_FILTER: *bytes = workspace_bytes(&c, g, MCN_OP_BACKWARD_FILTER); break;
+        default: *bytes = plan_bias((int64_t)g.H * g.W, g.D, g.N).ws_floats * sizeof(float); break;
+    }
+    return MCN_OK;
+}
+
+const char *mcn_convt_kernel_name(const mcn_convt_desc *desc, int op) {
+    mcn_conv_desc c;
+    Geom g;
+    if (conjugate_convolution(desc, &c, &g)) return NULL;
+    switch (op) {
+        case MCN_OP_FORWARD: return mcn_conv_kernel_name(&c, MCN_OP_BACKWARD_DATA);
+        case MCN_OP_BACKWARD_DATA: return mcn_conv_kernel_name(&c, MCN_OP_FORWARD);
+        case MCN_OP_BACKWARD_FILTER: return mcn_conv_kernel_name(&c, MCN_OP_BACKWARD_FILTER);
+        case MCN_OP_BACKWARD_BIAS: return plan_bias((int64_t)g.H * g.W, g.D, g.N).rows ? "reduce_rows" : "reduce2";
+        default: return NULL;
+    }
+}
+
+int mcn_convt_forward(const mcn_convt_desc *desc, const float *x, const float *f, const float *b, float *y,
+                      void *ws, size_t ws_bytes, void *stream) {
+    mcn_conv_desc c;
+    Geom g;
+    int st = conjugate_convolution(desc, &c, &g);
+    if (st) return st;
+    // y = M^T x + b: the input derivative of the conjugate convolution, taken at "dzdy" = x
+    return run_backward_data(&c, g, f, x, b, y, ws, ws_bytes, (hipStream_t)stream);
+}
+
+int mcn_convt_backward_data(const mcn_convt_desc *desc, const float *f, const float *dzdy, float *dzdx,
+                            void *ws, size_t ws_bytes, void *stream) {
+    mcn_conv_desc c;
+    Geom g;
+    int st = conjugate_convolution(desc, &c, &g);
+    if (st) return st;
+    // dzdx = M dzdy: the conjugate convolution itself, without a bias
+    return run_forward(&c, g, dzdy, f, nullptr, dzdx, ws, ws_bytes, (hipStream_t)stream);
+}
+
+int mcn_convt_backward_filter(const mcn_convt_desc *desc, const float *x, const float *dzdy, float *dzdf,
+                              void *ws, size_t ws_bytes, void *stream) {
+    mcn_conv_desc c;
+    Geom g;
+    int st = conjugate_convolution(desc, &c, &g);
+    if (st) return st;
+    // <dzdy, M^T x> = <M dzdy, x>: the filter derivative of the conjugate convolution whose input is
+    // dzdy and whose output derivative is x
+    return run_backward_filter(&c, g, dzdy, x, dzdf, ws, ws_bytes, (hipStream_t)stream);
+}
+
+int mcn_convt_backward_bias(const mcn_convt_desc *desc, const float *dzdy, float *dzdb, void *ws, size_t ws_bytes,
+                            void *stream) {
+    mcn_conv_desc c;
+    Geom g;
+    int st = conjugate_convolution(desc, &c, &g);
+    if (st) return st;
+    return run_backward_bias(g.H * g.W, g.D, g.N, dzdy, dzdb, ws, ws_bytes, (hipStream_t)stream);
 }
 
 const char *mcn_status_string(int status) {
@@ -382,6 +519,7 @@ const char *mcn_status_string(int status) {
         case MCN_WORKSPACE_TOO_SMALL: return "workspace too small";
         case MCN_UNSUPPORTED: return "array too large for 32-bit element offsets";
         case MCN_HIP_ERROR: return "HIP launch error";
+        case MCN_CROP_TOO_LARGE: return "crops leave no output";
         default: return "unknown status";
     }
 }

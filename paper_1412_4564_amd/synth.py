@@ -90,3 +90,55 @@ def make_dzdy(layer, Ho, Wo, seed=0):
     """dzdy ~ N(0,1) of shape (N, K, Wo, Ho); Ho, Wo come from the caller."""
     return torch.randn((layer["N"], layer["K"], int(Wo), int(Ho)), generator=_gen(layer, 3, seed),
                        dtype=torch.float32)
+
+
+# ---- convolution transpose (Sec. 4.2) ------------------------------------------------------
+# The manual names two uses of the block: decoders / deconvolutional networks that run a
+# convolution backwards, and learnable interpolation.  The shapes below are of those two kinds
+# (a stride-1 "deconvnet" mirror of a VGG 3x3 layer, a 2x upsampling decoder layer, 2x and 32x
+# per-class interpolation of score maps with one group per class, and one irregular layer).
+# Layer fields: x is H x W x D x N, f is H' x W' x K' x D, `groups` groups, y has groups*K'
+# channels.  Same distributions as above; f ~ N(0, 2/(H'W'D/groups)).
+def _tlayer(x, f, groups=1, up=(1, 1), crop=(0, 0, 0, 0), index=0):
+    H, W, D, N = x
+    Hf, Wf, Kf, Df = f
+    assert Df == D
+    return dict(H=H, W=W, D=D, N=N, Hf=Hf, Wf=Wf, Kf=Kf, groups=groups,
+                up=tuple(up), crop=tuple(crop), config=6, index=index)
+
+
+CONVT_LAYERS = OrderedDict([
+    ("t1", _tlayer((56, 56, 256, 32),  (3, 3, 256, 256),   1,  (1, 1),   (1, 1, 1, 1),     0)),
+    ("t2", _tlayer((28, 28, 256, 32),  (4, 4, 128, 256),   1,  (2, 2),   (1, 1, 1, 1),     1)),
+    ("t3", _tlayer((34, 34, 21, 8),    (4, 4, 21, 21),     1,  (2, 2),   (0, 0, 0, 0),     2)),
+    ("t4", _tlayer((16, 16, 21, 4),    (64, 64, 1, 21),    21, (32, 32), (16, 16, 16, 16), 3)),
+    ("t5", _tlayer((7, 5, 6, 3),       (5, 3, 4, 6),       2,  (3, 2),   (2, 0, 1, 3),     4)),
+])
+
+
+def tx_shape(layer):
+    return (layer["N"], layer["D"], layer["W"], layer["H"])
+
+
+def tf_shape(layer):
+    return (layer["D"], layer["Kf"], layer["Wf"], layer["Hf"])
+
+
+def make_tx(layer, seed=0):
+    return torch.randn(tx_shape(layer), generator=_gen(layer, 0, seed), dtype=torch.float32)
+
+
+def make_tf(layer, seed=0):
+    fan = layer["Hf"] * layer["Wf"] * (layer["D"] // layer["groups"])
+    f = torch.randn(tf_shape(layer), generator=_gen(layer, 1, seed), dtype=torch.float32)
+    return f * float((2.0 / fan) ** 0.5)
+
+
+def make_tb(layer, seed=0):
+    return torch.randn((layer["groups"] * layer["Kf"],), generator=_gen(layer, 2, seed), dtype=torch.float32) * 0.1
+
+
+def make_tdzdy(layer, Ho, Wo, seed=0):
+    """dzdy ~ N(0,1) of shape (N, groups*K', Wo, Ho); Ho, Wo come from the caller."""
+    return torch.randn((layer["N"], layer["groups"] * layer["Kf"], int(Wo), int(Ho)),
+                       generator=_gen(layer, 3, seed), dtype=torch.float32)

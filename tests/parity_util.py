@@ -117,3 +117,68 @@ def assert_errors(errs, precision=B.MCN_PREC_FP32, label=""):
     assert errs["backward_data"] <= tol_b, (label, errs)
     assert errs["backward_filter"] <= tol_b, (label, errs)
     assert errs["backward_bias"] <= TOL_BWD, (label, errs)
+
+
+# ---- convolution transpose ----
+from oracle import convt as oracle_t  # noqa: E402
+
+
+def _targs(L):
+    return L["up"], L["crop"], L["groups"]
+
+
+def run_convt_full(L, with_bias=True, seed=0):
+    """All four operations of the transpose block on layer L, every element compared."""
+    up, crop, G = _targs(L)
+    x, f, b = synth.make_tx(L, seed), synth.make_tf(L, seed), synth.make_tb(L, seed)
+    ho, wo = oracle_t.output_size(x.shape, f.shape, up, crop, G)
+    p = synth.make_tdzdy(L, ho, wo, seed)
+    xd, fd, bd, pd = np64(x), np64(f), np64(b), np64(p)
+    bb = bd if with_bias else None
+    xg, fg, bg, pg = gpu(x), gpu(f), gpu(b), gpu(p)
+    y = B.convt_forward(xg, fg, bg if with_bias else None, up, crop, G)
+    dx = B.convt_backward_data(x.shape, fg, pg, up, crop, G)
+    df = B.convt_backward_filter(xg, f.shape, pg, up, crop, G)
+    db = B.convt_backward_bias(x.shape, f.shape, pg, up, crop, G)
+    torch.cuda.synchronize()
+    assert tuple(y.shape) == (L["N"], G * L["Kf"], wo, ho)
+    out = {}
+    out["forward"] = norm_err(y.cpu().numpy(), oracle_t.forward(xd, fd, bb, up, crop, G),
+                              oracle_t.forward(np.abs(xd), np.abs(fd), None if bb is None else np.abs(bb), up, crop, G))
+    out["backward_data"] = norm_err(dx.cpu().numpy(), oracle_t.backward_data(x.shape, fd, pd, up, crop, G),
+                                    oracle_t.backward_data(x.shape, np.abs(fd), np.abs(pd), up, crop, G))
+    out["backward_filter"] = norm_err(df.cpu().numpy(), oracle_t.backward_filter(xd, f.shape, pd, up, crop, G),
+                                      oracle_t.backward_filter(np.abs(xd), f.shape, np.abs(pd), up, crop, G))
+    out["backward_bias"] = norm_err(db.cpu().numpy(), oracle_t.backward_bias(x.shape, f.shape, pd, up, crop, G),
+                                    oracle_t.backward_bias(x.shape, f.shape, np.abs(pd), up, crop, G))
+    return out
+
+
+def run_convt_sampled(L, n_out=4000, n_filt=96, seed=0):
+    """The transpose block at full size, compared at sampled places (bias derivative: all channels)."""
+    up, crop, G = _targs(L)
+    x, f, b = synth.make_tx(L, seed), synth.make_tf(L, seed), synth.make_tb(L, seed)
+    ho, wo = oracle_t.output_size(x.shape, f.shape, up, crop, G)
+    p = synth.make_tdzdy(L, ho, wo, seed)
+    xg, fg, bg, pg = gpu(x), gpu(f), gpu(b), gpu(p)
+    y = B.convt_forward(xg, fg, bg, up, crop, G)
+    dx = B.convt_backward_data(x.shape, fg, pg, up, crop, G)
+    df = B.convt_backward_filter(xg, f.shape, pg, up, crop, G)
+    db = B.convt_backward_bias(x.shape, f.shape, pg, up, crop, G)
+    torch.cuda.synchronize()
+    y, dx, df, db = (t.cpu().numpy().ravel() for t in (y, dx, df, db))
+    del xg, fg, pg
+    xd, fd, bd, pd = np64(x), np64(f), np64(b), np64(p)
+    out = {}
+    iy = sample_idx(y.size, n_out, 1)
+    out["forward"] = norm_err(y[iy], oracle_t.forward_at(xd, fd, bd, iy, up, crop, G),
+                              oracle_t.forward_at(np.abs(xd), np.abs(fd), np.abs(bd), iy, up, crop, G))
+    ix = sample_idx(dx.size, n_out, 2)
+    out["backward_data"] = norm_err(dx[ix], oracle_t.backward_data_at(x.shape, fd, pd, ix, up, crop, G),
+                                    oracle_t.backward_data_at(x.shape, np.abs(fd), np.abs(pd), ix, up, crop, G))
+    iw = sample_idx(df.size, n_filt, 3)
+    out["backward_filter"] = norm_err(df[iw], oracle_t.backward_filter_at(xd, f.shape, pd, iw, up, crop, G),
+                                      oracle_t.backward_filter_at(np.abs(xd), f.shape, np.abs(pd), iw, up, crop, G))
+    out["backward_bias"] = norm_err(db, oracle_t.backward_bias(x.shape, f.shape, pd, up, crop, G),
+                                    oracle_t.backward_bias(x.shape, f.shape, np.abs(pd), up, crop, G))
+    return out

@@ -100,7 +100,7 @@ def test_null_pointers_and_small_workspace_are_rejected():
 def test_status_strings():
     L = B.lib()
     seen = set()
-    for code in range(0, 7):
+    for code in range(0, 8):
         s = L.mcn_status_string(code).decode()
         assert s and s not in seen
         seen.add(s)
@@ -108,3 +108,71 @@ def test_status_strings():
     for op in range(4):
         assert B.mcn_conv_kernel_name(desc(), op)
     assert B.mcn_conv_kernel_name(desc(), 17) is None
+
+
+# ---- convolution transpose ----
+def tdesc(**kw):
+    base = dict(xshape=(2, 4, 5, 6), fshape=(4, 3, 3, 4), upsample=(2, 2), crop=(1, 0, 0, 1), groups=2)
+    base.update(kw)
+    return B.make_convt_desc(**base)
+
+
+def test_convt_output_size_closed_form():
+    # Sec. 4.2: H'' = S_h (H - 1) + H' - top - bottom
+    assert B.mcn_convt_output_size(tdesc()) == (2 * 5 + 4 - 1, 2 * 4 + 3 - 1)
+    assert B.mcn_convt_output_size(tdesc(upsample=(1, 3), crop=(0, 0, 2, 2))) == (5 + 4, 3 * 4 + 3 - 4)
+    # 32x bilinear upsampling of a 16x16 map with a 64-tap filter and 16 cropped on each side
+    assert B.mcn_convt_output_size(B.make_convt_desc((1, 21, 16, 16), (21, 1, 64, 64), (32, 32), (16, 16, 16, 16), 21)) == (512, 512)
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(upsample=(0, 1)), B.MCN_BAD_ARG),
+    (dict(upsample=(1, -2)), B.MCN_BAD_ARG),
+    (dict(crop=(0, 0, -1, 0)), B.MCN_BAD_ARG),
+    (dict(xshape=(0, 4, 5, 6)), B.MCN_BAD_ARG),
+    (dict(fshape=(4, 0, 3, 4)), B.MCN_BAD_ARG),
+    (dict(groups=0), B.MCN_BAD_ARG),
+    (dict(precision=9), B.MCN_BAD_ARG),
+    (dict(groups=3), B.MCN_BAD_GROUPS),                    # 3 groups do not divide D = 4
+    (dict(crop=(7, 7, 0, 0)), B.MCN_CROP_TOO_LARGE),       # 14 rows before cropping
+    (dict(crop=(0, 0, 11, 0)), B.MCN_CROP_TOO_LARGE),      # 11 columns before cropping
+    (dict(xshape=(1 << 18, 4, 64, 64), fshape=(4, 64, 3, 3)), B.MCN_UNSUPPORTED),   # y has >= 2^31 elements
+])
+def test_convt_bad_geometry_is_a_status_code_everywhere(kw, code):
+    d = tdesc(**kw)
+    L = B.lib()
+    assert L.mcn_convt_output_size(ctypes.byref(d), None, None) == code
+    n = ctypes.c_size_t(0)
+    assert L.mcn_convt_workspace_size(ctypes.byref(d), 0, ctypes.byref(n)) == code
+    p = 4096
+    assert B.mcn_convt_forward(d, p, p, p, p, None, 0, None) == code
+    assert B.mcn_convt_backward_data(d, p, p, p, None, 0, None) == code
+    assert B.mcn_convt_backward_filter(d, p, p, p, None, 0, None) == code
+    assert B.mcn_convt_backward_bias(d, p, p, None, 0, None) == code
+    assert B.mcn_convt_kernel_name(d, 0) is None
+
+
+def test_convt_null_pointers_and_small_workspace_are_rejected():
+    d = tdesc()
+    p = 4096
+    L = B.lib()
+    assert L.mcn_convt_output_size(None, None, None) == B.MCN_BAD_ARG
+    assert L.mcn_convt_workspace_size(ctypes.byref(d), 4, ctypes.byref(ctypes.c_size_t(0))) == B.MCN_BAD_ARG
+    assert L.mcn_convt_workspace_size(ctypes.byref(d), 0, None) == B.MCN_BAD_ARG
+    assert B.mcn_convt_forward(d, None, p, p, p, None, 0, None) == B.MCN_BAD_ARG
+    assert B.mcn_convt_forward(d, p, None, p, p, None, 0, None) == B.MCN_BAD_ARG
+    assert B.mcn_convt_forward(d, p, p, p, None, None, 0, None) == B.MCN_BAD_ARG
+    assert B.mcn_convt_backward_data(d, None, p, p, None, 0, None) == B.MCN_BAD_ARG
+    assert B.mcn_convt_backward_filter(d, p, p, None, None, 0, None) == B.MCN_BAD_ARG
+    assert B.mcn_convt_backward_bias(d, p, None, None, 0, None) == B.MCN_BAD_ARG
+    for op, call in [(B.MCN_OP_BACKWARD_BIAS, lambda ws, n: B.mcn_convt_backward_bias(d, p, p, ws, n, None)),
+                     (B.MCN_OP_FORWARD, lambda ws, n: B.mcn_convt_forward(d, p, p, p, p, ws, n, None)),
+                     (B.MCN_OP_BACKWARD_DATA, lambda ws, n: B.mcn_convt_backward_data(d, p, p, p, ws, n, None)),
+                     (B.MCN_OP_BACKWARD_FILTER, lambda ws, n: B.mcn_convt_backward_filter(d, p, p, p, ws, n, None))]:
+        need = B.mcn_convt_workspace_size(d, op)
+        if need:
+            assert call(p, need - 1) == B.MCN_WORKSPACE_TOO_SMALL
+            assert call(None, need) == B.MCN_WORKSPACE_TOO_SMALL
+    for op in range(4):
+        assert B.mcn_convt_kernel_name(d, op)
+    assert B.mcn_convt_kernel_name(d, 4) is None
