@@ -8,6 +8,9 @@ operands already resident in HBM.  The default workload is the deep 3x3 stack
 on which the headline metric is quoted.  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload vgg3x3|<layer names>]
+
+Layer names t1..t5 are shapes of the convolution transpose block (timing table only; the
+headline metric is quoted on the convolution block).
 """
 import argparse
 import json
@@ -80,6 +83,10 @@ class LayerState:
         nx, nw, ny = self.x.numel(), self.w.numel(), self.p.numel()
         self.bytes = [4 * (nx + nw + ny), 4 * (ny + nw + nx), 4 * (nx + ny + nw), 4 * (ny + L["K"])]
 
+    def shape_info(self):
+        L = self.L
+        return {"x_HWDN": [L["H"], L["W"], L["D"], L["N"]], "w_HWDK": [L["Hf"], L["Wf"], L["Df"], L["K"]]}
+
     def run(self, op, stream):
         d, ws, n = self.desc, self.ws.data_ptr(), self.ws.numel()
         x, p, y, dx = self.sets[self.turn % len(self.sets)]
@@ -95,6 +102,55 @@ class LayerState:
             st = B.mcn_conv_backward_bias(d, p.data_ptr(), self.db.data_ptr(), ws, n, stream)
         if st:
             raise B.McnError(st, OPS[op])
+
+
+class ConvtLayerState:
+    """The convolution transpose block on one of the synth.CONVT_LAYERS shapes (same interface)."""
+
+    def __init__(self, name, L, precision, rotate_mb=0):
+        self.name, self.L, self.prec = name, L, precision
+        self.x = synth.make_tx(L).cuda()
+        self.w = synth.make_tf(L).cuda()
+        self.b = synth.make_tb(L).cuda()
+        desc = B.make_convt_desc(self.x.shape, self.w.shape, L["up"], L["crop"], L["groups"], precision)
+        self.desc = desc
+        self.ho, self.wo = B.mcn_convt_output_size(desc)
+        self.p = synth.make_tdzdy(L, self.ho, self.wo).cuda()
+        self.y = torch.empty_like(self.p)
+        self.dx = torch.empty_like(self.x)
+        self.dw = torch.empty_like(self.w)
+        self.db = torch.empty_like(self.b)
+        # every input sample meets every filter tap once per output channel of its group
+        self.macs = L["H"] * L["W"] * L["D"] * L["N"] * L["Hf"] * L["Wf"] * L["Kf"]
+        self.kernels = [B.mcn_convt_kernel_name(desc, op) for op in range(4)]
+        ws = max(B.mcn_convt_workspace_size(desc, op) for op in range(4))
+        self.ws = torch.empty(max(ws, 16), dtype=torch.uint8, device="cuda")
+        nx, nw, ny = self.x.numel(), self.w.numel(), self.p.numel()
+        self.bytes = [4 * (nx + nw + ny), 4 * (ny + nw + nx), 4 * (nx + ny + nw), 4 * (ny + self.b.numel())]
+
+    def shape_info(self):
+        L = self.L
+        return {"block": "convt", "x_HWDN": [L["H"], L["W"], L["D"], L["N"]], "f_HWKD": [L["Hf"], L["Wf"], L["Kf"], L["D"]],
+                "groups": L["groups"], "up": list(L["up"]), "crop": list(L["crop"])}
+
+    def run(self, op, stream):
+        d, ws, n = self.desc, self.ws.data_ptr(), self.ws.numel()
+        if op == 0:
+            st = B.mcn_convt_forward(d, self.x.data_ptr(), self.w.data_ptr(), self.b.data_ptr(), self.y.data_ptr(), ws, n, stream)
+        elif op == 1:
+            st = B.mcn_convt_backward_data(d, self.w.data_ptr(), self.p.data_ptr(), self.dx.data_ptr(), ws, n, stream)
+        elif op == 2:
+            st = B.mcn_convt_backward_filter(d, self.x.data_ptr(), self.p.data_ptr(), self.dw.data_ptr(), ws, n, stream)
+        else:
+            st = B.mcn_convt_backward_bias(d, self.p.data_ptr(), self.db.data_ptr(), ws, n, stream)
+        if st:
+            raise B.McnError(st, "convt " + OPS[op])
+
+
+def make_state(name, precision, rotate_mb):
+    if name in synth.CONVT_LAYERS:
+        return ConvtLayerState(name, synth.CONVT_LAYERS[name], precision, rotate_mb)
+    return LayerState(name, synth.LAYERS[name], precision, rotate_mb)
 
 
 def cpu_baseline(names):
@@ -146,7 +202,7 @@ def main():
     torch.cuda.set_device(0)
     names = WORKLOADS.get(args.workload) or args.workload.split(",")
     prec = B.MCN_PREC_BF16 if args.precision == "bf16" else B.MCN_PREC_FP32
-    layers = [LayerState(n, synth.LAYERS[n], prec, args.rotate_mb) for n in names]
+    layers = [make_state(n, prec, args.rotate_mb) for n in names]
     stream_obj = torch.cuda.current_stream()
     stream = stream_obj.cuda_stream
 
@@ -222,8 +278,7 @@ def main():
         "config": {"workload": "conv fwd+bwd (dzdx, dzdw, dzdb) of layers " + ",".join(names) +
                                " (3x3 stride 1 pad 1, N=32)" if args.workload == "vgg3x3" else
                                "conv fwd+bwd of layers " + ",".join(names),
-                   "layers": {Ls.name: {"x_HWDN": [Ls.L["H"], Ls.L["W"], Ls.L["D"], Ls.L["N"]],
-                                        "w_HWDK": [Ls.L["Hf"], Ls.L["Wf"], Ls.L["Df"], Ls.L["K"]]} for Ls in layers}},
+                   "layers": {Ls.name: Ls.shape_info() for Ls in layers}},
         "frac_of_fp32_mfma_peak": round(value / FP32_MFMA_PEAK_TFLOPS, 4),
         "roofline": roof,
         "calls": detail,
@@ -234,7 +289,7 @@ def main():
         for _ in range(3):
             torch.mul(src, 1.0, out=dst)      # reads 256 MiB, writes 256 MiB
         torch.cuda.synchronize()
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and all(n in synth.LAYERS for n in names):
         out["cpu_baseline"] = cpu_baseline(names)
     print(json.dumps(out), flush=True)
 
