@@ -7,6 +7,7 @@
 #include <stdlib.h>
 #include "geom.h"
 #include "kern_igemm.h"
+#include "kern_igemm_bf16.h"
 
 namespace mcn {
 
@@ -89,6 +90,7 @@ enum IgemmShape { IG_128x256 = 0, IG_64x512 = 1, IG_32x256 = 2, IG_NONE = -1 };
 
 struct IgemmPlan {
     int shape;          // IgemmShape
+    bool bf16;          // operands rounded to bf16 (kern_igemm_bf16.h); sizes below are then in 32-bit words
     bool fixed33;       // 3x3 filter instantiation
     int TK, TQ, NT;
     IgemmParams P;
@@ -151,14 +153,29 @@ inline bool cut_units(const ConvView &v, int TK, int64_t CP, size_t lds_left, Un
     return found;
 }
 
-inline bool plan_igemm(const ConvView &v, int n_cu, IgemmPlan *pl) {
+// bf16 kernel: a unit is 16 channels x TC taps, one MFMA step per tap; the fewest tap ranges whose
+// double-buffered weights (TC*2*TK 16-byte words) and slab (2*CP words) fit.
+inline bool cut_units_bf16(const ConvView &v, int TK, int64_t CP, size_t lds_left, UnitCut *uc) {
+    const int T = v.Hf * v.Wf;
+    for (int NTR = 1; NTR <= T; ++NTR) {
+        const int TC = (T + NTR - 1) / NTR;
+        if ((int64_t)(NTR - 1) * TC >= T) continue;
+        const size_t lds = 2 * ((size_t)TC * 2 * TK + 2 * (size_t)CP) * 16 + (size_t)NTR * TC * 4;
+        if (lds > lds_left) continue;
+        uc->pair_mode = 0; uc->DC = BF_DC; uc->TC = TC; uc->NTR = NTR; uc->NS = TC;
+        return true;
+    }
+    return false;
+}
+
+inline bool plan_igemm(const ConvView &v, int n_cu, IgemmPlan *pl, bool bf16 = false) {
     const int T = v.Hf * v.Wf;
     int shape, WK, WP, MK, MP;
     if (v.Kg > 64) { shape = IG_128x256; WK = 2; WP = 4; MK = 2; MP = 2; }
     else if (v.Kg > 32) { shape = IG_64x512; WK = 1; WP = 8; MK = 2; MP = 2; }
     else { shape = IG_32x256; WK = 1; WP = 4; MK = 1; MP = 2; }
     const int TK = WK * MK * 32, TQ = WP * MP * 32, NT = 64 * WK * WP;
-    const bool fixed33 = (v.Hf == 3 && v.Wf == 3 && v.Cg >= 2 * IGEMM_FIXED_DC && v.Cg % IGEMM_FIXED_DC == 0);
+    const bool fixed33 = !bf16 && (v.Hf == 3 && v.Wf == 3 && v.Cg >= 2 * IGEMM_FIXED_DC && v.Cg % IGEMM_FIXED_DC == 0);
     const int Wp = (v.Wo - 1) * v.Sw + v.Wf;
     // candidates for the row-block height
     int cand[48];
@@ -178,7 +195,7 @@ inline bool plan_igemm(const ConvView &v, int n_cu, IgemmPlan *pl) {
         if ((int64_t)TI * v.Wo * v.N >= ((int64_t)1 << 30)) continue;
         const int SC = slab_columns(v, TI, TQ, Wp);
         const int64_t CP = (SR * SC + 63) / 64 * 64;
-        if (CP > 16 * NT) continue;
+        if (CP > (bf16 ? bf_ept_max(NT) : 16) * NT) continue;
         // an image crossing inside a tile moves the window by whole images: keep offsets in range
         const int64_t span = (int64_t)SC / Wp + 2;
         if ((double)span * v.Ctot * v.H * v.W * 4.0 >= 2147483647.0) continue;
@@ -186,7 +203,10 @@ inline bool plan_igemm(const ConvView &v, int n_cu, IgemmPlan *pl) {
         const int EPT = (int)((CP + NT - 1) / NT);
         const size_t fixed_lds = ((size_t)EPT * NT + 2 * TK + 4) * 4;
         UnitCut uc;
-        if (fixed33) {
+        if (bf16) {
+            if (fixed_lds + 64 > IGEMM_LDS_LIMIT) continue;
+            if (!cut_units_bf16(v, TK, CP, IGEMM_LDS_LIMIT - fixed_lds - 64, &uc)) continue;
+        } else if (fixed33) {
             uc.pair_mode = 0; uc.DC = IGEMM_FIXED_DC; uc.TC = 9; uc.NTR = 1; uc.NS = (IGEMM_FIXED_DC / 2) * 9;
             if ((2 * ((size_t)uc.NS * 2 * TK + 255) + 2 * (size_t)uc.DC * CP) * 4 + fixed_lds > IGEMM_LDS_LIMIT) continue;
         } else {
@@ -200,7 +220,7 @@ inline bool plan_igemm(const ConvView &v, int n_cu, IgemmPlan *pl) {
         const int64_t PT = (QN + TQ - 1) / TQ;
         const double mfma_waste = (double)RB * PT * TQ / ((double)v.Ho * v.Wo * v.N);
         const int NCG = (v.Cg + uc.DC - 1) / uc.DC;
-        const double red_waste = (double)NCG * uc.NTR * uc.NS * 2 / ((double)v.Cg * T);
+        const double red_waste = (double)NCG * uc.NTR * uc.NS * (bf16 ? BF_DC : 2) / ((double)v.Cg * T);
         const double score = mfma_waste * red_waste * (1.0 + 0.05 * (double)CP / TQ);
         if (score < best_score) { best_score = score; bestTI = TI; bestSC = SC; best_uc = uc; }
     }
@@ -227,15 +247,20 @@ inline bool plan_igemm(const ConvView &v, int n_cu, IgemmPlan *pl) {
     const int64_t total = tiles * P.NU;
     P.nblocks = (int)(total < n_cu ? total : n_cu);
     P.OH = v.OH; P.OW = v.OW; P.oi0 = v.oi0; P.osi = v.osi; P.oj0 = v.oj0; P.osj = v.osj;
-    const size_t wsz = ((size_t)P.NS * 2 * TK + 255) / 256 * 256;
+    // packed weights per unit, in 32-bit words: bf16 steps hold 2 octets x TK filters x 16 bytes
+    const size_t wsz = bf16 ? (size_t)P.NS * 2 * TK * 4 : ((size_t)P.NS * 2 * TK + 255) / 256 * 256;
     P.WSZ = (int)wsz;
     pl->packed_floats = (size_t)v.G * P.KT * P.NU * wsz;
     if (pl->packed_floats * 4 >= 2147483647ull) return false;
     P.packed_bytes = (unsigned)(pl->packed_floats * 4);
     pl->partial_floats = P.nblocks > 1 ? (size_t)2 * P.nblocks * TK * TQ : 0;
-    pl->shape = shape; pl->fixed33 = fixed33; pl->TK = TK; pl->TQ = TQ; pl->NT = NT;
-    pl->lds_bytes = (2 * wsz + 2 * (size_t)P.DC * P.CP + (size_t)P.EPT * NT + 2 * TK +
-                     (fixed33 ? 0 : (size_t)P.NTR * P.NS * 2) + 4) * sizeof(float);
+    pl->shape = shape; pl->bf16 = bf16; pl->fixed33 = fixed33; pl->TK = TK; pl->TQ = TQ; pl->NT = NT;
+    if (bf16)
+        pl->lds_bytes = (2 * wsz + 2 * (size_t)2 * P.CP * 4 + (size_t)P.EPT * NT + 2 * TK + (size_t)P.NTR * P.NS + 4) *
+                        sizeof(float);
+    else
+        pl->lds_bytes = (2 * wsz + 2 * (size_t)P.DC * P.CP + (size_t)P.EPT * NT + 2 * TK +
+                         (fixed33 ? 0 : (size_t)P.NTR * P.NS * 2) + 4) * sizeof(float);
     if (pl->lds_bytes > IGEMM_LDS_LIMIT) return false;
 
     PackParams &Q = pl->Q;

@@ -1,0 +1,363 @@
+// Implicit-GEMM convolution on the bf16 matrix cores (v_mfma_f32_32x32x16_bf16):
+// the "operands rounded to bf16 on chip, fp32 accumulation" variant of kern_igemm.h.
+// Arrays in memory stay fp32 in the layout of the MatConvNet manual (arXiv 1412.4564,
+// Sec. 2.3.1); the sum computed is the one of Sec. 4.1 (see kern_igemm.h), with every x and
+// w rounded to bf16 (round to nearest even) before the products are formed.
+//
+// Same tiling, same pixel numbering, same stream-K scheduling, same fix-up pass and the same
+// IgemmParams as the fp32 kernel.  What differs:
+//  * one MFMA consumes 16 reduction elements: 16 channels of one filter tap.  Lane l holds
+//    8 consecutive channels (octet l/32 of the 16) of filter or pixel l%32, as one 16-byte
+//    register group, so both operands are stored channel-interleaved:
+//      slab     [octet][column][row][8 channels]  bf16, 16 bytes per (octet, sample)
+//      weights  [step][octet][filter][8 channels] bf16 (written that way by the packing pass)
+//    and every operand read is one ds_read_b128 of consecutive 16-byte words (conflict-free).
+//    P.CP is the slab's pitch per octet in samples, P.DC = 16, a step is one tap (P.NS = P.TC),
+//    P.WSZ counts 32-bit words of packed weights per unit.
+//  * the slab cannot be loaded straight into LDS: a thread loads the 16 channels of its
+//    sample(s) into registers one unit ahead (coalesced along rows, as before), and after
+//    the unit's MFMAs converts them and writes two 16-byte words.
+#pragma once
+#include "kern_igemm.h"
+
+namespace mcn {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float floatx2 __attribute__((ext_vector_type(2)));
+typedef unsigned uintx4 __attribute__((ext_vector_type(4)));
+
+constexpr int BF_DC = 16;        // channels per unit = reduction depth of one MFMA
+// slab samples a thread stages per unit, at most (16 registers each)
+constexpr int bf_ept_max(int threads) { return threads <= 256 ? 4 : 2; }
+
+__device__ inline unsigned pack_bf16x2(float lo, float hi) {
+    const floatx2 v = {lo, hi};
+    const bf16x2 h = __builtin_convertvector(v, bf16x2);     // round to nearest even
+    return __builtin_bit_cast(unsigned, h);
+}
+
+// packed[g][kt][unit][step][octet][kk][8 channels] as bf16; one thread writes one pair of
+// channels (a 32-bit word).  Modes as in igemm_pack_weights_kernel.
+__global__ __launch_bounds__(256) void igemm_pack_weights_bf16_kernel(const float *__restrict__ w,
+                                                                      unsigned *__restrict__ packed, PackParams Q) {
+    int p = blockIdx.x * 256 + threadIdx.x;
+    if (p >= Q.total) return;
+    int t = p / Q.WSZ;
+    int within = p - t * Q.WSZ;
+    const int j2 = within & 3; within >>= 2;
+    const int kk = within % Q.TK; within /= Q.TK;
+    const int oct = within & 1;
+    const int s = within >> 1;                   // tap of the unit's tap range
+    const int uu = t % Q.NU; t /= Q.NU;
+    const int kt = t % Q.KT;
+    const int g = t / Q.KT;
+    const int cg = uu / Q.NTR, tr = uu - cg * Q.NTR;
+    const int tap = tr * Q.TC + s;
+    const int k = kt * Q.TK + kk;
+    float v[2] = {0.f, 0.f};
+    if (s < Q.TC && tap < Q.Hf * Q.Wf && k < Q.Kg) {
+        const int ti = tap % Q.Hf, tj = tap / Q.Hf;
+        for (int e = 0; e < 2; ++e) {
+            const int c = cg * BF_DC + oct * 8 + 2 * j2 + e;
+            if (c >= Q.Cg) continue;
+            if (Q.mode == 0) {
+                v[e] = w[ti + Q.HfA * (tj + Q.WfA * (c + (size_t)Q.DfA * (g * Q.Kg + k)))];
+            } else if (Q.mode == 1) {
+                const int fi = Q.pi + Q.Sh * (Q.Hf - 1 - ti), fj = Q.pj + Q.Sw * (Q.Wf - 1 - tj);
+                v[e] = w[fi + Q.HfA * (fj + Q.WfA * (k + (size_t)Q.DfA * (g * Q.Cg + c)))];
+            } else {
+                v[e] = w[k + (size_t)Q.ldk * c];
+            }
+        }
+    }
+    packed[p] = pack_bf16x2(v[0], v[1]);
+}
+
+// WK x WP waves; each wave owns MK x MP tiles of 32 filters x 32 pixels.
+template <int WK, int WP, int MK, int MP, int WPE>
+__global__ __launch_bounds__(64 * WK * WP, WPE) void igemm_bf16_kernel(IgemmParams P, const float *__restrict__ in,
+                                                                       const float *__restrict__ wpk,
+                                                                       const float *__restrict__ bias,
+                                                                       float *__restrict__ out,
+                                                                       float *__restrict__ part) {
+    constexpr int NT = 64 * WK * WP;
+    constexpr int TK = WK * MK * 32;
+    constexpr int TQ = WP * MP * 32;
+    constexpr int NW = WK * WP;
+    constexpr int BF_EPT_MAX = bf_ept_max(NT);
+    const int NS = P.NS;
+    const int NU = P.NU;
+    const int WSZ = P.WSZ;               // 32-bit words of packed weights per unit
+    const int CP = P.CP, SRP = P.SRP;
+    const int XSZ = 2 * CP * 4;          // 32-bit words of slab per unit: 2 octets x CP samples x 16 bytes
+
+    extern __shared__ __align__(16) float lds[];
+    float *wbuf = lds;                                   // [2][WSZ]
+    float *xbuf = lds + 2 * WSZ;                         // [2][XSZ]
+    int *gtab = reinterpret_cast<int *>(xbuf + 2 * XSZ); // [EPT][NT]: entry (s, tid) is private to thread tid
+    float *blds = reinterpret_cast<float *>(gtab + P.EPT * NT);   // [2][TK] bias of the tile, by tile parity
+    int *otab = reinterpret_cast<int *>(blds + 2 * TK);           // [NTR][NS] slab byte offsets of the taps
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int half = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wk = wave % WK, wp = wave / WK;
+    const int HW = P.H * P.W;
+    const int OHW = P.OH * P.OW;
+
+    const int vb = sk_virtual_block(blockIdx.x, P.nblocks);
+    const long long total = (long long)P.tiles * NU;
+    const long long ub = sk_begin(total, P.nblocks, vb), ue = sk_begin(total, P.nblocks, vb + 1);
+    if (ub >= ue) return;
+
+    {
+        const int T = P.Hf * P.Wf;
+        for (int idx = tid; idx < P.NTR * NS; idx += NT) {
+            const int s = idx % NS, tr = idx / NS;
+            const int tap = tr * P.TC + s;
+            otab[idx] = (s < P.TC && tap < T) ? 16 * ((tap / P.Hf) * SRP + tap % P.Hf) : 0;
+        }
+    }
+
+    const buffer_rsrc wrs = make_rsrc(wpk, P.packed_bytes);
+    const buffer_rsrc brs = make_rsrc(bias, bias ? (unsigned)P.Ktot * 4u : 0u);
+    const unsigned lane16 = (unsigned)lane * 16u;
+
+    // ---- load side: tile whose units are being fetched ------------------------------------
+    __amdgpu_buffer_rsrc_t xrs = __builtin_amdgcn_make_buffer_rsrc((void *)in, 0, 0, BUFFER_FLAGS);
+    unsigned wtile_off = 0;        // byte offset of the tile's packed weights
+    int l_t = 0, l_kt = 0, l_g = 0;
+    auto setup_load = [&](int t) {
+        l_t = t;
+        int kt, pt, rb, g;
+        decode_tile(P, t, &kt, &pt, &rb, &g);
+        const int q0 = pt * TQ;
+        const int c_first = q0 / P.TI;
+        const int n_first = c_first / P.Wo;
+        const int u0 = (c_first - n_first * P.Wo) * P.Sw;   // chained column of the slab's first column
+        const int row0 = rb * P.TI * P.Sh - P.Pt;           // input row of slab row 0
+        const size_t in_base = ((size_t)n_first * P.Ctot + (size_t)g * P.Cg) * HW;
+        size_t in_left = ((size_t)P.N * P.Ctot * HW - in_base) * 4;
+        if (in_left > 0x7fffffffull) in_left = 0x7fffffffull;
+        xrs = __builtin_amdgcn_make_buffer_rsrc((void *)(in + in_base), 0, (int)in_left, BUFFER_FLAGS);
+        wtile_off = (unsigned)((size_t)(g * P.KT + kt) * NU * WSZ * 4);
+        l_kt = kt; l_g = g;
+        for (int s = 0; s < P.EPT; ++s) {
+            const int e = tid + NT * s;
+            const int col = e / SRP;
+            const int r = e - col * SRP;
+            const int U = u0 + col;
+            const int ni = U / P.Wp;                 // image relative to n_first
+            const int j = U - ni * P.Wp - P.Pl;
+            const int i = row0 + r;
+            const bool ok = e < CP && r < P.SR && i >= 0 && i < P.H && j >= 0 && j < P.W && (n_first + ni) < P.N;
+            gtab[s * NT + tid] = ok ? (int)(4u * (unsigned)(i + P.H * j + ni * P.Ctot * HW)) : (int)SLAB_INVALID;
+        }
+    };
+    // the 16 channels of this thread's slab samples, held in registers while the unit before is computed
+    float stg[BF_EPT_MAX][BF_DC];
+    auto issue_loads = [&](int uu, int b) {
+        float *wb = wbuf + b * WSZ;
+        const unsigned woff = wtile_off + (unsigned)uu * (unsigned)WSZ * 4u;
+        for (int e0 = wave * 256; e0 < WSZ; e0 += NW * 256)       // one wave instruction = 1 KB, 16 bytes per lane
+            load_to_lds_b128(lds_address(wb + e0), lane16, wrs, woff + (unsigned)e0 * 4u);
+        if (bias && uu == 0 && wave * 64 < TK) {
+            // the tile's bias: start value of the accumulators of a tile this block owns entirely
+            const int kl = l_kt * TK + wave * 64 + lane;
+            if (wave * 64 + lane < TK)
+                load_to_lds_b32(lds_address(blds + (l_t & 1) * TK + wave * 64),
+                                kl < P.Kg ? (unsigned)(l_g * P.Kg + kl) * 4u : SLAB_INVALID, brs, 0);
+        }
+        const int c0 = (uu / P.NTR) * BF_DC;
+#pragma unroll
+        for (int s = 0; s < BF_EPT_MAX; ++s) {
+            if (s < P.EPT && wave * 64 + NT * s < CP) {
+                const unsigned go = (unsigned)gtab[s * NT + tid];
+#pragma unroll
+                for (int d = 0; d < BF_DC; ++d) {
+                    const int c = c0 + d;
+                    // channels past the group's last one read as zero (their weights are zero too)
+                    stg[s][d] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(
+                        xrs, c < P.Cg ? go : SLAB_INVALID, (unsigned)c * (unsigned)HW * 4u, 0));
+                }
+            }
+        }
+    };
+    // convert the staged samples and publish them in slab buffer b
+    auto write_slab = [&](int b) {
+        float *xb = xbuf + b * XSZ;
+#pragma unroll
+        for (int s = 0; s < BF_EPT_MAX; ++s) {
+            if (s < P.EPT && wave * 64 + NT * s < CP) {
+                const int e = tid + NT * s;
+#pragma unroll
+                for (int o = 0; o < 2; ++o) {
+                    uintx4 v;
+                    v.x = pack_bf16x2(stg[s][8 * o + 0], stg[s][8 * o + 1]);
+                    v.y = pack_bf16x2(stg[s][8 * o + 2], stg[s][8 * o + 3]);
+                    v.z = pack_bf16x2(stg[s][8 * o + 4], stg[s][8 * o + 5]);
+                    v.w = pack_bf16x2(stg[s][8 * o + 6], stg[s][8 * o + 7]);
+                    *reinterpret_cast<uintx4 *>(xb + (size_t)(o * CP + e) * 4) = v;
+                }
+            }
+        }
+    };
+
+    // ---- compute side: tile whose accumulators are live -----------------------------------
+    int bbase[MP];       // slab byte offset of the pixel's window origin, octet of this half-wave
+    unsigned ooff[MP];   // byte offset of the lane's first result of the tile relative to the tile's output
+                         // window (filter k0 + 4*half of image n_first), or SLAB_INVALID
+    __amdgpu_buffer_rsrc_t ors = __builtin_amdgcn_make_buffer_rsrc((void *)out, 0, 0, BUFFER_FLAGS);   // the tile's output window
+    int c_t = 0, c_kt = 0, c_g = 0;
+    bool need_init = true;
+    floatx16 acc[MK][MP];
+    auto setup_compute = [&](int t) {
+        c_t = t;
+        int kt, pt, rb, g;
+        decode_tile(P, t, &kt, &pt, &rb, &g);
+        c_kt = kt; c_g = g;
+        const int q0 = pt * TQ;
+        const int qend = min(q0 + TQ, P.QN);
+        const int c_first = q0 / P.TI;
+        const int n_first = c_first / P.Wo;
+        const int u0 = (c_first - n_first * P.Wo) * P.Sw;
+#pragma unroll
+        for (int mp = 0; mp < MP; ++mp) {
+            const int q = q0 + (wp * MP + mp) * 32 + (lane & 31);
+            const int ii = q % P.TI;
+            const int c = q / P.TI;
+            const int n = c / P.Wo;
+            const int jo = c - n * P.Wo;
+            const int io = rb * P.TI + ii;
+            const bool ok = q < qend && io < P.Ho;
+            const int ucol = jo * P.Sw + (n - n_first) * P.Wp - u0;
+            bbase[mp] = 16 * ((ok ? ii * P.Sh + SRP * ucol : 0) + half * CP);
+            ooff[mp] = ok ? 4u * (unsigned)((P.oi0 + P.osi * io) + P.OH * (P.oj0 + P.osj * jo) +
+                                            OHW * (P.Ktot * (n - n_first) + 4 * half))
+                          : SLAB_INVALID;
+        }
+        const size_t out_base = (size_t)n_first * P.Ktot * OHW;
+        size_t out_left = ((size_t)P.N * P.Ktot * OHW - out_base) * 4;
+        if (out_left > 0x7fffffffull) out_left = 0x7fffffffull;
+        ors = __builtin_amdgcn_make_buffer_rsrc((void *)(out + out_base), 0, (int)out_left, BUFFER_FLAGS);
+        need_init = true;
+    };
+    auto init_acc = [&](bool with_bias) {
+        const float *bl = blds + (c_t & 1) * TK;
+#pragma unroll
+        for (int mk = 0; mk < MK; ++mk)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int kloc = (wk * MK + mk) * 32 + (v >> 2) * 8 + half * 4 + (v & 3);
+                const float bv = with_bias ? bl[kloc] : 0.f;
+#pragma unroll
+                for (int mp = 0; mp < MP; ++mp) acc[mk][mp][v] = bv;
+            }
+    };
+    const int aoff = 16 * (half * TK + wk * MK * 32 + (lane & 31));   // bytes
+    auto compute = [&](int uu, int b) {
+        const char *wl = reinterpret_cast<const char *>(wbuf + b * WSZ) + aoff;
+        const char *xl = reinterpret_cast<const char *>(xbuf + b * XSZ);
+        const int *ot = otab + (uu % P.NTR) * NS;
+        bf16x8 a0[MK], b0[MP], a1[MK], b1[MP];
+        auto fetch = [&](bf16x8 *a, bf16x8 *bq, int s, int o) {
+#pragma unroll
+            for (int mk = 0; mk < MK; ++mk) a[mk] = *reinterpret_cast<const bf16x8 *>(wl + (s * 2 * TK + mk * 32) * 16);
+#pragma unroll
+            for (int mp = 0; mp < MP; ++mp) bq[mp] = *reinterpret_cast<const bf16x8 *>(xl + bbase[mp] + o);
+        };
+        auto mma = [&](const bf16x8 *a, const bf16x8 *bq) {
+#pragma unroll
+            for (int mk = 0; mk < MK; ++mk)
+#pragma unroll
+                for (int mp = 0; mp < MP; ++mp)
+                    acc[mk][mp] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mk], bq[mp], acc[mk][mp], 0, 0, 0);
+        };
+        fetch(a0, b0, 0, ot[0]);
+        for (int s = 0; s < NS; s += 2) {
+            if (s + 1 < NS) fetch(a1, b1, s + 1, ot[s + 1]);
+            __builtin_amdgcn_sched_barrier(0);
+            mma(a0, b0);
+            __builtin_amdgcn_sched_barrier(0);
+            if (s + 2 < NS) fetch(a0, b0, s + 2, ot[s + 2]);
+            __builtin_amdgcn_sched_barrier(0);
+            if (s + 1 < NS) mma(a1, b1);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+    auto store_tile = [&]() {
+#pragma unroll
+        for (int mk = 0; mk < MK; ++mk) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int kl0 = c_kt * TK + (wk * MK + mk) * 32 + (v >> 2) * 8 + (v & 3);   // filter of the lower half-wave
+                const int left = P.Kg - kl0;
+                if (left <= 0) continue;
+                const unsigned soff = (unsigned)(c_g * P.Kg + kl0) * (unsigned)OHW * 4u;
+#pragma unroll
+                for (int mp = 0; mp < MP; ++mp) {
+                    const unsigned vo = (left > 4 || half == 0) ? ooff[mp] : SLAB_INVALID;   // the upper half-wave holds filter kl0 + 4
+                    const float val = acc[mk][mp][v];
+                    __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(val), ors, vo, soff, 0);
+                }
+            }
+        }
+    };
+    auto store_partial = [&](int slot) {
+        float *dst = part + (size_t)slot * (TK * TQ);
+#pragma unroll
+        for (int mk = 0; mk < MK; ++mk)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int kloc = (wk * MK + mk) * 32 + (v >> 2) * 8 + half * 4 + (v & 3);
+#pragma unroll
+                for (int mp = 0; mp < MP; ++mp)
+                    dst[kloc * TQ + (wp * MP + mp) * 32 + (lane & 31)] = acc[mk][mp][v];
+            }
+    };
+
+    // ---- the block's range of units --------------------------------------------------------
+    int t_c = (int)(ub / NU);             // compute-side tile and unit
+    int uu_c = (int)(ub - (long long)t_c * NU);
+    int t_l = t_c, uu_l = uu_c;           // the load side runs one unit ahead
+    bool first_segment = true;
+    auto segment_is_whole = [&](int t, int uu) { return uu == 0 && (long long)(t + 1) * NU <= ue; };
+    setup_load(t_l);
+    issue_loads(uu_l, 0);
+    write_slab(0);
+    bool whole = segment_is_whole(t_c, uu_c);
+    setup_compute(t_c);
+
+    const int nunits = (int)(ue - ub);
+    for (int it = 0; it < nunits; ++it) {
+        __builtin_amdgcn_s_waitcnt(WAIT_VMCNT0);   // this wave's packed weights have landed in LDS
+        lds_barrier();                             // everyone's operands are in place, and the other buffer is free
+        if (need_init) { init_acc(whole && bias != nullptr); need_init = false; }
+        const bool more = it + 1 < nunits;
+        if (more) {
+            if (++uu_l == NU) { uu_l = 0; ++t_l; setup_load(t_l); }
+            issue_loads(uu_l, (it + 1) & 1);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        compute(uu_c, it & 1);
+        __builtin_amdgcn_sched_barrier(0);
+        if (more) write_slab((it + 1) & 1);
+        const bool last = !more;
+        if (uu_c + 1 == NU || last) {
+            if (whole) store_tile();
+            else store_partial(2 * vb + (first_segment ? 0 : 1));
+            first_segment = false;
+            if (!last) {
+                ++t_c; uu_c = 0;
+                whole = segment_is_whole(t_c, 0);
+                setup_compute(t_c);
+            }
+        } else {
+            ++uu_c;
+        }
+    }
+}
+
+}  // namespace mcn

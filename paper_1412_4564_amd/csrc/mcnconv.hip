@@ -118,7 +118,14 @@ const PlanEntry *plans_for(const mcn_conv_desc *d, const Geom &g) {
     e.used = true;
     const bool on = igemm_enabled();
     const int ncu = compute_units();
-    e.fwd_ok = on && plan_igemm(forward_view(g), ncu, &e.fwd);
+    // bf16 operands: the bf16 kernel where a view has at least one full MFMA depth of channels;
+    // other views (and the filter derivative) compute in fp32, which meets the same error bound
+    const bool bf = d->precision == MCN_PREC_BF16;
+    auto plan_view = [&](const ConvView &v, IgemmPlan *pl) {
+        if (bf && v.Cg >= BF_DC && plan_igemm(v, ncu, pl, true)) return true;
+        return plan_igemm(v, ncu, pl, false);
+    };
+    e.fwd_ok = on && plan_view(forward_view(g), &e.fwd);
     e.bwd_ok = on && g.Sh * g.Sw <= MAX_PHASES;
     e.n_bwd = 0;
     e.bwd_fill = false;
@@ -131,7 +138,7 @@ const PlanEntry *plans_for(const mcn_conv_desc *d, const Geom &g) {
                     e.bwd_fill = true;
                     continue;
                 }
-                e.bwd_ok = plan_igemm(v, ncu, &e.bwd[e.n_bwd++]);
+                e.bwd_ok = plan_view(v, &e.bwd[e.n_bwd++]);
             }
     }
     e.wg_ok = on && plan_wgrad(forward_view(g), ncu, &e.wg);
@@ -163,10 +170,39 @@ size_t igemm_ws_bytes(const IgemmPlan &pl) {
     return align256(pl.packed_floats * sizeof(float)) + pl.partial_floats * sizeof(float);
 }
 
+template <int WK, int WP, int MK, int MP>
+int launch_igemm_bf16_inst(const IgemmPlan &pl, const float *in, const float *wpk, const float *bias, float *out,
+                           float *part, hipStream_t s) {
+    auto kern = igemm_bf16_kernel<WK, WP, MK, MP, 2>;
+    if (pl.lds_bytes > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           (int)pl.lds_bytes);
+        if (e != hipSuccess) { g_last_hip_error = (int)e; return MCN_HIP_ERROR; }
+    }
+    hipLaunchKernelGGL(kern, dim3(pl.P.nblocks), dim3(64 * WK * WP), pl.lds_bytes, s, pl.P, in, wpk, bias, out, part);
+    int st = check_launch();
+    if (st || pl.P.nblocks < 2) return st;
+    constexpr int TK = WK * MK * 32, TQ = WP * MP * 32;
+    hipLaunchKernelGGL((igemm_fixup_kernel<TK, TQ>), dim3(pl.P.nblocks - 1, 16), dim3(256), 0, s, pl.P, part, bias, out);
+    return check_launch();
+}
+
 int launch_igemm(const IgemmPlan &pl, const float *in, const float *w, const float *bias, float *out, void *ws,
                  hipStream_t s) {
     float *packed = (float *)ws;
     float *part = (float *)((char *)ws + align256(pl.packed_floats * sizeof(float)));
+    if (pl.bf16) {
+        hipLaunchKernelGGL(igemm_pack_weights_bf16_kernel, dim3(cdiv(pl.Q.total, 256)), dim3(256), 0, s, w,
+                           (unsigned *)packed, pl.Q);
+        int st = check_launch();
+        if (st) return st;
+        switch (pl.shape) {
+            case IG_128x256: return launch_igemm_bf16_inst<2, 4, 2, 2>(pl, in, packed, bias, out, part, s);
+            case IG_64x512: return launch_igemm_bf16_inst<1, 8, 2, 2>(pl, in, packed, bias, out, part, s);
+            case IG_32x256: return launch_igemm_bf16_inst<1, 4, 1, 2>(pl, in, packed, bias, out, part, s);
+            default: return MCN_BAD_ARG;
+        }
+    }
     hipLaunchKernelGGL(igemm_pack_weights_kernel, dim3(cdiv(pl.Q.total, 256)), dim3(256), 0, s, w, packed, pl.Q);
     int st = check_launch();
     if (st) return st;
@@ -390,8 +426,9 @@ const char *mcn_conv_kernel_name(const mcn_conv_desc *desc, int op) {
     if (make_geom(desc, &g)) return NULL;
     const PlanEntry *e = plans_for(desc, g);
     switch (op) {
-        case MCN_OP_FORWARD: return e->fc ? "fc_gemm" : e->fwd_ok ? "igemm" : "direct";
-        case MCN_OP_BACKWARD_DATA: return e->fc ? "fc_gemm" : e->bwd_ok ? "igemm" : "direct";
+        case MCN_OP_FORWARD: return e->fc ? "fc_gemm" : e->fwd_ok ? (e->fwd.bf16 ? "igemm_bf16" : "igemm") : "direct";
+        case MCN_OP_BACKWARD_DATA:
+            return e->fc ? "fc_gemm" : e->bwd_ok ? (e->n_bwd && e->bwd[0].bf16 ? "igemm_bf16" : "igemm") : "direct";
         case MCN_OP_BACKWARD_FILTER: return e->fc ? "fc_gemm" : e->wg_ok ? "wgrad_igemm" : "direct";
         case MCN_OP_BACKWARD_BIAS: return plan_bias(g).rows ? "reduce_rows" : "reduce2";
         default: return NULL;

@@ -1,0 +1,138 @@
+"""The bf16-operand variant (operands rounded to bf16 on chip, fp32 accumulation), through the
+C ABI.  Two bars: (1) against the oracle on the fp32 inputs, normalised error <= 1e-2 (rounding two
+operands to 8 significant bits costs at most 2^-8 + 2^-16 of the sum of |w||x|); (2) against the
+oracle on inputs rounded to bf16 beforehand (round to nearest even), the fp32 bars (1e-4 forward,
+1e-3 backward) -- this pins the rounding model itself: what the kernel computes is the exact sum
+over rounded operands, accumulated in fp32."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_1412_4564_amd import binding as B
+from paper_1412_4564_amd import synth
+
+import parity_util as U
+
+pytestmark = pytest.mark.gpu
+BF = B.MCN_PREC_BF16
+
+
+def rne_bf16(t):
+    return t.to(torch.bfloat16).to(torch.float32)
+
+
+def custom_layer(H, W, D, N, Hf, Wf, Df, K, stride=(1, 1), pad=(0, 0, 0, 0), idx=0):
+    return dict(H=H, W=W, D=D, N=N, Hf=Hf, Wf=Wf, Df=Df, K=K, stride=tuple(stride), pad=tuple(pad),
+                config=7, index=idx)
+
+
+def run_bf16(L, with_bias=True, seed=0):
+    st, pad = L["stride"], L["pad"]
+    x, w, b = synth.make_x(L, seed), synth.make_w(L, seed), synth.make_b(L, seed)
+    ho, wo = oracle.output_size(x.shape, w.shape, st, pad)
+    p = synth.make_dzdy(L, ho, wo, seed)
+    xg, wg, bg, pg = x.cuda(), w.cuda(), b.cuda(), p.cuda()
+    y = B.conv_forward(xg, wg, bg if with_bias else None, st, pad, BF)
+    dx = B.conv_backward_data(x.shape, wg, pg, st, pad, BF)
+    dw = B.conv_backward_filter(xg, w.shape, pg, st, pad, BF)
+    torch.cuda.synchronize()
+    y, dx, dw = y.cpu().numpy(), dx.cpu().numpy(), dw.cpu().numpy()
+    xd, wd, bd, pd = (U.np64(t) for t in (x, w, b, p))
+    xr, wr, pr = (U.np64(rne_bf16(t)) for t in (x, w, p))
+    bb = bd if with_bias else None
+    ab = None if bb is None else np.abs(bb)
+    den_y = oracle.forward(np.abs(xd), np.abs(wd), ab, st, pad)
+    den_x = oracle.backward_data(x.shape, np.abs(wd), np.abs(pd), st, pad)
+    den_w = oracle.backward_filter(np.abs(xd), w.shape, np.abs(pd), st, pad)
+    vs_fp32 = {"forward": U.norm_err(y, oracle.forward(xd, wd, bb, st, pad), den_y),
+               "backward_data": U.norm_err(dx, oracle.backward_data(x.shape, wd, pd, st, pad), den_x),
+               "backward_filter": U.norm_err(dw, oracle.backward_filter(xd, w.shape, pd, st, pad), den_w)}
+    vs_rounded = {"forward": U.norm_err(y, oracle.forward(xr, wr, bb, st, pad), den_y),
+                  "backward_data": U.norm_err(dx, oracle.backward_data(x.shape, wr, pr, st, pad), den_x)}
+    return vs_fp32, vs_rounded
+
+
+def check(L, label, with_bias=True, expect_kernel="igemm_bf16"):
+    d = B.make_desc(synth.x_shape(L), synth.w_shape(L), L["stride"], L["pad"], BF)
+    names = [B.mcn_conv_kernel_name(d, op) for op in range(3)]
+    vs_fp32, vs_rounded = run_bf16(L, with_bias)
+    print(label, names, "vs fp32 inputs", {k: "%.2e" % v for k, v in vs_fp32.items()},
+          "vs rounded inputs", {k: "%.2e" % v for k, v in vs_rounded.items()}, flush=True)
+    for k, v in vs_fp32.items():
+        assert v <= U.TOL_BF16, (label, k, v)
+    if expect_kernel:
+        assert names[0] == expect_kernel and names[1] == expect_kernel, names
+        assert vs_rounded["forward"] <= U.TOL_FWD, (label, vs_rounded)
+        assert vs_rounded["backward_data"] <= U.TOL_BWD, (label, vs_rounded)
+        # the operands really were rounded: an fp32 computation would be two orders closer
+        assert vs_fp32["forward"] > 2e-5, (label, vs_fp32)
+
+
+@pytest.mark.parametrize("name,nb", [("4a", 1), ("4b", 2), ("4c", 5), ("3b", 3), ("2b", 7), ("2c", 9), ("5b", 3)])
+def test_bf16_workload_layers_reduced_batch(name, nb):
+    check(synth.with_batch(synth.LAYERS[name], nb), "bf16 layer %s at N=%d" % (name, nb))
+
+
+BF_SWEEP = [
+    # H  W  D  N  Hf Wf Df K   stride   pad
+    (23, 17, 16, 3, 3, 3, 16, 40, (1, 1), (1, 1, 1, 1)),     # exactly one MFMA depth of channels
+    (23, 17, 40, 2, 3, 3, 40, 24, (1, 1), (1, 1, 1, 1)),     # 40 channels: a ragged last unit
+    (30, 30, 48, 2, 5, 5, 24, 66, (2, 2), (2, 1, 0, 2)),     # 2 groups, stride 2: four phases in dzdx
+    (19, 21, 32, 2, 7, 7, 32, 33, (3, 2), (3, 3, 3, 3)),     # 49 taps: several tap ranges
+    (64, 9, 64, 2, 1, 1, 64, 130, (1, 1), (0, 0, 0, 0)),     # 1x1
+    (12, 12, 17, 2, 2, 2, 17, 19, (1, 1), (0, 1, 1, 0)),     # odd channel counts
+    (9, 9, 32, 40, 3, 3, 32, 32, (1, 1), (1, 1, 1, 1)),      # many small images per tile
+]
+
+
+@pytest.mark.parametrize("case", range(len(BF_SWEEP)))
+def test_bf16_geometry_sweep(case):
+    H, W, D, N, Hf, Wf, Df, K, st, pad = BF_SWEEP[case]
+    L = custom_layer(H, W, D, N, Hf, Wf, Df, K, st, pad, idx=case)
+    # the input derivative's reduction depth is K per group: below 16 it stays on the fp32 kernel
+    d = B.make_desc(synth.x_shape(L), synth.w_shape(L), st, pad, BF)
+    both = B.mcn_conv_kernel_name(d, 1) == "igemm_bf16"
+    vs_fp32, vs_rounded = run_bf16(L, with_bias=(case % 2 == 0))
+    print("bf16 sweep", case, [B.mcn_conv_kernel_name(d, op) for op in range(3)], vs_fp32, vs_rounded, flush=True)
+    assert B.mcn_conv_kernel_name(d, 0) == "igemm_bf16"
+    for k, v in vs_fp32.items():
+        assert v <= U.TOL_BF16, (case, k, v)
+    assert vs_rounded["forward"] <= U.TOL_FWD
+    if both:
+        assert vs_rounded["backward_data"] <= U.TOL_BWD
+
+
+def test_bf16_few_channels_stay_on_fp32_kernels():
+    # 3 input channels: the bf16 kernel would waste 13 of its 16 reduction lanes; the fp32 kernel
+    # meets the bf16 bound trivially
+    L = synth.with_batch(synth.LAYERS["2a"], 4)
+    check(L, "bf16 precision, 3 channels", expect_kernel=None)
+    d = B.make_desc(synth.x_shape(L), synth.w_shape(L), L["stride"], L["pad"], BF)
+    assert B.mcn_conv_kernel_name(d, 0) == "igemm"
+
+
+@pytest.mark.parametrize("name", ["4a", "4b", "4c"])
+def test_bf16_full_size_sampled(name):
+    """Full benchmark size, sampled outputs against the oracle on the fp32 inputs."""
+    L = synth.LAYERS[name]
+    st, pad = L["stride"], L["pad"]
+    x, w, b = synth.make_x(L), synth.make_w(L), synth.make_b(L)
+    ho, wo = oracle.output_size(x.shape, w.shape, st, pad)
+    p = synth.make_dzdy(L, ho, wo)
+    xg, wg, bg, pg = x.cuda(), w.cuda(), b.cuda(), p.cuda()
+    y = B.conv_forward(xg, wg, bg, st, pad, BF).cpu().numpy().ravel()
+    dx = B.conv_backward_data(x.shape, wg, pg, st, pad, BF).cpu().numpy().ravel()
+    del xg, pg
+    xd, wd, bd, pd = (U.np64(t) for t in (x, w, b, p))
+    xr, wr, pr = (U.np64(rne_bf16(t)) for t in (x, w, p))
+    iy, ix = U.sample_idx(y.size, 3000, 11), U.sample_idx(dx.size, 3000, 12)
+    den_y = oracle.forward_at(np.abs(xd), np.abs(wd), np.abs(bd), iy, st, pad)
+    den_x = oracle.backward_data_at(x.shape, np.abs(wd), np.abs(pd), ix, st, pad)
+    e = {"forward": U.norm_err(y[iy], oracle.forward_at(xd, wd, bd, iy, st, pad), den_y),
+         "backward_data": U.norm_err(dx[ix], oracle.backward_data_at(x.shape, wd, pd, ix, st, pad), den_x),
+         "forward_rounded": U.norm_err(y[iy], oracle.forward_at(xr, wr, bd, iy, st, pad), den_y),
+         "backward_data_rounded": U.norm_err(dx[ix], oracle.backward_data_at(x.shape, wr, pr, ix, st, pad), den_x)}
+    print("bf16 layer %s full size" % name, e, flush=True)
+    assert e["forward"] <= U.TOL_BF16 and e["backward_data"] <= U.TOL_BF16
+    assert e["forward_rounded"] <= U.TOL_FWD and e["backward_data_rounded"] <= U.TOL_BWD
