@@ -392,3 +392,124 @@ inline bool plan_wgrad(const ConvView &v, int n_cu, WgradPlan *pl) {
 }
 
 }  // namespace mcn
+
+// ---- filter derivative with bf16 operands (kern_wgrad_bf16.h) ---------------------------------
+#include "kern_wgrad_bf16.h"
+namespace mcn {
+
+enum WgradBfShape { WGB_128x256 = 0, WGB_64x256 = 1 };
+constexpr int WGB_MAX_HF = 5;      // filter heights with an instantiation
+
+struct WgradBfPlan {
+    int shape;
+    int TK, TR, NT;
+    WgradBfParams P;
+    size_t lds_bytes;
+    size_t partial_floats;   // one TK*TR piece per block when a tile's reduction is shared
+};
+
+// Slab pitches (in 16-byte words): lane r of an operand read addresses word
+// fi*CPF + fj*RGP + c*CPC (+ the same for all lanes); eight consecutive r should fall into eight
+// different 16-byte bank groups.  Smallest pitches with the fewest collisions.
+inline void wgb_pitches(int Hf, int Wf, int TIG, int SC, int *RGP, int *CPF, int *CPC) {
+    const int T = Hf * Wf;
+    long best_cost = -1;
+    for (int a = 0; a < 8; ++a)
+        for (int b = 0; b < 8; ++b)
+            for (int c = 0; c < 8; ++c) {
+                const int rgp = TIG + a, cpf = SC * rgp + b, cpc = Hf * cpf + c;
+                int coll = 0;
+                for (int r0 = 0; r0 < 8 * T; r0 += 8) {
+                    unsigned seen = 0;
+                    for (int r = r0; r < r0 + 8; ++r) {
+                        const int ch = r / T, tap = r % T, fj = tap / Hf, fi = tap % Hf;
+                        seen |= 1u << ((fi * cpf + fj * rgp + ch * cpc) & 7);
+                    }
+                    coll += 8 - __builtin_popcount(seen);
+                }
+                const long cost = (long)coll * 100000 + cpc;
+                if (best_cost < 0 || cost < best_cost) { best_cost = cost; *RGP = rgp; *CPF = cpf; *CPC = cpc; }
+            }
+}
+
+inline bool plan_wgrad_bf16(const ConvView &v, int n_cu, WgradBfPlan *pl) {
+    if (v.Sh != 1 || v.Hf > WGB_MAX_HF || v.Kg <= 32) return false;
+    const int T = v.Hf * v.Wf;
+    const int64_t R64 = (int64_t)T * v.Cg;
+    if (R64 >= ((int64_t)1 << 30)) return false;
+    const int R = (int)R64;
+    if ((double)v.H * v.W * v.Ctot * v.N * 4 >= 2147483647.0) return false;      // 32-bit byte offsets
+    if ((double)v.Ho * v.Wo * v.Ktot * v.N * 4 >= 2147483647.0) return false;
+    const int shape = v.Kg > 64 ? WGB_128x256 : WGB_64x256;
+    const int TK = v.Kg > 64 ? 128 : 64, TR = 256, NT = 512;
+    const int RT = (R + TR - 1) / TR;
+    int NCH = 0;
+    for (int rt = 0; rt < RT; ++rt) {
+        const int lo = rt * TR, hi = (lo + TR < R ? lo + TR : R);
+        const int n = (hi - 1) / T - lo / T + 1;
+        if (n > NCH) NCH = n;
+    }
+    int cand[40], nc = 0;
+    cand[nc++] = v.Ho;
+    for (int parts = 2; parts <= 8; ++parts) cand[nc++] = (v.Ho + parts - 1) / parts;
+    for (int t = 8; t <= 128; t += 8) cand[nc++] = t;
+    double best = 1e300;
+    WgradBfParams B = {};
+    for (int a = 0; a < nc; ++a) {
+        const int TI = cand[a];
+        if (TI < 1 || TI > v.Ho) continue;
+        const int TIG = (TI + 7) / 8;
+        for (int MC = 2; MC <= 32; MC += 2) {
+            const int PW = TIG * MC;
+            if ((int64_t)TK * PW > (int64_t)WGB_YT * NT) break;
+            const int SC = (MC - 1) * v.Sw + v.Wf;
+            if ((int64_t)NCH * SC * TIG > (int64_t)WGB_XT * NT) break;
+            int RGP, CPF, CPC;
+            wgb_pitches(v.Hf, v.Wf, TIG, SC, &RGP, &CPF, &CPC);
+            const int PYW = PW | 1;
+            const size_t lds = 2 * ((size_t)TK * PYW + (size_t)NCH * CPC) * 16;
+            if (lds > IGEMM_LDS_LIMIT) break;
+            const int RB = (v.Ho + TI - 1) / TI, CC = (v.Wo + MC - 1) / MC;
+            const double units = (double)RB * CC * v.N;
+            const double steps = (double)(MC / 2) * TIG;
+            const double cost = units * (steps + 3.0);           // a unit costs about three steps of set-up
+            if (cost < best) {
+                best = cost;
+                B.TI = TI; B.RB = RB; B.TIG = TIG; B.MC = MC; B.CC = CC; B.SC = SC;
+                B.PW = PW; B.PYW = PYW; B.RGP = RGP; B.CPF = CPF; B.CPC = CPC;
+            }
+        }
+    }
+    if (best >= 1e300) return false;
+    WgradBfParams &P = pl->P;
+    P = B;
+    P.H = v.H; P.W = v.W; P.N = v.N; P.Ctot = v.Ctot; P.Cg = v.Cg;
+    P.Ho = v.Ho; P.Wo = v.Wo; P.Ktot = v.Ktot; P.Kg = v.Kg; P.G = v.G;
+    P.Hf = v.Hf; P.Wf = v.Wf; P.Sw = v.Sw; P.Pt = v.Pt; P.Pl = v.Pl;
+    P.NCH = NCH;
+    P.KT = (v.Kg + TK - 1) / TK; P.RT = RT; P.R = R;
+    const int64_t NU = (int64_t)P.RB * P.CC * v.N;
+    const int64_t tiles = (int64_t)v.G * P.KT * RT;
+    if (NU >= ((int64_t)1 << 30) || tiles >= ((int64_t)1 << 20)) return false;
+    P.NU = (int)NU; P.tiles = (int)tiles;
+    // chunks per tile: fill the compute units in as few, as full rounds as possible
+    int best_nch = 1;
+    double best_eff = 0.0;
+    const int64_t max_nch = NU < 4 * (int64_t)n_cu ? NU : 4 * (int64_t)n_cu;
+    for (int64_t nch = 1; nch <= max_nch && nch * tiles <= 4 * (int64_t)n_cu; ++nch) {
+        const int64_t nb = nch * tiles;
+        const int64_t rounds = (nb + n_cu - 1) / n_cu;
+        // a round of chunks costs its units plus a fixed part (set-up, writing the piece)
+        const double time = (double)rounds * ((double)((NU + nch - 1) / nch) + 8.0);
+        const double eff = 1.0 / time;
+        if (eff > best_eff * 1.0000001) { best_eff = eff; best_nch = (int)nch; }
+    }
+    P.nchunks = best_nch;
+    P.nblocks = (int)(tiles * best_nch);
+    pl->shape = shape; pl->TK = TK; pl->TR = TR; pl->NT = NT;
+    pl->lds_bytes = 2 * ((size_t)TK * P.PYW + (size_t)NCH * P.CPC) * 16;
+    pl->partial_floats = P.nchunks > 1 ? (size_t)P.nblocks * TK * TR : 0;
+    return true;
+}
+
+}  // namespace mcn

@@ -99,6 +99,8 @@ struct PlanEntry {
     bool bwd_fill;             // some samples of dzdx belong to no phase with work: zero-fill first
     IgemmPlan bwd[MAX_PHASES];
     WgradPlan wg;
+    bool wgb_ok;               // filter derivative on the bf16 kernel
+    WgradBfPlan wgb;
     bool fc;                   // fully-connected layer: the three passes run as plain matrix products
     WgradPlan fc_fwd;
     IgemmPlan fc_bwd, fc_wg;
@@ -142,6 +144,7 @@ const PlanEntry *plans_for(const mcn_conv_desc *d, const Geom &g) {
             }
     }
     e.wg_ok = on && plan_wgrad(forward_view(g), ncu, &e.wg);
+    e.wgb_ok = on && bf && plan_wgrad_bf16(forward_view(g), ncu, &e.wgb);
     e.fc = on && is_fully_connected(g) && (int64_t)g.H * g.W * g.D < ((int64_t)1 << 30) &&
            plan_wgrad(fc_forward_view(g), ncu, &e.fc_fwd) && plan_igemm(fc_backward_data_view(g), ncu, &e.fc_bwd) &&
            plan_igemm(fc_backward_filter_view(g), ncu, &e.fc_wg);
@@ -260,6 +263,48 @@ int launch_wgrad(const WgradPlan &pl, const float *x, const float *dzdy, const f
     }
 }
 
+template <int WK, int WR, int MK, int MR, int HF>
+int launch_wgrad_bf16_inst(const WgradBfPlan &pl, const float *x, const float *dzdy, float *out, float *part,
+                           hipStream_t s) {
+    auto kern = wgrad_bf16_kernel<WK, WR, MK, MR, HF>;
+    if (pl.lds_bytes > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           (int)pl.lds_bytes);
+        if (e != hipSuccess) { g_last_hip_error = (int)e; return MCN_HIP_ERROR; }
+    }
+    hipLaunchKernelGGL(kern, dim3(wgb_grid(pl.P.nblocks)), dim3(64 * WK * WR), pl.lds_bytes, s, pl.P, x, dzdy, out, part);
+    int st = check_launch();
+    if (st || pl.P.nchunks < 2) return st;
+    constexpr int TK = WK * MK * 32, TR = WR * MR * 32;
+    int fy = 2048 / pl.P.tiles;          // about 2048 blocks in all
+    if (fy < 1) fy = 1;
+    if (fy > TK * TR / 64) fy = TK * TR / 64;
+    hipLaunchKernelGGL((wgrad_bf16_fixup_kernel<TK, TR>), dim3(pl.P.tiles, fy), dim3(512), 0, s, pl.P, part, out);
+    return check_launch();
+}
+
+template <int WK, int WR, int MK, int MR>
+int launch_wgrad_bf16_shape(const WgradBfPlan &pl, const float *x, const float *dzdy, float *out, float *part,
+                            hipStream_t s) {
+    switch (pl.P.Hf) {
+        case 1: return launch_wgrad_bf16_inst<WK, WR, MK, MR, 1>(pl, x, dzdy, out, part, s);
+        case 2: return launch_wgrad_bf16_inst<WK, WR, MK, MR, 2>(pl, x, dzdy, out, part, s);
+        case 3: return launch_wgrad_bf16_inst<WK, WR, MK, MR, 3>(pl, x, dzdy, out, part, s);
+        case 4: return launch_wgrad_bf16_inst<WK, WR, MK, MR, 4>(pl, x, dzdy, out, part, s);
+        case 5: return launch_wgrad_bf16_inst<WK, WR, MK, MR, 5>(pl, x, dzdy, out, part, s);
+        default: return MCN_BAD_ARG;
+    }
+}
+
+int launch_wgrad_bf16(const WgradBfPlan &pl, const float *x, const float *dzdy, float *out, void *ws, hipStream_t s) {
+    float *part = (float *)ws;
+    switch (pl.shape) {
+        case WGB_128x256: return launch_wgrad_bf16_shape<2, 4, 2, 2>(pl, x, dzdy, out, part, s);
+        case WGB_64x256: return launch_wgrad_bf16_shape<2, 4, 1, 2>(pl, x, dzdy, out, part, s);
+        default: return MCN_BAD_ARG;
+    }
+}
+
 size_t workspace_bytes(const mcn_conv_desc *d, const Geom &g, int op) {
     const PlanEntry *e = plans_for(d, g);
     switch (op) {
@@ -279,6 +324,7 @@ size_t workspace_bytes(const mcn_conv_desc *d, const Geom &g, int op) {
         }
         case MCN_OP_BACKWARD_FILTER:
             if (e->fc) return igemm_ws_bytes(e->fc_wg);
+            if (e->wgb_ok) return e->wgb.partial_floats * sizeof(float);
             return e->wg_ok ? e->wg.partial_floats * sizeof(float) : 0;
         default:
             return 0;
@@ -343,6 +389,7 @@ int run_backward_filter(const mcn_conv_desc *desc, const Geom &g, const float *x
     if (ws_bytes < need || (!ws && need)) return MCN_WORKSPACE_TOO_SMALL;
     const PlanEntry *pe = plans_for(desc, g);
     if (pe->fc) return launch_igemm(pe->fc_wg, x, dzdy, nullptr, dzdw, ws, s);
+    if (pe->wgb_ok) return launch_wgrad_bf16(pe->wgb, x, dzdy, dzdw, ws, s);
     if (pe->wg_ok) return launch_wgrad(pe->wg, x, dzdy, nullptr, dzdw, ws, s);
     const int total = (int)numel_w(g);
     hipLaunchKernelGGL(direct_backward_filter_kernel, dim3(cdiv(total, 4)), dim3(256), 0, s, g, x, dzdy, dzdw, total);
@@ -429,7 +476,7 @@ const char *mcn_conv_kernel_name(const mcn_conv_desc *desc, int op) {
         case MCN_OP_FORWARD: return e->fc ? "fc_gemm" : e->fwd_ok ? (e->fwd.bf16 ? "igemm_bf16" : "igemm") : "direct";
         case MCN_OP_BACKWARD_DATA:
             return e->fc ? "fc_gemm" : e->bwd_ok ? (e->n_bwd && e->bwd[0].bf16 ? "igemm_bf16" : "igemm") : "direct";
-        case MCN_OP_BACKWARD_FILTER: return e->fc ? "fc_gemm" : e->wg_ok ? "wgrad_igemm" : "direct";
+        case MCN_OP_BACKWARD_FILTER: return e->fc ? "fc_gemm" : e->wgb_ok ? "wgrad_bf16" : e->wg_ok ? "wgrad_igemm" : "direct";
         case MCN_OP_BACKWARD_BIAS: return plan_bias(g).rows ? "reduce_rows" : "reduce2";
         default: return NULL;
     }

@@ -49,8 +49,16 @@ def run_bf16(L, with_bias=True, seed=0):
                "backward_data": U.norm_err(dx, oracle.backward_data(x.shape, wd, pd, st, pad), den_x),
                "backward_filter": U.norm_err(dw, oracle.backward_filter(xd, w.shape, pd, st, pad), den_w)}
     vs_rounded = {"forward": U.norm_err(y, oracle.forward(xr, wr, bb, st, pad), den_y),
-                  "backward_data": U.norm_err(dx, oracle.backward_data(x.shape, wr, pr, st, pad), den_x)}
+                  "backward_data": U.norm_err(dx, oracle.backward_data(x.shape, wr, pr, st, pad), den_x),
+                  "backward_filter": U.norm_err(dw, oracle.backward_filter(xr, w.shape, pr, st, pad), den_w)}
     return vs_fp32, vs_rounded
+
+
+def check_filter_derivative(names, vs_fp32, vs_rounded, label):
+    """On the bf16 kernel the filter derivative is the exact sum over rounded x and dzdy."""
+    if names[2] == "wgrad_bf16":
+        assert vs_rounded["backward_filter"] <= U.TOL_BWD, (label, vs_rounded)
+        assert vs_fp32["backward_filter"] > 1e-6, (label, vs_fp32)
 
 
 def check(L, label, with_bias=True, expect_kernel="igemm_bf16"):
@@ -67,6 +75,7 @@ def check(L, label, with_bias=True, expect_kernel="igemm_bf16"):
         assert vs_rounded["backward_data"] <= U.TOL_BWD, (label, vs_rounded)
         # the operands really were rounded: an fp32 computation would be two orders closer
         assert vs_fp32["forward"] > 2e-5, (label, vs_fp32)
+    check_filter_derivative(names, vs_fp32, vs_rounded, label)
 
 
 @pytest.mark.parametrize("name,nb", [("4a", 1), ("4b", 2), ("4c", 5), ("3b", 3), ("2b", 7), ("2c", 9), ("5b", 3)])
@@ -101,6 +110,37 @@ def test_bf16_geometry_sweep(case):
     assert vs_rounded["forward"] <= U.TOL_FWD
     if both:
         assert vs_rounded["backward_data"] <= U.TOL_BWD
+    check_filter_derivative([B.mcn_conv_kernel_name(d, op) for op in range(3)], vs_fp32, vs_rounded, "sweep %d" % case)
+
+
+WG_SWEEP = [
+    # H  W  D  N  Hf Wf Df K   stride   pad                     expected filter-derivative kernel
+    (14, 14, 32, 5, 3, 3, 32, 64, (1, 1), (1, 1, 1, 1), "wgrad_bf16"),     # 14 rows: a partial octet in every patch
+    (23, 9, 24, 3, 3, 3, 24, 40, (1, 1), (1, 1, 1, 1), "wgrad_bf16"),      # odd width: a patch with a missing column
+    (30, 31, 16, 2, 5, 5, 8, 66, (1, 2), (2, 2, 1, 3), "wgrad_bf16"),      # two groups, horizontal stride 2
+    (40, 12, 8, 3, 1, 1, 8, 130, (1, 1), (0, 0, 0, 0), "wgrad_bf16"),      # 1x1
+    (17, 20, 6, 2, 2, 4, 6, 48, (1, 3), (0, 1, 2, 0), "wgrad_bf16"),       # even filter height, stride 3 across
+    (19, 19, 12, 2, 4, 2, 12, 100, (1, 1), (3, 0, 0, 1), "wgrad_bf16"),
+    (70, 6, 4, 2, 3, 3, 4, 36, (1, 1), (0, 0, 0, 0), "wgrad_bf16"),        # no padding, tall plane: several row blocks
+    (9, 9, 16, 70, 3, 3, 16, 64, (1, 1), (1, 1, 1, 1), "wgrad_bf16"),      # many images: several chunks per tile
+    (20, 20, 16, 2, 3, 3, 16, 24, (1, 1), (1, 1, 1, 1), "wgrad_igemm"),    # 24 filters: stays on the fp32 kernel
+    (20, 20, 16, 2, 3, 3, 16, 64, (2, 1), (1, 1, 1, 1), "wgrad_igemm"),    # vertical stride: stays on the fp32 kernel
+    (30, 30, 8, 2, 7, 7, 8, 64, (1, 1), (3, 3, 3, 3), "wgrad_igemm"),      # 7 filter rows: stays on the fp32 kernel
+]
+
+
+@pytest.mark.parametrize("case", range(len(WG_SWEEP)))
+def test_bf16_filter_derivative_sweep(case):
+    H, W, D, N, Hf, Wf, Df, K, st, pad, kernel = WG_SWEEP[case]
+    L = custom_layer(H, W, D, N, Hf, Wf, Df, K, st, pad, idx=50 + case)
+    d = B.make_desc(synth.x_shape(L), synth.w_shape(L), st, pad, BF)
+    names = [B.mcn_conv_kernel_name(d, op) for op in range(3)]
+    assert names[2] == kernel, names
+    vs_fp32, vs_rounded = run_bf16(L)
+    print("bf16 filter derivative", case, names, vs_fp32, vs_rounded, flush=True)
+    for k, v in vs_fp32.items():
+        assert v <= U.TOL_BF16, (case, k, v)
+    check_filter_derivative(names, vs_fp32, vs_rounded, "filter derivative %d" % case)
 
 
 def test_bf16_few_channels_stay_on_fp32_kernels():
@@ -123,6 +163,7 @@ def test_bf16_full_size_sampled(name):
     xg, wg, bg, pg = x.cuda(), w.cuda(), b.cuda(), p.cuda()
     y = B.conv_forward(xg, wg, bg, st, pad, BF).cpu().numpy().ravel()
     dx = B.conv_backward_data(x.shape, wg, pg, st, pad, BF).cpu().numpy().ravel()
+    dw = B.conv_backward_filter(xg, w.shape, pg, st, pad, BF).cpu().numpy().ravel()
     del xg, pg
     xd, wd, bd, pd = (U.np64(t) for t in (x, w, b, p))
     xr, wr, pr = (U.np64(rne_bf16(t)) for t in (x, w, p))
@@ -133,6 +174,11 @@ def test_bf16_full_size_sampled(name):
          "backward_data": U.norm_err(dx[ix], oracle.backward_data_at(x.shape, wd, pd, ix, st, pad), den_x),
          "forward_rounded": U.norm_err(y[iy], oracle.forward_at(xr, wr, bd, iy, st, pad), den_y),
          "backward_data_rounded": U.norm_err(dx[ix], oracle.backward_data_at(x.shape, wr, pr, ix, st, pad), den_x)}
+    iw = U.sample_idx(dw.size, 64, 13)
+    den_w = oracle.backward_filter_at(np.abs(xd), w.shape, np.abs(pd), iw, st, pad)
+    e["backward_filter"] = U.norm_err(dw[iw], oracle.backward_filter_at(xd, w.shape, pd, iw, st, pad), den_w)
+    e["backward_filter_rounded"] = U.norm_err(dw[iw], oracle.backward_filter_at(xr, w.shape, pr, iw, st, pad), den_w)
     print("bf16 layer %s full size" % name, e, flush=True)
+    assert e["backward_filter"] <= U.TOL_BF16 and e["backward_filter_rounded"] <= U.TOL_BWD
     assert e["forward"] <= U.TOL_BF16 and e["backward_data"] <= U.TOL_BF16
     assert e["forward_rounded"] <= U.TOL_FWD and e["backward_data_rounded"] <= U.TOL_BWD
