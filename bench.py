@@ -25,6 +25,7 @@ from paper_1412_4564_amd import binding as B
 from paper_1412_4564_amd import synth
 
 FP32_MFMA_PEAK_TFLOPS = 157.3     # 256 CU x 256 flop/clk x 2.4 GHz
+BF16_MFMA_PEAK_TFLOPS = 2500.0    # dense bf16 MFMA (kernels named *_bf16 run on it)
 HBM_PEAK_GBS = 8000.0
 
 WORKLOADS = {"vgg3x3": ["4a", "4b", "4c"]}
@@ -259,8 +260,9 @@ def main():
             detail["%s.%s" % (Ls.name, OPS[o])] = e
     if op < 3:
         ach = 2.0 * dom.macs / per[li, op] / 1e9
-        roof = {"bound": "mfma", "achieved": round(ach, 2), "peak": FP32_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-                "frac": round(ach / FP32_MFMA_PEAK_TFLOPS, 4),
+        peak = BF16_MFMA_PEAK_TFLOPS if "bf16" in dom.kernels[op] else FP32_MFMA_PEAK_TFLOPS
+        roof = {"bound": "mfma", "achieved": round(ach, 2), "peak": peak, "unit": "TFLOP/s",
+                "frac": round(ach / peak, 4),
                 "traffic": measured_traffic("%s.%s" % (dom.name, OPS[op])) if args.workload == "vgg3x3" else None,
                 "kernel": "%s.%s (%s)" % (dom.name, OPS[op], dom.kernels[op])}
     else:
@@ -271,7 +273,7 @@ def main():
                 "kernel": "%s.%s (%s)" % (dom.name, OPS[op], dom.kernels[op])}
 
     out = {
-        "metric": "conv fwd+bwd TFLOP/s (fp32) on VGG-style 3x3 layers",
+        "metric": "conv fwd+bwd TFLOP/s (%s) on VGG-style 3x3 layers" % ("fp32" if prec == B.MCN_PREC_FP32 else "bf16 operands, fp32 accumulation"),
         "value": round(value, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32" if prec == B.MCN_PREC_FP32 else "bf16-in/f32-acc", "data": "synthetic",
@@ -279,7 +281,7 @@ def main():
                                " (3x3 stride 1 pad 1, N=32)" if args.workload == "vgg3x3" else
                                "conv fwd+bwd of layers " + ",".join(names),
                    "layers": {Ls.name: Ls.shape_info() for Ls in layers}},
-        "frac_of_fp32_mfma_peak": round(value / FP32_MFMA_PEAK_TFLOPS, 4),
+        "frac_of_fp32_mfma_peak": round(value / FP32_MFMA_PEAK_TFLOPS, 4) if prec == B.MCN_PREC_FP32 else None,
         "roofline": roof,
         "calls": detail,
     }

@@ -58,8 +58,14 @@ typedef struct mcn_conv_desc {
 } mcn_conv_desc;
 
 enum { MCN_PREC_FP32 = 0,   /* fp32 operands, fp32 accumulation                        */
-       MCN_PREC_BF16 = 1 }; /* operands rounded to bf16 on chip, fp32 accumulation;
-                               arrays in memory stay fp32                              */
+       MCN_PREC_BF16 = 1 }; /* operands (x, w, dzdy) rounded to bf16 on chip, round to
+                               nearest even, products accumulated in fp32; arrays in
+                               memory stay fp32.  Normalised error <= 1e-2.  Geometries
+                               the bf16 kernels do not cover (fewer than 16 channels per
+                               group, fully-connected layers, the filter derivative with
+                               a vertical stride, more than 5 filter rows or at most 32
+                               filters per group) and the bias derivative compute in
+                               fp32, which meets the same bound.                      */
 
 typedef enum mcn_status {
     MCN_OK = 0,

@@ -160,7 +160,7 @@ inline bool cut_units_bf16(const ConvView &v, int TK, int64_t CP, size_t lds_lef
     for (int NTR = 1; NTR <= T; ++NTR) {
         const int TC = (T + NTR - 1) / NTR;
         if ((int64_t)(NTR - 1) * TC >= T) continue;
-        const size_t lds = 2 * ((size_t)TC * 2 * TK + 2 * (size_t)CP) * 16 + (size_t)NTR * TC * 4;
+        const size_t lds = 2 * ((size_t)TC * 2 * TK + 2 * (size_t)CP) * 16;
         if (lds > lds_left) continue;
         uc->pair_mode = 0; uc->DC = BF_DC; uc->TC = TC; uc->NTR = NTR; uc->NS = TC;
         return true;
@@ -256,7 +256,7 @@ inline bool plan_igemm(const ConvView &v, int n_cu, IgemmPlan *pl, bool bf16 = f
     pl->partial_floats = P.nblocks > 1 ? (size_t)2 * P.nblocks * TK * TQ : 0;
     pl->shape = shape; pl->bf16 = bf16; pl->fixed33 = fixed33; pl->TK = TK; pl->TQ = TQ; pl->NT = NT;
     if (bf16)
-        pl->lds_bytes = (2 * wsz + 2 * (size_t)2 * P.CP * 4 + (size_t)P.EPT * NT + 2 * TK + (size_t)P.NTR * P.NS + 4) *
+        pl->lds_bytes = (2 * wsz + 2 * (size_t)2 * P.CP * 4 + (size_t)P.EPT * NT + 2 * TK + 4) *
                         sizeof(float);
     else
         pl->lds_bytes = (2 * wsz + 2 * (size_t)P.DC * P.CP + (size_t)P.EPT * NT + 2 * TK +
@@ -453,6 +453,8 @@ inline bool plan_wgrad_bf16(const ConvView &v, int n_cu, WgradBfPlan *pl) {
     cand[nc++] = v.Ho;
     for (int parts = 2; parts <= 8; ++parts) cand[nc++] = (v.Ho + parts - 1) / parts;
     for (int t = 8; t <= 128; t += 8) cand[nc++] = t;
+    const bool streams_from_memory =
+        4.0 * ((double)v.H * v.W * v.Ctot + (double)v.Ho * v.Wo * v.Ktot) * v.N > 64.0 * 1024 * 1024;
     double best = 1e300;
     WgradBfParams B = {};
     for (int a = 0; a < nc; ++a) {
@@ -472,7 +474,9 @@ inline bool plan_wgrad_bf16(const ConvView &v, int n_cu, WgradBfPlan *pl) {
             const int RB = (v.Ho + TI - 1) / TI, CC = (v.Wo + MC - 1) / MC;
             const double units = (double)RB * CC * v.N;
             const double steps = (double)(MC / 2) * TIG;
-            const double cost = units * (steps + 3.0);           // a unit costs about three steps of set-up
+            // a unit costs about three steps of set-up; when the arrays do not fit the caches, short
+            // column segments waste most of every 128-byte line they touch
+            const double cost = units * (steps + 3.0) * (streams_from_memory ? 1.0 + 16.0 / TI : 1.0);
             if (cost < best) {
                 best = cost;
                 B.TI = TI; B.RB = RB; B.TIG = TIG; B.MC = MC; B.CC = CC; B.SC = SC;

@@ -97,7 +97,6 @@ __global__ __launch_bounds__(64 * WK * WP, WPE) void igemm_bf16_kernel(IgemmPara
     float *xbuf = lds + 2 * WSZ;                         // [2][XSZ]
     int *gtab = reinterpret_cast<int *>(xbuf + 2 * XSZ); // [EPT][NT]: entry (s, tid) is private to thread tid
     float *blds = reinterpret_cast<float *>(gtab + P.EPT * NT);   // [2][TK] bias of the tile, by tile parity
-    int *otab = reinterpret_cast<int *>(blds + 2 * TK);           // [NTR][NS] slab byte offsets of the taps
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -111,15 +110,6 @@ __global__ __launch_bounds__(64 * WK * WP, WPE) void igemm_bf16_kernel(IgemmPara
     const long long total = (long long)P.tiles * NU;
     const long long ub = sk_begin(total, P.nblocks, vb), ue = sk_begin(total, P.nblocks, vb + 1);
     if (ub >= ue) return;
-
-    {
-        const int T = P.Hf * P.Wf;
-        for (int idx = tid; idx < P.NTR * NS; idx += NT) {
-            const int s = idx % NS, tr = idx / NS;
-            const int tap = tr * P.TC + s;
-            otab[idx] = (s < P.TC && tap < T) ? 16 * ((tap / P.Hf) * SRP + tap % P.Hf) : 0;
-        }
-    }
 
     const buffer_rsrc wrs = make_rsrc(wpk, P.packed_bytes);
     const buffer_rsrc brs = make_rsrc(bias, bias ? (unsigned)P.Ktot * 4u : 0u);
@@ -171,16 +161,24 @@ __global__ __launch_bounds__(64 * WK * WP, WPE) void igemm_bf16_kernel(IgemmPara
                                 kl < P.Kg ? (unsigned)(l_g * P.Kg + kl) * 4u : SLAB_INVALID, brs, 0);
         }
         const int c0 = (uu / P.NTR) * BF_DC;
+        const bool full = c0 + BF_DC <= P.Cg;
 #pragma unroll
         for (int s = 0; s < BF_EPT_MAX; ++s) {
             if (s < P.EPT && wave * 64 + NT * s < CP) {
                 const unsigned go = (unsigned)gtab[s * NT + tid];
+                if (full) {
 #pragma unroll
-                for (int d = 0; d < BF_DC; ++d) {
-                    const int c = c0 + d;
-                    // channels past the group's last one read as zero (their weights are zero too)
-                    stg[s][d] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(
-                        xrs, c < P.Cg ? go : SLAB_INVALID, (unsigned)c * (unsigned)HW * 4u, 0));
+                    for (int d = 0; d < BF_DC; ++d)
+                        stg[s][d] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(
+                            xrs, go, (unsigned)(c0 + d) * (unsigned)HW * 4u, 0));
+                } else {
+#pragma unroll
+                    for (int d = 0; d < BF_DC; ++d) {
+                        const int c = c0 + d;
+                        // channels past the group's last one read as zero (their weights are zero too)
+                        stg[s][d] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(
+                            xrs, c < P.Cg ? go : SLAB_INVALID, (unsigned)c * (unsigned)HW * 4u, 0));
+                    }
                 }
             }
         }
@@ -257,16 +255,30 @@ __global__ __launch_bounds__(64 * WK * WP, WPE) void igemm_bf16_kernel(IgemmPara
             }
     };
     const int aoff = 16 * (half * TK + wk * MK * 32 + (lane & 31));   // bytes
+    // One step per tap of the unit's tap range.  The slab offset of the tap is kept in scalar registers
+    // (fi, fj run along; a step past the filter's last tap has zero weights and reads offset 0), the
+    // operands of step s+1 are requested before the MFMAs of step s, and the loop body has no branches
+    // so that the waits inserted for the LDS reads are exact.
     auto compute = [&](int uu, int b) {
         const char *wl = reinterpret_cast<const char *>(wbuf + b * WSZ) + aoff;
         const char *xl = reinterpret_cast<const char *>(xbuf + b * XSZ);
-        const int *ot = otab + (uu % P.NTR) * NS;
+        const int T = P.Hf * P.Wf;
+        int tap = (uu % P.NTR) * P.TC;
+        int fj = tap / P.Hf, fi = tap - fj * P.Hf;
+        int so = 16 * (fj * SRP + fi);                   // byte offset of the current tap in the slab
         bf16x8 a0[MK], b0[MP], a1[MK], b1[MP];
-        auto fetch = [&](bf16x8 *a, bf16x8 *bq, int s, int o) {
+        auto fetch = [&](bf16x8 *a, bf16x8 *bq) {
 #pragma unroll
-            for (int mk = 0; mk < MK; ++mk) a[mk] = *reinterpret_cast<const bf16x8 *>(wl + (s * 2 * TK + mk * 32) * 16);
+            for (int mk = 0; mk < MK; ++mk) a[mk] = *reinterpret_cast<const bf16x8 *>(wl + mk * 32 * 16);
 #pragma unroll
-            for (int mp = 0; mp < MP; ++mp) bq[mp] = *reinterpret_cast<const bf16x8 *>(xl + bbase[mp] + o);
+            for (int mp = 0; mp < MP; ++mp) bq[mp] = *reinterpret_cast<const bf16x8 *>(xl + bbase[mp] + so);
+            wl += 2 * TK * 16;
+            // next tap (all scalar)
+            ++tap;
+            const bool wrap = ++fi == P.Hf;
+            so += wrap ? 16 * (SRP - P.Hf + 1) : 16;
+            if (wrap) fi = 0;
+            if (tap >= T) so = 0;
         };
         auto mma = [&](const bf16x8 *a, const bf16x8 *bq) {
 #pragma unroll
@@ -275,16 +287,24 @@ __global__ __launch_bounds__(64 * WK * WP, WPE) void igemm_bf16_kernel(IgemmPara
                 for (int mp = 0; mp < MP; ++mp)
                     acc[mk][mp] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mk], bq[mp], acc[mk][mp], 0, 0, 0);
         };
-        fetch(a0, b0, 0, ot[0]);
-        for (int s = 0; s < NS; s += 2) {
-            if (s + 1 < NS) fetch(a1, b1, s + 1, ot[s + 1]);
+        fetch(a0, b0);
+        for (int s = 2; s < NS; s += 2) {        // steps s-2 and s-1, with s-1 and s in flight
+            fetch(a1, b1);
             __builtin_amdgcn_sched_barrier(0);
             mma(a0, b0);
             __builtin_amdgcn_sched_barrier(0);
-            if (s + 2 < NS) fetch(a0, b0, s + 2, ot[s + 2]);
+            fetch(a0, b0);
             __builtin_amdgcn_sched_barrier(0);
-            if (s + 1 < NS) mma(a1, b1);
+            mma(a1, b1);
             __builtin_amdgcn_sched_barrier(0);
+        }
+        if (NS & 1) {
+            mma(a0, b0);
+        } else {
+            fetch(a1, b1);
+            __builtin_amdgcn_sched_barrier(0);
+            mma(a0, b0);
+            mma(a1, b1);
         }
     };
     auto store_tile = [&]() {

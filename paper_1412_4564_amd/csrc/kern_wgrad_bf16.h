@@ -266,16 +266,25 @@ __global__ __launch_bounds__(64 * WK * WR, 2) void wgrad_bf16_kernel(WgradBfPara
                 for (int mr = 0; mr < MR; ++mr)
                     acc[mk][mr] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mk], bq[mr], acc[mk][mr], 0, 0, 0);
         };
+        // no branches inside the loop, so that the waits inserted for the LDS reads are exact
         fetch(a0, b0);
-        for (int s = 0; s < nsteps; s += 2) {
-            if (s + 1 < nsteps) fetch(a1, b1);
+        for (int s = 2; s < nsteps; s += 2) {        // steps s-2 and s-1, with s-1 and s in flight
+            fetch(a1, b1);
             __builtin_amdgcn_sched_barrier(0);
             mma(a0, b0);
             __builtin_amdgcn_sched_barrier(0);
-            if (s + 2 < nsteps) fetch(a0, b0);
+            fetch(a0, b0);
             __builtin_amdgcn_sched_barrier(0);
-            if (s + 1 < nsteps) mma(a1, b1);
+            mma(a1, b1);
             __builtin_amdgcn_sched_barrier(0);
+        }
+        if (nsteps & 1) {
+            mma(a0, b0);
+        } else {
+            fetch(a1, b1);
+            __builtin_amdgcn_sched_barrier(0);
+            mma(a0, b0);
+            mma(a1, b1);
         }
     };
 
