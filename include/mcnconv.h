@@ -115,6 +115,30 @@ int mcn_conv_backward_bias(const mcn_conv_desc *desc, const float *dzdy, float *
                            void *ws, size_t ws_bytes, void *stream);
 
 /* ------------------------------------------------------------------------
+ * Convolution followed by the ReLU block (Sec. 4.4, y = max{0, p}), fused
+ * ------------------------------------------------------------------------
+ * A network that follows a convolution by a ReLU otherwise writes the
+ * convolution's output, reads it back and writes it again; these two calls
+ * save that pass in each direction.
+ *
+ * Forward:  y = max(0, x * w + b), i.e. mcn_conv_forward with the maximum
+ * applied as the results are written.  Same arguments, workspace and errors
+ * as mcn_conv_forward. */
+int mcn_conv_relu_forward(const mcn_conv_desc *desc, const float *x, const float *w, const float *b,
+                          float *y, void *ws, size_t ws_bytes, void *stream);
+
+/* Backward through that ReLU, fused with the bias derivative (Sec. 6.4.1:
+ * dz/dp = [p > 0] dz/dy, and y > 0 exactly where p > 0):
+ *     dzdp[i'',j'',k,n] = dzdy[i'',j'',k,n] if y[i'',j'',k,n] > 0, else 0
+ *     dzdb[k]           = sum_{i'',j'',n} dzdp[i'',j'',k,n]
+ * y is the array mcn_conv_relu_forward wrote, dzdy the derivative with
+ * respect to it; dzdp (same shape) is what mcn_conv_backward_data and
+ * mcn_conv_backward_filter then take as their dzdy.  dzdp may be the same
+ * array as dzdy (in place).  Workspace: that of MCN_OP_BACKWARD_BIAS. */
+int mcn_conv_relu_backward_bias(const mcn_conv_desc *desc, const float *y, const float *dzdy,
+                                float *dzdp, float *dzdb, void *ws, size_t ws_bytes, void *stream);
+
+/* ------------------------------------------------------------------------
  * Convolution transpose (Sec. 4.2; derivation Sec. 6.2; output size Sec. 5.3)
  * ------------------------------------------------------------------------
  * Arrays (first index fastest, fp32, device pointers, as above):

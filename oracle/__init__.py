@@ -38,9 +38,10 @@ class _Geom(ctypes.Structure):
 
 
 def build(force: bool = False) -> str:
-    """Compile every C file of the oracle (this block's and the convolution transpose's)."""
-    from . import convt
+    """Compile every C file of the oracle (this block's, the convolution transpose's and the ReLU's)."""
+    from . import convt, relu
     convt.build(force)
+    relu.build(force)
     return compile_shared(_SRC, _LIB, force)
 
 

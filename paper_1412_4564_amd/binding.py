@@ -26,7 +26,7 @@ MCN_PREC_FP32, MCN_PREC_BF16 = 0, 1
 EXPORTS = (
     "mcn_conv_output_size", "mcn_conv_workspace_size", "mcn_conv_forward", "mcn_conv_backward_data",
     "mcn_conv_backward_filter", "mcn_conv_backward_bias", "mcn_status_string", "mcn_last_hip_error",
-    "mcn_conv_kernel_name",
+    "mcn_conv_kernel_name", "mcn_conv_relu_forward", "mcn_conv_relu_backward_bias",
     "mcn_convt_output_size", "mcn_convt_workspace_size", "mcn_convt_forward", "mcn_convt_backward_data",
     "mcn_convt_backward_filter", "mcn_convt_backward_bias", "mcn_convt_kernel_name",
 )
@@ -80,6 +80,10 @@ def lib():
         L.mcn_last_hip_error.restype = ctypes.c_int
         L.mcn_conv_kernel_name.argtypes = [D, ctypes.c_int]
         L.mcn_conv_kernel_name.restype = ctypes.c_char_p
+        L.mcn_conv_relu_forward.argtypes = [D, P, P, P, P, P, SZ, P]
+        L.mcn_conv_relu_backward_bias.argtypes = [D, P, P, P, P, P, SZ, P]
+        L.mcn_conv_relu_forward.restype = ctypes.c_int
+        L.mcn_conv_relu_backward_bias.restype = ctypes.c_int
         T = ctypes.POINTER(mcn_convt_desc)
         L.mcn_convt_output_size.argtypes = [T, I32P, I32P]
         L.mcn_convt_workspace_size.argtypes = [T, ctypes.c_int, ctypes.POINTER(SZ)]
@@ -142,6 +146,14 @@ def mcn_conv_backward_filter(desc, x, dzdy, dzdw, ws, ws_bytes, stream):
 
 def mcn_conv_backward_bias(desc, dzdy, dzdb, ws, ws_bytes, stream):
     return lib().mcn_conv_backward_bias(ctypes.byref(desc), dzdy, dzdb, ws, ws_bytes, stream)
+
+
+def mcn_conv_relu_forward(desc, x, w, b, y, ws, ws_bytes, stream):
+    return lib().mcn_conv_relu_forward(ctypes.byref(desc), x, w, b, y, ws, ws_bytes, stream)
+
+
+def mcn_conv_relu_backward_bias(desc, y, dzdy, dzdp, dzdb, ws, ws_bytes, stream):
+    return lib().mcn_conv_relu_backward_bias(ctypes.byref(desc), y, dzdy, dzdp, dzdb, ws, ws_bytes, stream)
 
 
 def make_convt_desc(xshape, fshape, upsample=(1, 1), crop=(0, 0, 0, 0), groups=1, precision=MCN_PREC_FP32):
@@ -283,6 +295,44 @@ def conv_backward_bias(xshape, wshape, dzdy, stride=(1, 1), pad=(0, 0, 0, 0), ou
     if st:
         raise McnError(st, "mcn_conv_backward_bias")
     return dzdb
+
+
+# ---- convolution + ReLU ----
+def conv_relu_forward(x, w, b=None, stride=(1, 1), pad=(0, 0, 0, 0), precision=MCN_PREC_FP32, out=None, workspace=None):
+    import torch
+    _check(x, None, "x"); _check(w, None, "w")
+    desc = make_desc(x.shape, w.shape, stride, pad, precision)
+    ho, wo = mcn_conv_output_size(desc)
+    if b is not None:
+        _check(b, (w.shape[0],), "b")
+    ysh = (x.shape[0], w.shape[0], wo, ho)
+    y = out if out is not None else torch.empty(ysh, dtype=torch.float32, device=x.device)
+    _check(y, ysh, "out")
+    wsp, wsn = (workspace or _default_ws).get(mcn_conv_workspace_size(desc, MCN_OP_FORWARD), x.device)
+    st = mcn_conv_relu_forward(desc, x.data_ptr(), w.data_ptr(), None if b is None else b.data_ptr(), y.data_ptr(),
+                               wsp, wsn, _stream())
+    if st:
+        raise McnError(st, "mcn_conv_relu_forward")
+    return y
+
+
+def conv_relu_backward_bias(xshape, wshape, y, dzdy, stride=(1, 1), pad=(0, 0, 0, 0), out=None, inplace=False,
+                            workspace=None):
+    """Returns (dzdp, dzdb); with inplace=True dzdp overwrites dzdy."""
+    import torch
+    desc = make_desc(xshape, wshape, stride, pad)
+    ho, wo = mcn_conv_output_size(desc)
+    ysh = (xshape[0], wshape[0], wo, ho)
+    _check(y, ysh, "y"); _check(dzdy, ysh, "dzdy")
+    dzdp = dzdy if inplace else (out if out is not None else torch.empty_like(dzdy))
+    _check(dzdp, ysh, "out")
+    dzdb = torch.empty((wshape[0],), dtype=torch.float32, device=dzdy.device)
+    wsp, wsn = (workspace or _default_ws).get(mcn_conv_workspace_size(desc, MCN_OP_BACKWARD_BIAS), dzdy.device)
+    st = mcn_conv_relu_backward_bias(desc, y.data_ptr(), dzdy.data_ptr(), dzdp.data_ptr(), dzdb.data_ptr(), wsp, wsn,
+                                     _stream())
+    if st:
+        raise McnError(st, "mcn_conv_relu_backward_bias")
+    return dzdp, dzdb
 
 
 # ---- convolution transpose ----

@@ -13,7 +13,7 @@ namespace mcn {
 __global__ __launch_bounds__(256) void direct_forward_kernel(Geom g, const float *__restrict__ x,
                                                              const float *__restrict__ w,
                                                              const float *__restrict__ b,
-                                                             float *__restrict__ y, int total) {
+                                                             float *__restrict__ y, int total, int relu) {
     int idx = blockIdx.x * 256 + threadIdx.x;
     if (idx >= total) return;
     int io = idx % g.Ho;
@@ -38,7 +38,7 @@ __global__ __launch_bounds__(256) void direct_forward_kernel(Geom g, const float
             }
         }
     }
-    y[idx] = acc;
+    y[idx] = relu ? fmaxf(acc, 0.f) : acc;
 }
 
 // dzdx[i,j,d,n] = sum over k in group(d), and all (io,fi), (jo,fj) with
@@ -162,6 +162,51 @@ __global__ __launch_bounds__(256) void bias_partial_kernel(const float *__restri
     if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = acc;
     __syncthreads();
     if (threadIdx.x == 0) part[(size_t)k * S + s] = (red[0] + red[1]) + (red[2] + red[3]);
+}
+
+// ---- ReLU mask fused with the bias derivative ------------------------------------------------------
+// Sec. 6.4.1 of the manual: through y = max(0, p) the derivative is dz/dp = [p > 0] dz/dy, and
+// y > 0 exactly where p > 0.  One pass reads y and dzdy, writes dzdp = [y > 0] * dzdy (the derivative
+// that the convolution's own backward passes take) and sums it per filter (dzdb).  Same two stages,
+// same unit order as bias_partial_kernel.  dzdp may be the array dzdy (each element is read, then
+// written, by one thread).
+__global__ __launch_bounds__(256) void relu_bias_partial_kernel(const float *__restrict__ y, const float *dzdy,
+                                                                float *dzdp, float *__restrict__ part, int HoWo,
+                                                                int K, int N, int chunks, int S) {
+    const int k = blockIdx.x, s = blockIdx.y;
+    const int units = N * chunks;
+    float acc = 0.f;
+    for (int u = s; u < units; u += S) {
+        const int n = u / chunks, c = u - n * chunks;
+        const size_t base = ((size_t)n * K + k) * HoWo;
+        const int lo = c * BIAS_CHUNK;
+        const int hi = min(lo + BIAS_CHUNK, HoWo);
+        for (int e = lo + threadIdx.x; e < hi; e += 256) {
+            const float m = y[base + e] > 0.f ? dzdy[base + e] : 0.f;
+            dzdp[base + e] = m;
+            acc += m;
+        }
+    }
+    __shared__ float red[4];
+    acc = wave_sum(acc);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) part[(size_t)k * S + s] = (red[0] + red[1]) + (red[2] + red[3]);
+}
+// small output planes: as bias_rows_partial_kernel
+__global__ __launch_bounds__(256) void relu_bias_rows_partial_kernel(const float *__restrict__ y, const float *dzdy,
+                                                                     float *dzdp, float *__restrict__ part,
+                                                                     int KHoWo, int N, int S) {
+    const int e = blockIdx.x * 256 + threadIdx.x, s = blockIdx.y;
+    if (e >= KHoWo) return;
+    float acc = 0.f;
+    for (int n = s; n < N; n += S) {
+        const size_t a = (size_t)n * KHoWo + e;
+        const float m = y[a] > 0.f ? dzdy[a] : 0.f;
+        dzdp[a] = m;
+        acc += m;
+    }
+    part[(size_t)s * KHoWo + e] = acc;
 }
 
 // Small output planes (down to the 1x1 output of a fully-connected layer): one image of dzdy is

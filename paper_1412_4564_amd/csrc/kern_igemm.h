@@ -108,6 +108,7 @@ struct IgemmParams {
     int OH, OW;         // plane size of the output array
     int oi0, osi, oj0, osj;   // row = oi0 + osi*io, column = oj0 + osj*jo
     unsigned packed_bytes;    // size of the packed weights of this view
+    int relu;                 // 1: results are written as max(0, .)  (fused ReLU block, Sec. 4.4 of the manual)
 };
 
 // Blocks on consecutive hardware ids land on different XCDs; give each XCD a contiguous
@@ -458,7 +459,8 @@ __global__ __launch_bounds__(64 * WK * WP, WPE) void igemm_sk_kernel(IgemmParams
                 for (int mp = 0; mp < MP; ++mp) {
                     // the upper half-wave holds filter kl0 + 4
                     const unsigned vo = (left > 4 || half == 0) ? ooff[mp] : SLAB_INVALID;
-                    const float val = acc[mk][mp][v];
+                    float val = acc[mk][mp][v];
+                    if (P.relu) val = fmaxf(val, 0.f);
                     __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(val), ors, vo, soff, 0);
                 }
             }
@@ -562,6 +564,7 @@ __global__ __launch_bounds__(256) void igemm_fixup_kernel(IgemmParams P, const f
             const int slot = 2 * b + (bb >= t_lo ? 0 : 1);
             acc += part[(size_t)slot * (TK * TQ) + e];
         }
+        if (P.relu) acc = fmaxf(acc, 0.f);
         out[(size_t)((P.oi0 + P.osi * io) + P.OH * ((P.oj0 + P.osj * jo) + P.OW * (P.Ktot * n))) +
             (size_t)OHW * (g * P.Kg + kl)] = acc;
     }

@@ -319,7 +319,8 @@ __global__ __launch_bounds__(64 * WK * WP, WPE) void igemm_bf16_kernel(IgemmPara
 #pragma unroll
                 for (int mp = 0; mp < MP; ++mp) {
                     const unsigned vo = (left > 4 || half == 0) ? ooff[mp] : SLAB_INVALID;   // the upper half-wave holds filter kl0 + 4
-                    const float val = acc[mk][mp][v];
+                    float val = acc[mk][mp][v];
+                    if (P.relu) val = fmaxf(val, 0.f);
                     __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(val), ors, vo, soff, 0);
                 }
             }

@@ -52,6 +52,7 @@ struct WgradParams {
     int R;               // Hf*Wf*Cg
     int XS;              // floats per slab buffer (max channels of an r tile * CP)
     int tiles, nblocks;
+    int relu;            // 1: results are written as max(0, .)  (forward pass of a fully-connected layer + ReLU)
 };
 
 // S1: vertical stride 1 (the slab rows of consecutive pixels are adjacent)
@@ -260,7 +261,11 @@ __global__ __launch_bounds__(64 * WK * WR, WPE) void wgrad_sk_kernel(WgradParams
 #pragma unroll
                     for (int v = 0; v < 16; ++v) {
                         const int kl = (wk * MK + mk) * 32 + (v >> 2) * 8 + half * 4 + (v & 3);
-                        if (kl < klim) out[(size_t)(c_g * P.Kg + c_kt * TK + kl) * P.R + r] = acc[mk][mr][v] + rb;
+                        if (kl < klim) {
+                            float val = acc[mk][mr][v] + rb;
+                            if (P.relu) val = fmaxf(val, 0.f);
+                            out[(size_t)(c_g * P.Kg + c_kt * TK + kl) * P.R + r] = val;
+                        }
                     }
             }
         }
@@ -360,6 +365,7 @@ __global__ __launch_bounds__(512) void wgrad_fixup_kernel(WgradParams P, const f
                 float v = ((red[0][el] + red[1][el]) + (red[2][el] + red[3][el])) +
                           ((red[4][el] + red[5][el]) + (red[6][el] + red[7][el]));
                 if (rbias) v += rbias[r];
+                if (P.relu) v = fmaxf(v, 0.f);
                 out[(size_t)(g * P.Kg + kt * TK + kloc) * P.R + r] = v;
             }
         }

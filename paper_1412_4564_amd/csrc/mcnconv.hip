@@ -153,18 +153,20 @@ const PlanEntry *plans_for(const mcn_conv_desc *d, const Geom &g) {
 
 template <int WK, int WP, int MK, int MP, int HF, int WF, int DCF>
 int launch_igemm_inst(const IgemmPlan &pl, const float *in, const float *wpk, const float *bias, float *out,
-                      float *part, hipStream_t s) {
+                      float *part, hipStream_t s, int relu) {
+    IgemmParams P = pl.P;
+    P.relu = relu;
     auto kern = igemm_sk_kernel<WK, WP, MK, MP, HF, WF, DCF, 2>;
     if (pl.lds_bytes > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
                                            (int)pl.lds_bytes);
         if (e != hipSuccess) { g_last_hip_error = (int)e; return MCN_HIP_ERROR; }
     }
-    hipLaunchKernelGGL(kern, dim3(pl.P.nblocks), dim3(64 * WK * WP), pl.lds_bytes, s, pl.P, in, wpk, bias, out, part);
+    hipLaunchKernelGGL(kern, dim3(P.nblocks), dim3(64 * WK * WP), pl.lds_bytes, s, P, in, wpk, bias, out, part);
     int st = check_launch();
-    if (st || pl.P.nblocks < 2) return st;
+    if (st || P.nblocks < 2) return st;
     constexpr int TK = WK * MK * 32, TQ = WP * MP * 32;
-    hipLaunchKernelGGL((igemm_fixup_kernel<TK, TQ>), dim3(pl.P.nblocks - 1, 16), dim3(256), 0, s, pl.P, part, bias, out);
+    hipLaunchKernelGGL((igemm_fixup_kernel<TK, TQ>), dim3(P.nblocks - 1, 16), dim3(256), 0, s, P, part, bias, out);
     return check_launch();
 }
 
@@ -175,23 +177,25 @@ size_t igemm_ws_bytes(const IgemmPlan &pl) {
 
 template <int WK, int WP, int MK, int MP>
 int launch_igemm_bf16_inst(const IgemmPlan &pl, const float *in, const float *wpk, const float *bias, float *out,
-                           float *part, hipStream_t s) {
+                           float *part, hipStream_t s, int relu) {
+    IgemmParams P = pl.P;
+    P.relu = relu;
     auto kern = igemm_bf16_kernel<WK, WP, MK, MP, 2>;
     if (pl.lds_bytes > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
                                            (int)pl.lds_bytes);
         if (e != hipSuccess) { g_last_hip_error = (int)e; return MCN_HIP_ERROR; }
     }
-    hipLaunchKernelGGL(kern, dim3(pl.P.nblocks), dim3(64 * WK * WP), pl.lds_bytes, s, pl.P, in, wpk, bias, out, part);
+    hipLaunchKernelGGL(kern, dim3(P.nblocks), dim3(64 * WK * WP), pl.lds_bytes, s, P, in, wpk, bias, out, part);
     int st = check_launch();
-    if (st || pl.P.nblocks < 2) return st;
+    if (st || P.nblocks < 2) return st;
     constexpr int TK = WK * MK * 32, TQ = WP * MP * 32;
-    hipLaunchKernelGGL((igemm_fixup_kernel<TK, TQ>), dim3(pl.P.nblocks - 1, 16), dim3(256), 0, s, pl.P, part, bias, out);
+    hipLaunchKernelGGL((igemm_fixup_kernel<TK, TQ>), dim3(P.nblocks - 1, 16), dim3(256), 0, s, P, part, bias, out);
     return check_launch();
 }
 
 int launch_igemm(const IgemmPlan &pl, const float *in, const float *w, const float *bias, float *out, void *ws,
-                 hipStream_t s) {
+                 hipStream_t s, int relu = 0) {
     float *packed = (float *)ws;
     float *part = (float *)((char *)ws + align256(pl.packed_floats * sizeof(float)));
     if (pl.bf16) {
@@ -200,9 +204,9 @@ int launch_igemm(const IgemmPlan &pl, const float *in, const float *w, const flo
         int st = check_launch();
         if (st) return st;
         switch (pl.shape) {
-            case IG_128x256: return launch_igemm_bf16_inst<2, 4, 2, 2>(pl, in, packed, bias, out, part, s);
-            case IG_64x512: return launch_igemm_bf16_inst<1, 8, 2, 2>(pl, in, packed, bias, out, part, s);
-            case IG_32x256: return launch_igemm_bf16_inst<1, 4, 1, 2>(pl, in, packed, bias, out, part, s);
+            case IG_128x256: return launch_igemm_bf16_inst<2, 4, 2, 2>(pl, in, packed, bias, out, part, s, relu);
+            case IG_64x512: return launch_igemm_bf16_inst<1, 8, 2, 2>(pl, in, packed, bias, out, part, s, relu);
+            case IG_32x256: return launch_igemm_bf16_inst<1, 4, 1, 2>(pl, in, packed, bias, out, part, s, relu);
             default: return MCN_BAD_ARG;
         }
     }
@@ -211,14 +215,14 @@ int launch_igemm(const IgemmPlan &pl, const float *in, const float *w, const flo
     if (st) return st;
     switch (pl.shape) {
         case IG_128x256:
-            return pl.fixed33 ? launch_igemm_inst<2, 4, 2, 2, 3, 3, IGEMM_FIXED_DC>(pl, in, packed, bias, out, part, s)
-                              : launch_igemm_inst<2, 4, 2, 2, 0, 0, 0>(pl, in, packed, bias, out, part, s);
+            return pl.fixed33 ? launch_igemm_inst<2, 4, 2, 2, 3, 3, IGEMM_FIXED_DC>(pl, in, packed, bias, out, part, s, relu)
+                              : launch_igemm_inst<2, 4, 2, 2, 0, 0, 0>(pl, in, packed, bias, out, part, s, relu);
         case IG_64x512:
-            return pl.fixed33 ? launch_igemm_inst<1, 8, 2, 2, 3, 3, IGEMM_FIXED_DC>(pl, in, packed, bias, out, part, s)
-                              : launch_igemm_inst<1, 8, 2, 2, 0, 0, 0>(pl, in, packed, bias, out, part, s);
+            return pl.fixed33 ? launch_igemm_inst<1, 8, 2, 2, 3, 3, IGEMM_FIXED_DC>(pl, in, packed, bias, out, part, s, relu)
+                              : launch_igemm_inst<1, 8, 2, 2, 0, 0, 0>(pl, in, packed, bias, out, part, s, relu);
         case IG_32x256:
-            return pl.fixed33 ? launch_igemm_inst<1, 4, 1, 2, 3, 3, IGEMM_FIXED_DC>(pl, in, packed, bias, out, part, s)
-                              : launch_igemm_inst<1, 4, 1, 2, 0, 0, 0>(pl, in, packed, bias, out, part, s);
+            return pl.fixed33 ? launch_igemm_inst<1, 4, 1, 2, 3, 3, IGEMM_FIXED_DC>(pl, in, packed, bias, out, part, s, relu)
+                              : launch_igemm_inst<1, 4, 1, 2, 0, 0, 0>(pl, in, packed, bias, out, part, s, relu);
         default:
             return MCN_BAD_ARG;
     }
@@ -226,39 +230,41 @@ int launch_igemm(const IgemmPlan &pl, const float *in, const float *w, const flo
 
 template <int WK, int WR, int MK, int MR, bool S1>
 int launch_wgrad_inst2(const WgradPlan &pl, const float *x, const float *dzdy, const float *rbias, float *out,
-                       float *part, hipStream_t s) {
+                       float *part, hipStream_t s, int relu) {
+    WgradParams P = pl.P;
+    P.relu = relu;
     auto kern = wgrad_sk_kernel<WK, WR, MK, MR, S1, 2>;
     if (pl.lds_bytes > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
                                            (int)pl.lds_bytes);
         if (e != hipSuccess) { g_last_hip_error = (int)e; return MCN_HIP_ERROR; }
     }
-    hipLaunchKernelGGL(kern, dim3(pl.P.nblocks), dim3(64 * WK * WR), pl.lds_bytes, s, pl.P, x, dzdy, rbias, out, part);
+    hipLaunchKernelGGL(kern, dim3(P.nblocks), dim3(64 * WK * WR), pl.lds_bytes, s, P, x, dzdy, rbias, out, part);
     int st = check_launch();
-    if (st || pl.P.nblocks < 2) return st;
+    if (st || P.nblocks < 2) return st;
     constexpr int TK = WK * MK * 32, TR = WR * MR * 32;
     // at most nblocks - 1 tiles are shared, but which ones is cheaper to find per tile
     int fy = 2048 / pl.P.tiles;          // about 2048 blocks in all
     if (fy < 1) fy = 1;
     if (fy > TK * TR / 64) fy = TK * TR / 64;
-    hipLaunchKernelGGL((wgrad_fixup_kernel<TK, TR>), dim3(pl.P.tiles, fy), dim3(512), 0, s, pl.P, part, rbias, out);
+    hipLaunchKernelGGL((wgrad_fixup_kernel<TK, TR>), dim3(P.tiles, fy), dim3(512), 0, s, P, part, rbias, out);
     return check_launch();
 }
 
 template <int WK, int WR, int MK, int MR>
 int launch_wgrad_inst(const WgradPlan &pl, const float *x, const float *dzdy, const float *rbias, float *out,
-                      float *part, hipStream_t s) {
-    return pl.P.Sh == 1 ? launch_wgrad_inst2<WK, WR, MK, MR, true>(pl, x, dzdy, rbias, out, part, s)
-                        : launch_wgrad_inst2<WK, WR, MK, MR, false>(pl, x, dzdy, rbias, out, part, s);
+                      float *part, hipStream_t s, int relu) {
+    return pl.P.Sh == 1 ? launch_wgrad_inst2<WK, WR, MK, MR, true>(pl, x, dzdy, rbias, out, part, s, relu)
+                        : launch_wgrad_inst2<WK, WR, MK, MR, false>(pl, x, dzdy, rbias, out, part, s, relu);
 }
 
 int launch_wgrad(const WgradPlan &pl, const float *x, const float *dzdy, const float *rbias, float *out, void *ws,
-                 hipStream_t s) {
+                 hipStream_t s, int relu = 0) {
     float *part = (float *)ws;
     switch (pl.shape) {
-        case WG_128x128: return launch_wgrad_inst<2, 2, 2, 2>(pl, x, dzdy, rbias, out, part, s);
-        case WG_64x192: return launch_wgrad_inst<2, 2, 1, 3>(pl, x, dzdy, rbias, out, part, s);
-        case WG_32x256: return launch_wgrad_inst<1, 4, 1, 2>(pl, x, dzdy, rbias, out, part, s);
+        case WG_128x128: return launch_wgrad_inst<2, 2, 2, 2>(pl, x, dzdy, rbias, out, part, s, relu);
+        case WG_64x192: return launch_wgrad_inst<2, 2, 1, 3>(pl, x, dzdy, rbias, out, part, s, relu);
+        case WG_32x256: return launch_wgrad_inst<1, 4, 1, 2>(pl, x, dzdy, rbias, out, part, s, relu);
         default: return MCN_BAD_ARG;
     }
 }
@@ -334,15 +340,15 @@ size_t workspace_bytes(const mcn_conv_desc *d, const Geom &g, int op) {
 // ---- the four passes on a validated geometry ---------------------------------------------
 
 int run_forward(const mcn_conv_desc *desc, const Geom &g, const float *x, const float *w, const float *b, float *y,
-                void *ws, size_t ws_bytes, hipStream_t s) {
+                void *ws, size_t ws_bytes, hipStream_t s, int relu = 0) {
     if (!x || !w || !y) return MCN_BAD_ARG;
     const size_t need = workspace_bytes(desc, g, MCN_OP_FORWARD);
     if (ws_bytes < need || (!ws && need)) return MCN_WORKSPACE_TOO_SMALL;
     const PlanEntry *pe = plans_for(desc, g);
-    if (pe->fc) return launch_wgrad(pe->fc_fwd, w, x, b, y, ws, s);
-    if (pe->fwd_ok) return launch_igemm(pe->fwd, x, w, b, y, ws, s);
+    if (pe->fc) return launch_wgrad(pe->fc_fwd, w, x, b, y, ws, s, relu);
+    if (pe->fwd_ok) return launch_igemm(pe->fwd, x, w, b, y, ws, s, relu);
     const int total = (int)numel_y(g);
-    hipLaunchKernelGGL(direct_forward_kernel, dim3(cdiv(total, 256)), dim3(256), 0, s, g, x, w, b, y, total);
+    hipLaunchKernelGGL(direct_forward_kernel, dim3(cdiv(total, 256)), dim3(256), 0, s, g, x, w, b, y, total, relu);
     return check_launch();
 }
 
@@ -396,9 +402,10 @@ int run_backward_filter(const mcn_conv_desc *desc, const Geom &g, const float *x
     return check_launch();
 }
 
-// dzdb[k] = sum of the plane x K x N array dzdy over its plane and its images
+// dzdb[k] = sum of the plane x K x N array dzdy over its plane and its images.  With y (and dzdp):
+// dzdp = [y > 0] * dzdy is written in the same pass and summed instead.
 int run_backward_bias(int plane, int K, int N, const float *dzdy, float *dzdb, void *ws, size_t ws_bytes,
-                      hipStream_t s) {
+                      hipStream_t s, const float *y = nullptr, float *dzdp = nullptr) {
     if (!dzdy || !dzdb) return MCN_BAD_ARG;
     const BiasPlan p = plan_bias(plane, K, N);
     const size_t need = p.ws_floats * sizeof(float);
@@ -407,13 +414,19 @@ int run_backward_bias(int plane, int K, int N, const float *dzdy, float *dzdb, v
     int st;
     if (p.rows) {
         const int row = K * plane;
-        hipLaunchKernelGGL(bias_rows_partial_kernel, dim3(cdiv(row, 256), p.S), dim3(256), 0, s, dzdy, part, row, N, p.S);
+        if (y)
+            hipLaunchKernelGGL(relu_bias_rows_partial_kernel, dim3(cdiv(row, 256), p.S), dim3(256), 0, s, y, dzdy, dzdp, part, row, N, p.S);
+        else
+            hipLaunchKernelGGL(bias_rows_partial_kernel, dim3(cdiv(row, 256), p.S), dim3(256), 0, s, dzdy, part, row, N, p.S);
         st = check_launch();
         if (st) return st;
         hipLaunchKernelGGL(bias_rows_final_kernel, dim3(cdiv(K, 4)), dim3(256), 0, s, part, dzdb, plane, K, p.S);
         return check_launch();
     }
-    hipLaunchKernelGGL(bias_partial_kernel, dim3(K, p.S), dim3(256), 0, s, dzdy, part, plane, K, N, p.chunks, p.S);
+    if (y)
+        hipLaunchKernelGGL(relu_bias_partial_kernel, dim3(K, p.S), dim3(256), 0, s, y, dzdy, dzdp, part, plane, K, N, p.chunks, p.S);
+    else
+        hipLaunchKernelGGL(bias_partial_kernel, dim3(K, p.S), dim3(256), 0, s, dzdy, part, plane, K, N, p.chunks, p.S);
     st = check_launch();
     if (st) return st;
     hipLaunchKernelGGL(bias_final_kernel, dim3(cdiv(K, 256)), dim3(256), 0, s, part, dzdb, K, p.S);
@@ -512,6 +525,25 @@ int mcn_conv_backward_bias(const mcn_conv_desc *desc, const float *dzdy, float *
     int st = make_geom(desc, &g);
     if (st) return st;
     return run_backward_bias(g.Ho * g.Wo, g.K, g.N, dzdy, dzdb, ws, ws_bytes, (hipStream_t)stream);
+}
+
+// ---- convolution + ReLU ------------------------------------------------------------------
+
+int mcn_conv_relu_forward(const mcn_conv_desc *desc, const float *x, const float *w, const float *b, float *y,
+                          void *ws, size_t ws_bytes, void *stream) {
+    Geom g;
+    int st = make_geom(desc, &g);
+    if (st) return st;
+    return run_forward(desc, g, x, w, b, y, ws, ws_bytes, (hipStream_t)stream, 1);
+}
+
+int mcn_conv_relu_backward_bias(const mcn_conv_desc *desc, const float *y, const float *dzdy, float *dzdp, float *dzdb,
+                                void *ws, size_t ws_bytes, void *stream) {
+    Geom g;
+    int st = make_geom(desc, &g);
+    if (st) return st;
+    if (!y || !dzdp) return MCN_BAD_ARG;
+    return run_backward_bias(g.Ho * g.Wo, g.K, g.N, dzdy, dzdb, ws, ws_bytes, (hipStream_t)stream, y, dzdp);
 }
 
 // ---- convolution transpose: the same kernels with the roles of the arrays exchanged ----------

@@ -71,6 +71,8 @@ def test_bad_geometry_is_a_status_code_everywhere(kw, code):
     assert B.mcn_conv_backward_data(d, p, p, p, None, 0, None) == code
     assert B.mcn_conv_backward_filter(d, p, p, p, None, 0, None) == code
     assert B.mcn_conv_backward_bias(d, p, p, None, 0, None) == code
+    assert B.mcn_conv_relu_forward(d, p, p, p, p, None, 0, None) == code
+    assert B.mcn_conv_relu_backward_bias(d, p, p, p, p, None, 0, None) == code
     assert B.mcn_conv_kernel_name(d, 0) is None
 
 
@@ -87,8 +89,15 @@ def test_null_pointers_and_small_workspace_are_rejected():
     assert B.mcn_conv_backward_data(d, p, None, p, None, 0, None) == B.MCN_BAD_ARG
     assert B.mcn_conv_backward_filter(d, p, p, None, None, 0, None) == B.MCN_BAD_ARG
     assert B.mcn_conv_backward_bias(d, None, p, None, 0, None) == B.MCN_BAD_ARG
+    assert B.mcn_conv_relu_forward(d, p, p, p, None, None, 0, None) == B.MCN_BAD_ARG
+    for bad in range(4):
+        args = [p, p, p, p]
+        args[bad] = None
+        assert B.mcn_conv_relu_backward_bias(d, *args, None, 0, None) == B.MCN_BAD_ARG
     for op, call in [(B.MCN_OP_BACKWARD_BIAS, lambda ws, n: B.mcn_conv_backward_bias(d, p, p, ws, n, None)),
+                     (B.MCN_OP_BACKWARD_BIAS, lambda ws, n: B.mcn_conv_relu_backward_bias(d, p, p, p, p, ws, n, None)),
                      (B.MCN_OP_FORWARD, lambda ws, n: B.mcn_conv_forward(d, p, p, p, p, ws, n, None)),
+                     (B.MCN_OP_FORWARD, lambda ws, n: B.mcn_conv_relu_forward(d, p, p, p, p, ws, n, None)),
                      (B.MCN_OP_BACKWARD_DATA, lambda ws, n: B.mcn_conv_backward_data(d, p, p, p, ws, n, None)),
                      (B.MCN_OP_BACKWARD_FILTER, lambda ws, n: B.mcn_conv_backward_filter(d, p, p, p, ws, n, None))]:
         need = B.mcn_conv_workspace_size(d, op)
