@@ -148,6 +148,62 @@ class ConvtLayerState:
             raise B.McnError(st, "convt " + OPS[op])
 
 
+def fused_relu_report(layers, stream_obj, steps):
+    """Per layer: conv+ReLU forward fused (one call) against conv forward followed by a separate in-place
+    ReLU pass, and the fused mask+bias backward against a separate masking pass followed by the bias
+    derivative.  The separate passes are torch's elementwise kernels: they only stand for 'one more
+    read and write of y' in the comparison."""
+    stream = stream_obj.cuda_stream
+
+    def timed(fn):
+        for _ in range(2):
+            fn()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record(stream_obj)
+        for _ in range(steps):
+            fn()
+        b.record(stream_obj)
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / steps
+
+    out = {}
+    for Ls in layers:
+        if not isinstance(Ls, LayerState):
+            continue
+        d, ws, n = Ls.desc, Ls.ws.data_ptr(), Ls.ws.numel()
+        x, w, b, y, p = Ls.x, Ls.w, Ls.b, Ls.y, Ls.p
+        dzdp = torch.empty_like(p)
+        zero = torch.zeros((), dtype=torch.float32, device="cuda")
+
+        def check(st):
+            if st:
+                raise B.McnError(st, "fused relu")
+
+        def fwd_fused():
+            check(B.mcn_conv_relu_forward(d, x.data_ptr(), w.data_ptr(), b.data_ptr(), y.data_ptr(), ws, n, stream))
+
+        def fwd_unfused():
+            check(B.mcn_conv_forward(d, x.data_ptr(), w.data_ptr(), b.data_ptr(), y.data_ptr(), ws, n, stream))
+            torch.relu_(y)
+
+        def bwd_fused():
+            check(B.mcn_conv_relu_backward_bias(d, y.data_ptr(), p.data_ptr(), dzdp.data_ptr(), Ls.db.data_ptr(), ws, n, stream))
+
+        def bwd_unfused():
+            torch.where(y > 0, p, zero, out=dzdp)
+            check(B.mcn_conv_backward_bias(d, dzdp.data_ptr(), Ls.db.data_ptr(), ws, n, stream))
+
+        t_ff, t_fu = timed(fwd_fused), timed(fwd_unfused)
+        fwd_fused()
+        t_bf, t_bu = timed(bwd_fused), timed(bwd_unfused)
+        ybytes = 4 * p.numel()
+        out[Ls.name] = {"forward_fused_ms": round(t_ff, 4), "forward_separate_relu_ms": round(t_fu, 4),
+                        "mask_bias_fused_ms": round(t_bf, 4), "mask_then_bias_ms": round(t_bu, 4),
+                        "mask_bias_fused_GBps": round(3 * ybytes / t_bf / 1e6, 1),     # reads y, dzdy; writes dzdp
+                        "frac_of_hbm_peak": round(3 * ybytes / t_bf / 1e6 / HBM_PEAK_GBS, 4)}
+    return out
+
+
 def make_state(name, precision, rotate_mb):
     if name in synth.CONVT_LAYERS:
         return ConvtLayerState(name, synth.CONVT_LAYERS[name], precision, rotate_mb)
@@ -191,6 +247,9 @@ def main():
     ap.add_argument("--rotate-mb", type=int, default=0,
                     help="rotate each layer's activations through copies totalling at least this many MiB "
                          "(cold-cache timing of the memory-bound layers)")
+    ap.add_argument("--fused-relu", action="store_true",
+                    help="also time the fused conv+ReLU calls against their unfused sequences (extra object "
+                         "'fused_relu' in the JSON line)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 256 MiB elementwise copy three times, so that a counter run "
                          "(rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE) holds a kernel of known traffic to scale by")
@@ -285,6 +344,8 @@ def main():
         "roofline": roof,
         "calls": detail,
     }
+    if args.fused_relu:
+        out["fused_relu"] = fused_relu_report(layers, stream_obj, args.steps)
     if args.copy_calibration:
         src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device="cuda")
         dst = torch.empty_like(src)
