@@ -38,10 +38,11 @@ class _Geom(ctypes.Structure):
 
 
 def build(force: bool = False) -> str:
-    """Compile every C file of the oracle (this block's, the convolution transpose's and the ReLU's)."""
-    from . import convt, relu
+    """Compile every C file of the oracle (this block's and those of the convolution transpose, ReLU and pooling blocks)."""
+    from . import convt, pool, relu
     convt.build(force)
     relu.build(force)
+    pool.build(force)
     return compile_shared(_SRC, _LIB, force)
 
 
