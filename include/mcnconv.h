@@ -77,7 +77,8 @@ typedef enum mcn_status {
     MCN_WORKSPACE_TOO_SMALL = 4,
     MCN_UNSUPPORTED = 5,         /* an array has 2^31 elements or more                  */
     MCN_HIP_ERROR = 6,           /* a launch failed; see mcn_last_hip_error()           */
-    MCN_CROP_TOO_LARGE = 7       /* convolution transpose: the crops leave no output     */
+    MCN_CROP_TOO_LARGE = 7,      /* convolution transpose: the crops leave no output     */
+    MCN_PAD_TOO_LARGE = 8        /* pooling: a pad exceeds window - 1 (Sec. 5.2.1)       */
 } mcn_status;
 
 enum { MCN_OP_FORWARD = 0, MCN_OP_BACKWARD_DATA = 1, MCN_OP_BACKWARD_FILTER = 2, MCN_OP_BACKWARD_BIAS = 3 };
@@ -199,6 +200,41 @@ int mcn_convt_backward_bias(const mcn_convt_desc *desc, const float *dzdy, float
 
 /* Name of the kernel family the dispatcher picks; NULL on a bad descriptor. */
 const char *mcn_convt_kernel_name(const mcn_convt_desc *desc, int op);
+
+/* ------------------------------------------------------------------------
+ * Spatial pooling (Sec. 4.3; geometry Sec. 5.2; derivative Sec. 6.3)
+ * ------------------------------------------------------------------------
+ * x : H x W x D x N  ->  y : H'' x W'' x D x N, each channel pooled on its own
+ * over windows of H' x W' samples placed like the filters of the convolution
+ * block (stride, four pads, the same output-size rule).  A window that
+ * straddles the boundary is cropped: the maximum is taken over, and the
+ * average divided by the number of, the samples inside the array.  Pads may
+ * not exceed window - 1 (MCN_PAD_TOO_LARGE), so every window holds a sample;
+ * MCN_FILTER_TOO_LARGE if the padded input is smaller than the window.
+ * No workspace.  Results are written, inputs are not modified. */
+enum { MCN_POOL_MAX = 0, MCN_POOL_AVG = 1 };
+
+typedef struct mcn_pool_desc {
+    int32_t H, W, D, N;          /* x : H x W x D x N                                 */
+    int32_t Hp, Wp;              /* window H' x W'                                     */
+    int32_t stride_h, stride_w;
+    int32_t pad_top, pad_bottom, pad_left, pad_right;
+    int32_t method;              /* MCN_POOL_MAX or MCN_POOL_AVG                       */
+} mcn_pool_desc;
+
+/* Writes H'' and W'' (either may be NULL); validates the descriptor.  Host only. */
+int mcn_pool_output_size(const mcn_pool_desc *desc, int32_t *Ho, int32_t *Wo);
+
+/* y[i'',j'',d,n] = max, or mean, of x[i,j,d,n] over the cropped window. */
+int mcn_pool_forward(const mcn_pool_desc *desc, const float *x, float *y, void *stream);
+
+/* dzdx = S(x)^T dzdy (Sec. 6.3).  Max: each window hands its dzdy to the
+ * sample it selected, the first maximum in memory order (rows fastest) where
+ * a window holds its maximum more than once; x is the forward input.
+ * Average: each window hands dzdy / (samples inside) to every sample inside;
+ * x is not read and may be NULL.  Writes all of dzdx. */
+int mcn_pool_backward(const mcn_pool_desc *desc, const float *x, const float *dzdy, float *dzdx,
+                      void *stream);
 
 /* Static description of a status code. */
 const char *mcn_status_string(int status);

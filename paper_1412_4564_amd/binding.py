@@ -19,7 +19,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libmcnconv.so")
 
 MCN_OK, MCN_BAD_ARG, MCN_BAD_GROUPS, MCN_FILTER_TOO_LARGE = 0, 1, 2, 3
-MCN_WORKSPACE_TOO_SMALL, MCN_UNSUPPORTED, MCN_HIP_ERROR, MCN_CROP_TOO_LARGE = 4, 5, 6, 7
+MCN_WORKSPACE_TOO_SMALL, MCN_UNSUPPORTED, MCN_HIP_ERROR, MCN_CROP_TOO_LARGE, MCN_PAD_TOO_LARGE = 4, 5, 6, 7, 8
+MCN_POOL_MAX, MCN_POOL_AVG = 0, 1
 MCN_OP_FORWARD, MCN_OP_BACKWARD_DATA, MCN_OP_BACKWARD_FILTER, MCN_OP_BACKWARD_BIAS = 0, 1, 2, 3
 MCN_PREC_FP32, MCN_PREC_BF16 = 0, 1
 
@@ -29,6 +30,7 @@ EXPORTS = (
     "mcn_conv_kernel_name", "mcn_conv_relu_forward", "mcn_conv_relu_backward_bias",
     "mcn_convt_output_size", "mcn_convt_workspace_size", "mcn_convt_forward", "mcn_convt_backward_data",
     "mcn_convt_backward_filter", "mcn_convt_backward_bias", "mcn_convt_kernel_name",
+    "mcn_pool_output_size", "mcn_pool_forward", "mcn_pool_backward",
 )
 
 
@@ -42,6 +44,12 @@ class mcn_convt_desc(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in (
         "H", "W", "D", "N", "Hf", "Wf", "Kf", "groups", "up_h", "up_w",
         "crop_top", "crop_bottom", "crop_left", "crop_right", "precision")]
+
+
+class mcn_pool_desc(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in (
+        "H", "W", "D", "N", "Hp", "Wp", "stride_h", "stride_w",
+        "pad_top", "pad_bottom", "pad_left", "pad_right", "method")]
 
 
 class McnError(RuntimeError):
@@ -84,6 +92,12 @@ def lib():
         L.mcn_conv_relu_backward_bias.argtypes = [D, P, P, P, P, P, SZ, P]
         L.mcn_conv_relu_forward.restype = ctypes.c_int
         L.mcn_conv_relu_backward_bias.restype = ctypes.c_int
+        PD = ctypes.POINTER(mcn_pool_desc)
+        L.mcn_pool_output_size.argtypes = [PD, I32P, I32P]
+        L.mcn_pool_forward.argtypes = [PD, P, P, P]
+        L.mcn_pool_backward.argtypes = [PD, P, P, P, P]
+        for f in ("mcn_pool_output_size", "mcn_pool_forward", "mcn_pool_backward"):
+            getattr(L, f).restype = ctypes.c_int
         T = ctypes.POINTER(mcn_convt_desc)
         L.mcn_convt_output_size.argtypes = [T, I32P, I32P]
         L.mcn_convt_workspace_size.argtypes = [T, ctypes.c_int, ctypes.POINTER(SZ)]
@@ -154,6 +168,29 @@ def mcn_conv_relu_forward(desc, x, w, b, y, ws, ws_bytes, stream):
 
 def mcn_conv_relu_backward_bias(desc, y, dzdy, dzdp, dzdb, ws, ws_bytes, stream):
     return lib().mcn_conv_relu_backward_bias(ctypes.byref(desc), y, dzdy, dzdp, dzdb, ws, ws_bytes, stream)
+
+
+def make_pool_desc(xshape, window, stride=(1, 1), pad=(0, 0, 0, 0), method=MCN_POOL_MAX):
+    """Descriptor from x's shape (N,D,W,H), window (Hp,Wp), stride (Sh,Sw), pad (t,b,l,r)."""
+    N, D, W, H = (int(v) for v in xshape)
+    return mcn_pool_desc(H, W, D, N, int(window[0]), int(window[1]), int(stride[0]), int(stride[1]),
+                         int(pad[0]), int(pad[1]), int(pad[2]), int(pad[3]), int(method))
+
+
+def mcn_pool_output_size(desc):
+    ho, wo = ctypes.c_int32(0), ctypes.c_int32(0)
+    st = lib().mcn_pool_output_size(ctypes.byref(desc), ctypes.byref(ho), ctypes.byref(wo))
+    if st:
+        raise McnError(st, "mcn_pool_output_size")
+    return ho.value, wo.value
+
+
+def mcn_pool_forward(desc, x, y, stream):
+    return lib().mcn_pool_forward(ctypes.byref(desc), x, y, stream)
+
+
+def mcn_pool_backward(desc, x, dzdy, dzdx, stream):
+    return lib().mcn_pool_backward(ctypes.byref(desc), x, dzdy, dzdx, stream)
 
 
 def make_convt_desc(xshape, fshape, upsample=(1, 1), crop=(0, 0, 0, 0), groups=1, precision=MCN_PREC_FP32):
@@ -400,3 +437,32 @@ def convt_backward_bias(xshape, fshape, dzdy, upsample=(1, 1), crop=(0, 0, 0, 0)
     if st:
         raise McnError(st, "mcn_convt_backward_bias")
     return dzdb
+
+
+# ---- spatial pooling ----
+def pool_forward(x, window, stride=(1, 1), pad=(0, 0, 0, 0), method=MCN_POOL_MAX, out=None):
+    import torch
+    _check(x, None, "x")
+    desc = make_pool_desc(x.shape, window, stride, pad, method)
+    ho, wo = mcn_pool_output_size(desc)
+    ysh = (x.shape[0], x.shape[1], wo, ho)
+    y = out if out is not None else torch.empty(ysh, dtype=torch.float32, device=x.device)
+    _check(y, ysh, "out")
+    st = mcn_pool_forward(desc, x.data_ptr(), y.data_ptr(), _stream())
+    if st:
+        raise McnError(st, "mcn_pool_forward")
+    return y
+
+
+def pool_backward(x, dzdy, window, stride=(1, 1), pad=(0, 0, 0, 0), method=MCN_POOL_MAX, out=None):
+    import torch
+    _check(x, None, "x")
+    desc = make_pool_desc(x.shape, window, stride, pad, method)
+    ho, wo = mcn_pool_output_size(desc)
+    _check(dzdy, (x.shape[0], x.shape[1], wo, ho), "dzdy")
+    dzdx = out if out is not None else torch.empty_like(x)
+    _check(dzdx, tuple(x.shape), "out")
+    st = mcn_pool_backward(desc, x.data_ptr(), dzdy.data_ptr(), dzdx.data_ptr(), _stream())
+    if st:
+        raise McnError(st, "mcn_pool_backward")
+    return dzdx

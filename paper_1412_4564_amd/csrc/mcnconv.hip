@@ -11,6 +11,7 @@
 #include "kern_direct.h"
 #include "kern_igemm.h"
 #include "igemm_plan.h"
+#include "kern_pool.h"
 
 using namespace mcn;
 
@@ -626,6 +627,57 @@ int mcn_convt_backward_bias(const mcn_convt_desc *desc, const float *dzdy, float
     return run_backward_bias(g.H * g.W, g.D, g.N, dzdy, dzdb, ws, ws_bytes, (hipStream_t)stream);
 }
 
+// ---- spatial pooling -------------------------------------------------------------------
+
+static int make_pool_geom(const mcn_pool_desc *d, PoolGeom *g) {
+    if (!d) return MCN_BAD_ARG;
+    if (d->H < 1 || d->W < 1 || d->D < 1 || d->N < 1) return MCN_BAD_ARG;
+    if (d->Hp < 1 || d->Wp < 1 || d->stride_h < 1 || d->stride_w < 1) return MCN_BAD_ARG;
+    if (d->pad_top < 0 || d->pad_bottom < 0 || d->pad_left < 0 || d->pad_right < 0) return MCN_BAD_ARG;
+    if (d->method != MCN_POOL_MAX && d->method != MCN_POOL_AVG) return MCN_BAD_ARG;
+    if (d->pad_top > d->Hp - 1 || d->pad_bottom > d->Hp - 1 || d->pad_left > d->Wp - 1 || d->pad_right > d->Wp - 1)
+        return MCN_PAD_TOO_LARGE;
+    const int64_t hp = (int64_t)d->H + d->pad_top + d->pad_bottom, wp = (int64_t)d->W + d->pad_left + d->pad_right;
+    if (hp < d->Hp || wp < d->Wp) return MCN_FILTER_TOO_LARGE;
+    const int64_t Ho = (hp - d->Hp) / d->stride_h + 1, Wo = (wp - d->Wp) / d->stride_w + 1;
+    const double lim = 2147483648.0;
+    if ((double)d->H * d->W * d->D * d->N >= lim || (double)Ho * Wo * d->D * d->N >= lim) return MCN_UNSUPPORTED;
+    if ((double)d->Hp + d->H >= lim / 4 || (double)d->Wp + d->W >= lim / 4) return MCN_UNSUPPORTED;
+    g->H = d->H; g->W = d->W; g->D = d->D; g->N = d->N;
+    g->Hp = d->Hp; g->Wp = d->Wp; g->Sh = d->stride_h; g->Sw = d->stride_w; g->Pt = d->pad_top; g->Pl = d->pad_left;
+    g->Ho = (int)Ho; g->Wo = (int)Wo; g->method = d->method;
+    return MCN_OK;
+}
+
+int mcn_pool_output_size(const mcn_pool_desc *desc, int32_t *Ho, int32_t *Wo) {
+    PoolGeom g;
+    int st = make_pool_geom(desc, &g);
+    if (st) return st;
+    if (Ho) *Ho = g.Ho;
+    if (Wo) *Wo = g.Wo;
+    return MCN_OK;
+}
+
+int mcn_pool_forward(const mcn_pool_desc *desc, const float *x, float *y, void *stream) {
+    PoolGeom g;
+    int st = make_pool_geom(desc, &g);
+    if (st) return st;
+    if (!x || !y) return MCN_BAD_ARG;
+    const int total = g.Ho * g.Wo * g.D * g.N;
+    hipLaunchKernelGGL(pool_forward_kernel, dim3(cdiv(total, 256)), dim3(256), 0, (hipStream_t)stream, g, x, y, total);
+    return check_launch();
+}
+
+int mcn_pool_backward(const mcn_pool_desc *desc, const float *x, const float *dzdy, float *dzdx, void *stream) {
+    PoolGeom g;
+    int st = make_pool_geom(desc, &g);
+    if (st) return st;
+    if (!dzdy || !dzdx || (g.method == MCN_POOL_MAX && !x)) return MCN_BAD_ARG;
+    const int total = g.H * g.W * g.D * g.N;
+    hipLaunchKernelGGL(pool_backward_kernel, dim3(cdiv(total, 256)), dim3(256), 0, (hipStream_t)stream, g, x, dzdy, dzdx, total);
+    return check_launch();
+}
+
 const char *mcn_status_string(int status) {
     switch (status) {
         case MCN_OK: return "ok";
@@ -636,6 +688,7 @@ const char *mcn_status_string(int status) {
         case MCN_UNSUPPORTED: return "array too large for 32-bit element offsets";
         case MCN_HIP_ERROR: return "HIP launch error";
         case MCN_CROP_TOO_LARGE: return "crops leave no output";
+        case MCN_PAD_TOO_LARGE: return "pooling pad larger than window - 1";
         default: return "unknown status";
     }
 }

@@ -142,3 +142,32 @@ def make_tdzdy(layer, Ho, Wo, seed=0):
     """dzdy ~ N(0,1) of shape (N, groups*K', Wo, Ho); Ho, Wo come from the caller."""
     return torch.randn((layer["N"], layer["groups"] * layer["Kf"], int(Wo), int(Ho)),
                        generator=_gen(layer, 3, seed), dtype=torch.float32)
+
+
+# ---- spatial pooling (Sec. 4.3) --------------------------------------------------------------
+# Pooling layers of the same networks: the 3x3/stride-2 pools of the CIFAR-sized stack (32 -> 16 -> 8,
+# bottom/right pad 1, the second one an average), the 3x3/stride-2 pools of the Krizhevsky-style network
+# (55 -> 27, 13 -> 6), the 2x2/stride-2 pool after the first VGG block, and one irregular layer.
+def _player(x, window, stride, pad, method, index):
+    H, W, D, N = x
+    return dict(H=H, W=W, D=D, N=N, window=tuple(window), stride=tuple(stride), pad=tuple(pad), method=method,
+                config=11, index=index)
+
+
+POOL_LAYERS = OrderedDict([
+    ("p1", _player((32, 32, 32, 100),   (3, 3), (2, 2), (0, 1, 0, 1), "max", 0)),
+    ("p2", _player((16, 16, 32, 100),   (3, 3), (2, 2), (0, 1, 0, 1), "avg", 1)),
+    ("p3", _player((55, 55, 96, 128),   (3, 3), (2, 2), (0, 0, 0, 0), "max", 2)),
+    ("p4", _player((224, 224, 64, 32),  (2, 2), (2, 2), (0, 0, 0, 0), "max", 3)),
+    ("p5", _player((13, 13, 256, 128),  (3, 3), (2, 2), (0, 0, 0, 0), "max", 4)),
+    ("p6", _player((37, 53, 16, 4),     (3, 5), (2, 3), (1, 0, 2, 1), "avg", 5)),
+])
+
+
+def make_px(layer, seed=0):
+    return torch.randn((layer["N"], layer["D"], layer["W"], layer["H"]), generator=_gen(layer, 0, seed),
+                       dtype=torch.float32)
+
+
+def make_pdzdy(layer, Ho, Wo, seed=0):
+    return torch.randn((layer["N"], layer["D"], int(Wo), int(Ho)), generator=_gen(layer, 3, seed), dtype=torch.float32)

@@ -109,7 +109,7 @@ def test_null_pointers_and_small_workspace_are_rejected():
 def test_status_strings():
     L = B.lib()
     seen = set()
-    for code in range(0, 8):
+    for code in range(0, 9):
         s = L.mcn_status_string(code).decode()
         assert s and s not in seen
         seen.add(s)
@@ -185,3 +185,46 @@ def test_convt_null_pointers_and_small_workspace_are_rejected():
     for op in range(4):
         assert B.mcn_convt_kernel_name(d, op)
     assert B.mcn_convt_kernel_name(d, 4) is None
+
+
+# ---- spatial pooling ----
+def pdesc(**kw):
+    base = dict(xshape=(2, 3, 9, 8), window=(3, 2), stride=(2, 1), pad=(1, 0, 0, 1), method=B.MCN_POOL_MAX)
+    base.update(kw)
+    return B.make_pool_desc(**base)
+
+
+def test_pool_output_size_closed_form():
+    assert B.mcn_pool_output_size(pdesc()) == ((8 - 3 + 1) // 2 + 1, (9 - 2 + 1) // 1 + 1)
+    assert B.mcn_pool_output_size(B.make_pool_desc((128, 96, 55, 55), (3, 3), (2, 2))) == (27, 27)
+    assert B.mcn_pool_output_size(B.make_pool_desc((100, 32, 32, 32), (3, 3), (2, 2), (0, 1, 0, 1))) == (16, 16)
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(window=(0, 2)), B.MCN_BAD_ARG),
+    (dict(stride=(1, 0)), B.MCN_BAD_ARG),
+    (dict(pad=(0, 0, -1, 0)), B.MCN_BAD_ARG),
+    (dict(xshape=(2, 0, 9, 8)), B.MCN_BAD_ARG),
+    (dict(method=2), B.MCN_BAD_ARG),
+    (dict(pad=(3, 0, 0, 0)), B.MCN_PAD_TOO_LARGE),          # window height 3: pads <= 2
+    (dict(pad=(0, 0, 0, 2)), B.MCN_PAD_TOO_LARGE),          # window width 2: pads <= 1
+    (dict(xshape=(2, 3, 9, 1), window=(3, 2), pad=(0, 0, 0, 0)), B.MCN_FILTER_TOO_LARGE),
+    (dict(xshape=(1 << 20, 64, 9, 8)), B.MCN_UNSUPPORTED),
+])
+def test_pool_bad_geometry_is_a_status_code_everywhere(kw, code):
+    d = pdesc(**kw)
+    L = B.lib()
+    assert L.mcn_pool_output_size(ctypes.byref(d), None, None) == code
+    p = 4096
+    assert B.mcn_pool_forward(d, p, p, None) == code
+    assert B.mcn_pool_backward(d, p, p, p, None) == code
+
+
+def test_pool_null_pointers_are_rejected():
+    d, p = pdesc(), 4096
+    assert B.lib().mcn_pool_output_size(None, None, None) == B.MCN_BAD_ARG
+    assert B.mcn_pool_forward(d, None, p, None) == B.MCN_BAD_ARG
+    assert B.mcn_pool_forward(d, p, None, None) == B.MCN_BAD_ARG
+    assert B.mcn_pool_backward(d, None, p, p, None) == B.MCN_BAD_ARG       # max pooling needs x
+    assert B.mcn_pool_backward(d, p, None, p, None) == B.MCN_BAD_ARG
+    assert B.mcn_pool_backward(d, p, p, None, None) == B.MCN_BAD_ARG

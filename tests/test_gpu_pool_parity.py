@@ -1,0 +1,134 @@
+"""Spatial pooling: GPU-vs-oracle parity through the C ABI.
+
+Max pooling forward copies samples (the comparisons are exact on both sides, the inputs being
+fp32 values), so it must match bit for bit; so must which sample each window selects.  Sums
+(average pooling, and the derivative where windows overlap) are compared with the normalised
+error of the convolution block: |gpu - oracle| / (the same operator on absolute values), 1e-4
+forward and 1e-3 backward (they come out near 1e-7)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import pool as oracle_pool
+from paper_1412_4564_amd import binding as B
+from paper_1412_4564_amd import synth
+
+import parity_util as U
+
+pytestmark = pytest.mark.gpu
+METHOD = {"max": B.MCN_POOL_MAX, "avg": B.MCN_POOL_AVG}
+
+
+def player(H, W, D, N, window, stride, pad, method, idx=0):
+    return dict(H=H, W=W, D=D, N=N, window=tuple(window), stride=tuple(stride), pad=tuple(pad), method=method,
+                config=12, index=idx)
+
+
+def run_pool(L, seed=0):
+    win, st, pad, m = L["window"], L["stride"], L["pad"], L["method"]
+    x = synth.make_px(L, seed)
+    ho, wo = oracle_pool.output_size(x.shape, win, st, pad, m)
+    p = synth.make_pdzdy(L, ho, wo, seed)
+    xg, pg = x.cuda(), p.cuda()
+    y = B.pool_forward(xg, win, st, pad, METHOD[m])
+    dx = B.pool_backward(xg, pg, win, st, pad, METHOD[m])
+    torch.cuda.synchronize()
+    assert tuple(y.shape) == (L["N"], L["D"], wo, ho)
+    xd, pd = U.np64(x), U.np64(p)
+    ref_y = oracle_pool.forward(xd, win, st, pad, m)
+    ref_dx = oracle_pool.backward(xd, pd, win, st, pad, m)
+    yh, dxh = y.cpu().numpy().astype(np.float64), dx.cpu().numpy().astype(np.float64)
+    if m == "max":
+        assert np.array_equal(yh, ref_y)
+        # the same samples are selected: the derivative is zero at exactly the same places
+        assert np.array_equal(dxh != 0, ref_dx != 0)
+        e_fwd = 0.0
+    else:
+        e_fwd = U.norm_err(yh, ref_y, oracle_pool.forward(np.abs(xd), win, st, pad, m))
+    e_bwd = U.norm_err(dxh, ref_dx, oracle_pool.backward(xd, np.abs(pd), win, st, pad, m))
+    return e_fwd, e_bwd
+
+
+@pytest.mark.parametrize("name,nb", [("p1", 100), ("p2", 100), ("p3", 8), ("p4", 2), ("p5", 128), ("p6", 4)])
+def test_pool_workload_layers(name, nb):
+    L = dict(synth.POOL_LAYERS[name])
+    L["N"] = nb
+    e = run_pool(L)
+    print("pool layer %s at N=%d" % (name, nb), "%.2e %.2e" % e, flush=True)
+    assert e[0] <= U.TOL_FWD and e[1] <= U.TOL_BWD
+
+
+@pytest.mark.parametrize("name", ["p3", "p4"])
+def test_pool_full_size_against_torch_free_properties(name):
+    """Full benchmark size: every window's result is a sample of its window and no sample of the window
+    is larger (max); all of dzdy is handed on (both methods)."""
+    L = synth.POOL_LAYERS[name]
+    win, st, pad = L["window"], L["stride"], L["pad"]
+    x = synth.make_px(L).cuda()
+    y = B.pool_forward(x, win, st, pad, B.MCN_POOL_MAX)
+    ho, wo = y.shape[3], y.shape[2]
+    p = synth.make_pdzdy(L, ho, wo).cuda()
+    dx = B.pool_backward(x, p, win, st, pad, B.MCN_POOL_MAX)
+    torch.cuda.synchronize()
+    # windows of these two layers lie inside the array: compare with the elementwise maximum of the shifted views
+    best = None
+    for fj in range(win[1]):
+        for fi in range(win[0]):
+            v = x[:, :, fj:fj + st[1] * (wo - 1) + 1:st[1], fi:fi + st[0] * (ho - 1) + 1:st[0]]
+            best = v if best is None else torch.maximum(best, v)
+    assert torch.equal(y, best)
+    tot_p, tot_dx = float(p.double().sum()), float(dx.double().sum())
+    assert abs(tot_p - tot_dx) <= 1e-6 * float(p.double().abs().sum())
+    lhs, rhs = float((dx.double() * x.double()).sum()), float((p.double() * y.double()).sum())
+    assert abs(lhs - rhs) <= 1e-6 * float((p.double().abs() * y.double().abs()).sum())
+
+
+PSWEEP = [
+    # H  W  D  N  window  stride  pad            method
+    (9, 7, 3, 2, (2, 2), (2, 2), (0, 0, 0, 0), "max"),
+    (9, 7, 3, 2, (2, 2), (2, 2), (1, 1, 1, 1), "avg"),
+    (10, 10, 2, 3, (3, 3), (1, 1), (1, 1, 1, 1), "max"),       # overlapping windows, same-size output
+    (10, 10, 2, 3, (3, 3), (1, 1), (2, 2, 2, 2), "avg"),       # the largest pads allowed
+    (17, 5, 4, 1, (5, 2), (3, 1), (4, 0, 0, 1), "max"),
+    (5, 17, 1, 2, (1, 4), (1, 5), (0, 0, 3, 3), "avg"),        # stride > window: samples no window reads
+    (6, 6, 2, 2, (6, 6), (1, 1), (0, 0, 0, 0), "max"),         # one window = the whole plane
+    (1, 1, 1, 1, (1, 1), (1, 1), (0, 0, 0, 0), "avg"),
+    (70, 3, 5, 2, (4, 3), (2, 2), (3, 1, 2, 0), "max"),
+]
+
+
+@pytest.mark.parametrize("case", range(len(PSWEEP)))
+def test_pool_geometry_sweep(case):
+    H, W, D, N, win, st, pad, m = PSWEEP[case]
+    for method in (m, "avg" if m == "max" else "max"):
+        e = run_pool(player(H, W, D, N, win, st, pad, method, case))
+        assert e[0] <= U.TOL_FWD and e[1] <= U.TOL_BWD
+
+
+def test_pool_random_geometries():
+    rng = np.random.default_rng(1618)
+    for t in range(40):
+        Hp, Wp = int(rng.integers(1, 6)), int(rng.integers(1, 6))
+        H, W = int(rng.integers(1, 30)), int(rng.integers(1, 30))
+        pad = [int(rng.integers(0, Hp)), int(rng.integers(0, Hp)), int(rng.integers(0, Wp)), int(rng.integers(0, Wp))]
+        H = max(H, Hp - pad[0] - pad[1])
+        W = max(W, Wp - pad[2] - pad[3])
+        L = player(H, W, int(rng.integers(1, 6)), int(rng.integers(1, 5)), (Hp, Wp),
+                   (int(rng.integers(1, 4)), int(rng.integers(1, 4))), pad, "max" if t % 2 else "avg", 100 + t)
+        print("random pool case", t, L, flush=True)
+        e = run_pool(L)
+        assert e[0] <= U.TOL_FWD and e[1] <= U.TOL_BWD
+
+
+def test_pool_ties_select_the_first_maximum():
+    x = torch.zeros(1, 1, 3, 3, device="cuda")
+    p = torch.arange(1.0, 5.0, device="cuda").reshape(1, 1, 2, 2)
+    dx = B.pool_backward(x, p, (2, 2), (1, 1), (0, 0, 0, 0), B.MCN_POOL_MAX)
+    ref = oracle_pool.backward(x.cpu().numpy(), p.cpu().numpy(), (2, 2), (1, 1), (0, 0, 0, 0), "max")
+    assert np.array_equal(dx.cpu().numpy().astype(np.float64), ref)
+    # average pooling does not read x
+    d = B.make_pool_desc(x.shape, (2, 2), (1, 1), (0, 0, 0, 0), B.MCN_POOL_AVG)
+    out = torch.empty_like(x)
+    assert B.mcn_pool_backward(d, None, p.data_ptr(), out.data_ptr(), torch.cuda.current_stream().cuda_stream) == 0
+    torch.cuda.synchronize()
+    assert np.allclose(out.cpu().numpy(), oracle_pool.backward(x.cpu().numpy(), p.cpu().numpy(), (2, 2), (1, 1), (0, 0, 0, 0), "avg"))
