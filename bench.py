@@ -53,6 +53,8 @@ def layer_macs(L, ho, wo):
 
 
 class LayerState:
+    op_names = OPS
+
     def __init__(self, name, L, precision, rotate_mb=0):
         self.name, self.L = name, L
         self.st, self.pad, self.prec = L["stride"], L["pad"], precision
@@ -107,6 +109,7 @@ class LayerState:
 
 class ConvtLayerState:
     """The convolution transpose block on one of the synth.CONVT_LAYERS shapes (same interface)."""
+    op_names = OPS
 
     def __init__(self, name, L, precision, rotate_mb=0):
         self.name, self.L, self.prec = name, L, precision
@@ -204,7 +207,50 @@ def fused_relu_report(layers, stream_obj, steps):
     return out
 
 
+class PoolLayerState:
+    """The spatial pooling block on one of the synth.POOL_LAYERS shapes: forward and backward."""
+    op_names = ["forward", "backward"]
+
+    def __init__(self, name, L, precision, rotate_mb=0):
+        self.name, self.L = name, L
+        self.method = B.MCN_POOL_MAX if L["method"] == "max" else B.MCN_POOL_AVG
+        self.x = synth.make_px(L).cuda()
+        self.desc = B.make_pool_desc(self.x.shape, L["window"], L["stride"], L["pad"], self.method)
+        self.ho, self.wo = B.mcn_pool_output_size(self.desc)
+        self.p = synth.make_pdzdy(L, self.ho, self.wo).cuda()
+        self.sets = [(self.x, self.p, torch.empty_like(self.p), torch.empty_like(self.x))]
+        if rotate_mb > 0:
+            per_set = 4 * (2 * self.x.numel() + 2 * self.p.numel())
+            for _ in range(min(256, max(1, -(-rotate_mb * (1 << 20) // per_set))) - 1):
+                self.sets.append((self.x.clone(), self.p.clone(), torch.empty_like(self.p), torch.empty_like(self.x)))
+        self.turn = 0
+        self.macs = 0
+        self.ws = torch.empty(max(B.mcn_pool_workspace_size(self.desc), 16), dtype=torch.uint8, device="cuda")
+        self.kernels = ["pool_forward", "pool_backward"]
+        nx, ny = self.x.numel(), self.p.numel()
+        # algorithmic bytes: forward reads x, writes y; backward reads dzdy (and x for max), writes dzdx
+        self.bytes = [4 * (nx + ny), 4 * (ny + nx + (nx if L["method"] == "max" else 0))]
+
+    def shape_info(self):
+        L = self.L
+        return {"block": "pool", "x_HWDN": [L["H"], L["W"], L["D"], L["N"]], "window": list(L["window"]),
+                "stride": list(L["stride"]), "pad": list(L["pad"]), "method": L["method"]}
+
+    def run(self, op, stream):
+        x, p, y, dx = self.sets[self.turn % len(self.sets)]
+        if op == 0:
+            st = B.mcn_pool_forward(self.desc, x.data_ptr(), y.data_ptr(), stream)
+        else:
+            st = B.mcn_pool_backward(self.desc, x.data_ptr(), p.data_ptr(), dx.data_ptr(), self.ws.data_ptr(),
+                                     self.ws.numel(), stream)
+            self.turn += 1
+        if st:
+            raise B.McnError(st, "pool " + self.op_names[op])
+
+
 def make_state(name, precision, rotate_mb):
+    if name in synth.POOL_LAYERS:
+        return PoolLayerState(name, synth.POOL_LAYERS[name], precision, rotate_mb)
     if name in synth.CONVT_LAYERS:
         return ConvtLayerState(name, synth.CONVT_LAYERS[name], precision, rotate_mb)
     return LayerState(name, synth.LAYERS[name], precision, rotate_mb)
@@ -266,14 +312,15 @@ def main():
     stream_obj = torch.cuda.current_stream()
     stream = stream_obj.cuda_stream
 
+    calls = [(li, op) for li, Ls in enumerate(layers) for op in range(len(Ls.op_names))]
+
     def step(events=None):
-        for li, Ls in enumerate(layers):
-            for op in range(4):
-                Ls.run(op, stream)
-                if events is not None:
-                    ev = torch.cuda.Event(enable_timing=True)
-                    ev.record(stream_obj)
-                    events.append(ev)
+        for li, op in calls:
+            layers[li].run(op, stream)
+            if events is not None:
+                ev = torch.cuda.Event(enable_timing=True)
+                ev.record(stream_obj)
+                events.append(ev)
 
     for _ in range(args.warmup):
         step()
@@ -296,12 +343,12 @@ def main():
         step(evs)
         torch.cuda.synchronize()
         prev = start
-        for i, ev in enumerate(evs):
-            per[i // 4, i % 4] += prev.elapsed_time(ev)
+        for (li, op), ev in zip(calls, evs):
+            per[li, op] += prev.elapsed_time(ev)
             prev = ev
     per /= args.steps     # ms per call
 
-    flops_step = sum(3 * 2.0 * Ls.macs for Ls in layers)
+    flops_step = sum(3 * 2.0 * Ls.macs for Ls in layers)      # pooling layers count no flops
     ms_per_step = 1e3 * elapsed / args.steps
     value = flops_step / (elapsed / args.steps) / 1e12
 
@@ -310,26 +357,27 @@ def main():
     dom = layers[li]
     detail = {}
     for i, Ls in enumerate(layers):
-        for o in range(4):
+        for o in range(len(Ls.op_names)):
             ms = per[i, o]
             e = {"kernel": Ls.kernels[o], "ms": round(float(ms), 4),
                  "GBps": round(Ls.bytes[o] / ms / 1e6, 1)}
-            if o < 3:
+            if o < 3 and Ls.macs:
                 e["TFLOPs"] = round(2.0 * Ls.macs / ms / 1e9, 2)
-            detail["%s.%s" % (Ls.name, OPS[o])] = e
-    if op < 3:
+            detail["%s.%s" % (Ls.name, Ls.op_names[o])] = e
+    OPS_dom = dom.op_names
+    if op < 3 and dom.macs:
         ach = 2.0 * dom.macs / per[li, op] / 1e9
         peak = BF16_MFMA_PEAK_TFLOPS if "bf16" in dom.kernels[op] else FP32_MFMA_PEAK_TFLOPS
         roof = {"bound": "mfma", "achieved": round(ach, 2), "peak": peak, "unit": "TFLOP/s",
                 "frac": round(ach / peak, 4),
-                "traffic": measured_traffic("%s.%s" % (dom.name, OPS[op])) if args.workload == "vgg3x3" else None,
-                "kernel": "%s.%s (%s)" % (dom.name, OPS[op], dom.kernels[op])}
+                "traffic": measured_traffic("%s.%s" % (dom.name, OPS_dom[op])) if args.workload == "vgg3x3" else None,
+                "kernel": "%s.%s (%s)" % (dom.name, OPS_dom[op], dom.kernels[op])}
     else:
         ach = dom.bytes[op] / per[li, op] / 1e6
         roof = {"bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(ach / HBM_PEAK_GBS, 4),
-                "traffic": measured_traffic("%s.%s" % (dom.name, OPS[op])) if args.workload == "vgg3x3" else None,
-                "kernel": "%s.%s (%s)" % (dom.name, OPS[op], dom.kernels[op])}
+                "traffic": measured_traffic("%s.%s" % (dom.name, OPS_dom[op])) if args.workload == "vgg3x3" else None,
+                "kernel": "%s.%s (%s)" % (dom.name, OPS_dom[op], dom.kernels[op])}
 
     out = {
         "metric": "conv fwd+bwd TFLOP/s (%s) on VGG-style 3x3 layers" % ("fp32" if prec == B.MCN_PREC_FP32 else "bf16 operands, fp32 accumulation"),

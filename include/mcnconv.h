@@ -211,7 +211,8 @@ const char *mcn_convt_kernel_name(const mcn_convt_desc *desc, int op);
  * average divided by the number of, the samples inside the array.  Pads may
  * not exceed window - 1 (MCN_PAD_TOO_LARGE), so every window holds a sample;
  * MCN_FILTER_TOO_LARGE if the padded input is smaller than the window.
- * No workspace.  Results are written, inputs are not modified. */
+ * Results are written, inputs are not modified.  Only the backward pass of
+ * max pooling takes a workspace (one byte per output sample). */
 enum { MCN_POOL_MAX = 0, MCN_POOL_AVG = 1 };
 
 typedef struct mcn_pool_desc {
@@ -225,6 +226,9 @@ typedef struct mcn_pool_desc {
 /* Writes H'' and W'' (either may be NULL); validates the descriptor.  Host only. */
 int mcn_pool_output_size(const mcn_pool_desc *desc, int32_t *Ho, int32_t *Wo);
 
+/* Bytes of scratch mcn_pool_backward needs for this descriptor.  Host only. */
+int mcn_pool_workspace_size(const mcn_pool_desc *desc, size_t *bytes);
+
 /* y[i'',j'',d,n] = max, or mean, of x[i,j,d,n] over the cropped window. */
 int mcn_pool_forward(const mcn_pool_desc *desc, const float *x, float *y, void *stream);
 
@@ -234,7 +238,7 @@ int mcn_pool_forward(const mcn_pool_desc *desc, const float *x, float *y, void *
  * Average: each window hands dzdy / (samples inside) to every sample inside;
  * x is not read and may be NULL.  Writes all of dzdx. */
 int mcn_pool_backward(const mcn_pool_desc *desc, const float *x, const float *dzdy, float *dzdx,
-                      void *stream);
+                      void *ws, size_t ws_bytes, void *stream);
 
 /* Static description of a status code. */
 const char *mcn_status_string(int status);

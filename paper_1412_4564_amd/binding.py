@@ -30,7 +30,7 @@ EXPORTS = (
     "mcn_conv_kernel_name", "mcn_conv_relu_forward", "mcn_conv_relu_backward_bias",
     "mcn_convt_output_size", "mcn_convt_workspace_size", "mcn_convt_forward", "mcn_convt_backward_data",
     "mcn_convt_backward_filter", "mcn_convt_backward_bias", "mcn_convt_kernel_name",
-    "mcn_pool_output_size", "mcn_pool_forward", "mcn_pool_backward",
+    "mcn_pool_output_size", "mcn_pool_workspace_size", "mcn_pool_forward", "mcn_pool_backward",
 )
 
 
@@ -95,8 +95,9 @@ def lib():
         PD = ctypes.POINTER(mcn_pool_desc)
         L.mcn_pool_output_size.argtypes = [PD, I32P, I32P]
         L.mcn_pool_forward.argtypes = [PD, P, P, P]
-        L.mcn_pool_backward.argtypes = [PD, P, P, P, P]
-        for f in ("mcn_pool_output_size", "mcn_pool_forward", "mcn_pool_backward"):
+        L.mcn_pool_backward.argtypes = [PD, P, P, P, P, SZ, P]
+        L.mcn_pool_workspace_size.argtypes = [PD, ctypes.POINTER(SZ)]
+        for f in ("mcn_pool_output_size", "mcn_pool_workspace_size", "mcn_pool_forward", "mcn_pool_backward"):
             getattr(L, f).restype = ctypes.c_int
         T = ctypes.POINTER(mcn_convt_desc)
         L.mcn_convt_output_size.argtypes = [T, I32P, I32P]
@@ -189,8 +190,16 @@ def mcn_pool_forward(desc, x, y, stream):
     return lib().mcn_pool_forward(ctypes.byref(desc), x, y, stream)
 
 
-def mcn_pool_backward(desc, x, dzdy, dzdx, stream):
-    return lib().mcn_pool_backward(ctypes.byref(desc), x, dzdy, dzdx, stream)
+def mcn_pool_workspace_size(desc):
+    n = ctypes.c_size_t(0)
+    st = lib().mcn_pool_workspace_size(ctypes.byref(desc), ctypes.byref(n))
+    if st:
+        raise McnError(st, "mcn_pool_workspace_size")
+    return int(n.value)
+
+
+def mcn_pool_backward(desc, x, dzdy, dzdx, ws, ws_bytes, stream):
+    return lib().mcn_pool_backward(ctypes.byref(desc), x, dzdy, dzdx, ws, ws_bytes, stream)
 
 
 def make_convt_desc(xshape, fshape, upsample=(1, 1), crop=(0, 0, 0, 0), groups=1, precision=MCN_PREC_FP32):
@@ -454,7 +463,7 @@ def pool_forward(x, window, stride=(1, 1), pad=(0, 0, 0, 0), method=MCN_POOL_MAX
     return y
 
 
-def pool_backward(x, dzdy, window, stride=(1, 1), pad=(0, 0, 0, 0), method=MCN_POOL_MAX, out=None):
+def pool_backward(x, dzdy, window, stride=(1, 1), pad=(0, 0, 0, 0), method=MCN_POOL_MAX, out=None, workspace=None):
     import torch
     _check(x, None, "x")
     desc = make_pool_desc(x.shape, window, stride, pad, method)
@@ -462,7 +471,8 @@ def pool_backward(x, dzdy, window, stride=(1, 1), pad=(0, 0, 0, 0), method=MCN_P
     _check(dzdy, (x.shape[0], x.shape[1], wo, ho), "dzdy")
     dzdx = out if out is not None else torch.empty_like(x)
     _check(dzdx, tuple(x.shape), "out")
-    st = mcn_pool_backward(desc, x.data_ptr(), dzdy.data_ptr(), dzdx.data_ptr(), _stream())
+    wsp, wsn = (workspace or _default_ws).get(mcn_pool_workspace_size(desc), x.device)
+    st = mcn_pool_backward(desc, x.data_ptr(), dzdy.data_ptr(), dzdx.data_ptr(), wsp, wsn, _stream())
     if st:
         raise McnError(st, "mcn_pool_backward")
     return dzdx

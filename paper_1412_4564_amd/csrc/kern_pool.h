@@ -7,64 +7,154 @@
 // Sec. 6.3: y = S(x) x, dz/dx = S(x)^T dz/dy; for max pooling S selects one sample per window --
 // the first maximum in memory order (rows fastest) -- and the backward pass is written as a
 // gather: a sample adds the dzdy of every window that selects it, so no two threads write one
-// element and the result does not depend on scheduling.
+// element and the result does not depend on scheduling.  Which sample a window selects is found
+// once per window by pool_argmax_kernel (one byte per window: the position inside the window);
+// windows of more than 256 samples take the one-kernel form that rescans the windows.
+//
+// These kernels move 4-12 bytes per result, so index arithmetic is what they could lose time on:
+// the divisions that split a thread's flat index into plane, column and row, and those by the
+// strides, are multiplications by reciprocals prepared on the host (exact for the sizes accepted).
 #pragma once
 #include <hip/hip_runtime.h>
+#include <stdint.h>
 
 namespace mcn {
+
+// n / d for 0 <= n, n*d < 2^32:  m = ceil(2^32 / d), n / d = floor(n * m / 2^32)   (d = 1: m does not fit, n / 1 = n)
+struct FastDiv {
+    unsigned d, m;
+};
+inline FastDiv make_fastdiv(int d) {
+    FastDiv f;
+    f.d = (unsigned)d;
+    f.m = d == 1 ? 0u : (unsigned)((((uint64_t)1 << 32) + (unsigned)d - 1) / (unsigned)d);
+    return f;
+}
+__device__ inline int fdiv(int n, FastDiv f) { return f.d == 1 ? n : (int)__umulhi((unsigned)n, f.m); }
+
+// n / d for any 0 <= n < 2^32 and 1 <= d < 2^32:  m = ceil(2^64 / d), n / d = floor(n * m / 2^64)
+struct FastDiv64 {
+    unsigned d;
+    unsigned long long m;
+};
+inline FastDiv64 make_fastdiv64(unsigned d) {
+    FastDiv64 f;
+    f.d = d;
+    f.m = d == 1 ? 0ull : ~0ull / d + 1;      // floor((2^64 - 1) / d) + 1 = ceil(2^64 / d) when d does not divide 2^64; powers of two: also exact
+    return f;
+}
+__device__ inline unsigned fdiv64(unsigned n, FastDiv64 f) { return f.d == 1 ? n : (unsigned)__umul64hi((unsigned long long)n, f.m); }
 
 struct PoolGeom {
     int H, W, D, N;
     int Hp, Wp, Sh, Sw, Pt, Pl;
     int Ho, Wo;
     int method;      // 0 max, 1 average
+    FastDiv dH, dHo, dSh, dSw;
+    FastDiv64 dIn, dOut;     // by the plane sizes H*W and Ho*Wo
 };
 
 __global__ __launch_bounds__(256) void pool_forward_kernel(PoolGeom g, const float *__restrict__ x,
-                                                           float *__restrict__ y, int total) {
-    const int idx = blockIdx.x * 256 + threadIdx.x;
+                                                           float *__restrict__ y, unsigned total) {
+    const unsigned idx = blockIdx.x * 256u + threadIdx.x;
     if (idx >= total) return;
-    const int io = idx % g.Ho;
-    int t = idx / g.Ho;
-    const int jo = t % g.Wo;
-    const int plane = t / g.Wo;
+    const unsigned plane = fdiv64(idx, g.dOut);
+    const int e = (int)(idx - plane * (unsigned)(g.Ho * g.Wo));
+    const int jo = fdiv(e, g.dHo), io = e - jo * g.Ho;
     const float *xp = x + (size_t)plane * g.H * g.W;
     const int i0 = max(g.Sh * io - g.Pt, 0), i1 = min(g.Sh * io - g.Pt + g.Hp, g.H);
     const int j0 = max(g.Sw * jo - g.Pl, 0), j1 = min(g.Sw * jo - g.Pl + g.Wp, g.W);
+    float r;
     if (g.method == 0) {
-        float m = xp[i0 + g.H * j0];
+        r = xp[i0 + g.H * j0];
         for (int j = j0; j < j1; ++j)
-            for (int i = i0; i < i1; ++i) m = fmaxf(m, xp[i + g.H * j]);
-        y[idx] = m;
+            for (int i = i0; i < i1; ++i) r = fmaxf(r, xp[i + g.H * j]);
     } else {
         float s = 0.f;
         for (int j = j0; j < j1; ++j)
             for (int i = i0; i < i1; ++i) s += xp[i + g.H * j];
-        y[idx] = s / (float)((i1 - i0) * (j1 - j0));
+        r = s / (float)((i1 - i0) * (j1 - j0));
     }
+    y[idx] = r;
 }
 
+// The windows that hold sample (i, j): Sh*io - Pt <= i <= Sh*io - Pt + Hp - 1, clipped to the output.
+struct WindowRange {
+    int io_lo, io_hi, jo_lo, jo_hi;
+};
+__device__ inline WindowRange windows_of(const PoolGeom &g, int i, int j) {
+    WindowRange r;
+    const int a = i + g.Pt - g.Hp + g.Sh, b = j + g.Pl - g.Wp + g.Sw;     // ceil((i + Pt - Hp + 1) / Sh) = floor(a / Sh)
+    r.io_lo = a > 0 ? fdiv(a, g.dSh) : 0;
+    r.io_hi = min(fdiv(i + g.Pt, g.dSh), g.Ho - 1);
+    r.jo_lo = b > 0 ? fdiv(b, g.dSw) : 0;
+    r.jo_hi = min(fdiv(j + g.Pl, g.dSw), g.Wo - 1);
+    return r;
+}
+
+// code[io,jo,plane] = fi + Hp*fj of the first maximum of window (io, jo), (fi, fj) counted from the
+// window's uncropped origin.  Needs Hp*Wp <= 256.
+__global__ __launch_bounds__(256) void pool_argmax_kernel(PoolGeom g, const float *__restrict__ x,
+                                                          unsigned char *__restrict__ code, unsigned total) {
+    const unsigned idx = blockIdx.x * 256u + threadIdx.x;
+    if (idx >= total) return;
+    const unsigned plane = fdiv64(idx, g.dOut);
+    const int e = (int)(idx - plane * (unsigned)(g.Ho * g.Wo));
+    const int jo = fdiv(e, g.dHo), io = e - jo * g.Ho;
+    const float *xp = x + (size_t)plane * g.H * g.W;
+    const int oi = g.Sh * io - g.Pt, oj = g.Sw * jo - g.Pl;
+    const int i0 = max(oi, 0), i1 = min(oi + g.Hp, g.H);
+    const int j0 = max(oj, 0), j1 = min(oj + g.Wp, g.W);
+    float m = xp[i0 + g.H * j0];
+    int best = (i0 - oi) + g.Hp * (j0 - oj);
+    for (int j = j0; j < j1; ++j)
+        for (int i = i0; i < i1; ++i) {
+            const float v = xp[i + g.H * j];
+            if (v > m) { m = v; best = (i - oi) + g.Hp * (j - oj); }
+        }
+    code[idx] = (unsigned char)best;
+}
+
+// dzdx[i,j] = sum of dzdy over the windows whose code points at (i, j)
+__global__ __launch_bounds__(256) void pool_backward_max_coded_kernel(PoolGeom g, const unsigned char *__restrict__ code,
+                                                                      const float *__restrict__ dzdy,
+                                                                      float *__restrict__ dzdx, unsigned total) {
+    const unsigned idx = blockIdx.x * 256u + threadIdx.x;
+    if (idx >= total) return;
+    const unsigned plane = fdiv64(idx, g.dIn);
+    const int e = (int)(idx - plane * (unsigned)(g.H * g.W));
+    const int j = fdiv(e, g.dH), i = e - j * g.H;
+    const size_t pbase = (size_t)plane * g.Ho * g.Wo;
+    const WindowRange r = windows_of(g, i, j);
+    float acc = 0.f;
+    for (int jo = r.jo_lo; jo <= r.jo_hi; ++jo) {
+        const int fj = j - (g.Sw * jo - g.Pl);
+        for (int io = r.io_lo; io <= r.io_hi; ++io) {
+            const int fi = i - (g.Sh * io - g.Pt);
+            const size_t a = pbase + io + (size_t)g.Ho * jo;
+            if (code[a] == fi + g.Hp * fj) acc += dzdy[a];
+        }
+    }
+    dzdx[idx] = acc;
+}
+
+// One-kernel backward pass: average pooling, and max pooling with windows too large for a byte code.
 __global__ __launch_bounds__(256) void pool_backward_kernel(PoolGeom g, const float *__restrict__ x,
                                                             const float *__restrict__ dzdy,
-                                                            float *__restrict__ dzdx, int total) {
-    const int idx = blockIdx.x * 256 + threadIdx.x;
+                                                            float *__restrict__ dzdx, unsigned total) {
+    const unsigned idx = blockIdx.x * 256u + threadIdx.x;
     if (idx >= total) return;
-    const int i = idx % g.H;
-    int t = idx / g.H;
-    const int j = t % g.W;
-    const int plane = t / g.W;
+    const unsigned plane = fdiv64(idx, g.dIn);
+    const int e = (int)(idx - plane * (unsigned)(g.H * g.W));
+    const int j = fdiv(e, g.dH), i = e - j * g.H;
     const float *pp = dzdy + (size_t)plane * g.Ho * g.Wo;
-    // windows that hold (i, j): Sh*io - Pt <= i <= Sh*io - Pt + Hp - 1
-    const int io_lo = max((i + g.Pt - g.Hp + g.Sh) / g.Sh, 0);       // ceil((i + Pt - Hp + 1) / Sh) where that is >= 0
-    const int io_hi = min((i + g.Pt) / g.Sh, g.Ho - 1);
-    const int jo_lo = max((j + g.Pl - g.Wp + g.Sw) / g.Sw, 0);
-    const int jo_hi = min((j + g.Pl) / g.Sw, g.Wo - 1);
+    const WindowRange r = windows_of(g, i, j);
     float acc = 0.f;
     if (g.method == 0) {
         const float *xp = x + (size_t)plane * g.H * g.W;
-        const float mine = xp[i + g.H * j];
-        for (int jo = jo_lo; jo <= jo_hi; ++jo)
-            for (int io = io_lo; io <= io_hi; ++io) {
+        const float mine = xp[e];
+        for (int jo = r.jo_lo; jo <= r.jo_hi; ++jo)
+            for (int io = r.io_lo; io <= r.io_hi; ++io) {
                 const int i0 = max(g.Sh * io - g.Pt, 0), i1 = min(g.Sh * io - g.Pt + g.Hp, g.H);
                 const int j0 = max(g.Sw * jo - g.Pl, 0), j1 = min(g.Sw * jo - g.Pl + g.Wp, g.W);
                 // selected iff no sample of the window is larger and none before (i, j) is equal
@@ -78,9 +168,9 @@ __global__ __launch_bounds__(256) void pool_backward_kernel(PoolGeom g, const fl
                 if (sel) acc += pp[io + g.Ho * jo];
             }
     } else {
-        for (int jo = jo_lo; jo <= jo_hi; ++jo) {
+        for (int jo = r.jo_lo; jo <= r.jo_hi; ++jo) {
             const int j0 = max(g.Sw * jo - g.Pl, 0), j1 = min(g.Sw * jo - g.Pl + g.Wp, g.W);
-            for (int io = io_lo; io <= io_hi; ++io) {
+            for (int io = r.io_lo; io <= r.io_hi; ++io) {
                 const int i0 = max(g.Sh * io - g.Pt, 0), i1 = min(g.Sh * io - g.Pt + g.Hp, g.H);
                 acc += pp[io + g.Ho * jo] / (float)((i1 - i0) * (j1 - j0));
             }

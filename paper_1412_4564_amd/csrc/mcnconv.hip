@@ -642,10 +642,15 @@ static int make_pool_geom(const mcn_pool_desc *d, PoolGeom *g) {
     const int64_t Ho = (hp - d->Hp) / d->stride_h + 1, Wo = (wp - d->Wp) / d->stride_w + 1;
     const double lim = 2147483648.0;
     if ((double)d->H * d->W * d->D * d->N >= lim || (double)Ho * Wo * d->D * d->N >= lim) return MCN_UNSUPPORTED;
-    if ((double)d->Hp + d->H >= lim / 4 || (double)d->Wp + d->W >= lim / 4) return MCN_UNSUPPORTED;
+    // the 32-bit reciprocal divisions in the kernels are exact below these sizes
+    if (d->H >= 32768 || d->W >= 32768 || d->Hp >= 32768 || d->Wp >= 32768 || d->stride_h >= 32768 || d->stride_w >= 32768)
+        return MCN_UNSUPPORTED;
     g->H = d->H; g->W = d->W; g->D = d->D; g->N = d->N;
     g->Hp = d->Hp; g->Wp = d->Wp; g->Sh = d->stride_h; g->Sw = d->stride_w; g->Pt = d->pad_top; g->Pl = d->pad_left;
     g->Ho = (int)Ho; g->Wo = (int)Wo; g->method = d->method;
+    g->dH = make_fastdiv(d->H); g->dHo = make_fastdiv((int)Ho);
+    g->dSh = make_fastdiv(d->stride_h); g->dSw = make_fastdiv(d->stride_w);
+    g->dIn = make_fastdiv64((unsigned)(d->H * d->W)); g->dOut = make_fastdiv64((unsigned)(Ho * Wo));
     return MCN_OK;
 }
 
@@ -663,18 +668,44 @@ int mcn_pool_forward(const mcn_pool_desc *desc, const float *x, float *y, void *
     int st = make_pool_geom(desc, &g);
     if (st) return st;
     if (!x || !y) return MCN_BAD_ARG;
-    const int total = g.Ho * g.Wo * g.D * g.N;
+    const unsigned total = (unsigned)g.Ho * g.Wo * g.D * g.N;
     hipLaunchKernelGGL(pool_forward_kernel, dim3(cdiv(total, 256)), dim3(256), 0, (hipStream_t)stream, g, x, y, total);
     return check_launch();
 }
 
-int mcn_pool_backward(const mcn_pool_desc *desc, const float *x, const float *dzdy, float *dzdx, void *stream) {
+// one byte per window for the position of its maximum, if a byte can hold it
+static size_t pool_ws_bytes(const PoolGeom &g) {
+    return (g.method == MCN_POOL_MAX && g.Hp * g.Wp <= 256) ? (size_t)g.Ho * g.Wo * g.D * g.N : 0;
+}
+
+int mcn_pool_workspace_size(const mcn_pool_desc *desc, size_t *bytes) {
+    PoolGeom g;
+    int st = make_pool_geom(desc, &g);
+    if (st) return st;
+    if (!bytes) return MCN_BAD_ARG;
+    *bytes = pool_ws_bytes(g);
+    return MCN_OK;
+}
+
+int mcn_pool_backward(const mcn_pool_desc *desc, const float *x, const float *dzdy, float *dzdx, void *ws,
+                      size_t ws_bytes, void *stream) {
     PoolGeom g;
     int st = make_pool_geom(desc, &g);
     if (st) return st;
     if (!dzdy || !dzdx || (g.method == MCN_POOL_MAX && !x)) return MCN_BAD_ARG;
-    const int total = g.H * g.W * g.D * g.N;
-    hipLaunchKernelGGL(pool_backward_kernel, dim3(cdiv(total, 256)), dim3(256), 0, (hipStream_t)stream, g, x, dzdy, dzdx, total);
+    const size_t need = pool_ws_bytes(g);
+    if (ws_bytes < need || (!ws && need)) return MCN_WORKSPACE_TOO_SMALL;
+    hipStream_t s = (hipStream_t)stream;
+    const unsigned n_in = (unsigned)g.H * g.W * g.D * g.N, n_out = (unsigned)g.Ho * g.Wo * g.D * g.N;
+    if (need) {
+        hipLaunchKernelGGL(pool_argmax_kernel, dim3(cdiv(n_out, 256)), dim3(256), 0, s, g, x, (unsigned char *)ws, n_out);
+        st = check_launch();
+        if (st) return st;
+        hipLaunchKernelGGL(pool_backward_max_coded_kernel, dim3(cdiv(n_in, 256)), dim3(256), 0, s, g,
+                           (const unsigned char *)ws, dzdy, dzdx, n_in);
+        return check_launch();
+    }
+    hipLaunchKernelGGL(pool_backward_kernel, dim3(cdiv(n_in, 256)), dim3(256), 0, s, g, x, dzdy, dzdx, n_in);
     return check_launch();
 }
 

@@ -217,7 +217,8 @@ def test_pool_bad_geometry_is_a_status_code_everywhere(kw, code):
     assert L.mcn_pool_output_size(ctypes.byref(d), None, None) == code
     p = 4096
     assert B.mcn_pool_forward(d, p, p, None) == code
-    assert B.mcn_pool_backward(d, p, p, p, None) == code
+    assert B.mcn_pool_backward(d, p, p, p, None, 0, None) == code
+    assert L.mcn_pool_workspace_size(ctypes.byref(d), ctypes.byref(ctypes.c_size_t(0))) == code
 
 
 def test_pool_null_pointers_are_rejected():
@@ -225,6 +226,12 @@ def test_pool_null_pointers_are_rejected():
     assert B.lib().mcn_pool_output_size(None, None, None) == B.MCN_BAD_ARG
     assert B.mcn_pool_forward(d, None, p, None) == B.MCN_BAD_ARG
     assert B.mcn_pool_forward(d, p, None, None) == B.MCN_BAD_ARG
-    assert B.mcn_pool_backward(d, None, p, p, None) == B.MCN_BAD_ARG       # max pooling needs x
-    assert B.mcn_pool_backward(d, p, None, p, None) == B.MCN_BAD_ARG
-    assert B.mcn_pool_backward(d, p, p, None, None) == B.MCN_BAD_ARG
+    need = B.mcn_pool_workspace_size(d)
+    assert need == 2 * 3 * 4 * 9      # one byte per output sample (4 x 9 per plane)
+    assert B.mcn_pool_backward(d, None, p, p, p, need, None) == B.MCN_BAD_ARG       # max pooling needs x
+    assert B.mcn_pool_backward(d, p, None, p, p, need, None) == B.MCN_BAD_ARG
+    assert B.mcn_pool_backward(d, p, p, None, p, need, None) == B.MCN_BAD_ARG
+    assert B.mcn_pool_backward(d, p, p, p, p, need - 1, None) == B.MCN_WORKSPACE_TOO_SMALL
+    assert B.mcn_pool_backward(d, p, p, p, None, need, None) == B.MCN_WORKSPACE_TOO_SMALL
+    assert B.mcn_pool_workspace_size(pdesc(method=B.MCN_POOL_AVG)) == 0
+    assert B.lib().mcn_pool_workspace_size(ctypes.byref(d), None) == B.MCN_BAD_ARG

@@ -94,6 +94,7 @@ PSWEEP = [
     (6, 6, 2, 2, (6, 6), (1, 1), (0, 0, 0, 0), "max"),         # one window = the whole plane
     (1, 1, 1, 1, (1, 1), (1, 1), (0, 0, 0, 0), "avg"),
     (70, 3, 5, 2, (4, 3), (2, 2), (3, 1, 2, 0), "max"),
+    (40, 36, 2, 2, (17, 16), (5, 7), (3, 2, 0, 9), "max"),     # 272 samples per window: the form without a workspace
 ]
 
 
@@ -129,6 +130,6 @@ def test_pool_ties_select_the_first_maximum():
     # average pooling does not read x
     d = B.make_pool_desc(x.shape, (2, 2), (1, 1), (0, 0, 0, 0), B.MCN_POOL_AVG)
     out = torch.empty_like(x)
-    assert B.mcn_pool_backward(d, None, p.data_ptr(), out.data_ptr(), torch.cuda.current_stream().cuda_stream) == 0
+    assert B.mcn_pool_backward(d, None, p.data_ptr(), out.data_ptr(), None, 0, torch.cuda.current_stream().cuda_stream) == 0
     torch.cuda.synchronize()
     assert np.allclose(out.cpu().numpy(), oracle_pool.backward(x.cpu().numpy(), p.cpu().numpy(), (2, 2), (1, 1), (0, 0, 0, 0), "avg"))
