@@ -384,6 +384,24 @@ inline bool plan_wgrad(const ConvView &v, int n_cu, WgradPlan *pl) {
     const int64_t total = tiles * NU;
     const int64_t want = (int64_t)n_cu * bestOcc;
     P.nblocks = (int)(total < want ? total : want);
+    P.nchunks = 0;
+    // Arrays that stream from memory: the chunked schedule (kern_wgrad.h) reads them about once instead of
+    // once per tile, if it keeps the compute units about as busy as equal ranges would (rounds of `want`
+    // resident blocks, each block a chunk plus a fixed part).  It costs about 1 % of time on the large
+    // layers (a few idle blocks, chunks that differ by a unit) and saves 2-10x of their memory traffic.
+    if (4.0 * ((double)v.H * v.W * v.Ctot + (double)v.Ho * v.Wo * v.Ktot) * v.N > 64.0 * 1024 * 1024) {
+        int best_nch = 0;
+        double best_time = 1e300;
+        for (int64_t nch = 1; nch <= NU && nch * tiles <= 4 * want; ++nch) {
+            const int64_t rounds = (nch * tiles + want - 1) / want;
+            const double time = (double)rounds * ((double)((NU + nch - 1) / nch) + 2.0);
+            if (time < best_time * 0.9999999) { best_time = time; best_nch = (int)nch; }
+        }
+        if (best_nch > 0 && ((double)total / (double)want) / best_time >= 0.95) {
+            P.nchunks = best_nch;
+            P.nblocks = (int)(tiles * best_nch);
+        }
+    }
     pl->occupancy = bestOcc;
     pl->partial_floats = P.nblocks > 1 ? (size_t)2 * P.nblocks * TK * TR : 0;
     pl->shape = shape; pl->TK = TK; pl->TR = TR; pl->NT = NT;

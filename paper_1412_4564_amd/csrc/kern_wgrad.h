@@ -53,7 +53,16 @@ struct WgradParams {
     int XS;              // floats per slab buffer (max channels of an r tile * CP)
     int tiles, nblocks;
     int relu;            // 1: results are written as max(0, .)  (forward pass of a fully-connected layer + ReLU)
+    int nchunks;         // 0: blocks share the list of all (tile, unit) pairs in equal contiguous ranges;
+                         // > 0: block (tile, chunk) sums chunk `chunk` of nchunks equal ranges of the tile's units
 };
+
+// Chunked schedule: blocks are numbered chunk-major (virtual block = tile + tiles*chunk) and the virtual
+// numbers are dealt to the XCDs in contiguous runs (consecutive hardware block ids land on different
+// XCDs), so the tiles of one chunk, which read the same dzdy and x at the same time, share one L2 and
+// memory delivers each operand about once.  The grid is padded to a multiple of 8; padding blocks do nothing.
+__device__ __host__ inline int wg_chunk_grid(int nblocks) { return nblocks < 8 ? nblocks : (nblocks + 7) / 8 * 8; }
+__device__ inline int wg_chunk_virtual_block(int b, int grid) { return grid % 8 == 0 ? (b % 8) * (grid / 8) + b / 8 : b; }
 
 // S1: vertical stride 1 (the slab rows of consecutive pixels are adjacent)
 template <int WK, int WR, int MK, int MR, bool S1, int WPE>
@@ -84,9 +93,20 @@ __global__ __launch_bounds__(64 * WK * WR, WPE) void wgrad_sk_kernel(WgradParams
     const int wk = wave % WK, wr = wave / WK;
     const int HW = P.H * P.W, HoWo = P.Ho * P.Wo;
 
-    const int vb = sk_virtual_block(blockIdx.x, P.nblocks);
-    const long long total = (long long)P.tiles * P.NU;
-    const long long ub = sk_begin(total, P.nblocks, vb), ue = sk_begin(total, P.nblocks, vb + 1);
+    int vb;
+    long long ub, ue;
+    if (P.nchunks > 0) {
+        vb = wg_chunk_virtual_block(blockIdx.x, gridDim.x);
+        if (vb >= P.nblocks) return;
+        const int tile = vb % P.tiles, chunk = vb / P.tiles;
+        ub = (long long)tile * P.NU + (long long)P.NU * chunk / P.nchunks;
+        ue = (long long)tile * P.NU + (long long)P.NU * (chunk + 1) / P.nchunks;
+    } else {
+        vb = sk_virtual_block(blockIdx.x, P.nblocks);
+        const long long total = (long long)P.tiles * P.NU;
+        ub = sk_begin(total, P.nblocks, vb);
+        ue = sk_begin(total, P.nblocks, vb + 1);
+    }
     if (ub >= ue) return;
 
     // ---- per-lane quantities that hold for every unit ------------------------------------------
@@ -356,6 +376,39 @@ __global__ __launch_bounds__(512) void wgrad_fixup_kernel(WgradParams P, const f
             const int slot = i == 0 ? slot0 : 2 * (b0 + i);
             acc += part[(size_t)slot * (TK * TR) + e];
         }
+        red[pg][el] = acc;
+        __syncthreads();
+        if (pg == 0) {
+            const int kloc = e / TR, rl = e - kloc * TR;
+            const int r = rt * TR + rl;
+            if (kloc < klim && r < P.R) {
+                float v = ((red[0][el] + red[1][el]) + (red[2][el] + red[3][el])) +
+                          ((red[4][el] + red[5][el]) + (red[6][el] + red[7][el]));
+                if (rbias) v += rbias[r];
+                if (P.relu) v = fmaxf(v, 0.f);
+                out[(size_t)(g * P.Kg + kt * TK + kloc) * P.R + r] = v;
+            }
+        }
+        __syncthreads();
+    }
+}
+
+// The same for the chunked schedule: the pieces of tile t are the first slots of blocks t + tiles*i.
+template <int TK, int TR>
+__global__ __launch_bounds__(512) void wgrad_chunk_fixup_kernel(WgradParams P, const float *__restrict__ part,
+                                                                const float *__restrict__ rbias, float *__restrict__ out) {
+    const int t = blockIdx.x;
+    int tt = t;
+    const int rt = tt % P.RT; tt /= P.RT;
+    const int kt = tt % P.KT;
+    const int g = tt / P.KT;
+    const int klim = min(P.Kg - kt * TK, TK);
+    __shared__ float red[8][64];
+    const int el = threadIdx.x & 63, pg = threadIdx.x >> 6;
+    for (int e0 = blockIdx.y * 64; e0 < TK * TR; e0 += gridDim.y * 64) {
+        const int e = e0 + el;
+        float acc = 0.f;
+        for (int i = pg; i < P.nchunks; i += 8) acc += part[(size_t)(2 * (t + P.tiles * i)) * (TK * TR) + e];
         red[pg][el] = acc;
         __syncthreads();
         if (pg == 0) {

@@ -240,15 +240,20 @@ int launch_wgrad_inst2(const WgradPlan &pl, const float *x, const float *dzdy, c
                                            (int)pl.lds_bytes);
         if (e != hipSuccess) { g_last_hip_error = (int)e; return MCN_HIP_ERROR; }
     }
-    hipLaunchKernelGGL(kern, dim3(P.nblocks), dim3(64 * WK * WR), pl.lds_bytes, s, P, x, dzdy, rbias, out, part);
+    const bool chunked = P.nchunks > 0;
+    hipLaunchKernelGGL(kern, dim3(chunked ? wg_chunk_grid(P.nblocks) : P.nblocks), dim3(64 * WK * WR), pl.lds_bytes, s, P,
+                       x, dzdy, rbias, out, part);
     int st = check_launch();
-    if (st || P.nblocks < 2) return st;
+    if (st || P.nblocks < 2 || P.nchunks == 1) return st;
     constexpr int TK = WK * MK * 32, TR = WR * MR * 32;
     // at most nblocks - 1 tiles are shared, but which ones is cheaper to find per tile
     int fy = 2048 / pl.P.tiles;          // about 2048 blocks in all
     if (fy < 1) fy = 1;
     if (fy > TK * TR / 64) fy = TK * TR / 64;
-    hipLaunchKernelGGL((wgrad_fixup_kernel<TK, TR>), dim3(P.tiles, fy), dim3(512), 0, s, P, part, rbias, out);
+    if (chunked)
+        hipLaunchKernelGGL((wgrad_chunk_fixup_kernel<TK, TR>), dim3(P.tiles, fy), dim3(512), 0, s, P, part, rbias, out);
+    else
+        hipLaunchKernelGGL((wgrad_fixup_kernel<TK, TR>), dim3(P.tiles, fy), dim3(512), 0, s, P, part, rbias, out);
     return check_launch();
 }
 
