@@ -19,6 +19,8 @@ struct ConvView {
     int OH, OW, oi0, osi, oj0, osj; // placement of the view's output pixels in the output array
     // weight packing (PackParams): mode, shape of the caller's filter array, stride phase
     int pack_mode, HfA, WfA, DfA, pSh, pSw, pi, pj, ldk;
+    // all stride phases of an input derivative merged into one view (pack mode 3; kern_igemm.h)
+    int mD, mPt, mPl, B0i, B0j;
 };
 
 inline ConvView forward_view(const Geom &g) {
@@ -52,6 +54,46 @@ inline bool backward_data_view(const Geom &g, int pi, int pj, ConvView *out) {
     v.Hf = A; v.Wf = Bt; v.Sh = 1; v.Sw = 1; v.Pt = A - 1 - b0; v.Pl = Bt - 1 - d0;
     v.OH = g.H; v.OW = g.W; v.oi0 = i0; v.osi = g.Sh; v.oj0 = j0; v.osj = g.Sw;
     v.pack_mode = 1; v.HfA = g.Hf; v.WfA = g.Wf; v.DfA = g.Df; v.pSh = g.Sh; v.pSw = g.Sw; v.pi = pi; v.pj = pj;
+    *out = v;
+    return true;
+}
+
+// Input derivative with all Sh*Sw stride phases in ONE view: the phases read the same dzdy, so they can
+// share the slab and sit side by side in the "filter" dimension of the GEMM (merged filter = channel
+// + D' * phase).  Worth it when a phase alone would leave most of a 32-row MFMA tile empty (few
+// channels per group, e.g. the derivative with respect to an image with 3 channels).  Per direction
+// the phases' tap ranges are put into one window: output row i0 + Sh*m of phase pi meets dzdy rows
+// m + b0 - a, a = 0..A-1; with B0 = max b0 the window covers rows m + B0 - t, t = 0..TH-1.  Phases
+// without taps (stride larger than the filter) are all-zero filters, so nothing is left to fill.
+inline bool merged_backward_data_view(const Geom &g, ConvView *out) {
+    if (g.Sh * g.Sw < 2 || g.Df > 16 || g.Df * g.Sh * g.Sw > 1024) return false;
+    int B0[2] = {0, 0}, TH[2] = {1, 1};
+    const int Hf[2] = {g.Hf, g.Wf}, S[2] = {g.Sh, g.Sw}, Pd[2] = {g.Pt, g.Pl};
+    for (int d = 0; d < 2; ++d) {
+        bool any = false;
+        for (int pi = 0; pi < S[d]; ++pi) {
+            if (pi >= Hf[d]) continue;
+            const int i0 = ((pi - Pd[d]) % S[d] + S[d]) % S[d];
+            const int b0 = (i0 + Pd[d] - pi) / S[d];
+            if (!any || b0 > B0[d]) B0[d] = b0;
+            any = true;
+        }
+        for (int pi = 0; pi < S[d]; ++pi) {
+            if (pi >= Hf[d]) continue;
+            const int A = (Hf[d] - pi + S[d] - 1) / S[d];
+            const int i0 = ((pi - Pd[d]) % S[d] + S[d]) % S[d];
+            const int b0 = (i0 + Pd[d] - pi) / S[d];
+            if (A + B0[d] - b0 > TH[d]) TH[d] = A + B0[d] - b0;
+        }
+    }
+    ConvView v = {};
+    v.H = g.Ho; v.W = g.Wo; v.N = g.N; v.Ctot = g.K; v.Cg = g.Kg;
+    v.Ho = (g.H + g.Sh - 1) / g.Sh; v.Wo = (g.W + g.Sw - 1) / g.Sw;
+    v.Ktot = g.D; v.Kg = g.Df * g.Sh * g.Sw; v.G = g.G;
+    v.Hf = TH[0]; v.Wf = TH[1]; v.Sh = 1; v.Sw = 1; v.Pt = TH[0] - 1 - B0[0]; v.Pl = TH[1] - 1 - B0[1];
+    v.OH = g.H; v.OW = g.W; v.oi0 = 0; v.osi = g.Sh; v.oj0 = 0; v.osj = g.Sw;
+    v.pack_mode = 3; v.HfA = g.Hf; v.WfA = g.Wf; v.DfA = g.Df; v.pSh = g.Sh; v.pSw = g.Sw;
+    v.mD = g.Df; v.mPt = g.Pt; v.mPl = g.Pl; v.B0i = B0[0]; v.B0j = B0[1];
     *out = v;
     return true;
 }
@@ -247,6 +289,7 @@ inline bool plan_igemm(const ConvView &v, int n_cu, IgemmPlan *pl, bool bf16 = f
     const int64_t total = tiles * P.NU;
     P.nblocks = (int)(total < n_cu ? total : n_cu);
     P.OH = v.OH; P.OW = v.OW; P.oi0 = v.oi0; P.osi = v.osi; P.oj0 = v.oj0; P.osj = v.osj;
+    P.mD = v.mD; P.mPt = v.mPt; P.mPl = v.mPl;
     // packed weights per unit, in 32-bit words: bf16 steps hold 2 octets x TK filters x 16 bytes
     const size_t wsz = bf16 ? (size_t)P.NS * 2 * TK * 4 : ((size_t)P.NS * 2 * TK + 255) / 256 * 256;
     P.WSZ = (int)wsz;
@@ -269,6 +312,7 @@ inline bool plan_igemm(const ConvView &v, int n_cu, IgemmPlan *pl, bool bf16 = f
     Q.Kg = v.Kg; Q.Cg = v.Cg; Q.G = v.G; Q.KT = P.KT; Q.NU = P.NU; Q.NTR = P.NTR; Q.NS = P.NS; Q.WSZ = P.WSZ; Q.TK = TK;
     Q.DC = P.DC; Q.TC = P.TC; Q.pair_mode = P.pair_mode; Q.mode = v.pack_mode;
     Q.Sh = v.pSh; Q.Sw = v.pSw; Q.pi = v.pi; Q.pj = v.pj; Q.ldk = v.ldk;
+    Q.mD = v.mD; Q.Pt = v.mPt; Q.Pl = v.mPl; Q.B0i = v.B0i; Q.B0j = v.B0j;
     Q.total = (int)pl->packed_floats;
     return true;
 }

@@ -109,7 +109,25 @@ struct IgemmParams {
     int oi0, osi, oj0, osj;   // row = oi0 + osi*io, column = oj0 + osj*jo
     unsigned packed_bytes;    // size of the packed weights of this view
     int relu;                 // 1: results are written as max(0, .)  (fused ReLU block, Sec. 4.4 of the manual)
+    // Merged stride phases of an input derivative (mD > 0): "filter" kl of a group is channel kl % mD of
+    // stride phase kl / mD (phase = pi + osi*pj); its results go to rows i0 + osi*io, columns j0 + osj*jo
+    // of that channel, i0 = (pi - mPt) mod osi, j0 = (pj - mPl) mod osj, where they exist.
+    int mD, mPt, mPl;
 };
+
+// Merged phases: channel, and placement of output pixel (0,0), of merged filter kl
+struct MergedFilter {
+    int c, i0, j0;
+};
+__device__ __host__ inline MergedFilter merged_filter(const IgemmParams &P, int kl) {
+    MergedFilter f;
+    const int p = kl / P.mD;
+    f.c = kl - p * P.mD;
+    const int pj = p / P.osi, pi = p - pj * P.osi;
+    f.i0 = ((pi - P.mPt) % P.osi + P.osi) % P.osi;
+    f.j0 = ((pj - P.mPl) % P.osj + P.osj) % P.osj;
+    return f;
+}
 
 // Blocks on consecutive hardware ids land on different XCDs; give each XCD a contiguous
 // share of the work so that neighbouring tiles (shared halo, same weights) meet in one L2.
@@ -157,14 +175,29 @@ __device__ inline void unit_element(int pair_mode, int DC, int TC, int T, int tr
 //                          wt(k,c,ti,tj) = w[fi, fj, k, g*Cg + c]
 // mode 2 (1x1 view whose weights are a transposed matrix, used for the filter derivative of a
 //     fully-connected layer):  wt(k,c) = w[k + ldk*c]
+// mode 3 (input derivative, all stride phases merged; Kg = D'*Sh*Sw "filters", see IgemmParams::mD):
+//     filter k = channel k % mD of phase (pi, pj); along the rows the phase has A = ceil((Hf-pi)/Sh)
+//     taps fi = pi + Sh*a, a = 0..A-1, which meet dzdy row m + b0 - a for output row i0 + Sh*m
+//     (b0 = (i0 + Pt - pi)/Sh).  All phases share one window of the view: view tap ti stands for
+//     t = Hfv-1-ti, dzdy row m + B0 - t, so a = t - (B0 - b0); taps a phase does not have are zero.
 struct PackParams {
     int Hf, Wf;            // taps of the view
     int HfA, WfA, DfA;     // shape of the caller's filter array (modes 0, 1)
     int Kg, Cg, G, KT, NU, NTR, NS, WSZ, TK, DC, TC, pair_mode, mode;
     int Sh, Sw, pi, pj;    // mode 1
     int ldk;               // mode 2
+    int mD, Pt, Pl, B0i, B0j;   // mode 3: channels per phase, pads of the convolution, largest b0 per direction
     int total;
 };
+
+// one direction of mode 3: filter tap of view tap ti for phase pi, or -1
+__device__ __host__ inline int merged_tap(int ti, int Hfv, int HfA, int S, int Pt, int B0, int pi) {
+    const int A = pi < HfA ? (HfA - pi + S - 1) / S : 0;
+    const int i0 = ((pi - Pt) % S + S) % S;
+    const int b0 = (i0 + Pt - pi) / S;
+    const int a = (Hfv - 1 - ti) - (B0 - b0);
+    return (a >= 0 && a < A) ? pi + S * a : -1;
+}
 
 __global__ __launch_bounds__(256) void igemm_pack_weights_kernel(const float *__restrict__ w, float *__restrict__ packed,
                                                                  PackParams Q) {
@@ -192,8 +225,14 @@ __global__ __launch_bounds__(256) void igemm_pack_weights_kernel(const float *__
         } else if (Q.mode == 1) {
             const int fi = Q.pi + Q.Sh * (Q.Hf - 1 - ti), fj = Q.pj + Q.Sw * (Q.Wf - 1 - tj);
             v = w[fi + Q.HfA * (fj + Q.WfA * (k + (size_t)Q.DfA * (g * Q.Cg + c)))];
-        } else {
+        } else if (Q.mode == 2) {
             v = w[k + (size_t)Q.ldk * c];
+        } else {
+            const int ph = k / Q.mD, cch = k - ph * Q.mD;
+            const int pj = ph / Q.Sh, pi = ph - pj * Q.Sh;
+            const int fi = merged_tap(ti, Q.Hf, Q.HfA, Q.Sh, Q.Pt, Q.B0i, pi);
+            const int fj = merged_tap(tj, Q.Wf, Q.WfA, Q.Sw, Q.Pl, Q.B0j, pj);
+            if (fi >= 0 && fj >= 0) v = w[fi + Q.HfA * (fj + Q.WfA * (cch + (size_t)Q.DfA * (g * Q.Cg + c)))];
         }
     }
     packed[p] = v;
@@ -300,9 +339,10 @@ __global__ __launch_bounds__(64 * WK * WP, WPE) void igemm_sk_kernel(IgemmParams
         if (bias && uu == 0 && wave * 64 < TK) {
             // the tile's bias: start value of the accumulators of a tile this block owns entirely
             const int kl = l_kt * TK + wave * 64 + lane;
+            const int bidx = P.mD ? l_g * P.mD + kl % P.mD : l_g * P.Kg + kl;
             if (wave * 64 + lane < TK)
                 load_to_lds_b32(lds_address(blds + (l_t & 1) * TK + wave * 64),
-                                kl < P.Kg ? (unsigned)(l_g * P.Kg + kl) * 4u : SLAB_INVALID, brs, 0);
+                                kl < P.Kg ? (unsigned)bidx * 4u : SLAB_INVALID, brs, 0);
         }
         const int cg = FIXED ? uu : uu / P.NTR;
         const int c0 = cg * DC;
@@ -323,6 +363,7 @@ __global__ __launch_bounds__(64 * WK * WP, WPE) void igemm_sk_kernel(IgemmParams
     int bbase[MP];   // slab offset (floats) of the pixel's window origin (+ channel half when FIXED)
     unsigned ooff[MP];   // byte offset of the lane's first result of the tile relative to the tile's output
                          // window (filter k0 + 4*half of image n_first), or SLAB_INVALID
+    bool last_row[MP], last_col[MP];   // merged phases: the pixel is in the view's last row / column
     __amdgpu_buffer_rsrc_t ors = __builtin_amdgcn_make_buffer_rsrc((void *)out, 0, 0, BUFFER_FLAGS);   // the tile's output window
     int c_t = 0, c_kt = 0, c_g = 0;
     bool need_init = true;
@@ -349,8 +390,10 @@ __global__ __launch_bounds__(64 * WK * WP, WPE) void igemm_sk_kernel(IgemmParams
             const int ucol = jo * P.Sw + (n - n_first) * P.Wp - u0;
             bbase[mp] = (ok ? ii * P.Sh + SRP * ucol : 0) + (FIXED ? half * CP : 0);
             ooff[mp] = ok ? 4u * (unsigned)((P.oi0 + P.osi * io) + P.OH * (P.oj0 + P.osj * jo) +
-                                            OHW * (P.Ktot * (n - n_first) + 4 * half))
+                                            OHW * (P.Ktot * (n - n_first) + (P.mD ? 0 : 4 * half)))
                           : SLAB_INVALID;
+            last_row[mp] = io == P.Ho - 1;
+            last_col[mp] = jo == P.Wo - 1;
         }
         const size_t out_base = (size_t)n_first * P.Ktot * OHW;
         size_t out_left = ((size_t)P.N * P.Ktot * OHW - out_base) * 4;
@@ -466,6 +509,41 @@ __global__ __launch_bounds__(64 * WK * WP, WPE) void igemm_sk_kernel(IgemmParams
             }
         }
     };
+    // Merged phases: the two half-waves hold filters of different phases, so the filter part of the address
+    // and the "does this pixel exist in this phase" test are per half-wave.
+    auto store_tile_merged = [&]() {
+#pragma unroll
+        for (int mk = 0; mk < MK; ++mk) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int kl0 = c_kt * TK + (wk * MK + mk) * 32 + (v >> 2) * 8 + (v & 3);
+                if (kl0 >= P.Kg) continue;
+                unsigned foff[2];
+                bool short_row[2], short_col[2], none[2];
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    const int kl = kl0 + 4 * h;
+                    none[h] = kl >= P.Kg;
+                    const MergedFilter f = merged_filter(P, none[h] ? 0 : kl);
+                    foff[h] = 4u * (unsigned)((c_g * P.mD + f.c) * OHW + f.i0 + P.OH * f.j0);
+                    short_row[h] = f.i0 + P.osi * (P.Ho - 1) >= P.OH;      // this phase has no last row
+                    short_col[h] = f.j0 + P.osj * (P.Wo - 1) >= P.OW;
+                }
+                const unsigned fo = half ? foff[1] : foff[0];
+                const bool sr = half ? short_row[1] : short_row[0];
+                const bool sc = half ? short_col[1] : short_col[0];
+                const bool no = half ? none[1] : none[0];
+#pragma unroll
+                for (int mp = 0; mp < MP; ++mp) {
+                    const bool drop = no || (sr && last_row[mp]) || (sc && last_col[mp]) || ooff[mp] == SLAB_INVALID;
+                    const unsigned vo = drop ? SLAB_INVALID : ooff[mp] + fo;
+                    float val = acc[mk][mp][v];
+                    if (P.relu) val = fmaxf(val, 0.f);
+                    __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(val), ors, vo, 0, 0);
+                }
+            }
+        }
+    };
     auto store_partial = [&](int slot) {
         float *dst = part + (size_t)slot * (TK * TQ);
 #pragma unroll
@@ -517,7 +595,7 @@ __global__ __launch_bounds__(64 * WK * WP, WPE) void igemm_sk_kernel(IgemmParams
             // the top of the next iteration and drain while it computes
             __builtin_amdgcn_s_waitcnt(WAIT_VMCNT0);
             loads_waited = true;
-            if (whole) store_tile();
+            if (whole) { if (P.mD) store_tile_merged(); else store_tile(); }
             else store_partial(2 * vb + (first_segment ? 0 : 1));
             first_segment = false;
             if (!last) {
@@ -557,7 +635,13 @@ __global__ __launch_bounds__(256) void igemm_fixup_kernel(IgemmParams P, const f
         const int jo = c - n * P.Wo;
         const int io = rb * P.TI + ii;
         if (kl >= P.Kg || q >= P.QN || io >= P.Ho) continue;
-        float acc = bias ? bias[g * P.Kg + kl] : 0.f;
+        int oi = P.oi0 + P.osi * io, oj = P.oj0 + P.osj * jo, och = g * P.Kg + kl;
+        if (P.mD) {
+            const MergedFilter f = merged_filter(P, kl);
+            oi += f.i0; oj += f.j0; och = g * P.mD + f.c;
+            if (oi >= P.OH || oj >= P.OW) continue;
+        }
+        float acc = bias ? bias[och] : 0.f;
         for (int b = j - 1; b < P.nblocks; ++b) {
             const long long bb = sk_begin(total, P.nblocks, b);
             if (bb >= t_hi) break;
@@ -565,8 +649,7 @@ __global__ __launch_bounds__(256) void igemm_fixup_kernel(IgemmParams P, const f
             acc += part[(size_t)slot * (TK * TQ) + e];
         }
         if (P.relu) acc = fmaxf(acc, 0.f);
-        out[(size_t)((P.oi0 + P.osi * io) + P.OH * ((P.oj0 + P.osj * jo) + P.OW * (P.Ktot * n))) +
-            (size_t)OHW * (g * P.Kg + kl)] = acc;
+        out[(size_t)(oi + P.OH * (oj + P.OW * (P.Ktot * n))) + (size_t)OHW * och] = acc;
     }
 }
 

@@ -125,14 +125,18 @@ const PlanEntry *plans_for(const mcn_conv_desc *d, const Geom &g) {
     // other views (and the filter derivative) compute in fp32, which meets the same error bound
     const bool bf = d->precision == MCN_PREC_BF16;
     auto plan_view = [&](const ConvView &v, IgemmPlan *pl) {
-        if (bf && v.Cg >= BF_DC && plan_igemm(v, ncu, pl, true)) return true;
+        if (bf && !v.mD && v.Cg >= BF_DC && plan_igemm(v, ncu, pl, true)) return true;    // merged phases: fp32 kernel only
         return plan_igemm(v, ncu, pl, false);
     };
     e.fwd_ok = on && plan_view(forward_view(g), &e.fwd);
     e.bwd_ok = on && g.Sh * g.Sw <= MAX_PHASES;
     e.n_bwd = 0;
     e.bwd_fill = false;
-    if (e.bwd_ok) {
+    ConvView mv;
+    if (on && merged_backward_data_view(g, &mv) && plan_view(mv, &e.bwd[0])) {
+        e.bwd_ok = true;       // one launch computes every stride phase
+        e.n_bwd = 1;
+    } else if (e.bwd_ok) {
         for (int pj = 0; pj < g.Sw && e.bwd_ok; ++pj)
             for (int pi = 0; pi < g.Sh && e.bwd_ok; ++pi) {
                 ConvView v;
