@@ -288,6 +288,9 @@ inline bool plan_igemm(const ConvView &v, int n_cu, IgemmPlan *pl, bool bf16 = f
     P.tiles = (int)tiles;
     const int64_t total = tiles * P.NU;
     P.nblocks = (int)(total < n_cu ? total : n_cu);
+    // whole tiles first, one share of the left-over tiles after (see IgemmParams::own): fewer tiles go through
+    // the workspace and the fix-up pass than when everything is shared
+    P.own = (int)(tiles / P.nblocks);
     P.OH = v.OH; P.OW = v.OW; P.oi0 = v.oi0; P.osi = v.osi; P.oj0 = v.oj0; P.osj = v.osj;
     P.mD = v.mD; P.mPt = v.mPt; P.mPl = v.mPl;
     // packed weights per unit, in 32-bit words: bf16 steps hold 2 octets x TK filters x 16 bytes

@@ -113,6 +113,10 @@ struct IgemmParams {
     // stride phase kl / mD (phase = pi + osi*pj); its results go to rows i0 + osi*io, columns j0 + osj*jo
     // of that channel, i0 = (pi - mPt) mod osi, j0 = (pj - mPl) mod osj, where they exist.
     int mD, mPt, mPl;
+    // Schedule: every block first computes `own` whole tiles of its own (tiles vb*own .. vb*own+own-1); only
+    // the tiles left over, own*nblocks .. tiles-1, are cut into equal contiguous ranges of units and shared.
+    // own = 0 shares everything.
+    int own;
 };
 
 // Merged phases: channel, and placement of output pixel (0,0), of merged filter kl
@@ -265,7 +269,7 @@ __global__ __launch_bounds__(64 * WK * WP, WPE) void igemm_sk_kernel(IgemmParams
     float *wbuf = lds;                                   // [2][WSZ]
     float *xbuf = lds + 2 * WSZ;                         // [2][DC*CP]
     int *gtab = reinterpret_cast<int *>(xbuf + 2 * XSZ); // [EPT][NT]: entry (s, tid) is private to thread tid
-    float *blds = reinterpret_cast<float *>(gtab + P.EPT * NT);   // [2][TK] bias of the tile, by tile parity
+    float *blds = reinterpret_cast<float *>(gtab + P.EPT * NT);   // [2][TK] bias of the tile, slots used in turn
     int *otab = reinterpret_cast<int *>(blds + 2 * TK);           // table mode: [NTR][NS][2] slab offsets
 
     const int tid = threadIdx.x;
@@ -277,9 +281,12 @@ __global__ __launch_bounds__(64 * WK * WP, WPE) void igemm_sk_kernel(IgemmParams
     const int OHW = P.OH * P.OW;
 
     const int vb = sk_virtual_block(blockIdx.x, P.nblocks);
-    const long long total = (long long)P.tiles * NU;
+    const int tile_s0 = P.own * P.nblocks;                          // first shared tile
+    const long long total = (long long)(P.tiles - tile_s0) * NU;    // units of the shared tiles
     const long long ub = sk_begin(total, P.nblocks, vb), ue = sk_begin(total, P.nblocks, vb + 1);
-    if (ub >= ue) return;
+    const int n_own = P.own * NU;                                    // units of this block's own tiles
+    const int nunits = n_own + (int)(ue - ub);
+    if (nunits == 0) return;
 
     if constexpr (!FIXED) {
         const int T = P.Hf * P.Wf;
@@ -301,9 +308,10 @@ __global__ __launch_bounds__(64 * WK * WP, WPE) void igemm_sk_kernel(IgemmParams
     // ---- load side: tile whose units are being fetched ------------------------------------
     buffer_rsrc xrs = wrs;
     unsigned wtile_off = 0;        // byte offset of the tile's packed weights
-    int l_t = 0, l_kt = 0, l_g = 0;
+    int l_kt = 0, l_g = 0;
+    int l_seq = -1, c_seq = -1;    // how many tiles the load / the compute side has started: picks the bias slot
     auto setup_load = [&](int t) {
-        l_t = t;
+        ++l_seq;
         int kt, pt, rb, g;
         decode_tile(P, t, &kt, &pt, &rb, &g);
         const int q0 = pt * TQ;
@@ -341,7 +349,7 @@ __global__ __launch_bounds__(64 * WK * WP, WPE) void igemm_sk_kernel(IgemmParams
             const int kl = l_kt * TK + wave * 64 + lane;
             const int bidx = P.mD ? l_g * P.mD + kl % P.mD : l_g * P.Kg + kl;
             if (wave * 64 + lane < TK)
-                load_to_lds_b32(lds_address(blds + (l_t & 1) * TK + wave * 64),
+                load_to_lds_b32(lds_address(blds + (l_seq & 1) * TK + wave * 64),
                                 kl < P.Kg ? (unsigned)bidx * 4u : SLAB_INVALID, brs, 0);
         }
         const int cg = FIXED ? uu : uu / P.NTR;
@@ -365,11 +373,11 @@ __global__ __launch_bounds__(64 * WK * WP, WPE) void igemm_sk_kernel(IgemmParams
                          // window (filter k0 + 4*half of image n_first), or SLAB_INVALID
     bool last_row[MP], last_col[MP];   // merged phases: the pixel is in the view's last row / column
     __amdgpu_buffer_rsrc_t ors = __builtin_amdgcn_make_buffer_rsrc((void *)out, 0, 0, BUFFER_FLAGS);   // the tile's output window
-    int c_t = 0, c_kt = 0, c_g = 0;
+    int c_kt = 0, c_g = 0;
     bool need_init = true;
     floatx16 acc[MK][MP];
     auto setup_compute = [&](int t) {
-        c_t = t;
+        ++c_seq;
         int kt, pt, rb, g;
         decode_tile(P, t, &kt, &pt, &rb, &g);
         c_kt = kt; c_g = g;
@@ -404,7 +412,7 @@ __global__ __launch_bounds__(64 * WK * WP, WPE) void igemm_sk_kernel(IgemmParams
     // start value of the accumulators: the bias for a tile this block owns entirely (staged in LDS with the
     // tile's first unit), zero for a piece of a shared tile (the fix-up pass adds the bias)
     auto init_acc = [&](bool with_bias) {
-        const float *bl = blds + (c_t & 1) * TK;
+        const float *bl = blds + (c_seq & 1) * TK;
 #pragma unroll
         for (int mk = 0; mk < MK; ++mk)
 #pragma unroll
@@ -558,13 +566,22 @@ __global__ __launch_bounds__(64 * WK * WP, WPE) void igemm_sk_kernel(IgemmParams
     };
 
     // ---- the block's range of units --------------------------------------------------------
-    int t_c = (int)(ub / NU);             // compute-side tile and unit
-    int uu_c = (int)(ub - (long long)t_c * NU);
+    // position = (tile, unit); `done` = units consumed so far.  After the block's own tiles comes its range
+    // of the shared ones, which may start in the middle of a tile.
+    const int t_s = tile_s0 + (int)(ub / NU), uu_s = (int)(ub - (ub / NU) * NU);
+    auto advance = [&](int &t, int &uu, int done) {
+        if (done == n_own) { t = t_s; uu = uu_s; }
+        else if (++uu == NU) { uu = 0; ++t; }
+    };
+    int t_c = n_own ? vb * P.own : t_s;   // compute-side tile and unit
+    int uu_c = n_own ? 0 : uu_s;
     int t_l = t_c, uu_l = uu_c;           // the load side runs one unit ahead
     bool first_segment = true;
-    // the segment starting at unit uu of tile t covers the tile iff it starts at 0 and the
-    // block's range reaches the tile's end
-    auto segment_is_whole = [&](int t, int uu) { return uu == 0 && (long long)(t + 1) * NU <= ue; };
+    // the segment starting at unit uu of tile t covers the tile iff the tile is the block's own, or it
+    // starts at 0 and the block's shared range reaches the tile's end
+    auto segment_is_whole = [&](int t, int uu) {
+        return t < tile_s0 || (uu == 0 && (long long)(t - tile_s0 + 1) * NU <= ue);
+    };
     setup_load(t_l);
     issue_loads(uu_l, 0);
     bool whole = segment_is_whole(t_c, uu_c);
@@ -573,7 +590,6 @@ __global__ __launch_bounds__(64 * WK * WP, WPE) void igemm_sk_kernel(IgemmParams
     // The two waves that share a SIMD fetch the next unit at different times (one before its
     // MFMAs, the other half-way through), so that one of them always feeds the matrix core.
     const bool late_fetch = NT == 512 && ((wave >> 2) & 1);
-    const int nunits = (int)(ue - ub);
     bool loads_waited = false;
     for (int it = 0; it < nunits; ++it) {
         if (!loads_waited) __builtin_amdgcn_s_waitcnt(WAIT_VMCNT0);   // this wave's LDS-direct loads have landed
@@ -582,7 +598,9 @@ __global__ __launch_bounds__(64 * WK * WP, WPE) void igemm_sk_kernel(IgemmParams
         if (need_init) { init_acc(whole && bias != nullptr); need_init = false; }
         const bool more = it + 1 < nunits;
         auto fetch_next = [&]() {
-            if (++uu_l == NU) { uu_l = 0; ++t_l; setup_load(t_l); }
+            const int t_prev = t_l;
+            advance(t_l, uu_l, it + 1);
+            if (t_l != t_prev) setup_load(t_l);
             issue_loads(uu_l, (it + 1) & 1);
         };
         if (more && !late_fetch) fetch_next();
@@ -597,10 +615,10 @@ __global__ __launch_bounds__(64 * WK * WP, WPE) void igemm_sk_kernel(IgemmParams
             loads_waited = true;
             if (whole) { if (P.mD) store_tile_merged(); else store_tile(); }
             else store_partial(2 * vb + (first_segment ? 0 : 1));
-            first_segment = false;
+            first_segment = it + 1 == n_own;      // the shared range starts with a "first" segment again
             if (!last) {
-                ++t_c; uu_c = 0;
-                whole = segment_is_whole(t_c, 0);
+                advance(t_c, uu_c, it + 1);
+                whole = segment_is_whole(t_c, uu_c);
                 setup_compute(t_c);
             }
         } else {
@@ -616,15 +634,34 @@ template <int TK, int TQ>
 __global__ __launch_bounds__(256) void igemm_fixup_kernel(IgemmParams P, const float *__restrict__ part,
                                                           const float *__restrict__ bias, float *__restrict__ out) {
     const int j = blockIdx.x + 1;                    // boundary between virtual blocks j-1 and j
-    const long long total = (long long)P.tiles * P.NU;
+    const int tile_s0 = P.own * P.nblocks;           // the shared tiles start here; unit numbers are relative to them
+    const long long total = (long long)(P.tiles - tile_s0) * P.NU;
     const long long B = sk_begin(total, P.nblocks, j);
-    const int t = (int)(B / P.NU);
-    const long long t_lo = (long long)t * P.NU, t_hi = t_lo + P.NU;
+    const int ts = (int)(B / P.NU);
+    const int t = tile_s0 + ts;
+    const long long t_lo = (long long)ts * P.NU, t_hi = t_lo + P.NU;
     if (B == t_lo) return;                                        // boundary on a tile edge: nothing shared
     if (sk_begin(total, P.nblocks, j - 1) > t_lo) return;         // an earlier boundary owns this tile
     int kt, pt, rb, g;
     decode_tile(P, t, &kt, &pt, &rb, &g);
     const int OHW = P.OH * P.OW;
+    // the tile's pieces, in block order: block j-1's (its first segment if its range starts in this tile,
+    // else its second), then the first segments of the following blocks that have units of this tile
+    constexpr int MAX_PIECES = 1024;
+    __shared__ int slots[MAX_PIECES];
+    __shared__ int npieces;
+    if (threadIdx.x == 0) {
+        int n = 0;
+        for (int b = j - 1; b < P.nblocks && n < MAX_PIECES; ++b) {
+            const long long bb = sk_begin(total, P.nblocks, b);
+            if (bb >= t_hi) break;
+            if (sk_begin(total, P.nblocks, b + 1) == bb) continue;      // a block without shared units wrote nothing
+            slots[n++] = 2 * b + (bb >= t_lo ? 0 : 1);
+        }
+        npieces = n;
+    }
+    __syncthreads();
+    const int np = npieces;
     for (int e = blockIdx.y * 256 + threadIdx.x; e < TK * TQ; e += gridDim.y * 256) {
         const int kloc = e / TQ, ql = e - kloc * TQ;
         const int kl = kt * TK + kloc;
@@ -642,12 +679,7 @@ __global__ __launch_bounds__(256) void igemm_fixup_kernel(IgemmParams P, const f
             if (oi >= P.OH || oj >= P.OW) continue;
         }
         float acc = bias ? bias[och] : 0.f;
-        for (int b = j - 1; b < P.nblocks; ++b) {
-            const long long bb = sk_begin(total, P.nblocks, b);
-            if (bb >= t_hi) break;
-            const int slot = 2 * b + (bb >= t_lo ? 0 : 1);
-            acc += part[(size_t)slot * (TK * TQ) + e];
-        }
+        for (int i = 0; i < np; ++i) acc += part[(size_t)slots[i] * (TK * TQ) + e];
         if (P.relu) acc = fmaxf(acc, 0.f);
         out[(size_t)(oi + P.OH * (oj + P.OW * (P.Ktot * n))) + (size_t)OHW * och] = acc;
     }

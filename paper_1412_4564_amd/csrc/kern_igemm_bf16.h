@@ -96,7 +96,7 @@ __global__ __launch_bounds__(64 * WK * WP, WPE) void igemm_bf16_kernel(IgemmPara
     float *wbuf = lds;                                   // [2][WSZ]
     float *xbuf = lds + 2 * WSZ;                         // [2][XSZ]
     int *gtab = reinterpret_cast<int *>(xbuf + 2 * XSZ); // [EPT][NT]: entry (s, tid) is private to thread tid
-    float *blds = reinterpret_cast<float *>(gtab + P.EPT * NT);   // [2][TK] bias of the tile, by tile parity
+    float *blds = reinterpret_cast<float *>(gtab + P.EPT * NT);   // [2][TK] bias of the tile, slots used in turn
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -107,9 +107,12 @@ __global__ __launch_bounds__(64 * WK * WP, WPE) void igemm_bf16_kernel(IgemmPara
     const int OHW = P.OH * P.OW;
 
     const int vb = sk_virtual_block(blockIdx.x, P.nblocks);
-    const long long total = (long long)P.tiles * NU;
+    const int tile_s0 = P.own * P.nblocks;                          // first shared tile
+    const long long total = (long long)(P.tiles - tile_s0) * NU;    // units of the shared tiles
     const long long ub = sk_begin(total, P.nblocks, vb), ue = sk_begin(total, P.nblocks, vb + 1);
-    if (ub >= ue) return;
+    const int n_own = P.own * NU;                                    // units of this block's own tiles
+    const int nunits = n_own + (int)(ue - ub);
+    if (nunits == 0) return;
 
     const buffer_rsrc wrs = make_rsrc(wpk, P.packed_bytes);
     const buffer_rsrc brs = make_rsrc(bias, bias ? (unsigned)P.Ktot * 4u : 0u);
@@ -118,9 +121,10 @@ __global__ __launch_bounds__(64 * WK * WP, WPE) void igemm_bf16_kernel(IgemmPara
     // ---- load side: tile whose units are being fetched ------------------------------------
     __amdgpu_buffer_rsrc_t xrs = __builtin_amdgcn_make_buffer_rsrc((void *)in, 0, 0, BUFFER_FLAGS);
     unsigned wtile_off = 0;        // byte offset of the tile's packed weights
-    int l_t = 0, l_kt = 0, l_g = 0;
+    int l_kt = 0, l_g = 0;
+    int l_seq = -1, c_seq = -1;    // how many tiles the load / the compute side has started: picks the bias slot
     auto setup_load = [&](int t) {
-        l_t = t;
+        ++l_seq;
         int kt, pt, rb, g;
         decode_tile(P, t, &kt, &pt, &rb, &g);
         const int q0 = pt * TQ;
@@ -157,7 +161,7 @@ __global__ __launch_bounds__(64 * WK * WP, WPE) void igemm_bf16_kernel(IgemmPara
             // the tile's bias: start value of the accumulators of a tile this block owns entirely
             const int kl = l_kt * TK + wave * 64 + lane;
             if (wave * 64 + lane < TK)
-                load_to_lds_b32(lds_address(blds + (l_t & 1) * TK + wave * 64),
+                load_to_lds_b32(lds_address(blds + (l_seq & 1) * TK + wave * 64),
                                 kl < P.Kg ? (unsigned)(l_g * P.Kg + kl) * 4u : SLAB_INVALID, brs, 0);
         }
         const int c0 = (uu / P.NTR) * BF_DC;
@@ -208,11 +212,11 @@ __global__ __launch_bounds__(64 * WK * WP, WPE) void igemm_bf16_kernel(IgemmPara
     unsigned ooff[MP];   // byte offset of the lane's first result of the tile relative to the tile's output
                          // window (filter k0 + 4*half of image n_first), or SLAB_INVALID
     __amdgpu_buffer_rsrc_t ors = __builtin_amdgcn_make_buffer_rsrc((void *)out, 0, 0, BUFFER_FLAGS);   // the tile's output window
-    int c_t = 0, c_kt = 0, c_g = 0;
+    int c_kt = 0, c_g = 0;
     bool need_init = true;
     floatx16 acc[MK][MP];
     auto setup_compute = [&](int t) {
-        c_t = t;
+        ++c_seq;
         int kt, pt, rb, g;
         decode_tile(P, t, &kt, &pt, &rb, &g);
         c_kt = kt; c_g = g;
@@ -243,7 +247,7 @@ __global__ __launch_bounds__(64 * WK * WP, WPE) void igemm_bf16_kernel(IgemmPara
         need_init = true;
     };
     auto init_acc = [&](bool with_bias) {
-        const float *bl = blds + (c_t & 1) * TK;
+        const float *bl = blds + (c_seq & 1) * TK;
 #pragma unroll
         for (int mk = 0; mk < MK; ++mk)
 #pragma unroll
@@ -340,25 +344,37 @@ __global__ __launch_bounds__(64 * WK * WP, WPE) void igemm_bf16_kernel(IgemmPara
     };
 
     // ---- the block's range of units --------------------------------------------------------
-    int t_c = (int)(ub / NU);             // compute-side tile and unit
-    int uu_c = (int)(ub - (long long)t_c * NU);
+    // position = (tile, unit); `done` = units consumed so far.  After the block's own tiles comes its range
+    // of the shared ones, which may start in the middle of a tile.
+    const int t_s = tile_s0 + (int)(ub / NU), uu_s = (int)(ub - (ub / NU) * NU);
+    auto advance = [&](int &t, int &uu, int done) {
+        if (done == n_own) { t = t_s; uu = uu_s; }
+        else if (++uu == NU) { uu = 0; ++t; }
+    };
+    int t_c = n_own ? vb * P.own : t_s;   // compute-side tile and unit
+    int uu_c = n_own ? 0 : uu_s;
     int t_l = t_c, uu_l = uu_c;           // the load side runs one unit ahead
     bool first_segment = true;
-    auto segment_is_whole = [&](int t, int uu) { return uu == 0 && (long long)(t + 1) * NU <= ue; };
+    // the segment starting at unit uu of tile t covers the tile iff the tile is the block's own, or it
+    // starts at 0 and the block's shared range reaches the tile's end
+    auto segment_is_whole = [&](int t, int uu) {
+        return t < tile_s0 || (uu == 0 && (long long)(t - tile_s0 + 1) * NU <= ue);
+    };
     setup_load(t_l);
     issue_loads(uu_l, 0);
     write_slab(0);
     bool whole = segment_is_whole(t_c, uu_c);
     setup_compute(t_c);
 
-    const int nunits = (int)(ue - ub);
     for (int it = 0; it < nunits; ++it) {
         __builtin_amdgcn_s_waitcnt(WAIT_VMCNT0);   // this wave's packed weights have landed in LDS
         lds_barrier();                             // everyone's operands are in place, and the other buffer is free
         if (need_init) { init_acc(whole && bias != nullptr); need_init = false; }
         const bool more = it + 1 < nunits;
         if (more) {
-            if (++uu_l == NU) { uu_l = 0; ++t_l; setup_load(t_l); }
+            const int t_prev = t_l;
+            advance(t_l, uu_l, it + 1);
+            if (t_l != t_prev) setup_load(t_l);
             issue_loads(uu_l, (it + 1) & 1);
         }
         __builtin_amdgcn_sched_barrier(0);
@@ -369,10 +385,10 @@ __global__ __launch_bounds__(64 * WK * WP, WPE) void igemm_bf16_kernel(IgemmPara
         if (uu_c + 1 == NU || last) {
             if (whole) store_tile();
             else store_partial(2 * vb + (first_segment ? 0 : 1));
-            first_segment = false;
+            first_segment = it + 1 == n_own;      // the shared range starts with a "first" segment again
             if (!last) {
-                ++t_c; uu_c = 0;
-                whole = segment_is_whole(t_c, 0);
+                advance(t_c, uu_c, it + 1);
+                whole = segment_is_whole(t_c, uu_c);
                 setup_compute(t_c);
             }
         } else {
