@@ -164,7 +164,7 @@ __global__ __launch_bounds__(64 * WK * WP, WPE) void igemm_bf16_kernel(IgemmPara
                 load_to_lds_b32(lds_address(blds + (l_seq & 1) * TK + wave * 64),
                                 kl < P.Kg ? (unsigned)(l_g * P.Kg + kl) * 4u : SLAB_INVALID, brs, 0);
         }
-        const int c0 = (uu / P.NTR) * BF_DC;
+        const int c0 = (P.NTR == 1 ? uu : uu / P.NTR) * BF_DC;      // one tap range is the common case: no division
         const bool full = c0 + BF_DC <= P.Cg;
 #pragma unroll
         for (int s = 0; s < BF_EPT_MAX; ++s) {
@@ -267,8 +267,12 @@ __global__ __launch_bounds__(64 * WK * WP, WPE) void igemm_bf16_kernel(IgemmPara
         const char *wl = reinterpret_cast<const char *>(wbuf + b * WSZ) + aoff;
         const char *xl = reinterpret_cast<const char *>(xbuf + b * XSZ);
         const int T = P.Hf * P.Wf;
-        int tap = (uu % P.NTR) * P.TC;
-        int fj = tap / P.Hf, fi = tap - fj * P.Hf;
+        int tap = 0, fj = 0, fi = 0;
+        if (P.NTR != 1) {
+            tap = (uu % P.NTR) * P.TC;
+            fj = tap / P.Hf;
+            fi = tap - fj * P.Hf;
+        }
         int so = 16 * (fj * SRP + fi);                   // byte offset of the current tap in the slab
         bf16x8 a0[MK], b0[MP], a1[MK], b1[MP];
         auto fetch = [&](bf16x8 *a, bf16x8 *bq) {
