@@ -226,6 +226,7 @@ inline bool plan_igemm(const ConvView &v, int n_cu, IgemmPlan *pl, bool bf16 = f
     for (int parts = 2; parts <= 16; ++parts) cand[nc++] = (v.Ho + parts - 1) / parts;
     for (int t = 32; t <= 256; t += 32) cand[nc++] = t;
     for (int t = 1; t <= 16; t *= 2) cand[nc++] = t;
+    const bool input_streams = 4.0 * v.H * v.W * (double)v.Ctot * v.N > 32.0 * 1024 * 1024;
     double best_score = 1e30;
     int bestTI = 0, bestSC = 0;
     UnitCut best_uc = {};
@@ -263,7 +264,9 @@ inline bool plan_igemm(const ConvView &v, int n_cu, IgemmPlan *pl, bool bf16 = f
         const double mfma_waste = (double)RB * PT * TQ / ((double)v.Ho * v.Wo * v.N);
         const int NCG = (v.Cg + uc.DC - 1) / uc.DC;
         const double red_waste = (double)NCG * uc.NTR * uc.NS * (bf16 ? BF_DC : 2) / ((double)v.Cg * T);
-        const double score = mfma_waste * red_waste * (1.0 + 0.05 * (double)CP / TQ);
+        // when the input streams from memory, short slab rows waste most of every 128-byte line they touch
+        const double score = mfma_waste * red_waste * (1.0 + 0.05 * (double)CP / TQ) *
+                             (input_streams ? 1.0 + 4.0 / (double)SR : 1.0);
         if (score < best_score) { best_score = score; bestTI = TI; bestSC = SC; best_uc = uc; }
     }
     if (!bestTI) return false;
