@@ -127,7 +127,7 @@ def _targs(L):
     return L["up"], L["crop"], L["groups"]
 
 
-def run_convt_full(L, with_bias=True, seed=0):
+def run_convt_full(L, with_bias=True, seed=0, precision=B.MCN_PREC_FP32):
     """All four operations of the transpose block on layer L, every element compared."""
     up, crop, G = _targs(L)
     x, f, b = synth.make_tx(L, seed), synth.make_tf(L, seed), synth.make_tb(L, seed)
@@ -136,9 +136,9 @@ def run_convt_full(L, with_bias=True, seed=0):
     xd, fd, bd, pd = np64(x), np64(f), np64(b), np64(p)
     bb = bd if with_bias else None
     xg, fg, bg, pg = gpu(x), gpu(f), gpu(b), gpu(p)
-    y = B.convt_forward(xg, fg, bg if with_bias else None, up, crop, G)
-    dx = B.convt_backward_data(x.shape, fg, pg, up, crop, G)
-    df = B.convt_backward_filter(xg, f.shape, pg, up, crop, G)
+    y = B.convt_forward(xg, fg, bg if with_bias else None, up, crop, G, precision)
+    dx = B.convt_backward_data(x.shape, fg, pg, up, crop, G, precision)
+    df = B.convt_backward_filter(xg, f.shape, pg, up, crop, G, precision)
     db = B.convt_backward_bias(x.shape, f.shape, pg, up, crop, G)
     torch.cuda.synchronize()
     assert tuple(y.shape) == (L["N"], G * L["Kf"], wo, ho)

@@ -37,6 +37,21 @@ def test_convt_workload_layers_full_size_sampled(name):
     U.assert_errors(U.run_convt_sampled(L), label="convt layer %s full size" % name)
 
 
+@pytest.mark.parametrize("name,nb", [("t1", 2), ("t2", 3), ("t3", 4)])
+def test_convt_bf16_operands(name, nb):
+    """The transpose block under the bf16-operand flag: its three MFMA passes run on the bf16 kernels where
+    those apply (error bar 1e-2 against the oracle on the fp32 inputs)."""
+    L = with_batch(synth.CONVT_LAYERS[name], nb)
+    d = B.make_convt_desc(synth.tx_shape(L), synth.tf_shape(L), L["up"], L["crop"], L["groups"], B.MCN_PREC_BF16)
+    names = [B.mcn_convt_kernel_name(d, op) for op in range(3)]
+    errs = U.run_convt_full(L, precision=B.MCN_PREC_BF16)
+    print("convt bf16", name, names, errs, flush=True)
+    U.assert_errors(errs, precision=B.MCN_PREC_BF16, label="convt bf16 %s" % name)
+    if name in ("t1", "t2"):
+        assert "bf16" in names[0] and "bf16" in names[1], names
+        assert errs["forward"] > 2e-5      # the operands really were rounded
+
+
 TSWEEP = [
     # H  W  D  N  Hf Wf Kf G   up      crop
     (5, 7, 4, 2, 3, 3, 5, 1, (1, 1), (0, 0, 0, 0)),          # plain full correlation
