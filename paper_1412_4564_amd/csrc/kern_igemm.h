@@ -24,12 +24,16 @@
 //  * reduction: a tile's reduction is cut into NU units of DC channels x TC taps.
 //    One unit = NS steps of one MFMA per accumulator; a step consumes either two
 //    channels of one tap (pair_mode 0) or two taps of one channel (pair_mode 1).
-//  * scheduling: the list of all (tile, unit) pairs is cut into nblocks equal
-//    contiguous ranges, one per resident block, so every compute unit gets the same
-//    amount of matrix work whatever the number of tiles.  A block that owns a whole
-//    tile writes it to `out`; pieces of a tile shared between blocks go to a
-//    workspace and are summed in block order by igemm_fixup_kernel (no float
-//    atomics: results do not depend on scheduling).
+//  * scheduling: every resident block first computes floor(tiles / nblocks) whole
+//    tiles of its own; the (tile, unit) pairs of the left-over tiles are cut into
+//    nblocks equal contiguous ranges, so every compute unit gets the same amount of
+//    matrix work whatever the number of tiles.  A block that computes a whole tile
+//    writes it to `out`; pieces of a tile shared between blocks go to a workspace
+//    and are summed in block order by igemm_fixup_kernel (no float atomics: results
+//    do not depend on scheduling).
+//  * input derivative with a stride: one launch per stride phase, or -- few channels
+//    per group -- all phases in one launch, side by side in the filter dimension
+//    (IgemmParams::mD).
 //  * staging: global -> LDS loads bypass the registers (buffer_load ... lds),
 //    double-buffered one unit ahead; padding is produced by the out-of-range rule of
 //    buffer loads (reads as zero).
