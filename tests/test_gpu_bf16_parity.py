@@ -143,6 +143,29 @@ def test_bf16_filter_derivative_sweep(case):
     check_filter_derivative(names, vs_fp32, vs_rounded, "filter derivative %d" % case)
 
 
+def test_bf16_random_geometries():
+    rng = np.random.default_rng(57721)
+    for t in range(24):
+        g = int(rng.choice([1, 1, 2]))
+        Df, Kg = int(rng.integers(8, 70)), int(rng.integers(20, 150))
+        Hf, Wf = int(rng.integers(1, 6)), int(rng.integers(1, 6))
+        H, W = int(rng.integers(Hf, 34)), int(rng.integers(Wf, 34))
+        st = (int(rng.integers(1, 3)), int(rng.integers(1, 3)))
+        pad = tuple(int(v) for v in rng.integers(0, 3, size=4))
+        L = custom_layer(H, W, g * Df, int(rng.integers(1, 5)), Hf, Wf, Df, g * Kg, st, pad, idx=200 + t)
+        d = B.make_desc(synth.x_shape(L), synth.w_shape(L), st, pad, BF)
+        names = [B.mcn_conv_kernel_name(d, op) for op in range(3)]
+        vs_fp32, vs_rounded = run_bf16(L, with_bias=bool(t % 2))
+        print("random bf16 case", t, L, names, vs_fp32, vs_rounded, flush=True)
+        for k, v in vs_fp32.items():
+            assert v <= U.TOL_BF16, (t, k, v)
+        if names[0] == "igemm_bf16":
+            assert vs_rounded["forward"] <= U.TOL_FWD, (t, vs_rounded)
+        if names[1] == "igemm_bf16":
+            assert vs_rounded["backward_data"] <= U.TOL_BWD, (t, vs_rounded)
+        check_filter_derivative(names, vs_fp32, vs_rounded, "random bf16 %d" % t)
+
+
 def test_bf16_few_channels_stay_on_fp32_kernels():
     # 3 input channels: the bf16 kernel would waste 13 of its 16 reduction lanes; the fp32 kernel
     # meets the bf16 bound trivially
