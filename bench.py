@@ -256,6 +256,47 @@ def make_state(name, precision, rotate_mb):
     return LayerState(name, synth.LAYERS[name], precision, rotate_mb)
 
 
+def measured_ceilings(stream_obj):
+    """What this GPU sustains, measured here with HIP events: the register-only MFMA loops of the
+    library (no memory, LDS or barrier in the loop) and a plain copy of 512 MiB (read + write = 1 GiB
+    of traffic, larger than the last-level cache)."""
+    stream = stream_obj.cuda_stream
+    sink = torch.empty(B.MCN_PROBE_SINK_FLOATS, dtype=torch.float32, device="cuda")
+
+    def timed(fn, reps=3):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream_obj)
+        for _ in range(reps):
+            fn()
+        e1.record(stream_obj)
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    out = {}
+    for key, prec in (("mfma_f32_TFLOPs", B.MCN_PREC_FP32), ("mfma_bf16_TFLOPs", B.MCN_PREC_BF16)):
+        flops = []
+
+        def loop():
+            st, f = B.mcn_probe_mfma(prec, 8000, sink.data_ptr(), sink.numel(), stream)
+            if st:
+                raise B.McnError(st, "mcn_probe_mfma")
+            flops.append(f)
+        ms = timed(loop)
+        out[key] = round(flops[0] / ms / 1e9, 1)
+    n = 128 * 1024 * 1024
+    src = torch.ones(n, dtype=torch.float32, device="cuda")
+    dst = torch.empty_like(src)
+
+    def copy():
+        st = B.mcn_probe_copy(src.data_ptr(), dst.data_ptr(), n, stream)
+        if st:
+            raise B.McnError(st, "mcn_probe_copy")
+    out["copy_GBps"] = round(8.0 * n / timed(copy) / 1e6, 1)
+    return out
+
+
 def cpu_baseline(names):
     """The oracle as it stands, timed on this machine's host cores on a bounded sample
     of the same workload: the same layers at a reduced batch."""
@@ -296,6 +337,8 @@ def main():
     ap.add_argument("--fused-relu", action="store_true",
                     help="also time the fused conv+ReLU calls against their unfused sequences (extra object "
                          "'fused_relu' in the JSON line)")
+    ap.add_argument("--no-ceilings", action="store_true",
+                    help="skip the measured ceilings (register-only MFMA loops, plain copy) in 'measured_ceilings'")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 256 MiB elementwise copy three times, so that a counter run "
                          "(rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE) holds a kernel of known traffic to scale by")
@@ -370,13 +413,13 @@ def main():
         peak = BF16_MFMA_PEAK_TFLOPS if "bf16" in dom.kernels[op] else FP32_MFMA_PEAK_TFLOPS
         roof = {"bound": "mfma", "achieved": round(ach, 2), "peak": peak, "unit": "TFLOP/s",
                 "frac": round(ach / peak, 4),
-                "traffic": measured_traffic("%s.%s" % (dom.name, OPS_dom[op])) if args.workload == "vgg3x3" else None,
+                "traffic": measured_traffic("%s.%s" % (dom.name, OPS_dom[op])) if args.workload == "vgg3x3" and prec == B.MCN_PREC_FP32 else None,
                 "kernel": "%s.%s (%s)" % (dom.name, OPS_dom[op], dom.kernels[op])}
     else:
         ach = dom.bytes[op] / per[li, op] / 1e6
         roof = {"bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(ach / HBM_PEAK_GBS, 4),
-                "traffic": measured_traffic("%s.%s" % (dom.name, OPS_dom[op])) if args.workload == "vgg3x3" else None,
+                "traffic": measured_traffic("%s.%s" % (dom.name, OPS_dom[op])) if args.workload == "vgg3x3" and prec == B.MCN_PREC_FP32 else None,
                 "kernel": "%s.%s (%s)" % (dom.name, OPS_dom[op], dom.kernels[op])}
 
     out = {
@@ -392,6 +435,14 @@ def main():
         "roofline": roof,
         "calls": detail,
     }
+    if not args.no_ceilings:
+        # outside the timed region: what the chip sustains, so that the fraction of the published peak in
+        # 'roofline' can be read beside the fraction of a ceiling measured on this very GPU
+        ceil = measured_ceilings(stream_obj)
+        out["measured_ceilings"] = ceil
+        top = (ceil["copy_GBps"] if roof["bound"] == "hbm" else
+               ceil["mfma_bf16_TFLOPs"] if roof["peak"] == BF16_MFMA_PEAK_TFLOPS else ceil["mfma_f32_TFLOPs"])
+        roof["frac_of_measured_ceiling"] = round(roof["achieved"] / top, 4)
     if args.fused_relu:
         out["fused_relu"] = fused_relu_report(layers, stream_obj, args.steps)
     if args.copy_calibration:

@@ -251,6 +251,29 @@ int mcn_last_hip_error(void);
  * descriptor.  Host only. */
 const char *mcn_conv_kernel_name(const mcn_conv_desc *desc, int op);
 
+/* ---- Measurement aids (no part of the paper's blocks) ---------------------------------
+ * The rates this GPU sustains on the two resources the kernels above are priced against,
+ * so that a benchmark can quote a fraction of the measured ceiling beside the fraction
+ * of the published one.  Both are asynchronous on `stream`; time them with HIP events. */
+
+/* Floats `sink` of mcn_probe_mfma must hold. */
+#define MCN_PROBE_SINK_FLOATS (2048 * 256)
+
+/* Register-only matrix-core loop: 2048 blocks of 4 waves, each wave issuing 4 * iters
+ * independent 32x32 MFMAs with no memory, LDS or barrier in the loop.
+ * precision MCN_PREC_FP32 -> v_mfma_f32_32x32x2_f32, MCN_PREC_BF16 -> v_mfma_f32_32x32x16_bf16.
+ * sink (device, MCN_PROBE_SINK_FLOATS floats, overwritten) keeps the loop alive;
+ * *flops (host, may be NULL) receives the floating-point operations the launch performs.
+ * MCN_BAD_ARG for a NULL sink, iters < 1 or an unknown precision; MCN_WORKSPACE_TOO_SMALL
+ * when sink_floats < MCN_PROBE_SINK_FLOATS. */
+int mcn_probe_mfma(int precision, int32_t iters, float *sink, size_t sink_floats, double *flops,
+                   void *stream);
+
+/* dst[0..n) = src[0..n) (device pointers, both 16-byte aligned, not overlapping) with
+ * 16-byte loads and stores: one read stream and one write stream, 8 * n bytes of traffic.
+ * MCN_BAD_ARG for NULL or misaligned pointers; n = 0 launches nothing. */
+int mcn_probe_copy(const float *src, float *dst, size_t n, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

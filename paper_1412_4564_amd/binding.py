@@ -31,7 +31,9 @@ EXPORTS = (
     "mcn_convt_output_size", "mcn_convt_workspace_size", "mcn_convt_forward", "mcn_convt_backward_data",
     "mcn_convt_backward_filter", "mcn_convt_backward_bias", "mcn_convt_kernel_name",
     "mcn_pool_output_size", "mcn_pool_workspace_size", "mcn_pool_forward", "mcn_pool_backward",
+    "mcn_probe_mfma", "mcn_probe_copy",
 )
+MCN_PROBE_SINK_FLOATS = 2048 * 256
 
 
 class mcn_conv_desc(ctypes.Structure):
@@ -99,6 +101,9 @@ def lib():
         L.mcn_pool_workspace_size.argtypes = [PD, ctypes.POINTER(SZ)]
         for f in ("mcn_pool_output_size", "mcn_pool_workspace_size", "mcn_pool_forward", "mcn_pool_backward"):
             getattr(L, f).restype = ctypes.c_int
+        L.mcn_probe_mfma.argtypes = [ctypes.c_int, ctypes.c_int32, P, SZ, ctypes.POINTER(ctypes.c_double), P]
+        L.mcn_probe_copy.argtypes = [P, P, SZ, P]
+        L.mcn_probe_mfma.restype = L.mcn_probe_copy.restype = ctypes.c_int
         T = ctypes.POINTER(mcn_convt_desc)
         L.mcn_convt_output_size.argtypes = [T, I32P, I32P]
         L.mcn_convt_workspace_size.argtypes = [T, ctypes.c_int, ctypes.POINTER(SZ)]
@@ -200,6 +205,17 @@ def mcn_pool_workspace_size(desc):
 
 def mcn_pool_backward(desc, x, dzdy, dzdx, ws, ws_bytes, stream):
     return lib().mcn_pool_backward(ctypes.byref(desc), x, dzdy, dzdx, ws, ws_bytes, stream)
+
+
+def mcn_probe_mfma(precision, iters, sink, sink_floats, stream):
+    """Launches the register-only MFMA loop; returns (status, flops of the launch)."""
+    flops = ctypes.c_double(0.0)
+    st = lib().mcn_probe_mfma(int(precision), int(iters), sink, sink_floats, ctypes.byref(flops), stream)
+    return st, flops.value
+
+
+def mcn_probe_copy(src, dst, n, stream):
+    return lib().mcn_probe_copy(src, dst, n, stream)
 
 
 def make_convt_desc(xshape, fshape, upsample=(1, 1), crop=(0, 0, 0, 0), groups=1, precision=MCN_PREC_FP32):

@@ -12,6 +12,7 @@
 #include "kern_igemm.h"
 #include "igemm_plan.h"
 #include "kern_pool.h"
+#include "kern_probe.h"
 
 using namespace mcn;
 
@@ -715,6 +716,30 @@ int mcn_pool_backward(const mcn_pool_desc *desc, const float *x, const float *dz
         return check_launch();
     }
     hipLaunchKernelGGL(pool_backward_kernel, dim3(cdiv(n_in, 256)), dim3(256), 0, s, g, x, dzdy, dzdx, n_in);
+    return check_launch();
+}
+
+int mcn_probe_mfma(int precision, int32_t iters, float *sink, size_t sink_floats, double *flops, void *stream) {
+    if (!sink || iters < 1 || (precision != MCN_PREC_FP32 && precision != MCN_PREC_BF16)) return MCN_BAD_ARG;
+    if (sink_floats < (size_t)MCN_PROBE_SINK_FLOATS) return MCN_WORKSPACE_TOO_SMALL;
+    static_assert(MCN_PROBE_SINK_FLOATS == PROBE_BLOCKS * PROBE_THREADS, "sink size");
+    hipStream_t s = (hipStream_t)stream;
+    const double per_mfma = precision == MCN_PREC_BF16 ? 2.0 * 32 * 32 * 16 : 2.0 * 32 * 32 * 2;
+    if (flops) *flops = per_mfma * PROBE_ACC * (double)iters * (PROBE_THREADS / 64) * PROBE_BLOCKS;
+    if (precision == MCN_PREC_BF16)
+        hipLaunchKernelGGL(probe_mfma_kernel<1>, dim3(PROBE_BLOCKS), dim3(PROBE_THREADS), 0, s, sink, iters, 1.0f);
+    else
+        hipLaunchKernelGGL(probe_mfma_kernel<0>, dim3(PROBE_BLOCKS), dim3(PROBE_THREADS), 0, s, sink, iters, 1.0f);
+    return check_launch();
+}
+
+int mcn_probe_copy(const float *src, float *dst, size_t n, void *stream) {
+    if (!src || !dst || ((uintptr_t)src & 15) || ((uintptr_t)dst & 15)) return MCN_BAD_ARG;
+    if (n == 0) return MCN_OK;
+    const size_t words = (n >> 2) + 1;
+    const unsigned blocks = (unsigned)(words < (size_t)PROBE_BLOCKS * PROBE_THREADS
+                                           ? (words + PROBE_THREADS - 1) / PROBE_THREADS : PROBE_BLOCKS * 4);
+    hipLaunchKernelGGL(probe_copy_kernel, dim3(blocks), dim3(PROBE_THREADS), 0, (hipStream_t)stream, src, dst, n);
     return check_launch();
 }
 

@@ -235,3 +235,20 @@ def test_pool_null_pointers_are_rejected():
     assert B.mcn_pool_backward(d, p, p, p, None, need, None) == B.MCN_WORKSPACE_TOO_SMALL
     assert B.mcn_pool_workspace_size(pdesc(method=B.MCN_POOL_AVG)) == 0
     assert B.lib().mcn_pool_workspace_size(ctypes.byref(d), None) == B.MCN_BAD_ARG
+
+
+def test_probe_arguments_are_checked():
+    # bad arguments come back as status codes before anything is launched
+    sink = 4096
+    assert B.mcn_probe_mfma(B.MCN_PREC_FP32, 1, None, B.MCN_PROBE_SINK_FLOATS, None)[0] == B.MCN_BAD_ARG
+    assert B.mcn_probe_mfma(B.MCN_PREC_FP32, 0, sink, B.MCN_PROBE_SINK_FLOATS, None)[0] == B.MCN_BAD_ARG
+    assert B.mcn_probe_mfma(5, 1, sink, B.MCN_PROBE_SINK_FLOATS, None)[0] == B.MCN_BAD_ARG
+    assert B.mcn_probe_mfma(B.MCN_PREC_BF16, 1, sink, B.MCN_PROBE_SINK_FLOATS - 1, None)[0] == B.MCN_WORKSPACE_TOO_SMALL
+    assert B.mcn_probe_copy(None, 4096, 16, None) == B.MCN_BAD_ARG
+    assert B.mcn_probe_copy(4096, None, 16, None) == B.MCN_BAD_ARG
+    assert B.mcn_probe_copy(4096 + 4, 8192, 16, None) == B.MCN_BAD_ARG       # misaligned source
+    assert B.mcn_probe_copy(4096, 8192 + 8, 16, None) == B.MCN_BAD_ARG       # misaligned destination
+    assert B.mcn_probe_copy(4096, 8192, 0, None) == B.MCN_OK                 # nothing to copy, nothing launched
+    hdr = open(os.path.join(ROOT, "include", "mcnconv.h")).read()
+    assert re.search(r"#define\s+MCN_PROBE_SINK_FLOATS\s+\(2048 \* 256\)", hdr)
+    assert B.MCN_PROBE_SINK_FLOATS == 2048 * 256
