@@ -133,7 +133,7 @@ enum IgemmShape { IG_128x256 = 0, IG_64x512 = 1, IG_32x256 = 2, IG_NONE = -1 };
 struct IgemmPlan {
     int shape;          // IgemmShape
     bool bf16;          // operands rounded to bf16 (kern_igemm_bf16.h); sizes below are then in 32-bit words
-    bool fixed33;       // 3x3 filter instantiation
+    int fixed;          // index into IGEMM_FIXED: an instantiation with compile-time filter size (0 = none)
     int TK, TQ, NT;
     IgemmParams P;
     PackParams Q;
@@ -143,7 +143,12 @@ struct IgemmPlan {
 };
 
 constexpr size_t IGEMM_LDS_LIMIT = 160 * 1024;
-constexpr int IGEMM_FIXED_DC = 8;
+// Instantiations with a compile-time filter size and channel count per unit: every LDS offset of
+// the MFMA loop is then an immediate or one of a few hoisted sums, against an offset-table read and
+// several address instructions per step in the general kernel.
+struct IgemmFixed { int HF, WF, DC; };
+constexpr IgemmFixed IGEMM_FIXED[] = {{0, 0, 0}, {3, 3, 8}, {1, 1, 32}, {5, 5, 4}};
+constexpr int IGEMM_N_FIXED = 4;
 
 // exact number of slab columns the worst pixel tile needs
 inline int slab_columns(const ConvView &v, int TI, int TQ, int Wp) {
@@ -210,14 +215,14 @@ inline bool cut_units_bf16(const ConvView &v, int TK, int64_t CP, size_t lds_lef
     return false;
 }
 
-inline bool plan_igemm(const ConvView &v, int n_cu, IgemmPlan *pl, bool bf16 = false) {
+inline bool plan_igemm_kind(const ConvView &v, int n_cu, IgemmPlan *pl, bool bf16, int fixed) {
     const int T = v.Hf * v.Wf;
+    const IgemmFixed FX = IGEMM_FIXED[fixed];
     int shape, WK, WP, MK, MP;
     if (v.Kg > 64) { shape = IG_128x256; WK = 2; WP = 4; MK = 2; MP = 2; }
     else if (v.Kg > 32) { shape = IG_64x512; WK = 1; WP = 8; MK = 2; MP = 2; }
     else { shape = IG_32x256; WK = 1; WP = 4; MK = 1; MP = 2; }
     const int TK = WK * MK * 32, TQ = WP * MP * 32, NT = 64 * WK * WP;
-    const bool fixed33 = !bf16 && (v.Hf == 3 && v.Wf == 3 && v.Cg >= 2 * IGEMM_FIXED_DC && v.Cg % IGEMM_FIXED_DC == 0);
     const int Wp = (v.Wo - 1) * v.Sw + v.Wf;
     // candidates for the row-block height
     int cand[48];
@@ -249,8 +254,8 @@ inline bool plan_igemm(const ConvView &v, int n_cu, IgemmPlan *pl, bool bf16 = f
         if (bf16) {
             if (fixed_lds + 64 > IGEMM_LDS_LIMIT) continue;
             if (!cut_units_bf16(v, TK, CP, IGEMM_LDS_LIMIT - fixed_lds - 64, &uc)) continue;
-        } else if (fixed33) {
-            uc.pair_mode = 0; uc.DC = IGEMM_FIXED_DC; uc.TC = 9; uc.NTR = 1; uc.NS = (IGEMM_FIXED_DC / 2) * 9;
+        } else if (fixed) {
+            uc.pair_mode = 0; uc.DC = FX.DC; uc.TC = T; uc.NTR = 1; uc.NS = (FX.DC / 2) * T;
             if ((2 * ((size_t)uc.NS * 2 * TK + 255) + 2 * (size_t)uc.DC * CP) * 4 + fixed_lds > IGEMM_LDS_LIMIT) continue;
         } else {
             if (fixed_lds + 4096 > IGEMM_LDS_LIMIT) continue;
@@ -303,13 +308,13 @@ inline bool plan_igemm(const ConvView &v, int n_cu, IgemmPlan *pl, bool bf16 = f
     if (pl->packed_floats * 4 >= 2147483647ull) return false;
     P.packed_bytes = (unsigned)(pl->packed_floats * 4);
     pl->partial_floats = P.nblocks > 1 ? (size_t)2 * P.nblocks * TK * TQ : 0;
-    pl->shape = shape; pl->bf16 = bf16; pl->fixed33 = fixed33; pl->TK = TK; pl->TQ = TQ; pl->NT = NT;
+    pl->shape = shape; pl->bf16 = bf16; pl->fixed = fixed; pl->TK = TK; pl->TQ = TQ; pl->NT = NT;
     if (bf16)
         pl->lds_bytes = (2 * wsz + 2 * (size_t)2 * P.CP * 4 + (size_t)P.EPT * NT + 2 * TK + 4) *
                         sizeof(float);
     else
         pl->lds_bytes = (2 * wsz + 2 * (size_t)P.DC * P.CP + (size_t)P.EPT * NT + 2 * TK +
-                         (fixed33 ? 0 : (size_t)P.NTR * P.NS * 2) + 4) * sizeof(float);
+                         (fixed ? 0 : (size_t)P.NTR * P.NS * 2) + 4) * sizeof(float);
     if (pl->lds_bytes > IGEMM_LDS_LIMIT) return false;
 
     PackParams &Q = pl->Q;
@@ -321,6 +326,19 @@ inline bool plan_igemm(const ConvView &v, int n_cu, IgemmPlan *pl, bool bf16 = f
     Q.mD = v.mD; Q.Pt = v.mPt; Q.Pl = v.mPl; Q.B0i = v.B0i; Q.B0j = v.B0j;
     Q.total = (int)pl->packed_floats;
     return true;
+}
+
+// The instantiation with this view's filter size if there is one, its channels divide into the
+// fixed units and a plan fits; the general kernel otherwise.
+inline bool plan_igemm(const ConvView &v, int n_cu, IgemmPlan *pl, bool bf16 = false) {
+    if (!bf16)
+        for (int f = 1; f < IGEMM_N_FIXED; ++f) {
+            const IgemmFixed FX = IGEMM_FIXED[f];
+            if (v.Hf == FX.HF && v.Wf == FX.WF && v.Cg >= 2 * FX.DC && v.Cg % FX.DC == 0 &&
+                plan_igemm_kind(v, n_cu, pl, false, f))
+                return true;
+        }
+    return plan_igemm_kind(v, n_cu, pl, bf16, 0);
 }
 
 }  // namespace mcn

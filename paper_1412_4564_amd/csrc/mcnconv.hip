@@ -200,6 +200,23 @@ int launch_igemm_bf16_inst(const IgemmPlan &pl, const float *in, const float *wp
     return check_launch();
 }
 
+// one block shape, every instantiation of IGEMM_FIXED
+template <int WK, int WP, int MK, int MP>
+int launch_igemm_fixed(const IgemmPlan &pl, const float *in, const float *wpk, const float *bias, float *out,
+                       float *part, hipStream_t s, int relu) {
+    static_assert(IGEMM_N_FIXED == 4, "one case per entry of IGEMM_FIXED");
+    switch (pl.fixed) {
+        case 0: return launch_igemm_inst<WK, WP, MK, MP, 0, 0, 0>(pl, in, wpk, bias, out, part, s, relu);
+        case 1: return launch_igemm_inst<WK, WP, MK, MP, IGEMM_FIXED[1].HF, IGEMM_FIXED[1].WF, IGEMM_FIXED[1].DC>(
+                    pl, in, wpk, bias, out, part, s, relu);
+        case 2: return launch_igemm_inst<WK, WP, MK, MP, IGEMM_FIXED[2].HF, IGEMM_FIXED[2].WF, IGEMM_FIXED[2].DC>(
+                    pl, in, wpk, bias, out, part, s, relu);
+        case 3: return launch_igemm_inst<WK, WP, MK, MP, IGEMM_FIXED[3].HF, IGEMM_FIXED[3].WF, IGEMM_FIXED[3].DC>(
+                    pl, in, wpk, bias, out, part, s, relu);
+        default: return MCN_BAD_ARG;
+    }
+}
+
 int launch_igemm(const IgemmPlan &pl, const float *in, const float *w, const float *bias, float *out, void *ws,
                  hipStream_t s, int relu = 0) {
     float *packed = (float *)ws;
@@ -220,17 +237,10 @@ int launch_igemm(const IgemmPlan &pl, const float *in, const float *w, const flo
     int st = check_launch();
     if (st) return st;
     switch (pl.shape) {
-        case IG_128x256:
-            return pl.fixed33 ? launch_igemm_inst<2, 4, 2, 2, 3, 3, IGEMM_FIXED_DC>(pl, in, packed, bias, out, part, s, relu)
-                              : launch_igemm_inst<2, 4, 2, 2, 0, 0, 0>(pl, in, packed, bias, out, part, s, relu);
-        case IG_64x512:
-            return pl.fixed33 ? launch_igemm_inst<1, 8, 2, 2, 3, 3, IGEMM_FIXED_DC>(pl, in, packed, bias, out, part, s, relu)
-                              : launch_igemm_inst<1, 8, 2, 2, 0, 0, 0>(pl, in, packed, bias, out, part, s, relu);
-        case IG_32x256:
-            return pl.fixed33 ? launch_igemm_inst<1, 4, 1, 2, 3, 3, IGEMM_FIXED_DC>(pl, in, packed, bias, out, part, s, relu)
-                              : launch_igemm_inst<1, 4, 1, 2, 0, 0, 0>(pl, in, packed, bias, out, part, s, relu);
-        default:
-            return MCN_BAD_ARG;
+        case IG_128x256: return launch_igemm_fixed<2, 4, 2, 2>(pl, in, packed, bias, out, part, s, relu);
+        case IG_64x512: return launch_igemm_fixed<1, 8, 2, 2>(pl, in, packed, bias, out, part, s, relu);
+        case IG_32x256: return launch_igemm_fixed<1, 4, 1, 2>(pl, in, packed, bias, out, part, s, relu);
+        default: return MCN_BAD_ARG;
     }
 }
 

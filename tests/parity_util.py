@@ -33,8 +33,16 @@ def layer_args(L):
     return dict(stride=L["stride"], pad=L["pad"])
 
 
-def gpu(t):
-    return t.cuda()
+def gpu(t, misalign=0):
+    """Copy to the GPU; with misalign = 1..3 the copy starts that many floats past a 16-byte
+    boundary (torch allocations are aligned to 256 bytes or more)."""
+    if not misalign:
+        return t.cuda()
+    flat = torch.empty(t.numel() + 4, dtype=t.dtype, device="cuda")
+    out = flat[misalign:misalign + t.numel()].view(t.shape)
+    out.copy_(t)
+    assert out.data_ptr() % 16 == 4 * misalign and out.is_contiguous()
+    return out
 
 
 def np64(t):
@@ -51,8 +59,9 @@ def sample_idx(total, count, seed):
     return idx
 
 
-def run_layer_full(L, precision=B.MCN_PREC_FP32, with_bias=True, seed=0):
-    """All four operations on layer L, every element compared.  Returns dict of errors."""
+def run_layer_full(L, precision=B.MCN_PREC_FP32, with_bias=True, seed=0, misalign=0):
+    """All four operations on layer L, every element compared.  Returns dict of errors.
+    misalign: the input arrays start that many floats past a 16-byte boundary."""
     st, pad = L["stride"], L["pad"]
     x, w, b = synth.make_x(L, seed), synth.make_w(L, seed), synth.make_b(L, seed)
     ho, wo = oracle.output_size(x.shape, w.shape, st, pad)
@@ -60,7 +69,7 @@ def run_layer_full(L, precision=B.MCN_PREC_FP32, with_bias=True, seed=0):
     xd, wd, bd, pd = np64(x), np64(w), np64(b), np64(p)
     bb = bd if with_bias else None
     out = {}
-    xg, wg, bg, pg = gpu(x), gpu(w), gpu(b), gpu(p)
+    xg, wg, bg, pg = gpu(x, misalign), gpu(w, misalign), gpu(b), gpu(p, misalign)
     y = B.conv_forward(xg, wg, bg if with_bias else None, st, pad, precision)
     dx = B.conv_backward_data(x.shape, wg, pg, st, pad, precision)
     dw = B.conv_backward_filter(xg, w.shape, pg, st, pad, precision)

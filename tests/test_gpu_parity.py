@@ -152,6 +152,34 @@ def test_tiles_shared_between_blocks_match_whole_tiles():
     U.assert_errors(U.run_layer_full(big5), label="whole tiles, 5x5, ragged filters")
 
 
+# ---- device pointers carry no alignment promise beyond that of a float ----------------------
+ANY_ALIGNMENT = [
+    custom_layer(16, 12, 16, 6, 3, 3, 16, 40, (1, 1), (1, 1, 1, 1), idx=90),      # 3x3 instantiation
+    custom_layer(24, 10, 64, 5, 1, 1, 64, 48, (1, 1), (0, 0, 0, 0), idx=91),      # 1x1 instantiation
+    custom_layer(8, 8, 8, 30, 5, 5, 8, 24, (1, 1), (2, 2, 2, 2), idx=92),         # 5x5 instantiation
+    custom_layer(20, 9, 6, 4, 4, 2, 6, 20, (1, 2), (2, 1, 0, 1), idx=93),         # general kernel, pad 2
+    custom_layer(28, 28, 12, 3, 3, 3, 6, 18, (2, 2), (0, 1, 1, 0), idx=94),       # stride 2, two groups
+    custom_layer(40, 7, 5, 9, 7, 3, 5, 12, (3, 1), (1, 1, 1, 1), idx=95),         # stride 3
+    custom_layer(4, 4, 40, 70, 4, 4, 40, 150, idx=96),                            # fully connected
+]
+
+
+@pytest.mark.parametrize("case", range(len(ANY_ALIGNMENT)))
+def test_inputs_at_any_pointer_alignment(case):
+    """x, w and dzdy 0, 4, 8 or 12 bytes past a 16-byte boundary (the kernels load some operands 16 bytes
+    per lane; none of that may lean on the caller's allocation)."""
+    for misalign in (0, 1, 2, 3):
+        U.assert_errors(U.run_layer_full(ANY_ALIGNMENT[case], misalign=misalign),
+                        label="case %d, %d floats past alignment" % (case, misalign))
+
+
+def test_tall_input_many_row_blocks():
+    # many row blocks per image (the planner cuts the 224 rows)
+    L = custom_layer(224, 40, 16, 2, 3, 3, 16, 64, (1, 1), (1, 1, 1, 1), idx=97)
+    U.assert_errors(U.run_layer_full(L), label="tall")
+    U.assert_errors(U.run_layer_full(L, misalign=2), label="tall, 8 bytes past alignment")
+
+
 # ---- semantics of the boundary ---------------------------------------------------
 def test_outputs_are_overwritten_and_runs_are_bit_identical():
     L = synth.with_batch(synth.LAYERS["2b"], 4)
