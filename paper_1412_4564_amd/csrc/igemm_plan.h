@@ -299,6 +299,19 @@ inline bool plan_igemm_kind(const ConvView &v, int n_cu, IgemmPlan *pl, bool bf1
     // whole tiles first, one share of the left-over tiles after (see IgemmParams::own): fewer tiles go through
     // the workspace and the fix-up pass than when everything is shared
     P.own = (int)(tiles / P.nblocks);
+    if (!bf16 && 2 * tiles >= n_cu && tiles < n_cu) {
+        // Somewhat fewer tiles than compute units: sharing every tile keeps all units busy but sends every tile through
+        // the workspace and the fix-up pass; one whole tile per block leaves some units idle and needs neither.
+        // Times in microseconds: a unit's MFMAs at about 80 % of the matrix core's rate (two waves per SIMD with
+        // 512 threads), the fix-up as a launch plus its traffic at about 4 TB/s.
+        const double unit_us = (NT / 256) * (double)P.NS * MK * MP * 64.0 / 0.8 / 2400.0;
+        const double fix_us = 6.0 + (double)P.nblocks * TK * TQ * 8.0 / 4.0e6;
+        const double shared_us = (double)((total + P.nblocks - 1) / P.nblocks) * unit_us + fix_us;
+        if ((double)P.NU * unit_us <= shared_us) {
+            P.nblocks = (int)tiles;
+            P.own = 1;
+        }
+    }
     P.OH = v.OH; P.OW = v.OW; P.oi0 = v.oi0; P.osi = v.osi; P.oj0 = v.oj0; P.osj = v.osj;
     P.mD = v.mD; P.mPt = v.mPt; P.mPl = v.mPl;
     // packed weights per unit, in 32-bit words: bf16 steps hold 2 octets x TK filters x 16 bytes
@@ -307,7 +320,8 @@ inline bool plan_igemm_kind(const ConvView &v, int n_cu, IgemmPlan *pl, bool bf1
     pl->packed_floats = (size_t)v.G * P.KT * P.NU * wsz;
     if (pl->packed_floats * 4 >= 2147483647ull) return false;
     P.packed_bytes = (unsigned)(pl->packed_floats * 4);
-    pl->partial_floats = P.nblocks > 1 ? (size_t)2 * P.nblocks * TK * TQ : 0;
+    // no workspace for partial tiles when no tile is shared
+    pl->partial_floats = P.nblocks > 1 && (int64_t)P.own * P.nblocks != tiles ? (size_t)2 * P.nblocks * TK * TQ : 0;
     pl->shape = shape; pl->bf16 = bf16; pl->fixed = fixed; pl->TK = TK; pl->TQ = TQ; pl->NT = NT;
     if (bf16)
         pl->lds_bytes = (2 * wsz + 2 * (size_t)2 * P.CP * 4 + (size_t)P.EPT * NT + 2 * TK + 4) *
