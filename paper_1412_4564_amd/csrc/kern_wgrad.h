@@ -64,15 +64,23 @@ struct WgradParams {
 __device__ __host__ inline int wg_chunk_grid(int nblocks) { return nblocks < 8 ? nblocks : (nblocks + 7) / 8 * 8; }
 __device__ inline int wg_chunk_virtual_block(int b, int grid) { return grid % 8 == 0 ? (b % 8) * (grid / 8) + b / 8 : b; }
 
+// Waves beyond the WK*WR computing ones only fetch.  A wave that issues global -> LDS loads is held at
+// each one until the memory pipeline takes it (some 50-150 cycles per instruction here), and a computing
+// wave held there feeds no MFMAs: with the fetches in waves of their own, the computing waves run from
+// barrier to barrier without a stall, and the fetching waves have a whole unit's time to issue.
+constexpr int WGRAD_LOADER_WAVES = 4;
+
 // S1: vertical stride 1 (the slab rows of consecutive pixels are adjacent)
 template <int WK, int WR, int MK, int MR, bool S1, int WPE>
-__global__ __launch_bounds__(64 * WK * WR, WPE) void wgrad_sk_kernel(WgradParams P, const float *__restrict__ x,
+__global__ __launch_bounds__(64 * (WK * WR + WGRAD_LOADER_WAVES), WPE) void wgrad_sk_kernel(WgradParams P, const float *__restrict__ x,
                                                                      const float *__restrict__ dzdy,
                                                                      const float *__restrict__ rbias,
                                                                      float *__restrict__ out,
                                                                      float *__restrict__ part) {
-    constexpr int NT = 64 * WK * WR;
+    constexpr int NT = 64 * WK * WR;           // computing threads
     constexpr int NW = WK * WR;
+    constexpr int LW = WGRAD_LOADER_WAVES;
+    constexpr int NTB = NT + 64 * LW;          // threads of the block
     constexpr int TK = WK * MK * 32;
     constexpr int TR = WR * MR * 32;
     constexpr int NSEGMAX = 2;                 // PCH <= 128
@@ -85,12 +93,13 @@ __global__ __launch_bounds__(64 * WK * WR, WPE) void wgrad_sk_kernel(WgradParams
     extern __shared__ __align__(16) float lds[];
     float *ybuf = lds;                                        // [2][TK*PCHP]
     float *xbuf = lds + 2 * YS;                               // [2][XS]
-    int *etab = reinterpret_cast<int *>(xbuf + 2 * P.XS);     // [EPT][NT] slab position -> (row | column << 16); private per thread
+    int *etab = reinterpret_cast<int *>(xbuf + 2 * P.XS);     // [EPT*NT] slab position -> (row | column << 16)
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int half = lane >> 5, l32 = lane & 31;
-    const int wk = wave % WK, wr = wave / WK;
+    const bool loader = wave >= NW;            // scalar: whole waves
+    const int wk = wave % WK, wr = (wave / WK) % WR;
     const int HW = P.H * P.W, HoWo = P.Ho * P.Wo;
 
     int vb;
@@ -111,13 +120,13 @@ __global__ __launch_bounds__(64 * WK * WR, WPE) void wgrad_sk_kernel(WgradParams
 
     // ---- per-lane quantities that hold for every unit ------------------------------------------
     // slab position e = col*SRP + r
-    for (int s = 0; s < P.EPT; ++s) {
-        const int e = tid + NT * s;
+    for (int e = tid; e < P.EPT * NT; e += NTB) {
         const int col = e / SRP;
         const int r = e - col * SRP;
         const bool ok = col < P.SC && r < P.SR;
-        etab[s * NT + tid] = ok ? (r | col << 16) : 0x7fff;       // pitch padding: any row will do, it is never read
+        etab[e] = ok ? (r | col << 16) : 0x7fff;       // pitch padding: any row will do, it is never read
     }
+    __syncthreads();                                   // the fetching waves read every entry
     // pixel p = ii + TIE*dc of the patch
     int p_ii[NSEGMAX], p_dc[NSEGMAX];
     unsigned p_off[NSEGMAX];
@@ -163,7 +172,7 @@ __global__ __launch_bounds__(64 * WK * WR, WPE) void wgrad_sk_kernel(WgradParams
         for (int seg = 0; seg < NSEG; ++seg) {
             const unsigned yoff = (p_ii[seg] < rows && p_dc[seg] < cols) ? p_off[seg] + ybase : SLAB_INVALID;
             if (seg * 64 + lane < PCH) {
-                for (int k = wave; k < l_klim; k += NW)
+                for (int k = wave - NW; k < l_klim; k += LW)
                     load_to_lds_b32(lds_address(yb + k * PCHP + seg * 64), yoff, yrs, (unsigned)k * (unsigned)HoWo * 4u);
             }
         }
@@ -171,19 +180,19 @@ __global__ __launch_bounds__(64 * WK * WR, WPE) void wgrad_sk_kernel(WgradParams
         const int i0 = io0 * P.Sh - P.Pt, j0 = jo0 * P.Sw - P.Pl;
         const int xbase = 4 * (i0 + P.H * j0 + n * (P.Ctot * HW));
         const int ntot = SRP * P.SC;
-        for (int s = 0; s < P.EPT; ++s) {
-            const int e0 = wave * 64 + NT * s;
-            if (e0 >= ntot) break;
-            const int rc = etab[s * NT + tid];
+        // every fetching wave walks all 64-position chunks and takes every LW-th channel of each, starting
+        // one channel further per chunk, so that the waves carry equal shares whatever the chunk count
+        int chunk = 0;
+        for (int e0 = 0; e0 < ntot; e0 += 64, ++chunk) {
+            const int rc = etab[e0 + lane];
             const int r = rc & 0xffff, col = rc >> 16;
             const int rel = 4 * (r + P.H * col);
             const bool ok = (unsigned)(r + i0) < (unsigned)P.H && (unsigned)(col + j0) < (unsigned)P.W;
             const unsigned go = ok ? (unsigned)(rel + xbase) : SLAB_INVALID;
             if (e0 + lane < ntot) {
-                for (int d = 0; d < l_nch; ++d)
+                for (int d = (wave - NW + chunk) % LW; d < l_nch; d += LW)
                     load_to_lds_b32(lds_address(xb + d * CP + e0), go, xrs, (unsigned)d * (unsigned)HW * 4u);
             }
-
         }
     };
 
@@ -310,21 +319,29 @@ __global__ __launch_bounds__(64 * WK * WR, WPE) void wgrad_sk_kernel(WgradParams
     int t_l = t_c, uu_l = uu_c;
     bool first_segment = true;
     auto segment_is_whole = [&](int t, int uu) { return uu == 0 && (long long)(t + 1) * NU <= ue; };
-    setup_load(t_l);
-    issue_loads(uu_l, 0);
+    const int nunits = (int)(ue - ub);
+    if (loader) {
+        // Fetching wave: unit it+1 goes into the buffer that the computing waves left at the barrier of
+        // iteration it; its own loads have landed before it joins the next barrier.  One barrier per unit,
+        // the same number as the computing waves pass.
+        setup_load(t_l);
+        issue_loads(uu_l, 0);
+        for (int it = 0; it < nunits; ++it) {
+            __builtin_amdgcn_s_waitcnt(WAIT_VMCNT0);
+            lds_barrier();
+            if (it + 1 < nunits) {
+                if (++uu_l == NU) { uu_l = 0; ++t_l; setup_load(t_l); }
+                issue_loads(uu_l, (it + 1) & 1);
+            }
+        }
+        return;
+    }
     bool whole = segment_is_whole(t_c, uu_c);
     setup_compute(t_c);
 
-    const int nunits = (int)(ue - ub);
     for (int it = 0; it < nunits; ++it) {
-        __builtin_amdgcn_s_waitcnt(WAIT_VMCNT0);
-        lds_barrier();
+        lds_barrier();          // unit it is in LDS (the fetching waves waited for it); results stored earlier drain on their own
         const bool more = it + 1 < nunits;
-        auto fetch_next = [&]() {
-            if (++uu_l == NU) { uu_l = 0; ++t_l; setup_load(t_l); }
-            issue_loads(uu_l, (it + 1) & 1);
-        };
-        if (more) fetch_next();
         compute(it & 1);
         const bool last = !more;
         if (uu_c + 1 == NU || last) {

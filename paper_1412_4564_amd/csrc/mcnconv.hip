@@ -249,14 +249,15 @@ int launch_wgrad_inst2(const WgradPlan &pl, const float *x, const float *dzdy, c
                        float *part, hipStream_t s, int relu) {
     WgradParams P = pl.P;
     P.relu = relu;
-    auto kern = wgrad_sk_kernel<WK, WR, MK, MR, S1, 2>;
+    auto kern = wgrad_sk_kernel<WK, WR, MK, MR, S1, 4>;      // two blocks of 4 + 2 waves per compute unit
     if (pl.lds_bytes > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
                                            (int)pl.lds_bytes);
         if (e != hipSuccess) { g_last_hip_error = (int)e; return MCN_HIP_ERROR; }
     }
     const bool chunked = P.nchunks > 0;
-    hipLaunchKernelGGL(kern, dim3(chunked ? wg_chunk_grid(P.nblocks) : P.nblocks), dim3(64 * WK * WR), pl.lds_bytes, s, P,
+    hipLaunchKernelGGL(kern, dim3(chunked ? wg_chunk_grid(P.nblocks) : P.nblocks),
+                       dim3(64 * (WK * WR + WGRAD_LOADER_WAVES)), pl.lds_bytes, s, P,
                        x, dzdy, rbias, out, part);
     int st = check_launch();
     if (st || P.nblocks < 2 || P.nchunks == 1) return st;
