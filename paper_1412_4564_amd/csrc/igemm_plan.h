@@ -128,7 +128,7 @@ inline ConvView fc_backward_filter_view(const Geom &g) {
     return v;
 }
 
-enum IgemmShape { IG_128x256 = 0, IG_64x512 = 1, IG_32x256 = 2, IG_NONE = -1 };
+enum IgemmShape { IG_128x256 = 0, IG_64x512 = 1, IG_32x256 = 2, IG_64x256 = 3, IG_NONE = -1 };
 
 struct IgemmPlan {
     int shape;          // IgemmShape
@@ -143,6 +143,7 @@ struct IgemmPlan {
 };
 
 constexpr size_t IGEMM_LDS_LIMIT = 160 * 1024;
+constexpr int IGEMM_LOADER_WAVES = 4;     // fetching waves of the IG_64x256 blocks: as many threads as compute
 // Instantiations with a compile-time filter size and channel count per unit: every LDS offset of
 // the MFMA loop is then an immediate or one of a few hoisted sums, against an offset-table read and
 // several address instructions per step in the general kernel.
@@ -215,11 +216,16 @@ inline bool cut_units_bf16(const ConvView &v, int TK, int64_t CP, size_t lds_lef
     return false;
 }
 
-inline bool plan_igemm_kind(const ConvView &v, int n_cu, IgemmPlan *pl, bool bf16, int fixed) {
+inline bool plan_igemm_kind(const ConvView &v, int n_cu, IgemmPlan *pl, bool bf16, int fixed, bool two = false) {
     const int T = v.Hf * v.Wf;
     const IgemmFixed FX = IGEMM_FIXED[fixed];
     int shape, WK, WP, MK, MP;
-    if (v.Kg > 64) { shape = IG_128x256; WK = 2; WP = 4; MK = 2; MP = 2; }
+    // `two`: blocks of four waves, two of them resident per compute unit (half the LDS each): while one is
+    // at its barrier or writes a tile, the other keeps the matrix cores busy
+    const size_t lds_limit = two ? IGEMM_LDS_LIMIT / 2 : IGEMM_LDS_LIMIT;
+    const int resident = two ? 2 * n_cu : n_cu;
+    if (two) { shape = IG_64x256; WK = 1; WP = 4; MK = 2; MP = 2; }
+    else if (v.Kg > 64) { shape = IG_128x256; WK = 2; WP = 4; MK = 2; MP = 2; }
     else if (v.Kg > 32) { shape = IG_64x512; WK = 1; WP = 8; MK = 2; MP = 2; }
     else { shape = IG_32x256; WK = 1; WP = 4; MK = 1; MP = 2; }
     const int TK = WK * MK * 32, TQ = WP * MP * 32, NT = 64 * WK * WP;
@@ -252,15 +258,15 @@ inline bool plan_igemm_kind(const ConvView &v, int n_cu, IgemmPlan *pl, bool bf1
         const size_t fixed_lds = ((size_t)EPT * NT + 2 * TK + 4) * 4;
         UnitCut uc;
         if (bf16) {
-            if (fixed_lds + 64 > IGEMM_LDS_LIMIT) continue;
-            if (!cut_units_bf16(v, TK, CP, IGEMM_LDS_LIMIT - fixed_lds - 64, &uc)) continue;
+            if (fixed_lds + 64 > lds_limit) continue;
+            if (!cut_units_bf16(v, TK, CP, lds_limit - fixed_lds - 64, &uc)) continue;
         } else if (fixed) {
             uc.pair_mode = 0; uc.DC = FX.DC; uc.TC = T; uc.NTR = 1; uc.NS = (FX.DC / 2) * T;
-            if ((2 * ((size_t)uc.NS * 2 * TK + 255) + 2 * (size_t)uc.DC * CP) * 4 + fixed_lds > IGEMM_LDS_LIMIT) continue;
+            if ((2 * ((size_t)uc.NS * 2 * TK + 255) + 2 * (size_t)uc.DC * CP) * 4 + fixed_lds > lds_limit) continue;
         } else {
-            if (fixed_lds + 4096 > IGEMM_LDS_LIMIT) continue;
+            if (fixed_lds + 4096 + 16384 > lds_limit) continue;
             // the offset table needs NTR*NS*2 ints: reserve 16 KB for it up front
-            if (!cut_units(v, TK, CP, IGEMM_LDS_LIMIT - fixed_lds - 16384, &uc)) continue;
+            if (!cut_units(v, TK, CP, lds_limit - fixed_lds - 16384, &uc)) continue;
             if ((size_t)uc.NTR * uc.NS * 2 * 4 > 16384) continue;
         }
         const int RB = (v.Ho + TI - 1) / TI;
@@ -295,16 +301,16 @@ inline bool plan_igemm_kind(const ConvView &v, int n_cu, IgemmPlan *pl, bool bf1
     if (tiles >= ((int64_t)1 << 30)) return false;
     P.tiles = (int)tiles;
     const int64_t total = tiles * P.NU;
-    P.nblocks = (int)(total < n_cu ? total : n_cu);
+    P.nblocks = (int)(total < resident ? total : resident);
     // whole tiles first, one share of the left-over tiles after (see IgemmParams::own): fewer tiles go through
     // the workspace and the fix-up pass than when everything is shared
     P.own = (int)(tiles / P.nblocks);
-    if (!bf16 && 2 * tiles >= n_cu && tiles < n_cu) {
+    if (!bf16 && 2 * tiles >= resident && tiles < resident) {
         // Somewhat fewer tiles than compute units: sharing every tile keeps all units busy but sends every tile through
         // the workspace and the fix-up pass; one whole tile per block leaves some units idle and needs neither.
         // Times in microseconds: a unit's MFMAs at about 80 % of the matrix core's rate (two waves per SIMD with
-        // 512 threads), the fix-up as a launch plus its traffic at about 4 TB/s.
-        const double unit_us = (NT / 256) * (double)P.NS * MK * MP * 64.0 / 0.8 / 2400.0;
+        // 512 threads or two resident blocks), the fix-up as a launch plus its traffic at about 4 TB/s.
+        const double unit_us = (two ? 2 : NT / 256) * (double)P.NS * MK * MP * 64.0 / 0.8 / 2400.0;
         const double fix_us = 6.0 + (double)P.nblocks * TK * TQ * 8.0 / 4.0e6;
         const double shared_us = (double)((total + P.nblocks - 1) / P.nblocks) * unit_us + fix_us;
         if ((double)P.NU * unit_us <= shared_us) {
@@ -314,6 +320,8 @@ inline bool plan_igemm_kind(const ConvView &v, int n_cu, IgemmPlan *pl, bool bf1
     }
     P.OH = v.OH; P.OW = v.OW; P.oi0 = v.oi0; P.osi = v.osi; P.oj0 = v.oj0; P.osj = v.osj;
     P.mD = v.mD; P.mPt = v.mPt; P.mPl = v.mPl;
+    P.dTI = make_div32(P.TI); P.dWo = make_div32(P.Wo); P.dWp = make_div32(P.Wp); P.dSRP = make_div32(P.SRP);
+    P.dKT = make_div32(P.KT); P.dRB = make_div32(P.RB); P.dPT = make_div32(P.PT);
     // packed weights per unit, in 32-bit words: bf16 steps hold 2 octets x TK filters x 16 bytes
     const size_t wsz = bf16 ? (size_t)P.NS * 2 * TK * 4 : ((size_t)P.NS * 2 * TK + 255) / 256 * 256;
     P.WSZ = (int)wsz;
@@ -329,7 +337,7 @@ inline bool plan_igemm_kind(const ConvView &v, int n_cu, IgemmPlan *pl, bool bf1
     else
         pl->lds_bytes = (2 * wsz + 2 * (size_t)P.DC * P.CP + (size_t)P.EPT * NT + 2 * TK +
                          (fixed ? 0 : (size_t)P.NTR * P.NS * 2) + 4) * sizeof(float);
-    if (pl->lds_bytes > IGEMM_LDS_LIMIT) return false;
+    if (pl->lds_bytes > lds_limit) return false;
 
     PackParams &Q = pl->Q;
     Q = PackParams{};
@@ -345,13 +353,17 @@ inline bool plan_igemm_kind(const ConvView &v, int n_cu, IgemmPlan *pl, bool bf1
 // The instantiation with this view's filter size if there is one, its channels divide into the
 // fixed units and a plan fits; the general kernel otherwise.
 inline bool plan_igemm(const ConvView &v, int n_cu, IgemmPlan *pl, bool bf16 = false) {
-    if (!bf16)
+    if (!bf16) {
+        // with more than 32 filters per group: two resident blocks of four waves rather than one of eight
+        const bool two = v.Kg > 32;
         for (int f = 1; f < IGEMM_N_FIXED; ++f) {
             const IgemmFixed FX = IGEMM_FIXED[f];
             if (v.Hf == FX.HF && v.Wf == FX.WF && v.Cg >= 2 * FX.DC && v.Cg % FX.DC == 0 &&
-                plan_igemm_kind(v, n_cu, pl, false, f))
+                ((two && plan_igemm_kind(v, n_cu, pl, false, f, true)) || plan_igemm_kind(v, n_cu, pl, false, f)))
                 return true;
         }
+        if (two && plan_igemm_kind(v, n_cu, pl, false, 0, true)) return true;
+    }
     return plan_igemm_kind(v, n_cu, pl, bf16, 0);
 }
 

@@ -87,6 +87,24 @@ __device__ inline void load_to_lds_b128(unsigned lds_addr, unsigned voffset, buf
 // is computed.  Loads into LDS are waited for explicitly (vmcnt) where they are consumed.
 __device__ inline void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
+// n / d for 0 <= n < 2^31 and d >= 1 as a multiplication, an addition and a shift: with l = ceil(log2 d)
+// and m = floor(2^32 (2^l - d) / d) + 1,  n / d = (floor(m n / 2^32) + n) >> l.  The code that sets a tile
+// up divides by block-wide constants for every slab position and pixel; a hardware-less integer division is
+// some 35 vector instructions, each of which takes issue cycles from the matrix core.
+struct Div32 {
+    unsigned m;
+    int l;
+};
+inline Div32 make_div32(int d) {
+    Div32 f;
+    int l = 0;
+    while (((int64_t)1 << l) < d) ++l;
+    f.l = l;
+    f.m = (unsigned)((((uint64_t)1 << 32) * (((uint64_t)1 << l) - (uint64_t)d)) / (uint64_t)d + 1);
+    return f;
+}
+__device__ inline int div32(int n, Div32 f) { return (int)((__umulhi(f.m, (unsigned)n) + (unsigned)n) >> f.l); }
+
 struct IgemmParams {
     int H, W, N;        // input plane size, batch
     int Ctot, Cg;       // channels in the input array / per group (reduction depth)
@@ -121,6 +139,7 @@ struct IgemmParams {
     // the tiles left over, own*nblocks .. tiles-1, are cut into equal contiguous ranges of units and shared.
     // own = 0 shares everything.
     int own;
+    Div32 dTI, dWo, dWp, dSRP, dKT, dRB, dPT;   // reciprocals of the fields of these names
 };
 
 // Merged phases: channel, and placement of output pixel (0,0), of merged filter kl
@@ -150,10 +169,13 @@ __device__ __host__ inline long long sk_begin(long long total, int nblocks, int 
 // columns (vertically adjacent tiles share the cache lines their halo rows touch), then the
 // strips, then the groups.
 __device__ inline void decode_tile(const IgemmParams &P, int t, int *kt, int *pt, int *rb, int *g) {
-    *kt = t % P.KT; t /= P.KT;
-    *rb = t % P.RB; t /= P.RB;
-    *pt = t % P.PT;
-    *g = t / P.PT;
+    int q = div32(t, P.dKT);
+    *kt = t - q * P.KT; t = q;
+    q = div32(t, P.dRB);
+    *rb = t - q * P.RB; t = q;
+    q = div32(t, P.dPT);
+    *pt = t - q * P.PT;
+    *g = q;
 }
 
 // ---- reduction order of a unit ------------------------------------------------------------
@@ -251,16 +273,23 @@ __global__ __launch_bounds__(256) void igemm_pack_weights_kernel(const float *__
 // HF, WF > 0: filter size and DCF channels per unit known at compile time (pair_mode 0, one tap
 // range, fully unrolled); HF = 0: everything read from the parameters, offsets from a table.
 // WPE: waves per SIMD the register allocation must allow.
-template <int WK, int WP, int MK, int MP, int HF, int WF, int DCF, int WPE>
-__global__ __launch_bounds__(64 * WK * WP, WPE) void igemm_sk_kernel(IgemmParams P, const float *__restrict__ in,
+// LW > 0: LW more waves that only fetch.  A wave that issues global -> LDS loads is held at each one until
+// the memory pipeline takes it, and a computing wave held there feeds no MFMAs; fetching waves have a whole
+// unit's time to issue, and the computing waves run from barrier to barrier.
+template <int WK, int WP, int MK, int MP, int HF, int WF, int DCF, int WPE, int LW = 0>
+__global__ __launch_bounds__(64 * (WK * WP + LW), WPE) void igemm_sk_kernel(IgemmParams P, const float *__restrict__ in,
                                                                      const float *__restrict__ wpk,
                                                                      const float *__restrict__ bias,
                                                                      float *__restrict__ out,
                                                                      float *__restrict__ part) {
-    constexpr int NT = 64 * WK * WP;
+    constexpr int NT = 64 * WK * WP;               // computing threads
+    constexpr int NTB = NT + 64 * LW;              // threads of the block
+    constexpr int NL = LW ? 64 * LW : NT;          // fetching threads
+    constexpr int NLW = LW ? LW : WK * WP;         // fetching waves
     constexpr int TK = WK * MK * 32;
     constexpr int TQ = WP * MP * 32;
     constexpr bool FIXED = HF > 0;
+    static_assert(NLW * 64 >= TK, "the fetching waves stage one bias value per lane");
     const int DC = FIXED ? DCF : P.DC;
     const int NS = FIXED ? (DCF / 2) * HF * WF : P.NS;
     const int NU = P.NU;
@@ -272,15 +301,18 @@ __global__ __launch_bounds__(64 * WK * WP, WPE) void igemm_sk_kernel(IgemmParams
     extern __shared__ __align__(16) float lds[];
     float *wbuf = lds;                                   // [2][WSZ]
     float *xbuf = lds + 2 * WSZ;                         // [2][DC*CP]
-    int *gtab = reinterpret_cast<int *>(xbuf + 2 * XSZ); // [EPT][NT]: entry (s, tid) is private to thread tid
-    float *blds = reinterpret_cast<float *>(gtab + P.EPT * NT);   // [2][TK] bias of the tile, slots used in turn
+    int *gtab = reinterpret_cast<int *>(xbuf + 2 * XSZ); // [EPT][NL]: entry (s, t) is private to fetching thread t
+    float *blds = reinterpret_cast<float *>(gtab + P.EPT * NL);   // [2][TK] bias of the tile, slots used in turn
     int *otab = reinterpret_cast<int *>(blds + 2 * TK);           // table mode: [NTR][NS][2] slab offsets
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int half = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wk = wave % WK, wp = wave / WK;
+    const int wk = wave % WK, wp = (wave / WK) % WP;
+    const bool loader = LW > 0 && wave >= WK * WP;          // whole waves
+    const int ltid = LW ? tid - NT : tid;                   // index among the fetching threads
+    const int lwave = LW ? wave - WK * WP : wave;
     const int HW = P.H * P.W;
     const int OHW = P.OH * P.OW;
 
@@ -294,7 +326,7 @@ __global__ __launch_bounds__(64 * WK * WP, WPE) void igemm_sk_kernel(IgemmParams
 
     if constexpr (!FIXED) {
         const int T = P.Hf * P.Wf;
-        for (int idx = tid; idx < P.NTR * NS * 2; idx += NT) {
+        for (int idx = tid; idx < P.NTR * NS * 2; idx += NTB) {
             const int h = idx & 1;
             const int s = (idx >> 1) % NS;
             const int tr = (idx >> 1) / NS;
@@ -319,8 +351,8 @@ __global__ __launch_bounds__(64 * WK * WP, WPE) void igemm_sk_kernel(IgemmParams
         int kt, pt, rb, g;
         decode_tile(P, t, &kt, &pt, &rb, &g);
         const int q0 = pt * TQ;
-        const int c_first = q0 / P.TI;
-        const int n_first = c_first / P.Wo;
+        const int c_first = div32(q0, P.dTI);
+        const int n_first = div32(c_first, P.dWo);
         const int u0 = (c_first - n_first * P.Wo) * P.Sw;   // chained column of the slab's first column
         const int row0 = rb * P.TI * P.Sh - P.Pt;           // input row of slab row 0
         const size_t in_base = ((size_t)n_first * P.Ctot + (size_t)g * P.Cg) * HW;
@@ -330,15 +362,15 @@ __global__ __launch_bounds__(64 * WK * WP, WPE) void igemm_sk_kernel(IgemmParams
         wtile_off = (unsigned)((size_t)(g * P.KT + kt) * NU * WSZ * 4);
         l_kt = kt; l_g = g;
         for (int s = 0; s < P.EPT; ++s) {
-            const int e = tid + NT * s;
-            const int col = e / SRP;
+            const int e = ltid + NL * s;
+            const int col = div32(e, P.dSRP);
             const int r = e - col * SRP;
             const int U = u0 + col;
-            const int ni = U / P.Wp;                 // image relative to n_first
+            const int ni = div32(U, P.dWp);          // image relative to n_first
             const int j = U - ni * P.Wp - P.Pl;
             const int i = row0 + r;
             const bool ok = e < CP && r < P.SR && i >= 0 && i < P.H && j >= 0 && j < P.W && (n_first + ni) < P.N;
-            gtab[s * NT + tid] = ok ? (int)(4u * (unsigned)(i + P.H * j + ni * P.Ctot * HW)) : (int)SLAB_INVALID;
+            gtab[s * NL + ltid] = ok ? (int)(4u * (unsigned)(i + P.H * j + ni * P.Ctot * HW)) : (int)SLAB_INVALID;
         }
     };
     // fetch unit uu of the load-side tile into buffer b
@@ -346,22 +378,22 @@ __global__ __launch_bounds__(64 * WK * WP, WPE) void igemm_sk_kernel(IgemmParams
         float *wb = wbuf + b * WSZ;
         float *xb = xbuf + b * XSZ;
         const unsigned woff = wtile_off + (unsigned)uu * (unsigned)WSZ * 4u;
-        for (int e0 = wave * 256; e0 < WSZ; e0 += NW * 256)       // one wave instruction = 256 floats, 16 bytes per lane
+        for (int e0 = lwave * 256; e0 < WSZ; e0 += NLW * 256)     // one wave instruction = 256 floats, 16 bytes per lane
             load_to_lds_b128(lds_address(wb + e0), lane16, wrs, woff + (unsigned)e0 * 4u);
-        if (bias && uu == 0 && wave * 64 < TK) {
+        if (bias && uu == 0 && lwave * 64 < TK) {
             // the tile's bias: start value of the accumulators of a tile this block owns entirely
-            const int kl = l_kt * TK + wave * 64 + lane;
+            const int kl = l_kt * TK + lwave * 64 + lane;
             const int bidx = P.mD ? l_g * P.mD + kl % P.mD : l_g * P.Kg + kl;
-            if (wave * 64 + lane < TK)
-                load_to_lds_b32(lds_address(blds + (l_seq & 1) * TK + wave * 64),
+            if (lwave * 64 + lane < TK)
+                load_to_lds_b32(lds_address(blds + (l_seq & 1) * TK + lwave * 64),
                                 kl < P.Kg ? (unsigned)bidx * 4u : SLAB_INVALID, brs, 0);
         }
-        const int cg = FIXED ? uu : uu / P.NTR;
+        const int cg = (FIXED || P.NTR == 1) ? uu : uu / P.NTR;
         const int c0 = cg * DC;
         for (int s = 0; s < P.EPT; ++s) {
-            const int e0 = wave * 64 + NT * s;
+            const int e0 = lwave * 64 + NL * s;
             if (e0 >= CP) break;
-            const unsigned go = (unsigned)gtab[s * NT + tid];
+            const unsigned go = (unsigned)gtab[s * NL + ltid];
             for (int d = 0; d < DC; ++d) {
                 const int c = c0 + d;
                 // channels past the group's last one read as zero (their weights are zero too)
@@ -387,15 +419,15 @@ __global__ __launch_bounds__(64 * WK * WP, WPE) void igemm_sk_kernel(IgemmParams
         c_kt = kt; c_g = g;
         const int q0 = pt * TQ;
         const int qend = min(q0 + TQ, P.QN);
-        const int c_first = q0 / P.TI;
-        const int n_first = c_first / P.Wo;
+        const int c_first = div32(q0, P.dTI);
+        const int n_first = div32(c_first, P.dWo);
         const int u0 = (c_first - n_first * P.Wo) * P.Sw;
 #pragma unroll
         for (int mp = 0; mp < MP; ++mp) {
             const int q = q0 + (wp * MP + mp) * 32 + (lane & 31);
-            const int ii = q % P.TI;
-            const int c = q / P.TI;
-            const int n = c / P.Wo;
+            const int c = div32(q, P.dTI);
+            const int ii = q - c * P.TI;
+            const int n = div32(c, P.dWo);
             const int jo = c - n * P.Wo;
             const int io = rb * P.TI + ii;
             const bool ok = q < qend && io < P.Ho;
@@ -461,7 +493,7 @@ __global__ __launch_bounds__(64 * WK * WP, WPE) void igemm_sk_kernel(IgemmParams
                 __builtin_amdgcn_sched_barrier(0);
             }
         } else {
-            const int tr = uu % P.NTR;
+            const int tr = P.NTR == 1 ? 0 : uu % P.NTR;
             const int *ot = otab + tr * NS * 2 + half;
             const int mid = (NS >> 2) << 1;                 // even
             const int s0 = part ? mid : 0, s1 = part ? NS : mid;
@@ -501,7 +533,13 @@ __global__ __launch_bounds__(64 * WK * WP, WPE) void igemm_sk_kernel(IgemmParams
     // lane holds pixel (lane&31) of each pixel tile and 16 filters of each filter tile
     // Buffer stores: the filter part of the address is a scalar offset, pixels that do not exist
     // carry an out-of-range offset and are dropped by the hardware, so no per-store vector arithmetic.
-    auto store_tile = [&]() {
+    // (No vector arithmetic per store on the usual path: every vector instruction here is issued between the
+    // MFMAs of the block that shares the compute unit.)
+    auto store_tile_as = [&](auto RELU) {
+        constexpr bool relu = decltype(RELU)::value;
+        unsigned olow[MP];      // offsets for a store of which only the lower half-wave's filter exists
+#pragma unroll
+        for (int mp = 0; mp < MP; ++mp) olow[mp] = half == 0 ? ooff[mp] : SLAB_INVALID;
 #pragma unroll
         for (int mk = 0; mk < MK; ++mk) {
 #pragma unroll
@@ -510,16 +548,26 @@ __global__ __launch_bounds__(64 * WK * WP, WPE) void igemm_sk_kernel(IgemmParams
                 const int left = P.Kg - kl0;
                 if (left <= 0) continue;
                 const unsigned soff = (unsigned)(c_g * P.Kg + kl0) * (unsigned)OHW * 4u;
+                // the upper half-wave holds filter kl0 + 4
+                if (left > 4) {
 #pragma unroll
-                for (int mp = 0; mp < MP; ++mp) {
-                    // the upper half-wave holds filter kl0 + 4
-                    const unsigned vo = (left > 4 || half == 0) ? ooff[mp] : SLAB_INVALID;
-                    float val = acc[mk][mp][v];
-                    if (P.relu) val = fmaxf(val, 0.f);
-                    __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(val), ors, vo, soff, 0);
+                    for (int mp = 0; mp < MP; ++mp) {
+                        const float val = relu ? fmaxf(acc[mk][mp][v], 0.f) : acc[mk][mp][v];
+                        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(val), ors, ooff[mp], soff, 0);
+                    }
+                } else {
+#pragma unroll
+                    for (int mp = 0; mp < MP; ++mp) {
+                        const float val = relu ? fmaxf(acc[mk][mp][v], 0.f) : acc[mk][mp][v];
+                        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(val), ors, olow[mp], soff, 0);
+                    }
                 }
             }
         }
+    };
+    auto store_tile = [&]() {
+        if (P.relu) store_tile_as(std::true_type{});
+        else store_tile_as(std::false_type{});
     };
     // Merged phases: the two half-waves hold filters of different phases, so the filter part of the address
     // and the "does this pixel exist in this phase" test are per half-wave.
@@ -586,8 +634,29 @@ __global__ __launch_bounds__(64 * WK * WP, WPE) void igemm_sk_kernel(IgemmParams
     auto segment_is_whole = [&](int t, int uu) {
         return t < tile_s0 || (uu == 0 && (long long)(t - tile_s0 + 1) * NU <= ue);
     };
-    setup_load(t_l);
-    issue_loads(uu_l, 0);
+    if constexpr (LW > 0) {
+        if (loader) {
+            // Fetching wave: unit it+1 goes into the buffer that the computing waves left at the barrier of
+            // iteration it; its own loads have landed before it joins the next barrier.  One barrier per
+            // unit, as many as the computing waves pass.
+            setup_load(t_l);
+            issue_loads(uu_l, 0);
+            for (int it = 0; it < nunits; ++it) {
+                __builtin_amdgcn_s_waitcnt(WAIT_VMCNT0);
+                lds_barrier();
+                if (it + 1 < nunits) {
+                    const int t_prev = t_l;
+                    advance(t_l, uu_l, it + 1);
+                    if (t_l != t_prev) setup_load(t_l);
+                    issue_loads(uu_l, (it + 1) & 1);
+                }
+            }
+            return;
+        }
+    } else {
+        setup_load(t_l);
+        issue_loads(uu_l, 0);
+    }
     bool whole = segment_is_whole(t_c, uu_c);
     setup_compute(t_c);
 
@@ -596,7 +665,7 @@ __global__ __launch_bounds__(64 * WK * WP, WPE) void igemm_sk_kernel(IgemmParams
     const bool late_fetch = NT == 512 && ((wave >> 2) & 1);
     bool loads_waited = false;
     for (int it = 0; it < nunits; ++it) {
-        if (!loads_waited) __builtin_amdgcn_s_waitcnt(WAIT_VMCNT0);   // this wave's LDS-direct loads have landed
+        if (LW == 0 && !loads_waited) __builtin_amdgcn_s_waitcnt(WAIT_VMCNT0);   // this wave's LDS-direct loads have landed
         loads_waited = false;
         lds_barrier();                             // everyone's have, and the other buffer is free
         if (need_init) { init_acc(whole && bias != nullptr); need_init = false; }
@@ -607,16 +676,18 @@ __global__ __launch_bounds__(64 * WK * WP, WPE) void igemm_sk_kernel(IgemmParams
             if (t_l != t_prev) setup_load(t_l);
             issue_loads(uu_l, (it + 1) & 1);
         };
-        if (more && !late_fetch) fetch_next();
+        if (LW == 0 && more && !late_fetch) fetch_next();
         compute(std::integral_constant<int, 0>{}, uu_c, it & 1);
-        if (more && late_fetch) fetch_next();
+        if (LW == 0 && more && late_fetch) fetch_next();
         compute(std::integral_constant<int, 1>{}, uu_c, it & 1);
         const bool last = !more;
         if (uu_c + 1 == NU || last) {
             // wait for the next unit's loads now, so that the stores below need not be waited for at
             // the top of the next iteration and drain while it computes
-            __builtin_amdgcn_s_waitcnt(WAIT_VMCNT0);
-            loads_waited = true;
+            if (LW == 0) {
+                __builtin_amdgcn_s_waitcnt(WAIT_VMCNT0);
+                loads_waited = true;
+            }
             if (whole) { if (P.mD) store_tile_merged(); else store_tile(); }
             else store_partial(2 * vb + (first_segment ? 0 : 1));
             first_segment = it + 1 == n_own;      // the shared range starts with a "first" segment again

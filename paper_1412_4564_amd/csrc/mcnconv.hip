@@ -157,18 +157,22 @@ const PlanEntry *plans_for(const mcn_conv_desc *d, const Geom &g) {
     return &e;
 }
 
+// blocks of four waves run two to a compute unit, each with four more waves that only fetch
+// (16 waves per unit: the registers of a wave are capped at 128)
 template <int WK, int WP, int MK, int MP, int HF, int WF, int DCF>
 int launch_igemm_inst(const IgemmPlan &pl, const float *in, const float *wpk, const float *bias, float *out,
                       float *part, hipStream_t s, int relu) {
     IgemmParams P = pl.P;
     P.relu = relu;
-    auto kern = igemm_sk_kernel<WK, WP, MK, MP, HF, WF, DCF, 2>;
+    constexpr bool two = WK * WP == 4 && MK == 2;          // IG_64x256
+    constexpr int LW = two ? IGEMM_LOADER_WAVES : 0;
+    auto kern = igemm_sk_kernel<WK, WP, MK, MP, HF, WF, DCF, two ? 4 : 2, LW>;
     if (pl.lds_bytes > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
                                            (int)pl.lds_bytes);
         if (e != hipSuccess) { g_last_hip_error = (int)e; return MCN_HIP_ERROR; }
     }
-    hipLaunchKernelGGL(kern, dim3(P.nblocks), dim3(64 * WK * WP), pl.lds_bytes, s, P, in, wpk, bias, out, part);
+    hipLaunchKernelGGL(kern, dim3(P.nblocks), dim3(64 * (WK * WP + LW)), pl.lds_bytes, s, P, in, wpk, bias, out, part);
     int st = check_launch();
     if (st || P.nblocks < 2 || P.own * P.nblocks == P.tiles) return st;      // no tile is shared
     constexpr int TK = WK * MK * 32, TQ = WP * MP * 32;
@@ -240,6 +244,7 @@ int launch_igemm(const IgemmPlan &pl, const float *in, const float *w, const flo
         case IG_128x256: return launch_igemm_fixed<2, 4, 2, 2>(pl, in, packed, bias, out, part, s, relu);
         case IG_64x512: return launch_igemm_fixed<1, 8, 2, 2>(pl, in, packed, bias, out, part, s, relu);
         case IG_32x256: return launch_igemm_fixed<1, 4, 1, 2>(pl, in, packed, bias, out, part, s, relu);
+        case IG_64x256: return launch_igemm_fixed<1, 4, 2, 2>(pl, in, packed, bias, out, part, s, relu);
         default: return MCN_BAD_ARG;
     }
 }
