@@ -143,7 +143,7 @@ struct IgemmPlan {
 };
 
 constexpr size_t IGEMM_LDS_LIMIT = 160 * 1024;
-constexpr int IGEMM_LOADER_WAVES = 4;     // fetching waves of the IG_64x256 blocks: as many threads as compute
+constexpr int IGEMM_LOADER_WAVES = 4;     // fetching waves per block of the fp32 kernel
 // Instantiations with a compile-time filter size and channel count per unit: every LDS offset of
 // the MFMA loop is then an immediate or one of a few hoisted sums, against an offset-table read and
 // several address instructions per step in the general kernel.
@@ -229,6 +229,7 @@ inline bool plan_igemm_kind(const ConvView &v, int n_cu, IgemmPlan *pl, bool bf1
     else if (v.Kg > 32) { shape = IG_64x512; WK = 1; WP = 8; MK = 2; MP = 2; }
     else { shape = IG_32x256; WK = 1; WP = 4; MK = 1; MP = 2; }
     const int TK = WK * MK * 32, TQ = WP * MP * 32, NT = 64 * WK * WP;
+    const int NL = bf16 ? NT : 64 * IGEMM_LOADER_WAVES;      // threads that fetch (fp32: the fetching waves)
     const int Wp = (v.Wo - 1) * v.Sw + v.Wf;
     // candidates for the row-block height
     int cand[48];
@@ -249,13 +250,13 @@ inline bool plan_igemm_kind(const ConvView &v, int n_cu, IgemmPlan *pl, bool bf1
         if ((int64_t)TI * v.Wo * v.N >= ((int64_t)1 << 30)) continue;
         const int SC = slab_columns(v, TI, TQ, Wp);
         const int64_t CP = (SR * SC + 63) / 64 * 64;
-        if (CP > (bf16 ? bf_ept_max(NT) : 16) * NT) continue;
+        if (CP > (bf16 ? bf_ept_max(NT) : 32) * NL) continue;
         // an image crossing inside a tile moves the window by whole images: keep offsets in range
         const int64_t span = (int64_t)SC / Wp + 2;
         if ((double)span * v.Ctot * v.H * v.W * 4.0 >= 2147483647.0) continue;
         if ((double)(span + 1) * v.Ktot * v.OH * v.OW * 4.0 >= 2147483647.0) continue;   // and inside its output window
-        const int EPT = (int)((CP + NT - 1) / NT);
-        const size_t fixed_lds = ((size_t)EPT * NT + 2 * TK + 4) * 4;
+        const int EPT = (int)((CP + NL - 1) / NL);
+        const size_t fixed_lds = ((size_t)EPT * NL + 2 * TK + 4) * 4;
         UnitCut uc;
         if (bf16) {
             if (fixed_lds + 64 > lds_limit) continue;
@@ -291,7 +292,7 @@ inline bool plan_igemm_kind(const ConvView &v, int n_cu, IgemmPlan *pl, bool bf1
     P.Wp = Wp;
     P.SR = (bestTI - 1) * v.Sh + v.Hf; P.SRP = P.SR;
     P.CP = (P.SRP * bestSC + 63) / 64 * 64;
-    P.EPT = (P.CP + NT - 1) / NT;
+    P.EPT = (P.CP + NL - 1) / NL;
     P.KT = (v.Kg + TK - 1) / TK;
     P.QN = bestTI * v.Wo * v.N;
     P.PT = (P.QN + TQ - 1) / TQ;
@@ -332,10 +333,10 @@ inline bool plan_igemm_kind(const ConvView &v, int n_cu, IgemmPlan *pl, bool bf1
     pl->partial_floats = P.nblocks > 1 && (int64_t)P.own * P.nblocks != tiles ? (size_t)2 * P.nblocks * TK * TQ : 0;
     pl->shape = shape; pl->bf16 = bf16; pl->fixed = fixed; pl->TK = TK; pl->TQ = TQ; pl->NT = NT;
     if (bf16)
-        pl->lds_bytes = (2 * wsz + 2 * (size_t)2 * P.CP * 4 + (size_t)P.EPT * NT + 2 * TK + 4) *
+        pl->lds_bytes = (2 * wsz + 2 * (size_t)2 * P.CP * 4 + (size_t)P.EPT * NL + 2 * TK + 4) *
                         sizeof(float);
     else
-        pl->lds_bytes = (2 * wsz + 2 * (size_t)P.DC * P.CP + (size_t)P.EPT * NT + 2 * TK +
+        pl->lds_bytes = (2 * wsz + 2 * (size_t)P.DC * P.CP + (size_t)P.EPT * NL + 2 * TK +
                          (fixed ? 0 : (size_t)P.NTR * P.NS * 2) + 4) * sizeof(float);
     if (pl->lds_bytes > lds_limit) return false;
 

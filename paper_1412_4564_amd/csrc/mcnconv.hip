@@ -157,16 +157,17 @@ const PlanEntry *plans_for(const mcn_conv_desc *d, const Geom &g) {
     return &e;
 }
 
-// blocks of four waves run two to a compute unit, each with four more waves that only fetch
-// (16 waves per unit: the registers of a wave are capped at 128)
+// every block has four more waves that only fetch; blocks of four computing waves (IG_64x256) run two to a
+// compute unit (16 waves per unit: the registers of a wave are capped at 128)
 template <int WK, int WP, int MK, int MP, int HF, int WF, int DCF>
 int launch_igemm_inst(const IgemmPlan &pl, const float *in, const float *wpk, const float *bias, float *out,
                       float *part, hipStream_t s, int relu) {
     IgemmParams P = pl.P;
     P.relu = relu;
-    constexpr bool two = WK * WP == 4 && MK == 2;          // IG_64x256
-    constexpr int LW = two ? IGEMM_LOADER_WAVES : 0;
-    auto kern = igemm_sk_kernel<WK, WP, MK, MP, HF, WF, DCF, two ? 4 : 2, LW>;
+    constexpr int LW = IGEMM_LOADER_WAVES;
+    // waves per SIMD the registers must allow: two blocks of 4 + 4 waves (IG_64x256), else one of 8 + 4 or 4 + 4
+    constexpr int WPE = (WK * WP == 4 && MK == 2) ? 4 : (WK * WP == 8 ? 3 : 2);
+    auto kern = igemm_sk_kernel<WK, WP, MK, MP, HF, WF, DCF, WPE, LW>;
     if (pl.lds_bytes > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
                                            (int)pl.lds_bytes);
