@@ -143,7 +143,7 @@ struct IgemmPlan {
 };
 
 constexpr size_t IGEMM_LDS_LIMIT = 160 * 1024;
-constexpr int IGEMM_LOADER_WAVES = 4;     // fetching waves per block of the fp32 kernel
+constexpr int IGEMM_LOADER_WAVES = 4;     // fetching waves per block
 // Instantiations with a compile-time filter size and channel count per unit: every LDS offset of
 // the MFMA loop is then an immediate or one of a few hoisted sums, against an offset-table read and
 // several address instructions per step in the general kernel.
@@ -229,7 +229,7 @@ inline bool plan_igemm_kind(const ConvView &v, int n_cu, IgemmPlan *pl, bool bf1
     else if (v.Kg > 32) { shape = IG_64x512; WK = 1; WP = 8; MK = 2; MP = 2; }
     else { shape = IG_32x256; WK = 1; WP = 4; MK = 1; MP = 2; }
     const int TK = WK * MK * 32, TQ = WP * MP * 32, NT = 64 * WK * WP;
-    const int NL = bf16 ? NT : 64 * IGEMM_LOADER_WAVES;      // threads that fetch (fp32: the fetching waves)
+    const int NL = 64 * IGEMM_LOADER_WAVES;      // threads of the fetching (bf16: staging) waves
     const int Wp = (v.Wo - 1) * v.Sw + v.Wf;
     // candidates for the row-block height
     int cand[48];
@@ -250,7 +250,7 @@ inline bool plan_igemm_kind(const ConvView &v, int n_cu, IgemmPlan *pl, bool bf1
         if ((int64_t)TI * v.Wo * v.N >= ((int64_t)1 << 30)) continue;
         const int SC = slab_columns(v, TI, TQ, Wp);
         const int64_t CP = (SR * SC + 63) / 64 * 64;
-        if (CP > (bf16 ? bf_ept_max(NT) : 32) * NL) continue;
+        if (CP > (bf16 ? bf_ept_max(NL) : 32) * NL) continue;
         // an image crossing inside a tile moves the window by whole images: keep offsets in range
         const int64_t span = (int64_t)SC / Wp + 2;
         if ((double)span * v.Ctot * v.H * v.W * 4.0 >= 2147483647.0) continue;

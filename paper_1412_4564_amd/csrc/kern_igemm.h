@@ -73,10 +73,12 @@ __device__ inline buffer_rsrc make_rsrc(const void *base, unsigned bytes) {
 __device__ inline unsigned lds_address(const void *p) { return (unsigned)(size_t)MCN_LDS_PTR(p); }
 // lds_addr: wave-uniform LDS byte address of lane 0's element
 __device__ inline void load_to_lds_b32(unsigned lds_addr, unsigned voffset, buffer_rsrc rsrc, unsigned soffset) {
+    lds_addr = __builtin_amdgcn_readfirstlane(lds_addr);      // wave-uniform by construction; keeps it in a scalar register
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, %3 offen lds"
                  :: "s"(lds_addr), "v"(voffset), "s"(rsrc), "s"(soffset) : "memory");
 }
 __device__ inline void load_to_lds_b128(unsigned lds_addr, unsigned voffset, buffer_rsrc rsrc, unsigned soffset) {
+    lds_addr = __builtin_amdgcn_readfirstlane(lds_addr);
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
                  :: "s"(lds_addr), "v"(voffset), "s"(rsrc), "s"(soffset) : "memory");
 }

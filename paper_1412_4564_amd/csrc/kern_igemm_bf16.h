@@ -75,17 +75,21 @@ __global__ __launch_bounds__(256) void igemm_pack_weights_bf16_kernel(const floa
 }
 
 // WK x WP waves; each wave owns MK x MP tiles of 32 filters x 32 pixels.
-template <int WK, int WP, int MK, int MP, int WPE>
-__global__ __launch_bounds__(64 * WK * WP, WPE) void igemm_bf16_kernel(IgemmParams P, const float *__restrict__ in,
+// LW > 0: LW more waves that stage the operands (load, convert, write the slab; the packed weights go
+// straight to LDS) while the WK x WP waves only read LDS and issue MFMAs; see igemm_sk_kernel.
+template <int WK, int WP, int MK, int MP, int WPE, int LW = 0>
+__global__ __launch_bounds__(64 * (WK * WP + LW), WPE) void igemm_bf16_kernel(IgemmParams P, const float *__restrict__ in,
                                                                        const float *__restrict__ wpk,
                                                                        const float *__restrict__ bias,
                                                                        float *__restrict__ out,
                                                                        float *__restrict__ part) {
-    constexpr int NT = 64 * WK * WP;
+    constexpr int NT = 64 * WK * WP;               // computing threads
+    constexpr int NL = LW ? 64 * LW : NT;          // staging threads
+    constexpr int NLW = LW ? LW : WK * WP;         // staging waves
     constexpr int TK = WK * MK * 32;
     constexpr int TQ = WP * MP * 32;
-    constexpr int NW = WK * WP;
-    constexpr int BF_EPT_MAX = bf_ept_max(NT);
+    constexpr int BF_EPT_MAX = bf_ept_max(NL);
+    static_assert(NLW * 64 >= TK, "the staging waves fetch one bias value per lane");
     const int NS = P.NS;
     const int NU = P.NU;
     const int WSZ = P.WSZ;               // 32-bit words of packed weights per unit
@@ -95,14 +99,17 @@ __global__ __launch_bounds__(64 * WK * WP, WPE) void igemm_bf16_kernel(IgemmPara
     extern __shared__ __align__(16) float lds[];
     float *wbuf = lds;                                   // [2][WSZ]
     float *xbuf = lds + 2 * WSZ;                         // [2][XSZ]
-    int *gtab = reinterpret_cast<int *>(xbuf + 2 * XSZ); // [EPT][NT]: entry (s, tid) is private to thread tid
-    float *blds = reinterpret_cast<float *>(gtab + P.EPT * NT);   // [2][TK] bias of the tile, slots used in turn
+    int *gtab = reinterpret_cast<int *>(xbuf + 2 * XSZ); // [EPT][NL]: entry (s, t) is private to staging thread t
+    float *blds = reinterpret_cast<float *>(gtab + P.EPT * NL);   // [2][TK] bias of the tile, slots used in turn
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int half = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wk = wave % WK, wp = wave / WK;
+    const int wk = wave % WK, wp = (wave / WK) % WP;
+    const bool loader = LW > 0 && wave >= WK * WP;          // whole waves
+    const int ltid = LW ? tid - NT : tid;                   // index among the staging threads
+    const int lwave = LW ? wave - WK * WP : wave;
     const int HW = P.H * P.W;
     const int OHW = P.OH * P.OW;
 
@@ -128,8 +135,8 @@ __global__ __launch_bounds__(64 * WK * WP, WPE) void igemm_bf16_kernel(IgemmPara
         int kt, pt, rb, g;
         decode_tile(P, t, &kt, &pt, &rb, &g);
         const int q0 = pt * TQ;
-        const int c_first = q0 / P.TI;
-        const int n_first = c_first / P.Wo;
+        const int c_first = div32(q0, P.dTI);
+        const int n_first = div32(c_first, P.dWo);
         const int u0 = (c_first - n_first * P.Wo) * P.Sw;   // chained column of the slab's first column
         const int row0 = rb * P.TI * P.Sh - P.Pt;           // input row of slab row 0
         const size_t in_base = ((size_t)n_first * P.Ctot + (size_t)g * P.Cg) * HW;
@@ -139,15 +146,15 @@ __global__ __launch_bounds__(64 * WK * WP, WPE) void igemm_bf16_kernel(IgemmPara
         wtile_off = (unsigned)((size_t)(g * P.KT + kt) * NU * WSZ * 4);
         l_kt = kt; l_g = g;
         for (int s = 0; s < P.EPT; ++s) {
-            const int e = tid + NT * s;
-            const int col = e / SRP;
+            const int e = ltid + NL * s;
+            const int col = div32(e, P.dSRP);
             const int r = e - col * SRP;
             const int U = u0 + col;
-            const int ni = U / P.Wp;                 // image relative to n_first
+            const int ni = div32(U, P.dWp);          // image relative to n_first
             const int j = U - ni * P.Wp - P.Pl;
             const int i = row0 + r;
             const bool ok = e < CP && r < P.SR && i >= 0 && i < P.H && j >= 0 && j < P.W && (n_first + ni) < P.N;
-            gtab[s * NT + tid] = ok ? (int)(4u * (unsigned)(i + P.H * j + ni * P.Ctot * HW)) : (int)SLAB_INVALID;
+            gtab[s * NL + ltid] = ok ? (int)(4u * (unsigned)(i + P.H * j + ni * P.Ctot * HW)) : (int)SLAB_INVALID;
         }
     };
     // the 16 channels of this thread's slab samples, held in registers while the unit before is computed
@@ -155,21 +162,21 @@ __global__ __launch_bounds__(64 * WK * WP, WPE) void igemm_bf16_kernel(IgemmPara
     auto issue_loads = [&](int uu, int b) {
         float *wb = wbuf + b * WSZ;
         const unsigned woff = wtile_off + (unsigned)uu * (unsigned)WSZ * 4u;
-        for (int e0 = wave * 256; e0 < WSZ; e0 += NW * 256)       // one wave instruction = 1 KB, 16 bytes per lane
+        for (int e0 = lwave * 256; e0 < WSZ; e0 += NLW * 256)     // one wave instruction = 1 KB, 16 bytes per lane
             load_to_lds_b128(lds_address(wb + e0), lane16, wrs, woff + (unsigned)e0 * 4u);
-        if (bias && uu == 0 && wave * 64 < TK) {
+        if (bias && uu == 0 && lwave * 64 < TK) {
             // the tile's bias: start value of the accumulators of a tile this block owns entirely
-            const int kl = l_kt * TK + wave * 64 + lane;
-            if (wave * 64 + lane < TK)
-                load_to_lds_b32(lds_address(blds + (l_seq & 1) * TK + wave * 64),
+            const int kl = l_kt * TK + lwave * 64 + lane;
+            if (lwave * 64 + lane < TK)
+                load_to_lds_b32(lds_address(blds + (l_seq & 1) * TK + lwave * 64),
                                 kl < P.Kg ? (unsigned)(l_g * P.Kg + kl) * 4u : SLAB_INVALID, brs, 0);
         }
         const int c0 = (P.NTR == 1 ? uu : uu / P.NTR) * BF_DC;      // one tap range is the common case: no division
         const bool full = c0 + BF_DC <= P.Cg;
 #pragma unroll
         for (int s = 0; s < BF_EPT_MAX; ++s) {
-            if (s < P.EPT && wave * 64 + NT * s < CP) {
-                const unsigned go = (unsigned)gtab[s * NT + tid];
+            if (s < P.EPT && lwave * 64 + NL * s < CP) {
+                const unsigned go = (unsigned)gtab[s * NL + ltid];
                 if (full) {
 #pragma unroll
                     for (int d = 0; d < BF_DC; ++d)
@@ -192,8 +199,8 @@ __global__ __launch_bounds__(64 * WK * WP, WPE) void igemm_bf16_kernel(IgemmPara
         float *xb = xbuf + b * XSZ;
 #pragma unroll
         for (int s = 0; s < BF_EPT_MAX; ++s) {
-            if (s < P.EPT && wave * 64 + NT * s < CP) {
-                const int e = tid + NT * s;
+            if (s < P.EPT && lwave * 64 + NL * s < CP) {
+                const int e = ltid + NL * s;
 #pragma unroll
                 for (int o = 0; o < 2; ++o) {
                     uintx4 v;
@@ -222,15 +229,15 @@ __global__ __launch_bounds__(64 * WK * WP, WPE) void igemm_bf16_kernel(IgemmPara
         c_kt = kt; c_g = g;
         const int q0 = pt * TQ;
         const int qend = min(q0 + TQ, P.QN);
-        const int c_first = q0 / P.TI;
-        const int n_first = c_first / P.Wo;
+        const int c_first = div32(q0, P.dTI);
+        const int n_first = div32(c_first, P.dWo);
         const int u0 = (c_first - n_first * P.Wo) * P.Sw;
 #pragma unroll
         for (int mp = 0; mp < MP; ++mp) {
             const int q = q0 + (wp * MP + mp) * 32 + (lane & 31);
-            const int ii = q % P.TI;
-            const int c = q / P.TI;
-            const int n = c / P.Wo;
+            const int c = div32(q, P.dTI);
+            const int ii = q - c * P.TI;
+            const int n = div32(c, P.dWo);
             const int jo = c - n * P.Wo;
             const int io = rb * P.TI + ii;
             const bool ok = q < qend && io < P.Ho;
@@ -364,18 +371,40 @@ __global__ __launch_bounds__(64 * WK * WP, WPE) void igemm_bf16_kernel(IgemmPara
     auto segment_is_whole = [&](int t, int uu) {
         return t < tile_s0 || (uu == 0 && (long long)(t - tile_s0 + 1) * NU <= ue);
     };
-    setup_load(t_l);
-    issue_loads(uu_l, 0);
-    write_slab(0);
+    if constexpr (LW > 0) {
+        if (loader) {
+            // Staging wave: unit it+1 goes into the buffers the computing waves left at the barrier of
+            // iteration it, and is complete (weights landed, slab written) before the next barrier.
+            setup_load(t_l);
+            issue_loads(uu_l, 0);
+            write_slab(0);
+            for (int it = 0; it < nunits; ++it) {
+                __builtin_amdgcn_s_waitcnt(WAIT_VMCNT0);
+                lds_barrier();
+                if (it + 1 < nunits) {
+                    const int t_prev = t_l;
+                    advance(t_l, uu_l, it + 1);
+                    if (t_l != t_prev) setup_load(t_l);
+                    issue_loads(uu_l, (it + 1) & 1);
+                    write_slab((it + 1) & 1);
+                }
+            }
+            return;
+        }
+    } else {
+        setup_load(t_l);
+        issue_loads(uu_l, 0);
+        write_slab(0);
+    }
     bool whole = segment_is_whole(t_c, uu_c);
     setup_compute(t_c);
 
     for (int it = 0; it < nunits; ++it) {
-        __builtin_amdgcn_s_waitcnt(WAIT_VMCNT0);   // this wave's packed weights have landed in LDS
+        if (LW == 0) __builtin_amdgcn_s_waitcnt(WAIT_VMCNT0);   // this wave's packed weights have landed in LDS
         lds_barrier();                             // everyone's operands are in place, and the other buffer is free
         if (need_init) { init_acc(whole && bias != nullptr); need_init = false; }
         const bool more = it + 1 < nunits;
-        if (more) {
+        if (LW == 0 && more) {
             const int t_prev = t_l;
             advance(t_l, uu_l, it + 1);
             if (t_l != t_prev) setup_load(t_l);
@@ -384,7 +413,7 @@ __global__ __launch_bounds__(64 * WK * WP, WPE) void igemm_bf16_kernel(IgemmPara
         __builtin_amdgcn_sched_barrier(0);
         compute(uu_c, it & 1);
         __builtin_amdgcn_sched_barrier(0);
-        if (more) write_slab((it + 1) & 1);
+        if (LW == 0 && more) write_slab((it + 1) & 1);
         const bool last = !more;
         if (uu_c + 1 == NU || last) {
             if (whole) store_tile();

@@ -191,13 +191,15 @@ int launch_igemm_bf16_inst(const IgemmPlan &pl, const float *in, const float *wp
                            float *part, hipStream_t s, int relu) {
     IgemmParams P = pl.P;
     P.relu = relu;
-    auto kern = igemm_bf16_kernel<WK, WP, MK, MP, 2>;
+    // one block per compute unit: 8 computing + 4 staging waves (3 per SIMD), or 4 + 4
+    constexpr int LW = IGEMM_LOADER_WAVES;
+    auto kern = igemm_bf16_kernel<WK, WP, MK, MP, WK * WP == 8 ? 3 : 2, LW>;
     if (pl.lds_bytes > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
                                            (int)pl.lds_bytes);
         if (e != hipSuccess) { g_last_hip_error = (int)e; return MCN_HIP_ERROR; }
     }
-    hipLaunchKernelGGL(kern, dim3(P.nblocks), dim3(64 * WK * WP), pl.lds_bytes, s, P, in, wpk, bias, out, part);
+    hipLaunchKernelGGL(kern, dim3(P.nblocks), dim3(64 * (WK * WP + LW)), pl.lds_bytes, s, P, in, wpk, bias, out, part);
     int st = check_launch();
     if (st || P.nblocks < 2 || P.own * P.nblocks == P.tiles) return st;      // no tile is shared
     constexpr int TK = WK * MK * 32, TQ = WP * MP * 32;
