@@ -180,17 +180,21 @@ __global__ __launch_bounds__(64 * (WK * WR + WGRAD_LOADER_WAVES), WPE) void wgra
         const int i0 = io0 * P.Sh - P.Pt, j0 = jo0 * P.Sw - P.Pl;
         const int xbase = 4 * (i0 + P.H * j0 + n * (P.Ctot * HW));
         const int ntot = SRP * P.SC;
-        // every fetching wave walks all 64-position chunks and takes every LW-th channel of each, starting
-        // one channel further per chunk, so that the waves carry equal shares whatever the chunk count
-        int chunk = 0;
-        for (int e0 = 0; e0 < ntot; e0 += 64, ++chunk) {
+        // The fetching waves share the (chunk of 64 positions, channel) pairs.  With at least LW channels every
+        // wave walks all chunks and takes every LW-th channel of each, starting one channel further per chunk
+        // (equal shares whatever the chunk count); with fewer channels (depthwise-like tiles with large slabs)
+        // a wave takes every LW-th chunk with all its channels, so that no wave computes addresses it does not use.
+        const bool by_chunk = l_nch < LW;
+        const int lw = wave - NW;
+        for (int chunk = by_chunk ? lw : 0; chunk * 64 < ntot; chunk += by_chunk ? LW : 1) {
+            const int e0 = chunk * 64;
             const int rc = etab[e0 + lane];
             const int r = rc & 0xffff, col = rc >> 16;
             const int rel = 4 * (r + P.H * col);
             const bool ok = (unsigned)(r + i0) < (unsigned)P.H && (unsigned)(col + j0) < (unsigned)P.W;
             const unsigned go = ok ? (unsigned)(rel + xbase) : SLAB_INVALID;
             if (e0 + lane < ntot) {
-                for (int d = (wave - NW + chunk) % LW; d < l_nch; d += LW)
+                for (int d = by_chunk ? 0 : (lw + chunk) % LW; d < l_nch; d += by_chunk ? 1 : LW)
                     load_to_lds_b32(lds_address(xb + d * CP + e0), go, xrs, (unsigned)d * (unsigned)HW * 4u);
             }
         }
