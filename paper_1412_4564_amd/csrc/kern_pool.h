@@ -54,6 +54,11 @@ struct PoolGeom {
     FastDiv64 dIn, dOut;     // by the plane sizes H*W and Ho*Wo
 };
 
+// HP, WP > 0: window size known at compile time.  The window's samples are then read with clamped
+// addresses and no branches, so that all loads are in flight together (a loop with run-time bounds
+// issues them one after the other); samples outside the input are left out by selection, in the same
+// order as the loop takes them.
+template <int HP, int WP>
 __global__ __launch_bounds__(256) void pool_forward_kernel(PoolGeom g, const float *__restrict__ x,
                                                            float *__restrict__ y, unsigned total) {
     const unsigned idx = blockIdx.x * 256u + threadIdx.x;
@@ -62,6 +67,31 @@ __global__ __launch_bounds__(256) void pool_forward_kernel(PoolGeom g, const flo
     const int e = (int)(idx - plane * (unsigned)(g.Ho * g.Wo));
     const int jo = fdiv(e, g.dHo), io = e - jo * g.Ho;
     const float *xp = x + (size_t)plane * g.H * g.W;
+    if constexpr (HP > 0) {
+        const int oi = g.Sh * io - g.Pt, oj = g.Sw * jo - g.Pl;
+        float v[WP][HP];
+        bool ok[WP][HP];
+#pragma unroll
+        for (int fj = 0; fj < WP; ++fj)
+#pragma unroll
+            for (int fi = 0; fi < HP; ++fi) {
+                const int i = oi + fi, j = oj + fj;
+                ok[fj][fi] = (unsigned)i < (unsigned)g.H && (unsigned)j < (unsigned)g.W;
+                v[fj][fi] = xp[min(max(i, 0), g.H - 1) + g.H * min(max(j, 0), g.W - 1)];
+            }
+        float r = 0.f;
+        int cnt = 0;
+#pragma unroll
+        for (int fj = 0; fj < WP; ++fj)
+#pragma unroll
+            for (int fi = 0; fi < HP; ++fi) {
+                if (g.method == 0) r = !ok[fj][fi] ? r : cnt == 0 ? v[fj][fi] : fmaxf(r, v[fj][fi]);
+                else r += ok[fj][fi] ? v[fj][fi] : 0.f;
+                cnt += ok[fj][fi] ? 1 : 0;
+            }
+        y[idx] = g.method == 0 ? r : r / (float)cnt;
+        return;
+    }
     const int i0 = max(g.Sh * io - g.Pt, 0), i1 = min(g.Sh * io - g.Pt + g.Hp, g.H);
     const int j0 = max(g.Sw * jo - g.Pl, 0), j1 = min(g.Sw * jo - g.Pl + g.Wp, g.W);
     float r;
@@ -94,6 +124,7 @@ __device__ inline WindowRange windows_of(const PoolGeom &g, int i, int j) {
 
 // code[io,jo,plane] = fi + Hp*fj of the first maximum of window (io, jo), (fi, fj) counted from the
 // window's uncropped origin.  Needs Hp*Wp <= 256.
+template <int HP, int WP>
 __global__ __launch_bounds__(256) void pool_argmax_kernel(PoolGeom g, const float *__restrict__ x,
                                                           unsigned char *__restrict__ code, unsigned total) {
     const unsigned idx = blockIdx.x * 256u + threadIdx.x;
@@ -103,6 +134,27 @@ __global__ __launch_bounds__(256) void pool_argmax_kernel(PoolGeom g, const floa
     const int jo = fdiv(e, g.dHo), io = e - jo * g.Ho;
     const float *xp = x + (size_t)plane * g.H * g.W;
     const int oi = g.Sh * io - g.Pt, oj = g.Sw * jo - g.Pl;
+    if constexpr (HP > 0) {
+        float v[WP][HP];
+#pragma unroll
+        for (int fj = 0; fj < WP; ++fj)
+#pragma unroll
+            for (int fi = 0; fi < HP; ++fi)
+                v[fj][fi] = xp[min(max(oi + fi, 0), g.H - 1) + g.H * min(max(oj + fj, 0), g.W - 1)];
+        float m = 0.f;
+        int best = -1;
+#pragma unroll
+        for (int fj = 0; fj < WP; ++fj)
+#pragma unroll
+            for (int fi = 0; fi < HP; ++fi) {
+                const bool ok = (unsigned)(oi + fi) < (unsigned)g.H && (unsigned)(oj + fj) < (unsigned)g.W;
+                const bool take = ok && (best < 0 || v[fj][fi] > m);
+                m = take ? v[fj][fi] : m;
+                best = take ? fi + HP * fj : best;
+            }
+        code[idx] = (unsigned char)best;
+        return;
+    }
     const int i0 = max(oi, 0), i1 = min(oi + g.Hp, g.H);
     const int j0 = max(oj, 0), j1 = min(oj + g.Wp, g.W);
     float m = xp[i0 + g.H * j0];
@@ -116,6 +168,9 @@ __global__ __launch_bounds__(256) void pool_argmax_kernel(PoolGeom g, const floa
 }
 
 // dzdx[i,j] = sum of dzdy over the windows whose code points at (i, j)
+// NH, NW > 0: at most NH x NW windows hold one sample (ceil(Hp / Sh) x ceil(Wp / Sw)); their codes and
+// derivatives are read with clamped addresses and no branches.
+template <int NH, int NW>
 __global__ __launch_bounds__(256) void pool_backward_max_coded_kernel(PoolGeom g, const unsigned char *__restrict__ code,
                                                                       const float *__restrict__ dzdy,
                                                                       float *__restrict__ dzdx, unsigned total) {
@@ -127,6 +182,28 @@ __global__ __launch_bounds__(256) void pool_backward_max_coded_kernel(PoolGeom g
     const size_t pbase = (size_t)plane * g.Ho * g.Wo;
     const WindowRange r = windows_of(g, i, j);
     float acc = 0.f;
+    if constexpr (NH > 0) {
+        unsigned char c[NW][NH];
+        float p[NW][NH];
+#pragma unroll
+        for (int b = 0; b < NW; ++b)
+#pragma unroll
+            for (int a = 0; a < NH; ++a) {
+                const size_t at = pbase + min(r.io_lo + a, g.Ho - 1) + (size_t)g.Ho * min(r.jo_lo + b, g.Wo - 1);
+                c[b][a] = code[at];
+                p[b][a] = dzdy[at];
+            }
+#pragma unroll
+        for (int b = 0; b < NW; ++b)
+#pragma unroll
+            for (int a = 0; a < NH; ++a) {
+                const int io = r.io_lo + a, jo = r.jo_lo + b;
+                const int fi = i - (g.Sh * io - g.Pt), fj = j - (g.Sw * jo - g.Pl);
+                if (io <= r.io_hi && jo <= r.jo_hi && c[b][a] == fi + g.Hp * fj) acc += p[b][a];
+            }
+        dzdx[idx] = acc;
+        return;
+    }
     for (int jo = r.jo_lo; jo <= r.jo_hi; ++jo) {
         const int fj = j - (g.Sw * jo - g.Pl);
         for (int io = r.io_lo; io <= r.io_hi; ++io) {
@@ -136,6 +213,56 @@ __global__ __launch_bounds__(256) void pool_backward_max_coded_kernel(PoolGeom g
         }
     }
     dzdx[idx] = acc;
+}
+
+// Max pooling whose windows do not overlap (stride = window size): every sample lies in at most one window,
+// so one thread per window reads its samples, finds the first maximum and writes the window's share of dzdx
+// (the derivative at the maximum, zero elsewhere) in one pass: x, dzdy and dzdx each move once and no code
+// array is needed.  Rows and columns past the last window are cleared by the last windows of each column / row.
+template <int HP, int WP>
+__global__ __launch_bounds__(256) void pool_backward_max_disjoint_kernel(PoolGeom g, const float *__restrict__ x,
+                                                                         const float *__restrict__ dzdy,
+                                                                         float *__restrict__ dzdx, unsigned total) {
+    const unsigned idx = blockIdx.x * 256u + threadIdx.x;
+    if (idx >= total) return;
+    const unsigned plane = fdiv64(idx, g.dOut);
+    const int e = (int)(idx - plane * (unsigned)(g.Ho * g.Wo));
+    const int jo = fdiv(e, g.dHo), io = e - jo * g.Ho;
+    const size_t base = (size_t)plane * g.H * g.W;
+    const float *xp = x + base;
+    float *dp = dzdx + base;
+    const int oi = HP * io - g.Pt, oj = WP * jo - g.Pl;
+    const float p = dzdy[idx];
+    float v[WP][HP];
+#pragma unroll
+    for (int fj = 0; fj < WP; ++fj)
+#pragma unroll
+        for (int fi = 0; fi < HP; ++fi)
+            v[fj][fi] = xp[min(max(oi + fi, 0), g.H - 1) + g.H * min(max(oj + fj, 0), g.W - 1)];
+    float m = 0.f;
+    int best = -1;
+#pragma unroll
+    for (int fj = 0; fj < WP; ++fj)
+#pragma unroll
+        for (int fi = 0; fi < HP; ++fi) {
+            const bool ok = (unsigned)(oi + fi) < (unsigned)g.H && (unsigned)(oj + fj) < (unsigned)g.W;
+            const bool take = ok && (best < 0 || v[fj][fi] > m);
+            m = take ? v[fj][fi] : m;
+            best = take ? fi + HP * fj : best;
+        }
+#pragma unroll
+    for (int fj = 0; fj < WP; ++fj)
+#pragma unroll
+        for (int fi = 0; fi < HP; ++fi)
+            if ((unsigned)(oi + fi) < (unsigned)g.H && (unsigned)(oj + fj) < (unsigned)g.W)
+                dp[(oi + fi) + g.H * (oj + fj)] = best == fi + HP * fj ? p : 0.f;
+    // samples no window reads
+    const int i_end = io == g.Ho - 1 ? g.H : oi + HP;          // rows [oi + HP, i_end) below this window
+    const int j_end = jo == g.Wo - 1 ? g.W : oj + WP;          // columns [oj + WP, j_end) right of it
+    for (int j = max(oj, 0); j < min(oj + WP, g.W); ++j)
+        for (int i = oi + HP; i < i_end; ++i) dp[i + g.H * j] = 0.f;
+    for (int j = oj + WP; j < j_end; ++j)
+        for (int i = max(oi, 0); i < i_end; ++i) dp[i + g.H * j] = 0.f;
 }
 
 // One-kernel backward pass: average pooling, and max pooling with windows too large for a byte code.

@@ -698,13 +698,23 @@ int mcn_pool_forward(const mcn_pool_desc *desc, const float *x, float *y, void *
     if (st) return st;
     if (!x || !y) return MCN_BAD_ARG;
     const unsigned total = (unsigned)g.Ho * g.Wo * g.D * g.N;
-    hipLaunchKernelGGL(pool_forward_kernel, dim3(cdiv(total, 256)), dim3(256), 0, (hipStream_t)stream, g, x, y, total);
+    const dim3 grid(cdiv(total, 256));
+    if (g.Hp == 2 && g.Wp == 2)
+        hipLaunchKernelGGL((pool_forward_kernel<2, 2>), grid, dim3(256), 0, (hipStream_t)stream, g, x, y, total);
+    else if (g.Hp == 3 && g.Wp == 3)
+        hipLaunchKernelGGL((pool_forward_kernel<3, 3>), grid, dim3(256), 0, (hipStream_t)stream, g, x, y, total);
+    else
+        hipLaunchKernelGGL((pool_forward_kernel<0, 0>), grid, dim3(256), 0, (hipStream_t)stream, g, x, y, total);
     return check_launch();
 }
 
-// one byte per window for the position of its maximum, if a byte can hold it
+// max pooling with 2x2 or 3x3 windows that do not overlap: derivative in one pass (kern_pool.h)
+static bool pool_disjoint(const PoolGeom &g) {
+    return g.method == MCN_POOL_MAX && g.Sh == g.Hp && g.Sw == g.Wp && g.Hp == g.Wp && (g.Hp == 2 || g.Hp == 3);
+}
+// one byte per window for the position of its maximum, if a byte can hold it and the two-pass form is used
 static size_t pool_ws_bytes(const PoolGeom &g) {
-    return (g.method == MCN_POOL_MAX && g.Hp * g.Wp <= 256) ? (size_t)g.Ho * g.Wo * g.D * g.N : 0;
+    return (g.method == MCN_POOL_MAX && g.Hp * g.Wp <= 256 && !pool_disjoint(g)) ? (size_t)g.Ho * g.Wo * g.D * g.N : 0;
 }
 
 int mcn_pool_workspace_size(const mcn_pool_desc *desc, size_t *bytes) {
@@ -726,12 +736,36 @@ int mcn_pool_backward(const mcn_pool_desc *desc, const float *x, const float *dz
     if (ws_bytes < need || (!ws && need)) return MCN_WORKSPACE_TOO_SMALL;
     hipStream_t s = (hipStream_t)stream;
     const unsigned n_in = (unsigned)g.H * g.W * g.D * g.N, n_out = (unsigned)g.Ho * g.Wo * g.D * g.N;
+    if (pool_disjoint(g)) {
+        if (g.Hp == 2)
+            hipLaunchKernelGGL((pool_backward_max_disjoint_kernel<2, 2>), dim3(cdiv(n_out, 256)), dim3(256), 0, s, g, x, dzdy, dzdx, n_out);
+        else
+            hipLaunchKernelGGL((pool_backward_max_disjoint_kernel<3, 3>), dim3(cdiv(n_out, 256)), dim3(256), 0, s, g, x, dzdy, dzdx, n_out);
+        return check_launch();
+    }
     if (need) {
-        hipLaunchKernelGGL(pool_argmax_kernel, dim3(cdiv(n_out, 256)), dim3(256), 0, s, g, x, (unsigned char *)ws, n_out);
+        const dim3 go(cdiv(n_out, 256));
+        if (g.Hp == 2 && g.Wp == 2)
+            hipLaunchKernelGGL((pool_argmax_kernel<2, 2>), go, dim3(256), 0, s, g, x, (unsigned char *)ws, n_out);
+        else if (g.Hp == 3 && g.Wp == 3)
+            hipLaunchKernelGGL((pool_argmax_kernel<3, 3>), go, dim3(256), 0, s, g, x, (unsigned char *)ws, n_out);
+        else
+            hipLaunchKernelGGL((pool_argmax_kernel<0, 0>), go, dim3(256), 0, s, g, x, (unsigned char *)ws, n_out);
         st = check_launch();
         if (st) return st;
-        hipLaunchKernelGGL(pool_backward_max_coded_kernel, dim3(cdiv(n_in, 256)), dim3(256), 0, s, g,
-                           (const unsigned char *)ws, dzdy, dzdx, n_in);
+        // windows that can hold one sample, per direction
+        const int nh = (g.Hp + g.Sh - 1) / g.Sh, nw = (g.Wp + g.Sw - 1) / g.Sw;
+        const int nmax = nh > nw ? nh : nw;
+        const dim3 gi(cdiv(n_in, 256));
+        const unsigned char *code = (const unsigned char *)ws;
+        if (nmax == 1)
+            hipLaunchKernelGGL((pool_backward_max_coded_kernel<1, 1>), gi, dim3(256), 0, s, g, code, dzdy, dzdx, n_in);
+        else if (nmax == 2)
+            hipLaunchKernelGGL((pool_backward_max_coded_kernel<2, 2>), gi, dim3(256), 0, s, g, code, dzdy, dzdx, n_in);
+        else if (nmax == 3)
+            hipLaunchKernelGGL((pool_backward_max_coded_kernel<3, 3>), gi, dim3(256), 0, s, g, code, dzdy, dzdx, n_in);
+        else
+            hipLaunchKernelGGL((pool_backward_max_coded_kernel<0, 0>), gi, dim3(256), 0, s, g, code, dzdy, dzdx, n_in);
         return check_launch();
     }
     hipLaunchKernelGGL(pool_backward_kernel, dim3(cdiv(n_in, 256)), dim3(256), 0, s, g, x, dzdy, dzdx, n_in);

@@ -121,6 +121,35 @@ def test_pool_random_geometries():
         assert e[0] <= U.TOL_FWD and e[1] <= U.TOL_BWD
 
 
+DISJOINT = [
+    # stride = window size (2 or 3): the one-pass derivative.  H  W  D  N  window  pad
+    (8, 8, 3, 2, (2, 2), (0, 0, 0, 0)),
+    (9, 7, 2, 3, (2, 2), (0, 0, 0, 0)),        # a last row and a last column that no window reads
+    (9, 7, 2, 3, (2, 2), (1, 0, 1, 0)),        # padded at the top / left only
+    (9, 7, 2, 3, (2, 2), (1, 1, 1, 1)),
+    (10, 11, 4, 2, (3, 3), (0, 0, 0, 0)),      # 1 row, 2 columns left over
+    (10, 11, 4, 2, (3, 3), (2, 1, 1, 2)),
+    (3, 3, 1, 1, (3, 3), (0, 0, 0, 0)),        # one window
+    (2, 5, 1, 2, (2, 2), (0, 0, 0, 1)),
+    (70, 66, 5, 3, (2, 2), (0, 0, 0, 0)),      # several thread blocks per plane
+]
+
+
+@pytest.mark.parametrize("case", range(len(DISJOINT)))
+def test_pool_windows_that_do_not_overlap(case):
+    H, W, D, N, win, pad = DISJOINT[case]
+    e = run_pool(player(H, W, D, N, win, win, pad, "max", 200 + case))
+    assert e[0] <= U.TOL_FWD and e[1] <= U.TOL_BWD
+    # ties: a constant input selects the first sample of every window; the rest of dzdx is exactly zero
+    x = torch.full((N, D, W, H), 1.5, device="cuda")
+    ho, wo = oracle_pool.output_size(x.shape, win, win, pad, "max")
+    p = torch.randn((N, D, wo, ho), generator=torch.Generator().manual_seed(case)).cuda()
+    dx = torch.full_like(x, float("nan"))
+    B.pool_backward(x, p, win, win, pad, B.MCN_POOL_MAX, out=dx)
+    ref = oracle_pool.backward(x.cpu().numpy().astype(np.float64), p.cpu().numpy().astype(np.float64), win, win, pad, "max")
+    assert np.array_equal(dx.cpu().numpy().astype(np.float64), ref)
+
+
 def test_pool_ties_select_the_first_maximum():
     x = torch.zeros(1, 1, 3, 3, device="cuda")
     p = torch.arange(1.0, 5.0, device="cuda").reshape(1, 1, 2, 2)
