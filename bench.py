@@ -344,8 +344,8 @@ def main():
                          "(rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE) holds a kernel of known traffic to scale by")
     args = ap.parse_args()
     if args.gpus != 1:
-        sys.exit("bench.py: this build runs on ONE GPU; --gpus %d is not supported (the path shards over the batch, "
-                 "see DESIGN.md)" % args.gpus)
+        sys.exit("bench.py: this build runs on ONE GPU; --gpus %d is not supported (across GPUs the path would shard "
+                 "over the batch, with one all-reduce of dzdw and dzdb)" % args.gpus)
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
     torch.cuda.set_device(0)
