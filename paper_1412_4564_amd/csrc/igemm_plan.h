@@ -277,8 +277,9 @@ inline bool plan_igemm_kind(const ConvView &v, int n_cu, IgemmPlan *pl, bool bf1
         const int NCG = (v.Cg + uc.DC - 1) / uc.DC;
         const double red_waste = (double)NCG * uc.NTR * uc.NS * (bf16 ? BF_DC : 2) / ((double)v.Cg * T);
         // when the input streams from memory, short slab rows waste most of every 128-byte line they touch
+        // results are stored in column runs of TI samples: short runs are partial memory lines
         const double score = mfma_waste * red_waste * (1.0 + 0.05 * (double)CP / TQ) *
-                             (input_streams ? 1.0 + 4.0 / (double)SR : 1.0);
+                             (input_streams ? 1.0 + 4.0 / (double)SR : 1.0) * (1.0 + 2.0 / (double)TI);
         if (score < best_score) { best_score = score; bestTI = TI; bestSC = SC; best_uc = uc; }
     }
     if (!bestTI) return false;
