@@ -140,6 +140,7 @@ struct IgemmPlan {
     size_t lds_bytes;
     size_t packed_floats;
     size_t partial_floats;   // 2 slots of TK*TQ per resident block
+    double score;            // the planner's cost figure of the chosen row-block height (lower is better)
 };
 
 constexpr size_t IGEMM_LDS_LIMIT = 160 * 1024;
@@ -333,6 +334,7 @@ inline bool plan_igemm_kind(const ConvView &v, int n_cu, IgemmPlan *pl, bool bf1
     // no workspace for partial tiles when no tile is shared
     pl->partial_floats = P.nblocks > 1 && (int64_t)P.own * P.nblocks != tiles ? (size_t)2 * P.nblocks * TK * TQ : 0;
     pl->shape = shape; pl->bf16 = bf16; pl->fixed = fixed; pl->TK = TK; pl->TQ = TQ; pl->NT = NT;
+    pl->score = best_score;
     if (bf16)
         pl->lds_bytes = (2 * wsz + 2 * (size_t)2 * P.CP * 4 + (size_t)P.EPT * NL + 2 * TK + 4) *
                         sizeof(float);
@@ -355,18 +357,23 @@ inline bool plan_igemm_kind(const ConvView &v, int n_cu, IgemmPlan *pl, bool bf1
 // The instantiation with this view's filter size if there is one, its channels divide into the
 // fixed units and a plan fits; the general kernel otherwise.
 inline bool plan_igemm(const ConvView &v, int n_cu, IgemmPlan *pl, bool bf16 = false) {
-    if (!bf16) {
-        // with more than 32 filters per group: two resident blocks of four waves rather than one of eight
-        const bool two = v.Kg > 32;
-        for (int f = 1; f < IGEMM_N_FIXED; ++f) {
-            const IgemmFixed FX = IGEMM_FIXED[f];
-            if (v.Hf == FX.HF && v.Wf == FX.WF && v.Cg >= 2 * FX.DC && v.Cg % FX.DC == 0 &&
-                ((two && plan_igemm_kind(v, n_cu, pl, false, f, true)) || plan_igemm_kind(v, n_cu, pl, false, f)))
-                return true;
-        }
-        if (two && plan_igemm_kind(v, n_cu, pl, false, 0, true)) return true;
+    if (bf16) return plan_igemm_kind(v, n_cu, pl, true, 0);
+    // the instantiation with this view's filter size, if there is one and the channels divide into its units
+    int fixed = 0;
+    for (int f = 1; f < IGEMM_N_FIXED; ++f) {
+        const IgemmFixed FX = IGEMM_FIXED[f];
+        if (v.Hf == FX.HF && v.Wf == FX.WF && v.Cg >= 2 * FX.DC && v.Cg % FX.DC == 0) fixed = f;
     }
-    return plan_igemm_kind(v, n_cu, pl, bf16, 0);
+    for (int f = fixed;; f = 0) {
+        // With more than 32 filters per group: two resident blocks of four waves rather than one of eight,
+        // unless half the LDS forces a much worse row-block height on it (the scores are comparable).
+        IgemmPlan one, two;
+        const bool ok1 = plan_igemm_kind(v, n_cu, &one, false, f);
+        const bool ok2 = v.Kg > 32 && plan_igemm_kind(v, n_cu, &two, false, f, true);
+        if (ok2 && (!ok1 || two.score <= 1.15 * one.score)) { *pl = two; return true; }
+        if (ok1) { *pl = one; return true; }
+        if (f == 0) return false;
+    }
 }
 
 }  // namespace mcn
