@@ -296,7 +296,6 @@ __global__ __launch_bounds__(64 * (WK * WP + LW), WPE) void igemm_sk_kernel(Igem
     const int NS = FIXED ? (DCF / 2) * HF * WF : P.NS;
     const int NU = P.NU;
     const int WSZ = FIXED ? (((DCF / 2) * HF * WF * 2 * TK + 255) & ~255) : P.WSZ;   // floats of packed weights per unit
-    constexpr int NW = WK * WP;
     const int CP = P.CP, SRP = P.SRP;
     const int XSZ = DC * CP;
 
