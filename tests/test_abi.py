@@ -252,3 +252,38 @@ def test_probe_arguments_are_checked():
     hdr = open(os.path.join(ROOT, "include", "mcnconv.h")).read()
     assert re.search(r"#define\s+MCN_PROBE_SINK_FLOATS\s+\(2048 \* 256\)", hdr)
     assert B.MCN_PROBE_SINK_FLOATS == 2048 * 256
+
+
+def test_planner_puts_every_workload_layer_on_the_matrix_core_kernels():
+    # host logic only: kernel choice and workspace sizes need no GPU (the planner assumes 256 compute units then)
+    from paper_1412_4564_amd import synth
+    for name, L in synth.LAYERS.items():
+        for prec in (B.MCN_PREC_FP32, B.MCN_PREC_BF16):
+            d = B.make_desc(synth.x_shape(L), synth.w_shape(L), L["stride"], L["pad"], prec)
+            names = [B.mcn_conv_kernel_name(d, op) for op in range(4)]
+            assert "direct" not in names, (name, names)
+            sizes = [B.mcn_conv_workspace_size(d, op) for op in range(4)]
+            assert all(0 <= s < (1 << 28) for s in sizes), (name, sizes)       # scratch stays below 256 MiB
+    d = B.make_desc(synth.x_shape(synth.LAYERS["5a"]), synth.w_shape(synth.LAYERS["5a"]))
+    assert [B.mcn_conv_kernel_name(d, op) for op in range(3)] == ["fc_gemm"] * 3
+    # bf16 operands: the deep layers on the bf16 kernels, the 3-channel first layers on the fp32 ones
+    for name, expect in (("4b", ["igemm_bf16", "igemm_bf16", "wgrad_bf16"]), ("3a", ["igemm", "igemm", "wgrad_igemm"])):
+        L = synth.LAYERS[name]
+        d = B.make_desc(synth.x_shape(L), synth.w_shape(L), L["stride"], L["pad"], B.MCN_PREC_BF16)
+        assert [B.mcn_conv_kernel_name(d, op) for op in range(3)] == expect, name
+
+
+def test_planner_handles_odd_geometries_on_the_host():
+    # a sweep of descriptors through the size and workspace queries: every valid one must plan (or fall back)
+    # without error, and the answers must not depend on the order of the queries (plans are cached per thread)
+    import itertools
+    seen = {}
+    for H, Hf, S, P, D, K in itertools.product((1, 7, 30), (1, 3, 5), (1, 2, 3), (0, 2), (1, 3, 16, 40), (1, 24, 96)):
+        if H + 2 * P < Hf:
+            continue
+        d = B.make_desc((3, D, H + 2, H), (K, D, Hf, Hf), (S, S), (P, P, P, 0))
+        seen[(H, Hf, S, P, D, K)] = [B.mcn_conv_workspace_size(d, op) for op in range(4)]
+    for key in list(seen)[::7]:
+        H, Hf, S, P, D, K = key
+        d = B.make_desc((3, D, H + 2, H), (K, D, Hf, Hf), (S, S), (P, P, P, 0))
+        assert [B.mcn_conv_workspace_size(d, op) for op in range(4)] == seen[key], key
