@@ -88,6 +88,23 @@ def test_random_geometries():
         U.assert_errors(U.run_layer_full(L, with_bias=bool(t % 2), seed=t), label="random %d %r" % (t, L))
 
 
+def test_random_geometries_many_channels():
+    """Channel and filter counts large enough for the instantiations with a compile-time filter size (1x1, 3x3,
+    5x5), the two-blocks-per-unit shapes and ragged filter tiles, at random sizes, strides and pads."""
+    rng = np.random.default_rng(27182)
+    for t in range(24):
+        g = int(rng.choice([1, 1, 1, 2]))
+        F = int(rng.choice([1, 3, 3, 5]))
+        Df = int(rng.choice([8, 16, 24, 32, 64, 72])) if F > 1 else int(rng.choice([64, 96, 128]))
+        Kg = int(rng.integers(33, 200))
+        H, W = int(rng.integers(F, 31)), int(rng.integers(F, 31))
+        pad = [int(v) for v in rng.integers(0, F, size=4)] if F > 1 else [0, 0, 0, 0]
+        st = (int(rng.integers(1, 3)), int(rng.integers(1, 3)))
+        L = custom_layer(H, W, g * Df, int(rng.integers(1, 7)), F, F, Df, g * Kg, st, pad, idx=300 + t)
+        print("random wide case", t, L, flush=True)
+        U.assert_errors(U.run_layer_full(L, with_bias=bool(t % 2), seed=t), label="random wide %d %r" % (t, L))
+
+
 # ---- which kernels the dispatcher picks ----------------------------------------------
 def test_workload_layers_run_on_the_matrix_core_kernels():
     """No layer of the workloads may fall back to the one-result-per-thread kernels."""
