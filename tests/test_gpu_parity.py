@@ -105,6 +105,36 @@ def test_random_geometries_many_channels():
         U.assert_errors(U.run_layer_full(L, with_bias=bool(t % 2), seed=t), label="random wide %d %r" % (t, L))
 
 
+_FALLBACK_SCRIPT = r"""
+import sys
+sys.path.insert(0, sys.argv[1]); sys.path.insert(0, sys.argv[1] + "/tests")
+import parity_util as U
+from paper_1412_4564_amd import binding as B, synth
+cases = [(13, 9, 4, 3, 3, 2, 2, 6, (2, 1), (1, 2, 0, 1)), (16, 16, 12, 2, 1, 1, 4, 9, (1, 1), (0, 0, 0, 0)),
+         (10, 11, 2, 2, 4, 4, 2, 3, (5, 6), (0, 0, 0, 0)), (3, 3, 2, 2, 2, 2, 2, 2, (1, 1), (4, 4, 4, 4)),
+         (31, 29, 6, 5, 3, 3, 3, 130, (1, 1), (1, 1, 1, 1)), (4, 5, 3, 4, 4, 5, 3, 10, (1, 1), (0, 0, 0, 0))]
+for i, (H, W, D, N, Hf, Wf, Df, K, st, pad) in enumerate(cases):
+    L = dict(H=H, W=W, D=D, N=N, Hf=Hf, Wf=Wf, Df=Df, K=K, stride=st, pad=pad, config=9, index=400 + i)
+    d = B.make_desc(synth.x_shape(L), synth.w_shape(L), st, pad)
+    names = [B.mcn_conv_kernel_name(d, op) for op in range(3)]
+    assert names == ["direct"] * 3, names
+    U.assert_errors(U.run_layer_full(L, with_bias=bool(i % 2)), label="fallback %d" % i)
+print("FALLBACK-OK")
+"""
+
+
+def test_fallback_kernels_in_a_process_of_their_own():
+    """The one-result-per-thread kernels serve geometries the planners reject; MCN_FORCE_DIRECT=1 (read once per
+    process) routes everything to them, so they are checked against the oracle in a child process."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    env = dict(os.environ, MCN_FORCE_DIRECT="1")
+    r = subprocess.run([sys.executable, "-c", _FALLBACK_SCRIPT, root], env=env, capture_output=True, text=True, timeout=300)
+    assert r.returncode == 0 and "FALLBACK-OK" in r.stdout, (r.stdout[-2000:], r.stderr[-2000:])
+
+
 # ---- which kernels the dispatcher picks ----------------------------------------------
 def test_workload_layers_run_on_the_matrix_core_kernels():
     """No layer of the workloads may fall back to the one-result-per-thread kernels."""
