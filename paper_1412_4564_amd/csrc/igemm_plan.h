@@ -321,6 +321,11 @@ inline bool plan_igemm_kind(const ConvView &v, int n_cu, IgemmPlan *pl, bool bf1
             P.own = 1;
         }
     }
+    // two blocks per compute unit, whole tiles for every block and some left over: the blocks dispatched
+    // first take the left-over units (see IgemmParams::nshare)
+    P.nshare = P.nblocks;
+    if (two && P.own >= 1 && (int64_t)P.own * P.nblocks != tiles && P.nblocks == resident && P.nblocks % 16 == 0)
+        P.nshare = P.nblocks / 2;
     P.OH = v.OH; P.OW = v.OW; P.oi0 = v.oi0; P.osi = v.osi; P.oj0 = v.oj0; P.osj = v.osj;
     P.mD = v.mD; P.mPt = v.mPt; P.mPl = v.mPl;
     P.dTI = make_div32(P.TI); P.dWo = make_div32(P.Wo); P.dWp = make_div32(P.Wp); P.dSRP = make_div32(P.SRP);

@@ -141,6 +141,11 @@ struct IgemmParams {
     // the tiles left over, own*nblocks .. tiles-1, are cut into equal contiguous ranges of units and shared.
     // own = 0 shares everything.
     int own;
+    // Blocks that share the left-over tiles: all of them (nshare = nblocks), or the nshare = nblocks / 2 blocks with
+    // the lowest hardware ids.  Of the two blocks resident on a compute unit the one dispatched first (the lower
+    // id) gets more of the matrix core and would finish some 10 % earlier on equal work; it takes the left-over
+    // units, the other only its own tiles, and half as many partial tiles go through the workspace.
+    int nshare;
     Div32 dTI, dWo, dWp, dSRP, dKT, dRB, dPT;   // reciprocals of the fields of these names
 };
 
@@ -165,6 +170,20 @@ __device__ __host__ inline int sk_virtual_block(int b, int nblocks) {
 }
 __device__ __host__ inline long long sk_begin(long long total, int nblocks, int vb) {
     return total * vb / nblocks;
+}
+// Rank of virtual block vb among the nshare sharing blocks (in virtual order), or -1; and its inverse.  With
+// nshare < nblocks (both multiples of 8) the sharing blocks are hardware ids 0 .. nshare-1, i.e. the first
+// nshare/8 virtual blocks of each XCD's run of nblocks/8.
+__device__ __host__ inline int sk_share_rank(int nblocks, int nshare, int vb) {
+    if (nshare == nblocks) return vb;
+    const int G = nblocks / 8, S = nshare / 8;
+    const int x = vb / G, i = vb - x * G;
+    return i < S ? x * S + i : -1;
+}
+__device__ __host__ inline int sk_share_block(int nblocks, int nshare, int r) {
+    if (nshare == nblocks) return r;
+    const int G = nblocks / 8, S = nshare / 8;
+    return (r / S) * G + r % S;
 }
 
 // Tile order: filter tiles fastest (they share the slab), then the row blocks of one strip of
@@ -320,7 +339,8 @@ __global__ __launch_bounds__(64 * (WK * WP + LW), WPE) void igemm_sk_kernel(Igem
     const int vb = sk_virtual_block(blockIdx.x, P.nblocks);
     const int tile_s0 = P.own * P.nblocks;                          // first shared tile
     const long long total = (long long)(P.tiles - tile_s0) * NU;    // units of the shared tiles
-    const long long ub = sk_begin(total, P.nblocks, vb), ue = sk_begin(total, P.nblocks, vb + 1);
+    const int rank = sk_share_rank(P.nblocks, P.nshare, vb);
+    const long long ub = rank < 0 ? 0 : sk_begin(total, P.nshare, rank), ue = rank < 0 ? 0 : sk_begin(total, P.nshare, rank + 1);
     const int n_own = P.own * NU;                                    // units of this block's own tiles
     const int nunits = n_own + (int)(ue - ub);
     if (nunits == 0) return;
@@ -709,15 +729,15 @@ __global__ __launch_bounds__(64 * (WK * WP + LW), WPE) void igemm_sk_kernel(Igem
 template <int TK, int TQ>
 __global__ __launch_bounds__(256) void igemm_fixup_kernel(IgemmParams P, const float *__restrict__ part,
                                                           const float *__restrict__ bias, float *__restrict__ out) {
-    const int j = blockIdx.x + 1;                    // boundary between virtual blocks j-1 and j
+    const int j = blockIdx.x + 1;                    // boundary between sharing blocks j-1 and j (by rank)
     const int tile_s0 = P.own * P.nblocks;           // the shared tiles start here; unit numbers are relative to them
     const long long total = (long long)(P.tiles - tile_s0) * P.NU;
-    const long long B = sk_begin(total, P.nblocks, j);
+    const long long B = sk_begin(total, P.nshare, j);
     const int ts = (int)(B / P.NU);
     const int t = tile_s0 + ts;
     const long long t_lo = (long long)ts * P.NU, t_hi = t_lo + P.NU;
     if (B == t_lo) return;                                        // boundary on a tile edge: nothing shared
-    if (sk_begin(total, P.nblocks, j - 1) > t_lo) return;         // an earlier boundary owns this tile
+    if (sk_begin(total, P.nshare, j - 1) > t_lo) return;          // an earlier boundary owns this tile
     int kt, pt, rb, g;
     decode_tile(P, t, &kt, &pt, &rb, &g);
     const int OHW = P.OH * P.OW;
@@ -728,11 +748,11 @@ __global__ __launch_bounds__(256) void igemm_fixup_kernel(IgemmParams P, const f
     __shared__ int npieces;
     if (threadIdx.x == 0) {
         int n = 0;
-        for (int b = j - 1; b < P.nblocks && n < MAX_PIECES; ++b) {
-            const long long bb = sk_begin(total, P.nblocks, b);
+        for (int b = j - 1; b < P.nshare && n < MAX_PIECES; ++b) {
+            const long long bb = sk_begin(total, P.nshare, b);
             if (bb >= t_hi) break;
-            if (sk_begin(total, P.nblocks, b + 1) == bb) continue;      // a block without shared units wrote nothing
-            slots[n++] = 2 * b + (bb >= t_lo ? 0 : 1);
+            if (sk_begin(total, P.nshare, b + 1) == bb) continue;       // a block without shared units wrote nothing
+            slots[n++] = 2 * sk_share_block(P.nblocks, P.nshare, b) + (bb >= t_lo ? 0 : 1);
         }
         npieces = n;
     }

@@ -116,7 +116,8 @@ __global__ __launch_bounds__(64 * (WK * WP + LW), WPE) void igemm_bf16_kernel(Ig
     const int vb = sk_virtual_block(blockIdx.x, P.nblocks);
     const int tile_s0 = P.own * P.nblocks;                          // first shared tile
     const long long total = (long long)(P.tiles - tile_s0) * NU;    // units of the shared tiles
-    const long long ub = sk_begin(total, P.nblocks, vb), ue = sk_begin(total, P.nblocks, vb + 1);
+    const int rank = sk_share_rank(P.nblocks, P.nshare, vb);
+    const long long ub = rank < 0 ? 0 : sk_begin(total, P.nshare, rank), ue = rank < 0 ? 0 : sk_begin(total, P.nshare, rank + 1);
     const int n_own = P.own * NU;                                    // units of this block's own tiles
     const int nunits = n_own + (int)(ue - ub);
     if (nunits == 0) return;

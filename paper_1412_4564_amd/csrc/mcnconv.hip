@@ -177,7 +177,7 @@ int launch_igemm_inst(const IgemmPlan &pl, const float *in, const float *wpk, co
     int st = check_launch();
     if (st || P.nblocks < 2 || P.own * P.nblocks == P.tiles) return st;      // no tile is shared
     constexpr int TK = WK * MK * 32, TQ = WP * MP * 32;
-    hipLaunchKernelGGL((igemm_fixup_kernel<TK, TQ>), dim3(P.nblocks - 1, 16), dim3(256), 0, s, P, part, bias, out);
+    hipLaunchKernelGGL((igemm_fixup_kernel<TK, TQ>), dim3(P.nshare - 1, 16), dim3(256), 0, s, P, part, bias, out);
     return check_launch();
 }
 
@@ -203,7 +203,7 @@ int launch_igemm_bf16_inst(const IgemmPlan &pl, const float *in, const float *wp
     int st = check_launch();
     if (st || P.nblocks < 2 || P.own * P.nblocks == P.tiles) return st;      // no tile is shared
     constexpr int TK = WK * MK * 32, TQ = WP * MP * 32;
-    hipLaunchKernelGGL((igemm_fixup_kernel<TK, TQ>), dim3(P.nblocks - 1, 16), dim3(256), 0, s, P, part, bias, out);
+    hipLaunchKernelGGL((igemm_fixup_kernel<TK, TQ>), dim3(P.nshare - 1, 16), dim3(256), 0, s, P, part, bias, out);
     return check_launch();
 }
 
