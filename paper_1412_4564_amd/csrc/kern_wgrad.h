@@ -54,7 +54,12 @@ struct WgradParams {
     int tiles, nblocks;
     int relu;            // 1: results are written as max(0, .)  (forward pass of a fully-connected layer + ReLU)
     int nchunks;         // 0: blocks share the list of all (tile, unit) pairs in equal contiguous ranges;
-                         // > 0: block (tile, chunk) sums chunk `chunk` of nchunks equal ranges of the tile's units
+                         // > 0: block (tile, chunk) sums chunk `chunk` of nchunks ranges of the tile's units
+    // Chunk sizes: a chunk computed by one of the first n_first blocks (hardware ids; the blocks dispatched
+    // first, one per compute unit) weighs w_first, any other w_later.  Of the two blocks resident on a
+    // compute unit the one dispatched first gets more of the matrix core; with equal chunks it finishes
+    // early and leaves the other to run alone, which uses the core less well.
+    int n_first, w_first, w_later;
 };
 
 // Chunked schedule: blocks are numbered chunk-major (virtual block = tile + tiles*chunk) and the virtual
@@ -108,8 +113,20 @@ __global__ __launch_bounds__(64 * (WK * WR + WGRAD_LOADER_WAVES), WPE) void wgra
         vb = wg_chunk_virtual_block(blockIdx.x, gridDim.x);
         if (vb >= P.nblocks) return;
         const int tile = vb % P.tiles, chunk = vb / P.tiles;
-        ub = (long long)tile * P.NU + (long long)P.NU * chunk / P.nchunks;
-        ue = (long long)tile * P.NU + (long long)P.NU * (chunk + 1) / P.nchunks;
+        // weight of the tile's chunks before this one, of this one, and of all of them
+        const int G8 = (int)gridDim.x >> 3;
+        long long w_before = 0, w_all = 0;
+        int w_mine = P.w_later;
+        for (int c = 0; c < P.nchunks; ++c) {
+            const int v = tile + P.tiles * c;
+            const int b = gridDim.x % 8 == 0 ? 8 * (v % G8) + v / G8 : v;      // hardware id of virtual block v
+            const int w = b < P.n_first ? P.w_first : P.w_later;
+            if (c < chunk) w_before += w;
+            if (c == chunk) w_mine = w;
+            w_all += w;
+        }
+        ub = (long long)tile * P.NU + (long long)P.NU * w_before / w_all;
+        ue = (long long)tile * P.NU + (long long)P.NU * (w_before + w_mine) / w_all;
     } else {
         vb = sk_virtual_block(blockIdx.x, P.nblocks);
         const long long total = (long long)P.tiles * P.NU;
