@@ -128,7 +128,8 @@ inline ConvView fc_backward_filter_view(const Geom &g) {
     return v;
 }
 
-enum IgemmShape { IG_128x256 = 0, IG_64x512 = 1, IG_32x256 = 2, IG_64x256 = 3, IG_NONE = -1 };
+// IG_W*: the WINO kernels (filters x pairs of output rows)
+enum IgemmShape { IG_128x256 = 0, IG_64x512 = 1, IG_32x256 = 2, IG_64x256 = 3, IG_W128x128 = 4, IG_W64x256 = 5, IG_NONE = -1 };
 
 struct IgemmPlan {
     int shape;          // IgemmShape
@@ -151,6 +152,7 @@ constexpr int IGEMM_LOADER_WAVES = 4;     // fetching waves per block
 struct IgemmFixed { int HF, WF, DC; };
 constexpr IgemmFixed IGEMM_FIXED[] = {{0, 0, 0}, {3, 3, 8}, {1, 1, 32}, {5, 5, 4}};
 constexpr int IGEMM_N_FIXED = 4;
+constexpr IgemmFixed IGEMM_WINO = {4, 3, 8};      // the WINO kernels: four row combinations x three columns, 8 channels per unit
 
 // exact number of slab columns the worst pixel tile needs
 inline int slab_columns(const ConvView &v, int TI, int TQ, int Wp) {
@@ -217,15 +219,20 @@ inline bool cut_units_bf16(const ConvView &v, int TK, int64_t CP, size_t lds_lef
     return false;
 }
 
-inline bool plan_igemm_kind(const ConvView &v, int n_cu, IgemmPlan *pl, bool bf16, int fixed, bool two = false) {
+// wino: `v` is the stride-2, four-tap view of pairs of output rows (wino_view) and wino_Ho the real number of rows
+inline bool plan_igemm_kind(const ConvView &v, int n_cu, IgemmPlan *pl, bool bf16, int fixed, bool two = false,
+                            int wino_Ho = 0) {
     const int T = v.Hf * v.Wf;
-    const IgemmFixed FX = IGEMM_FIXED[fixed];
+    const bool wino = wino_Ho > 0;
+    const IgemmFixed FX = wino ? IGEMM_WINO : IGEMM_FIXED[fixed];
     int shape, WK, WP, MK, MP;
     // `two`: blocks of four waves, two of them resident per compute unit (half the LDS each): while one is
     // at its barrier or writes a tile, the other keeps the matrix cores busy
     const size_t lds_limit = two ? IGEMM_LDS_LIMIT / 2 : IGEMM_LDS_LIMIT;
     const int resident = two ? 2 * n_cu : n_cu;
-    if (two) { shape = IG_64x256; WK = 1; WP = 4; MK = 2; MP = 2; }
+    if (wino && v.Kg > 64) { shape = IG_W128x128; WK = 2; WP = 4; MK = 2; MP = 1; }
+    else if (wino) { shape = IG_W64x256; WK = 1; WP = 8; MK = 2; MP = 1; }
+    else if (two) { shape = IG_64x256; WK = 1; WP = 4; MK = 2; MP = 2; }
     else if (v.Kg > 64) { shape = IG_128x256; WK = 2; WP = 4; MK = 2; MP = 2; }
     else if (v.Kg > 32) { shape = IG_64x512; WK = 1; WP = 8; MK = 2; MP = 2; }
     else { shape = IG_32x256; WK = 1; WP = 4; MK = 1; MP = 2; }
@@ -262,7 +269,7 @@ inline bool plan_igemm_kind(const ConvView &v, int n_cu, IgemmPlan *pl, bool bf1
         if (bf16) {
             if (fixed_lds + 64 > lds_limit) continue;
             if (!cut_units_bf16(v, TK, CP, lds_limit - fixed_lds - 64, &uc)) continue;
-        } else if (fixed) {
+        } else if (fixed || wino) {
             uc.pair_mode = 0; uc.DC = FX.DC; uc.TC = T; uc.NTR = 1; uc.NS = (FX.DC / 2) * T;
             if ((2 * ((size_t)uc.NS * 2 * TK + 255) + 2 * (size_t)uc.DC * CP) * 4 + fixed_lds > lds_limit) continue;
         } else {
@@ -314,7 +321,7 @@ inline bool plan_igemm_kind(const ConvView &v, int n_cu, IgemmPlan *pl, bool bf1
         // Times in microseconds: a unit's MFMAs at about 80 % of the matrix core's rate (two waves per SIMD with
         // 512 threads or two resident blocks), the fix-up as a launch plus its traffic at about 4 TB/s.
         const double unit_us = (two ? 2 : NT / 256) * (double)P.NS * MK * MP * 64.0 / 0.8 / 2400.0;
-        const double fix_us = 6.0 + (double)P.nblocks * TK * TQ * 8.0 / 4.0e6;
+        const double fix_us = 6.0 + (double)P.nblocks * TK * TQ * (wino ? 16.0 : 8.0) / 4.0e6;
         const double shared_us = (double)((total + P.nblocks - 1) / P.nblocks) * unit_us + fix_us;
         if ((double)P.NU * unit_us <= shared_us) {
             P.nblocks = (int)tiles;
@@ -328,6 +335,7 @@ inline bool plan_igemm_kind(const ConvView &v, int n_cu, IgemmPlan *pl, bool bf1
         P.nshare = P.nblocks / 2;
     P.OH = v.OH; P.OW = v.OW; P.oi0 = v.oi0; P.osi = v.osi; P.oj0 = v.oj0; P.osj = v.osj;
     P.mD = v.mD; P.mPt = v.mPt; P.mPl = v.mPl;
+    P.wino_Ho = wino_Ho;
     P.dTI = make_div32(P.TI); P.dWo = make_div32(P.Wo); P.dWp = make_div32(P.Wp); P.dSRP = make_div32(P.SRP);
     P.dKT = make_div32(P.KT); P.dRB = make_div32(P.RB); P.dPT = make_div32(P.PT);
     // packed weights per unit, in 32-bit words: bf16 steps hold 2 octets x TK filters x 16 bytes
@@ -337,7 +345,7 @@ inline bool plan_igemm_kind(const ConvView &v, int n_cu, IgemmPlan *pl, bool bf1
     if (pl->packed_floats * 4 >= 2147483647ull) return false;
     P.packed_bytes = (unsigned)(pl->packed_floats * 4);
     // no workspace for partial tiles when no tile is shared
-    pl->partial_floats = P.nblocks > 1 && (int64_t)P.own * P.nblocks != tiles ? (size_t)2 * P.nblocks * TK * TQ : 0;
+    pl->partial_floats = P.nblocks > 1 && (int64_t)P.own * P.nblocks != tiles ? (size_t)2 * P.nblocks * TK * TQ * (wino ? 2 : 1) : 0;
     pl->shape = shape; pl->bf16 = bf16; pl->fixed = fixed; pl->TK = TK; pl->TQ = TQ; pl->NT = NT;
     pl->score = best_score;
     if (bf16)
@@ -345,7 +353,7 @@ inline bool plan_igemm_kind(const ConvView &v, int n_cu, IgemmPlan *pl, bool bf1
                         sizeof(float);
     else
         pl->lds_bytes = (2 * wsz + 2 * (size_t)P.DC * P.CP + (size_t)P.EPT * NL + 2 * TK +
-                         (fixed ? 0 : (size_t)P.NTR * P.NS * 2) + 4) * sizeof(float);
+                         (fixed || wino ? 0 : (size_t)P.NTR * P.NS * 2) + 4) * sizeof(float);
     if (pl->lds_bytes > lds_limit) return false;
 
     PackParams &Q = pl->Q;
@@ -355,14 +363,34 @@ inline bool plan_igemm_kind(const ConvView &v, int n_cu, IgemmPlan *pl, bool bf1
     Q.DC = P.DC; Q.TC = P.TC; Q.pair_mode = P.pair_mode; Q.mode = v.pack_mode;
     Q.Sh = v.pSh; Q.Sw = v.pSw; Q.pi = v.pi; Q.pj = v.pj; Q.ldk = v.ldk;
     Q.mD = v.mD; Q.Pt = v.mPt; Q.Pl = v.mPl; Q.B0i = v.B0i; Q.B0j = v.B0j;
+    Q.wino = wino ? 1 : 0;
     Q.total = (int)pl->packed_floats;
     return true;
+}
+
+// 3x3 filters at stride 1 whose channels divide into units of 8: the view of pairs of output rows that the
+// WINO kernels compute (kern_igemm.h).  Its rows are pairs, its four "taps" per column the four input rows a
+// pair reads; results go to rows oi0 + osi * (2 * pair + {0, 1}) of the output array.
+inline bool wino_view(const ConvView &v, ConvView *out) {
+    if (v.Hf != 3 || v.Wf != 3 || v.Sh != 1 || v.Sw != 1 || v.mD || v.pack_mode > 1) return false;
+    if (v.HfA != 3 || v.WfA != 3 || (v.pack_mode == 1 && (v.pSh != 1 || v.pSw != 1))) return false;
+    if (v.Cg % IGEMM_WINO.DC != 0 || v.Cg < 2 * IGEMM_WINO.DC || v.Ho < 2) return false;
+    ConvView p = v;
+    p.Hf = 4; p.Sh = 2; p.Ho = (v.Ho + 1) / 2; p.osi = 2 * v.osi;
+    *out = p;
+    return true;
+}
+inline bool wino_enabled() {
+    static const bool on = getenv("MCN_WINO") != nullptr;
+    return on;
 }
 
 // The instantiation with this view's filter size if there is one, its channels divide into the
 // fixed units and a plan fits; the general kernel otherwise.
 inline bool plan_igemm(const ConvView &v, int n_cu, IgemmPlan *pl, bool bf16 = false) {
     if (bf16) return plan_igemm_kind(v, n_cu, pl, true, 0);
+    ConvView pv;
+    if (wino_enabled() && wino_view(v, &pv) && plan_igemm_kind(pv, n_cu, pl, false, 0, false, v.Ho)) return true;
     // the instantiation with this view's filter size, if there is one and the channels divide into its units
     int fixed = 0;
     for (int f = 1; f < IGEMM_N_FIXED; ++f) {

@@ -37,6 +37,15 @@
 //  * staging: global -> LDS loads bypass the registers (buffer_load ... lds),
 //    double-buffered one unit ahead; padding is produced by the out-of-range rule of
 //    buffer loads (reads as zero).
+//  * 3x3 filters at stride 1 (template flag WINO): the sum over the three filter rows is evaluated for two
+//    output rows at a time with four products instead of six (the minimal-filtering identity F(2,3):
+//    with d0..d3 the four input rows that the pair of output rows reads and g0..g2 the filter rows,
+//      m0 = (d0-d2) g0,  m1 = (d1+d2) (g0+g1+g2)/2,  m2 = (d2-d1) (g0-g1+g2)/2,  m3 = (d1-d3) g2,
+//      y0 = m0 + m1 + m2,  y1 = m1 - m2 - m3).
+//    The sum over channels and filter columns is taken inside each m, on the matrix core; a "pixel" of
+//    the GEMM is then a pair of output rows, the slab is that of a stride-2 view with four taps per
+//    column, the packed weights hold the four row combinations, and there are four sets of
+//    accumulators.  Two thirds of the MFMAs for the same result, up to rounding order.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -146,6 +155,9 @@ struct IgemmParams {
     // id) gets more of the matrix core and would finish some 10 % earlier on equal work; it takes the left-over
     // units, the other only its own tiles, and half as many partial tiles go through the workspace.
     int nshare;
+    // WINO kernels: the view's real number of output rows (Ho, TI, QN, Sh, Hf and osi above then describe pairs of
+    // rows: Ho = ceil(wino_Ho / 2), Sh = 2, Hf = 4, osi = twice the row step of the output array); 0 otherwise
+    int wino_Ho;
     Div32 dTI, dWo, dWp, dSRP, dKT, dRB, dPT;   // reciprocals of the fields of these names
 };
 
@@ -238,6 +250,7 @@ struct PackParams {
     int Sh, Sw, pi, pj;    // mode 1
     int ldk;               // mode 2
     int mD, Pt, Pl, B0i, B0j;   // mode 3: channels per phase, pads of the convolution, largest b0 per direction
+    int wino;              // modes 0, 1 with a 3x3 filter: Hf = 4 and view tap (ti, tj) is row combination ti of column tj
     int total;
 };
 
@@ -271,7 +284,14 @@ __global__ __launch_bounds__(256) void igemm_pack_weights_kernel(const float *__
     float v = 0.f;
     if (tap >= 0 && k < Q.Kg && c < Q.Cg) {
         const int ti = tap % Q.Hf, tj = tap / Q.Hf;
-        if (Q.mode == 0) {
+        if (Q.wino) {
+            // the three filter rows of column tj (input derivative: of the flipped filter), combined
+            float gr[3];
+            for (int fi = 0; fi < 3; ++fi)
+                gr[fi] = Q.mode == 0 ? w[fi + 3 * (tj + 3 * (c + (size_t)Q.DfA * (g * Q.Kg + k)))]
+                                     : w[(2 - fi) + 3 * ((2 - tj) + 3 * (k + (size_t)Q.DfA * (g * Q.Cg + c)))];
+            v = ti == 0 ? gr[0] : ti == 1 ? 0.5f * (gr[0] + gr[1] + gr[2]) : ti == 2 ? 0.5f * (gr[0] - gr[1] + gr[2]) : gr[2];
+        } else if (Q.mode == 0) {
             v = w[ti + Q.HfA * (tj + Q.WfA * (c + (size_t)Q.DfA * (g * Q.Kg + k)))];
         } else if (Q.mode == 1) {
             const int fi = Q.pi + Q.Sh * (Q.Hf - 1 - ti), fj = Q.pj + Q.Sw * (Q.Wf - 1 - tj);
@@ -297,7 +317,8 @@ __global__ __launch_bounds__(256) void igemm_pack_weights_kernel(const float *__
 // LW > 0: LW more waves that only fetch.  A wave that issues global -> LDS loads is held at each one until
 // the memory pipeline takes it, and a computing wave held there feeds no MFMAs; fetching waves have a whole
 // unit's time to issue, and the computing waves run from barrier to barrier.
-template <int WK, int WP, int MK, int MP, int HF, int WF, int DCF, int WPE, int LW = 0>
+// WINO: two output rows per GEMM pixel, four row combinations per filter column (HF = 4, WF = 3; see the top).
+template <int WK, int WP, int MK, int MP, int HF, int WF, int DCF, int WPE, int LW = 0, bool WINO = false>
 __global__ __launch_bounds__(64 * (WK * WP + LW), WPE) void igemm_sk_kernel(IgemmParams P, const float *__restrict__ in,
                                                                      const float *__restrict__ wpk,
                                                                      const float *__restrict__ bias,
@@ -310,6 +331,8 @@ __global__ __launch_bounds__(64 * (WK * WP + LW), WPE) void igemm_sk_kernel(Igem
     constexpr int TK = WK * MK * 32;
     constexpr int TQ = WP * MP * 32;
     constexpr bool FIXED = HF > 0;
+    constexpr int NX = WINO ? 4 : 1;               // sets of accumulators
+    static_assert(!WINO || (HF == 4 && WF == 3 && DCF % 4 == 0), "WINO: four row combinations of a 3x3 filter");
     static_assert(NLW * 64 >= TK, "the fetching waves stage one bias value per lane");
     const int DC = FIXED ? DCF : P.DC;
     const int NS = FIXED ? (DCF / 2) * HF * WF : P.NS;
@@ -428,11 +451,12 @@ __global__ __launch_bounds__(64 * (WK * WP + LW), WPE) void igemm_sk_kernel(Igem
     int bbase[MP];   // slab offset (floats) of the pixel's window origin (+ channel half when FIXED)
     unsigned ooff[MP];   // byte offset of the lane's first result of the tile relative to the tile's output
                          // window (filter k0 + 4*half of image n_first), or SLAB_INVALID
+    unsigned ooff1[MP];  // WINO: the same for the second row of the pair, SLAB_INVALID if the view has no such row
     bool last_row[MP], last_col[MP];   // merged phases: the pixel is in the view's last row / column
     __amdgpu_buffer_rsrc_t ors = __builtin_amdgcn_make_buffer_rsrc((void *)out, 0, 0, BUFFER_FLAGS);   // the tile's output window
     int c_kt = 0, c_g = 0;
     bool need_init = true;
-    floatx16 acc[MK][MP];
+    floatx16 acc[NX][MK][MP];
     auto setup_compute = [&](int t) {
         ++c_seq;
         int kt, pt, rb, g;
@@ -459,7 +483,10 @@ __global__ __launch_bounds__(64 * (WK * WP + LW), WPE) void igemm_sk_kernel(Igem
                           : SLAB_INVALID;
             last_row[mp] = io == P.Ho - 1;
             last_col[mp] = jo == P.Wo - 1;
+            if constexpr (WINO)
+                ooff1[mp] = ok && 2 * io + 1 < P.wino_Ho ? ooff[mp] + 4u * (unsigned)(P.osi >> 1) : SLAB_INVALID;
         }
+        (void)ooff1;
         const size_t out_base = (size_t)n_first * P.Ktot * OHW;
         size_t out_left = ((size_t)P.N * P.Ktot * OHW - out_base) * 4;
         if (out_left > 0x7fffffffull) out_left = 0x7fffffffull;
@@ -477,7 +504,13 @@ __global__ __launch_bounds__(64 * (WK * WP + LW), WPE) void igemm_sk_kernel(Igem
                 const int kloc = (wk * MK + mk) * 32 + (v >> 2) * 8 + half * 4 + (v & 3);
                 const float bv = with_bias ? bl[kloc] : 0.f;
 #pragma unroll
-                for (int mp = 0; mp < MP; ++mp) acc[mk][mp][v] = bv;
+                for (int mp = 0; mp < MP; ++mp) {
+                    acc[0][mk][mp][v] = bv;
+                    if constexpr (WINO) {
+                        // y0 = m0 + m1 + m2, y1 = m1 - m2 - m3: the bias enters both rows through m0 and -m3
+                        acc[1][mk][mp][v] = 0.f; acc[2][mk][mp][v] = 0.f; acc[3][mk][mp][v] = -bv;
+                    }
+                }
             }
     };
     const int aoff = half * TK + wk * MK * 32 + (lane & 31);
@@ -486,7 +519,58 @@ __global__ __launch_bounds__(64 * (WK * WP + LW), WPE) void igemm_sk_kernel(Igem
         constexpr int part = decltype(PART)::value;
         const float *wl = wbuf + b * WSZ + aoff;
         const float *xl = xbuf + b * XSZ;
-        if constexpr (FIXED) {
+        if constexpr (WINO) {
+            // One macro-step per (channel pair, filter column): the four input rows of the lane's pair of
+            // output rows come as two 8-byte reads (every term of the address is even), are combined
+            // into the four B operands, and meet the four row combinations of the weights.  Rows of the
+            // next macro-step and the weights of the next step are read ahead of the MFMAs.
+            constexpr int NM = (DCF / 2) * 3;
+            constexpr int M0 = part * (NM / 2), M1 = part ? NM : NM / 2;
+            const float2 *xl2 = reinterpret_cast<const float2 *>(xl);
+            const int CP2 = CP, SRP2 = SRP >> 1;          // pitches of a channel pair and of a column, in float2
+            float2 d[2][MP][2];
+            float a[2][MK];
+            auto fetch_d = [&](int m, int slot) {
+                const int dp = m / 3, fj = m % 3;
+#pragma unroll
+                for (int mp = 0; mp < MP; ++mp) {
+                    const int o = (bbase[mp] >> 1) + dp * CP2 + fj * SRP2;
+                    d[slot][mp][0] = xl2[o];
+                    d[slot][mp][1] = xl2[o + 1];
+                }
+            };
+            auto fetch_a = [&](int st, int slot) {
+#pragma unroll
+                for (int mk = 0; mk < MK; ++mk) a[slot][mk] = wl[st * 2 * TK + mk * 32];
+            };
+            fetch_d(M0, M0 & 1);
+            fetch_a(M0 * 4, 0);
+#pragma unroll
+            for (int m = M0; m < M1; ++m) {
+                if (m + 1 < M1) fetch_d(m + 1, (m + 1) & 1);
+                float bv[MP][4];
+#pragma unroll
+                for (int mp = 0; mp < MP; ++mp) {
+                    const float2 lo = d[m & 1][mp][0], hi = d[m & 1][mp][1];
+                    bv[mp][0] = lo.x - hi.x;
+                    bv[mp][1] = lo.y + hi.x;
+                    bv[mp][2] = hi.x - lo.y;
+                    bv[mp][3] = lo.y - hi.y;
+                }
+#pragma unroll
+                for (int xi = 0; xi < 4; ++xi) {
+                    const int st = m * 4 + xi;
+                    if (st + 1 < M1 * 4) fetch_a(st + 1, (st + 1) & 1);
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int mk = 0; mk < MK; ++mk)
+#pragma unroll
+                        for (int mp = 0; mp < MP; ++mp)
+                            acc[xi][mk][mp] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[st & 1][mk], bv[mp][xi], acc[xi][mk][mp], 0, 0, 0);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+        } else if constexpr (FIXED) {
             // the (channel pair, tap) steps of a unit form one flat, fully unrolled list; the LDS
             // reads of step s+1 are issued before the MFMAs of step s.
             constexpr int TT = HF * WF;
@@ -510,7 +594,7 @@ __global__ __launch_bounds__(64 * (WK * WP + LW), WPE) void igemm_sk_kernel(Igem
                 for (int mk = 0; mk < MK; ++mk)
 #pragma unroll
                     for (int mp = 0; mp < MP; ++mp)
-                        acc[mk][mp] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[s & 1][mk], bb[s & 1][mp], acc[mk][mp], 0, 0, 0);
+                        acc[0][mk][mp] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[s & 1][mk], bb[s & 1][mp], acc[0][mk][mp], 0, 0, 0);
                 __builtin_amdgcn_sched_barrier(0);
             }
         } else {
@@ -532,7 +616,7 @@ __global__ __launch_bounds__(64 * (WK * WP + LW), WPE) void igemm_sk_kernel(Igem
                 for (int mk = 0; mk < MK; ++mk)
 #pragma unroll
                     for (int mp = 0; mp < MP; ++mp)
-                        acc[mk][mp] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[mk], bq[mp], acc[mk][mp], 0, 0, 0);
+                        acc[0][mk][mp] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[mk], bq[mp], acc[0][mk][mp], 0, 0, 0);
             };
             fetch(a0, b0, s0, o0);
             for (int s = s0; s < s1; s += 2) {
@@ -570,16 +654,26 @@ __global__ __launch_bounds__(64 * (WK * WP + LW), WPE) void igemm_sk_kernel(Igem
                 if (left <= 0) continue;
                 const unsigned soff = (unsigned)(c_g * P.Kg + kl0) * (unsigned)OHW * 4u;
                 // the upper half-wave holds filter kl0 + 4
-                if (left > 4) {
+                if constexpr (WINO) {
 #pragma unroll
                     for (int mp = 0; mp < MP; ++mp) {
-                        const float val = relu ? fmaxf(acc[mk][mp][v], 0.f) : acc[mk][mp][v];
+                        const float m1 = acc[1][mk][mp][v], m2 = acc[2][mk][mp][v];
+                        float y0 = acc[0][mk][mp][v] + m1 + m2, y1 = m1 - m2 - acc[3][mk][mp][v];
+                        if (relu) { y0 = fmaxf(y0, 0.f); y1 = fmaxf(y1, 0.f); }
+                        const bool both = left > 4 || half == 0;
+                        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(y0), ors, both ? ooff[mp] : SLAB_INVALID, soff, 0);
+                        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(y1), ors, both ? ooff1[mp] : SLAB_INVALID, soff, 0);
+                    }
+                } else if (left > 4) {
+#pragma unroll
+                    for (int mp = 0; mp < MP; ++mp) {
+                        const float val = relu ? fmaxf(acc[0][mk][mp][v], 0.f) : acc[0][mk][mp][v];
                         __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(val), ors, ooff[mp], soff, 0);
                     }
                 } else {
 #pragma unroll
                     for (int mp = 0; mp < MP; ++mp) {
-                        const float val = relu ? fmaxf(acc[mk][mp][v], 0.f) : acc[mk][mp][v];
+                        const float val = relu ? fmaxf(acc[0][mk][mp][v], 0.f) : acc[0][mk][mp][v];
                         __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(val), ors, olow[mp], soff, 0);
                     }
                 }
@@ -618,23 +712,35 @@ __global__ __launch_bounds__(64 * (WK * WP + LW), WPE) void igemm_sk_kernel(Igem
                 for (int mp = 0; mp < MP; ++mp) {
                     const bool drop = no || (sr && last_row[mp]) || (sc && last_col[mp]) || ooff[mp] == SLAB_INVALID;
                     const unsigned vo = drop ? SLAB_INVALID : ooff[mp] + fo;
-                    float val = acc[mk][mp][v];
+                    float val = acc[0][mk][mp][v];
                     if (P.relu) val = fmaxf(val, 0.f);
                     __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(val), ors, vo, 0, 0);
                 }
             }
         }
     };
+    // a piece of a shared tile, [filter][pixel]; WINO: in the output domain (the combination of the four sums
+    // is linear), pixel = 2 * pair + row, so that the fix-up pass sees an ordinary tile of 2*TQ pixels
     auto store_partial = [&](int slot) {
-        float *dst = part + (size_t)slot * (TK * TQ);
+        float *dst = part + (size_t)slot * (TK * TQ * (WINO ? 2 : 1));
 #pragma unroll
         for (int mk = 0; mk < MK; ++mk)
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int kloc = (wk * MK + mk) * 32 + (v >> 2) * 8 + half * 4 + (v & 3);
 #pragma unroll
-                for (int mp = 0; mp < MP; ++mp)
-                    dst[kloc * TQ + (wp * MP + mp) * 32 + (lane & 31)] = acc[mk][mp][v];
+                for (int mp = 0; mp < MP; ++mp) {
+                    const int ql = (wp * MP + mp) * 32 + (lane & 31);
+                    if constexpr (WINO) {
+                        const float m1 = acc[1][mk][mp][v], m2 = acc[2][mk][mp][v];
+                        float2 y;
+                        y.x = acc[0][mk][mp][v] + m1 + m2;
+                        y.y = m1 - m2 - acc[3][mk][mp][v];
+                        *reinterpret_cast<float2 *>(dst + kloc * (2 * TQ) + 2 * ql) = y;
+                    } else {
+                        dst[kloc * TQ + ql] = acc[0][mk][mp][v];
+                    }
+                }
             }
     };
 

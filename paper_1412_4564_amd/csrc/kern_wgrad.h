@@ -70,9 +70,10 @@ __device__ __host__ inline int wg_chunk_grid(int nblocks) { return nblocks < 8 ?
 __device__ inline int wg_chunk_virtual_block(int b, int grid) { return grid % 8 == 0 ? (b % 8) * (grid / 8) + b / 8 : b; }
 
 // Waves beyond the WK*WR computing ones only fetch.  A wave that issues global -> LDS loads is held at
-// each one until the memory pipeline takes it (some 50-150 cycles per instruction here), and a computing
-// wave held there feeds no MFMAs: with the fetches in waves of their own, the computing waves run from
-// barrier to barrier without a stall, and the fetching waves have a whole unit's time to issue.
+// each one until the memory pipeline takes it (measured: in proportion to the bytes, some 20-130 cycles
+// per 256-byte instruction depending on the access pattern and on how many waves load at once), and a
+// computing wave held there feeds no MFMAs: with the fetches in waves of their own, the computing waves
+// run from barrier to barrier without a stall, and the fetching waves have a whole unit's time to issue.
 constexpr int WGRAD_LOADER_WAVES = 4;
 
 // S1: vertical stride 1 (the slab rows of consecutive pixels are adjacent)

@@ -181,6 +181,30 @@ int launch_igemm_inst(const IgemmPlan &pl, const float *in, const float *wpk, co
     return check_launch();
 }
 
+// The WINO kernels (pairs of output rows, kern_igemm.h): 8 computing + 4 fetching waves, 128 accumulator
+// registers per lane.  The fix-up pass sees the shared tiles in the output domain: rows instead of pairs.
+template <int WK, int WP, int MK>
+int launch_igemm_wino(const IgemmPlan &pl, const float *in, const float *wpk, const float *bias, float *out,
+                      float *part, hipStream_t s, int relu) {
+    IgemmParams P = pl.P;
+    P.relu = relu;
+    constexpr int LW = IGEMM_LOADER_WAVES;
+    auto kern = igemm_sk_kernel<WK, WP, MK, 1, IGEMM_WINO.HF, IGEMM_WINO.WF, IGEMM_WINO.DC, 3, LW, true>;
+    if (pl.lds_bytes > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           (int)pl.lds_bytes);
+        if (e != hipSuccess) { g_last_hip_error = (int)e; return MCN_HIP_ERROR; }
+    }
+    hipLaunchKernelGGL(kern, dim3(P.nblocks), dim3(64 * (WK * WP + LW)), pl.lds_bytes, s, P, in, wpk, bias, out, part);
+    int st = check_launch();
+    if (st || P.nblocks < 2 || P.own * P.nblocks == P.tiles) return st;      // no tile is shared
+    constexpr int TK = WK * MK * 32, TQ = WP * 32;
+    IgemmParams F = P;
+    F.TI = 2 * P.TI; F.QN = 2 * P.QN; F.Ho = P.wino_Ho; F.osi = P.osi / 2;
+    hipLaunchKernelGGL((igemm_fixup_kernel<TK, 2 * TQ>), dim3(P.nshare - 1, 16), dim3(256), 0, s, F, part, bias, out);
+    return check_launch();
+}
+
 // workspace of one view: [packed weights][partial tiles]
 size_t igemm_ws_bytes(const IgemmPlan &pl) {
     return align256(pl.packed_floats * sizeof(float)) + pl.partial_floats * sizeof(float);
@@ -248,6 +272,8 @@ int launch_igemm(const IgemmPlan &pl, const float *in, const float *w, const flo
         case IG_64x512: return launch_igemm_fixed<1, 8, 2, 2>(pl, in, packed, bias, out, part, s, relu);
         case IG_32x256: return launch_igemm_fixed<1, 4, 1, 2>(pl, in, packed, bias, out, part, s, relu);
         case IG_64x256: return launch_igemm_fixed<1, 4, 2, 2>(pl, in, packed, bias, out, part, s, relu);
+        case IG_W128x128: return launch_igemm_wino<2, 4, 2>(pl, in, packed, bias, out, part, s, relu);
+        case IG_W64x256: return launch_igemm_wino<1, 8, 2>(pl, in, packed, bias, out, part, s, relu);
         default: return MCN_BAD_ARG;
     }
 }
