@@ -375,14 +375,15 @@ inline bool wino_view(const ConvView &v, ConvView *out) {
     if (v.Hf != 3 || v.Wf != 3 || v.Sh != 1 || v.Sw != 1 || v.mD || v.pack_mode > 1) return false;
     if (v.HfA != 3 || v.WfA != 3 || (v.pack_mode == 1 && (v.pSh != 1 || v.pSw != 1))) return false;
     if (v.Cg % IGEMM_WINO.DC != 0 || v.Cg < 2 * IGEMM_WINO.DC || v.Ho < 2) return false;
+    if (v.Kg <= 32) return false;      // the WINO tiles are 64 or 128 filters wide; narrower layers keep the 32-filter tiles
     ConvView p = v;
     p.Hf = 4; p.Sh = 2; p.Ho = (v.Ho + 1) / 2; p.osi = 2 * v.osi;
     *out = p;
     return true;
 }
 inline bool wino_enabled() {
-    static const bool on = getenv("MCN_WINO") != nullptr;
-    return on;
+    static const bool off = getenv("MCN_NO_WINO") != nullptr;      // benchmarking / debugging override
+    return !off;
 }
 
 // The instantiation with this view's filter size if there is one, its channels divide into the

@@ -55,6 +55,7 @@ namespace mcn {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef unsigned uintx2 __attribute__((ext_vector_type(2)));
 
 #define MCN_LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
 
@@ -158,6 +159,8 @@ struct IgemmParams {
     // WINO kernels: the view's real number of output rows (Ho, TI, QN, Sh, Hf and osi above then describe pairs of
     // rows: Ho = ceil(wino_Ho / 2), Sh = 2, Hf = 4, osi = twice the row step of the output array); 0 otherwise
     int wino_Ho;
+    int wino_pairs;     // WINO: 1 = both rows of a pair go out in one 8-byte store (rows adjacent in memory, every such
+                        // address a multiple of 8: output pointer aligned to 8 bytes and an even number of rows per plane)
     Div32 dTI, dWo, dWp, dSRP, dKT, dRB, dPT;   // reciprocals of the fields of these names
 };
 
@@ -642,6 +645,8 @@ __global__ __launch_bounds__(64 * (WK * WP + LW), WPE) void igemm_sk_kernel(Igem
     // MFMAs of the block that shares the compute unit.)
     auto store_tile_as = [&](auto RELU) {
         constexpr bool relu = decltype(RELU)::value;
+        const bool pairs = WINO && P.wino_pairs, odd_rows = WINO && (P.wino_Ho & 1);     // block-wide
+        (void)pairs; (void)odd_rows;
         unsigned olow[MP];      // offsets for a store of which only the lower half-wave's filter exists
 #pragma unroll
         for (int mp = 0; mp < MP; ++mp) olow[mp] = half == 0 ? ooff[mp] : SLAB_INVALID;
@@ -661,8 +666,18 @@ __global__ __launch_bounds__(64 * (WK * WP + LW), WPE) void igemm_sk_kernel(Igem
                         float y0 = acc[0][mk][mp][v] + m1 + m2, y1 = m1 - m2 - acc[3][mk][mp][v];
                         if (relu) { y0 = fmaxf(y0, 0.f); y1 = fmaxf(y1, 0.f); }
                         const bool both = left > 4 || half == 0;
-                        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(y0), ors, both ? ooff[mp] : SLAB_INVALID, soff, 0);
-                        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(y1), ors, both ? ooff1[mp] : SLAB_INVALID, soff, 0);
+                        if (pairs) {
+                            // both rows in one store; a pair without a second row (odd number of rows) goes alone
+                            const bool two_rows = ooff1[mp] != SLAB_INVALID;
+                            uintx2 yy;
+                            yy.x = __float_as_uint(y0); yy.y = __float_as_uint(y1);
+                            __builtin_amdgcn_raw_buffer_store_b64(yy, ors, both && two_rows ? ooff[mp] : SLAB_INVALID, soff, 0);
+                            if (odd_rows)
+                                __builtin_amdgcn_raw_buffer_store_b32(yy.x, ors, both && !two_rows ? ooff[mp] : SLAB_INVALID, soff, 0);
+                        } else {
+                            __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(y0), ors, both ? ooff[mp] : SLAB_INVALID, soff, 0);
+                            __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(y1), ors, both ? ooff1[mp] : SLAB_INVALID, soff, 0);
+                        }
                     }
                 } else if (left > 4) {
 #pragma unroll

@@ -188,6 +188,7 @@ int launch_igemm_wino(const IgemmPlan &pl, const float *in, const float *wpk, co
                       float *part, hipStream_t s, int relu) {
     IgemmParams P = pl.P;
     P.relu = relu;
+    P.wino_pairs = P.osi == 2 && P.OH % 2 == 0 && ((uintptr_t)out & 7) == 0;
     constexpr int LW = IGEMM_LOADER_WAVES;
     auto kern = igemm_sk_kernel<WK, WP, MK, 1, IGEMM_WINO.HF, IGEMM_WINO.WF, IGEMM_WINO.DC, 3, LW, true>;
     if (pl.lds_bytes > 48 * 1024) {
@@ -542,9 +543,12 @@ const char *mcn_conv_kernel_name(const mcn_conv_desc *desc, int op) {
     if (make_geom(desc, &g)) return NULL;
     const PlanEntry *e = plans_for(desc, g);
     switch (op) {
-        case MCN_OP_FORWARD: return e->fc ? "fc_gemm" : e->fwd_ok ? (e->fwd.bf16 ? "igemm_bf16" : "igemm") : "direct";
+        case MCN_OP_FORWARD:
+            return e->fc ? "fc_gemm" : e->fwd_ok ? (e->fwd.bf16 ? "igemm_bf16" : e->fwd.P.wino_Ho ? "igemm_f23" : "igemm") : "direct";
         case MCN_OP_BACKWARD_DATA:
-            return e->fc ? "fc_gemm" : e->bwd_ok ? (e->n_bwd && e->bwd[0].bf16 ? "igemm_bf16" : "igemm") : "direct";
+            return e->fc ? "fc_gemm"
+                         : e->bwd_ok ? (e->n_bwd && e->bwd[0].bf16 ? "igemm_bf16" : e->n_bwd && e->bwd[0].P.wino_Ho ? "igemm_f23" : "igemm")
+                                     : "direct";
         case MCN_OP_BACKWARD_FILTER: return e->fc ? "fc_gemm" : e->wgb_ok ? "wgrad_bf16" : e->wg_ok ? "wgrad_igemm" : "direct";
         case MCN_OP_BACKWARD_BIAS: return plan_bias(g).rows ? "reduce_rows" : "reduce2";
         default: return NULL;

@@ -266,6 +266,11 @@ def test_planner_puts_every_workload_layer_on_the_matrix_core_kernels():
             assert all(0 <= s < (1 << 28) for s in sizes), (name, sizes)       # scratch stays below 256 MiB
     d = B.make_desc(synth.x_shape(synth.LAYERS["5a"]), synth.w_shape(synth.LAYERS["5a"]))
     assert [B.mcn_conv_kernel_name(d, op) for op in range(3)] == ["fc_gemm"] * 3
+    # the 3x3 stride-1 layers: forward and input derivative on the kernel that computes pairs of output rows
+    for name in ("4a", "4b", "4c"):
+        L = synth.LAYERS[name]
+        d = B.make_desc(synth.x_shape(L), synth.w_shape(L), L["stride"], L["pad"])
+        assert [B.mcn_conv_kernel_name(d, op) for op in range(3)] == ["igemm_f23", "igemm_f23", "wgrad_igemm"], name
     # bf16 operands: the deep layers on the bf16 kernels, the 3-channel first layers on the fp32 ones
     for name, expect in (("4b", ["igemm_bf16", "igemm_bf16", "wgrad_bf16"]), ("3a", ["igemm", "igemm", "wgrad_igemm"])):
         L = synth.LAYERS[name]

@@ -135,6 +135,76 @@ def test_fallback_kernels_in_a_process_of_their_own():
     assert r.returncode == 0 and "FALLBACK-OK" in r.stdout, (r.stdout[-2000:], r.stderr[-2000:])
 
 
+# ---- 3x3 filters at stride 1: the kernel that computes pairs of output rows -------------
+ROW_PAIRS = [
+    # H   W   D   N  Df   K   pad
+    (16, 12, 16, 3, 16, 48, (1, 1, 1, 1)),       # even number of output rows
+    (15, 13, 16, 2, 16, 40, (1, 1, 1, 1)),       # odd: the last pair has one row
+    (17, 9, 24, 2, 24, 64, (0, 0, 0, 0)),        # no padding
+    (11, 14, 40, 3, 40, 72, (2, 0, 1, 2)),       # four different pads, filters ragged against the tile
+    (20, 10, 48, 2, 16, 144, (1, 1, 1, 1)),      # three groups
+    (14, 14, 64, 4, 64, 160, (1, 1, 1, 1)),      # two filter tiles of 128, the second ragged
+    (150, 6, 16, 2, 16, 40, (1, 1, 1, 1)),       # tall planes: several row blocks
+    (40, 40, 32, 8, 32, 64, (1, 1, 1, 1)),       # more tiles than compute units, some shared between blocks
+    (28, 28, 64, 16, 64, 256, (1, 1, 1, 1)),
+    (3, 3, 16, 1, 16, 40, (1, 1, 1, 1)),         # one pair and a single row
+    (6, 7, 16, 2, 16, 36, (3, 2, 2, 3)),         # pads larger than the filter reach
+]
+
+
+@pytest.mark.parametrize("case", range(len(ROW_PAIRS)))
+def test_3x3_stride1_row_pair_kernel(case):
+    H, W, D, N, Df, K, pad = ROW_PAIRS[case]
+    L = custom_layer(H, W, D, N, 3, 3, Df, K, (1, 1), pad, idx=500 + case)
+    d = B.make_desc(synth.x_shape(L), synth.w_shape(L), (1, 1), pad)
+    # the input derivative is a 3x3 sum over dzdy with the layer's input channels as its filters: the row-pair
+    # kernel takes it when those are more than 32 and the filters per group fill its units of 8 channels
+    Kg = K // (D // Df)
+    bwd = "igemm_f23" if Df > 32 and Kg % 8 == 0 else "igemm"
+    assert [B.mcn_conv_kernel_name(d, op) for op in range(2)] == ["igemm_f23", bwd]
+    for with_bias in (True, False):
+        U.assert_errors(U.run_layer_full(L, with_bias=with_bias, misalign=case % 2), label="row pairs %d" % case)
+
+
+def test_row_pair_kernel_only_where_it_applies():
+    """Other filter sizes, strides, few filters per group or channels that do not fill its units of 8 keep the
+    kernels that compute one output row per pixel."""
+    for (Hf, Wf, Df, K, st) in ((3, 3, 16, 32, (1, 1)), (3, 3, 12, 64, (1, 1)), (3, 3, 16, 64, (2, 1)), (3, 3, 16, 64, (1, 2)),
+                                (4, 3, 16, 64, (1, 1)), (3, 5, 16, 64, (1, 1)), (3, 3, 8, 64, (1, 1))):
+        L = custom_layer(12, 12, Df, 2, Hf, Wf, Df, K, st, (1, 1, 1, 1), idx=520)
+        d = B.make_desc(synth.x_shape(L), synth.w_shape(L), st, (1, 1, 1, 1))
+        assert B.mcn_conv_kernel_name(d, 0) == "igemm", (Hf, Wf, Df, K, st)
+
+
+_ONE_ROW_SCRIPT = r"""
+import sys
+sys.path.insert(0, sys.argv[1]); sys.path.insert(0, sys.argv[1] + "/tests")
+import parity_util as U
+from paper_1412_4564_amd import binding as B, synth
+cases = [(16, 12, 16, 3, 16, 48, (1, 1, 1, 1)), (15, 13, 16, 2, 16, 40, (1, 1, 1, 1)), (11, 14, 32, 3, 32, 70, (2, 0, 1, 2)),
+         (20, 10, 48, 2, 16, 144, (1, 1, 1, 1)), (40, 40, 32, 8, 32, 64, (1, 1, 1, 1)), (28, 28, 64, 16, 64, 256, (1, 1, 1, 1))]
+for i, (H, W, D, N, Df, K, pad) in enumerate(cases):
+    L = dict(H=H, W=W, D=D, N=N, Hf=3, Wf=3, Df=Df, K=K, stride=(1, 1), pad=pad, config=9, index=540 + i)
+    d = B.make_desc(synth.x_shape(L), synth.w_shape(L), (1, 1), pad)
+    names = [B.mcn_conv_kernel_name(d, op) for op in range(2)]
+    assert names == ["igemm"] * 2, names
+    U.assert_errors(U.run_layer_full(L, with_bias=bool(i % 2)), label="one row per pixel %d" % i)
+print("ONE-ROW-OK")
+"""
+
+
+def test_3x3_stride1_one_row_kernels_in_a_process_of_their_own():
+    """With MCN_NO_WINO=1 (read once per process) 3x3 stride-1 layers run on the kernels that compute one output
+    row per pixel, as they did before the row-pair kernel existed; those instantiations stay checked."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    env = dict(os.environ, MCN_NO_WINO="1")
+    r = subprocess.run([sys.executable, "-c", _ONE_ROW_SCRIPT, root], env=env, capture_output=True, text=True, timeout=300)
+    assert r.returncode == 0 and "ONE-ROW-OK" in r.stdout, (r.stdout[-2000:], r.stderr[-2000:])
+
+
 # ---- which kernels the dispatcher picks ----------------------------------------------
 def test_workload_layers_run_on_the_matrix_core_kernels():
     """No layer of the workloads may fall back to the one-result-per-thread kernels."""
