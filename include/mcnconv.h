@@ -247,9 +247,9 @@ const char *mcn_status_string(int status);
 int mcn_last_hip_error(void);
 
 /* Name of the kernel family the dispatcher picks for this descriptor and
- * operation ("direct", "igemm", "igemm_f23" = the matrix-core kernel that computes
- * pairs of output rows of a 3x3 stride-1 layer with four products per filter column,
- * ...); for reports and tests.  Returns NULL on a bad descriptor.  Host only. */
+ * operation ("direct", "igemm", "igemm_f23" / "wgrad_f23" = the matrix-core kernels
+ * that take pairs of output rows of a 3x3 stride-1 layer with four products per filter
+ * column, ...); for reports and tests.  Returns NULL on a bad descriptor.  Host only. */
 const char *mcn_conv_kernel_name(const mcn_conv_desc *desc, int op);
 
 /* ---- Measurement aids (no part of the paper's blocks) ---------------------------------

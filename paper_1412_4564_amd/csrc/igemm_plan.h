@@ -416,7 +416,8 @@ inline bool plan_igemm(const ConvView &v, int n_cu, IgemmPlan *pl, bool bf16 = f
 #include "kern_wgrad.h"
 namespace mcn {
 
-enum WgradShape { WG_128x128 = 0, WG_64x192 = 1, WG_32x256 = 2 };
+// WG_W*: the WINO kernels (filters x (filter column, channel) pairs)
+enum WgradShape { WG_128x128 = 0, WG_64x192 = 1, WG_32x256 = 2, WG_W128x128 = 3 };
 
 struct WgradPlan {
     int shape;
@@ -425,18 +426,22 @@ struct WgradPlan {
     size_t lds_bytes;
     int occupancy;           // resident blocks per compute unit
     size_t partial_floats;   // 2 slots of TK*TR per resident block
+    bool wino;               // kern_wgrad.h, template flag WINO; TR then counts coefficients (3 per B lane)
 };
 
-inline bool plan_wgrad(const ConvView &v, int n_cu, WgradPlan *pl) {
-    const int T = v.Hf * v.Wf;
-    const int64_t R64 = (int64_t)T * v.Cg;
-    if (R64 >= ((int64_t)1 << 30)) return false;
-    const int R = (int)R64;
+// wino: the WINO kernel (3x3 filters at stride 1).  Its tiles are 128 filters wide and a unit's staging is paid for
+// by a third fewer MFMAs, so it is used with more than 64 filters per group only.
+inline bool plan_wgrad(const ConvView &v, int n_cu, WgradPlan *pl, bool wino = false) {
+    if (wino && (v.Hf != 3 || v.Wf != 3 || v.Sh != 1 || v.Sw != 1 || v.Ho < 2 || v.Kg <= 64)) return false;
+    const int T = wino ? v.Wf : v.Hf * v.Wf;             // B lanes per channel
+    if ((int64_t)v.Hf * v.Wf * v.Cg >= ((int64_t)1 << 30)) return false;
+    const int R = T * v.Cg;                              // B lanes in all
     // byte offsets into x and dzdy are 32-bit
     if ((double)v.H * v.W * v.Ctot * v.N * 4 >= 2147483647.0) return false;
     if ((double)v.Ho * v.Wo * v.Ktot * v.N * 4 >= 2147483647.0) return false;
     int shape, WK, WR, MK, MR;
-    if (v.Kg > 64) { shape = WG_128x128; WK = 2; WR = 2; MK = 2; MR = 2; }
+    if (wino) { shape = WG_W128x128; WK = 2; WR = 4; MK = 2; MR = 1; }
+    else if (v.Kg > 64) { shape = WG_128x128; WK = 2; WR = 2; MK = 2; MR = 2; }
     else if (v.Kg > 32) { shape = WG_64x192; WK = 2; WR = 2; MK = 1; MR = 3; }
     else { shape = WG_32x256; WK = 1; WR = 4; MK = 1; MR = 2; }
     const int TK = WK * MK * 32, TR = WR * MR * 32, NT = 64 * WK * WR;
@@ -451,18 +456,21 @@ inline bool plan_wgrad(const ConvView &v, int n_cu, WgradPlan *pl) {
 
     // a unit is a patch of TI rows x MC columns of one image's output plane, at most 128 pixels
     double best = 1e30;
-    int bestTI = 0, bestMC = 0, bestSRP = 0, bestCP = 0, bestOcc = 0;
+    int bestTI = 0, bestMC = 0, bestSRP = 0, bestCP = 0, bestOcc = 0, bestPCHP = 0;
     size_t bestLds = 0;
     for (int TI = 1; TI <= v.Ho && TI <= 128; ++TI) {
         const int RB = (v.Ho + TI - 1) / TI;
         if (TI > 1 && TI < v.Ho && (v.Ho + TI - 2) / (TI - 1) == RB) continue;   // a smaller TI gives the same row blocks
-        const int TIE = (TI + 1) & ~1;
+        const int TIE = wino ? (TI + 3) & ~3 : (TI + 1) & ~1;
         const int64_t SR = (int64_t)(TIE - 1) * v.Sh + v.Hf;     // rows the padding pixel of an odd TI reads are staged too
         if (SR > 16384) continue;
         // pitches chosen so that the 32 coefficients a half-wave reads fall in 32 different LDS banks:
         // bank(r) = fi + SRP*fj + CP*c  ==  r  (mod 32)
+        // (WINO: 8-byte reads at SRP/2 * fj + CP/2 * c, in units of 8 bytes: SRP/2 odd and CP = 3 SRP (mod 64)
+        // make that SRP/2 * (fj + 3c), different for the lanes of a half-wave)
         int SRP = (int)SR;
-        while (SRP % 32 != v.Hf % 32) ++SRP;
+        if (wino) while (SRP % 4 != 2) ++SRP;
+        else while (SRP % 32 != v.Hf % 32) ++SRP;
         for (int MC = 1; MC <= v.Wo && TIE * MC <= 128; ++MC) {
             const int CC = (v.Wo + MC - 1) / MC;
             if (MC > 1 && MC < v.Wo && (v.Wo + MC - 2) / (MC - 1) == CC) continue;
@@ -470,19 +478,22 @@ inline bool plan_wgrad(const ConvView &v, int n_cu, WgradPlan *pl) {
             const int64_t SC = (int64_t)(MC - 1) * v.Sw + v.Wf;
             if (SC >= 32768) continue;
             int64_t CP = (int64_t)SRP * SC;
-            while (CP % 32 != T % 32) ++CP;
+            if (wino) while (CP % 64 != (3 * SRP) % 64) ++CP;
+            else while (CP % 32 != T % 32) ++CP;
             const int64_t XS = (int64_t)nch_max * CP;
-            const int PCHP = PCH | 1;
+            int PCHP = PCH | 1;
+            if (wino) { PCHP = PCH; while (PCHP % 4 != 2) ++PCHP; }
             const int EPT = (int)(((int64_t)SRP * SC + NT - 1) / NT);
             const int64_t lds = (2 * (int64_t)TK * PCHP + 2 * XS + (int64_t)EPT * NT + 4) * 4;
             if (lds > (int64_t)IGEMM_LDS_LIMIT) continue;
             int occ = (int)((int64_t)IGEMM_LDS_LIMIT / lds);
             if (occ > 2) occ = 2;   // the kernels are compiled for two waves per SIMD
+            if (NT == 512) occ = 1; // 8 computing + 4 fetching waves: one block per compute unit
             // cost of a unit in matrix-core cycles: its MFMAs plus what staging it costs beside them
             // (fitted to measurements: a fixed part and a part per staged element, about twice as
             // much when only one block fits a compute unit and nothing else hides it)
             const double units = (double)v.N * RB * CC;
-            const double mfma = (double)(PCH / 2) * MK * MR * 64.0;
+            const double mfma = wino ? (double)(PCH / 4) * 4 * MK * MR * 64.0 : (double)(PCH / 2) * MK * MR * 64.0;
             const double elems = (double)klim * PCH + (double)nch_max * (double)(SRP * SC);
             // row runs that do not start on 128-byte lines cost extra memory transactions (a patch of whole
             // columns is one contiguous run of dzdy)
@@ -491,7 +502,7 @@ inline bool plan_wgrad(const ConvView &v, int n_cu, WgradPlan *pl) {
             const double score = units * (mfma + ovh);
             if (score < best) {
                 best = score; bestTI = TI; bestMC = MC; bestSRP = SRP; bestCP = (int)CP; bestOcc = occ;
-                bestLds = (size_t)lds;
+                bestLds = (size_t)lds; bestPCHP = PCHP;
             }
         }
     }
@@ -504,16 +515,16 @@ inline bool plan_wgrad(const ConvView &v, int n_cu, WgradPlan *pl) {
     P.Hf = v.Hf; P.Wf = v.Wf; P.Sh = v.Sh; P.Sw = v.Sw; P.Pt = v.Pt; P.Pl = v.Pl;
     P.TI = bestTI; P.RB = (v.Ho + bestTI - 1) / bestTI;
     P.MC = bestMC; P.CC = (v.Wo + bestMC - 1) / bestMC;
-    P.TIE = (bestTI + 1) & ~1;
+    P.TIE = wino ? (bestTI + 3) & ~3 : (bestTI + 1) & ~1;
     P.SR = (P.TIE - 1) * v.Sh + v.Hf;
     P.SRP = bestSRP; P.SC = (bestMC - 1) * v.Sw + v.Wf; P.CP = bestCP;
     P.EPT = (bestSRP * P.SC + NT - 1) / NT;
     P.KT = (v.Kg + TK - 1) / TK; P.RT = RT;
-    P.PCH = P.TIE * bestMC; P.PCHP = P.PCH | 1;
+    P.PCH = P.TIE * bestMC; P.PCHP = bestPCHP;
     const int64_t NU = (int64_t)v.N * P.RB * P.CC;
     if (NU >= ((int64_t)1 << 30)) return false;
     P.NU = (int)NU;
-    P.R = R;
+    P.R = v.Hf * v.Wf * v.Cg;
     P.XS = nch_max * bestCP;
     const int64_t tiles = (int64_t)v.G * P.KT * RT;
     if (tiles >= ((int64_t)1 << 30)) return false;
@@ -546,8 +557,9 @@ inline bool plan_wgrad(const ConvView &v, int n_cu, WgradPlan *pl) {
         P.w_first = 3; P.w_later = 2;      // measured on layers 4a/4b: 11:9 -1.5 %, 3:2 -2.2 %, 13:7 +1 %
     }
     pl->occupancy = bestOcc;
-    pl->partial_floats = P.nblocks > 1 ? (size_t)2 * P.nblocks * TK * TR : 0;
-    pl->shape = shape; pl->TK = TK; pl->TR = TR; pl->NT = NT;
+    pl->wino = wino;
+    pl->partial_floats = P.nblocks > 1 ? (size_t)2 * P.nblocks * TK * TR * (wino ? 3 : 1) : 0;
+    pl->shape = shape; pl->TK = TK; pl->TR = wino ? 3 * TR : TR; pl->NT = NT;
     pl->lds_bytes = bestLds;
     return true;
 }

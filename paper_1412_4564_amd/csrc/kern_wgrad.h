@@ -25,6 +25,16 @@
 // written to need few vector instructions: per-lane quantities are precomputed once per block,
 // unit-dependent quantities are scalar.
 //
+// 3x3 filters at stride 1 (template flag WINO): the three row taps of a filter column are obtained for two
+// output rows at a time from four products instead of six (the transpose of the minimal-filtering identity
+// F(2,3) that the forward kernel uses: with d0..d3 the four input rows a pair of output rows reads and e0, e1
+// the two rows of dzdy,
+//   m0 = e0 (d0-d2),  m1 = (e0+e1)(d1+d2),  m2 = (e0-e1)(d2-d1),  m3 = e1 (d1-d3),
+//   dzdw[0] = m0 + (m1+m2)/2,  dzdw[1] = (m1-m2)/2,  dzdw[2] = (m1+m2)/2 - m3,
+// each m summed over all pairs of rows, columns and images on the matrix core).  A lane of the B operand
+// is then a (filter column, channel) pair r' = fj + 3c, a pixel of the GEMM a pair of output rows, there are
+// four sets of accumulators, and the combination above is applied once, when a tile is written.
+//
 // With a 1x1 view this kernel is a plain GEMM  OUT[k][c] = sum_p A[k][p] B[c][p]  with both
 // operands contiguous along the reduction, which is what the forward pass of a
 // fully-connected layer needs (Sec. 4.1, "fully connected" case): there p runs over the filter
@@ -60,6 +70,9 @@ struct WgradParams {
     // compute unit the one dispatched first gets more of the matrix core; with equal chunks it finishes
     // early and leaves the other to run alone, which uses the core less well.
     int n_first, w_first, w_later;
+    // WINO kernels: TIE is TI rounded up to a multiple of 4 (two pairs of rows per MFMA step) and SRP, CP, PCHP
+    // are even (8-byte LDS reads); tiles are counted in (filter column, channel) pairs, TR of them = 3*TR
+    // coefficients.
 };
 
 // Chunked schedule: blocks are numbered chunk-major (virtual block = tile + tiles*chunk) and the virtual
@@ -77,7 +90,7 @@ __device__ inline int wg_chunk_virtual_block(int b, int grid) { return grid % 8 
 constexpr int WGRAD_LOADER_WAVES = 4;
 
 // S1: vertical stride 1 (the slab rows of consecutive pixels are adjacent)
-template <int WK, int WR, int MK, int MR, bool S1, int WPE>
+template <int WK, int WR, int MK, int MR, bool S1, int WPE, bool WINO = false>
 __global__ __launch_bounds__(64 * (WK * WR + WGRAD_LOADER_WAVES), WPE) void wgrad_sk_kernel(WgradParams P, const float *__restrict__ x,
                                                                      const float *__restrict__ dzdy,
                                                                      const float *__restrict__ rbias,
@@ -88,13 +101,17 @@ __global__ __launch_bounds__(64 * (WK * WR + WGRAD_LOADER_WAVES), WPE) void wgra
     constexpr int LW = WGRAD_LOADER_WAVES;
     constexpr int NTB = NT + 64 * LW;          // threads of the block
     constexpr int TK = WK * MK * 32;
-    constexpr int TR = WR * MR * 32;
+    constexpr int TR = WR * MR * 32;           // lanes of the B operand per tile: coefficients, or (WINO) column-channel pairs
+    constexpr int NX = WINO ? 4 : 1;           // sets of accumulators
+    constexpr int TRO = WINO ? 3 * TR : TR;    // coefficients per tile
+    static_assert(!WINO || S1, "WINO: stride 1");
     constexpr int NSEGMAX = 2;                 // PCH <= 128
     const int PCH = P.PCH, PCHP = P.PCHP;
     const int NSEG = (PCH + 63) >> 6;
     const int YS = TK * PCHP;
     const int CP = P.CP, SRP = P.SRP;
-    const int T = P.Hf * P.Wf;
+    const int T = WINO ? P.Wf : P.Hf * P.Wf;   // B lanes per channel
+    const int RL = T * P.Cg;                   // B lanes in all
 
     extern __shared__ __align__(16) float lds[];
     float *ybuf = lds;                                        // [2][TK*PCHP]
@@ -168,7 +185,7 @@ __global__ __launch_bounds__(64 * (WK * WR + WGRAD_LOADER_WAVES), WPE) void wgra
         const int kt = t % P.KT;
         const int g = t / P.KT;
         const int r_lo = rt * TR;
-        const int r_hi = min(r_lo + TR, P.R);
+        const int r_hi = min(r_lo + TR, RL);
         const int c_lo = r_lo / T;
         l_nch = (r_hi - 1) / T - c_lo + 1;
         l_klim = min(P.Kg - kt * TK, TK);
@@ -221,7 +238,7 @@ __global__ __launch_bounds__(64 * (WK * WR + WGRAD_LOADER_WAVES), WPE) void wgra
     // ---- compute side ----------------------------------------------------------------------
     int roff[MR];
     int c_rt = 0, c_kt = 0, c_g = 0;
-    floatx16 acc[MK][MR];
+    floatx16 acc[NX][MK][MR];
     auto setup_compute = [&](int t) {
         const int rt = t % P.RT; t /= P.RT;
         const int kt = t % P.KT;
@@ -233,25 +250,83 @@ __global__ __launch_bounds__(64 * (WK * WR + WGRAD_LOADER_WAVES), WPE) void wgra
         for (int mr = 0; mr < MR; ++mr) {
             const int r = r_lo + (wr * MR + mr) * 32 + l32;
             int o = 0;
-            if (r < P.R) {
+            if (r < RL) {
                 const int c = r / T;
                 const int tap = r - c * T;
-                const int fj = tap / P.Hf;
-                const int fi = tap - fj * P.Hf;
+                const int fj = WINO ? tap : tap / P.Hf;
+                const int fi = WINO ? 0 : tap - fj * P.Hf;
                 o = (c - c_lo) * CP + fj * SRP + fi;
             }
-            roff[mr] = o + half * P.Sh;             // the upper half-wave takes the odd pixel of a step
+            // the upper half-wave takes the odd pixel (WINO: the odd pair of rows) of a step
+            roff[mr] = o + half * (WINO ? 2 : P.Sh);
         }
 #pragma unroll
-        for (int mk = 0; mk < MK; ++mk)
+        for (int x = 0; x < NX; ++x)
 #pragma unroll
-            for (int mr = 0; mr < MR; ++mr)
+            for (int mk = 0; mk < MK; ++mk)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) acc[mk][mr][v] = 0.f;
+                for (int mr = 0; mr < MR; ++mr)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) acc[x][mk][mr][v] = 0.f;
     };
     const int aoff = (wk * MK * 32 + l32) * PCHP + half;
     // all steps of the unit in buffer b: columns of the patch, two pixels per step
     auto compute = [&](int b) {
+        if constexpr (WINO) {
+            // One step = two pairs of output rows (one per half-wave).  Per filter tile an 8-byte read gives the
+            // pair's two rows of dzdy, per B tile two give the four input rows; every index below is in units of
+            // 8 bytes (all pitches are even).
+            const float2 *y2 = reinterpret_cast<const float2 *>(ybuf);
+            const float2 *x2 = reinterpret_cast<const float2 *>(xbuf);
+            int ya[MK], xr[MR];
+#pragma unroll
+            for (int mk = 0; mk < MK; ++mk) ya[mk] = ((b * YS + (wk * MK * 32 + mk * 32 + l32) * PCHP) >> 1) + half;
+#pragma unroll
+            for (int mr = 0; mr < MR; ++mr) xr[mr] = (b * P.XS + roff[mr]) >> 1;
+            const int steps_col = P.TIE >> 2;
+            const int xcol = (SRP - P.TIE) >> 1;          // from the end of a column to the start of the next
+            float2 e[2][MK], lo[2][MR], hi[2][MR];
+            auto fetch = [&](int slot) {
+#pragma unroll
+                for (int mk = 0; mk < MK; ++mk) { e[slot][mk] = y2[ya[mk]]; ya[mk] += 2; }
+#pragma unroll
+                for (int mr = 0; mr < MR; ++mr) { lo[slot][mr] = x2[xr[mr]]; hi[slot][mr] = x2[xr[mr] + 1]; xr[mr] += 2; }
+            };
+            auto step = [&](int slot) {
+                float av[4][MK], bv[4][MR];
+#pragma unroll
+                for (int mk = 0; mk < MK; ++mk) {
+                    const float2 q = e[slot][mk];
+                    av[0][mk] = q.x; av[1][mk] = q.x + q.y; av[2][mk] = q.x - q.y; av[3][mk] = q.y;
+                }
+#pragma unroll
+                for (int mr = 0; mr < MR; ++mr) {
+                    const float2 l = lo[slot][mr], h = hi[slot][mr];
+                    bv[0][mr] = l.x - h.x; bv[1][mr] = l.y + h.x; bv[2][mr] = h.x - l.y; bv[3][mr] = l.y - h.y;
+                }
+#pragma unroll
+                for (int x = 0; x < 4; ++x)
+#pragma unroll
+                    for (int mk = 0; mk < MK; ++mk)
+#pragma unroll
+                        for (int mr = 0; mr < MR; ++mr)
+                            acc[x][mk][mr] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[x][mk], bv[x][mr], acc[x][mk][mr], 0, 0, 0);
+            };
+            for (int dc = 0; dc < P.MC; ++dc) {
+                fetch(0);
+                int t = 0;
+                for (; t + 2 <= steps_col; t += 2) {
+                    fetch(1);
+                    step(0);
+                    if (t + 2 < steps_col) fetch(0);
+                    step(1);
+                }
+                if (t < steps_col) step(0);
+#pragma unroll
+                for (int mr = 0; mr < MR; ++mr) xr[mr] += xcol;
+            }
+            return;
+        }
         // running LDS indices (floats) of the lane's operands
         int ya[MK], xr[MR];
 #pragma unroll
@@ -266,7 +341,7 @@ __global__ __launch_bounds__(64 * (WK * WR + WGRAD_LOADER_WAVES), WPE) void wgra
             for (int mk = 0; mk < MK; ++mk)
 #pragma unroll
                 for (int mr = 0; mr < MR; ++mr)
-                    acc[mk][mr] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[mk], bq[mr], acc[mk][mr], 0, 0, 0);
+                    acc[0][mk][mr] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[mk], bq[mr], acc[0][mk][mr], 0, 0, 0);
         };
         for (int dc = 0; dc < P.MC; ++dc) {
             int t = 0;
@@ -300,8 +375,41 @@ __global__ __launch_bounds__(64 * (WK * WR + WGRAD_LOADER_WAVES), WPE) void wgra
         }
     };
     // lane holds coefficient r (lane&31) of each r tile and 16 filters of each filter tile
+    // WINO: the three row taps of the lane's (filter column, channel) pair from the four sums
+    auto taps = [&](int mk, int mr, int v, float *w3) {
+        const float m1 = acc[NX > 1 ? 1 : 0][mk][mr][v], m2 = acc[NX > 2 ? 2 : 0][mk][mr][v];
+        const float hs = 0.5f * (m1 + m2);
+        w3[0] = acc[0][mk][mr][v] + hs;
+        w3[1] = 0.5f * (m1 - m2);
+        w3[2] = hs - acc[NX > 3 ? 3 : 0][mk][mr][v];
+    };
     auto store_tile = [&]() {
         const int klim = min(P.Kg - c_kt * TK, TK);
+        if constexpr (WINO) {
+#pragma unroll
+            for (int mr = 0; mr < MR; ++mr) {
+                const int rl = c_rt * TR + (wr * MR + mr) * 32 + l32;
+                if (rl >= RL) continue;
+#pragma unroll
+                for (int mk = 0; mk < MK; ++mk)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const int kl = (wk * MK + mk) * 32 + (v >> 2) * 8 + half * 4 + (v & 3);
+                        if (kl < klim) {
+                            float w3[3];
+                            taps(mk, mr, v, w3);
+                            float *o = out + (size_t)(c_g * P.Kg + c_kt * TK + kl) * P.R + 3 * rl;
+#pragma unroll
+                            for (int fi = 0; fi < 3; ++fi) {
+                                float val = w3[fi] + (rbias ? rbias[3 * rl + fi] : 0.f);
+                                if (P.relu) val = fmaxf(val, 0.f);
+                                o[fi] = val;
+                            }
+                        }
+                    }
+            }
+            return;
+        }
 #pragma unroll
         for (int mr = 0; mr < MR; ++mr) {
             const int r = c_rt * TR + (wr * MR + mr) * 32 + l32;
@@ -313,7 +421,7 @@ __global__ __launch_bounds__(64 * (WK * WR + WGRAD_LOADER_WAVES), WPE) void wgra
                     for (int v = 0; v < 16; ++v) {
                         const int kl = (wk * MK + mk) * 32 + (v >> 2) * 8 + half * 4 + (v & 3);
                         if (kl < klim) {
-                            float val = acc[mk][mr][v] + rb;
+                            float val = acc[0][mk][mr][v] + rb;
                             if (P.relu) val = fmaxf(val, 0.f);
                             out[(size_t)(c_g * P.Kg + c_kt * TK + kl) * P.R + r] = val;
                         }
@@ -321,8 +429,9 @@ __global__ __launch_bounds__(64 * (WK * WR + WGRAD_LOADER_WAVES), WPE) void wgra
             }
         }
     };
+    // a piece of a shared tile, [filter][coefficient] (WINO: combined into coefficients first, which is linear)
     auto store_partial = [&](int slot) {
-        float *dst = part + (size_t)slot * (TK * TR);
+        float *dst = part + (size_t)slot * (TK * TRO);
 #pragma unroll
         for (int mr = 0; mr < MR; ++mr)
 #pragma unroll
@@ -330,7 +439,15 @@ __global__ __launch_bounds__(64 * (WK * WR + WGRAD_LOADER_WAVES), WPE) void wgra
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
                     const int kloc = (wk * MK + mk) * 32 + (v >> 2) * 8 + half * 4 + (v & 3);
-                    dst[kloc * TR + (wr * MR + mr) * 32 + l32] = acc[mk][mr][v];
+                    const int rl = (wr * MR + mr) * 32 + l32;
+                    if constexpr (WINO) {
+                        float w3[3];
+                        taps(mk, mr, v, w3);
+#pragma unroll
+                        for (int fi = 0; fi < 3; ++fi) dst[kloc * TRO + 3 * rl + fi] = w3[fi];
+                    } else {
+                        dst[kloc * TR + rl] = acc[0][mk][mr][v];
+                    }
                 }
     };
 

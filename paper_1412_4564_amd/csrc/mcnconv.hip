@@ -149,7 +149,8 @@ const PlanEntry *plans_for(const mcn_conv_desc *d, const Geom &g) {
                 e.bwd_ok = plan_view(v, &e.bwd[e.n_bwd++]);
             }
     }
-    e.wg_ok = on && plan_wgrad(forward_view(g), ncu, &e.wg);
+    e.wg_ok = on && ((wino_enabled() && plan_wgrad(forward_view(g), ncu, &e.wg, true)) ||
+                     plan_wgrad(forward_view(g), ncu, &e.wg));
     e.wgb_ok = on && bf && plan_wgrad_bf16(forward_view(g), ncu, &e.wgb);
     e.fc = on && is_fully_connected(g) && (int64_t)g.H * g.W * g.D < ((int64_t)1 << 30) &&
            plan_wgrad(fc_forward_view(g), ncu, &e.fc_fwd) && plan_igemm(fc_backward_data_view(g), ncu, &e.fc_bwd) &&
@@ -279,12 +280,12 @@ int launch_igemm(const IgemmPlan &pl, const float *in, const float *w, const flo
     }
 }
 
-template <int WK, int WR, int MK, int MR, bool S1>
+template <int WK, int WR, int MK, int MR, bool S1, bool WINO = false, int WPE = 4>
 int launch_wgrad_inst2(const WgradPlan &pl, const float *x, const float *dzdy, const float *rbias, float *out,
                        float *part, hipStream_t s, int relu) {
     WgradParams P = pl.P;
     P.relu = relu;
-    auto kern = wgrad_sk_kernel<WK, WR, MK, MR, S1, 4>;      // two blocks of 4 + 2 waves per compute unit
+    auto kern = wgrad_sk_kernel<WK, WR, MK, MR, S1, WPE, WINO>;      // WPE 4: two blocks of 4 + 4 waves per compute unit
     if (pl.lds_bytes > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
                                            (int)pl.lds_bytes);
@@ -296,7 +297,7 @@ int launch_wgrad_inst2(const WgradPlan &pl, const float *x, const float *dzdy, c
                        x, dzdy, rbias, out, part);
     int st = check_launch();
     if (st || P.nblocks < 2 || P.nchunks == 1) return st;
-    constexpr int TK = WK * MK * 32, TR = WR * MR * 32;
+    constexpr int TK = WK * MK * 32, TR = WR * MR * 32 * (WINO ? 3 : 1);     // coefficients per tile
     // at most nblocks - 1 tiles are shared, but which ones is cheaper to find per tile
     int fy = 2048 / pl.P.tiles;          // about 2048 blocks in all
     if (fy < 1) fy = 1;
@@ -322,6 +323,7 @@ int launch_wgrad(const WgradPlan &pl, const float *x, const float *dzdy, const f
         case WG_128x128: return launch_wgrad_inst<2, 2, 2, 2>(pl, x, dzdy, rbias, out, part, s, relu);
         case WG_64x192: return launch_wgrad_inst<2, 2, 1, 3>(pl, x, dzdy, rbias, out, part, s, relu);
         case WG_32x256: return launch_wgrad_inst<1, 4, 1, 2>(pl, x, dzdy, rbias, out, part, s, relu);
+        case WG_W128x128: return launch_wgrad_inst2<2, 4, 2, 1, true, true, 3>(pl, x, dzdy, rbias, out, part, s, relu);
         default: return MCN_BAD_ARG;
     }
 }
@@ -549,7 +551,7 @@ const char *mcn_conv_kernel_name(const mcn_conv_desc *desc, int op) {
             return e->fc ? "fc_gemm"
                          : e->bwd_ok ? (e->n_bwd && e->bwd[0].bf16 ? "igemm_bf16" : e->n_bwd && e->bwd[0].P.wino_Ho ? "igemm_f23" : "igemm")
                                      : "direct";
-        case MCN_OP_BACKWARD_FILTER: return e->fc ? "fc_gemm" : e->wgb_ok ? "wgrad_bf16" : e->wg_ok ? "wgrad_igemm" : "direct";
+        case MCN_OP_BACKWARD_FILTER: return e->fc ? "fc_gemm" : e->wgb_ok ? "wgrad_bf16" : e->wg_ok ? (e->wg.wino ? "wgrad_f23" : "wgrad_igemm") : "direct";
         case MCN_OP_BACKWARD_BIAS: return plan_bias(g).rows ? "reduce_rows" : "reduce2";
         default: return NULL;
     }

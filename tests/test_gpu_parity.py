@@ -149,6 +149,13 @@ ROW_PAIRS = [
     (28, 28, 64, 16, 64, 256, (1, 1, 1, 1)),
     (3, 3, 16, 1, 16, 40, (1, 1, 1, 1)),         # one pair and a single row
     (6, 7, 16, 2, 16, 36, (3, 2, 2, 3)),         # pads larger than the filter reach
+    # more than 64 filters per group: the filter derivative takes pairs of rows too
+    (15, 13, 16, 2, 16, 80, (1, 1, 1, 1)),       # odd number of output rows
+    (150, 6, 16, 2, 16, 72, (1, 1, 1, 1)),       # several row blocks
+    (6, 7, 16, 2, 16, 68, (3, 2, 2, 3)),
+    (3, 3, 16, 1, 16, 72, (1, 1, 1, 1)),
+    (9, 10, 20, 3, 20, 96, (0, 1, 1, 0)),        # channels that do not fill units of 8: the filter derivative alone
+    (30, 30, 160, 6, 80, 400, (1, 1, 1, 1)),     # two groups, several tiles in both directions, shared between blocks
 ]
 
 
@@ -160,8 +167,10 @@ def test_3x3_stride1_row_pair_kernel(case):
     # the input derivative is a 3x3 sum over dzdy with the layer's input channels as its filters: the row-pair
     # kernel takes it when those are more than 32 and the filters per group fill its units of 8 channels
     Kg = K // (D // Df)
+    fwd = "igemm_f23" if Df % 8 == 0 else "igemm"
     bwd = "igemm_f23" if Df > 32 and Kg % 8 == 0 else "igemm"
-    assert [B.mcn_conv_kernel_name(d, op) for op in range(2)] == ["igemm_f23", bwd]
+    wg = "wgrad_f23" if Kg > 64 else "wgrad_igemm"
+    assert [B.mcn_conv_kernel_name(d, op) for op in range(3)] == [fwd, bwd, wg]
     for with_bias in (True, False):
         U.assert_errors(U.run_layer_full(L, with_bias=with_bias, misalign=case % 2), label="row pairs %d" % case)
 
@@ -186,8 +195,8 @@ cases = [(16, 12, 16, 3, 16, 48, (1, 1, 1, 1)), (15, 13, 16, 2, 16, 40, (1, 1, 1
 for i, (H, W, D, N, Df, K, pad) in enumerate(cases):
     L = dict(H=H, W=W, D=D, N=N, Hf=3, Wf=3, Df=Df, K=K, stride=(1, 1), pad=pad, config=9, index=540 + i)
     d = B.make_desc(synth.x_shape(L), synth.w_shape(L), (1, 1), pad)
-    names = [B.mcn_conv_kernel_name(d, op) for op in range(2)]
-    assert names == ["igemm"] * 2, names
+    names = [B.mcn_conv_kernel_name(d, op) for op in range(3)]
+    assert names == ["igemm", "igemm", "wgrad_igemm"], names
     U.assert_errors(U.run_layer_full(L, with_bias=bool(i % 2)), label="one row per pixel %d" % i)
 print("ONE-ROW-OK")
 """
