@@ -417,7 +417,7 @@ inline bool plan_igemm(const ConvView &v, int n_cu, IgemmPlan *pl, bool bf16 = f
 namespace mcn {
 
 // WG_W*: the WINO kernels (filters x (filter column, channel) pairs)
-enum WgradShape { WG_128x128 = 0, WG_64x192 = 1, WG_32x256 = 2, WG_W128x128 = 3 };
+enum WgradShape { WG_128x128 = 0, WG_64x192 = 1, WG_32x256 = 2, WG_W128x128 = 3, WG_W64x192 = 4 };
 
 struct WgradPlan {
     int shape;
@@ -429,10 +429,11 @@ struct WgradPlan {
     bool wino;               // kern_wgrad.h, template flag WINO; TR then counts coefficients (3 per B lane)
 };
 
-// wino: the WINO kernel (3x3 filters at stride 1).  Its tiles are 128 filters wide and a unit's staging is paid for
-// by a third fewer MFMAs, so it is used with more than 64 filters per group only.
+// wino: the WINO kernels (3x3 filters at stride 1, more than 32 filters per group): tiles of 128 filters x 128
+// (filter column, channel) pairs on 8 computing waves, or, up to 64 filters per group, 64 x 192 on 12 computing
+// waves (one 32 x 32 tile with its four sets of accumulators each), which holds all of a 64-channel layer.
 inline bool plan_wgrad(const ConvView &v, int n_cu, WgradPlan *pl, bool wino = false) {
-    if (wino && (v.Hf != 3 || v.Wf != 3 || v.Sh != 1 || v.Sw != 1 || v.Ho < 2 || v.Kg <= 64)) return false;
+    if (wino && (v.Hf != 3 || v.Wf != 3 || v.Sh != 1 || v.Sw != 1 || v.Ho < 2 || v.Kg <= 32)) return false;
     const int T = wino ? v.Wf : v.Hf * v.Wf;             // B lanes per channel
     if ((int64_t)v.Hf * v.Wf * v.Cg >= ((int64_t)1 << 30)) return false;
     const int R = T * v.Cg;                              // B lanes in all
@@ -440,7 +441,8 @@ inline bool plan_wgrad(const ConvView &v, int n_cu, WgradPlan *pl, bool wino = f
     if ((double)v.H * v.W * v.Ctot * v.N * 4 >= 2147483647.0) return false;
     if ((double)v.Ho * v.Wo * v.Ktot * v.N * 4 >= 2147483647.0) return false;
     int shape, WK, WR, MK, MR;
-    if (wino) { shape = WG_W128x128; WK = 2; WR = 4; MK = 2; MR = 1; }
+    if (wino && v.Kg > 64) { shape = WG_W128x128; WK = 2; WR = 4; MK = 2; MR = 1; }
+    else if (wino) { shape = WG_W64x192; WK = 2; WR = 6; MK = 1; MR = 1; }     // 12 computing waves, one tile each per set
     else if (v.Kg > 64) { shape = WG_128x128; WK = 2; WR = 2; MK = 2; MR = 2; }
     else if (v.Kg > 32) { shape = WG_64x192; WK = 2; WR = 2; MK = 1; MR = 3; }
     else { shape = WG_32x256; WK = 1; WR = 4; MK = 1; MR = 2; }
@@ -488,7 +490,7 @@ inline bool plan_wgrad(const ConvView &v, int n_cu, WgradPlan *pl, bool wino = f
             if (lds > (int64_t)IGEMM_LDS_LIMIT) continue;
             int occ = (int)((int64_t)IGEMM_LDS_LIMIT / lds);
             if (occ > 2) occ = 2;   // the kernels are compiled for two waves per SIMD
-            if (NT == 512) occ = 1; // 8 computing + 4 fetching waves: one block per compute unit
+            if (NT >= 512) occ = 1; // 8 or 12 computing + 4 fetching waves: one block per compute unit
             // cost of a unit in matrix-core cycles: its MFMAs plus what staging it costs beside them
             // (fitted to measurements: a fixed part and a part per staged element, about twice as
             // much when only one block fits a compute unit and nothing else hides it)

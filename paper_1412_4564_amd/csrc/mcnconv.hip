@@ -324,6 +324,7 @@ int launch_wgrad(const WgradPlan &pl, const float *x, const float *dzdy, const f
         case WG_64x192: return launch_wgrad_inst<2, 2, 1, 3>(pl, x, dzdy, rbias, out, part, s, relu);
         case WG_32x256: return launch_wgrad_inst<1, 4, 1, 2>(pl, x, dzdy, rbias, out, part, s, relu);
         case WG_W128x128: return launch_wgrad_inst2<2, 4, 2, 1, true, true, 3>(pl, x, dzdy, rbias, out, part, s, relu);
+        case WG_W64x192: return launch_wgrad_inst2<2, 6, 1, 1, true, true, 4>(pl, x, dzdy, rbias, out, part, s, relu);
         default: return MCN_BAD_ARG;
     }
 }

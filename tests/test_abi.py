@@ -270,9 +270,7 @@ def test_planner_puts_every_workload_layer_on_the_matrix_core_kernels():
     for name in ("4a", "4b", "4c"):
         L = synth.LAYERS[name]
         d = B.make_desc(synth.x_shape(L), synth.w_shape(L), L["stride"], L["pad"])
-        # the filter derivative too where a group has more than 64 filters
-        wg = "wgrad_igemm" if name == "4a" else "wgrad_f23"
-        assert [B.mcn_conv_kernel_name(d, op) for op in range(3)] == ["igemm_f23", "igemm_f23", wg], name
+        assert [B.mcn_conv_kernel_name(d, op) for op in range(3)] == ["igemm_f23", "igemm_f23", "wgrad_f23"], name
     # bf16 operands: the deep layers on the bf16 kernels, the 3-channel first layers on the fp32 ones
     for name, expect in (("4b", ["igemm_bf16", "igemm_bf16", "wgrad_bf16"]), ("3a", ["igemm", "igemm", "wgrad_igemm"])):
         L = synth.LAYERS[name]

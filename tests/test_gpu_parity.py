@@ -149,7 +149,7 @@ ROW_PAIRS = [
     (28, 28, 64, 16, 64, 256, (1, 1, 1, 1)),
     (3, 3, 16, 1, 16, 40, (1, 1, 1, 1)),         # one pair and a single row
     (6, 7, 16, 2, 16, 36, (3, 2, 2, 3)),         # pads larger than the filter reach
-    # more than 64 filters per group: the filter derivative takes pairs of rows too
+    # more than 64 filters per group: wider tiles in the filter derivative
     (15, 13, 16, 2, 16, 80, (1, 1, 1, 1)),       # odd number of output rows
     (150, 6, 16, 2, 16, 72, (1, 1, 1, 1)),       # several row blocks
     (6, 7, 16, 2, 16, 68, (3, 2, 2, 3)),
@@ -169,7 +169,7 @@ def test_3x3_stride1_row_pair_kernel(case):
     Kg = K // (D // Df)
     fwd = "igemm_f23" if Df % 8 == 0 else "igemm"
     bwd = "igemm_f23" if Df > 32 and Kg % 8 == 0 else "igemm"
-    wg = "wgrad_f23" if Kg > 64 else "wgrad_igemm"
+    wg = "wgrad_f23"
     assert [B.mcn_conv_kernel_name(d, op) for op in range(3)] == [fwd, bwd, wg]
     for with_bias in (True, False):
         U.assert_errors(U.run_layer_full(L, with_bias=with_bias, misalign=case % 2), label="row pairs %d" % case)
@@ -183,6 +183,9 @@ def test_row_pair_kernel_only_where_it_applies():
         L = custom_layer(12, 12, Df, 2, Hf, Wf, Df, K, st, (1, 1, 1, 1), idx=520)
         d = B.make_desc(synth.x_shape(L), synth.w_shape(L), st, (1, 1, 1, 1))
         assert B.mcn_conv_kernel_name(d, 0) == "igemm", (Hf, Wf, Df, K, st)
+        # the filter derivative: 3x3 at stride 1 with more than 32 filters per group, whatever the channels
+        expect = "wgrad_f23" if (Hf, Wf, st) == (3, 3, (1, 1)) and K > 32 else "wgrad_igemm"
+        assert B.mcn_conv_kernel_name(d, 2) == expect, (Hf, Wf, Df, K, st)
 
 
 _ONE_ROW_SCRIPT = r"""
