@@ -175,6 +175,24 @@ def test_3x3_stride1_row_pair_kernel(case):
         U.assert_errors(U.run_layer_full(L, with_bias=with_bias, misalign=case % 2), label="row pairs %d" % case)
 
 
+def test_row_pair_kernels_random_geometries():
+    """3x3 filters at stride 1 at random plane sizes (odd and even, down to 2 rows), pads up to 3 per side, one to
+    three groups, ragged filter and channel counts: whichever of the three passes qualify run on the row-pair
+    kernels, the rest on the others."""
+    rng = np.random.default_rng(161803)
+    for t in range(20):
+        g = int(rng.choice([1, 1, 2, 3]))
+        Df = int(rng.choice([8, 16, 20, 24, 40, 48, 72, 104]))
+        Kg = int(rng.choice([33, 40, 56, 64, 65, 72, 96, 130, 136, 200]))
+        pad = [int(v) for v in rng.integers(0, 4, size=4)]
+        H = int(rng.integers(max(1, 3 - pad[0] - pad[1]), 45))
+        W = int(rng.integers(max(1, 3 - pad[2] - pad[3]), 30))
+        L = custom_layer(H, W, g * Df, int(rng.integers(1, 6)), 3, 3, Df, g * Kg, (1, 1), pad, idx=560 + t)
+        d = B.make_desc(synth.x_shape(L), synth.w_shape(L), (1, 1), pad)
+        print("random row-pair case", t, L, [B.mcn_conv_kernel_name(d, op) for op in range(3)], flush=True)
+        U.assert_errors(U.run_layer_full(L, with_bias=bool(t % 2), seed=t, misalign=t % 4), label="random row pairs %d %r" % (t, L))
+
+
 def test_row_pair_kernel_only_where_it_applies():
     """Other filter sizes, strides, few filters per group or channels that do not fill its units of 8 keep the
     kernels that compute one output row per pixel."""
