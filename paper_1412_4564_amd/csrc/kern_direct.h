@@ -164,6 +164,38 @@ __global__ __launch_bounds__(256) void bias_partial_kernel(const float *__restri
     if (threadIdx.x == 0) part[(size_t)k * S + s] = (red[0] + red[1]) + (red[2] + red[3]);
 }
 
+// The same with 16-byte loads, four of them in flight per thread before the first addition: for planes of a
+// multiple of 4 samples in an array aligned to 16 bytes (then every (n, k) plane and every chunk is aligned).
+// The order of the additions differs from the kernel above but is as fixed.
+__global__ __launch_bounds__(256) void bias_partial_v4_kernel(const float *__restrict__ dzdy, float *__restrict__ part,
+                                                              int HoWo, int K, int N, int chunks, int S) {
+    const int k = blockIdx.x, s = blockIdx.y;
+    const int units = N * chunks;
+    float4 a0 = {0.f, 0.f, 0.f, 0.f}, a1 = a0, a2 = a0, a3 = a0;
+    for (int u = s; u < units; u += S) {
+        const int n = u / chunks, c = u - n * chunks;
+        const float4 *p = reinterpret_cast<const float4 *>(dzdy + ((size_t)n * K + k) * HoWo);
+        const int lo = c * (BIAS_CHUNK / 4);
+        const int hi = min(lo + BIAS_CHUNK / 4, HoWo / 4);
+        const int e = lo + threadIdx.x;
+        const float4 z = {0.f, 0.f, 0.f, 0.f};
+        static_assert(BIAS_CHUNK == 4 * 4 * 256, "four 16-byte loads per thread and chunk");
+        const float4 v0 = e < hi ? p[e] : z, v1 = e + 256 < hi ? p[e + 256] : z;
+        const float4 v2 = e + 512 < hi ? p[e + 512] : z, v3 = e + 768 < hi ? p[e + 768] : z;
+        a0.x += v0.x; a0.y += v0.y; a0.z += v0.z; a0.w += v0.w;
+        a1.x += v1.x; a1.y += v1.y; a1.z += v1.z; a1.w += v1.w;
+        a2.x += v2.x; a2.y += v2.y; a2.z += v2.z; a2.w += v2.w;
+        a3.x += v3.x; a3.y += v3.y; a3.z += v3.z; a3.w += v3.w;
+    }
+    float acc = ((a0.x + a0.y) + (a0.z + a0.w)) + ((a1.x + a1.y) + (a1.z + a1.w)) +
+                (((a2.x + a2.y) + (a2.z + a2.w)) + ((a3.x + a3.y) + (a3.z + a3.w)));
+    __shared__ float red[4];
+    acc = wave_sum(acc);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) part[(size_t)k * S + s] = (red[0] + red[1]) + (red[2] + red[3]);
+}
+
 // ---- ReLU mask fused with the bias derivative ------------------------------------------------------
 // Sec. 6.4.1 of the manual: through y = max(0, p) the derivative is dz/dp = [p > 0] dz/dy, and
 // y > 0 exactly where p > 0.  One pass reads y and dzdy, writes dzdp = [y > 0] * dzdy (the derivative

@@ -485,6 +485,8 @@ int run_backward_bias(int plane, int K, int N, const float *dzdy, float *dzdb, v
     }
     if (y)
         hipLaunchKernelGGL(relu_bias_partial_kernel, dim3(K, p.S), dim3(256), 0, s, y, dzdy, dzdp, part, plane, K, N, p.chunks, p.S);
+    else if (plane % 4 == 0 && plane >= 1024 && ((uintptr_t)dzdy & 15) == 0)     // planes that fill a block's 16-byte loads
+        hipLaunchKernelGGL(bias_partial_v4_kernel, dim3(K, p.S), dim3(256), 0, s, dzdy, part, plane, K, N, p.chunks, p.S);
     else
         hipLaunchKernelGGL(bias_partial_kernel, dim3(K, p.S), dim3(256), 0, s, dzdy, part, plane, K, N, p.chunks, p.S);
     st = check_launch();
