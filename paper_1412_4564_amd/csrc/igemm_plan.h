@@ -286,8 +286,17 @@ inline bool plan_igemm_kind(const ConvView &v, int n_cu, IgemmPlan *pl, bool bf1
         const double red_waste = (double)NCG * uc.NTR * uc.NS * (bf16 ? BF_DC : 2) / ((double)v.Cg * T);
         // when the input streams from memory, short slab rows waste most of every 128-byte line they touch
         // results are stored in column runs of TI samples: short runs are partial memory lines
-        const double score = mfma_waste * red_waste * (1.0 + 0.05 * (double)CP / TQ) *
-                             (input_streams ? 1.0 + 4.0 / (double)SR : 1.0) * (1.0 + 2.0 / (double)TI);
+        double score = mfma_waste * red_waste * (1.0 + 0.05 * (double)CP / TQ) *
+                       (input_streams ? 1.0 + 4.0 / (double)SR : 1.0) * (1.0 + 2.0 / (double)TI);
+        if (wino) {
+            // The row-pair kernels issue fewer MFMAs per staged byte and per stored line, and what was measured on
+            // them weighs differently: short slab rows cost little, column runs of results (2*TI samples) that are
+            // whole 128-byte lines are worth some 5 % (layer 4a: 32-row runs 0.74 ms, 112-row runs 0.78, 28-row 0.80).
+            const double run_bytes = 8.0 * TI;
+            const bool whole_lines = (8 * TI) % 128 == 0 && ((int64_t)v.OH * 4) % 128 == 0;
+            score = mfma_waste * red_waste * (1.0 + 0.05 * (double)CP / TQ) *
+                    (input_streams ? 1.0 + 1.0 / (double)SR : 1.0) * (1.0 + (whole_lines ? 0.0 : 0.25 * 128.0 / run_bytes));
+        }
         if (score < best_score) { best_score = score; bestTI = TI; bestSC = SC; best_uc = uc; }
     }
     if (!bestTI) return false;
