@@ -377,13 +377,13 @@ inline bool plan_igemm_kind(const ConvView &v, int n_cu, IgemmPlan *pl, bool bf1
     return true;
 }
 
-// 3x3 filters at stride 1 whose channels divide into units of 8: the view of pairs of output rows that the
+// 3x3 filters at stride 1 with at least 16 channels per group: the view of pairs of output rows that the
 // WINO kernels compute (kern_igemm.h).  Its rows are pairs, its four "taps" per column the four input rows a
 // pair reads; results go to rows oi0 + osi * (2 * pair + {0, 1}) of the output array.
 inline bool wino_view(const ConvView &v, ConvView *out) {
     if (v.Hf != 3 || v.Wf != 3 || v.Sh != 1 || v.Sw != 1 || v.mD || v.pack_mode > 1) return false;
     if (v.HfA != 3 || v.WfA != 3 || (v.pack_mode == 1 && (v.pSh != 1 || v.pSw != 1))) return false;
-    if (v.Cg % IGEMM_WINO.DC != 0 || v.Cg < 2 * IGEMM_WINO.DC || v.Ho < 2) return false;
+    if (v.Cg < 2 * IGEMM_WINO.DC || v.Ho < 2) return false;      // channels are padded to units of 8 (zero weights, slab reads as zero)
     if (v.Kg <= 32) return false;      // the WINO tiles are 64 or 128 filters wide; narrower layers keep the 32-filter tiles
     ConvView p = v;
     p.Hf = 4; p.Sh = 2; p.Ho = (v.Ho + 1) / 2; p.osi = 2 * v.osi;

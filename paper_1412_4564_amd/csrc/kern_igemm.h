@@ -444,7 +444,7 @@ __global__ __launch_bounds__(64 * (WK * WP + LW), WPE) void igemm_sk_kernel(Igem
             for (int d = 0; d < DC; ++d) {
                 const int c = c0 + d;
                 // channels past the group's last one read as zero (their weights are zero too)
-                const buffer_rsrc rs = (FIXED || c < P.Cg) ? xrs : zrs;
+                const buffer_rsrc rs = ((FIXED && !WINO) || c < P.Cg) ? xrs : zrs;
                 load_to_lds_b32(lds_address(xb + d * CP + e0), go, rs, (unsigned)c * (unsigned)HW * 4u);
             }
         }

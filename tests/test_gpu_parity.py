@@ -154,7 +154,8 @@ ROW_PAIRS = [
     (150, 6, 16, 2, 16, 72, (1, 1, 1, 1)),       # several row blocks
     (6, 7, 16, 2, 16, 68, (3, 2, 2, 3)),
     (3, 3, 16, 1, 16, 72, (1, 1, 1, 1)),
-    (9, 10, 20, 3, 20, 96, (0, 1, 1, 0)),        # channels that do not fill units of 8: the filter derivative alone
+    (9, 10, 20, 3, 20, 96, (0, 1, 1, 0)),        # channels that do not fill units of 8
+    (10, 9, 50, 2, 50, 75, (1, 1, 0, 0)),        # neither do the filters, which are the input derivative's channels
     (30, 30, 160, 6, 80, 400, (1, 1, 1, 1)),     # two groups, several tiles in both directions, shared between blocks
 ]
 
@@ -165,10 +166,10 @@ def test_3x3_stride1_row_pair_kernel(case):
     L = custom_layer(H, W, D, N, 3, 3, Df, K, (1, 1), pad, idx=500 + case)
     d = B.make_desc(synth.x_shape(L), synth.w_shape(L), (1, 1), pad)
     # the input derivative is a 3x3 sum over dzdy with the layer's input channels as its filters: the row-pair
-    # kernel takes it when those are more than 32 and the filters per group fill its units of 8 channels
+    # kernel takes it when those are more than 32
     Kg = K // (D // Df)
-    fwd = "igemm_f23" if Df % 8 == 0 else "igemm"
-    bwd = "igemm_f23" if Df > 32 and Kg % 8 == 0 else "igemm"
+    fwd = "igemm_f23"
+    bwd = "igemm_f23" if Df > 32 else "igemm"
     wg = "wgrad_f23"
     assert [B.mcn_conv_kernel_name(d, op) for op in range(3)] == [fwd, bwd, wg]
     for with_bias in (True, False):
@@ -194,10 +195,10 @@ def test_row_pair_kernels_random_geometries():
 
 
 def test_row_pair_kernel_only_where_it_applies():
-    """Other filter sizes, strides, few filters per group or channels that do not fill its units of 8 keep the
-    kernels that compute one output row per pixel."""
+    """Other filter sizes, strides, few filters or few channels per group keep the kernels that compute one output
+    row per pixel."""
     for (Hf, Wf, Df, K, st) in ((3, 3, 16, 32, (1, 1)), (3, 3, 12, 64, (1, 1)), (3, 3, 16, 64, (2, 1)), (3, 3, 16, 64, (1, 2)),
-                                (4, 3, 16, 64, (1, 1)), (3, 5, 16, 64, (1, 1)), (3, 3, 8, 64, (1, 1))):
+                                (4, 3, 16, 64, (1, 1)), (3, 5, 16, 64, (1, 1)), (3, 3, 8, 64, (1, 1))):      # 12, 8: under 16 channels
         L = custom_layer(12, 12, Df, 2, Hf, Wf, Df, K, st, (1, 1, 1, 1), idx=520)
         d = B.make_desc(synth.x_shape(L), synth.w_shape(L), st, (1, 1, 1, 1))
         assert B.mcn_conv_kernel_name(d, 0) == "igemm", (Hf, Wf, Df, K, st)
