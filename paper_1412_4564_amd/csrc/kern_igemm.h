@@ -312,6 +312,37 @@ __global__ __launch_bounds__(256) void igemm_pack_weights_kernel(const float *__
     packed[p] = v;
 }
 
+// The same packing for the WINO kernels (PackParams::wino, modes 0 and 1), four results per thread: a thread
+// reads the three row taps of one (filter, channel, filter column) once and writes their four combinations,
+// where igemm_pack_weights_kernel would read them once per combination.  One unit takes exactly NS*2*TK floats
+// (no pitch padding: NS = 48).  Thread index: kk fastest, then h, fj, channel pair, unit, filter tile, group.
+__global__ __launch_bounds__(256) void igemm_pack_wino_kernel(const float *__restrict__ w, float *__restrict__ packed,
+                                                              PackParams Q) {
+    int p = blockIdx.x * 256 + threadIdx.x;
+    if (p >= Q.total / 4) return;
+    const int kk = p % Q.TK; p /= Q.TK;
+    const int h = p & 1; p >>= 1;
+    const int fj = p % 3; p /= 3;
+    const int dp = p % (Q.DC / 2); p /= (Q.DC / 2);
+    const int uu = p % Q.NU; p /= Q.NU;
+    const int kt = p % Q.KT;
+    const int g = p / Q.KT;
+    const int k = kt * Q.TK + kk;
+    const int c = uu * Q.DC + 2 * dp + h;
+    float g0 = 0.f, g1 = 0.f, g2 = 0.f;
+    if (k < Q.Kg && c < Q.Cg) {
+        const float *src = Q.mode == 0 ? w + 3 * (fj + 3 * (c + (size_t)Q.DfA * (g * Q.Kg + k)))
+                                       : w + 3 * ((2 - fj) + 3 * (k + (size_t)Q.DfA * (g * Q.Cg + c)));
+        g0 = src[0]; g1 = src[1]; g2 = src[2];
+        if (Q.mode != 0) { const float t = g0; g0 = g2; g2 = t; }      // input derivative: the flipped filter
+    }
+    float *dst = packed + ((size_t)((g * Q.KT + kt) * Q.NU + uu) * Q.NS + (size_t)(dp * 3 + fj) * 4) * 2 * Q.TK + h * Q.TK + kk;
+    dst[0] = g0;
+    dst[2 * Q.TK] = 0.5f * (g0 + g1 + g2);
+    dst[4 * Q.TK] = 0.5f * (g0 - g1 + g2);
+    dst[6 * Q.TK] = g2;
+}
+
 // ---- main kernel -----------------------------------------------------------------------
 // WK x WP waves; each wave owns MK x MP tiles of 32 filters x 32 pixels.
 // HF, WF > 0: filter size and DCF channels per unit known at compile time (pair_mode 0, one tap

@@ -266,7 +266,10 @@ int launch_igemm(const IgemmPlan &pl, const float *in, const float *w, const flo
             default: return MCN_BAD_ARG;
         }
     }
-    hipLaunchKernelGGL(igemm_pack_weights_kernel, dim3(cdiv(pl.Q.total, 256)), dim3(256), 0, s, w, packed, pl.Q);
+    if (pl.Q.wino && pl.P.WSZ == pl.Q.NS * 2 * pl.Q.TK)
+        hipLaunchKernelGGL(igemm_pack_wino_kernel, dim3(cdiv(pl.Q.total / 4, 256)), dim3(256), 0, s, w, packed, pl.Q);
+    else
+        hipLaunchKernelGGL(igemm_pack_weights_kernel, dim3(cdiv(pl.Q.total, 256)), dim3(256), 0, s, w, packed, pl.Q);
     int st = check_launch();
     if (st) return st;
     switch (pl.shape) {
