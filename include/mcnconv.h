@@ -81,7 +81,8 @@ typedef enum mcn_status {
     MCN_PAD_TOO_LARGE = 8        /* pooling: a pad exceeds window - 1 (Sec. 5.2.1)       */
 } mcn_status;
 
-enum { MCN_OP_FORWARD = 0, MCN_OP_BACKWARD_DATA = 1, MCN_OP_BACKWARD_FILTER = 2, MCN_OP_BACKWARD_BIAS = 3 };
+enum { MCN_OP_FORWARD = 0, MCN_OP_BACKWARD_DATA = 1, MCN_OP_BACKWARD_FILTER = 2, MCN_OP_BACKWARD_BIAS = 3,
+       MCN_OP_BACKWARD_FILTER_BIAS = 4 /* convolution block only: mcn_conv_backward_filter_bias */ };
 
 /* Sec. 4.1 "Output size" (derived in Sec. 5.2): writes H'' and W''.
  * Validates the whole descriptor; Ho / Wo may be NULL.  Host only. */
@@ -109,6 +110,15 @@ int mcn_conv_backward_data(const mcn_conv_desc *desc, const float *w, const floa
  * dzdw = d<dzdy, y>/dw.  Writes all of dzdw. */
 int mcn_conv_backward_filter(const mcn_conv_desc *desc, const float *x, const float *dzdy,
                              float *dzdw, void *ws, size_t ws_bytes, void *stream);
+
+/* Sec. 2.3.2: the block's backward mode returns dzdw and dzdb together.  Both of the two
+ * results above in one call, same arguments and meaning; workspace that of
+ * MCN_OP_BACKWARD_FILTER_BIAS.  Where the filter derivative's kernel can sum dzdy on
+ * the way (3x3 filters at stride 1, 33 to 64 filters per group, arrays that stream
+ * from memory; mcn_conv_kernel_name says "wgrad_f23+bias") dzdy is read once for
+ * both; otherwise the two passes run one after the other ("two passes"). */
+int mcn_conv_backward_filter_bias(const mcn_conv_desc *desc, const float *x, const float *dzdy,
+                                  float *dzdw, float *dzdb, void *ws, size_t ws_bytes, void *stream);
 
 /* y is affine in b with coefficient one, so
  * dzdb[k] = sum_{i'',j'',n} dzdy[i'',j'',k,n].  Writes K values. */

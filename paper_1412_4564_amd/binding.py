@@ -22,11 +22,13 @@ MCN_OK, MCN_BAD_ARG, MCN_BAD_GROUPS, MCN_FILTER_TOO_LARGE = 0, 1, 2, 3
 MCN_WORKSPACE_TOO_SMALL, MCN_UNSUPPORTED, MCN_HIP_ERROR, MCN_CROP_TOO_LARGE, MCN_PAD_TOO_LARGE = 4, 5, 6, 7, 8
 MCN_POOL_MAX, MCN_POOL_AVG = 0, 1
 MCN_OP_FORWARD, MCN_OP_BACKWARD_DATA, MCN_OP_BACKWARD_FILTER, MCN_OP_BACKWARD_BIAS = 0, 1, 2, 3
+MCN_OP_BACKWARD_FILTER_BIAS = 4
 MCN_PREC_FP32, MCN_PREC_BF16 = 0, 1
 
 EXPORTS = (
     "mcn_conv_output_size", "mcn_conv_workspace_size", "mcn_conv_forward", "mcn_conv_backward_data",
-    "mcn_conv_backward_filter", "mcn_conv_backward_bias", "mcn_status_string", "mcn_last_hip_error",
+    "mcn_conv_backward_filter", "mcn_conv_backward_bias", "mcn_conv_backward_filter_bias", "mcn_status_string",
+    "mcn_last_hip_error",
     "mcn_conv_kernel_name", "mcn_conv_relu_forward", "mcn_conv_relu_backward_bias",
     "mcn_convt_output_size", "mcn_convt_workspace_size", "mcn_convt_forward", "mcn_convt_backward_data",
     "mcn_convt_backward_filter", "mcn_convt_backward_bias", "mcn_convt_kernel_name",
@@ -85,6 +87,8 @@ def lib():
         L.mcn_conv_backward_data.argtypes = [D, P, P, P, P, SZ, P]
         L.mcn_conv_backward_filter.argtypes = [D, P, P, P, P, SZ, P]
         L.mcn_conv_backward_bias.argtypes = [D, P, P, P, SZ, P]
+        L.mcn_conv_backward_filter_bias.argtypes = [D, P, P, P, P, P, SZ, P]
+        L.mcn_conv_backward_filter_bias.restype = ctypes.c_int
         L.mcn_status_string.argtypes = [ctypes.c_int]
         L.mcn_status_string.restype = ctypes.c_char_p
         L.mcn_last_hip_error.restype = ctypes.c_int
@@ -162,6 +166,10 @@ def mcn_conv_backward_data(desc, w, dzdy, dzdx, ws, ws_bytes, stream):
 
 def mcn_conv_backward_filter(desc, x, dzdy, dzdw, ws, ws_bytes, stream):
     return lib().mcn_conv_backward_filter(ctypes.byref(desc), x, dzdy, dzdw, ws, ws_bytes, stream)
+
+
+def mcn_conv_backward_filter_bias(desc, x, dzdy, dzdw, dzdb, ws, ws_bytes, stream):
+    return lib().mcn_conv_backward_filter_bias(ctypes.byref(desc), x, dzdy, dzdw, dzdb, ws, ws_bytes, stream)
 
 
 def mcn_conv_backward_bias(desc, dzdy, dzdb, ws, ws_bytes, stream):
@@ -343,6 +351,24 @@ def conv_backward_filter(x, wshape, dzdy, stride=(1, 1), pad=(0, 0, 0, 0), preci
     if st:
         raise McnError(st, "mcn_conv_backward_filter")
     return dzdw
+
+
+def conv_backward_filter_bias(x, wshape, dzdy, stride=(1, 1), pad=(0, 0, 0, 0), precision=MCN_PREC_FP32, out=None, workspace=None):
+    """(dzdw, dzdb) in one call; out = (dzdw, dzdb) to write into existing tensors."""
+    import torch
+    _check(x, None, "x")
+    desc = make_desc(x.shape, wshape, stride, pad, precision)
+    ho, wo = mcn_conv_output_size(desc)
+    _check(dzdy, (x.shape[0], wshape[0], wo, ho), "dzdy")
+    dzdw = out[0] if out is not None else torch.empty(tuple(wshape), dtype=torch.float32, device=x.device)
+    dzdb = out[1] if out is not None else torch.empty((wshape[0],), dtype=torch.float32, device=x.device)
+    _check(dzdw, tuple(wshape), "out[0]")
+    _check(dzdb, (wshape[0],), "out[1]")
+    wsp, wsn = (workspace or _default_ws).get(mcn_conv_workspace_size(desc, MCN_OP_BACKWARD_FILTER_BIAS), x.device)
+    st = mcn_conv_backward_filter_bias(desc, x.data_ptr(), dzdy.data_ptr(), dzdw.data_ptr(), dzdb.data_ptr(), wsp, wsn, _stream())
+    if st:
+        raise McnError(st, "mcn_conv_backward_filter_bias")
+    return dzdw, dzdb
 
 
 def conv_backward_bias(xshape, wshape, dzdy, stride=(1, 1), pad=(0, 0, 0, 0), out=None, workspace=None):

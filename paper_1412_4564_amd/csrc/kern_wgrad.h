@@ -90,12 +90,19 @@ __device__ inline int wg_chunk_virtual_block(int b, int grid) { return grid % 8 
 constexpr int WGRAD_LOADER_WAVES = 4;
 
 // S1: vertical stride 1 (the slab rows of consecutive pixels are adjacent)
-template <int WK, int WR, int MK, int MR, bool S1, int WPE, bool WINO = false>
+// BIAS (WINO kernels, chunked schedule): the bias derivative of Sec. 4.1's y = x*w + b, dzdb[k] = sum of dzdy[.,.,k,.],
+// falls out of this kernel's operands: the second A operand of a step is e0 + e1, the sum of the two rows of dzdy
+// that a lane holds, so the waves of the first B tile of the first coefficient tile add it up per filter (one
+// vector addition per step) and leave one partial sum per filter and block in `bpart` ([2*block][TK], beside the
+// partial tiles); wgrad_bias_final_kernel adds the blocks' sums in block order.
+template <int WK, int WR, int MK, int MR, bool S1, int WPE, bool WINO = false, bool BIAS = false>
 __global__ __launch_bounds__(64 * (WK * WR + WGRAD_LOADER_WAVES), WPE) void wgrad_sk_kernel(WgradParams P, const float *__restrict__ x,
                                                                      const float *__restrict__ dzdy,
                                                                      const float *__restrict__ rbias,
                                                                      float *__restrict__ out,
-                                                                     float *__restrict__ part) {
+                                                                     float *__restrict__ part,
+                                                                     float *__restrict__ bpart = nullptr) {
+    static_assert(!BIAS || WINO, "the bias derivative is a by-product of the WINO kernels only");
     constexpr int NT = 64 * WK * WR;           // computing threads
     constexpr int NW = WK * WR;
     constexpr int LW = WGRAD_LOADER_WAVES;
@@ -239,11 +246,18 @@ __global__ __launch_bounds__(64 * (WK * WR + WGRAD_LOADER_WAVES), WPE) void wgra
     int roff[MR];
     int c_rt = 0, c_kt = 0, c_g = 0;
     floatx16 acc[NX][MK][MR];
+    float bsum[MK];          // BIAS: this lane's sum of dzdy over the pairs of rows it has held, per filter tile
+    bool bias_on = false;    // BIAS: this wave sums (first B tile of the block, first coefficient tile)
+    float bias_w = 0.f;      // 1 in those waves, 0 in the others
     auto setup_compute = [&](int t) {
         const int rt = t % P.RT; t /= P.RT;
         const int kt = t % P.KT;
         const int g = t / P.KT;
         c_rt = rt; c_kt = kt; c_g = g;
+        bias_on = BIAS && wr == 0 && rt == 0;
+        bias_w = bias_on ? 1.f : 0.f;
+#pragma unroll
+        for (int mk = 0; mk < MK; ++mk) bsum[mk] = 0.f;
         const int r_lo = rt * TR;
         const int c_lo = r_lo / T;
 #pragma unroll
@@ -298,6 +312,7 @@ __global__ __launch_bounds__(64 * (WK * WR + WGRAD_LOADER_WAVES), WPE) void wgra
                 for (int mk = 0; mk < MK; ++mk) {
                     const float2 q = e[slot][mk];
                     av[0][mk] = q.x; av[1][mk] = q.x + q.y; av[2][mk] = q.x - q.y; av[3][mk] = q.y;
+                    if constexpr (BIAS) bsum[mk] = fmaf(bias_w, av[1][mk], bsum[mk]);      // no branch in the MFMA loop
                 }
 #pragma unroll
                 for (int mr = 0; mr < MR; ++mr) {
@@ -429,6 +444,17 @@ __global__ __launch_bounds__(64 * (WK * WR + WGRAD_LOADER_WAVES), WPE) void wgra
             }
         }
     };
+    // BIAS: the two half-waves hold different pairs of rows of the same filters
+    auto store_bias = [&](int slot) {
+        if constexpr (BIAS) {
+            if (!bias_on) return;
+#pragma unroll
+            for (int mk = 0; mk < MK; ++mk) {
+                const float v = bsum[mk] + __shfl_xor(bsum[mk], 32);
+                if (half == 0) bpart[(size_t)slot * TK + (wk * MK + mk) * 32 + l32] = v;
+            }
+        }
+    };
     // a piece of a shared tile, [filter][coefficient] (WINO: combined into coefficients first, which is linear)
     auto store_partial = [&](int slot) {
         float *dst = part + (size_t)slot * (TK * TRO);
@@ -486,6 +512,7 @@ __global__ __launch_bounds__(64 * (WK * WR + WGRAD_LOADER_WAVES), WPE) void wgra
         if (uu_c + 1 == NU || last) {
             if (whole) store_tile();
             else store_partial(2 * vb + (first_segment ? 0 : 1));
+            store_bias(2 * vb + (first_segment ? 0 : 1));
             first_segment = false;
             if (!last) {
                 ++t_c; uu_c = 0;
@@ -580,6 +607,25 @@ __global__ __launch_bounds__(512) void wgrad_chunk_fixup_kernel(WgradParams P, c
         }
         __syncthreads();
     }
+}
+
+// BIAS: dzdb[k] = the sum over the chunks of the partial sums that the blocks of the first coefficient tile
+// (rt = 0) of k's filter tile left in bpart.  One block per (group, filter tile); thread (k, j) adds the chunks
+// i = j, j + 8, ... (eight independent streams of loads), the eight sums are then added in a fixed order.
+template <int TK>
+__global__ __launch_bounds__(TK * 8) void wgrad_bias_final_kernel(WgradParams P, const float *__restrict__ bpart,
+                                                                  float *__restrict__ dzdb) {
+    const int kt = blockIdx.x % P.KT, g = blockIdx.x / P.KT;
+    const int t0 = P.RT * (kt + P.KT * g);
+    const int k = threadIdx.x % TK, j = threadIdx.x / TK;
+    __shared__ float red[8][TK];
+    float acc = 0.f;
+    for (int i = j; i < P.nchunks; i += 8) acc += bpart[(size_t)(2 * (t0 + P.tiles * i)) * TK + k];
+    red[j][k] = acc;
+    __syncthreads();
+    if (j == 0 && kt * TK + k < P.Kg)
+        dzdb[g * P.Kg + kt * TK + k] = ((red[0][k] + red[1][k]) + (red[2][k] + red[3][k])) +
+                                       ((red[4][k] + red[5][k]) + (red[6][k] + red[7][k]));
 }
 
 }  // namespace mcn

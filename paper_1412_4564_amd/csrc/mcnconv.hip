@@ -283,12 +283,15 @@ int launch_igemm(const IgemmPlan &pl, const float *in, const float *w, const flo
     }
 }
 
-template <int WK, int WR, int MK, int MR, bool S1, bool WINO = false, int WPE = 4>
+// dzdb != NULL (BIAS instantiations only): the bias derivative is computed on the way (kern_wgrad.h); its partial
+// sums follow the partial tiles in the workspace
+template <int WK, int WR, int MK, int MR, bool S1, bool WINO = false, int WPE = 4, bool BIAS = false>
 int launch_wgrad_inst2(const WgradPlan &pl, const float *x, const float *dzdy, const float *rbias, float *out,
-                       float *part, hipStream_t s, int relu) {
+                       float *part, hipStream_t s, int relu, float *dzdb = nullptr) {
     WgradParams P = pl.P;
     P.relu = relu;
-    auto kern = wgrad_sk_kernel<WK, WR, MK, MR, S1, WPE, WINO>;      // WPE 4: two blocks of 4 + 4 waves per compute unit
+    auto kern = wgrad_sk_kernel<WK, WR, MK, MR, S1, WPE, WINO, BIAS>;      // WPE 4: two blocks of 4 + 4 waves per compute unit
+    float *bpart = part + pl.partial_floats;
     if (pl.lds_bytes > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
                                            (int)pl.lds_bytes);
@@ -297,8 +300,13 @@ int launch_wgrad_inst2(const WgradPlan &pl, const float *x, const float *dzdy, c
     const bool chunked = P.nchunks > 0;
     hipLaunchKernelGGL(kern, dim3(chunked ? wg_chunk_grid(P.nblocks) : P.nblocks),
                        dim3(64 * (WK * WR + WGRAD_LOADER_WAVES)), pl.lds_bytes, s, P,
-                       x, dzdy, rbias, out, part);
+                       x, dzdy, rbias, out, part, bpart);
     int st = check_launch();
+    if constexpr (BIAS) {
+        if (st) return st;
+        hipLaunchKernelGGL((wgrad_bias_final_kernel<WK * MK * 32>), dim3(P.G * P.KT), dim3(WK * MK * 32 * 8), 0, s, P, bpart, dzdb);
+        st = check_launch();
+    }
     if (st || P.nblocks < 2 || P.nchunks == 1) return st;
     constexpr int TK = WK * MK * 32, TR = WR * MR * 32 * (WINO ? 3 : 1);     // coefficients per tile
     // at most nblocks - 1 tiles are shared, but which ones is cheaper to find per tile
@@ -319,9 +327,18 @@ int launch_wgrad_inst(const WgradPlan &pl, const float *x, const float *dzdy, co
                         : launch_wgrad_inst2<WK, WR, MK, MR, false>(pl, x, dzdy, rbias, out, part, s, relu);
 }
 
+// The filter derivative can leave the bias derivative as a by-product: the 12-wave WINO shape on the chunked schedule
+// (every block then holds one piece of one tile)
+bool wgrad_gives_bias(const WgradPlan &pl) { return pl.wino && pl.shape == WG_W64x192 && pl.P.nchunks > 0; }
+size_t wgrad_bias_floats(const WgradPlan &pl) { return (size_t)2 * pl.P.nblocks * pl.TK; }
+
 int launch_wgrad(const WgradPlan &pl, const float *x, const float *dzdy, const float *rbias, float *out, void *ws,
-                 hipStream_t s, int relu = 0) {
+                 hipStream_t s, int relu = 0, float *dzdb = nullptr) {
     float *part = (float *)ws;
+    if (dzdb) {
+        if (!wgrad_gives_bias(pl)) return MCN_BAD_ARG;
+        return launch_wgrad_inst2<2, 6, 1, 1, true, true, 4, true>(pl, x, dzdy, rbias, out, part, s, relu, dzdb);
+    }
     switch (pl.shape) {
         case WG_128x128: return launch_wgrad_inst<2, 2, 2, 2>(pl, x, dzdy, rbias, out, part, s, relu);
         case WG_64x192: return launch_wgrad_inst<2, 2, 1, 3>(pl, x, dzdy, rbias, out, part, s, relu);
@@ -395,6 +412,13 @@ size_t workspace_bytes(const mcn_conv_desc *d, const Geom &g, int op) {
             if (e->fc) return igemm_ws_bytes(e->fc_wg);
             if (e->wgb_ok) return e->wgb.partial_floats * sizeof(float);
             return e->wg_ok ? e->wg.partial_floats * sizeof(float) : 0;
+        case MCN_OP_BACKWARD_FILTER_BIAS: {
+            // fused: the filter derivative's scratch and the partial bias sums; otherwise the two passes one
+            // after the other in the same region
+            const size_t f = workspace_bytes(d, g, MCN_OP_BACKWARD_FILTER), b = workspace_bytes(d, g, MCN_OP_BACKWARD_BIAS);
+            if (!e->fc && !e->wgb_ok && e->wg_ok && wgrad_gives_bias(e->wg)) return f + wgrad_bias_floats(e->wg) * sizeof(float);
+            return f > b ? f : b;
+        }
         default:
             return 0;
     }
@@ -465,10 +489,27 @@ int run_backward_filter(const mcn_conv_desc *desc, const Geom &g, const float *x
     return check_launch();
 }
 
+int run_backward_bias(int plane, int K, int N, const float *dzdy, float *dzdb, void *ws, size_t ws_bytes,
+                      hipStream_t s, const float *y = nullptr, float *dzdp = nullptr);
+
+// dzdw and dzdb in one call: one kernel where the filter derivative's kernel sums dzdy on the way, else the two passes
+int run_backward_filter_bias(const mcn_conv_desc *desc, const Geom &g, const float *x, const float *dzdy, float *dzdw,
+                             float *dzdb, void *ws, size_t ws_bytes, hipStream_t s) {
+    if (!x || !dzdy || !dzdw || !dzdb) return MCN_BAD_ARG;
+    const size_t need = workspace_bytes(desc, g, MCN_OP_BACKWARD_FILTER_BIAS);
+    if (ws_bytes < need || (!ws && need)) return MCN_WORKSPACE_TOO_SMALL;
+    const PlanEntry *pe = plans_for(desc, g);
+    if (!pe->fc && !pe->wgb_ok && pe->wg_ok && wgrad_gives_bias(pe->wg))
+        return launch_wgrad(pe->wg, x, dzdy, nullptr, dzdw, ws, s, 0, dzdb);
+    const int st = run_backward_filter(desc, g, x, dzdy, dzdw, ws, ws_bytes, s);
+    if (st) return st;
+    return run_backward_bias(g.Ho * g.Wo, g.K, g.N, dzdy, dzdb, ws, ws_bytes, s, nullptr, nullptr);
+}
+
 // dzdb[k] = sum of the plane x K x N array dzdy over its plane and its images.  With y (and dzdp):
 // dzdp = [y > 0] * dzdy is written in the same pass and summed instead.
 int run_backward_bias(int plane, int K, int N, const float *dzdy, float *dzdb, void *ws, size_t ws_bytes,
-                      hipStream_t s, const float *y = nullptr, float *dzdp = nullptr) {
+                      hipStream_t s, const float *y, float *dzdp) {
     if (!dzdy || !dzdb) return MCN_BAD_ARG;
     const BiasPlan p = plan_bias(plane, K, N);
     const size_t need = p.ws_floats * sizeof(float);
@@ -541,7 +582,7 @@ int mcn_conv_workspace_size(const mcn_conv_desc *desc, int op, size_t *bytes) {
     Geom g;
     int st = make_geom(desc, &g);
     if (st) return st;
-    if (!bytes || op < MCN_OP_FORWARD || op > MCN_OP_BACKWARD_BIAS) return MCN_BAD_ARG;
+    if (!bytes || op < MCN_OP_FORWARD || op > MCN_OP_BACKWARD_FILTER_BIAS) return MCN_BAD_ARG;
     *bytes = workspace_bytes(desc, g, op);
     return MCN_OK;
 }
@@ -559,6 +600,8 @@ const char *mcn_conv_kernel_name(const mcn_conv_desc *desc, int op) {
                                      : "direct";
         case MCN_OP_BACKWARD_FILTER: return e->fc ? "fc_gemm" : e->wgb_ok ? "wgrad_bf16" : e->wg_ok ? (e->wg.wino ? "wgrad_f23" : "wgrad_igemm") : "direct";
         case MCN_OP_BACKWARD_BIAS: return plan_bias(g).rows ? "reduce_rows" : "reduce2";
+        case MCN_OP_BACKWARD_FILTER_BIAS:
+            return !e->fc && !e->wgb_ok && e->wg_ok && wgrad_gives_bias(e->wg) ? "wgrad_f23+bias" : "two passes";
         default: return NULL;
     }
 }
@@ -585,6 +628,14 @@ int mcn_conv_backward_filter(const mcn_conv_desc *desc, const float *x, const fl
     int st = make_geom(desc, &g);
     if (st) return st;
     return run_backward_filter(desc, g, x, dzdy, dzdw, ws, ws_bytes, (hipStream_t)stream);
+}
+
+int mcn_conv_backward_filter_bias(const mcn_conv_desc *desc, const float *x, const float *dzdy, float *dzdw,
+                                  float *dzdb, void *ws, size_t ws_bytes, void *stream) {
+    Geom g;
+    int st = make_geom(desc, &g);
+    if (st) return st;
+    return run_backward_filter_bias(desc, g, x, dzdy, dzdw, dzdb, ws, ws_bytes, (hipStream_t)stream);
 }
 
 int mcn_conv_backward_bias(const mcn_conv_desc *desc, const float *dzdy, float *dzdb, void *ws, size_t ws_bytes,

@@ -194,6 +194,53 @@ def test_row_pair_kernels_random_geometries():
         U.assert_errors(U.run_layer_full(L, with_bias=bool(t % 2), seed=t, misalign=t % 4), label="random row pairs %d %r" % (t, L))
 
 
+# ---- dzdw and dzdb in one call (Sec. 2.3.2: the backward mode returns both) ---------------
+def test_filter_and_bias_derivative_in_one_call_small():
+    """Geometries where the call runs the two passes one after the other: results identical to the separate calls."""
+    for i, (H, W, D, N, Hf, Wf, Df, K, st, pad) in enumerate((
+            (13, 9, 4, 3, 3, 2, 2, 6, (2, 1), (1, 2, 0, 1)), (20, 20, 16, 2, 3, 3, 16, 48, (1, 1), (1, 1, 1, 1)),
+            (6, 6, 8, 5, 6, 6, 8, 7, (1, 1), (0, 0, 0, 0)), (16, 16, 32, 4, 5, 5, 32, 32, (1, 1), (2, 2, 2, 2)))):
+        L = custom_layer(H, W, D, N, Hf, Wf, Df, K, st, pad, idx=600 + i)
+        x, p = U.gpu(synth.make_x(L)), None
+        ho, wo = oracle.output_size(synth.x_shape(L), synth.w_shape(L), st, pad)
+        p = U.gpu(synth.make_dzdy(L, ho, wo))
+        d = B.make_desc(synth.x_shape(L), synth.w_shape(L), st, pad)
+        assert B.mcn_conv_kernel_name(d, B.MCN_OP_BACKWARD_FILTER_BIAS) == "two passes"
+        dw, db = B.conv_backward_filter_bias(x, synth.w_shape(L), p, st, pad)
+        dw2 = B.conv_backward_filter(x, synth.w_shape(L), p, st, pad)
+        db2 = B.conv_backward_bias(synth.x_shape(L), synth.w_shape(L), p, st, pad)
+        torch.cuda.synchronize()
+        assert torch.equal(dw, dw2) and torch.equal(db, db2), i
+
+
+@pytest.mark.parametrize("case", range(3))
+def test_filter_and_bias_derivative_in_one_kernel(case):
+    """Large 3x3 stride-1 layers with 33 to 64 filters per group: the filter derivative's kernel sums dzdy on the way.
+    Both results against the oracle (dzdw at sampled places, dzdb everywhere), odd and even planes, groups."""
+    H, W, D, N, Df, K, pad = ((224, 224, 64, 32, 64, 64, (1, 1, 1, 1)),          # layer 4a
+                              (199, 181, 32, 48, 16, 80, (0, 1, 2, 1)),          # odd planes, two groups of 40 filters
+                              (200, 180, 24, 40, 24, 48, (1, 1, 1, 1)))[case]
+    L = custom_layer(H, W, D, N, 3, 3, Df, K, (1, 1), pad, idx=620 + case)
+    st = (1, 1)
+    d = B.make_desc(synth.x_shape(L), synth.w_shape(L), st, pad)
+    # (the planner cuts the reduction into chunks, and so fuses, when every block gets some 40 units or more)
+    assert B.mcn_conv_kernel_name(d, B.MCN_OP_BACKWARD_FILTER_BIAS) == "wgrad_f23+bias"
+    x, w = synth.make_x(L), synth.make_w(L)
+    ho, wo = oracle.output_size(x.shape, w.shape, st, pad)
+    p = synth.make_dzdy(L, ho, wo)
+    dw, db = B.conv_backward_filter_bias(U.gpu(x), w.shape, U.gpu(p), st, pad)
+    torch.cuda.synchronize()
+    dw, db = dw.cpu().numpy().ravel(), db.cpu().numpy().ravel()
+    xd, pd = U.np64(x), U.np64(p)
+    iw = U.sample_idx(dw.size, 96, 3)
+    e_w = U.norm_err(dw[iw], oracle.backward_filter_at(xd, w.shape, pd, iw, st, pad),
+                     oracle.backward_filter_at(np.abs(xd), w.shape, np.abs(pd), iw, st, pad))
+    e_b = U.norm_err(db, oracle.backward_bias(x.shape, w.shape, pd, st, pad),
+                     oracle.backward_bias(x.shape, w.shape, np.abs(pd), st, pad))
+    print("one kernel, case", case, "dzdw %.2e dzdb %.2e" % (e_w, e_b), flush=True)
+    assert e_w <= U.TOL_BWD and e_b <= U.TOL_BWD
+
+
 def test_row_pair_kernel_only_where_it_applies():
     """Other filter sizes, strides, few filters or few channels per group keep the kernels that compute one output
     row per pixel."""
