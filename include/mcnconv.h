@@ -114,9 +114,9 @@ int mcn_conv_backward_filter(const mcn_conv_desc *desc, const float *x, const fl
 /* Sec. 2.3.2: the block's backward mode returns dzdw and dzdb together.  Both of the two
  * results above in one call, same arguments and meaning; workspace that of
  * MCN_OP_BACKWARD_FILTER_BIAS.  Where the filter derivative's kernel can sum dzdy on
- * the way (3x3 filters at stride 1, 33 to 64 filters per group, arrays that stream
- * from memory; mcn_conv_kernel_name says "wgrad_f23+bias") dzdy is read once for
- * both; otherwise the two passes run one after the other ("two passes"). */
+ * the way (3x3 filters at stride 1, more than 32 filters per group, arrays that
+ * stream from memory; mcn_conv_kernel_name says "wgrad_f23+bias") dzdy is read once
+ * for both; otherwise the two passes run one after the other ("two passes"). */
 int mcn_conv_backward_filter_bias(const mcn_conv_desc *desc, const float *x, const float *dzdy,
                                   float *dzdw, float *dzdb, void *ws, size_t ws_bytes, void *stream);
 

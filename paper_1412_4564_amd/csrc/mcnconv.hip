@@ -327,9 +327,9 @@ int launch_wgrad_inst(const WgradPlan &pl, const float *x, const float *dzdy, co
                         : launch_wgrad_inst2<WK, WR, MK, MR, false>(pl, x, dzdy, rbias, out, part, s, relu);
 }
 
-// The filter derivative can leave the bias derivative as a by-product: the 12-wave WINO shape on the chunked schedule
+// The filter derivative can leave the bias derivative as a by-product: the WINO kernels on the chunked schedule
 // (every block then holds one piece of one tile)
-bool wgrad_gives_bias(const WgradPlan &pl) { return pl.wino && pl.shape == WG_W64x192 && pl.P.nchunks > 0; }
+bool wgrad_gives_bias(const WgradPlan &pl) { return pl.wino && pl.P.nchunks > 0; }
 size_t wgrad_bias_floats(const WgradPlan &pl) { return (size_t)2 * pl.P.nblocks * pl.TK; }
 
 int launch_wgrad(const WgradPlan &pl, const float *x, const float *dzdy, const float *rbias, float *out, void *ws,
@@ -337,6 +337,8 @@ int launch_wgrad(const WgradPlan &pl, const float *x, const float *dzdy, const f
     float *part = (float *)ws;
     if (dzdb) {
         if (!wgrad_gives_bias(pl)) return MCN_BAD_ARG;
+        if (pl.shape == WG_W128x128)
+            return launch_wgrad_inst2<2, 4, 2, 1, true, true, 3, true>(pl, x, dzdy, rbias, out, part, s, relu, dzdb);
         return launch_wgrad_inst2<2, 6, 1, 1, true, true, 4, true>(pl, x, dzdy, rbias, out, part, s, relu, dzdb);
     }
     switch (pl.shape) {

@@ -213,13 +213,15 @@ def test_filter_and_bias_derivative_in_one_call_small():
         assert torch.equal(dw, dw2) and torch.equal(db, db2), i
 
 
-@pytest.mark.parametrize("case", range(3))
+@pytest.mark.parametrize("case", range(5))
 def test_filter_and_bias_derivative_in_one_kernel(case):
-    """Large 3x3 stride-1 layers with 33 to 64 filters per group: the filter derivative's kernel sums dzdy on the way.
+    """Large 3x3 stride-1 layers: the filter derivative's kernel sums dzdy on the way (both of its tile shapes).
     Both results against the oracle (dzdw at sampled places, dzdb everywhere), odd and even planes, groups."""
     H, W, D, N, Df, K, pad = ((224, 224, 64, 32, 64, 64, (1, 1, 1, 1)),          # layer 4a
                               (199, 181, 32, 48, 16, 80, (0, 1, 2, 1)),          # odd planes, two groups of 40 filters
-                              (200, 180, 24, 40, 24, 48, (1, 1, 1, 1)))[case]
+                              (200, 180, 24, 40, 24, 48, (1, 1, 1, 1)),
+                              (56, 56, 256, 32, 256, 256, (1, 1, 1, 1)),         # layer 4b: tiles of 128 filters
+                              (75, 61, 96, 56, 48, 200, (1, 0, 0, 1)))[case]     # two groups of 100 filters, odd planes
     L = custom_layer(H, W, D, N, 3, 3, Df, K, (1, 1), pad, idx=620 + case)
     st = (1, 1)
     d = B.make_desc(synth.x_shape(L), synth.w_shape(L), st, pad)
