@@ -290,7 +290,9 @@ int launch_wgrad_inst2(const WgradPlan &pl, const float *x, const float *dzdy, c
                        float *part, hipStream_t s, int relu, float *dzdb = nullptr) {
     WgradParams P = pl.P;
     P.relu = relu;
-    auto kern = wgrad_sk_kernel<WK, WR, MK, MR, S1, WPE, WINO, BIAS>;      // WPE 4: two blocks of 4 + 4 waves per compute unit
+    // WPE = waves per SIMD the registers must allow: 4 for two blocks of 4 + 4 waves per compute unit or one of 12 + 4,
+    // 3 for one block of 8 + 4
+    auto kern = wgrad_sk_kernel<WK, WR, MK, MR, S1, WPE, WINO, BIAS>;
     float *bpart = part + pl.partial_floats;
     if (pl.lds_bytes > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
