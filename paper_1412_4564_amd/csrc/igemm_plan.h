@@ -443,6 +443,9 @@ struct WgradPlan {
 // waves (one 32 x 32 tile with its four sets of accumulators each), which holds all of a 64-channel layer.
 inline bool plan_wgrad(const ConvView &v, int n_cu, WgradPlan *pl, bool wino = false) {
     if (wino && (v.Hf != 3 || v.Wf != 3 || v.Sh != 1 || v.Sw != 1 || v.Ho < 2 || v.Kg <= 32)) return false;
+    // A filter row that meets no input row at all (planes of one or two rows under large pads) has a derivative of
+    // exactly zero; the WINO kernel would form it as a difference of sums that cancel only up to rounding.
+    if (wino && (v.H + v.Pt < 3 || v.Ho - 1 < v.Pt)) return false;
     const int T = wino ? v.Wf : v.Hf * v.Wf;             // B lanes per channel
     if ((int64_t)v.Hf * v.Wf * v.Cg >= ((int64_t)1 << 30)) return false;
     const int R = T * v.Cg;                              // B lanes in all

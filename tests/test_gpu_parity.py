@@ -243,6 +243,21 @@ def test_filter_and_bias_derivative_in_one_kernel(case):
     assert e_w <= U.TOL_BWD and e_b <= U.TOL_BWD
 
 
+def test_filter_rows_that_meet_no_input_keep_exact_zeros():
+    """Planes of one or two rows under large pads: some filter row never overlaps the input, its derivative is
+    structurally zero and must come out as exactly 0 (norm_err checks that), which a difference of rounded sums
+    would not give: the filter derivative of such layers stays on the kernel that sums the taps one by one."""
+    for i, (H, W, D, N, Df, K, pad) in enumerate(((1, 20, 72, 1, 24, 387, (1, 3, 1, 0)), (1, 9, 16, 2, 16, 40, (2, 1, 1, 1)),
+                                                  (2, 12, 32, 3, 32, 72, (3, 3, 0, 2)), (2, 7, 16, 2, 16, 96, (0, 1, 1, 1)))):
+        L = custom_layer(H, W, D, N, 3, 3, Df, K, (1, 1), pad, idx=640 + i)
+        d = B.make_desc(synth.x_shape(L), synth.w_shape(L), (1, 1), pad)
+        names = [B.mcn_conv_kernel_name(d, op) for op in range(3)]
+        print("case", i, L, names, flush=True)
+        if i < 2:       # in the other two every filter row meets an input row
+            assert names[2] == "wgrad_igemm", names
+        U.assert_errors(U.run_layer_full(L, with_bias=bool(i % 2)), label="few rows %d" % i)
+
+
 def test_row_pair_kernel_only_where_it_applies():
     """Other filter sizes, strides, few filters or few channels per group keep the kernels that compute one output
     row per pixel."""
