@@ -177,17 +177,18 @@ def test_3x3_stride1_row_pair_kernel(case):
 
 
 def test_row_pair_kernels_random_geometries():
-    """3x3 filters at stride 1 at random plane sizes (odd and even, down to 2 rows), pads up to 3 per side, one to
+    """3x3 filters at stride 1 at random plane sizes (odd and even, down to a single row), pads up to 5 per side, one to
     three groups, ragged filter and channel counts: whichever of the three passes qualify run on the row-pair
     kernels, the rest on the others."""
     rng = np.random.default_rng(161803)
-    for t in range(20):
+    for t in range(40):
         g = int(rng.choice([1, 1, 2, 3]))
         Df = int(rng.choice([8, 16, 20, 24, 40, 48, 72, 104]))
         Kg = int(rng.choice([33, 40, 56, 64, 65, 72, 96, 130, 136, 200]))
-        pad = [int(v) for v in rng.integers(0, 4, size=4)]
-        H = int(rng.integers(max(1, 3 - pad[0] - pad[1]), 45))
-        W = int(rng.integers(max(1, 3 - pad[2] - pad[3]), 30))
+        pad = [int(v) for v in rng.integers(0, 6, size=4)]
+        lo_h, lo_w = max(1, 3 - pad[0] - pad[1]), max(1, 3 - pad[2] - pad[3])
+        H = int(rng.integers(lo_h, lo_h + int(rng.choice([4, 12, 45]))))       # a third of the planes are tiny
+        W = int(rng.integers(lo_w, lo_w + int(rng.choice([4, 12, 30]))))
         L = custom_layer(H, W, g * Df, int(rng.integers(1, 6)), 3, 3, Df, g * Kg, (1, 1), pad, idx=560 + t)
         d = B.make_desc(synth.x_shape(L), synth.w_shape(L), (1, 1), pad)
         print("random row-pair case", t, L, [B.mcn_conv_kernel_name(d, op) for op in range(3)], flush=True)
