@@ -89,6 +89,10 @@ def test_null_pointers_and_small_workspace_are_rejected():
     assert B.mcn_conv_backward_data(d, p, None, p, None, 0, None) == B.MCN_BAD_ARG
     assert B.mcn_conv_backward_filter(d, p, p, None, None, 0, None) == B.MCN_BAD_ARG
     assert B.mcn_conv_backward_bias(d, None, p, None, 0, None) == B.MCN_BAD_ARG
+    for bad in range(4):
+        args = [p, p, p, p]
+        args[bad] = None
+        assert B.mcn_conv_backward_filter_bias(d, *args, None, 0, None) == B.MCN_BAD_ARG
     assert B.mcn_conv_relu_forward(d, p, p, p, None, None, 0, None) == B.MCN_BAD_ARG
     for bad in range(4):
         args = [p, p, p, p]
@@ -99,11 +103,25 @@ def test_null_pointers_and_small_workspace_are_rejected():
                      (B.MCN_OP_FORWARD, lambda ws, n: B.mcn_conv_forward(d, p, p, p, p, ws, n, None)),
                      (B.MCN_OP_FORWARD, lambda ws, n: B.mcn_conv_relu_forward(d, p, p, p, p, ws, n, None)),
                      (B.MCN_OP_BACKWARD_DATA, lambda ws, n: B.mcn_conv_backward_data(d, p, p, p, ws, n, None)),
-                     (B.MCN_OP_BACKWARD_FILTER, lambda ws, n: B.mcn_conv_backward_filter(d, p, p, p, ws, n, None))]:
+                     (B.MCN_OP_BACKWARD_FILTER, lambda ws, n: B.mcn_conv_backward_filter(d, p, p, p, ws, n, None)),
+                     (B.MCN_OP_BACKWARD_FILTER_BIAS, lambda ws, n: B.mcn_conv_backward_filter_bias(d, p, p, p, p, ws, n, None))]:
         need = B.mcn_conv_workspace_size(d, op)
         if need:
             assert call(p, need - 1) == B.MCN_WORKSPACE_TOO_SMALL
             assert call(None, need) == B.MCN_WORKSPACE_TOO_SMALL
+
+
+def test_one_call_filter_and_bias_workspace_covers_both_passes():
+    # host logic: the scratch of the one-call filter + bias derivative is never smaller than that of either pass,
+    # and where one kernel gives both (layers 4a, 4b) it also holds the partial bias sums
+    from paper_1412_4564_amd import synth
+    for name, L in synth.LAYERS.items():
+        d = B.make_desc(synth.x_shape(L), synth.w_shape(L), L["stride"], L["pad"])
+        both = B.mcn_conv_workspace_size(d, B.MCN_OP_BACKWARD_FILTER_BIAS)
+        f, b = B.mcn_conv_workspace_size(d, B.MCN_OP_BACKWARD_FILTER), B.mcn_conv_workspace_size(d, B.MCN_OP_BACKWARD_BIAS)
+        fused = B.mcn_conv_kernel_name(d, B.MCN_OP_BACKWARD_FILTER_BIAS) == "wgrad_f23+bias"
+        assert fused == (name in ("4a", "4b")), name
+        assert both > f if fused else both == max(f, b), (name, both, f, b)
 
 
 def test_status_strings():
