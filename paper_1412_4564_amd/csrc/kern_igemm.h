@@ -254,6 +254,7 @@ struct PackParams {
     int ldk;               // mode 2
     int mD, Pt, Pl, B0i, B0j;   // mode 3: channels per phase, pads of the convolution, largest b0 per direction
     int wino;              // modes 0, 1 with a 3x3 filter: Hf = 4 and view tap (ti, tj) is row combination ti of column tj
+                           // (packed by igemm_pack_wino_kernel)
     int total;
 };
 
@@ -287,14 +288,7 @@ __global__ __launch_bounds__(256) void igemm_pack_weights_kernel(const float *__
     float v = 0.f;
     if (tap >= 0 && k < Q.Kg && c < Q.Cg) {
         const int ti = tap % Q.Hf, tj = tap / Q.Hf;
-        if (Q.wino) {
-            // the three filter rows of column tj (input derivative: of the flipped filter), combined
-            float gr[3];
-            for (int fi = 0; fi < 3; ++fi)
-                gr[fi] = Q.mode == 0 ? w[fi + 3 * (tj + 3 * (c + (size_t)Q.DfA * (g * Q.Kg + k)))]
-                                     : w[(2 - fi) + 3 * ((2 - tj) + 3 * (k + (size_t)Q.DfA * (g * Q.Cg + c)))];
-            v = ti == 0 ? gr[0] : ti == 1 ? 0.5f * (gr[0] + gr[1] + gr[2]) : ti == 2 ? 0.5f * (gr[0] - gr[1] + gr[2]) : gr[2];
-        } else if (Q.mode == 0) {
+        if (Q.mode == 0) {
             v = w[ti + Q.HfA * (tj + Q.WfA * (c + (size_t)Q.DfA * (g * Q.Kg + k)))];
         } else if (Q.mode == 1) {
             const int fi = Q.pi + Q.Sh * (Q.Hf - 1 - ti), fj = Q.pj + Q.Sw * (Q.Wf - 1 - tj);
@@ -312,10 +306,10 @@ __global__ __launch_bounds__(256) void igemm_pack_weights_kernel(const float *__
     packed[p] = v;
 }
 
-// The same packing for the WINO kernels (PackParams::wino, modes 0 and 1), four results per thread: a thread
-// reads the three row taps of one (filter, channel, filter column) once and writes their four combinations,
-// where igemm_pack_weights_kernel would read them once per combination.  One unit takes exactly NS*2*TK floats
-// (no pitch padding: NS = 48).  Thread index: kk fastest, then h, fj, channel pair, unit, filter tile, group.
+// The packing for the WINO kernels (PackParams::wino, modes 0 and 1; same layout), four results per thread: a
+// thread reads the three row taps of one (filter, channel, filter column) once and writes their four combinations
+//   g0,  (g0+g1+g2)/2,  (g0-g1+g2)/2,  g2      (input derivative: of the flipped filter).
+// One unit takes exactly NS*2*TK floats (no pitch padding: NS = 48).  Thread index: kk fastest, then h, fj, channel pair, unit, filter tile, group.
 __global__ __launch_bounds__(256) void igemm_pack_wino_kernel(const float *__restrict__ w, float *__restrict__ packed,
                                                               PackParams Q) {
     int p = blockIdx.x * 256 + threadIdx.x;

@@ -266,7 +266,8 @@ int launch_igemm(const IgemmPlan &pl, const float *in, const float *w, const flo
             default: return MCN_BAD_ARG;
         }
     }
-    if (pl.Q.wino && pl.P.WSZ == pl.Q.NS * 2 * pl.Q.TK)
+    if (pl.Q.wino && pl.P.WSZ != pl.Q.NS * 2 * pl.Q.TK) return MCN_BAD_ARG;      // the planner never pads these units
+    if (pl.Q.wino)
         hipLaunchKernelGGL(igemm_pack_wino_kernel, dim3(cdiv(pl.Q.total / 4, 256)), dim3(256), 0, s, w, packed, pl.Q);
     else
         hipLaunchKernelGGL(igemm_pack_weights_kernel, dim3(cdiv(pl.Q.total, 256)), dim3(256), 0, s, w, packed, pl.Q);
