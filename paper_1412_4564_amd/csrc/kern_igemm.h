@@ -342,11 +342,11 @@ __global__ __launch_bounds__(256) void igemm_pack_wino_kernel(const float *__res
 // HF, WF > 0: filter size and DCF channels per unit known at compile time (pair_mode 0, one tap
 // range, fully unrolled); HF = 0: everything read from the parameters, offsets from a table.
 // WPE: waves per SIMD the register allocation must allow.
-// LW > 0: LW more waves that only fetch.  A wave that issues global -> LDS loads is held at each one until
+// LW: that many more waves only fetch.  A wave that issues global -> LDS loads is held at each one until
 // the memory pipeline takes it, and a computing wave held there feeds no MFMAs; fetching waves have a whole
 // unit's time to issue, and the computing waves run from barrier to barrier.
 // WINO: two output rows per GEMM pixel, four row combinations per filter column (HF = 4, WF = 3; see the top).
-template <int WK, int WP, int MK, int MP, int HF, int WF, int DCF, int WPE, int LW = 0, bool WINO = false>
+template <int WK, int WP, int MK, int MP, int HF, int WF, int DCF, int WPE, int LW, bool WINO = false>
 __global__ __launch_bounds__(64 * (WK * WP + LW), WPE) void igemm_sk_kernel(IgemmParams P, const float *__restrict__ in,
                                                                      const float *__restrict__ wpk,
                                                                      const float *__restrict__ bias,
@@ -354,8 +354,9 @@ __global__ __launch_bounds__(64 * (WK * WP + LW), WPE) void igemm_sk_kernel(Igem
                                                                      float *__restrict__ part) {
     constexpr int NT = 64 * WK * WP;               // computing threads
     constexpr int NTB = NT + 64 * LW;              // threads of the block
-    constexpr int NL = LW ? 64 * LW : NT;          // fetching threads
-    constexpr int NLW = LW ? LW : WK * WP;         // fetching waves
+    static_assert(LW > 0, "the computing waves do not fetch");
+    constexpr int NL = 64 * LW;                    // fetching threads
+    constexpr int NLW = LW;                        // fetching waves
     constexpr int TK = WK * MK * 32;
     constexpr int TQ = WP * MP * 32;
     constexpr bool FIXED = HF > 0;
@@ -381,9 +382,9 @@ __global__ __launch_bounds__(64 * (WK * WP + LW), WPE) void igemm_sk_kernel(Igem
     const int half = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wk = wave % WK, wp = (wave / WK) % WP;
-    const bool loader = LW > 0 && wave >= WK * WP;          // whole waves
-    const int ltid = LW ? tid - NT : tid;                   // index among the fetching threads
-    const int lwave = LW ? wave - WK * WP : wave;
+    const bool loader = wave >= WK * WP;                    // whole waves
+    const int ltid = tid - NT;                              // index among the fetching threads
+    const int lwave = wave - WK * WP;
     const int HW = P.H * P.W;
     const int OHW = P.OH * P.OW;
 
@@ -801,60 +802,36 @@ __global__ __launch_bounds__(64 * (WK * WP + LW), WPE) void igemm_sk_kernel(Igem
     auto segment_is_whole = [&](int t, int uu) {
         return t < tile_s0 || (uu == 0 && (long long)(t - tile_s0 + 1) * NU <= ue);
     };
-    if constexpr (LW > 0) {
-        if (loader) {
-            // Fetching wave: unit it+1 goes into the buffer that the computing waves left at the barrier of
-            // iteration it; its own loads have landed before it joins the next barrier.  One barrier per
-            // unit, as many as the computing waves pass.
-            setup_load(t_l);
-            issue_loads(uu_l, 0);
-            for (int it = 0; it < nunits; ++it) {
-                __builtin_amdgcn_s_waitcnt(WAIT_VMCNT0);
-                lds_barrier();
-                if (it + 1 < nunits) {
-                    const int t_prev = t_l;
-                    advance(t_l, uu_l, it + 1);
-                    if (t_l != t_prev) setup_load(t_l);
-                    issue_loads(uu_l, (it + 1) & 1);
-                }
-            }
-            return;
-        }
-    } else {
+    if (loader) {
+        // Fetching wave: unit it+1 goes into the buffer that the computing waves left at the barrier of
+        // iteration it; its own loads have landed before it joins the next barrier.  One barrier per
+        // unit, as many as the computing waves pass.
         setup_load(t_l);
         issue_loads(uu_l, 0);
+        for (int it = 0; it < nunits; ++it) {
+            __builtin_amdgcn_s_waitcnt(WAIT_VMCNT0);
+            lds_barrier();
+            if (it + 1 < nunits) {
+                const int t_prev = t_l;
+                advance(t_l, uu_l, it + 1);
+                if (t_l != t_prev) setup_load(t_l);
+                issue_loads(uu_l, (it + 1) & 1);
+            }
+        }
+        return;
     }
     bool whole = segment_is_whole(t_c, uu_c);
     setup_compute(t_c);
 
-    // The two waves that share a SIMD fetch the next unit at different times (one before its
-    // MFMAs, the other half-way through), so that one of them always feeds the matrix core.
-    const bool late_fetch = NT == 512 && ((wave >> 2) & 1);
-    bool loads_waited = false;
     for (int it = 0; it < nunits; ++it) {
-        if (LW == 0 && !loads_waited) __builtin_amdgcn_s_waitcnt(WAIT_VMCNT0);   // this wave's LDS-direct loads have landed
-        loads_waited = false;
-        lds_barrier();                             // everyone's have, and the other buffer is free
+        lds_barrier();      // unit it is in LDS (the fetching waves waited for it) and the other buffer is free; results
+                            // stored earlier drain on their own
         if (need_init) { init_acc(whole && bias != nullptr); need_init = false; }
-        const bool more = it + 1 < nunits;
-        auto fetch_next = [&]() {
-            const int t_prev = t_l;
-            advance(t_l, uu_l, it + 1);
-            if (t_l != t_prev) setup_load(t_l);
-            issue_loads(uu_l, (it + 1) & 1);
-        };
-        if (LW == 0 && more && !late_fetch) fetch_next();
+        // the unit's steps in two halves (two unrolled lists)
         compute(std::integral_constant<int, 0>{}, uu_c, it & 1);
-        if (LW == 0 && more && late_fetch) fetch_next();
         compute(std::integral_constant<int, 1>{}, uu_c, it & 1);
-        const bool last = !more;
+        const bool last = it + 1 == nunits;
         if (uu_c + 1 == NU || last) {
-            // wait for the next unit's loads now, so that the stores below need not be waited for at
-            // the top of the next iteration and drain while it computes
-            if (LW == 0) {
-                __builtin_amdgcn_s_waitcnt(WAIT_VMCNT0);
-                loads_waited = true;
-            }
             if (whole) { if (P.mD) store_tile_merged(); else store_tile(); }
             else store_partial(2 * vb + (first_segment ? 0 : 1));
             first_segment = it + 1 == n_own;      // the shared range starts with a "first" segment again

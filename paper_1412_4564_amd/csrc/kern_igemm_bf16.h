@@ -75,17 +75,18 @@ __global__ __launch_bounds__(256) void igemm_pack_weights_bf16_kernel(const floa
 }
 
 // WK x WP waves; each wave owns MK x MP tiles of 32 filters x 32 pixels.
-// LW > 0: LW more waves that stage the operands (load, convert, write the slab; the packed weights go
+// LW more waves stage the operands (load, convert, write the slab; the packed weights go
 // straight to LDS) while the WK x WP waves only read LDS and issue MFMAs; see igemm_sk_kernel.
-template <int WK, int WP, int MK, int MP, int WPE, int LW = 0>
+template <int WK, int WP, int MK, int MP, int WPE, int LW>
 __global__ __launch_bounds__(64 * (WK * WP + LW), WPE) void igemm_bf16_kernel(IgemmParams P, const float *__restrict__ in,
                                                                        const float *__restrict__ wpk,
                                                                        const float *__restrict__ bias,
                                                                        float *__restrict__ out,
                                                                        float *__restrict__ part) {
     constexpr int NT = 64 * WK * WP;               // computing threads
-    constexpr int NL = LW ? 64 * LW : NT;          // staging threads
-    constexpr int NLW = LW ? LW : WK * WP;         // staging waves
+    static_assert(LW > 0, "the computing waves do not stage operands");
+    constexpr int NL = 64 * LW;                    // staging threads
+    constexpr int NLW = LW;                        // staging waves
     constexpr int TK = WK * MK * 32;
     constexpr int TQ = WP * MP * 32;
     constexpr int BF_EPT_MAX = bf_ept_max(NL);
@@ -107,9 +108,9 @@ __global__ __launch_bounds__(64 * (WK * WP + LW), WPE) void igemm_bf16_kernel(Ig
     const int half = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wk = wave % WK, wp = (wave / WK) % WP;
-    const bool loader = LW > 0 && wave >= WK * WP;          // whole waves
-    const int ltid = LW ? tid - NT : tid;                   // index among the staging threads
-    const int lwave = LW ? wave - WK * WP : wave;
+    const bool loader = wave >= WK * WP;                    // whole waves
+    const int ltid = tid - NT;                              // index among the staging threads
+    const int lwave = wave - WK * WP;
     const int HW = P.H * P.W;
     const int OHW = P.OH * P.OW;
 
@@ -372,50 +373,35 @@ __global__ __launch_bounds__(64 * (WK * WP + LW), WPE) void igemm_bf16_kernel(Ig
     auto segment_is_whole = [&](int t, int uu) {
         return t < tile_s0 || (uu == 0 && (long long)(t - tile_s0 + 1) * NU <= ue);
     };
-    if constexpr (LW > 0) {
-        if (loader) {
-            // Staging wave: unit it+1 goes into the buffers the computing waves left at the barrier of
-            // iteration it, and is complete (weights landed, slab written) before the next barrier.
-            setup_load(t_l);
-            issue_loads(uu_l, 0);
-            write_slab(0);
-            for (int it = 0; it < nunits; ++it) {
-                __builtin_amdgcn_s_waitcnt(WAIT_VMCNT0);
-                lds_barrier();
-                if (it + 1 < nunits) {
-                    const int t_prev = t_l;
-                    advance(t_l, uu_l, it + 1);
-                    if (t_l != t_prev) setup_load(t_l);
-                    issue_loads(uu_l, (it + 1) & 1);
-                    write_slab((it + 1) & 1);
-                }
-            }
-            return;
-        }
-    } else {
+    if (loader) {
+        // Staging wave: unit it+1 goes into the buffers the computing waves left at the barrier of
+        // iteration it, and is complete (weights landed, slab written) before the next barrier.
         setup_load(t_l);
         issue_loads(uu_l, 0);
         write_slab(0);
+        for (int it = 0; it < nunits; ++it) {
+            __builtin_amdgcn_s_waitcnt(WAIT_VMCNT0);
+            lds_barrier();
+            if (it + 1 < nunits) {
+                const int t_prev = t_l;
+                advance(t_l, uu_l, it + 1);
+                if (t_l != t_prev) setup_load(t_l);
+                issue_loads(uu_l, (it + 1) & 1);
+                write_slab((it + 1) & 1);
+            }
+        }
+        return;
     }
     bool whole = segment_is_whole(t_c, uu_c);
     setup_compute(t_c);
 
     for (int it = 0; it < nunits; ++it) {
-        if (LW == 0) __builtin_amdgcn_s_waitcnt(WAIT_VMCNT0);   // this wave's packed weights have landed in LDS
-        lds_barrier();                             // everyone's operands are in place, and the other buffer is free
+        lds_barrier();                             // the staging waves' operands are in place, and the other buffer is free
         if (need_init) { init_acc(whole && bias != nullptr); need_init = false; }
-        const bool more = it + 1 < nunits;
-        if (LW == 0 && more) {
-            const int t_prev = t_l;
-            advance(t_l, uu_l, it + 1);
-            if (t_l != t_prev) setup_load(t_l);
-            issue_loads(uu_l, (it + 1) & 1);
-        }
         __builtin_amdgcn_sched_barrier(0);
         compute(uu_c, it & 1);
         __builtin_amdgcn_sched_barrier(0);
-        if (LW == 0 && more) write_slab((it + 1) & 1);
-        const bool last = !more;
+        const bool last = it + 1 == nunits;
         if (uu_c + 1 == NU || last) {
             if (whole) store_tile();
             else store_partial(2 * vb + (first_segment ? 0 : 1));
