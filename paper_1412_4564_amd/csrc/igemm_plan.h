@@ -446,6 +446,9 @@ inline bool plan_wgrad(const ConvView &v, int n_cu, WgradPlan *pl, bool wino = f
     // A filter row that meets no input row at all (planes of one or two rows under large pads) has a derivative of
     // exactly zero; the WINO kernel would form it as a difference of sums that cancel only up to rounding.
     if (wino && (v.H + v.Pt < 3 || v.Ho - 1 < v.Pt)) return false;
+    // Each of its sums also holds the products of the neighbouring row of dzdy, which cancel up to rounding; over a
+    // handful of terms one small factor can leave that rounding large against the result's own terms.
+    if (wino && (int64_t)v.N * v.Ho * v.Wo < 64) return false;
     const int T = wino ? v.Wf : v.Hf * v.Wf;             // B lanes per channel
     if ((int64_t)v.Hf * v.Wf * v.Cg >= ((int64_t)1 << 30)) return false;
     const int R = T * v.Cg;                              // B lanes in all
