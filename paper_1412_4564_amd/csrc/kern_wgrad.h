@@ -610,22 +610,25 @@ __global__ __launch_bounds__(512) void wgrad_chunk_fixup_kernel(WgradParams P, c
 }
 
 // BIAS: dzdb[k] = the sum over the chunks of the partial sums that the blocks of the first coefficient tile
-// (rt = 0) of k's filter tile left in bpart.  One block per (group, filter tile); thread (k, j) adds the chunks
-// i = j, j + 8, ... (eight independent streams of loads), the eight sums are then added in a fixed order.
+// (rt = 0) of k's filter tile left in bpart.  One block of 1024 threads per (group, filter tile); thread (k, j) adds
+// the chunks i = j, j + NS, ... (NS = 1024 / TK independent streams of loads), the NS sums are then added in order.
 template <int TK>
-__global__ __launch_bounds__(TK * 8) void wgrad_bias_final_kernel(WgradParams P, const float *__restrict__ bpart,
-                                                                  float *__restrict__ dzdb) {
+__global__ __launch_bounds__(1024) void wgrad_bias_final_kernel(WgradParams P, const float *__restrict__ bpart,
+                                                                float *__restrict__ dzdb) {
+    constexpr int NS = 1024 / TK;
     const int kt = blockIdx.x % P.KT, g = blockIdx.x / P.KT;
     const int t0 = P.RT * (kt + P.KT * g);
     const int k = threadIdx.x % TK, j = threadIdx.x / TK;
-    __shared__ float red[8][TK];
+    __shared__ float red[NS][TK];
     float acc = 0.f;
-    for (int i = j; i < P.nchunks; i += 8) acc += bpart[(size_t)(2 * (t0 + P.tiles * i)) * TK + k];
+    for (int i = j; i < P.nchunks; i += NS) acc += bpart[(size_t)(2 * (t0 + P.tiles * i)) * TK + k];
     red[j][k] = acc;
     __syncthreads();
-    if (j == 0 && kt * TK + k < P.Kg)
-        dzdb[g * P.Kg + kt * TK + k] = ((red[0][k] + red[1][k]) + (red[2][k] + red[3][k])) +
-                                       ((red[4][k] + red[5][k]) + (red[6][k] + red[7][k]));
+    if (j == 0 && kt * TK + k < P.Kg) {
+        float v = red[0][k];
+        for (int i = 1; i < NS; ++i) v += red[i][k];
+        dzdb[g * P.Kg + kt * TK + k] = v;
+    }
 }
 
 }  // namespace mcn

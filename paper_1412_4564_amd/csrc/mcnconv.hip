@@ -307,7 +307,7 @@ int launch_wgrad_inst2(const WgradPlan &pl, const float *x, const float *dzdy, c
     int st = check_launch();
     if constexpr (BIAS) {
         if (st) return st;
-        hipLaunchKernelGGL((wgrad_bias_final_kernel<WK * MK * 32>), dim3(P.G * P.KT), dim3(WK * MK * 32 * 8), 0, s, P, bpart, dzdb);
+        hipLaunchKernelGGL((wgrad_bias_final_kernel<WK * MK * 32>), dim3(P.G * P.KT), dim3(1024), 0, s, P, bpart, dzdb);
         st = check_launch();
     }
     if (st || P.nblocks < 2 || P.nchunks == 1) return st;
