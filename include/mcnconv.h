@@ -54,18 +54,37 @@ typedef struct mcn_conv_desc {
     int32_t Hf, Wf, Df, K;      /* w : H' x W' x D' x K;  groups g = D / Df         */
     int32_t stride_h, stride_w; /* S_h, S_w >= 1                                    */
     int32_t pad_top, pad_bottom, pad_left, pad_right; /* P_h^-, P_h^+, P_w^-, P_w^+ */
-    int32_t precision;          /* MCN_PREC_FP32 or MCN_PREC_BF16                   */
+    int32_t precision;          /* MCN_PREC_*                                       */
 } mcn_conv_desc;
 
-enum { MCN_PREC_FP32 = 0,   /* fp32 operands, fp32 accumulation                        */
-       MCN_PREC_BF16 = 1 }; /* operands (x, w, dzdy) rounded to bf16 on chip, round to
-                               nearest even, products accumulated in fp32; arrays in
-                               memory stay fp32.  Normalised error <= 1e-2.  Geometries
-                               the bf16 kernels do not cover (fewer than 16 channels per
-                               group, fully-connected layers, the filter derivative with
-                               a vertical stride, more than 5 filter rows or at most 32
-                               filters per group) and the bias derivative compute in
-                               fp32, which meets the same bound.                      */
+/* Arithmetic of the three matrix-core passes (forward, dzdx, dzdw); the bias derivative is
+ * always a plain fp32 sum.  The manual fixes the result of the sum of Sec. 4.1, not the order
+ * of its additions, so every mode below returns that sum up to fp32 rounding.
+ *
+ * MCN_PREC_FP32 (default): fp32 operands and accumulation.  Layers with 3x3 filters at stride 1
+ *   (more than 32 filters and at least 16 channels per group) take two output rows at a time
+ *   and evaluate the three filter rows with four products instead of six (the minimal-filtering
+ *   identity F(2,3), exact in real arithmetic; mcn_conv_kernel_name says "igemm_f23" /
+ *   "wgrad_f23").  Each result is then a signed combination of four sums, each of which also
+ *   holds products of the neighbouring output row that cancel between the sums.  Its rounding
+ *   error therefore scales with the sum of |w||x| over the FOUR input rows that the pair of
+ *   output rows reads (dzdw: over both rows of dzdy of a pair), not over the result's own
+ *   three-row field: a result whose own terms are tiny beside its neighbour row's terms loses
+ *   relative accuracy (graded magnitudes along rows), and a result that is exactly zero
+ *   because of zeros in the DATA may come out as rounding noise (zeros that come from padding
+ *   stay exact).  For inputs of one scale (the workloads here) the error equals that of the
+ *   plain order, about 1e-7 of the sum of |w||x|.
+ * MCN_PREC_FP32_PLAIN: fp32 operands and accumulation, every product of the sum of Sec. 4.1
+ *   formed as written and added one by one ("igemm" / "wgrad_igemm"): error bound n * 2^-24
+ *   of the result's own sum of |w||x|; 3x3 stride-1 layers run about 1.3 times slower.
+ * MCN_PREC_BF16: operands (x, w, dzdy) rounded to bf16 on chip, round to nearest even,
+ *   products accumulated in fp32; arrays in memory stay fp32.  Normalised error <= 1e-2.
+ *   Geometries the bf16 kernels do not cover (fewer than 16 channels per group,
+ *   fully-connected layers, the filter derivative with a vertical stride, more than 5 filter
+ *   rows or at most 32 filters per group) compute in fp32, which meets the same bound.
+ * The environment variable MCN_NO_WINO=1 (read once per process) makes MCN_PREC_FP32 behave as
+ * MCN_PREC_FP32_PLAIN; it exists for benchmarks. */
+enum { MCN_PREC_FP32 = 0, MCN_PREC_BF16 = 1, MCN_PREC_FP32_PLAIN = 2 };
 
 typedef enum mcn_status {
     MCN_OK = 0,
@@ -73,7 +92,8 @@ typedef enum mcn_status {
                                     unknown precision or operation                      */
     MCN_BAD_GROUPS = 2,          /* Df does not divide D, or D/Df does not divide K     */
     MCN_FILTER_TOO_LARGE = 3,    /* H + top + bottom < H'  or  W + left + right < W'
-                                    (Sec. 4.1: "otherwise an error is thrown")          */
+                                    (Sec. 4.1, "Output size": the padded input must be
+                                    at least as large as the filter)                    */
     MCN_WORKSPACE_TOO_SMALL = 4,
     MCN_UNSUPPORTED = 5,         /* an array has 2^31 elements or more                  */
     MCN_HIP_ERROR = 6,           /* a launch failed; see mcn_last_hip_error()           */

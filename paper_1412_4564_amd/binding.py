@@ -23,7 +23,7 @@ MCN_WORKSPACE_TOO_SMALL, MCN_UNSUPPORTED, MCN_HIP_ERROR, MCN_CROP_TOO_LARGE, MCN
 MCN_POOL_MAX, MCN_POOL_AVG = 0, 1
 MCN_OP_FORWARD, MCN_OP_BACKWARD_DATA, MCN_OP_BACKWARD_FILTER, MCN_OP_BACKWARD_BIAS = 0, 1, 2, 3
 MCN_OP_BACKWARD_FILTER_BIAS = 4
-MCN_PREC_FP32, MCN_PREC_BF16 = 0, 1
+MCN_PREC_FP32, MCN_PREC_BF16, MCN_PREC_FP32_PLAIN = 0, 1, 2
 
 EXPORTS = (
     "mcn_conv_output_size", "mcn_conv_workspace_size", "mcn_conv_forward", "mcn_conv_backward_data",

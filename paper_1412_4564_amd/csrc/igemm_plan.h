@@ -391,16 +391,19 @@ inline bool wino_view(const ConvView &v, ConvView *out) {
     return true;
 }
 inline bool wino_enabled() {
-    static const bool off = getenv("MCN_NO_WINO") != nullptr;      // benchmarking / debugging override
+    // process-wide override for benchmarks; a caller chooses per call with MCN_PREC_FP32_PLAIN
+    static const bool off = getenv("MCN_NO_WINO") != nullptr;
     return !off;
 }
 
 // The instantiation with this view's filter size if there is one, its channels divide into the
 // fixed units and a plan fits; the general kernel otherwise.
-inline bool plan_igemm(const ConvView &v, int n_cu, IgemmPlan *pl, bool bf16 = false) {
+// row_pairs: 3x3 stride-1 views may take the kernels that compute two output rows from four products per
+// filter column (the caller asks for the plain order of summation with MCN_PREC_FP32_PLAIN).
+inline bool plan_igemm(const ConvView &v, int n_cu, IgemmPlan *pl, bool bf16 = false, bool row_pairs = true) {
     if (bf16) return plan_igemm_kind(v, n_cu, pl, true, 0);
     ConvView pv;
-    if (wino_enabled() && wino_view(v, &pv) && plan_igemm_kind(pv, n_cu, pl, false, 0, false, v.Ho)) return true;
+    if (row_pairs && wino_enabled() && wino_view(v, &pv) && plan_igemm_kind(pv, n_cu, pl, false, 0, false, v.Ho)) return true;
     // the instantiation with this view's filter size, if there is one and the channels divide into its units
     int fixed = 0;
     for (int f = 1; f < IGEMM_N_FIXED; ++f) {
@@ -452,9 +455,9 @@ inline bool plan_wgrad(const ConvView &v, int n_cu, WgradPlan *pl, bool wino = f
     const int T = wino ? v.Wf : v.Hf * v.Wf;             // B lanes per channel
     if ((int64_t)v.Hf * v.Wf * v.Cg >= ((int64_t)1 << 30)) return false;
     const int R = T * v.Cg;                              // B lanes in all
-    // byte offsets into x and dzdy are 32-bit
-    if ((double)v.H * v.W * v.Ctot * v.N * 4 >= 2147483647.0) return false;
-    if ((double)v.Ho * v.Wo * v.Ktot * v.N * 4 >= 2147483647.0) return false;
+    // byte offsets into x and dzdy are 32-bit and relative to the start of an image
+    if ((double)v.H * v.W * v.Ctot * 4 >= 2147483647.0) return false;
+    if ((double)v.Ho * v.Wo * v.Ktot * 4 >= 2147483647.0) return false;
     int shape, WK, WR, MK, MR;
     if (wino && v.Kg > 64) { shape = WG_W128x128; WK = 2; WR = 4; MK = 2; MR = 1; }
     else if (wino) { shape = WG_W64x192; WK = 2; WR = 6; MK = 1; MR = 1; }     // 12 computing waves, one tile each per set
@@ -628,8 +631,8 @@ inline bool plan_wgrad_bf16(const ConvView &v, int n_cu, WgradBfPlan *pl) {
     const int64_t R64 = (int64_t)T * v.Cg;
     if (R64 >= ((int64_t)1 << 30)) return false;
     const int R = (int)R64;
-    if ((double)v.H * v.W * v.Ctot * v.N * 4 >= 2147483647.0) return false;      // 32-bit byte offsets
-    if ((double)v.Ho * v.Wo * v.Ktot * v.N * 4 >= 2147483647.0) return false;
+    if ((double)v.H * v.W * v.Ctot * 4 >= 2147483647.0) return false;      // 32-bit byte offsets inside an image
+    if ((double)v.Ho * v.Wo * v.Ktot * 4 >= 2147483647.0) return false;
     const int shape = v.Kg > 64 ? WGB_128x256 : WGB_64x256;
     const int TK = v.Kg > 64 ? 128 : 64, TR = 256, NT = 512;
     const int RT = (R + TR - 1) / TR;

@@ -50,6 +50,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <type_traits>
+#include "fastdiv.h"
 
 namespace mcn {
 
@@ -81,16 +82,20 @@ __device__ inline buffer_rsrc make_rsrc(const void *base, unsigned bytes) {
     return r;
 }
 __device__ inline unsigned lds_address(const void *p) { return (unsigned)(size_t)MCN_LDS_PTR(p); }
-// lds_addr: wave-uniform LDS byte address of lane 0's element
+// lds_addr: wave-uniform LDS byte address of lane 0's element.  M0 is saved and restored around the load, so the
+// statement leaves no register changed that the compiler may be keeping a value in (the loads are issued by the
+// fetching waves, whose scalar instructions cost the computing waves nothing).
 __device__ inline void load_to_lds_b32(unsigned lds_addr, unsigned voffset, buffer_rsrc rsrc, unsigned soffset) {
     lds_addr = __builtin_amdgcn_readfirstlane(lds_addr);      // wave-uniform by construction; keeps it in a scalar register
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, %3 offen lds"
-                 :: "s"(lds_addr), "v"(voffset), "s"(rsrc), "s"(soffset) : "memory");
+    unsigned saved_m0;
+    asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tbuffer_load_dword %2, %3, %4 offen lds\n\ts_mov_b32 m0, %0"
+                 : "=&s"(saved_m0) : "s"(lds_addr), "v"(voffset), "s"(rsrc), "s"(soffset) : "memory");
 }
 __device__ inline void load_to_lds_b128(unsigned lds_addr, unsigned voffset, buffer_rsrc rsrc, unsigned soffset) {
     lds_addr = __builtin_amdgcn_readfirstlane(lds_addr);
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
-                 :: "s"(lds_addr), "v"(voffset), "s"(rsrc), "s"(soffset) : "memory");
+    unsigned saved_m0;
+    asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tbuffer_load_dwordx4 %2, %3, %4 offen lds\n\ts_mov_b32 m0, %0"
+                 : "=&s"(saved_m0) : "s"(lds_addr), "v"(voffset), "s"(rsrc), "s"(soffset) : "memory");
 }
 
 
@@ -98,24 +103,6 @@ __device__ inline void load_to_lds_b128(unsigned lds_addr, unsigned voffset, buf
 // this wave's outstanding global stores, so a finished tile drains to memory while the next one
 // is computed.  Loads into LDS are waited for explicitly (vmcnt) where they are consumed.
 __device__ inline void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
-
-// n / d for 0 <= n < 2^31 and d >= 1 as a multiplication, an addition and a shift: with l = ceil(log2 d)
-// and m = floor(2^32 (2^l - d) / d) + 1,  n / d = (floor(m n / 2^32) + n) >> l.  The code that sets a tile
-// up divides by block-wide constants for every slab position and pixel; a hardware-less integer division is
-// some 35 vector instructions, each of which takes issue cycles from the matrix core.
-struct Div32 {
-    unsigned m;
-    int l;
-};
-inline Div32 make_div32(int d) {
-    Div32 f;
-    int l = 0;
-    while (((int64_t)1 << l) < d) ++l;
-    f.l = l;
-    f.m = (unsigned)((((uint64_t)1 << 32) * (((uint64_t)1 << l) - (uint64_t)d)) / (uint64_t)d + 1);
-    return f;
-}
-__device__ inline int div32(int n, Div32 f) { return (int)((__umulhi(f.m, (unsigned)n) + (unsigned)n) >> f.l); }
 
 struct IgemmParams {
     int H, W, N;        // input plane size, batch

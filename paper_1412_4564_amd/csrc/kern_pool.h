@@ -13,44 +13,20 @@
 //
 // These kernels move 4-12 bytes per result, so index arithmetic is what they could lose time on:
 // the divisions that split a thread's flat index into plane, column and row, and those by the
-// strides, are multiplications by reciprocals prepared on the host (exact for the sizes accepted).
+// strides, are multiplications by reciprocals prepared on the host (exact for every index below 2^31).
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include "fastdiv.h"
 
 namespace mcn {
-
-// n / d for 0 <= n, n*d < 2^32:  m = ceil(2^32 / d), n / d = floor(n * m / 2^32)   (d = 1: m does not fit, n / 1 = n)
-struct FastDiv {
-    unsigned d, m;
-};
-inline FastDiv make_fastdiv(int d) {
-    FastDiv f;
-    f.d = (unsigned)d;
-    f.m = d == 1 ? 0u : (unsigned)((((uint64_t)1 << 32) + (unsigned)d - 1) / (unsigned)d);
-    return f;
-}
-__device__ inline int fdiv(int n, FastDiv f) { return f.d == 1 ? n : (int)__umulhi((unsigned)n, f.m); }
-
-// n / d for any 0 <= n < 2^32 and 1 <= d < 2^32:  m = ceil(2^64 / d), n / d = floor(n * m / 2^64)
-struct FastDiv64 {
-    unsigned d;
-    unsigned long long m;
-};
-inline FastDiv64 make_fastdiv64(unsigned d) {
-    FastDiv64 f;
-    f.d = d;
-    f.m = d == 1 ? 0ull : ~0ull / d + 1;      // floor((2^64 - 1) / d) + 1 = ceil(2^64 / d) when d does not divide 2^64; powers of two: also exact
-    return f;
-}
-__device__ inline unsigned fdiv64(unsigned n, FastDiv64 f) { return f.d == 1 ? n : (unsigned)__umul64hi((unsigned long long)n, f.m); }
 
 struct PoolGeom {
     int H, W, D, N;
     int Hp, Wp, Sh, Sw, Pt, Pl;
     int Ho, Wo;
     int method;      // 0 max, 1 average
-    FastDiv dH, dHo, dSh, dSw;
+    Div32 dH, dHo, dSh, dSw;  // exact for every index below 2^31 (fastdiv.h)
     FastDiv64 dIn, dOut;     // by the plane sizes H*W and Ho*Wo
 };
 
@@ -63,9 +39,9 @@ __global__ __launch_bounds__(256) void pool_forward_kernel(PoolGeom g, const flo
                                                            float *__restrict__ y, unsigned total) {
     const unsigned idx = blockIdx.x * 256u + threadIdx.x;
     if (idx >= total) return;
-    const unsigned plane = fdiv64(idx, g.dOut);
+    const unsigned plane = div64(idx, g.dOut);
     const int e = (int)(idx - plane * (unsigned)(g.Ho * g.Wo));
-    const int jo = fdiv(e, g.dHo), io = e - jo * g.Ho;
+    const int jo = div32(e, g.dHo), io = e - jo * g.Ho;
     const float *xp = x + (size_t)plane * g.H * g.W;
     if constexpr (HP > 0) {
         const int oi = g.Sh * io - g.Pt, oj = g.Sw * jo - g.Pl;
@@ -115,10 +91,10 @@ struct WindowRange {
 __device__ inline WindowRange windows_of(const PoolGeom &g, int i, int j) {
     WindowRange r;
     const int a = i + g.Pt - g.Hp + g.Sh, b = j + g.Pl - g.Wp + g.Sw;     // ceil((i + Pt - Hp + 1) / Sh) = floor(a / Sh)
-    r.io_lo = a > 0 ? fdiv(a, g.dSh) : 0;
-    r.io_hi = min(fdiv(i + g.Pt, g.dSh), g.Ho - 1);
-    r.jo_lo = b > 0 ? fdiv(b, g.dSw) : 0;
-    r.jo_hi = min(fdiv(j + g.Pl, g.dSw), g.Wo - 1);
+    r.io_lo = a > 0 ? div32(a, g.dSh) : 0;
+    r.io_hi = min(div32(i + g.Pt, g.dSh), g.Ho - 1);
+    r.jo_lo = b > 0 ? div32(b, g.dSw) : 0;
+    r.jo_hi = min(div32(j + g.Pl, g.dSw), g.Wo - 1);
     return r;
 }
 
@@ -129,9 +105,9 @@ __global__ __launch_bounds__(256) void pool_argmax_kernel(PoolGeom g, const floa
                                                           unsigned char *__restrict__ code, unsigned total) {
     const unsigned idx = blockIdx.x * 256u + threadIdx.x;
     if (idx >= total) return;
-    const unsigned plane = fdiv64(idx, g.dOut);
+    const unsigned plane = div64(idx, g.dOut);
     const int e = (int)(idx - plane * (unsigned)(g.Ho * g.Wo));
-    const int jo = fdiv(e, g.dHo), io = e - jo * g.Ho;
+    const int jo = div32(e, g.dHo), io = e - jo * g.Ho;
     const float *xp = x + (size_t)plane * g.H * g.W;
     const int oi = g.Sh * io - g.Pt, oj = g.Sw * jo - g.Pl;
     if constexpr (HP > 0) {
@@ -176,9 +152,9 @@ __global__ __launch_bounds__(256) void pool_backward_max_coded_kernel(PoolGeom g
                                                                       float *__restrict__ dzdx, unsigned total) {
     const unsigned idx = blockIdx.x * 256u + threadIdx.x;
     if (idx >= total) return;
-    const unsigned plane = fdiv64(idx, g.dIn);
+    const unsigned plane = div64(idx, g.dIn);
     const int e = (int)(idx - plane * (unsigned)(g.H * g.W));
-    const int j = fdiv(e, g.dH), i = e - j * g.H;
+    const int j = div32(e, g.dH), i = e - j * g.H;
     const size_t pbase = (size_t)plane * g.Ho * g.Wo;
     const WindowRange r = windows_of(g, i, j);
     float acc = 0.f;
@@ -225,9 +201,9 @@ __global__ __launch_bounds__(256) void pool_backward_max_disjoint_kernel(PoolGeo
                                                                          float *__restrict__ dzdx, unsigned total) {
     const unsigned idx = blockIdx.x * 256u + threadIdx.x;
     if (idx >= total) return;
-    const unsigned plane = fdiv64(idx, g.dOut);
+    const unsigned plane = div64(idx, g.dOut);
     const int e = (int)(idx - plane * (unsigned)(g.Ho * g.Wo));
-    const int jo = fdiv(e, g.dHo), io = e - jo * g.Ho;
+    const int jo = div32(e, g.dHo), io = e - jo * g.Ho;
     const size_t base = (size_t)plane * g.H * g.W;
     const float *xp = x + base;
     float *dp = dzdx + base;
@@ -271,9 +247,9 @@ __global__ __launch_bounds__(256) void pool_backward_kernel(PoolGeom g, const fl
                                                             float *__restrict__ dzdx, unsigned total) {
     const unsigned idx = blockIdx.x * 256u + threadIdx.x;
     if (idx >= total) return;
-    const unsigned plane = fdiv64(idx, g.dIn);
+    const unsigned plane = div64(idx, g.dIn);
     const int e = (int)(idx - plane * (unsigned)(g.H * g.W));
-    const int j = fdiv(e, g.dH), i = e - j * g.H;
+    const int j = div32(e, g.dH), i = e - j * g.H;
     const float *pp = dzdy + (size_t)plane * g.Ho * g.Wo;
     const WindowRange r = windows_of(g, i, j);
     float acc = 0.f;

@@ -184,9 +184,10 @@ __global__ __launch_bounds__(64 * (WK * WR + WGRAD_LOADER_WAVES), WPE) void wgra
     }
 
     // ---- load side -------------------------------------------------------------------------
-    buffer_rsrc xrs = make_rsrc(x, 0x7fffffffu);
-    buffer_rsrc yrs = xrs;
+    // The buffer resources are rebuilt per unit, at the unit's image: offsets then stay inside one image (the
+    // host checks that an image of x and of dzdy is under 2^31 bytes), whatever the batch size.
     int l_klim = 0, l_nch = 0;
+    int l_xch = 0, l_ych = 0;      // first channel of x / of dzdy that the tile reads
     auto setup_load = [&](int t) {
         const int rt = t % P.RT; t /= P.RT;
         const int kt = t % P.KT;
@@ -196,8 +197,8 @@ __global__ __launch_bounds__(64 * (WK * WR + WGRAD_LOADER_WAVES), WPE) void wgra
         const int c_lo = r_lo / T;
         l_nch = (r_hi - 1) / T - c_lo + 1;
         l_klim = min(P.Kg - kt * TK, TK);
-        xrs = make_rsrc(x + ((size_t)g * P.Cg + c_lo) * HW, 0x7fffffffu);
-        yrs = make_rsrc(dzdy + ((size_t)g * P.Kg + (size_t)kt * TK) * HoWo, 0x7fffffffu);
+        l_xch = g * P.Cg + c_lo;
+        l_ych = g * P.Kg + kt * TK;
     };
     auto issue_loads = [&](int uu, int b) {
         float *yb = ybuf + b * YS;
@@ -209,8 +210,10 @@ __global__ __launch_bounds__(64 * (WK * WR + WGRAD_LOADER_WAVES), WPE) void wgra
         const int jc = rem / P.RB, rb = rem - jc * P.RB;
         const int io0 = rb * P.TI, jo0 = jc * P.MC;
         const int rows = min(P.TI, P.Ho - io0), cols = min(P.MC, P.Wo - jo0);
+        const buffer_rsrc xrs = make_rsrc(x + ((size_t)n * P.Ctot + l_xch) * HW, 0x7fffffffu);
+        const buffer_rsrc yrs = make_rsrc(dzdy + ((size_t)n * P.Ktot + l_ych) * HoWo, 0x7fffffffu);
         // dzdy tile: one wave instruction = 64 pixels of one filter
-        const unsigned ybase = 4u * (unsigned)(io0 + P.Ho * jo0 + n * (P.Ktot * HoWo));
+        const unsigned ybase = 4u * (unsigned)(io0 + P.Ho * jo0);
         for (int seg = 0; seg < NSEG; ++seg) {
             const unsigned yoff = (p_ii[seg] < rows && p_dc[seg] < cols) ? p_off[seg] + ybase : SLAB_INVALID;
             if (seg * 64 + lane < PCH) {
@@ -220,7 +223,7 @@ __global__ __launch_bounds__(64 * (WK * WR + WGRAD_LOADER_WAVES), WPE) void wgra
         }
         // x slab of the tile's channels: rows i0 + r, columns j0 + col of image n
         const int i0 = io0 * P.Sh - P.Pt, j0 = jo0 * P.Sw - P.Pl;
-        const int xbase = 4 * (i0 + P.H * j0 + n * (P.Ctot * HW));
+        const int xbase = 4 * (i0 + P.H * j0);
         const int ntot = SRP * P.SC;
         // The fetching waves share the (chunk of 64 positions, channel) pairs.  With at least LW channels every
         // wave walks all chunks and takes every LW-th channel of each, starting one channel further per chunk

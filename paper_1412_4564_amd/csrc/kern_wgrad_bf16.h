@@ -90,14 +90,11 @@ __global__ __launch_bounds__(64 * WK * WR, 2) void wgrad_bf16_kernel(WgradBfPara
     const int nch = (r_hi - 1) / T - c_lo + 1;
     const int klim = min(P.Kg - kt * TK, TK);
 
-    // the arrays from the tile's first filter / channel on; offsets below are relative to these
+    // the arrays from the tile's first filter / channel of an image on; the buffer resources are built per unit at
+    // the unit's image, so offsets stay inside one image (under 2^31 bytes: checked on the host) whatever the batch
     const size_t ybase = ((size_t)g * P.Kg + (size_t)kt * TK) * HoWo;
     const size_t xbase = ((size_t)g * P.Cg + c_lo) * HW;
-    size_t yleft = ((size_t)P.N * P.Ktot * HoWo - ybase) * 4, xleft = ((size_t)P.N * P.Ctot * HW - xbase) * 4;
-    if (yleft > 0x7fffffffull) yleft = 0x7fffffffull;
-    if (xleft > 0x7fffffffull) xleft = 0x7fffffffull;
-    const __amdgpu_buffer_rsrc_t yrs = __builtin_amdgcn_make_buffer_rsrc((void *)(dzdy + ybase), 0, (int)yleft, BUFFER_FLAGS);
-    const __amdgpu_buffer_rsrc_t xrs = __builtin_amdgcn_make_buffer_rsrc((void *)(x + xbase), 0, (int)xleft, BUFFER_FLAGS);
+    const int yleft = (int)(((size_t)P.Ktot * HoWo - ybase) * 4), xleft = (int)(((size_t)P.Ctot * HW - xbase) * 4);
 
     // ---- what this thread stages, fixed for the whole kernel -----------------------------------
     int y_k[WGB_YT], y_dc[WGB_YT], y_rg[WGB_YT], y_lds[WGB_YT];
@@ -156,8 +153,11 @@ __global__ __launch_bounds__(64 * WK * WR, 2) void wgrad_bf16_kernel(WgradBfPara
     uintx4 y_lo[WGB_YT], y_hi[WGB_YT];
     float x_dat[WGB_XT][NE];
     auto issue_loads = [&](int n) {
-        const unsigned ysoff = (unsigned)n * (unsigned)(P.Ktot * HoWo) * 4u;
-        const unsigned xsoff = (unsigned)n * (unsigned)(P.Ctot * HW) * 4u;
+        const __amdgpu_buffer_rsrc_t yrs = __builtin_amdgcn_make_buffer_rsrc(
+            (void *)(dzdy + ybase + (size_t)n * P.Ktot * HoWo), 0, yleft, BUFFER_FLAGS);
+        const __amdgpu_buffer_rsrc_t xrs = __builtin_amdgcn_make_buffer_rsrc(
+            (void *)(x + xbase + (size_t)n * P.Ctot * HW), 0, xleft, BUFFER_FLAGS);
+        const unsigned ysoff = 0u, xsoff = 0u;
 #pragma unroll
         for (int s = 0; s < WGB_YT; ++s) {
             if (s * NT < TK * P.PW) {          // block-uniform

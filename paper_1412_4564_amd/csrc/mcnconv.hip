@@ -125,9 +125,10 @@ const PlanEntry *plans_for(const mcn_conv_desc *d, const Geom &g) {
     // bf16 operands: the bf16 kernel where a view has at least one full MFMA depth of channels;
     // other views (and the filter derivative) compute in fp32, which meets the same error bound
     const bool bf = d->precision == MCN_PREC_BF16;
+    const bool pairs = d->precision != MCN_PREC_FP32_PLAIN;     // the row-pair kernels for 3x3 stride-1 layers
     auto plan_view = [&](const ConvView &v, IgemmPlan *pl) {
         if (bf && !v.mD && v.Cg >= BF_DC && plan_igemm(v, ncu, pl, true)) return true;    // merged phases: fp32 kernel only
-        return plan_igemm(v, ncu, pl, false);
+        return plan_igemm(v, ncu, pl, false, pairs);
     };
     e.fwd_ok = on && plan_view(forward_view(g), &e.fwd);
     e.bwd_ok = on && g.Sh * g.Sw <= MAX_PHASES;
@@ -149,7 +150,7 @@ const PlanEntry *plans_for(const mcn_conv_desc *d, const Geom &g) {
                 e.bwd_ok = plan_view(v, &e.bwd[e.n_bwd++]);
             }
     }
-    e.wg_ok = on && ((wino_enabled() && plan_wgrad(forward_view(g), ncu, &e.wg, true)) ||
+    e.wg_ok = on && ((pairs && wino_enabled() && plan_wgrad(forward_view(g), ncu, &e.wg, true)) ||
                      plan_wgrad(forward_view(g), ncu, &e.wg));
     e.wgb_ok = on && bf && plan_wgrad_bf16(forward_view(g), ncu, &e.wgb);
     e.fc = on && is_fully_connected(g) && (int64_t)g.H * g.W * g.D < ((int64_t)1 << 30) &&
@@ -554,7 +555,7 @@ int conjugate_convolution(const mcn_convt_desc *t, mcn_conv_desc *c, Geom *g) {
     if (t->Hf < 1 || t->Wf < 1 || t->Kf < 1 || t->groups < 1) return MCN_BAD_ARG;
     if (t->up_h < 1 || t->up_w < 1) return MCN_BAD_ARG;
     if (t->crop_top < 0 || t->crop_bottom < 0 || t->crop_left < 0 || t->crop_right < 0) return MCN_BAD_ARG;
-    if (t->precision != MCN_PREC_FP32 && t->precision != MCN_PREC_BF16) return MCN_BAD_ARG;
+    if (t->precision != MCN_PREC_FP32 && t->precision != MCN_PREC_BF16 && t->precision != MCN_PREC_FP32_PLAIN) return MCN_BAD_ARG;
     if (t->D % t->groups != 0) return MCN_BAD_GROUPS;
     const int64_t lim = (int64_t)1 << 31;
     const int64_t Ho = (int64_t)t->up_h * (t->H - 1) + t->Hf - t->crop_top - t->crop_bottom;
@@ -603,7 +604,13 @@ const char *mcn_conv_kernel_name(const mcn_conv_desc *desc, int op) {
             return e->fc ? "fc_gemm"
                          : e->bwd_ok ? (e->n_bwd && e->bwd[0].bf16 ? "igemm_bf16" : e->n_bwd && e->bwd[0].P.wino_Ho ? "igemm_f23" : "igemm")
                                      : "direct";
-        case MCN_OP_BACKWARD_FILTER: return e->fc ? "fc_gemm" : e->wgb_ok ? "wgrad_bf16" : e->wg_ok ? (e->wg.wino ? "wgrad_f23" : "wgrad_igemm") : "direct";
+        case MCN_OP_BACKWARD_FILTER:
+            if (e->fc) return "fc_gemm";
+            if (e->wgb_ok) return "wgrad_bf16";
+            if (!e->wg_ok) return "direct";
+            // "_chunked": the schedule for arrays that stream from memory (kern_wgrad.h, WgradParams::nchunks)
+            if (e->wg.P.nchunks > 0) return e->wg.wino ? "wgrad_f23_chunked" : "wgrad_igemm_chunked";
+            return e->wg.wino ? "wgrad_f23" : "wgrad_igemm";
         case MCN_OP_BACKWARD_BIAS: return plan_bias(g).rows ? "reduce_rows" : "reduce2";
         case MCN_OP_BACKWARD_FILTER_BIAS:
             return !e->fc && !e->wgb_ok && e->wg_ok && wgrad_gives_bias(e->wg) ? "wgrad_f23+bias" : "two passes";
@@ -765,14 +772,13 @@ static int make_pool_geom(const mcn_pool_desc *d, PoolGeom *g) {
     const int64_t Ho = (hp - d->Hp) / d->stride_h + 1, Wo = (wp - d->Wp) / d->stride_w + 1;
     const double lim = 2147483648.0;
     if ((double)d->H * d->W * d->D * d->N >= lim || (double)Ho * Wo * d->D * d->N >= lim) return MCN_UNSUPPORTED;
-    // the 32-bit reciprocal divisions in the kernels are exact below these sizes
-    if (d->H >= 32768 || d->W >= 32768 || d->Hp >= 32768 || d->Wp >= 32768 || d->stride_h >= 32768 || d->stride_w >= 32768)
-        return MCN_UNSUPPORTED;
+    // window and stride sizes the kernels' 32-bit index arithmetic is written for
+    if (d->Hp >= 32768 || d->Wp >= 32768 || d->stride_h >= 32768 || d->stride_w >= 32768) return MCN_UNSUPPORTED;
     g->H = d->H; g->W = d->W; g->D = d->D; g->N = d->N;
     g->Hp = d->Hp; g->Wp = d->Wp; g->Sh = d->stride_h; g->Sw = d->stride_w; g->Pt = d->pad_top; g->Pl = d->pad_left;
     g->Ho = (int)Ho; g->Wo = (int)Wo; g->method = d->method;
-    g->dH = make_fastdiv(d->H); g->dHo = make_fastdiv((int)Ho);
-    g->dSh = make_fastdiv(d->stride_h); g->dSw = make_fastdiv(d->stride_w);
+    g->dH = make_div32(d->H); g->dHo = make_div32((int)Ho);
+    g->dSh = make_div32(d->stride_h); g->dSw = make_div32(d->stride_w);
     g->dIn = make_fastdiv64((unsigned)(d->H * d->W)); g->dOut = make_fastdiv64((unsigned)(Ho * Wo));
     return MCN_OK;
 }

@@ -88,8 +88,8 @@ def run_layer_full(L, precision=B.MCN_PREC_FP32, with_bias=True, seed=0, misalig
 
 
 def run_layer_sampled(L, n_out=4000, n_filt=96, precision=B.MCN_PREC_FP32, seed=0):
-    """All four operations at full size; results compared at sampled places that the
-    oracle computes one by one (bias derivative: all K)."""
+    """All four operations at full size; y and dzdx compared at sampled places that the oracle computes one by
+    one, dzdw at n_filt sampled places or (n_filt=None) everywhere, the bias derivative everywhere."""
     st, pad = L["stride"], L["pad"]
     x, w, b = synth.make_x(L, seed), synth.make_w(L, seed), synth.make_b(L, seed)
     ho, wo = oracle.output_size(x.shape, w.shape, st, pad)
@@ -110,12 +110,35 @@ def run_layer_sampled(L, n_out=4000, n_filt=96, precision=B.MCN_PREC_FP32, seed=
     ix = sample_idx(dx.size, n_out, 2)
     out["backward_data"] = norm_err(dx[ix], oracle.backward_data_at(x.shape, wd, pd, ix, st, pad),
                                     oracle.backward_data_at(x.shape, np.abs(wd), np.abs(pd), ix, st, pad))
-    iw = sample_idx(dw.size, n_filt, 3)
-    out["backward_filter"] = norm_err(dw[iw], oracle.backward_filter_at(xd, w.shape, pd, iw, st, pad),
-                                      oracle.backward_filter_at(np.abs(xd), w.shape, np.abs(pd), iw, st, pad))
+    if n_filt is None:      # every filter coefficient
+        out["backward_filter"] = norm_err(dw, oracle.backward_filter(xd, w.shape, pd, st, pad),
+                                          oracle.backward_filter(np.abs(xd), w.shape, np.abs(pd), st, pad))
+    else:
+        iw = sample_idx(dw.size, n_filt, 3)
+        out["backward_filter"] = norm_err(dw[iw], oracle.backward_filter_at(xd, w.shape, pd, iw, st, pad),
+                                          oracle.backward_filter_at(np.abs(xd), w.shape, np.abs(pd), iw, st, pad))
     out["backward_bias"] = norm_err(db, oracle.backward_bias(x.shape, w.shape, pd, st, pad),
                                     oracle.backward_bias(x.shape, w.shape, np.abs(pd), st, pad))
     return out
+
+
+class OracleResults:
+    """The four results of the oracle for layer L and their normalisers (the same operators on absolute values), every
+    element, computed once so that several GPU runs (summation orders, entry points) can be compared with them."""
+
+    def __init__(self, L, seed=0, filter_only=False):
+        self.L, self.st, self.pad = L, L["stride"], L["pad"]
+        st, pad = self.st, self.pad
+        self.x, self.w, self.b = synth.make_x(L, seed), synth.make_w(L, seed), synth.make_b(L, seed)
+        self.ho, self.wo = oracle.output_size(self.x.shape, self.w.shape, st, pad)
+        self.p = synth.make_dzdy(L, self.ho, self.wo, seed)
+        xd, wd, bd, pd = np64(self.x), np64(self.w), np64(self.b), np64(self.p)
+        xs, ws = self.x.shape, self.w.shape
+        if not filter_only:
+            self.y, self.y_den = oracle.forward(xd, wd, bd, st, pad), oracle.forward(np.abs(xd), np.abs(wd), np.abs(bd), st, pad)
+            self.dx, self.dx_den = oracle.backward_data(xs, wd, pd, st, pad), oracle.backward_data(xs, np.abs(wd), np.abs(pd), st, pad)
+        self.dw, self.dw_den = oracle.backward_filter(xd, ws, pd, st, pad), oracle.backward_filter(np.abs(xd), ws, np.abs(pd), st, pad)
+        self.db, self.db_den = oracle.backward_bias(xs, ws, pd, st, pad), oracle.backward_bias(xs, ws, np.abs(pd), st, pad)
 
 
 def assert_errors(errs, precision=B.MCN_PREC_FP32, label=""):

@@ -288,9 +288,13 @@ def test_planner_puts_every_workload_layer_on_the_matrix_core_kernels():
     for name in ("4a", "4b", "4c"):
         L = synth.LAYERS[name]
         d = B.make_desc(synth.x_shape(L), synth.w_shape(L), L["stride"], L["pad"])
-        assert [B.mcn_conv_kernel_name(d, op) for op in range(3)] == ["igemm_f23", "igemm_f23", "wgrad_f23"], name
+        wg = "wgrad_f23" if name == "4c" else "wgrad_f23_chunked"      # 4a, 4b stream from memory: chunked schedule
+        assert [B.mcn_conv_kernel_name(d, op) for op in range(3)] == ["igemm_f23", "igemm_f23", wg], name
+        # the plain order of summation, chosen per call
+        d = B.make_desc(synth.x_shape(L), synth.w_shape(L), L["stride"], L["pad"], B.MCN_PREC_FP32_PLAIN)
+        assert [B.mcn_conv_kernel_name(d, op) for op in range(3)] == ["igemm", "igemm", wg.replace("f23", "igemm")], name
     # bf16 operands: the deep layers on the bf16 kernels, the 3-channel first layers on the fp32 ones
-    for name, expect in (("4b", ["igemm_bf16", "igemm_bf16", "wgrad_bf16"]), ("3a", ["igemm", "igemm", "wgrad_igemm"])):
+    for name, expect in (("4b", ["igemm_bf16", "igemm_bf16", "wgrad_bf16"]), ("3a", ["igemm", "igemm", "wgrad_igemm_chunked"])):
         L = synth.LAYERS[name]
         d = B.make_desc(synth.x_shape(L), synth.w_shape(L), L["stride"], L["pad"], B.MCN_PREC_BF16)
         assert [B.mcn_conv_kernel_name(d, op) for op in range(3)] == expect, name
@@ -310,3 +314,20 @@ def test_planner_handles_odd_geometries_on_the_host():
         H, Hf, S, P, D, K = key
         d = B.make_desc((3, D, H + 2, H), (K, D, Hf, Hf), (S, S), (P, P, P, 0))
         assert [B.mcn_conv_workspace_size(d, op) for op in range(4)] == seen[key], key
+
+
+def test_environment_override_of_the_summation_order():
+    """MCN_NO_WINO=1 (read once per process, for benchmarks) makes the default precision behave as
+    MCN_PREC_FP32_PLAIN; without it the choice is the descriptor's, per call."""
+    import os
+    import subprocess
+    import sys
+    script = ("import sys; sys.path.insert(0, sys.argv[1])\n"
+              "from paper_1412_4564_amd import binding as B, synth\n"
+              "L = synth.LAYERS['4b']\n"
+              "d = B.make_desc(synth.x_shape(L), synth.w_shape(L), L['stride'], L['pad'])\n"
+              "print(','.join(B.mcn_conv_kernel_name(d, op) for op in range(3)))\n")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, "-c", script, root], env=dict(os.environ, MCN_NO_WINO="1"), capture_output=True,
+                       text=True, timeout=120)
+    assert r.returncode == 0 and r.stdout.strip() == "igemm,igemm,wgrad_igemm_chunked", (r.stdout, r.stderr[-500:])

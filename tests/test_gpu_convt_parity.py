@@ -127,4 +127,4 @@ def test_convt_kernel_choice():
         # t1 is a 3x3 filter without upsampling: both passes run on the kernel that computes pairs of rows
         expect = "igemm_f23" if name == "t1" else "igemm"
         assert names[0] == expect and names[1] == expect, (name, names)
-        assert names[2] == ("wgrad_f23" if name == "t1" else "wgrad_igemm"), (name, names)
+        assert names[2].startswith("wgrad_f23" if name == "t1" else "wgrad_igemm"), (name, names)

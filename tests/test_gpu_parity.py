@@ -36,10 +36,7 @@ def test_workload_layers_reduced_batch_full(name, nb):
 
 
 # ---- full-size workloads, in the configuration the benchmark times: sampled -------
-@pytest.mark.parametrize("name", ["2a", "2b", "3a", "3b", "4a", "4b", "4c", "5a", "5b"])
-def test_workload_layers_full_size_sampled(name):
-    L = synth.LAYERS[name]
-    U.assert_errors(U.run_layer_sampled(L), label="layer %s full size" % name)
+# (full-size workloads, in the configuration the benchmark times: tests/test_gpu_full_size_parity.py)
 
 
 # ---- irregular geometry sweep: strides, four pads, groups, non-square everything ---
@@ -273,33 +270,19 @@ def test_row_pair_kernel_only_where_it_applies():
         assert B.mcn_conv_kernel_name(d, 2) == expect, (Hf, Wf, Df, K, st)
 
 
-_ONE_ROW_SCRIPT = r"""
-import sys
-sys.path.insert(0, sys.argv[1]); sys.path.insert(0, sys.argv[1] + "/tests")
-import parity_util as U
-from paper_1412_4564_amd import binding as B, synth
-cases = [(16, 12, 16, 3, 16, 48, (1, 1, 1, 1)), (15, 13, 16, 2, 16, 40, (1, 1, 1, 1)), (11, 14, 32, 3, 32, 70, (2, 0, 1, 2)),
-         (20, 10, 48, 2, 16, 144, (1, 1, 1, 1)), (40, 40, 32, 8, 32, 64, (1, 1, 1, 1)), (28, 28, 64, 16, 64, 256, (1, 1, 1, 1))]
-for i, (H, W, D, N, Df, K, pad) in enumerate(cases):
-    L = dict(H=H, W=W, D=D, N=N, Hf=3, Wf=3, Df=Df, K=K, stride=(1, 1), pad=pad, config=9, index=540 + i)
-    d = B.make_desc(synth.x_shape(L), synth.w_shape(L), (1, 1), pad)
-    names = [B.mcn_conv_kernel_name(d, op) for op in range(3)]
-    assert names == ["igemm", "igemm", "wgrad_igemm"], names
-    U.assert_errors(U.run_layer_full(L, with_bias=bool(i % 2)), label="one row per pixel %d" % i)
-print("ONE-ROW-OK")
-"""
+ONE_ROW = [(16, 12, 16, 3, 16, 48, (1, 1, 1, 1)), (15, 13, 16, 2, 16, 40, (1, 1, 1, 1)), (11, 14, 32, 3, 32, 70, (2, 0, 1, 2)),
+           (20, 10, 48, 2, 16, 144, (1, 1, 1, 1)), (40, 40, 32, 8, 32, 64, (1, 1, 1, 1)), (28, 28, 64, 16, 64, 256, (1, 1, 1, 1))]
 
 
-def test_3x3_stride1_one_row_kernels_in_a_process_of_their_own():
-    """With MCN_NO_WINO=1 (read once per process) 3x3 stride-1 layers run on the kernels that compute one output
-    row per pixel, as they did before the row-pair kernel existed; those instantiations stay checked."""
-    import os
-    import subprocess
-    import sys
-    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-    env = dict(os.environ, MCN_NO_WINO="1")
-    r = subprocess.run([sys.executable, "-c", _ONE_ROW_SCRIPT, root], env=env, capture_output=True, text=True, timeout=300)
-    assert r.returncode == 0 and "ONE-ROW-OK" in r.stdout, (r.stdout[-2000:], r.stderr[-2000:])
+@pytest.mark.parametrize("case", range(len(ONE_ROW)))
+def test_3x3_stride1_plain_order_of_summation(case):
+    """MCN_PREC_FP32_PLAIN, chosen per call: 3x3 stride-1 layers on the kernels that compute one output row per
+    pixel and add the products of Sec. 4.1's sum one by one."""
+    H, W, D, N, Df, K, pad = ONE_ROW[case]
+    L = custom_layer(H, W, D, N, 3, 3, Df, K, (1, 1), pad, idx=540 + case)
+    d = B.make_desc(synth.x_shape(L), synth.w_shape(L), (1, 1), pad, B.MCN_PREC_FP32_PLAIN)
+    assert [B.mcn_conv_kernel_name(d, op) for op in range(3)] == ["igemm", "igemm", "wgrad_igemm"]
+    U.assert_errors(U.run_layer_full(L, precision=B.MCN_PREC_FP32_PLAIN, with_bias=bool(case % 2)), label="one row per pixel %d" % case)
 
 
 # ---- which kernels the dispatcher picks ----------------------------------------------
@@ -435,3 +418,93 @@ def test_runs_on_a_side_stream():
         y = B.conv_forward(x, w, b, st, pad)
     s.synchronize()
     assert torch.equal(ref, y)
+
+
+# ---- the two orders of summation on inputs of graded magnitude -------------------------------------
+def _graded_layer_tensors(L, seed):
+    """Filter rows scaled 1e3, 1, 1e-3 and input rows scaled 1e-3, 1, 1e3 in turn: for every third output row the
+    result's own products w[t] x[i+t] are all of size 1 while products of other pairings of the same rows
+    (w[0] x[i+2]) are of size 1e6."""
+    x, w, b = synth.make_x(L, seed), synth.make_w(L, seed), synth.make_b(L, seed)
+    rows = torch.tensor([1e-3, 1.0, 1e3])[torch.arange(L["H"]) % 3]
+    x = (x * rows).contiguous()                      # last axis = rows (first index of the manual's arrays)
+    w = (w * torch.tensor([1e3, 1.0, 1e-3])).contiguous()
+    return x, w, b
+
+
+def test_summation_order_modes_on_graded_magnitudes():
+    """3x3 stride-1 layer whose filter rows and input rows span six orders of magnitude.  MCN_PREC_FP32_PLAIN must
+    meet the bars against each result's own sum of |w||x|.  The default order (pairs of output rows, four products per
+    filter column) is bounded by the sum over ALL pairings of the three filter rows with the three input rows of
+    the result's field (forward, dzdx) resp. by the sum of the normalisers of the three row taps of a filter
+    column (dzdw); against the result's own normaliser its error is reported, and is expected to be much larger."""
+    L = custom_layer(36, 20, 32, 4, 3, 3, 32, 64, (1, 1), (1, 1, 1, 1), idx=700)
+    st, pad = L["stride"], L["pad"]
+    x, w, b = _graded_layer_tensors(L, 0)
+    ho, wo = oracle.output_size(x.shape, w.shape, st, pad)
+    p = synth.make_dzdy(L, ho, wo)
+    p = (p * torch.tensor([1e3, 1.0, 1e-3])[torch.arange(ho) % 3]).contiguous()
+    xd, wd, bd, pd = U.np64(x), U.np64(w), U.np64(b), U.np64(p)
+    ref = {"y": oracle.forward(xd, wd, bd, st, pad), "dx": oracle.backward_data(x.shape, wd, pd, st, pad),
+           "dw": oracle.backward_filter(xd, w.shape, pd, st, pad)}
+    own = {"y": oracle.forward(np.abs(xd), np.abs(wd), np.abs(bd), st, pad),
+           "dx": oracle.backward_data(x.shape, np.abs(wd), np.abs(pd), st, pad),
+           "dw": oracle.backward_filter(np.abs(xd), w.shape, np.abs(pd), st, pad)}
+    # every filter row replaced by the sum of the three rows' absolute values: all pairings of rows
+    wsum = np.broadcast_to(np.abs(wd).sum(axis=3, keepdims=True), wd.shape).copy()
+    cross = {"y": oracle.forward(np.abs(xd), wsum, np.abs(bd), st, pad),
+             "dx": oracle.backward_data(x.shape, wsum, np.abs(pd), st, pad),
+             "dw": np.broadcast_to(own["dw"].sum(axis=3, keepdims=True), own["dw"].shape).copy()}
+    xg, wg, bg, pg = U.gpu(x), U.gpu(w), U.gpu(b), U.gpu(p)
+    report = {}
+    for prec in (B.MCN_PREC_FP32, B.MCN_PREC_FP32_PLAIN):
+        d = B.make_desc(x.shape, w.shape, st, pad, prec)
+        names = [B.mcn_conv_kernel_name(d, op) for op in range(3)]
+        assert names == (["igemm_f23", "igemm", "wgrad_f23"] if prec == B.MCN_PREC_FP32 else ["igemm", "igemm", "wgrad_igemm"])
+        got = {"y": B.conv_forward(xg, wg, bg, st, pad, prec), "dx": B.conv_backward_data(x.shape, wg, pg, st, pad, prec),
+               "dw": B.conv_backward_filter(xg, w.shape, pg, st, pad, prec)}
+        torch.cuda.synchronize()
+        for k in got:
+            g = got[k].cpu().numpy()
+            report[(prec, k)] = (U.norm_err(g, ref[k], own[k]), U.norm_err(g, ref[k], cross[k]))
+    for (prec, k), (e_own, e_cross) in sorted(report.items()):
+        print("graded magnitudes, precision %d, %s: error / own sum %.2e, / sum over all row pairings %.2e" % (prec, k, e_own, e_cross), flush=True)
+    for k, tol in (("y", U.TOL_FWD), ("dx", U.TOL_BWD), ("dw", U.TOL_BWD)):
+        assert report[(B.MCN_PREC_FP32_PLAIN, k)][0] <= tol, (k, report)
+        assert report[(B.MCN_PREC_FP32, k)][1] <= tol, (k, report)
+    # the input derivative of this layer (32 channels) runs on the one-row kernel in both modes
+    assert report[(B.MCN_PREC_FP32, "dx")][0] <= U.TOL_BWD
+
+
+def test_summation_order_modes_on_graded_magnitudes_wide():
+    """The same with more than 32 channels per group, so that the input derivative takes the row-pair kernel too."""
+    L = custom_layer(24, 16, 48, 3, 3, 3, 48, 64, (1, 1), (1, 1, 1, 1), idx=701)
+    st, pad = L["stride"], L["pad"]
+    x, w, b = _graded_layer_tensors(L, 1)
+    ho, wo = oracle.output_size(x.shape, w.shape, st, pad)
+    p = synth.make_dzdy(L, ho, wo)
+    p = (p * torch.tensor([1e3, 1.0, 1e-3])[torch.arange(ho) % 3]).contiguous()
+    wd, pd = U.np64(w), U.np64(p)
+    ref = oracle.backward_data(x.shape, wd, pd, st, pad)
+    own = oracle.backward_data(x.shape, np.abs(wd), np.abs(pd), st, pad)
+    wsum = np.broadcast_to(np.abs(wd).sum(axis=3, keepdims=True), wd.shape).copy()
+    cross = oracle.backward_data(x.shape, wsum, np.abs(pd), st, pad)
+    wg, pg = U.gpu(w), U.gpu(p)
+    d = B.make_desc(x.shape, w.shape, st, pad)
+    assert B.mcn_conv_kernel_name(d, 1) == "igemm_f23"
+    dx = B.conv_backward_data(x.shape, wg, pg, st, pad).cpu().numpy()
+    dxp = B.conv_backward_data(x.shape, wg, pg, st, pad, B.MCN_PREC_FP32_PLAIN).cpu().numpy()
+    e = (U.norm_err(dx, ref, own), U.norm_err(dx, ref, cross), U.norm_err(dxp, ref, own))
+    print("graded magnitudes, dzdx: default order %.2e of own sum, %.2e of all pairings; plain order %.2e of own sum" % e, flush=True)
+    assert e[1] <= U.TOL_BWD and e[2] <= U.TOL_BWD
+
+
+def test_batches_of_more_than_two_gibibytes():
+    """Arrays of 2^31 bytes or more (under 2^31 elements) run on the matrix-core kernels: offsets inside the kernels
+    are relative to an image.  Results at sampled places, dzdw and dzdb everywhere."""
+    L = custom_layer(64, 64, 16, 8400, 3, 3, 16, 16, (1, 1), (1, 1, 1, 1), idx=710)
+    assert 4 * L["H"] * L["W"] * L["D"] * L["N"] > (1 << 31)
+    d = B.make_desc(synth.x_shape(L), synth.w_shape(L), L["stride"], L["pad"])
+    names = [B.mcn_conv_kernel_name(d, op) for op in range(4)]
+    assert "direct" not in names, names
+    U.assert_errors(U.run_layer_sampled(L, n_filt=None), label="2.2 GB arrays %r" % names)

@@ -162,3 +162,22 @@ def test_pool_ties_select_the_first_maximum():
     assert B.mcn_pool_backward(d, None, p.data_ptr(), out.data_ptr(), None, 0, torch.cuda.current_stream().cuda_stream) == 0
     torch.cuda.synchronize()
     assert np.allclose(out.cpu().numpy(), oracle_pool.backward(x.cpu().numpy(), p.cpu().numpy(), (2, 2), (1, 1), (0, 0, 0, 0), "avg"))
+
+
+LARGE_PLANES = [
+    # planes whose flat index times the plane height passes 2^32: the split of a thread's index into row and column
+    # must still be exact.  H  W  D  N  window  stride  pad  method
+    (2240, 2240, 1, 1, (3, 3), (2, 2), (0, 1, 0, 1), "max"),      # overlapping windows: the two-kernel derivative
+    (2240, 2240, 1, 1, (2, 2), (2, 2), (0, 0, 0, 0), "max"),      # windows that do not overlap: one pass
+    (3000, 3001, 1, 1, (3, 2), (3, 2), (1, 0, 0, 1), "avg"),
+    (1500, 6000, 1, 2, (2, 3), (1, 2), (1, 1, 2, 0), "max"),
+    (40000, 40, 1, 1, (5, 3), (4, 1), (0, 0, 1, 1), "avg"),       # a plane taller than 32767 rows
+]
+
+
+@pytest.mark.parametrize("case", range(len(LARGE_PLANES)))
+def test_pool_large_planes(case):
+    H, W, D, N, win, st, pad, m = LARGE_PLANES[case]
+    e = run_pool(player(H, W, D, N, win, st, pad, m, 300 + case))
+    print("large plane", case, "%.2e %.2e" % e, flush=True)
+    assert e[0] <= U.TOL_FWD and e[1] <= U.TOL_BWD
