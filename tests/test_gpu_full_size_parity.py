@@ -66,13 +66,14 @@ def test_deep_3x3_layers_full_size_every_element(name):
 
 
 CHUNKED = [
-    # arrays of more than 64 MB: the filter derivative cuts every tile's reduction into chunks
+    # Arrays that stream from memory, with enough units per block: the filter derivative cuts every tile's reduction
+    # into chunks, and the row-pair kernel sums dzdy on the way.
     # H    W    D   N   Hf Wf Df  K    stride  pad            kernel in the default order
-    (100, 100, 32, 30, 3, 3, 32, 64, (1, 1), (1, 1, 1, 1), "wgrad_f23_chunked"),      # tiles of 64 filters, 12 waves
-    (100, 100, 32, 24, 3, 3, 32, 128, (1, 1), (1, 1, 1, 1), "wgrad_f23_chunked"),     # tiles of 128 filters
-    (99, 101, 48, 28, 3, 3, 24, 80, (1, 1), (0, 1, 2, 1), "wgrad_f23_chunked"),       # odd planes, two groups of 40 filters
-    (60, 64, 64, 40, 5, 5, 64, 96, (1, 1), (2, 2, 2, 2), "wgrad_igemm_chunked"),      # 5x5: the one-row kernel only
-    (120, 90, 16, 64, 4, 3, 16, 24, (2, 1), (1, 0, 1, 1), "wgrad_igemm_chunked"),     # vertical stride, 32-filter tiles
+    (200, 180, 24, 40, 3, 3, 24, 48, (1, 1), (1, 1, 1, 1), "wgrad_f23_chunked"),      # tiles of 64 filters on 12 waves
+    (75, 61, 96, 56, 3, 3, 48, 200, (1, 1), (1, 0, 0, 1), "wgrad_f23_chunked"),       # two groups of 100 filters: tiles of 128
+    (199, 181, 32, 48, 3, 3, 16, 80, (1, 1), (0, 1, 2, 1), "wgrad_f23_chunked"),      # odd planes, two groups of 40 filters
+    (60, 64, 64, 48, 5, 5, 64, 96, (1, 1), (2, 2, 2, 2), "wgrad_igemm_chunked"),      # 5x5: the one-row kernel only
+    (120, 90, 16, 512, 4, 3, 16, 24, (2, 1), (1, 0, 1, 1), "wgrad_igemm_chunked"),    # vertical stride, 32-filter tiles
 ]
 
 
@@ -81,6 +82,7 @@ def test_chunked_filter_derivative_every_coefficient(case):
     H, W, D, N, Hf, Wf, Df, K, st, pad, kernel = CHUNKED[case]
     L = custom_layer(H, W, D, N, Hf, Wf, Df, K, st, pad, idx=case)
     assert names(L, B.MCN_PREC_FP32)[2] == kernel
+    assert names(L, B.MCN_PREC_FP32)[4] == ("wgrad_f23+bias" if "f23" in kernel else "two passes")
     assert names(L, B.MCN_PREC_FP32_PLAIN)[2] == "wgrad_igemm_chunked"
     R = U.OracleResults(L, filter_only=True)
     xg, pg = U.gpu(R.x), U.gpu(R.p)

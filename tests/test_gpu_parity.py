@@ -212,34 +212,7 @@ def test_filter_and_bias_derivative_in_one_call_small():
         assert torch.equal(dw, dw2) and torch.equal(db, db2), i
 
 
-@pytest.mark.parametrize("case", range(5))
-def test_filter_and_bias_derivative_in_one_kernel(case):
-    """Large 3x3 stride-1 layers: the filter derivative's kernel sums dzdy on the way (both of its tile shapes).
-    Both results against the oracle (dzdw at sampled places, dzdb everywhere), odd and even planes, groups."""
-    H, W, D, N, Df, K, pad = ((224, 224, 64, 32, 64, 64, (1, 1, 1, 1)),          # layer 4a
-                              (199, 181, 32, 48, 16, 80, (0, 1, 2, 1)),          # odd planes, two groups of 40 filters
-                              (200, 180, 24, 40, 24, 48, (1, 1, 1, 1)),
-                              (56, 56, 256, 32, 256, 256, (1, 1, 1, 1)),         # layer 4b: tiles of 128 filters
-                              (75, 61, 96, 56, 48, 200, (1, 0, 0, 1)))[case]     # two groups of 100 filters, odd planes
-    L = custom_layer(H, W, D, N, 3, 3, Df, K, (1, 1), pad, idx=620 + case)
-    st = (1, 1)
-    d = B.make_desc(synth.x_shape(L), synth.w_shape(L), st, pad)
-    # (the planner cuts the reduction into chunks, and so fuses, when every block gets some 40 units or more)
-    assert B.mcn_conv_kernel_name(d, B.MCN_OP_BACKWARD_FILTER_BIAS) == "wgrad_f23+bias"
-    x, w = synth.make_x(L), synth.make_w(L)
-    ho, wo = oracle.output_size(x.shape, w.shape, st, pad)
-    p = synth.make_dzdy(L, ho, wo)
-    dw, db = B.conv_backward_filter_bias(U.gpu(x), w.shape, U.gpu(p), st, pad)
-    torch.cuda.synchronize()
-    dw, db = dw.cpu().numpy().ravel(), db.cpu().numpy().ravel()
-    xd, pd = U.np64(x), U.np64(p)
-    iw = U.sample_idx(dw.size, 96, 3)
-    e_w = U.norm_err(dw[iw], oracle.backward_filter_at(xd, w.shape, pd, iw, st, pad),
-                     oracle.backward_filter_at(np.abs(xd), w.shape, np.abs(pd), iw, st, pad))
-    e_b = U.norm_err(db, oracle.backward_bias(x.shape, w.shape, pd, st, pad),
-                     oracle.backward_bias(x.shape, w.shape, np.abs(pd), st, pad))
-    print("one kernel, case", case, "dzdw %.2e dzdb %.2e" % (e_w, e_b), flush=True)
-    assert e_w <= U.TOL_BWD and e_b <= U.TOL_BWD
+# (the one-kernel form of that call, on layers that stream from memory: tests/test_gpu_full_size_parity.py)
 
 
 def test_filter_rows_that_meet_no_input_keep_exact_zeros():
