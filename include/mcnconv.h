@@ -98,7 +98,9 @@ typedef enum mcn_status {
     MCN_UNSUPPORTED = 5,         /* an array has 2^31 elements or more                  */
     MCN_HIP_ERROR = 6,           /* a launch failed; see mcn_last_hip_error()           */
     MCN_CROP_TOO_LARGE = 7,      /* convolution transpose: the crops leave no output     */
-    MCN_PAD_TOO_LARGE = 8        /* pooling: a pad exceeds window - 1 (Sec. 5.2.1)       */
+    MCN_PAD_TOO_LARGE = 8,       /* pooling: a pad exceeds window - 1 (Sec. 5.2.1)       */
+    MCN_STATIC_SCRATCH_EXCEEDED = 9  /* mcn_conv_backward_bias_static: the geometry needs more
+                                    than MCN_STATIC_SCRATCH_BYTES of scratch            */
 } mcn_status;
 
 enum { MCN_OP_FORWARD = 0, MCN_OP_BACKWARD_DATA = 1, MCN_OP_BACKWARD_FILTER = 2, MCN_OP_BACKWARD_BIAS = 3,
@@ -144,6 +146,20 @@ int mcn_conv_backward_filter_bias(const mcn_conv_desc *desc, const float *x, con
  * dzdb[k] = sum_{i'',j'',n} dzdy[i'',j'',k,n].  Writes K values. */
 int mcn_conv_backward_bias(const mcn_conv_desc *desc, const float *dzdy, float *dzdb,
                            void *ws, size_t ws_bytes, void *stream);
+
+/* For callers that cannot allocate device memory or hold a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  The same result as
+ * mcn_conv_backward_bias, bit for bit (same kernels, same order of additions), with the partial
+ * sums kept in a buffer of MCN_STATIC_SCRATCH_BYTES that is part of the library's code object on
+ * every GPU it runs on (held until the process ends).  The call allocates nothing and frees
+ * nothing; its first call on a device looks the buffer's address up (no allocation either;
+ * make that call outside a graph capture).  Geometries that need more scratch (K * H''W'' above
+ * 262144 for output planes under 64 samples, or more than about 260000 filters) return
+ * MCN_STATIC_SCRATCH_EXCEEDED before any GPU work.  All calls on one GPU share the one buffer:
+ * calls that may overlap there (different streams, different threads) race; calls on one
+ * stream are ordered and safe.  Nothing in the buffer has to be cleared between calls. */
+#define MCN_STATIC_SCRATCH_BYTES (1 << 20)
+int mcn_conv_backward_bias_static(const mcn_conv_desc *desc, const float *dzdy, float *dzdb, void *stream);
 
 /* ------------------------------------------------------------------------
  * Convolution followed by the ReLU block (Sec. 4.4, y = max{0, p}), fused

@@ -20,6 +20,8 @@ LIB_PATH = os.path.join(_HERE, "libmcnconv.so")
 
 MCN_OK, MCN_BAD_ARG, MCN_BAD_GROUPS, MCN_FILTER_TOO_LARGE = 0, 1, 2, 3
 MCN_WORKSPACE_TOO_SMALL, MCN_UNSUPPORTED, MCN_HIP_ERROR, MCN_CROP_TOO_LARGE, MCN_PAD_TOO_LARGE = 4, 5, 6, 7, 8
+MCN_STATIC_SCRATCH_EXCEEDED = 9
+MCN_STATIC_SCRATCH_BYTES = 1 << 20
 MCN_POOL_MAX, MCN_POOL_AVG = 0, 1
 MCN_OP_FORWARD, MCN_OP_BACKWARD_DATA, MCN_OP_BACKWARD_FILTER, MCN_OP_BACKWARD_BIAS = 0, 1, 2, 3
 MCN_OP_BACKWARD_FILTER_BIAS = 4
@@ -33,7 +35,7 @@ EXPORTS = (
     "mcn_convt_output_size", "mcn_convt_workspace_size", "mcn_convt_forward", "mcn_convt_backward_data",
     "mcn_convt_backward_filter", "mcn_convt_backward_bias", "mcn_convt_kernel_name",
     "mcn_pool_output_size", "mcn_pool_workspace_size", "mcn_pool_forward", "mcn_pool_backward",
-    "mcn_probe_mfma", "mcn_probe_copy",
+    "mcn_probe_mfma", "mcn_probe_copy", "mcn_conv_backward_bias_static",
 )
 MCN_PROBE_SINK_FLOATS = 2048 * 256
 
@@ -89,6 +91,8 @@ def lib():
         L.mcn_conv_backward_bias.argtypes = [D, P, P, P, SZ, P]
         L.mcn_conv_backward_filter_bias.argtypes = [D, P, P, P, P, P, SZ, P]
         L.mcn_conv_backward_filter_bias.restype = ctypes.c_int
+        L.mcn_conv_backward_bias_static.argtypes = [D, P, P, P]
+        L.mcn_conv_backward_bias_static.restype = ctypes.c_int
         L.mcn_status_string.argtypes = [ctypes.c_int]
         L.mcn_status_string.restype = ctypes.c_char_p
         L.mcn_last_hip_error.restype = ctypes.c_int
@@ -174,6 +178,10 @@ def mcn_conv_backward_filter_bias(desc, x, dzdy, dzdw, dzdb, ws, ws_bytes, strea
 
 def mcn_conv_backward_bias(desc, dzdy, dzdb, ws, ws_bytes, stream):
     return lib().mcn_conv_backward_bias(ctypes.byref(desc), dzdy, dzdb, ws, ws_bytes, stream)
+
+
+def mcn_conv_backward_bias_static(desc, dzdy, dzdb, stream):
+    return lib().mcn_conv_backward_bias_static(ctypes.byref(desc), dzdy, dzdb, stream)
 
 
 def mcn_conv_relu_forward(desc, x, w, b, y, ws, ws_bytes, stream):

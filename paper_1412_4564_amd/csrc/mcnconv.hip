@@ -5,6 +5,7 @@
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
+#include <mutex>
 
 #include "../../include/mcnconv.h"
 #include "geom.h"
@@ -658,6 +659,46 @@ int mcn_conv_backward_bias(const mcn_conv_desc *desc, const float *dzdy, float *
     return run_backward_bias(g.Ho * g.Wo, g.K, g.N, dzdy, dzdb, ws, ws_bytes, (hipStream_t)stream);
 }
 
+// ---- the bias derivative for callers that cannot allocate ------------------------------------
+// Its partial sums go to an array that is part of the library's code object, so that the call needs neither a
+// workspace argument nor an allocation.  In host code the array's name is only a handle: its address on the
+// current device is asked once per device (hipGetSymbolAddress) and kept.
+static __device__ __align__(256) float scratch[MCN_STATIC_SCRATCH_BYTES / sizeof(float)];
+
+namespace {
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_mutex;
+float *g_scratch_ptr[MAX_DEVICES];      // per device: where `scratch` lives there (NULL until first asked)
+
+// Address of `scratch` on the current device; NULL (and the HIP error recorded) on failure.
+float *static_scratch() {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e == hipSuccess && (dev < 0 || dev >= MAX_DEVICES)) e = hipErrorInvalidDevice;
+    if (e != hipSuccess) { g_last_hip_error = (int)e; return nullptr; }
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) { g_last_hip_error = (int)(e != hipSuccess ? e : hipErrorInvalidSymbol); return nullptr; }
+        g_scratch_ptr[dev] = (float *)p;
+    }
+    return g_scratch_ptr[dev];
+}
+}  // namespace
+
+int mcn_conv_backward_bias_static(const mcn_conv_desc *desc, const float *dzdy, float *dzdb, void *stream) {
+    Geom g;
+    int st = make_geom(desc, &g);
+    if (st) return st;
+    if (!dzdy || !dzdb) return MCN_BAD_ARG;
+    if (plan_bias(g).ws_floats * sizeof(float) > (size_t)MCN_STATIC_SCRATCH_BYTES) return MCN_STATIC_SCRATCH_EXCEEDED;
+    float *ptr = static_scratch();
+    if (!ptr) return MCN_HIP_ERROR;
+    // every partial sum the second stage reads is written by the first: nothing in the array needs clearing
+    return run_backward_bias(g.Ho * g.Wo, g.K, g.N, dzdy, dzdb, ptr, MCN_STATIC_SCRATCH_BYTES, (hipStream_t)stream);
+}
+
 // ---- convolution + ReLU ------------------------------------------------------------------
 
 int mcn_conv_relu_forward(const mcn_conv_desc *desc, const float *x, const float *w, const float *b, float *y,
@@ -907,6 +948,7 @@ const char *mcn_status_string(int status) {
         case MCN_HIP_ERROR: return "HIP launch error";
         case MCN_CROP_TOO_LARGE: return "crops leave no output";
         case MCN_PAD_TOO_LARGE: return "pooling pad larger than window - 1";
+        case MCN_STATIC_SCRATCH_EXCEEDED: return "the call needs more scratch than the library's static buffer holds";
         default: return "unknown status";
     }
 }

@@ -331,3 +331,17 @@ def test_environment_override_of_the_summation_order():
     r = subprocess.run([sys.executable, "-c", script, root], env=dict(os.environ, MCN_NO_WINO="1"), capture_output=True,
                        text=True, timeout=120)
     assert r.returncode == 0 and r.stdout.strip() == "igemm,igemm,wgrad_igemm_chunked", (r.stdout, r.stderr[-500:])
+
+
+def test_static_scratch_entry_point_rejects_what_does_not_fit():
+    """mcn_conv_backward_bias_static checks the descriptor, the pointers and the size of its fixed buffer on the host,
+    before anything touches a GPU."""
+    # 1x1 output planes with 300000 filters: one row of K values per partial sum exceeds the 1 MiB buffer
+    d = B.make_desc((4, 2, 1, 1), (300000, 2, 1, 1))
+    assert B.mcn_conv_workspace_size(d, B.MCN_OP_BACKWARD_BIAS) > B.MCN_STATIC_SCRATCH_BYTES
+    assert B.mcn_conv_backward_bias_static(d, 16, 16, None) == B.MCN_STATIC_SCRATCH_EXCEEDED
+    d = B.make_desc((4, 2, 8, 8), (6, 2, 3, 3))
+    assert B.mcn_conv_backward_bias_static(d, None, 16, None) == B.MCN_BAD_ARG
+    d.stride_h = 0
+    assert B.mcn_conv_backward_bias_static(d, 16, 16, None) == B.MCN_BAD_ARG
+    assert b"static buffer" in B.lib().mcn_status_string(B.MCN_STATIC_SCRATCH_EXCEEDED)
