@@ -29,30 +29,68 @@ BF16_MFMA_PEAK_TFLOPS = 2500.0    # dense bf16 MFMA (kernels named *_bf16 run on
 HBM_PEAK_GBS = 8000.0
 
 WORKLOADS = {"vgg3x3": ["4a", "4b", "4c"]}
-TRAFFIC_FILE = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "vgg3x3_hbm_traffic.txt")
-
+ROOT = os.path.dirname(os.path.abspath(__file__))
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "vgg3x3_hbm_traffic.txt")
+MFMA_FILE = os.path.join(ROOT, "profiles", "vgg3x3_mfma_counters.txt")
 
 FUSED_AWAY = "(with backward_filter)"      # 'kernel' of a call that is not made: its result came with another's
 
+# The roof that bounds each layer's three matrix passes (the bias derivative is always a stream from memory): the
+# 3-channel first layers, the 1x1 layer and the tiny irregular layer move more bytes than the matrix core can be
+# kept busy with; the fully-connected layer is priced against both.
+BOUND = {"1": "hbm", "2a": "hbm", "3a": "hbm", "5b": "hbm", "5c": "hbm"}
+
+
+def sources_id():
+    """Identifies the kernel sources a counter summary under profiles/ was taken from: the summaries carry the
+    same figure, and a summary of other sources is not quoted."""
+    import hashlib
+    h = hashlib.sha256()
+    d = os.path.join(ROOT, "paper_1412_4564_amd", "csrc")
+    for name in sorted(os.listdir(d)):
+        if name.endswith((".h", ".hip")):
+            with open(os.path.join(d, name), "rb") as f:
+                h.update(name.encode() + b"\0" + f.read())
+    return h.hexdigest()[:16]
+
+
+def profile_lines(path):
+    """Lines of a committed counter summary, or [] if it is absent or was taken from other kernel sources
+    (line 'SOURCES <id>')."""
+    try:
+        with open(path) as f:
+            lines = [l.split() for l in f]
+    except OSError:
+        return []
+    if not any(len(t) == 2 and t[0] == "SOURCES" and t[1] == sources_id() for t in lines):
+        return []
+    return lines
+
 
 def issued_share(kernel):
-    """Flops the matrix core executes per flop of the plain sum: the *_f23 kernels take the three row taps of a
-    3x3 filter for two output rows with four products instead of six."""
+    """Flops the matrix core executes per flop of the plain sum, by arithmetic: the *_f23 kernels take the three
+    row taps of a 3x3 filter for two output rows with four products instead of six.  (Padding of channel and
+    filter counts to tile sizes comes on top; the counter summary, where there is one, has the measured figure.)"""
     return 2.0 / 3.0 if "_f23" in kernel else 1.0
+
+
+def measured_mfma(call):
+    """(flops the matrix core executed, its busy fraction) for one call, from the committed summary of a
+    rocprofv3 --pmc run of this benchmark (lines 'CALL <layer>.<operation> <mfma flops> <busy fraction>'),
+    or None."""
+    for t in profile_lines(MFMA_FILE):
+        if len(t) == 4 and t[0] == "CALL" and t[1] == call:
+            return float(t[2]), float(t[3])
+    return None
 
 
 def measured_traffic(call):
     """HBM bytes (fetch + write) of one call, from the committed summary of the two rocprofv3 --pmc
     runs of this benchmark (lines 'TOTAL <layer>.<operation> <fetch bytes> <write bytes>'); None if
-    the summary does not hold the call."""
-    try:
-        with open(TRAFFIC_FILE) as f:
-            for line in f:
-                t = line.split()
-                if len(t) == 4 and t[0] == "TOTAL" and t[1] == call:
-                    return int(float(t[2]) + float(t[3]))
-    except OSError:
-        pass
+    the summary does not hold the call or is stale."""
+    for t in profile_lines(TRAFFIC_FILE):
+        if len(t) == 4 and t[0] == "TOTAL" and t[1] == call:
+            return int(float(t[2]) + float(t[3]))
     return None
 
 
@@ -105,6 +143,20 @@ class LayerState:
     def shape_info(self):
         L = self.L
         return {"x_HWDN": [L["H"], L["W"], L["D"], L["N"]], "w_HWDK": [L["Hf"], L["Wf"], L["Df"], L["K"]]}
+
+    def with_precision(self, precision):
+        """The same layer on the same device arrays under another MCN_PREC_* value."""
+        import copy
+        o = copy.copy(self)
+        o.prec = precision
+        o.desc = B.make_desc(self.x.shape, self.w.shape, self.st, self.pad, precision)
+        o.kernels = [B.mcn_conv_kernel_name(o.desc, op) for op in range(4)]
+        o.fused_bias = B.mcn_conv_kernel_name(o.desc, B.MCN_OP_BACKWARD_FILTER_BIAS) == "wgrad_f23+bias"
+        if o.fused_bias:
+            o.kernels[2], o.kernels[3] = "wgrad_f23+bias", FUSED_AWAY
+        ws = max(B.mcn_conv_workspace_size(o.desc, op) for op in range(5))
+        o.ws = torch.empty(max(ws, 16), dtype=torch.uint8, device="cuda")
+        return o
 
     def run(self, op, stream):
         d, ws, n = self.desc, self.ws.data_ptr(), self.ws.numel()
@@ -344,13 +396,111 @@ def cpu_baseline(names):
             "sample": "fwd+bwd of layers " + ", ".join(desc) + " (fp64 loop nest, %.1f s)" % secs}
 
 
+def time_calls(layers, stream_obj, steps, warmup):
+    """(seconds per step, ms per call [layer, op]) for the step 'every operation of every layer': `warmup` untimed
+    steps, exactly `steps` timed ones between two synchronisations, then the same steps again with an event after
+    every call (a separate pass, so that the event records do not perturb the first figure)."""
+    stream = stream_obj.cuda_stream
+    calls = [(li, op) for li, Ls in enumerate(layers) for op in range(len(Ls.op_names))]
+
+    def step(events=None):
+        for li, op in calls:
+            layers[li].run(op, stream)
+            if events is not None:
+                ev = torch.cuda.Event(enable_timing=True)
+                ev.record(stream_obj)
+                events.append(ev)
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    per = np.zeros((len(layers), 4))
+    for _ in range(steps):
+        start = torch.cuda.Event(enable_timing=True)
+        start.record(stream_obj)
+        evs = []
+        step(evs)
+        torch.cuda.synchronize()
+        prev = start
+        for (li, op), ev in zip(calls, evs):
+            per[li, op] += prev.elapsed_time(ev)
+            prev = ev
+    return elapsed / steps, per / steps
+
+
+def call_report(Ls, op, ms):
+    """One call: kernel, time, the rates of the plain sum and of what the matrix core executes, and the fraction
+    of the roof that bounds it."""
+    kernel = Ls.kernels[op]
+    e = {"kernel": kernel, "ms": round(float(ms), 4)}
+    if kernel == FUSED_AWAY:
+        return e
+    e["GBps"] = round(Ls.bytes[op] / ms / 1e6, 1)
+    matrix_pass = op < 3 and Ls.macs and len(Ls.op_names) == 4
+    if matrix_pass:
+        tf = 2.0 * Ls.macs / ms / 1e9
+        e["TFLOPs"] = round(tf, 2)
+        e["issued_TFLOPs"] = round(issued_share(kernel) * tf, 2)
+    bound = "mfma" if matrix_pass and BOUND.get(Ls.name, "mfma") == "mfma" else "hbm"
+    e["bound"] = bound
+    if bound == "mfma":
+        peak = BF16_MFMA_PEAK_TFLOPS if "bf16" in kernel else FP32_MFMA_PEAK_TFLOPS
+        e["frac"] = round(e["issued_TFLOPs"] / peak, 4)
+    else:
+        e["frac"] = round(e["GBps"] / HBM_PEAK_GBS, 4)
+    return e
+
+
+def all_layers_report(stream_obj, precision, have, reps=10):
+    """Every layer of the synthetic workloads, one call at a time, outside the timed region: `reps` launches of the
+    call between two events.  Activations rotate through copies of at least 600 MiB in all (the last-level cache
+    holds 256 MB), so a launch is not served from the cache by the launch before it."""
+    stream = stream_obj.cuda_stream
+    out = {}
+    for name in synth.LAYERS:
+        Ls = have.get(name)
+        mine = Ls is None
+        if mine:
+            Ls = LayerState(name, synth.LAYERS[name], precision, rotate_mb=600)
+        for op in range(4):
+            if Ls.kernels[op] == FUSED_AWAY:
+                out["%s.%s" % (name, OPS[op])] = {"kernel": FUSED_AWAY}
+                continue
+            # warm-up: at least 20 ms of this very call, so that the clock has left its idle state (the layer's
+            # inputs were just generated on the host; the first launches after a pause run some 15 % slower)
+            t0 = time.perf_counter()
+            while True:
+                for _ in range(5):
+                    Ls.run(op, stream); Ls.turn += 1
+                torch.cuda.synchronize()
+                if time.perf_counter() - t0 > 0.02:
+                    break
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream_obj)
+            for _ in range(reps):
+                Ls.run(op, stream); Ls.turn += 1
+            e1.record(stream_obj)
+            torch.cuda.synchronize()
+            out["%s.%s" % (name, OPS[op])] = call_report(Ls, op, e0.elapsed_time(e1) / reps)
+        if mine:
+            del Ls
+            torch.cuda.empty_cache()
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="vgg3x3", help="vgg3x3 or comma-separated layer names (e.g. 2b,3b)")
-    ap.add_argument("--precision", default="fp32", choices=["fp32", "bf16"])
+    ap.add_argument("--precision", default="fp32", choices=["fp32", "fp32-plain", "bf16"],
+                    help="fp32: the library's default order of summation; fp32-plain: MCN_PREC_FP32_PLAIN")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--rotate-mb", type=int, default=0,
                     help="rotate each layer's activations through copies totalling at least this many MiB "
@@ -360,6 +510,10 @@ def main():
                          "'fused_relu' in the JSON line)")
     ap.add_argument("--no-ceilings", action="store_true",
                     help="skip the measured ceilings (register-only MFMA loops, plain copy) in 'measured_ceilings'")
+    ap.add_argument("--no-all-layers", action="store_true",
+                    help="skip the per-call table of all twelve workload layers ('all_layers')")
+    ap.add_argument("--no-plain-leg", action="store_true",
+                    help="skip the second timed leg in the plain order of summation ('value_plain_order')")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 256 MiB elementwise copy three times, so that a counter run "
                          "(rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE) holds a kernel of known traffic to scale by")
@@ -371,50 +525,17 @@ def main():
         sys.exit("bench.py: no GPU visible")
     torch.cuda.set_device(0)
     names = WORKLOADS.get(args.workload) or args.workload.split(",")
-    prec = B.MCN_PREC_BF16 if args.precision == "bf16" else B.MCN_PREC_FP32
+    prec = {"fp32": B.MCN_PREC_FP32, "fp32-plain": B.MCN_PREC_FP32_PLAIN, "bf16": B.MCN_PREC_BF16}[args.precision]
+    fp32 = prec != B.MCN_PREC_BF16
+    headline = args.workload == "vgg3x3"
     layers = [make_state(n, prec, args.rotate_mb) for n in names]
     stream_obj = torch.cuda.current_stream()
-    stream = stream_obj.cuda_stream
 
-    calls = [(li, op) for li, Ls in enumerate(layers) for op in range(len(Ls.op_names))]
-
-    def step(events=None):
-        for li, op in calls:
-            layers[li].run(op, stream)
-            if events is not None:
-                ev = torch.cuda.Event(enable_timing=True)
-                ev.record(stream_obj)
-                events.append(ev)
-
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-
-    # timed region: exactly --steps steps
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-
-    # per-call durations with events on the launch stream (a second, separately timed pass of the same steps,
-    # so that the event records do not perturb the headline number)
-    per = np.zeros((len(layers), 4))
-    for _ in range(args.steps):
-        start = torch.cuda.Event(enable_timing=True)
-        start.record(stream_obj)
-        evs = []
-        step(evs)
-        torch.cuda.synchronize()
-        prev = start
-        for (li, op), ev in zip(calls, evs):
-            per[li, op] += prev.elapsed_time(ev)
-            prev = ev
-    per /= args.steps     # ms per call
+    sec_per_step, per = time_calls(layers, stream_obj, args.steps, args.warmup)
 
     flops_step = sum(3 * 2.0 * Ls.macs for Ls in layers)      # pooling layers count no flops
-    ms_per_step = 1e3 * elapsed / args.steps
-    value = flops_step / (elapsed / args.steps) / 1e12
+    ms_per_step = 1e3 * sec_per_step
+    value = flops_step / sec_per_step / 1e12
 
     # dominant kernel: the call that takes the most time per step
     li, op = np.unravel_index(np.argmax(per), per.shape)
@@ -423,48 +544,57 @@ def main():
     issued_step = 0.0        # flops the matrix core executes per step (see issued_share)
     for i, Ls in enumerate(layers):
         for o in range(len(Ls.op_names)):
-            ms = per[i, o]
-            e = {"kernel": Ls.kernels[o], "ms": round(float(ms), 4)}
-            if Ls.kernels[o] != FUSED_AWAY:
-                e["GBps"] = round(Ls.bytes[o] / ms / 1e6, 1)
-            if o < 3 and Ls.macs:
-                e["TFLOPs"] = round(2.0 * Ls.macs / ms / 1e9, 2)
-                if issued_share(Ls.kernels[o]) != 1.0:
-                    e["issued_TFLOPs"] = round(issued_share(Ls.kernels[o]) * 2.0 * Ls.macs / ms / 1e9, 2)
+            detail["%s.%s" % (Ls.name, Ls.op_names[o])] = call_report(Ls, o, per[i, o])
+            if o < 3 and Ls.macs and Ls.kernels[o] != FUSED_AWAY:
                 issued_step += issued_share(Ls.kernels[o]) * 2.0 * Ls.macs
-            detail["%s.%s" % (Ls.name, Ls.op_names[o])] = e
-    OPS_dom = dom.op_names
+    dom_call = "%s.%s" % (dom.name, dom.op_names[op])
+    traffic = measured_traffic(dom_call) if headline and prec == B.MCN_PREC_FP32 else None
     if op < 3 and dom.macs:
-        ach = 2.0 * dom.macs / per[li, op] / 1e9
+        # 'achieved' = the flops the matrix core executes for the call (what its peak bounds); 'algorithmic_equiv' =
+        # the flops of the sum as the paper writes it, 2 * MACs (the *_f23 kernels execute two thirds of them)
+        equiv = 2.0 * dom.macs / per[li, op] / 1e9
         peak = BF16_MFMA_PEAK_TFLOPS if "bf16" in dom.kernels[op] else FP32_MFMA_PEAK_TFLOPS
-        # 'achieved' counts the flops of the sum as the paper writes it; 'issued' those the MFMAs of this kernel
-        # execute for it (two thirds in the *_f23 kernels), which is what the matrix core's peak bounds
-        share = issued_share(dom.kernels[op])
-        roof = {"bound": "mfma", "achieved": round(ach, 2), "peak": peak, "unit": "TFLOP/s",
-                "frac": round(ach / peak, 4), "issued": round(share * ach, 2), "frac_issued": round(share * ach / peak, 4),
-                "traffic": measured_traffic("%s.%s" % (dom.name, OPS_dom[op])) if args.workload == "vgg3x3" and prec == B.MCN_PREC_FP32 else None,
-                "kernel": "%s.%s (%s)" % (dom.name, OPS_dom[op], dom.kernels[op])}
+        ach, source = issued_share(dom.kernels[op]) * equiv, "arithmetic (2/3 of 2*MACs for *_f23 kernels, else all)"
+        counters = measured_mfma(dom_call) if headline and prec == B.MCN_PREC_FP32 else None
+        if counters:
+            ach, source = counters[0] / per[li, op] / 1e9, "profiles/vgg3x3_mfma_counters.txt (SQ_INSTS_VALU_MFMA_MOPS_F32)"
+        roof = {"bound": "mfma", "achieved": round(ach, 2), "peak": peak, "unit": "TFLOP/s", "frac": round(ach / peak, 4),
+                "achieved_source": source, "algorithmic_equiv": round(equiv, 2), "traffic": traffic,
+                "kernel": "%s (%s)" % (dom_call, dom.kernels[op])}
+        if counters:
+            roof["mfma_busy_frac"] = counters[1]
     else:
         ach = dom.bytes[op] / per[li, op] / 1e6
         roof = {"bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(ach / HBM_PEAK_GBS, 4),
-                "traffic": measured_traffic("%s.%s" % (dom.name, OPS_dom[op])) if args.workload == "vgg3x3" and prec == B.MCN_PREC_FP32 else None,
-                "kernel": "%s.%s (%s)" % (dom.name, OPS_dom[op], dom.kernels[op])}
+                "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": traffic, "kernel": "%s (%s)" % (dom_call, dom.kernels[op])}
 
+    issued_tflops = issued_step / sec_per_step / 1e12
     out = {
-        "metric": "conv fwd+bwd TFLOP/s (%s) on VGG-style 3x3 layers" % ("fp32" if prec == B.MCN_PREC_FP32 else "bf16 operands, fp32 accumulation"),
+        "metric": "conv fwd+bwd TFLOP/s (%s) on VGG-style 3x3 layers" % ("fp32" if fp32 else "bf16 operands, fp32 accumulation"),
         "value": round(value, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32" if prec == B.MCN_PREC_FP32 else "bf16-in/f32-acc", "data": "synthetic",
+        "dtype": "f32" if fp32 else "bf16-in/f32-acc", "data": "synthetic",
         "config": {"workload": "conv fwd+bwd (dzdx, dzdw, dzdb) of layers " + ",".join(names) +
-                               " (3x3 stride 1 pad 1, N=32)" if args.workload == "vgg3x3" else
+                               " (3x3 stride 1 pad 1, N=32)" if headline else
                                "conv fwd+bwd of layers " + ",".join(names),
+                   "summation_order": "plain" if prec == B.MCN_PREC_FP32_PLAIN else "default",
                    "layers": {Ls.name: Ls.shape_info() for Ls in layers}},
-        "frac_of_fp32_mfma_peak": round(value / FP32_MFMA_PEAK_TFLOPS, 4) if prec == B.MCN_PREC_FP32 else None,
-        "mfma_issued_TFLOPs": round(issued_step / (elapsed / args.steps) / 1e12, 3),
+        # 'value' counts 2 * MACs of the plain sum; the matrix core executes fewer flops for it in the *_f23 kernels:
+        "mfma_issued_TFLOPs": round(issued_tflops, 3),
+        "mfma_issued_frac_of_peak": round(issued_tflops / (FP32_MFMA_PEAK_TFLOPS if fp32 else BF16_MFMA_PEAK_TFLOPS), 4),
         "roofline": roof,
         "calls": detail,
     }
+    if prec == B.MCN_PREC_FP32 and not args.no_plain_leg and all(n in synth.LAYERS for n in names):
+        # second timed leg: the same step with every product of the paper's sum formed and added one by one
+        plain = [Ls.with_precision(B.MCN_PREC_FP32_PLAIN) for Ls in layers]
+        sec_plain, per_plain = time_calls(plain, stream_obj, args.steps, args.warmup)
+        out["value_plain_order"] = round(flops_step / sec_plain / 1e12, 3)
+        out["ms_per_step_plain_order"] = round(1e3 * sec_plain, 4)
+        out["plain_order_frac_of_peak"] = round(flops_step / sec_plain / 1e12 / FP32_MFMA_PEAK_TFLOPS, 4)
+        out["calls_plain_order"] = {"%s.%s" % (Ls.name, Ls.op_names[o]): call_report(Ls, o, per_plain[i, o])
+                                    for i, Ls in enumerate(plain) for o in range(4)}
+        del plain
     if not args.no_ceilings:
         # outside the timed region: what the chip sustains, so that the fraction of the published peak in
         # 'roofline' can be read beside the fraction of a ceiling measured on this very GPU
@@ -475,6 +605,10 @@ def main():
         roof["frac_of_measured_ceiling"] = round(roof["achieved"] / top, 4)
     if args.fused_relu:
         out["fused_relu"] = fused_relu_report(layers, stream_obj, args.steps)
+    if not args.no_all_layers and headline and fp32:
+        # layers whose activations exceed the last-level cache need no rotation: their state is reused
+        big = {Ls.name: Ls for Ls in layers if 4 * (Ls.x.numel() + Ls.p.numel()) >= (256 << 20)}
+        out["all_layers"] = all_layers_report(stream_obj, prec, big)
     if args.copy_calibration:
         src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device="cuda")
         dst = torch.empty_like(src)

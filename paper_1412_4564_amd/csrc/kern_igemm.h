@@ -173,6 +173,23 @@ __device__ __host__ inline int sk_virtual_block(int b, int nblocks) {
 __device__ __host__ inline long long sk_begin(long long total, int nblocks, int vb) {
     return total * vb / nblocks;
 }
+// The same value for many vb at the price of one 64-bit division (which takes a GPU thread some hundred
+// instructions): with total = q * nblocks + r,  total * vb / nblocks = q * vb + r * vb / nblocks, and r * vb stays
+// below nblocks^2 (nblocks <= 65535), a 32-bit division.
+struct SkSplit {
+    long long q;
+    unsigned r, n;
+};
+__device__ __host__ inline SkSplit sk_split(long long total, int nblocks) {
+    SkSplit s;
+    s.q = total / nblocks;
+    s.r = (unsigned)(total - s.q * nblocks);
+    s.n = (unsigned)nblocks;
+    return s;
+}
+__device__ __host__ inline long long sk_begin(const SkSplit &s, int vb) {
+    return s.q * vb + (long long)(s.r * (unsigned)vb / s.n);
+}
 // Rank of virtual block vb among the nshare sharing blocks (in virtual order), or -1; and its inverse.  With
 // nshare < nblocks (both multiples of 8) the sharing blocks are hardware ids 0 .. nshare-1, i.e. the first
 // nshare/8 virtual blocks of each XCD's run of nblocks/8.
@@ -842,12 +859,13 @@ __global__ __launch_bounds__(256) void igemm_fixup_kernel(IgemmParams P, const f
     const int j = blockIdx.x + 1;                    // boundary between sharing blocks j-1 and j (by rank)
     const int tile_s0 = P.own * P.nblocks;           // the shared tiles start here; unit numbers are relative to them
     const long long total = (long long)(P.tiles - tile_s0) * P.NU;
-    const long long B = sk_begin(total, P.nshare, j);
+    const SkSplit split = sk_split(total, P.nshare);
+    const long long B = sk_begin(split, j);
     const int ts = (int)(B / P.NU);
     const int t = tile_s0 + ts;
     const long long t_lo = (long long)ts * P.NU, t_hi = t_lo + P.NU;
     if (B == t_lo) return;                                        // boundary on a tile edge: nothing shared
-    if (sk_begin(total, P.nshare, j - 1) > t_lo) return;          // an earlier boundary owns this tile
+    if (sk_begin(split, j - 1) > t_lo) return;                    // an earlier boundary owns this tile
     int kt, pt, rb, g;
     decode_tile(P, t, &kt, &pt, &rb, &g);
     const int OHW = P.OH * P.OW;
@@ -859,9 +877,9 @@ __global__ __launch_bounds__(256) void igemm_fixup_kernel(IgemmParams P, const f
     if (threadIdx.x == 0) {
         int n = 0;
         for (int b = j - 1; b < P.nshare && n < MAX_PIECES; ++b) {
-            const long long bb = sk_begin(total, P.nshare, b);
+            const long long bb = sk_begin(split, b);
             if (bb >= t_hi) break;
-            if (sk_begin(total, P.nshare, b + 1) == bb) continue;       // a block without shared units wrote nothing
+            if (sk_begin(split, b + 1) == bb) continue;                  // a block without shared units wrote nothing
             slots[n++] = 2 * sk_share_block(P.nblocks, P.nshare, b) + (bb >= t_lo ? 0 : 1);
         }
         npieces = n;

@@ -528,84 +528,104 @@ __global__ __launch_bounds__(64 * (WK * WR + WGRAD_LOADER_WAVES), WPE) void wgra
     }
 }
 
-// Sum the pieces of every tile shared between blocks and write the tile.  The order of the
-// additions is fixed: piece i goes to partial sum i mod 8, the partial sums are added as a
-// balanced tree.  blockIdx.x = tile; one block = 64 results x 8 partial sums.
-template <int TK, int TR>
+// Sum the pieces of every tile shared between blocks and write the tile.  blockIdx.x = tile, blockIdx.y = a
+// slice of the tile's results.  The order of the additions is fixed by the plan: with G = 512 / Q partial sums
+// per result (a power of two chosen on the host from the number of pieces), piece i goes to partial sum i mod G
+// and the G sums are added as a balanced tree.  A thread handles four consecutive coefficients of one filter
+// (one 16-byte load per piece, four pieces in flight); rows and columns of the tile beyond the filters and
+// coefficients that exist are skipped, so a layer whose coefficients fill a fraction of a tile reads that
+// fraction of every piece.
+// CHUNKED: the pieces of tile t are the first slots of blocks t + tiles*i, i < nchunks; else those of the blocks
+// whose equal ranges of units overlap the tile.
+template <int TK, int TR, bool CHUNKED>
 __global__ __launch_bounds__(512) void wgrad_fixup_kernel(WgradParams P, const float *__restrict__ part,
-                                                          const float *__restrict__ rbias, float *__restrict__ out) {
+                                                          const float *__restrict__ rbias, float *__restrict__ out,
+                                                          int G) {
     const int t = blockIdx.x;
-    const long long total = (long long)P.tiles * P.NU;
-    const long long t_lo = (long long)t * P.NU, t_hi = t_lo + P.NU;
-    // first block with units of this tile
-    int b0 = (int)(t_lo * P.nblocks / total);
-    while (b0 + 1 < P.nblocks && sk_begin(total, P.nblocks, b0 + 1) <= t_lo) ++b0;
-    while (b0 > 0 && sk_begin(total, P.nblocks, b0) > t_lo) --b0;
-    const long long b0_lo = sk_begin(total, P.nblocks, b0);
-    if (sk_begin(total, P.nblocks, b0 + 1) >= t_hi) return;      // computed by one block alone: already written
-    int b_last = b0 + 1;
-    while (b_last + 1 < P.nblocks && sk_begin(total, P.nblocks, b_last + 1) < t_hi) ++b_last;
-    const int npieces = b_last - b0 + 1;
-    // block b0's piece is its first one if it starts with this tile, else its last; the others start inside the tile
-    const int slot0 = 2 * b0 + (b0_lo >= t_lo ? 0 : 1);
+    int npieces, slot0 = 0, b0 = 0;
+    if constexpr (CHUNKED) {
+        npieces = P.nchunks;
+    } else {
+        // Block b holds the units [total*b/nblocks, total*(b+1)/nblocks).  The first and the last block with units
+        // of this tile follow from two divisions (and at most a step of correction each); one thread finds them.
+        __shared__ int found[3];
+        if (threadIdx.x == 0) {
+            const long long total = (long long)P.tiles * P.NU;
+            const long long t_lo = (long long)t * P.NU, t_hi = t_lo + P.NU;
+            const SkSplit split = sk_split(total, P.nblocks);
+            int first = (int)(t_lo * P.nblocks / total);
+            while (first + 1 < P.nblocks && sk_begin(split, first + 1) <= t_lo) ++first;
+            while (first > 0 && sk_begin(split, first) > t_lo) --first;
+            int last = (int)((t_hi - 1) * P.nblocks / total);
+            while (last + 1 < P.nblocks && sk_begin(split, last + 1) < t_hi) ++last;
+            while (last > first && sk_begin(split, last) >= t_hi) --last;
+            found[0] = first;
+            found[1] = last - first + 1;
+            // the first block's piece is its first one if it starts with this tile, else its last; the others start inside the tile
+            found[2] = 2 * first + (sk_begin(split, first) >= t_lo ? 0 : 1);
+        }
+        __syncthreads();
+        b0 = found[0]; npieces = found[1]; slot0 = found[2];
+        if (npieces < 2) return;      // computed by one block alone: already written
+    }
+    auto slot_of = [&](int i) { return CHUNKED ? 2 * (t + P.tiles * i) : (i == 0 ? slot0 : 2 * (b0 + i)); };
     int tt = t;
     const int rt = tt % P.RT; tt /= P.RT;
     const int kt = tt % P.KT;
     const int g = tt / P.KT;
     const int klim = min(P.Kg - kt * TK, TK);
-    __shared__ float red[8][64];
-    const int el = threadIdx.x & 63, pg = threadIdx.x >> 6;
-    for (int e0 = blockIdx.y * 64; e0 < TK * TR; e0 += gridDim.y * 64) {
-        const int e = e0 + el;
-        float acc = 0.f;
-        for (int i = pg; i < npieces; i += 8) {
-            const int slot = i == 0 ? slot0 : 2 * (b0 + i);
-            acc += part[(size_t)slot * (TK * TR) + e];
+    const int rlim = min(P.R - rt * TR, TR);           // coefficients of the tile that exist
+    const int C4 = (rlim + 3) >> 2;                     // 16-byte words per filter row that hold any of them
+    const int nwords = klim * C4;
+    const int Q = 512 / G;                              // words per block and pass
+    const int q = threadIdx.x % Q, pg = threadIdx.x / Q;
+    __shared__ float4 red[512];
+    for (int w0 = blockIdx.y * Q; w0 < nwords; w0 += gridDim.y * Q) {
+        const int w = w0 + q;
+        const bool valid = w < nwords;
+        const int kloc = valid ? w / C4 : 0, c4 = valid ? w - kloc * C4 : 0;
+        const float *src = part + (size_t)kloc * TR + 4 * c4;
+        float4 acc = {0.f, 0.f, 0.f, 0.f};
+        if (valid) {
+            int i = pg;
+            for (; i + 3 * G < npieces; i += 4 * G) {
+                const float4 v0 = *reinterpret_cast<const float4 *>(src + (size_t)slot_of(i) * (TK * TR));
+                const float4 v1 = *reinterpret_cast<const float4 *>(src + (size_t)slot_of(i + G) * (TK * TR));
+                const float4 v2 = *reinterpret_cast<const float4 *>(src + (size_t)slot_of(i + 2 * G) * (TK * TR));
+                const float4 v3 = *reinterpret_cast<const float4 *>(src + (size_t)slot_of(i + 3 * G) * (TK * TR));
+                acc.x += v0.x; acc.y += v0.y; acc.z += v0.z; acc.w += v0.w;
+                acc.x += v1.x; acc.y += v1.y; acc.z += v1.z; acc.w += v1.w;
+                acc.x += v2.x; acc.y += v2.y; acc.z += v2.z; acc.w += v2.w;
+                acc.x += v3.x; acc.y += v3.y; acc.z += v3.z; acc.w += v3.w;
+            }
+            for (; i < npieces; i += G) {
+                const float4 v = *reinterpret_cast<const float4 *>(src + (size_t)slot_of(i) * (TK * TR));
+                acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+            }
         }
-        red[pg][el] = acc;
-        __syncthreads();
-        if (pg == 0) {
-            const int kloc = e / TR, rl = e - kloc * TR;
-            const int r = rt * TR + rl;
-            if (kloc < klim && r < P.R) {
-                float v = ((red[0][el] + red[1][el]) + (red[2][el] + red[3][el])) +
-                          ((red[4][el] + red[5][el]) + (red[6][el] + red[7][el]));
-                if (rbias) v += rbias[r];
-                if (P.relu) v = fmaxf(v, 0.f);
-                out[(size_t)(g * P.Kg + kt * TK + kloc) * P.R + r] = v;
+        red[pg * Q + q] = acc;
+        // balanced tree over the G partial sums: the sums pg and pg + h are added, h = G/2, G/4, ..., 1
+        for (int h = G >> 1; h >= 1; h >>= 1) {
+            __syncthreads();
+            if (pg < h) {
+                const float4 a = red[pg * Q + q], c = red[(pg + h) * Q + q];
+                red[pg * Q + q] = float4{a.x + c.x, a.y + c.y, a.z + c.z, a.w + c.w};
             }
         }
         __syncthreads();
-    }
-}
-
-// The same for the chunked schedule: the pieces of tile t are the first slots of blocks t + tiles*i.
-template <int TK, int TR>
-__global__ __launch_bounds__(512) void wgrad_chunk_fixup_kernel(WgradParams P, const float *__restrict__ part,
-                                                                const float *__restrict__ rbias, float *__restrict__ out) {
-    const int t = blockIdx.x;
-    int tt = t;
-    const int rt = tt % P.RT; tt /= P.RT;
-    const int kt = tt % P.KT;
-    const int g = tt / P.KT;
-    const int klim = min(P.Kg - kt * TK, TK);
-    __shared__ float red[8][64];
-    const int el = threadIdx.x & 63, pg = threadIdx.x >> 6;
-    for (int e0 = blockIdx.y * 64; e0 < TK * TR; e0 += gridDim.y * 64) {
-        const int e = e0 + el;
-        float acc = 0.f;
-        for (int i = pg; i < P.nchunks; i += 8) acc += part[(size_t)(2 * (t + P.tiles * i)) * (TK * TR) + e];
-        red[pg][el] = acc;
-        __syncthreads();
-        if (pg == 0) {
-            const int kloc = e / TR, rl = e - kloc * TR;
-            const int r = rt * TR + rl;
-            if (kloc < klim && r < P.R) {
-                float v = ((red[0][el] + red[1][el]) + (red[2][el] + red[3][el])) +
-                          ((red[4][el] + red[5][el]) + (red[6][el] + red[7][el]));
-                if (rbias) v += rbias[r];
-                if (P.relu) v = fmaxf(v, 0.f);
-                out[(size_t)(g * P.Kg + kt * TK + kloc) * P.R + r] = v;
+        if (pg == 0 && valid) {
+            const float4 v4 = red[q];
+            const float vv[4] = {v4.x, v4.y, v4.z, v4.w};
+            float *o = out + (size_t)(g * P.Kg + kt * TK + kloc) * P.R + rt * TR;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int rl = 4 * c4 + j;
+                if (rl < rlim) {
+                    float v = vv[j];
+                    if (rbias) v += rbias[rt * TR + rl];
+                    if (P.relu) v = fmaxf(v, 0.f);
+                    o[rl] = v;
+                }
             }
         }
         __syncthreads();

@@ -286,6 +286,27 @@ int launch_igemm(const IgemmPlan &pl, const float *in, const float *w, const flo
     }
 }
 
+// The pass that adds the pieces of the tiles shared between blocks (kern_wgrad.h).  G partial sums per result: about
+// the number of pieces per tile, at most 32; about 1024 blocks in all, none without work.
+template <int TK, int TR>
+int launch_wgrad_fixup(const WgradParams &P, const float *part, const float *rbias, float *out, hipStream_t s) {
+    const bool chunked = P.nchunks > 0;
+    const long long pieces = chunked ? P.nchunks : ((long long)P.nblocks + P.tiles - 1) / P.tiles + 1;
+    int G = 2;
+    while (G < 32 && G < pieces) G *= 2;
+    const int Q = 512 / G;
+    const int klim = P.Kg < TK ? P.Kg : TK, rlim = P.R < TR ? P.R : TR;
+    const int passes = (klim * ((rlim + 3) / 4) + Q - 1) / Q;      // of the largest tile
+    int fy = 1024 / P.tiles;
+    if (fy < 1) fy = 1;
+    if (fy > passes) fy = passes;
+    if (chunked)
+        hipLaunchKernelGGL((wgrad_fixup_kernel<TK, TR, true>), dim3(P.tiles, fy), dim3(512), 0, s, P, part, rbias, out, G);
+    else
+        hipLaunchKernelGGL((wgrad_fixup_kernel<TK, TR, false>), dim3(P.tiles, fy), dim3(512), 0, s, P, part, rbias, out, G);
+    return check_launch();
+}
+
 // dzdb != NULL (BIAS instantiations only): the bias derivative is computed on the way (kern_wgrad.h); its partial
 // sums follow the partial tiles in the workspace
 template <int WK, int WR, int MK, int MR, bool S1, bool WINO = false, int WPE = 4, bool BIAS = false>
@@ -314,15 +335,7 @@ int launch_wgrad_inst2(const WgradPlan &pl, const float *x, const float *dzdy, c
     }
     if (st || P.nblocks < 2 || P.nchunks == 1) return st;
     constexpr int TK = WK * MK * 32, TR = WR * MR * 32 * (WINO ? 3 : 1);     // coefficients per tile
-    // at most nblocks - 1 tiles are shared, but which ones is cheaper to find per tile
-    int fy = 2048 / pl.P.tiles;          // about 2048 blocks in all
-    if (fy < 1) fy = 1;
-    if (fy > TK * TR / 64) fy = TK * TR / 64;
-    if (chunked)
-        hipLaunchKernelGGL((wgrad_chunk_fixup_kernel<TK, TR>), dim3(P.tiles, fy), dim3(512), 0, s, P, part, rbias, out);
-    else
-        hipLaunchKernelGGL((wgrad_fixup_kernel<TK, TR>), dim3(P.tiles, fy), dim3(512), 0, s, P, part, rbias, out);
-    return check_launch();
+    return launch_wgrad_fixup<TK, TR>(P, part, rbias, out, s);
 }
 
 template <int WK, int WR, int MK, int MR>
