@@ -562,7 +562,7 @@ def main():
                 "achieved_source": source, "algorithmic_equiv": round(equiv, 2), "traffic": traffic,
                 "kernel": "%s (%s)" % (dom_call, dom.kernels[op])}
         if counters:
-            roof["mfma_busy_frac"] = counters[1]
+            roof["profiled_mfma_util"] = counters[1]
     else:
         ach = dom.bytes[op] / per[li, op] / 1e6
         roof = {"bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
