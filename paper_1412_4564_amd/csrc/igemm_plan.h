@@ -129,7 +129,9 @@ inline ConvView fc_backward_filter_view(const Geom &g) {
 }
 
 // IG_W*: the WINO kernels (filters x pairs of output rows)
-enum IgemmShape { IG_128x256 = 0, IG_64x512 = 1, IG_32x256 = 2, IG_64x256 = 3, IG_W128x128 = 4, IG_W64x256 = 5, IG_NONE = -1 };
+// IG_96x256: eight waves of 96 filters x 32 pixels each, for 65 to 96 filters per group (a quarter fewer MFMAs than 128-filter tiles)
+enum IgemmShape { IG_128x256 = 0, IG_64x512 = 1, IG_32x256 = 2, IG_64x256 = 3, IG_W128x128 = 4, IG_W64x256 = 5, IG_96x256 = 6,
+                  IG_NONE = -1 };
 
 struct IgemmPlan {
     int shape;          // IgemmShape
@@ -233,6 +235,7 @@ inline bool plan_igemm_kind(const ConvView &v, int n_cu, IgemmPlan *pl, bool bf1
     if (wino && v.Kg > 64) { shape = IG_W128x128; WK = 2; WP = 4; MK = 2; MP = 1; }
     else if (wino) { shape = IG_W64x256; WK = 1; WP = 8; MK = 2; MP = 1; }
     else if (two) { shape = IG_64x256; WK = 1; WP = 4; MK = 2; MP = 2; }
+    else if (!bf16 && v.Kg > 64 && v.Kg <= 96) { shape = IG_96x256; WK = 1; WP = 8; MK = 3; MP = 1; }
     else if (v.Kg > 64) { shape = IG_128x256; WK = 2; WP = 4; MK = 2; MP = 2; }
     else if (v.Kg > 32) { shape = IG_64x512; WK = 1; WP = 8; MK = 2; MP = 2; }
     else { shape = IG_32x256; WK = 1; WP = 4; MK = 1; MP = 2; }
@@ -281,7 +284,9 @@ inline bool plan_igemm_kind(const ConvView &v, int n_cu, IgemmPlan *pl, bool bf1
         const int RB = (v.Ho + TI - 1) / TI;
         const int64_t QN = (int64_t)TI * v.Wo * v.N;
         const int64_t PT = (QN + TQ - 1) / TQ;
-        const double mfma_waste = (double)RB * PT * TQ / ((double)v.Ho * v.Wo * v.N);
+        // rows of pixel tiles and of filter tiles that compute nothing
+        const double mfma_waste = (double)RB * PT * TQ / ((double)v.Ho * v.Wo * v.N) *
+                                  (double)((v.Kg + TK - 1) / TK * TK) / (double)v.Kg;
         const int NCG = (v.Cg + uc.DC - 1) / uc.DC;
         const double red_waste = (double)NCG * uc.NTR * uc.NS * (bf16 ? BF_DC : 2) / ((double)v.Cg * T);
         // when the input streams from memory, short slab rows waste most of every 128-byte line they touch
@@ -429,7 +434,9 @@ inline bool plan_igemm(const ConvView &v, int n_cu, IgemmPlan *pl, bool bf16 = f
 namespace mcn {
 
 // WG_W*: the WINO kernels (filters x (filter column, channel) pairs)
-enum WgradShape { WG_128x128 = 0, WG_64x192 = 1, WG_32x256 = 2, WG_W128x128 = 3, WG_W64x192 = 4 };
+// WG_96x128, WG_96x384: 65 to 96 filters per group; the second on 12 computing waves, for filters of more than 256
+// coefficients per group (one tile then holds 384 of them and dzdy is staged once for all)
+enum WgradShape { WG_128x128 = 0, WG_64x192 = 1, WG_32x256 = 2, WG_W128x128 = 3, WG_W64x192 = 4, WG_96x128 = 5, WG_96x384 = 6 };
 
 struct WgradPlan {
     int shape;
@@ -461,6 +468,8 @@ inline bool plan_wgrad(const ConvView &v, int n_cu, WgradPlan *pl, bool wino = f
     int shape, WK, WR, MK, MR;
     if (wino && v.Kg > 64) { shape = WG_W128x128; WK = 2; WR = 4; MK = 2; MR = 1; }
     else if (wino) { shape = WG_W64x192; WK = 2; WR = 6; MK = 1; MR = 1; }     // 12 computing waves, one tile each per set
+    else if (v.Kg > 64 && v.Kg <= 96 && R > 256) { shape = WG_96x384; WK = 3; WR = 4; MK = 1; MR = 3; }
+    else if (v.Kg > 64 && v.Kg <= 96) { shape = WG_96x128; WK = 1; WR = 4; MK = 3; MR = 1; }
     else if (v.Kg > 64) { shape = WG_128x128; WK = 2; WR = 2; MK = 2; MR = 2; }
     else if (v.Kg > 32) { shape = WG_64x192; WK = 2; WR = 2; MK = 1; MR = 3; }
     else { shape = WG_32x256; WK = 1; WR = 4; MK = 1; MR = 2; }

@@ -178,7 +178,8 @@ int launch_igemm_inst(const IgemmPlan &pl, const float *in, const float *wpk, co
     }
     hipLaunchKernelGGL(kern, dim3(P.nblocks), dim3(64 * (WK * WP + LW)), pl.lds_bytes, s, P, in, wpk, bias, out, part);
     int st = check_launch();
-    if (st || P.nblocks < 2 || P.own * P.nblocks == P.tiles) return st;      // no tile is shared
+    // no tile is shared; tiles of a single unit cannot be cut, so every block's range holds whole tiles
+    if (st || P.nblocks < 2 || P.own * P.nblocks == P.tiles || P.NU == 1) return st;
     constexpr int TK = WK * MK * 32, TQ = WP * MP * 32;
     hipLaunchKernelGGL((igemm_fixup_kernel<TK, TQ>), dim3(P.nshare - 1, 16), dim3(256), 0, s, P, part, bias, out);
     return check_launch();
@@ -229,7 +230,8 @@ int launch_igemm_bf16_inst(const IgemmPlan &pl, const float *in, const float *wp
     }
     hipLaunchKernelGGL(kern, dim3(P.nblocks), dim3(64 * (WK * WP + LW)), pl.lds_bytes, s, P, in, wpk, bias, out, part);
     int st = check_launch();
-    if (st || P.nblocks < 2 || P.own * P.nblocks == P.tiles) return st;      // no tile is shared
+    // no tile is shared; tiles of a single unit cannot be cut, so every block's range holds whole tiles
+    if (st || P.nblocks < 2 || P.own * P.nblocks == P.tiles || P.NU == 1) return st;
     constexpr int TK = WK * MK * 32, TQ = WP * MP * 32;
     hipLaunchKernelGGL((igemm_fixup_kernel<TK, TQ>), dim3(P.nshare - 1, 16), dim3(256), 0, s, P, part, bias, out);
     return check_launch();
@@ -280,6 +282,7 @@ int launch_igemm(const IgemmPlan &pl, const float *in, const float *w, const flo
         case IG_64x512: return launch_igemm_fixed<1, 8, 2, 2>(pl, in, packed, bias, out, part, s, relu);
         case IG_32x256: return launch_igemm_fixed<1, 4, 1, 2>(pl, in, packed, bias, out, part, s, relu);
         case IG_64x256: return launch_igemm_fixed<1, 4, 2, 2>(pl, in, packed, bias, out, part, s, relu);
+        case IG_96x256: return launch_igemm_fixed<1, 8, 3, 1>(pl, in, packed, bias, out, part, s, relu);
         case IG_W128x128: return launch_igemm_wino<2, 4, 2>(pl, in, packed, bias, out, part, s, relu);
         case IG_W64x256: return launch_igemm_wino<1, 8, 2>(pl, in, packed, bias, out, part, s, relu);
         default: return MCN_BAD_ARG;
@@ -363,6 +366,8 @@ int launch_wgrad(const WgradPlan &pl, const float *x, const float *dzdy, const f
         case WG_128x128: return launch_wgrad_inst<2, 2, 2, 2>(pl, x, dzdy, rbias, out, part, s, relu);
         case WG_64x192: return launch_wgrad_inst<2, 2, 1, 3>(pl, x, dzdy, rbias, out, part, s, relu);
         case WG_32x256: return launch_wgrad_inst<1, 4, 1, 2>(pl, x, dzdy, rbias, out, part, s, relu);
+        case WG_96x128: return launch_wgrad_inst<1, 4, 3, 1>(pl, x, dzdy, rbias, out, part, s, relu);
+        case WG_96x384: return launch_wgrad_inst<3, 4, 1, 3>(pl, x, dzdy, rbias, out, part, s, relu);
         case WG_W128x128: return launch_wgrad_inst2<2, 4, 2, 1, true, true, 3>(pl, x, dzdy, rbias, out, part, s, relu);
         case WG_W64x192: return launch_wgrad_inst2<2, 6, 1, 1, true, true, 4>(pl, x, dzdy, rbias, out, part, s, relu);
         default: return MCN_BAD_ARG;
