@@ -69,9 +69,10 @@ def profile_lines(path):
 
 def issued_share(kernel):
     """Flops the matrix core executes per flop of the plain sum, by arithmetic: the *_f23 kernels take the three
-    row taps of a 3x3 filter for two output rows with four products instead of six.  (Padding of channel and
-    filter counts to tile sizes comes on top; the counter summary, where there is one, has the measured figure.)"""
-    return 2.0 / 3.0 if "_f23" in kernel else 1.0
+    row taps of a 3x3 filter for two output rows with four products instead of six; the bf16x3 kernels form every
+    product from three bf16 products.  (Padding of channel and filter counts to tile sizes comes on top; the
+    counter summary, where there is one, has the measured figure.)"""
+    return 2.0 / 3.0 if "_f23" in kernel else 3.0 if "bf16x3" in kernel else 1.0
 
 
 def measured_mfma(call):
@@ -499,7 +500,7 @@ def main():
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="vgg3x3", help="vgg3x3 or comma-separated layer names (e.g. 2b,3b)")
-    ap.add_argument("--precision", default="fp32", choices=["fp32", "fp32-plain", "bf16"],
+    ap.add_argument("--precision", default="fp32", choices=["fp32", "fp32-plain", "bf16", "bf16x3"],
                     help="fp32: the library's default order of summation; fp32-plain: MCN_PREC_FP32_PLAIN")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--rotate-mb", type=int, default=0,
@@ -525,7 +526,8 @@ def main():
         sys.exit("bench.py: no GPU visible")
     torch.cuda.set_device(0)
     names = WORKLOADS.get(args.workload) or args.workload.split(",")
-    prec = {"fp32": B.MCN_PREC_FP32, "fp32-plain": B.MCN_PREC_FP32_PLAIN, "bf16": B.MCN_PREC_BF16}[args.precision]
+    prec = {"fp32": B.MCN_PREC_FP32, "fp32-plain": B.MCN_PREC_FP32_PLAIN, "bf16": B.MCN_PREC_BF16,
+            "bf16x3": B.MCN_PREC_FP32_BF16X3}[args.precision]
     fp32 = prec != B.MCN_PREC_BF16
     headline = args.workload == "vgg3x3"
     layers = [make_state(n, prec, args.rotate_mb) for n in names]
@@ -573,7 +575,8 @@ def main():
         "metric": "conv fwd+bwd TFLOP/s (%s) on VGG-style 3x3 layers" % ("fp32" if fp32 else "bf16 operands, fp32 accumulation"),
         "value": round(value, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32" if fp32 else "bf16-in/f32-acc", "data": "synthetic",
+        "dtype": ("f32" if prec != B.MCN_PREC_FP32_BF16X3 else "f32 arrays, bf16x3 products, f32 accumulation") if fp32 else "bf16-in/f32-acc",
+        "data": "synthetic",
         "config": {"workload": "conv fwd+bwd (dzdx, dzdw, dzdb) of layers " + ",".join(names) +
                                " (3x3 stride 1 pad 1, N=32)" if headline else
                                "conv fwd+bwd of layers " + ",".join(names),
@@ -595,6 +598,15 @@ def main():
         out["calls_plain_order"] = {"%s.%s" % (Ls.name, Ls.op_names[o]): call_report(Ls, o, per_plain[i, o])
                                     for i, Ls in enumerate(plain) for o in range(4)}
         del plain
+        # third timed leg: fp32 arrays with the operands of forward / dzdx split into two bf16 planes on chip
+        # (MCN_PREC_FP32_BF16X3: three bf16 MFMAs per product, 16 significant bits, fp32 accumulation)
+        split = [Ls.with_precision(B.MCN_PREC_FP32_BF16X3) for Ls in layers]
+        sec_split, per_split = time_calls(split, stream_obj, args.steps, args.warmup)
+        out["value_bf16x3_operands"] = round(flops_step / sec_split / 1e12, 3)
+        out["ms_per_step_bf16x3_operands"] = round(1e3 * sec_split, 4)
+        out["calls_bf16x3_operands"] = {"%s.%s" % (Ls.name, Ls.op_names[o]): call_report(Ls, o, per_split[i, o])
+                                        for i, Ls in enumerate(split) for o in range(4)}
+        del split
     if not args.no_ceilings:
         # outside the timed region: what the chip sustains, so that the fraction of the published peak in
         # 'roofline' can be read beside the fraction of a ceiling measured on this very GPU

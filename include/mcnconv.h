@@ -82,9 +82,18 @@ typedef struct mcn_conv_desc {
  *   Geometries the bf16 kernels do not cover (fewer than 16 channels per group,
  *   fully-connected layers, the filter derivative with a vertical stride, more than 5 filter
  *   rows or at most 32 filters per group) compute in fp32, which meets the same bound.
+ * MCN_PREC_FP32_BF16X3: fp32 arrays, fp32 accumulation, and every operand of the forward pass and of
+ *   dzdx held on chip as TWO bf16 values, hi = bf16(v) and lo = bf16(v - hi) (16 bits of v's
+ *   significand), with each product formed as w_hi*x_hi + w_hi*x_lo + w_lo*x_hi on the bf16 matrix core
+ *   ("igemm_bf16x3").  Error per product below 1.2e-5 of |w||x| in the worst case, so the normalised
+ *   error stays under the fp32 bars (1e-4 forward, 1e-3 backward) with a margin of eight or more, and
+ *   measures about 1e-6; three bf16 MFMAs cost a fifth of one fp32 MFMA, which makes the two passes 2 to
+ *   2.5 times as fast as MCN_PREC_FP32 on the 3x3 layers.  For callers who would otherwise trade fp32 for
+ *   bf16 operands: this keeps 16 instead of 8 significant bits.  dzdw, dzdb and the geometries the bf16
+ *   kernels do not cover compute as under MCN_PREC_FP32.
  * The environment variable MCN_NO_WINO=1 (read once per process) makes MCN_PREC_FP32 behave as
  * MCN_PREC_FP32_PLAIN; it exists for benchmarks. */
-enum { MCN_PREC_FP32 = 0, MCN_PREC_BF16 = 1, MCN_PREC_FP32_PLAIN = 2 };
+enum { MCN_PREC_FP32 = 0, MCN_PREC_BF16 = 1, MCN_PREC_FP32_PLAIN = 2, MCN_PREC_FP32_BF16X3 = 3 };
 
 typedef enum mcn_status {
     MCN_OK = 0,

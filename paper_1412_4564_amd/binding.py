@@ -25,7 +25,7 @@ MCN_STATIC_SCRATCH_BYTES = 1 << 20
 MCN_POOL_MAX, MCN_POOL_AVG = 0, 1
 MCN_OP_FORWARD, MCN_OP_BACKWARD_DATA, MCN_OP_BACKWARD_FILTER, MCN_OP_BACKWARD_BIAS = 0, 1, 2, 3
 MCN_OP_BACKWARD_FILTER_BIAS = 4
-MCN_PREC_FP32, MCN_PREC_BF16, MCN_PREC_FP32_PLAIN = 0, 1, 2
+MCN_PREC_FP32, MCN_PREC_BF16, MCN_PREC_FP32_PLAIN, MCN_PREC_FP32_BF16X3 = 0, 1, 2, 3
 
 EXPORTS = (
     "mcn_conv_output_size", "mcn_conv_workspace_size", "mcn_conv_forward", "mcn_conv_backward_data",

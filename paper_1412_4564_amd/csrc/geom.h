@@ -28,7 +28,7 @@ inline int make_geom(const mcn_conv_desc *d, Geom *g) {
     if (d->Hf < 1 || d->Wf < 1 || d->Df < 1 || d->K < 1) return MCN_BAD_ARG;
     if (d->stride_h < 1 || d->stride_w < 1) return MCN_BAD_ARG;
     if (d->pad_top < 0 || d->pad_bottom < 0 || d->pad_left < 0 || d->pad_right < 0) return MCN_BAD_ARG;
-    if (d->precision != MCN_PREC_FP32 && d->precision != MCN_PREC_BF16 && d->precision != MCN_PREC_FP32_PLAIN) return MCN_BAD_ARG;
+    if (d->precision < MCN_PREC_FP32 || d->precision > MCN_PREC_FP32_BF16X3) return MCN_BAD_ARG;
     if (d->D % d->Df != 0) return MCN_BAD_GROUPS;
     const int G = d->D / d->Df;
     if (d->K % G != 0) return MCN_BAD_GROUPS;

@@ -136,6 +136,7 @@ enum IgemmShape { IG_128x256 = 0, IG_64x512 = 1, IG_32x256 = 2, IG_64x256 = 3, I
 struct IgemmPlan {
     int shape;          // IgemmShape
     bool bf16;          // operands rounded to bf16 (kern_igemm_bf16.h); sizes below are then in 32-bit words
+    int planes;         // bf16: 1, or 2 = operands split into hi and lo bf16 planes, three products each
     int fixed;          // index into IGEMM_FIXED: an instantiation with compile-time filter size (0 = none)
     int TK, TQ, NT;
     IgemmParams P;
@@ -208,12 +209,12 @@ inline bool cut_units(const ConvView &v, int TK, int64_t CP, size_t lds_left, Un
 
 // bf16 kernel: a unit is 16 channels x TC taps, one MFMA step per tap; the fewest tap ranges whose
 // double-buffered weights (TC*2*TK 16-byte words) and slab (2*CP words) fit.
-inline bool cut_units_bf16(const ConvView &v, int TK, int64_t CP, size_t lds_left, UnitCut *uc) {
+inline bool cut_units_bf16(const ConvView &v, int TK, int64_t CP, size_t lds_left, UnitCut *uc, int planes = 1) {
     const int T = v.Hf * v.Wf;
     for (int NTR = 1; NTR <= T; ++NTR) {
         const int TC = (T + NTR - 1) / NTR;
         if ((int64_t)(NTR - 1) * TC >= T) continue;
-        const size_t lds = 2 * ((size_t)TC * 2 * TK + 2 * (size_t)CP) * 16;
+        const size_t lds = 2 * ((size_t)TC * 2 * TK + 2 * (size_t)CP) * 16 * planes;
         if (lds > lds_left) continue;
         uc->pair_mode = 0; uc->DC = BF_DC; uc->TC = TC; uc->NTR = NTR; uc->NS = TC;
         return true;
@@ -223,7 +224,7 @@ inline bool cut_units_bf16(const ConvView &v, int TK, int64_t CP, size_t lds_lef
 
 // wino: `v` is the stride-2, four-tap view of pairs of output rows (wino_view) and wino_Ho the real number of rows
 inline bool plan_igemm_kind(const ConvView &v, int n_cu, IgemmPlan *pl, bool bf16, int fixed, bool two = false,
-                            int wino_Ho = 0) {
+                            int wino_Ho = 0, int planes = 1) {
     const int T = v.Hf * v.Wf;
     const bool wino = wino_Ho > 0;
     const IgemmFixed FX = wino ? IGEMM_WINO : IGEMM_FIXED[fixed];
@@ -271,7 +272,7 @@ inline bool plan_igemm_kind(const ConvView &v, int n_cu, IgemmPlan *pl, bool bf1
         UnitCut uc;
         if (bf16) {
             if (fixed_lds + 64 > lds_limit) continue;
-            if (!cut_units_bf16(v, TK, CP, lds_limit - fixed_lds - 64, &uc)) continue;
+            if (!cut_units_bf16(v, TK, CP, lds_limit - fixed_lds - 64, &uc, planes)) continue;
         } else if (fixed || wino) {
             uc.pair_mode = 0; uc.DC = FX.DC; uc.TC = T; uc.NTR = 1; uc.NS = (FX.DC / 2) * T;
             if ((2 * ((size_t)uc.NS * 2 * TK + 255) + 2 * (size_t)uc.DC * CP) * 4 + fixed_lds > lds_limit) continue;
@@ -293,6 +294,11 @@ inline bool plan_igemm_kind(const ConvView &v, int n_cu, IgemmPlan *pl, bool bf1
         // results are stored in column runs of TI samples: short runs are partial memory lines
         double score = mfma_waste * red_waste * (1.0 + 0.05 * (double)CP / TQ) *
                        (input_streams ? 1.0 + 4.0 / (double)SR : 1.0) * (1.0 + 2.0 / (double)TI);
+        // bf16 kernels: every tap range of a group of channels is a unit of its own (a barrier, a prologue of LDS
+        // reads); a smaller slab that leaves room for more taps per unit is worth a less regular row block
+        // (measured with split operands, same box: layer 4a with one tap range 0.41 against 0.50 ms with three;
+        // 4b with two 0.378 against 0.40 with three)
+        if (bf16) score *= 1.0 + 0.5 * (uc.NTR - 1);
         if (wino) {
             // The row-pair kernels issue fewer MFMAs per staged byte and per stored line, and what was measured on
             // them weighs differently: short slab rows cost little, column runs of results (2*TI samples) that are
@@ -353,17 +359,17 @@ inline bool plan_igemm_kind(const ConvView &v, int n_cu, IgemmPlan *pl, bool bf1
     P.dTI = make_div32(P.TI); P.dWo = make_div32(P.Wo); P.dWp = make_div32(P.Wp); P.dSRP = make_div32(P.SRP);
     P.dKT = make_div32(P.KT); P.dRB = make_div32(P.RB); P.dPT = make_div32(P.PT);
     // packed weights per unit, in 32-bit words: bf16 steps hold 2 octets x TK filters x 16 bytes
-    const size_t wsz = bf16 ? (size_t)P.NS * 2 * TK * 4 : ((size_t)P.NS * 2 * TK + 255) / 256 * 256;
+    const size_t wsz = bf16 ? (size_t)P.NS * planes * 2 * TK * 4 : ((size_t)P.NS * 2 * TK + 255) / 256 * 256;
     P.WSZ = (int)wsz;
     pl->packed_floats = (size_t)v.G * P.KT * P.NU * wsz;
     if (pl->packed_floats * 4 >= 2147483647ull) return false;
     P.packed_bytes = (unsigned)(pl->packed_floats * 4);
     // no workspace for partial tiles when no tile is shared
     pl->partial_floats = P.nblocks > 1 && (int64_t)P.own * P.nblocks != tiles ? (size_t)2 * P.nblocks * TK * TQ * (wino ? 2 : 1) : 0;
-    pl->shape = shape; pl->bf16 = bf16; pl->fixed = fixed; pl->TK = TK; pl->TQ = TQ; pl->NT = NT;
+    pl->shape = shape; pl->bf16 = bf16; pl->planes = bf16 ? planes : 1; pl->fixed = fixed; pl->TK = TK; pl->TQ = TQ; pl->NT = NT;
     pl->score = best_score;
     if (bf16)
-        pl->lds_bytes = (2 * wsz + 2 * (size_t)2 * P.CP * 4 + (size_t)P.EPT * NL + 2 * TK + 4) *
+        pl->lds_bytes = (2 * wsz + 2 * (size_t)planes * 2 * P.CP * 4 + (size_t)P.EPT * NL + 2 * TK + 4) *
                         sizeof(float);
     else
         pl->lds_bytes = (2 * wsz + 2 * (size_t)P.DC * P.CP + (size_t)P.EPT * NL + 2 * TK +
@@ -378,6 +384,7 @@ inline bool plan_igemm_kind(const ConvView &v, int n_cu, IgemmPlan *pl, bool bf1
     Q.Sh = v.pSh; Q.Sw = v.pSw; Q.pi = v.pi; Q.pj = v.pj; Q.ldk = v.ldk;
     Q.mD = v.mD; Q.Pt = v.mPt; Q.Pl = v.mPl; Q.B0i = v.B0i; Q.B0j = v.B0j;
     Q.wino = wino ? 1 : 0;
+    Q.planes = bf16 ? planes : 1;
     Q.total = (int)pl->packed_floats;
     return true;
 }
@@ -405,8 +412,9 @@ inline bool wino_enabled() {
 // fixed units and a plan fits; the general kernel otherwise.
 // row_pairs: 3x3 stride-1 views may take the kernels that compute two output rows from four products per
 // filter column (the caller asks for the plain order of summation with MCN_PREC_FP32_PLAIN).
-inline bool plan_igemm(const ConvView &v, int n_cu, IgemmPlan *pl, bool bf16 = false, bool row_pairs = true) {
-    if (bf16) return plan_igemm_kind(v, n_cu, pl, true, 0);
+// planes (bf16 only): 2 = split operands (kern_igemm_bf16.h)
+inline bool plan_igemm(const ConvView &v, int n_cu, IgemmPlan *pl, bool bf16 = false, bool row_pairs = true, int planes = 1) {
+    if (bf16) return plan_igemm_kind(v, n_cu, pl, true, 0, false, 0, planes);
     ConvView pv;
     if (row_pairs && wino_enabled() && wino_view(v, &pv) && plan_igemm_kind(pv, n_cu, pl, false, 0, false, v.Ho)) return true;
     // the instantiation with this view's filter size, if there is one and the channels divide into its units

@@ -257,6 +257,7 @@ struct PackParams {
     int Sh, Sw, pi, pj;    // mode 1
     int ldk;               // mode 2
     int mD, Pt, Pl, B0i, B0j;   // mode 3: channels per phase, pads of the convolution, largest b0 per direction
+    int planes;            // bf16 packing: 1 = values rounded to bf16, 2 = hi and lo planes (kern_igemm_bf16.h)
     int wino;              // modes 0, 1 with a 3x3 filter: Hf = 4 and view tap (ti, tj) is row combination ti of column tj
                            // (packed by igemm_pack_wino_kernel)
     int total;

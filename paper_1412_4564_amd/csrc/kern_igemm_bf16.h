@@ -17,6 +17,16 @@
 //  * the slab cannot be loaded straight into LDS: a thread loads the 16 channels of its
 //    sample(s) into registers one unit ahead (coalesced along rows, as before), and after
 //    the unit's MFMAs converts them and writes two 16-byte words.
+//  * a unit is 16 channels x one range of taps; the slab depends on the channels only, so it is
+//    staged when a unit starts a new group of 16 channels (or the block's range) and kept for the
+//    units of the group's other tap ranges.
+//
+// Split operands (template parameter PL = 2, "bf16x3"): every fp32 value v is held as two bf16 planes,
+// hi = bf16(v) and lo = bf16(v - hi), which together carry 16 bits of its significand, and every product
+// w*x is formed as  w_hi*x_hi + w_hi*x_lo + w_lo*x_hi  (three MFMAs; the dropped w_lo*x_lo is below 2^-16 of
+// |w||x|, the two roundings to lo below 2^-17 each).  The sum is that of Sec. 4.1 with products exact to
+// about 1e-5 of |w||x| in the worst case, on a matrix core that runs these MFMAs 16 times as fast as the
+// fp32 ones.  Planes sit side by side: slab [plane][octet][sample][8], weights [step][plane][octet][filter][8].
 #pragma once
 #include "kern_igemm.h"
 
@@ -37,8 +47,16 @@ __device__ inline unsigned pack_bf16x2(float lo, float hi) {
     return __builtin_bit_cast(unsigned, h);
 }
 
-// packed[g][kt][unit][step][octet][kk][8 channels] as bf16; one thread writes one pair of
-// channels (a 32-bit word).  Modes as in igemm_pack_weights_kernel.
+// hi and lo planes of a pair of fp32 values: hi = bf16(v), lo = bf16(v - hi) (the difference is exact in fp32)
+__device__ inline void split_bf16x2(float v0, float v1, unsigned *hi, unsigned *lo) {
+    const unsigned h = pack_bf16x2(v0, v1);
+    *hi = h;
+    *lo = pack_bf16x2(v0 - __uint_as_float(h << 16), v1 - __uint_as_float(h & 0xffff0000u));
+}
+
+// packed[g][kt][unit][step][plane][octet][kk][8 channels] as bf16 (Q.planes = 1: the values rounded to bf16;
+// 2: their hi and lo planes); one thread writes one pair of channels (a 32-bit word).  Modes as in
+// igemm_pack_weights_kernel.
 __global__ __launch_bounds__(256) void igemm_pack_weights_bf16_kernel(const float *__restrict__ w,
                                                                       unsigned *__restrict__ packed, PackParams Q) {
     int p = blockIdx.x * 256 + threadIdx.x;
@@ -47,8 +65,9 @@ __global__ __launch_bounds__(256) void igemm_pack_weights_bf16_kernel(const floa
     int within = p - t * Q.WSZ;
     const int j2 = within & 3; within >>= 2;
     const int kk = within % Q.TK; within /= Q.TK;
-    const int oct = within & 1;
-    const int s = within >> 1;                   // tap of the unit's tap range
+    const int oct = within & 1; within >>= 1;
+    const int plane = within % Q.planes;
+    const int s = within / Q.planes;             // tap of the unit's tap range
     const int uu = t % Q.NU; t /= Q.NU;
     const int kt = t % Q.KT;
     const int g = t / Q.KT;
@@ -71,13 +90,16 @@ __global__ __launch_bounds__(256) void igemm_pack_weights_bf16_kernel(const floa
             }
         }
     }
-    packed[p] = pack_bf16x2(v[0], v[1]);
+    unsigned hi, lo;
+    split_bf16x2(v[0], v[1], &hi, &lo);
+    packed[p] = plane ? lo : hi;
 }
 
 // WK x WP waves; each wave owns MK x MP tiles of 32 filters x 32 pixels.
 // LW more waves stage the operands (load, convert, write the slab; the packed weights go
 // straight to LDS) while the WK x WP waves only read LDS and issue MFMAs; see igemm_sk_kernel.
-template <int WK, int WP, int MK, int MP, int WPE, int LW>
+// PL: operand planes (1: values rounded to bf16; 2: hi and lo planes, three products per pair of operands)
+template <int WK, int WP, int MK, int MP, int WPE, int LW, int PL = 1>
 __global__ __launch_bounds__(64 * (WK * WP + LW), WPE) void igemm_bf16_kernel(IgemmParams P, const float *__restrict__ in,
                                                                        const float *__restrict__ wpk,
                                                                        const float *__restrict__ bias,
@@ -95,7 +117,7 @@ __global__ __launch_bounds__(64 * (WK * WP + LW), WPE) void igemm_bf16_kernel(Ig
     const int NU = P.NU;
     const int WSZ = P.WSZ;               // 32-bit words of packed weights per unit
     const int CP = P.CP, SRP = P.SRP;
-    const int XSZ = 2 * CP * 4;          // 32-bit words of slab per unit: 2 octets x CP samples x 16 bytes
+    const int XSZ = PL * 2 * CP * 4;     // 32-bit words of slab per buffer: PL planes x 2 octets x CP samples x 16 bytes
 
     extern __shared__ __align__(16) float lds[];
     float *wbuf = lds;                                   // [2][WSZ]
@@ -161,7 +183,9 @@ __global__ __launch_bounds__(64 * (WK * WP + LW), WPE) void igemm_bf16_kernel(Ig
     };
     // the 16 channels of this thread's slab samples, held in registers while the unit before is computed
     float stg[BF_EPT_MAX][BF_DC];
-    auto issue_loads = [&](int uu, int b) {
+    // weights (and bias) of unit uu into weight buffer b; with_slab: the unit starts a group of channels (or the
+    // block's range), so the group's samples are fetched into registers as well
+    auto issue_loads = [&](int uu, int b, bool with_slab) {
         float *wb = wbuf + b * WSZ;
         const unsigned woff = wtile_off + (unsigned)uu * (unsigned)WSZ * 4u;
         for (int e0 = lwave * 256; e0 < WSZ; e0 += NLW * 256)     // one wave instruction = 1 KB, 16 bytes per lane
@@ -173,6 +197,7 @@ __global__ __launch_bounds__(64 * (WK * WP + LW), WPE) void igemm_bf16_kernel(Ig
                 load_to_lds_b32(lds_address(blds + (l_seq & 1) * TK + lwave * 64),
                                 kl < P.Kg ? (unsigned)(l_g * P.Kg + kl) * 4u : SLAB_INVALID, brs, 0);
         }
+        if (!with_slab) return;
         const int c0 = (P.NTR == 1 ? uu : uu / P.NTR) * BF_DC;      // one tap range is the common case: no division
         const bool full = c0 + BF_DC <= P.Cg;
 #pragma unroll
@@ -205,12 +230,12 @@ __global__ __launch_bounds__(64 * (WK * WP + LW), WPE) void igemm_bf16_kernel(Ig
                 const int e = ltid + NL * s;
 #pragma unroll
                 for (int o = 0; o < 2; ++o) {
-                    uintx4 v;
-                    v.x = pack_bf16x2(stg[s][8 * o + 0], stg[s][8 * o + 1]);
-                    v.y = pack_bf16x2(stg[s][8 * o + 2], stg[s][8 * o + 3]);
-                    v.z = pack_bf16x2(stg[s][8 * o + 4], stg[s][8 * o + 5]);
-                    v.w = pack_bf16x2(stg[s][8 * o + 6], stg[s][8 * o + 7]);
+                    unsigned hi[4], lo[4];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) split_bf16x2(stg[s][8 * o + 2 * j], stg[s][8 * o + 2 * j + 1], &hi[j], &lo[j]);
+                    const uintx4 v = {hi[0], hi[1], hi[2], hi[3]}, l = {lo[0], lo[1], lo[2], lo[3]};
                     *reinterpret_cast<uintx4 *>(xb + (size_t)(o * CP + e) * 4) = v;
+                    if constexpr (PL == 2) *reinterpret_cast<uintx4 *>(xb + (size_t)((2 + o) * CP + e) * 4) = l;
                 }
             }
         }
@@ -272,9 +297,9 @@ __global__ __launch_bounds__(64 * (WK * WP + LW), WPE) void igemm_bf16_kernel(Ig
     // (fi, fj run along; a step past the filter's last tap has zero weights and reads offset 0), the
     // operands of step s+1 are requested before the MFMAs of step s, and the loop body has no branches
     // so that the waits inserted for the LDS reads are exact.
-    auto compute = [&](int uu, int b) {
+    auto compute = [&](int uu, int b, int xb) {
         const char *wl = reinterpret_cast<const char *>(wbuf + b * WSZ) + aoff;
-        const char *xl = reinterpret_cast<const char *>(xbuf + b * XSZ);
+        const char *xl = reinterpret_cast<const char *>(xbuf + xb * XSZ);
         const int T = P.Hf * P.Wf;
         int tap = 0, fj = 0, fi = 0;
         if (P.NTR != 1) {
@@ -283,13 +308,18 @@ __global__ __launch_bounds__(64 * (WK * WP + LW), WPE) void igemm_bf16_kernel(Ig
             fi = tap - fj * P.Hf;
         }
         int so = 16 * (fj * SRP + fi);                   // byte offset of the current tap in the slab
-        bf16x8 a0[MK], b0[MP], a1[MK], b1[MP];
+        // operand registers: [plane * M + m]
+        bf16x8 a0[PL * MK], b0[PL * MP], a1[PL * MK], b1[PL * MP];
+        const int xplane = 2 * CP * 16;                  // bytes from a slab plane to the next
         auto fetch = [&](bf16x8 *a, bf16x8 *bq) {
 #pragma unroll
-            for (int mk = 0; mk < MK; ++mk) a[mk] = *reinterpret_cast<const bf16x8 *>(wl + mk * 32 * 16);
+            for (int pl = 0; pl < PL; ++pl) {
 #pragma unroll
-            for (int mp = 0; mp < MP; ++mp) bq[mp] = *reinterpret_cast<const bf16x8 *>(xl + bbase[mp] + so);
-            wl += 2 * TK * 16;
+                for (int mk = 0; mk < MK; ++mk) a[pl * MK + mk] = *reinterpret_cast<const bf16x8 *>(wl + (pl * 2 * TK + mk * 32) * 16);
+#pragma unroll
+                for (int mp = 0; mp < MP; ++mp) bq[pl * MP + mp] = *reinterpret_cast<const bf16x8 *>(xl + bbase[mp] + so + pl * xplane);
+            }
+            wl += PL * 2 * TK * 16;
             // next tap (all scalar)
             ++tap;
             const bool wrap = ++fi == P.Hf;
@@ -298,6 +328,19 @@ __global__ __launch_bounds__(64 * (WK * WP + LW), WPE) void igemm_bf16_kernel(Ig
             if (tap >= T) so = 0;
         };
         auto mma = [&](const bf16x8 *a, const bf16x8 *bq) {
+            if constexpr (PL == 2) {
+                // the two small products first, then the large one
+#pragma unroll
+                for (int mk = 0; mk < MK; ++mk)
+#pragma unroll
+                    for (int mp = 0; mp < MP; ++mp)
+                        acc[mk][mp] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[MK + mk], bq[mp], acc[mk][mp], 0, 0, 0);
+#pragma unroll
+                for (int mk = 0; mk < MK; ++mk)
+#pragma unroll
+                    for (int mp = 0; mp < MP; ++mp)
+                        acc[mk][mp] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mk], bq[MP + mp], acc[mk][mp], 0, 0, 0);
+            }
 #pragma unroll
             for (int mk = 0; mk < MK; ++mk)
 #pragma unroll
@@ -360,9 +403,12 @@ __global__ __launch_bounds__(64 * (WK * WP + LW), WPE) void igemm_bf16_kernel(Ig
     // position = (tile, unit); `done` = units consumed so far.  After the block's own tiles comes its range
     // of the shared ones, which may start in the middle of a tile.
     const int t_s = tile_s0 + (int)(ub / NU), uu_s = (int)(ub - (ub / NU) * NU);
+    // returns whether the next unit starts a new slab: a new group of channels, a new tile, or the jump from the
+    // block's own tiles to its range of the shared ones (which may land inside a group)
     auto advance = [&](int &t, int &uu, int done) {
-        if (done == n_own) { t = t_s; uu = uu_s; }
-        else if (++uu == NU) { uu = 0; ++t; }
+        if (done == n_own) { t = t_s; uu = uu_s; return true; }
+        if (++uu == NU) { uu = 0; ++t; }
+        return P.NTR == 1 || uu % P.NTR == 0;
     };
     int t_c = n_own ? vb * P.own : t_s;   // compute-side tile and unit
     int uu_c = n_own ? 0 : uu_s;
@@ -376,18 +422,21 @@ __global__ __launch_bounds__(64 * (WK * WP + LW), WPE) void igemm_bf16_kernel(Ig
     if (loader) {
         // Staging wave: unit it+1 goes into the buffers the computing waves left at the barrier of
         // iteration it, and is complete (weights landed, slab written) before the next barrier.
+        // Slab buffers are used in turn, one per group of channels: the buffer written for the next group was last
+        // read by the group before the current one, whose units ended at an earlier barrier.
+        int slab = 0;
         setup_load(t_l);
-        issue_loads(uu_l, 0);
+        issue_loads(uu_l, 0, true);
         write_slab(0);
         for (int it = 0; it < nunits; ++it) {
             __builtin_amdgcn_s_waitcnt(WAIT_VMCNT0);
             lds_barrier();
             if (it + 1 < nunits) {
                 const int t_prev = t_l;
-                advance(t_l, uu_l, it + 1);
+                const bool fresh = advance(t_l, uu_l, it + 1);
                 if (t_l != t_prev) setup_load(t_l);
-                issue_loads(uu_l, (it + 1) & 1);
-                write_slab((it + 1) & 1);
+                issue_loads(uu_l, (it + 1) & 1, fresh);
+                if (fresh) { slab ^= 1; write_slab(slab); }
             }
         }
         return;
@@ -395,11 +444,12 @@ __global__ __launch_bounds__(64 * (WK * WP + LW), WPE) void igemm_bf16_kernel(Ig
     bool whole = segment_is_whole(t_c, uu_c);
     setup_compute(t_c);
 
+    int slab_c = 0;                                // slab buffer of the current unit (see the staging waves)
     for (int it = 0; it < nunits; ++it) {
         lds_barrier();                             // the staging waves' operands are in place, and the other buffer is free
         if (need_init) { init_acc(whole && bias != nullptr); need_init = false; }
         __builtin_amdgcn_sched_barrier(0);
-        compute(uu_c, it & 1);
+        compute(uu_c, it & 1, slab_c);
         __builtin_amdgcn_sched_barrier(0);
         const bool last = it + 1 == nunits;
         if (uu_c + 1 == NU || last) {
@@ -407,12 +457,14 @@ __global__ __launch_bounds__(64 * (WK * WP + LW), WPE) void igemm_bf16_kernel(Ig
             else store_partial(2 * vb + (first_segment ? 0 : 1));
             first_segment = it + 1 == n_own;      // the shared range starts with a "first" segment again
             if (!last) {
-                advance(t_c, uu_c, it + 1);
+                advance(t_c, uu_c, it + 1);        // a new tile or the jump to the shared range: a new slab either way
+                slab_c ^= 1;
                 whole = segment_is_whole(t_c, uu_c);
                 setup_compute(t_c);
             }
         } else {
             ++uu_c;
+            if (P.NTR == 1 || uu_c % P.NTR == 0) slab_c ^= 1;
         }
     }
 }

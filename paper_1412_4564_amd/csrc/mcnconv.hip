@@ -125,10 +125,12 @@ const PlanEntry *plans_for(const mcn_conv_desc *d, const Geom &g) {
     const int ncu = compute_units();
     // bf16 operands: the bf16 kernel where a view has at least one full MFMA depth of channels;
     // other views (and the filter derivative) compute in fp32, which meets the same error bound
-    const bool bf = d->precision == MCN_PREC_BF16;
+    // the bf16 matrix core: operands rounded to bf16, or (MCN_PREC_FP32_BF16X3) split into two bf16 planes
+    const bool bf = d->precision == MCN_PREC_BF16 || d->precision == MCN_PREC_FP32_BF16X3;
+    const int planes = d->precision == MCN_PREC_FP32_BF16X3 ? 2 : 1;
     const bool pairs = d->precision != MCN_PREC_FP32_PLAIN;     // the row-pair kernels for 3x3 stride-1 layers
     auto plan_view = [&](const ConvView &v, IgemmPlan *pl) {
-        if (bf && !v.mD && v.Cg >= BF_DC && plan_igemm(v, ncu, pl, true)) return true;    // merged phases: fp32 kernel only
+        if (bf && !v.mD && v.Cg >= BF_DC && plan_igemm(v, ncu, pl, true, true, planes)) return true;    // merged phases: fp32 kernel only
         return plan_igemm(v, ncu, pl, false, pairs);
     };
     e.fwd_ok = on && plan_view(forward_view(g), &e.fwd);
@@ -153,7 +155,7 @@ const PlanEntry *plans_for(const mcn_conv_desc *d, const Geom &g) {
     }
     e.wg_ok = on && ((pairs && wino_enabled() && plan_wgrad(forward_view(g), ncu, &e.wg, true)) ||
                      plan_wgrad(forward_view(g), ncu, &e.wg));
-    e.wgb_ok = on && bf && plan_wgrad_bf16(forward_view(g), ncu, &e.wgb);
+    e.wgb_ok = on && d->precision == MCN_PREC_BF16 && plan_wgrad_bf16(forward_view(g), ncu, &e.wgb);
     e.fc = on && is_fully_connected(g) && (int64_t)g.H * g.W * g.D < ((int64_t)1 << 30) &&
            plan_wgrad(fc_forward_view(g), ncu, &e.fc_fwd) && plan_igemm(fc_backward_data_view(g), ncu, &e.fc_bwd) &&
            plan_igemm(fc_backward_filter_view(g), ncu, &e.fc_wg);
@@ -215,14 +217,15 @@ size_t igemm_ws_bytes(const IgemmPlan &pl) {
     return align256(pl.packed_floats * sizeof(float)) + pl.partial_floats * sizeof(float);
 }
 
-template <int WK, int WP, int MK, int MP>
+template <int WK, int WP, int MK, int MP, int PL = 1>
 int launch_igemm_bf16_inst(const IgemmPlan &pl, const float *in, const float *wpk, const float *bias, float *out,
                            float *part, hipStream_t s, int relu) {
+    if (PL == 1 && pl.planes == 2) return launch_igemm_bf16_inst<WK, WP, MK, MP, 2>(pl, in, wpk, bias, out, part, s, relu);
     IgemmParams P = pl.P;
     P.relu = relu;
     // one block per compute unit: 8 computing + 4 staging waves (3 per SIMD), or 4 + 4
     constexpr int LW = IGEMM_LOADER_WAVES;
-    auto kern = igemm_bf16_kernel<WK, WP, MK, MP, WK * WP == 8 ? 3 : 2, LW>;
+    auto kern = igemm_bf16_kernel<WK, WP, MK, MP, WK * WP == 8 ? 3 : 2, LW, PL>;
     if (pl.lds_bytes > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
                                            (int)pl.lds_bytes);
@@ -574,7 +577,7 @@ int conjugate_convolution(const mcn_convt_desc *t, mcn_conv_desc *c, Geom *g) {
     if (t->Hf < 1 || t->Wf < 1 || t->Kf < 1 || t->groups < 1) return MCN_BAD_ARG;
     if (t->up_h < 1 || t->up_w < 1) return MCN_BAD_ARG;
     if (t->crop_top < 0 || t->crop_bottom < 0 || t->crop_left < 0 || t->crop_right < 0) return MCN_BAD_ARG;
-    if (t->precision != MCN_PREC_FP32 && t->precision != MCN_PREC_BF16 && t->precision != MCN_PREC_FP32_PLAIN) return MCN_BAD_ARG;
+    if (t->precision < MCN_PREC_FP32 || t->precision > MCN_PREC_FP32_BF16X3) return MCN_BAD_ARG;
     if (t->D % t->groups != 0) return MCN_BAD_GROUPS;
     const int64_t lim = (int64_t)1 << 31;
     const int64_t Ho = (int64_t)t->up_h * (t->H - 1) + t->Hf - t->crop_top - t->crop_bottom;
@@ -612,17 +615,19 @@ int mcn_conv_workspace_size(const mcn_conv_desc *desc, int op, size_t *bytes) {
     return MCN_OK;
 }
 
+static const char *igemm_name(const IgemmPlan &pl) {
+    return pl.bf16 ? (pl.planes == 2 ? "igemm_bf16x3" : "igemm_bf16") : pl.P.wino_Ho ? "igemm_f23" : "igemm";
+}
+
 const char *mcn_conv_kernel_name(const mcn_conv_desc *desc, int op) {
     Geom g;
     if (make_geom(desc, &g)) return NULL;
     const PlanEntry *e = plans_for(desc, g);
     switch (op) {
         case MCN_OP_FORWARD:
-            return e->fc ? "fc_gemm" : e->fwd_ok ? (e->fwd.bf16 ? "igemm_bf16" : e->fwd.P.wino_Ho ? "igemm_f23" : "igemm") : "direct";
+            return e->fc ? "fc_gemm" : e->fwd_ok ? igemm_name(e->fwd) : "direct";
         case MCN_OP_BACKWARD_DATA:
-            return e->fc ? "fc_gemm"
-                         : e->bwd_ok ? (e->n_bwd && e->bwd[0].bf16 ? "igemm_bf16" : e->n_bwd && e->bwd[0].P.wino_Ho ? "igemm_f23" : "igemm")
-                                     : "direct";
+            return e->fc ? "fc_gemm" : e->bwd_ok ? (e->n_bwd ? igemm_name(e->bwd[0]) : "igemm") : "direct";
         case MCN_OP_BACKWARD_FILTER:
             if (e->fc) return "fc_gemm";
             if (e->wgb_ok) return "wgrad_bf16";

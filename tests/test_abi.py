@@ -53,6 +53,7 @@ def test_output_size_closed_form():
     (dict(xshape=(0, 4, 9, 8)), B.MCN_BAD_ARG),
     (dict(wshape=(6, 2, 3, 0)), B.MCN_BAD_ARG),
     (dict(precision=7), B.MCN_BAD_ARG),
+    (dict(precision=4), B.MCN_BAD_ARG),
     (dict(wshape=(6, 3, 3, 3)), B.MCN_BAD_GROUPS),       # D' = 3 does not divide D = 4
     (dict(wshape=(5, 2, 3, 3)), B.MCN_BAD_GROUPS),       # 2 groups do not divide 5 filters
     (dict(wshape=(6, 2, 3, 9)), B.MCN_FILTER_TOO_LARGE),  # H = 8 < H' = 9
@@ -346,3 +347,16 @@ def test_static_scratch_entry_point_rejects_what_does_not_fit():
     d.stride_h = 0
     assert B.mcn_conv_backward_bias_static(d, 16, 16, None) == B.MCN_BAD_ARG
     assert b"static buffer" in B.lib().mcn_status_string(B.MCN_STATIC_SCRATCH_EXCEEDED)
+
+
+def test_split_operand_precision_picks_the_bf16_matrix_core_for_forward_and_dzdx_only():
+    from paper_1412_4564_amd import synth
+    for name in ("4a", "4b", "4c"):
+        L = synth.LAYERS[name]
+        d = B.make_desc(synth.x_shape(L), synth.w_shape(L), L["stride"], L["pad"], B.MCN_PREC_FP32_BF16X3)
+        names = [B.mcn_conv_kernel_name(d, op) for op in range(3)]
+        assert names[:2] == ["igemm_bf16x3", "igemm_bf16x3"] and names[2].startswith("wgrad_f23"), (name, names)
+        assert B.mcn_conv_workspace_size(d, 0) < (1 << 28)
+    L = synth.LAYERS["3a"]      # 3 channels: fp32 kernels
+    d = B.make_desc(synth.x_shape(L), synth.w_shape(L), L["stride"], L["pad"], B.MCN_PREC_FP32_BF16X3)
+    assert B.mcn_conv_kernel_name(d, 0) == "igemm"
