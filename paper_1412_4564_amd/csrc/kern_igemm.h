@@ -887,26 +887,47 @@ __global__ __launch_bounds__(256) void igemm_fixup_kernel(IgemmParams P, const f
     }
     __syncthreads();
     const int np = npieces;
-    for (int e = blockIdx.y * 256 + threadIdx.x; e < TK * TQ; e += gridDim.y * 256) {
-        const int kloc = e / TQ, ql = e - kloc * TQ;
+    // a thread takes four consecutive pixels of one filter: one 16-byte load per piece, two pieces in flight
+    constexpr int Q4 = TQ / 4;
+    for (int e4 = blockIdx.y * 256 + threadIdx.x; e4 < TK * Q4; e4 += gridDim.y * 256) {
+        const int kloc = e4 / Q4, ql = 4 * (e4 - kloc * Q4);
         const int kl = kt * TK + kloc;
-        const int q = pt * TQ + ql;
-        const int ii = q % P.TI;
-        const int c = q / P.TI;
-        const int n = c / P.Wo;
-        const int jo = c - n * P.Wo;
-        const int io = rb * P.TI + ii;
-        if (kl >= P.Kg || q >= P.QN || io >= P.Ho) continue;
-        int oi = P.oi0 + P.osi * io, oj = P.oj0 + P.osj * jo, och = g * P.Kg + kl;
+        if (kl >= P.Kg || pt * TQ + ql >= P.QN) continue;
+        int och = g * P.Kg + kl, fi0 = 0, fj0 = 0;
         if (P.mD) {
             const MergedFilter f = merged_filter(P, kl);
-            oi += f.i0; oj += f.j0; och = g * P.mD + f.c;
-            if (oi >= P.OH || oj >= P.OW) continue;
+            fi0 = f.i0; fj0 = f.j0; och = g * P.mD + f.c;
         }
-        float acc = bias ? bias[och] : 0.f;
-        for (int i = 0; i < np; ++i) acc += part[(size_t)slots[i] * (TK * TQ) + e];
-        if (P.relu) acc = fmaxf(acc, 0.f);
-        out[(size_t)(oi + P.OH * (oj + P.OW * (P.Ktot * n))) + (size_t)OHW * och] = acc;
+        const float bv = bias ? bias[och] : 0.f;
+        const float *src = part + (size_t)kloc * TQ + ql;
+        float4 acc = {bv, bv, bv, bv};
+        int i = 0;
+        for (; i + 1 < np; i += 2) {
+            const float4 v0 = *reinterpret_cast<const float4 *>(src + (size_t)slots[i] * (TK * TQ));
+            const float4 v1 = *reinterpret_cast<const float4 *>(src + (size_t)slots[i + 1] * (TK * TQ));
+            acc.x += v0.x; acc.y += v0.y; acc.z += v0.z; acc.w += v0.w;
+            acc.x += v1.x; acc.y += v1.y; acc.z += v1.z; acc.w += v1.w;
+        }
+        if (i < np) {
+            const float4 v0 = *reinterpret_cast<const float4 *>(src + (size_t)slots[i] * (TK * TQ));
+            acc.x += v0.x; acc.y += v0.y; acc.z += v0.z; acc.w += v0.w;
+        }
+        const float vv[4] = {acc.x, acc.y, acc.z, acc.w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int q = pt * TQ + ql + j;
+            const int c = div32(q, P.dTI);
+            const int ii = q - c * P.TI;
+            const int n = div32(c, P.dWo);
+            const int jo = c - n * P.Wo;
+            const int io = rb * P.TI + ii;
+            if (q >= P.QN || io >= P.Ho) continue;
+            const int oi = P.oi0 + P.osi * io + fi0, oj = P.oj0 + P.osj * jo + fj0;
+            if (P.mD && (oi >= P.OH || oj >= P.OW)) continue;
+            float v = vv[j];
+            if (P.relu) v = fmaxf(v, 0.f);
+            out[(size_t)(oi + P.OH * (oj + P.OW * (P.Ktot * n))) + (size_t)OHW * och] = v;
+        }
     }
 }
 

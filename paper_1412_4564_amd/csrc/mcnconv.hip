@@ -208,6 +208,7 @@ int launch_igemm_wino(const IgemmPlan &pl, const float *in, const float *wpk, co
     constexpr int TK = WK * MK * 32, TQ = WP * 32;
     IgemmParams F = P;
     F.TI = 2 * P.TI; F.QN = 2 * P.QN; F.Ho = P.wino_Ho; F.osi = P.osi / 2;
+    F.dTI = make_div32(F.TI);
     hipLaunchKernelGGL((igemm_fixup_kernel<TK, 2 * TQ>), dim3(P.nshare - 1, 16), dim3(256), 0, s, F, part, bias, out);
     return check_launch();
 }

@@ -258,6 +258,27 @@ def test_3x3_stride1_plain_order_of_summation(case):
     U.assert_errors(U.run_layer_full(L, precision=B.MCN_PREC_FP32_PLAIN, with_bias=bool(case % 2)), label="one row per pixel %d" % case)
 
 
+# ---- 65 to 96 filters per group: tiles of 96 filters -------------------------------------------
+FILTERS_96 = [
+    # H   W   D   N  Hf  Wf  Df  K    stride  pad
+    (31, 29, 6, 5, 3, 3, 3, 130, (1, 1), (1, 1, 1, 1)),       # two groups of 65
+    (20, 20, 16, 4, 3, 3, 16, 96, (1, 1), (1, 1, 1, 1)),      # exactly one tile
+    (40, 33, 3, 6, 7, 7, 3, 80, (2, 2), (3, 3, 3, 3)),        # three channels, stride 2
+    (16, 16, 64, 8, 1, 1, 64, 90, (1, 1), (0, 0, 0, 0)),      # 1x1
+    (24, 24, 8, 5, 5, 5, 8, 192, (1, 1), (2, 2, 2, 2)),       # two tiles per group
+    (55, 55, 3, 16, 11, 11, 3, 96, (4, 4), (0, 0, 0, 0)),     # first layer of the Krizhevsky-style network, small: 363 coefficients in one tile
+    (30, 26, 12, 6, 5, 5, 12, 72, (1, 1), (2, 2, 2, 2)),      # 300 coefficients: the 96 x 384 tile, ragged both ways
+]
+
+
+@pytest.mark.parametrize("case", range(len(FILTERS_96)))
+def test_layers_with_65_to_96_filters_per_group(case):
+    H, W, D, N, Hf, Wf, Df, K, st, pad = FILTERS_96[case]
+    L = custom_layer(H, W, D, N, Hf, Wf, Df, K, st, pad, idx=800 + case)
+    for prec in (B.MCN_PREC_FP32, B.MCN_PREC_FP32_PLAIN):
+        U.assert_errors(U.run_layer_full(L, precision=prec, with_bias=bool(case % 2)), label="96-filter tiles %d" % case)
+
+
 # ---- which kernels the dispatcher picks ----------------------------------------------
 def test_workload_layers_run_on_the_matrix_core_kernels():
     """No layer of the workloads may fall back to the one-result-per-thread kernels."""
