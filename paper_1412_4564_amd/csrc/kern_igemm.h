@@ -451,13 +451,18 @@ __global__ __launch_bounds__(64 * (WK * WP + LW), WPE) void igemm_sk_kernel(Igem
             gtab[s * NL + ltid] = ok ? (int)(4u * (unsigned)(i + P.H * j + ni * P.Ctot * HW)) : (int)SLAB_INVALID;
         }
     };
+    // LDS byte addresses as 32-bit scalars: arithmetic on generic pointers would cost every load a 64-bit
+    // addition and a null check.  The per-unit bases are pinned to scalar registers: an addition that lands on
+    // the vector ALU makes a fetching wave queue behind the matrix instructions of the computing waves.
+    const unsigned wbuf_lds = __builtin_amdgcn_readfirstlane(lds_address(wbuf));
+    const unsigned xbuf_lds = __builtin_amdgcn_readfirstlane(lds_address(xbuf));
     // fetch unit uu of the load-side tile into buffer b
     auto issue_loads = [&](int uu, int b) {
-        float *wb = wbuf + b * WSZ;
-        float *xb = xbuf + b * XSZ;
+        const unsigned wb = __builtin_amdgcn_readfirstlane(wbuf_lds + (unsigned)(b * WSZ) * 4u);
+        const unsigned xb = __builtin_amdgcn_readfirstlane(xbuf_lds + (unsigned)(b * XSZ + lwave * 64) * 4u);    // this wave's first element
         const unsigned woff = wtile_off + (unsigned)uu * (unsigned)WSZ * 4u;
         for (int e0 = lwave * 256; e0 < WSZ; e0 += NLW * 256)     // one wave instruction = 256 floats, 16 bytes per lane
-            load_to_lds_b128(lds_address(wb + e0), lane16, wrs, woff + (unsigned)e0 * 4u);
+            load_to_lds_b128(wb + (unsigned)e0 * 4u, lane16, wrs, woff + (unsigned)e0 * 4u);
         if (bias && uu == 0 && lwave * 64 < TK) {
             // the tile's bias: start value of the accumulators of a tile this block owns entirely
             const int kl = l_kt * TK + lwave * 64 + lane;
@@ -468,17 +473,28 @@ __global__ __launch_bounds__(64 * (WK * WP + LW), WPE) void igemm_sk_kernel(Igem
         }
         const int cg = (FIXED || P.NTR == 1) ? uu : uu / P.NTR;
         const int c0 = cg * DC;
-        for (int s = 0; s < P.EPT; ++s) {
-            const int e0 = lwave * 64 + NL * s;
-            if (e0 >= CP) break;
-            const unsigned go = (unsigned)gtab[s * NL + ltid];
+        // up to four table entries per wait: a slab of one or two channels with many elements per thread would
+        // otherwise pay one LDS round trip per load, and the fetching waves would set the pace of the block
+        const int ept = min(P.EPT, (CP - lwave * 64 + NL - 1) / NL);     // rows of the table with elements of this wave
+        auto batch = [&](auto count, int s) {
+            constexpr int Q = decltype(count)::value;
+            unsigned go[Q];
+#pragma unroll
+            for (int q = 0; q < Q; ++q) go[q] = (unsigned)gtab[(s + q) * NL + ltid];
             for (int d = 0; d < DC; ++d) {
                 const int c = c0 + d;
                 // channels past the group's last one read as zero (their weights are zero too)
                 const buffer_rsrc rs = ((FIXED && !WINO) || c < P.Cg) ? xrs : zrs;
-                load_to_lds_b32(lds_address(xb + d * CP + e0), go, rs, (unsigned)c * (unsigned)HW * 4u);
+                const unsigned soff = (unsigned)c * (unsigned)HW * 4u;
+#pragma unroll
+                for (int q = 0; q < Q; ++q)
+                    load_to_lds_b32(xb + (unsigned)(d * CP + NL * (s + q)) * 4u, go[q], rs, soff);
             }
-        }
+        };
+        int s = 0;
+        for (; s + 4 <= ept; s += 4) batch(std::integral_constant<int, 4>{}, s);
+        if (ept - s == 3) { batch(std::integral_constant<int, 3>{}, s); s += 3; }
+        for (; s < ept; ++s) batch(std::integral_constant<int, 1>{}, s);   // one or two rows: all channels of a row in turn
     };
 
     // ---- compute side: tile whose accumulators are live -----------------------------------
@@ -660,7 +676,9 @@ __global__ __launch_bounds__(64 * (WK * WP + LW), WPE) void igemm_sk_kernel(Igem
                 __builtin_amdgcn_sched_barrier(0);
                 mma(a0, b0);
                 __builtin_amdgcn_sched_barrier(0);
-                if (s + 2 < s1) fetch(a0, b0, s + 2, o0n);
+                // no branch here (the last pass fetches a step again, for nothing): with one the compiler makes the
+                // products below wait for these reads too, and the wave sits out an LDS round trip every two steps
+                fetch(a0, b0, min(s + 2, s1 - 1), o0n);
                 __builtin_amdgcn_sched_barrier(0);
                 mma(a1, b1);
                 __builtin_amdgcn_sched_barrier(0);

@@ -200,9 +200,14 @@ __global__ __launch_bounds__(64 * (WK * WR + WGRAD_LOADER_WAVES), WPE) void wgra
         l_xch = g * P.Cg + c_lo;
         l_ych = g * P.Kg + kt * TK;
     };
+    // LDS byte addresses as 32-bit scalars: no 64-bit pointer arithmetic per load, and pinned to scalar registers
+    // here so that none of the per-load additions lands on the vector ALU, where a fetching wave would queue
+    // behind the matrix instructions of the computing waves
+    const unsigned ybuf_lds = __builtin_amdgcn_readfirstlane(lds_address(ybuf));
+    const unsigned xbuf_lds = __builtin_amdgcn_readfirstlane(lds_address(xbuf));
     auto issue_loads = [&](int uu, int b) {
-        float *yb = ybuf + b * YS;
-        float *xb = xbuf + b * P.XS;
+        const unsigned yb = __builtin_amdgcn_readfirstlane(ybuf_lds + (unsigned)(b * YS) * 4u);
+        const unsigned xb = __builtin_amdgcn_readfirstlane(xbuf_lds + (unsigned)(b * P.XS) * 4u);
         // unit -> image, patch (all scalar)
         const int per_image = P.RB * P.CC;
         const int n = uu / per_image;
@@ -218,7 +223,7 @@ __global__ __launch_bounds__(64 * (WK * WR + WGRAD_LOADER_WAVES), WPE) void wgra
             const unsigned yoff = (p_ii[seg] < rows && p_dc[seg] < cols) ? p_off[seg] + ybase : SLAB_INVALID;
             if (seg * 64 + lane < PCH) {
                 for (int k = wave - NW; k < l_klim; k += LW)
-                    load_to_lds_b32(lds_address(yb + k * PCHP + seg * 64), yoff, yrs, (unsigned)k * (unsigned)HoWo * 4u);
+                    load_to_lds_b32(yb + (unsigned)(k * PCHP + seg * 64) * 4u, yoff, yrs, (unsigned)k * (unsigned)HoWo * 4u);
             }
         }
         // x slab of the tile's channels: rows i0 + r, columns j0 + col of image n
@@ -240,7 +245,7 @@ __global__ __launch_bounds__(64 * (WK * WR + WGRAD_LOADER_WAVES), WPE) void wgra
             const unsigned go = ok ? (unsigned)(rel + xbase) : SLAB_INVALID;
             if (e0 + lane < ntot) {
                 for (int d = by_chunk ? 0 : (lw + chunk) % LW; d < l_nch; d += by_chunk ? 1 : LW)
-                    load_to_lds_b32(lds_address(xb + d * CP + e0), go, xrs, (unsigned)d * (unsigned)HW * 4u);
+                    load_to_lds_b32(xb + (unsigned)(d * CP + e0) * 4u, go, xrs, (unsigned)d * (unsigned)HW * 4u);
             }
         }
     };

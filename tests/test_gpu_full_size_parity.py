@@ -72,7 +72,8 @@ CHUNKED = [
     (200, 180, 24, 40, 3, 3, 24, 48, (1, 1), (1, 1, 1, 1), "wgrad_f23_chunked"),      # tiles of 64 filters on 12 waves
     (75, 61, 96, 56, 3, 3, 48, 200, (1, 1), (1, 0, 0, 1), "wgrad_f23_chunked"),       # two groups of 100 filters: tiles of 128
     (199, 181, 32, 48, 3, 3, 16, 80, (1, 1), (0, 1, 2, 1), "wgrad_f23_chunked"),      # odd planes, two groups of 40 filters
-    (60, 64, 64, 48, 5, 5, 64, 96, (1, 1), (2, 2, 2, 2), "wgrad_igemm_chunked"),      # 5x5: the one-row kernel only
+    (60, 64, 64, 48, 5, 5, 64, 112, (1, 1), (2, 2, 2, 2), "wgrad_igemm_chunked"),     # 5x5: the one-row kernel only
+    (100, 80, 64, 48, 5, 5, 64, 96, (1, 1), (2, 2, 2, 2), "wgrad_igemm_chunked"),     # 5x5 on tiles of 96 filters
     (120, 90, 16, 512, 4, 3, 16, 24, (2, 1), (1, 0, 1, 1), "wgrad_igemm_chunked"),    # vertical stride, 32-filter tiles
 ]
 
