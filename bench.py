@@ -233,8 +233,14 @@ def fused_relu_report(layers, stream_obj, steps):
     stream = stream_obj.cuda_stream
 
     def timed(fn):
-        for _ in range(2):
-            fn()
+        # warm-up: at least 20 ms of this very call, so that the clock has left its idle state
+        t0 = time.perf_counter()
+        while True:
+            for _ in range(2):
+                fn()
+            torch.cuda.synchronize()
+            if time.perf_counter() - t0 > 0.02:
+                break
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         a.record(stream_obj)
         for _ in range(steps):
