@@ -379,7 +379,7 @@ inline bool plan_igemm_kind(const ConvView &v, int n_cu, IgemmPlan *pl, bool bf1
     PackParams &Q = pl->Q;
     Q = PackParams{};
     Q.Hf = v.Hf; Q.Wf = v.Wf; Q.HfA = v.HfA; Q.WfA = v.WfA; Q.DfA = v.DfA;
-    Q.Kg = v.Kg; Q.Cg = v.Cg; Q.G = v.G; Q.KT = P.KT; Q.NU = P.NU; Q.NTR = P.NTR; Q.NS = P.NS; Q.WSZ = P.WSZ; Q.TK = TK;
+    Q.Kg = v.Kg; Q.Cg = v.Cg; Q.G = v.G; Q.KT = P.KT; Q.NU = P.NU; Q.NTR = P.NTR; Q.NS = P.NS; Q.WSZ = P.WSZ; Q.TK = TK; Q.MK = MK;
     Q.DC = P.DC; Q.TC = P.TC; Q.pair_mode = P.pair_mode; Q.mode = v.pack_mode;
     Q.Sh = v.pSh; Q.Sw = v.pSw; Q.pi = v.pi; Q.pj = v.pj; Q.ldk = v.ldk;
     Q.mD = v.mD; Q.Pt = v.mPt; Q.Pl = v.mPl; Q.B0i = v.B0i; Q.B0j = v.B0j;

@@ -258,10 +258,21 @@ struct PackParams {
     int ldk;               // mode 2
     int mD, Pt, Pl, B0i, B0j;   // mode 3: channels per phase, pads of the convolution, largest b0 per direction
     int planes;            // bf16 packing: 1 = values rounded to bf16, 2 = hi and lo planes (kern_igemm_bf16.h)
+    int MK;                // fp32 packing: 32-filter blocks per computing wave (see packed_filter_slot)
     int wino;              // modes 0, 1 with a 3x3 filter: Hf = 4 and view tap (ti, tj) is row combination ti of column tj
                            // (packed by igemm_pack_wino_kernel)
     int total;
 };
+
+// Where filter kk of a tile sits among the TK values of one reduction element of a step.  A wave of the fp32
+// kernels owns MK blocks of 32 filters (filter = (wave*MK + block)*32 + lane).  With two blocks per wave a lane's
+// two values are stored side by side, so they come with ONE 8-byte LDS read whose offset is an immediate of the
+// instruction (16 bits: any step of the unit); as two 4-byte values 128 bytes apart they came with a two-address
+// read, whose 8-bit offsets the compiler had to rebase with a vector addition every other step.
+__device__ __host__ inline int packed_filter_slot(int kk, int MK) {
+    if (MK != 2) return kk;
+    return (((kk >> 6) << 5) + (kk & 31)) * 2 + ((kk >> 5) & 1);
+}
 
 // one direction of mode 3: filter tap of view tap ti for phase pi, or -1
 __device__ __host__ inline int merged_tap(int ti, int Hfv, int HfA, int S, int Pt, int B0, int pi) {
@@ -282,6 +293,7 @@ __global__ __launch_bounds__(256) void igemm_pack_weights_kernel(const float *__
     const int kk = within % Q.TK; within /= Q.TK;
     const int h = within & 1;
     const int s = within >> 1;
+    p += packed_filter_slot(kk, Q.MK) - kk;         // pitch padding aside, the threads of a step permute its slots
     const int uu = t % Q.NU; t /= Q.NU;
     const int kt = t % Q.KT;
     const int g = t / Q.KT;
@@ -335,7 +347,7 @@ __global__ __launch_bounds__(256) void igemm_pack_wino_kernel(const float *__res
         g0 = src[0]; g1 = src[1]; g2 = src[2];
         if (Q.mode != 0) { const float t = g0; g0 = g2; g2 = t; }      // input derivative: the flipped filter
     }
-    float *dst = packed + ((size_t)((g * Q.KT + kt) * Q.NU + uu) * Q.NS + (size_t)(dp * 3 + fj) * 4) * 2 * Q.TK + h * Q.TK + kk;
+    float *dst = packed + ((size_t)((g * Q.KT + kt) * Q.NU + uu) * Q.NS + (size_t)(dp * 3 + fj) * 4) * 2 * Q.TK + h * Q.TK + packed_filter_slot(kk, Q.MK);
     dst[0] = g0;
     dst[2 * Q.TK] = 0.5f * (g0 + g1 + g2);
     dst[4 * Q.TK] = 0.5f * (g0 - g1 + g2);
@@ -563,7 +575,17 @@ __global__ __launch_bounds__(64 * (WK * WP + LW), WPE) void igemm_sk_kernel(Igem
                 }
             }
     };
-    const int aoff = half * TK + wk * MK * 32 + (lane & 31);
+    // the lane's first weight of a step (packed_filter_slot: with MK == 2 its two values are adjacent)
+    const int aoff = half * TK + (MK == 2 ? (wk * 32 + (lane & 31)) * 2 : wk * MK * 32 + (lane & 31));
+    auto read_a = [&](float *a, const float *wstep) {         // wstep: wl + step * 2 * TK
+        if constexpr (MK == 2) {
+            const float2 v = *reinterpret_cast<const float2 *>(wstep);
+            a[0] = v.x; a[1] = v.y;
+        } else {
+#pragma unroll
+            for (int mk = 0; mk < MK; ++mk) a[mk] = wstep[mk * 32];
+        }
+    };
     // steps [part*NS/2, (part+1)*NS/2) of unit uu, operands in buffer b
     auto compute = [&](auto PART, int uu, int b) {
         constexpr int part = decltype(PART)::value;
@@ -580,18 +602,20 @@ __global__ __launch_bounds__(64 * (WK * WP + LW), WPE) void igemm_sk_kernel(Igem
             const int CP2 = CP, SRP2 = SRP >> 1;          // pitches of a channel pair and of a column, in float2
             float2 d[2][MP][2];
             float a[2][MK];
+            const float2 *xq[MP];                          // the lane's window origin: one vector addition per macro-step
+#pragma unroll
+            for (int mp = 0; mp < MP; ++mp) xq[mp] = xl2 + (bbase[mp] >> 1);
             auto fetch_d = [&](int m, int slot) {
                 const int dp = m / 3, fj = m % 3;
+                const int o = dp * CP2 + fj * SRP2;
 #pragma unroll
                 for (int mp = 0; mp < MP; ++mp) {
-                    const int o = (bbase[mp] >> 1) + dp * CP2 + fj * SRP2;
-                    d[slot][mp][0] = xl2[o];
-                    d[slot][mp][1] = xl2[o + 1];
+                    d[slot][mp][0] = xq[mp][o];
+                    d[slot][mp][1] = xq[mp][o + 1];
                 }
             };
             auto fetch_a = [&](int st, int slot) {
-#pragma unroll
-                for (int mk = 0; mk < MK; ++mk) a[slot][mk] = wl[st * 2 * TK + mk * 32];
+                read_a(a[slot], wl + st * 2 * TK);
             };
             fetch_d(M0, M0 & 1);
             fetch_a(M0 * 4, 0);
@@ -630,8 +654,7 @@ __global__ __launch_bounds__(64 * (WK * WP + LW), WPE) void igemm_sk_kernel(Igem
             auto fetch = [&](int s, int slot) {
                 const int dp = s / TT, tap = s % TT;
                 const int fj = tap / HF, fi = tap % HF;
-#pragma unroll
-                for (int mk = 0; mk < MK; ++mk) a[slot][mk] = wl[s * 2 * TK + mk * 32];
+                read_a(a[slot], wl + s * 2 * TK);
 #pragma unroll
                 for (int mp = 0; mp < MP; ++mp) bb[slot][mp] = xl[bbase[mp] + dp * 2 * CP + fj * SRP + fi];
             };
@@ -656,8 +679,7 @@ __global__ __launch_bounds__(64 * (WK * WP + LW), WPE) void igemm_sk_kernel(Igem
             float a0[MK], b0[MP], a1[MK], b1[MP];
             int o0 = ot[2 * s0], o1 = ot[2 * s0 + 2];
             auto fetch = [&](float *a, float *bq, int s, int o) {
-#pragma unroll
-                for (int mk = 0; mk < MK; ++mk) a[mk] = wl[s * 2 * TK + mk * 32];
+                read_a(a, wl + s * 2 * TK);
 #pragma unroll
                 for (int mp = 0; mp < MP; ++mp) bq[mp] = xl[bbase[mp] + o];
             };
