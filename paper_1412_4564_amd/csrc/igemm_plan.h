@@ -235,7 +235,7 @@ inline bool plan_igemm_kind(const ConvView &v, int n_cu, IgemmPlan *pl, bool bf1
     const int resident = two ? 2 * n_cu : n_cu;
     if (wino && v.Kg > 64) { shape = IG_W128x128; WK = 2; WP = 4; MK = 2; MP = 1; }
     else if (wino) { shape = IG_W64x256; WK = 1; WP = 8; MK = 2; MP = 1; }
-    else if (two) { shape = IG_64x256; WK = 1; WP = 4; MK = 2; MP = 2; }
+    else if (two && v.Kg > 32) { shape = IG_64x256; WK = 1; WP = 4; MK = 2; MP = 2; }
     else if (!bf16 && v.Kg > 64 && v.Kg <= 96) { shape = IG_96x256; WK = 1; WP = 8; MK = 3; MP = 1; }
     else if (v.Kg > 64) { shape = IG_128x256; WK = 2; WP = 4; MK = 2; MP = 2; }
     else if (v.Kg > 32) { shape = IG_64x512; WK = 1; WP = 8; MK = 2; MP = 2; }
@@ -426,9 +426,13 @@ inline bool plan_igemm(const ConvView &v, int n_cu, IgemmPlan *pl, bool bf16 = f
     for (int f = fixed;; f = 0) {
         // With more than 32 filters per group: two resident blocks of four waves rather than one of eight,
         // unless half the LDS forces a much worse row-block height on it (the scores are comparable).
+        // Up to 32 filters the block has four computing waves either way; two of them per compute unit pay when
+        // there are more tiles than compute units (layer 2a, 400 tiles: every block one whole tile, no fix-up
+        // pass, forward 20 -> 17 us), not when tiles are shared anyway (layer 2b, 100 tiles in 512 pieces: +23 %).
         IgemmPlan one, two;
         const bool ok1 = plan_igemm_kind(v, n_cu, &one, false, f);
-        const bool ok2 = v.Kg > 32 && plan_igemm_kind(v, n_cu, &two, false, f, true);
+        bool ok2 = plan_igemm_kind(v, n_cu, &two, false, f, true);
+        if (ok2 && v.Kg <= 32 && two.P.tiles <= n_cu) ok2 = false;
         if (ok2 && (!ok1 || two.score <= 1.15 * one.score)) { *pl = two; return true; }
         if (ok1) { *pl = one; return true; }
         if (f == 0) return false;
