@@ -87,8 +87,8 @@ typedef struct mcn_conv_desc {
  *   significand), with each product formed as w_hi*x_hi + w_hi*x_lo + w_lo*x_hi on the bf16 matrix core
  *   ("igemm_bf16x3").  Error per product below 1.2e-5 of |w||x| in the worst case, so the normalised
  *   error stays under the fp32 bars (1e-4 forward, 1e-3 backward) with a margin of eight or more, and
- *   measures about 1e-6; three bf16 MFMAs cost a fifth of one fp32 MFMA, which makes the two passes 2 to
- *   2.5 times as fast as MCN_PREC_FP32 on the 3x3 layers.  For callers who would otherwise trade fp32 for
+ *   measures 5e-7 to 6e-6; the two passes run 1.5 to 1.8 times as fast as under MCN_PREC_FP32 on the
+ *   3x3 layers of the benchmark (staging, not the matrix core, bounds them).  For callers who would otherwise trade fp32 for
  *   bf16 operands: this keeps 16 instead of 8 significant bits.  dzdw, dzdb and the geometries the bf16
  *   kernels do not cover compute as under MCN_PREC_FP32.
  * The environment variable MCN_NO_WINO=1 (read once per process) makes MCN_PREC_FP32 behave as
