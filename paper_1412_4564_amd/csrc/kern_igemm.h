@@ -892,42 +892,45 @@ __global__ __launch_bounds__(64 * (WK * WP + LW), WPE) void igemm_sk_kernel(Igem
 }
 
 // Sum the pieces of every tile that was shared between blocks, in block order, add the bias,
-// and write the tile.  One thread group per (block boundary, slice of the tile); a boundary
-// handles its tile only if it is the first boundary inside that tile.
+// and write the tile.  Grid: (left-over tiles, slices of a tile).
 template <int TK, int TQ>
 __global__ __launch_bounds__(256) void igemm_fixup_kernel(IgemmParams P, const float *__restrict__ part,
                                                           const float *__restrict__ bias, float *__restrict__ out) {
-    const int j = blockIdx.x + 1;                    // boundary between sharing blocks j-1 and j (by rank)
+    const int ts = blockIdx.x;                       // shared tile (the grid has one row of blocks per shared tile)
     const int tile_s0 = P.own * P.nblocks;           // the shared tiles start here; unit numbers are relative to them
-    const long long total = (long long)(P.tiles - tile_s0) * P.NU;
-    const SkSplit split = sk_split(total, P.nshare);
-    const long long B = sk_begin(split, j);
-    const int ts = (int)(B / P.NU);
     const int t = tile_s0 + ts;
     const long long t_lo = (long long)ts * P.NU, t_hi = t_lo + P.NU;
-    if (B == t_lo) return;                                        // boundary on a tile edge: nothing shared
-    if (sk_begin(split, j - 1) > t_lo) return;                    // an earlier boundary owns this tile
-    int kt, pt, rb, g;
-    decode_tile(P, t, &kt, &pt, &rb, &g);
-    const int OHW = P.OH * P.OW;
-    // the tile's pieces, in block order: block j-1's (its first segment if its range starts in this tile,
-    // else its second), then the first segments of the following blocks that have units of this tile
+    // The tile's pieces, in block order.  Sharing block of rank r holds the units [total*r/nshare, total*(r+1)/nshare):
+    // the first rank with units of this tile follows from one division (and a step of correction); its piece is
+    // its first segment if its range starts in this tile, else its second; the following ranks' pieces are first
+    // segments.  One thread lists them.
     constexpr int MAX_PIECES = 1024;
     __shared__ int slots[MAX_PIECES];
     __shared__ int npieces;
     if (threadIdx.x == 0) {
+        const long long total = (long long)(P.tiles - tile_s0) * P.NU;
+        const SkSplit split = sk_split(total, P.nshare);
+        int first = (int)(t_lo * P.nshare / total);
+        while (first + 1 < P.nshare && sk_begin(split, first + 1) <= t_lo) ++first;
+        while (first > 0 && sk_begin(split, first) > t_lo) --first;
         int n = 0;
-        for (int b = j - 1; b < P.nshare && n < MAX_PIECES; ++b) {
+        for (int b = first; b < P.nshare && n < MAX_PIECES; ++b) {
             const long long bb = sk_begin(split, b);
             if (bb >= t_hi) break;
-            if (sk_begin(split, b + 1) == bb) continue;                  // a block without shared units wrote nothing
+            const long long be = sk_begin(split, b + 1);
+            if (be == bb || be <= t_lo) continue;                        // a block without units of this tile wrote nothing
+            if (bb <= t_lo && be >= t_hi) { n = 0; break; }              // one block computed the whole tile and stored it itself
             slots[n++] = 2 * sk_share_block(P.nblocks, P.nshare, b) + (bb >= t_lo ? 0 : 1);
         }
         npieces = n;
     }
     __syncthreads();
+    if (npieces == 0) return;
+    int kt, pt, rb, g;
+    decode_tile(P, t, &kt, &pt, &rb, &g);
+    const int OHW = P.OH * P.OW;
     const int np = npieces;
-    // a thread takes four consecutive pixels of one filter: one 16-byte load per piece, two pieces in flight
+    // a thread takes four consecutive pixels of one filter: one 16-byte load per piece, up to four pieces in flight
     constexpr int Q4 = TQ / 4;
     for (int e4 = blockIdx.y * 256 + threadIdx.x; e4 < TK * Q4; e4 += gridDim.y * 256) {
         const int kloc = e4 / Q4, ql = 4 * (e4 - kloc * Q4);
@@ -942,6 +945,13 @@ __global__ __launch_bounds__(256) void igemm_fixup_kernel(IgemmParams P, const f
         const float *src = part + (size_t)kloc * TQ + ql;
         float4 acc = {bv, bv, bv, bv};
         int i = 0;
+        for (; i + 3 < np; i += 4) {                  // four pieces in flight, added in piece order
+            float4 v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) v[u] = *reinterpret_cast<const float4 *>(src + (size_t)slots[i + u] * (TK * TQ));
+#pragma unroll
+            for (int u = 0; u < 4; ++u) { acc.x += v[u].x; acc.y += v[u].y; acc.z += v[u].z; acc.w += v[u].w; }
+        }
         for (; i + 1 < np; i += 2) {
             const float4 v0 = *reinterpret_cast<const float4 *>(src + (size_t)slots[i] * (TK * TQ));
             const float4 v1 = *reinterpret_cast<const float4 *>(src + (size_t)slots[i + 1] * (TK * TQ));

@@ -90,6 +90,8 @@ int compute_units() {
 }
 
 constexpr int MAX_PHASES = 64;
+// blocks per shared tile in igemm_fixup_kernel (8 to 32 take the same time: the pass moves the pieces once)
+constexpr int IGEMM_FIXUP_SLICES = 16;
 
 // Plans depend only on the descriptor; planning walks candidate tilings, so the last few
 // descriptors' plans are remembered per host thread (host memory only, no device state).
@@ -183,7 +185,7 @@ int launch_igemm_inst(const IgemmPlan &pl, const float *in, const float *wpk, co
     // no tile is shared; tiles of a single unit cannot be cut, so every block's range holds whole tiles
     if (st || P.nblocks < 2 || P.own * P.nblocks == P.tiles || P.NU == 1) return st;
     constexpr int TK = WK * MK * 32, TQ = WP * MP * 32;
-    hipLaunchKernelGGL((igemm_fixup_kernel<TK, TQ>), dim3(P.nshare - 1, 16), dim3(256), 0, s, P, part, bias, out);
+    hipLaunchKernelGGL((igemm_fixup_kernel<TK, TQ>), dim3(P.tiles - P.own * P.nblocks, IGEMM_FIXUP_SLICES), dim3(256), 0, s, P, part, bias, out);
     return check_launch();
 }
 
@@ -209,7 +211,7 @@ int launch_igemm_wino(const IgemmPlan &pl, const float *in, const float *wpk, co
     IgemmParams F = P;
     F.TI = 2 * P.TI; F.QN = 2 * P.QN; F.Ho = P.wino_Ho; F.osi = P.osi / 2;
     F.dTI = make_div32(F.TI);
-    hipLaunchKernelGGL((igemm_fixup_kernel<TK, 2 * TQ>), dim3(P.nshare - 1, 16), dim3(256), 0, s, F, part, bias, out);
+    hipLaunchKernelGGL((igemm_fixup_kernel<TK, 2 * TQ>), dim3(P.tiles - P.own * P.nblocks, IGEMM_FIXUP_SLICES), dim3(256), 0, s, F, part, bias, out);
     return check_launch();
 }
 
@@ -237,7 +239,7 @@ int launch_igemm_bf16_inst(const IgemmPlan &pl, const float *in, const float *wp
     // no tile is shared; tiles of a single unit cannot be cut, so every block's range holds whole tiles
     if (st || P.nblocks < 2 || P.own * P.nblocks == P.tiles || P.NU == 1) return st;
     constexpr int TK = WK * MK * 32, TQ = WP * MP * 32;
-    hipLaunchKernelGGL((igemm_fixup_kernel<TK, TQ>), dim3(P.nshare - 1, 16), dim3(256), 0, s, P, part, bias, out);
+    hipLaunchKernelGGL((igemm_fixup_kernel<TK, TQ>), dim3(P.tiles - P.own * P.nblocks, IGEMM_FIXUP_SLICES), dim3(256), 0, s, P, part, bias, out);
     return check_launch();
 }
 
