@@ -51,6 +51,7 @@
 #include <stdint.h>
 #include <type_traits>
 #include "fastdiv.h"
+#include "streamk.h"
 
 namespace mcn {
 
@@ -163,46 +164,6 @@ __device__ __host__ inline MergedFilter merged_filter(const IgemmParams &P, int 
     f.i0 = ((pi - P.mPt) % P.osi + P.osi) % P.osi;
     f.j0 = ((pj - P.mPl) % P.osj + P.osj) % P.osj;
     return f;
-}
-
-// Blocks on consecutive hardware ids land on different XCDs; give each XCD a contiguous
-// share of the work so that neighbouring tiles (shared halo, same weights) meet in one L2.
-__device__ __host__ inline int sk_virtual_block(int b, int nblocks) {
-    return (nblocks % 8 == 0) ? (b % 8) * (nblocks / 8) + b / 8 : b;
-}
-__device__ __host__ inline long long sk_begin(long long total, int nblocks, int vb) {
-    return total * vb / nblocks;
-}
-// The same value for many vb at the price of one 64-bit division (which takes a GPU thread some hundred
-// instructions): with total = q * nblocks + r,  total * vb / nblocks = q * vb + r * vb / nblocks, and r * vb stays
-// below nblocks^2 (nblocks <= 65535), a 32-bit division.
-struct SkSplit {
-    long long q;
-    unsigned r, n;
-};
-__device__ __host__ inline SkSplit sk_split(long long total, int nblocks) {
-    SkSplit s;
-    s.q = total / nblocks;
-    s.r = (unsigned)(total - s.q * nblocks);
-    s.n = (unsigned)nblocks;
-    return s;
-}
-__device__ __host__ inline long long sk_begin(const SkSplit &s, int vb) {
-    return s.q * vb + (long long)(s.r * (unsigned)vb / s.n);
-}
-// Rank of virtual block vb among the nshare sharing blocks (in virtual order), or -1; and its inverse.  With
-// nshare < nblocks (both multiples of 8) the sharing blocks are hardware ids 0 .. nshare-1, i.e. the first
-// nshare/8 virtual blocks of each XCD's run of nblocks/8.
-__device__ __host__ inline int sk_share_rank(int nblocks, int nshare, int vb) {
-    if (nshare == nblocks) return vb;
-    const int G = nblocks / 8, S = nshare / 8;
-    const int x = vb / G, i = vb - x * G;
-    return i < S ? x * S + i : -1;
-}
-__device__ __host__ inline int sk_share_block(int nblocks, int nshare, int r) {
-    if (nshare == nblocks) return r;
-    const int G = nblocks / 8, S = nshare / 8;
-    return (r / S) * G + r % S;
 }
 
 // Tile order: filter tiles fastest (they share the slab), then the row blocks of one strip of
@@ -899,7 +860,6 @@ __global__ __launch_bounds__(256) void igemm_fixup_kernel(IgemmParams P, const f
     const int ts = blockIdx.x;                       // shared tile (the grid has one row of blocks per shared tile)
     const int tile_s0 = P.own * P.nblocks;           // the shared tiles start here; unit numbers are relative to them
     const int t = tile_s0 + ts;
-    const long long t_lo = (long long)ts * P.NU, t_hi = t_lo + P.NU;
     // The tile's pieces, in block order.  Sharing block of rank r holds the units [total*r/nshare, total*(r+1)/nshare):
     // the first rank with units of this tile follows from one division (and a step of correction); its piece is
     // its first segment if its range starts in this tile, else its second; the following ranks' pieces are first
@@ -907,23 +867,8 @@ __global__ __launch_bounds__(256) void igemm_fixup_kernel(IgemmParams P, const f
     constexpr int MAX_PIECES = 1024;
     __shared__ int slots[MAX_PIECES];
     __shared__ int npieces;
-    if (threadIdx.x == 0) {
-        const long long total = (long long)(P.tiles - tile_s0) * P.NU;
-        const SkSplit split = sk_split(total, P.nshare);
-        int first = (int)(t_lo * P.nshare / total);
-        while (first + 1 < P.nshare && sk_begin(split, first + 1) <= t_lo) ++first;
-        while (first > 0 && sk_begin(split, first) > t_lo) --first;
-        int n = 0;
-        for (int b = first; b < P.nshare && n < MAX_PIECES; ++b) {
-            const long long bb = sk_begin(split, b);
-            if (bb >= t_hi) break;
-            const long long be = sk_begin(split, b + 1);
-            if (be == bb || be <= t_lo) continue;                        // a block without units of this tile wrote nothing
-            if (bb <= t_lo && be >= t_hi) { n = 0; break; }              // one block computed the whole tile and stored it itself
-            slots[n++] = 2 * sk_share_block(P.nblocks, P.nshare, b) + (bb >= t_lo ? 0 : 1);
-        }
-        npieces = n;
-    }
+    if (threadIdx.x == 0)
+        npieces = sk_tile_pieces((long long)(P.tiles - tile_s0) * P.NU, P.NU, P.nblocks, P.nshare, ts, slots, MAX_PIECES);
     __syncthreads();
     if (npieces == 0) return;
     int kt, pt, rb, g;

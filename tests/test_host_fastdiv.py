@@ -13,3 +13,13 @@ def test_reciprocal_divisions_are_exact(tmp_path):
                            "-o", exe, os.path.join(ROOT, "tests", "fastdiv_check.cpp")])
     r = subprocess.run([exe], capture_output=True, text=True, timeout=300)
     assert r.returncode == 0 and r.stdout.startswith("OK"), r.stdout[-500:] + r.stderr[-500:]
+
+
+def test_stream_k_piece_lists_match_a_simulation_of_the_blocks(tmp_path):
+    """csrc/streamk.h compiles as plain C++: the pieces the fix-up pass adds for every left-over tile against the
+    segments the main kernel's blocks write (tests/streamk_check.cpp)."""
+    exe = str(tmp_path / "streamk_check")
+    subprocess.check_call(["g++", "-O2", "-std=c++17", "-Wall", "-I", os.path.join(ROOT, "paper_1412_4564_amd", "csrc"),
+                           "-o", exe, os.path.join(ROOT, "tests", "streamk_check.cpp")])
+    r = subprocess.run([exe], capture_output=True, text=True, timeout=300)
+    assert r.returncode == 0 and r.stdout.startswith("OK"), r.stdout[-500:] + r.stderr[-500:]
