@@ -597,6 +597,9 @@ inline bool plan_wgrad(const ConvView &v, int n_cu, WgradPlan *pl, bool wino = f
     if (P.nchunks > 0 && bestOcc == 2 && P.nblocks > n_cu && NU / P.nchunks >= 16) {
         P.w_first = 3; P.w_later = 2;      // measured on layers 4a/4b: 11:9 -1.5 %, 3:2 -2.2 %, 13:7 +1 %
     }
+    // one tile, cut into a chunk per block: the blocks of an XCD take the units of their common range in turn
+    // (WgradParams::deal; remainders in 32 bits: NU < 2^30 and rem * chunk < nchunks^2)
+    P.deal = (P.nchunks >= 16 && P.tiles == 1 && P.nchunks % 8 == 0 && P.w_first == P.w_later && P.nchunks <= 32768) ? 1 : 0;
     pl->occupancy = bestOcc;
     pl->wino = wino;
     pl->partial_floats = P.nblocks > 1 ? (size_t)2 * P.nblocks * TK * TR * (wino ? 3 : 1) : 0;

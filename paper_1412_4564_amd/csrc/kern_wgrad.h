@@ -70,6 +70,12 @@ struct WgradParams {
     // compute unit the one dispatched first gets more of the matrix core; with equal chunks it finishes
     // early and leaves the other to run alone, which uses the core less well.
     int n_first, w_first, w_later;
+    // deal = 1 (one tile, equal chunk weights, a grid that is a multiple of 8): the chunks of the blocks on one XCD
+    // cover a contiguous range of the tile's units between them, and the blocks take its units in turn (block i
+    // of the XCD's n: units i, n + i, 2n + i, ... of the range) instead of a contiguous chunk each.  Units that
+    // are adjacent in the plane, which share memory lines (half a line of dzdy per 16-row column run, the halo
+    // rows and columns of x), are then fetched by the XCD's blocks at the same time and meet in its L2.
+    int deal;
     // WINO kernels: TIE is TI rounded up to a multiple of 4 (two pairs of rows per MFMA step) and SRP, CP, PCHP
     // are even (8-byte LDS reads); tiles are counted in (filter column, channel) pairs, TR of them = 3*TR
     // coefficients.
@@ -134,6 +140,7 @@ __global__ __launch_bounds__(64 * (WK * WR + WGRAD_LOADER_WAVES), WPE) void wgra
 
     int vb;
     long long ub, ue;
+    int deal_n = 0, deal_q = 0, deal_cl = 0, deal_base = 0, deal_long = 0;
     if (P.nchunks > 0) {
         vb = wg_chunk_virtual_block(blockIdx.x, gridDim.x);
         if (vb >= P.nblocks) return;
@@ -152,6 +159,14 @@ __global__ __launch_bounds__(64 * (WK * WR + WGRAD_LOADER_WAVES), WPE) void wgra
         }
         ub = (long long)tile * P.NU + (long long)P.NU * w_before / w_all;
         ue = (long long)tile * P.NU + (long long)P.NU * (w_before + w_mine) / w_all;
+        if (P.deal) {
+            // chunk c holds q or q + 1 units (ub = q*c + rem*c/nchunks); the XCD's chunks are c0 .. c0 + n - 1
+            const int q = P.NU / P.nchunks, rem = P.NU - q * P.nchunks;
+            const int c0 = (vb / G8) * G8, cl = vb - c0;
+            deal_n = G8; deal_q = q; deal_cl = cl;
+            deal_base = q * c0 + rem * c0 / P.nchunks;
+            deal_long = rem * (c0 + cl) / P.nchunks - rem * c0 / P.nchunks;      // chunks before this one with q + 1 units
+        }
     } else {
         vb = sk_virtual_block(blockIdx.x, P.nblocks);
         const long long total = (long long)P.tiles * P.NU;
@@ -497,14 +512,21 @@ __global__ __launch_bounds__(64 * (WK * WR + WGRAD_LOADER_WAVES), WPE) void wgra
         // Fetching wave: unit it+1 goes into the buffer that the computing waves left at the barrier of
         // iteration it; its own loads have landed before it joins the next barrier.  One barrier per unit,
         // the same number as the computing waves pass.
+        // dealt units (WgradParams::deal): in round k < q the XCD's blocks take units base + n*k + i; in the last,
+        // partial round the blocks with q + 1 units take the rest in block order
+        auto dealt_unit = [&](int k) { return deal_base + deal_n * k + (k < deal_q ? deal_cl : deal_long); };
         setup_load(t_l);
-        issue_loads(uu_l, 0);
+        issue_loads(P.deal ? dealt_unit(0) : uu_l, 0);
         for (int it = 0; it < nunits; ++it) {
             __builtin_amdgcn_s_waitcnt(WAIT_VMCNT0);
             lds_barrier();
             if (it + 1 < nunits) {
-                if (++uu_l == NU) { uu_l = 0; ++t_l; setup_load(t_l); }
-                issue_loads(uu_l, (it + 1) & 1);
+                if (P.deal) {
+                    issue_loads(dealt_unit(it + 1), (it + 1) & 1);
+                } else {
+                    if (++uu_l == NU) { uu_l = 0; ++t_l; setup_load(t_l); }
+                    issue_loads(uu_l, (it + 1) & 1);
+                }
             }
         }
         return;
