@@ -140,7 +140,7 @@ __global__ __launch_bounds__(64 * (WK * WR + WGRAD_LOADER_WAVES), WPE) void wgra
 
     int vb;
     long long ub, ue;
-    int deal_n = 0, deal_q = 0, deal_cl = 0, deal_base = 0, deal_long = 0;
+    DealSplit deal = {};
     if (P.nchunks > 0) {
         vb = wg_chunk_virtual_block(blockIdx.x, gridDim.x);
         if (vb >= P.nblocks) return;
@@ -159,14 +159,7 @@ __global__ __launch_bounds__(64 * (WK * WR + WGRAD_LOADER_WAVES), WPE) void wgra
         }
         ub = (long long)tile * P.NU + (long long)P.NU * w_before / w_all;
         ue = (long long)tile * P.NU + (long long)P.NU * (w_before + w_mine) / w_all;
-        if (P.deal) {
-            // chunk c holds q or q + 1 units (ub = q*c + rem*c/nchunks); the XCD's chunks are c0 .. c0 + n - 1
-            const int q = P.NU / P.nchunks, rem = P.NU - q * P.nchunks;
-            const int c0 = (vb / G8) * G8, cl = vb - c0;
-            deal_n = G8; deal_q = q; deal_cl = cl;
-            deal_base = q * c0 + rem * c0 / P.nchunks;
-            deal_long = rem * (c0 + cl) / P.nchunks - rem * c0 / P.nchunks;      // chunks before this one with q + 1 units
-        }
+        if (P.deal) deal = make_deal(P.NU, P.nchunks, G8, vb);      // one tile: the chunk is vb
     } else {
         vb = sk_virtual_block(blockIdx.x, P.nblocks);
         const long long total = (long long)P.tiles * P.NU;
@@ -512,17 +505,14 @@ __global__ __launch_bounds__(64 * (WK * WR + WGRAD_LOADER_WAVES), WPE) void wgra
         // Fetching wave: unit it+1 goes into the buffer that the computing waves left at the barrier of
         // iteration it; its own loads have landed before it joins the next barrier.  One barrier per unit,
         // the same number as the computing waves pass.
-        // dealt units (WgradParams::deal): in round k < q the XCD's blocks take units base + n*k + i; in the last,
-        // partial round the blocks with q + 1 units take the rest in block order
-        auto dealt_unit = [&](int k) { return deal_base + deal_n * k + (k < deal_q ? deal_cl : deal_long); };
         setup_load(t_l);
-        issue_loads(P.deal ? dealt_unit(0) : uu_l, 0);
+        issue_loads(P.deal ? dealt_unit(deal, 0) : uu_l, 0);
         for (int it = 0; it < nunits; ++it) {
             __builtin_amdgcn_s_waitcnt(WAIT_VMCNT0);
             lds_barrier();
             if (it + 1 < nunits) {
                 if (P.deal) {
-                    issue_loads(dealt_unit(it + 1), (it + 1) & 1);
+                    issue_loads(dealt_unit(deal, it + 1), (it + 1) & 1);
                 } else {
                     if (++uu_l == NU) { uu_l = 0; ++t_l; setup_load(t_l); }
                     issue_loads(uu_l, (it + 1) & 1);

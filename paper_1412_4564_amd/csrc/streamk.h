@@ -70,4 +70,23 @@ MCN_HOST_DEVICE inline int sk_tile_pieces(long long total, int NU, int nblocks, 
     return n;
 }
 
+// Dealt unit order of a tile cut into nchunks chunks, one per block (kern_wgrad.h, WgradParams::deal).  Chunk c
+// holds the q or q + 1 units [NU*c/nchunks, NU*(c+1)/nchunks) by count; the chunks c0 .. c0 + n - 1 of the blocks on
+// one XCD cover one contiguous range between them, and their blocks take its units in turn: in round k < q block i
+// takes unit base + n*k + i, and in the last, partial round the blocks with q + 1 units take the rest in block order.
+struct DealSplit {
+    int n, q, i, base, n_long;      // chunks on the XCD, units per short chunk, this chunk's place among them,
+                                    // first unit of the XCD's range, chunks before this one with q + 1 units
+};
+MCN_HOST_DEVICE inline DealSplit make_deal(int NU, int nchunks, int n, int chunk) {
+    DealSplit d;
+    const int q = NU / nchunks, rem = NU - q * nchunks;          // rem * chunk < nchunks^2: 32 bits for nchunks <= 32768
+    const int c0 = (chunk / n) * n;
+    d.n = n; d.q = q; d.i = chunk - c0;
+    d.base = q * c0 + rem * c0 / nchunks;
+    d.n_long = rem * chunk / nchunks - rem * c0 / nchunks;
+    return d;
+}
+MCN_HOST_DEVICE inline int dealt_unit(const DealSplit &d, int k) { return d.base + d.n * k + (k < d.q ? d.i : d.n_long); }
+
 }  // namespace mcn

@@ -72,6 +72,29 @@ int main() {
         if (check(tiles, NU, nblocks, (rnd() & 1) ? nblocks : nblocks / 2)) return 1;
         ++cases;
     }
+    // dealt unit order: every unit of the tile exactly once, each XCD's blocks inside their common range, and the
+    // units of one round adjacent
+    for (int i = 0; i < 4000; ++i) {
+        const int n = 2 + rnd() % 64;                   // chunks per XCD
+        const int nchunks = 8 * n;
+        const int NU = nchunks + rnd() % (i < 2000 ? 4 * nchunks : 100000);
+        std::vector<int> seen(NU, 0);
+        for (int c = 0; c < nchunks; ++c) {
+            const long long ub = sk_begin((long long)NU, nchunks, c), ue = sk_begin((long long)NU, nchunks, c + 1);
+            const DealSplit d = make_deal(NU, nchunks, n, c);
+            const int c0 = (c / n) * n;
+            const long long lo = sk_begin((long long)NU, nchunks, c0), hi = sk_begin((long long)NU, nchunks, c0 + n);
+            for (int k = 0; k < (int)(ue - ub); ++k) {
+                const int u = dealt_unit(d, k);
+                if (u < lo || u >= hi) { printf("dealt unit %d outside [%lld, %lld): NU %d nchunks %d chunk %d k %d\n", u, lo, hi, NU, nchunks, c, k); return 1; }
+                if (k < d.q && u != lo + (long long)n * k + (c - c0)) { printf("round %d not adjacent: NU %d nchunks %d chunk %d\n", k, NU, nchunks, c); return 1; }
+                ++seen[u];
+            }
+        }
+        for (int u = 0; u < NU; ++u)
+            if (seen[u] != 1) { printf("unit %d taken %d times: NU %d nchunks %d\n", u, seen[u], NU, nchunks); return 1; }
+        ++cases;
+    }
     printf("OK %lld cases\n", cases);
     return 0;
 }
