@@ -799,6 +799,16 @@ __global__ __launch_bounds__(64 * (WK * WP + LW), WPE) void igemm_sk_kernel(Igem
         if (done == n_own) { t = t_s; uu = uu_s; }
         else if (++uu == NU) { uu = 0; ++t; }
     };
+    // The whole tiles of a block are numbered vb*own .. vb*own + own - 1; which tiles those are is dealt among the
+    // blocks of an XCD (block i of the XCD's G takes the tiles i, G + i, 2G + i, ... of the XCD's run): tiles that
+    // are neighbours in the plane, which read the same halo rows and the same weights, are then in flight on one
+    // XCD at the same time and meet in its L2.  The left-over tiles keep their numbers.
+    auto tile_of = [&](int t) {
+        if (t >= tile_s0 || (P.nblocks & 7) != 0) return t;
+        const int b = t / P.own, j = t - b * P.own;
+        const int G = P.nblocks >> 3, x = b / G, i = b - x * G;
+        return (x * G) * P.own + j * G + i;
+    };
     int t_c = n_own ? vb * P.own : t_s;   // compute-side tile and unit
     int uu_c = n_own ? 0 : uu_s;
     int t_l = t_c, uu_l = uu_c;           // the load side runs one unit ahead
@@ -812,7 +822,7 @@ __global__ __launch_bounds__(64 * (WK * WP + LW), WPE) void igemm_sk_kernel(Igem
         // Fetching wave: unit it+1 goes into the buffer that the computing waves left at the barrier of
         // iteration it; its own loads have landed before it joins the next barrier.  One barrier per
         // unit, as many as the computing waves pass.
-        setup_load(t_l);
+        setup_load(tile_of(t_l));
         issue_loads(uu_l, 0);
         for (int it = 0; it < nunits; ++it) {
             __builtin_amdgcn_s_waitcnt(WAIT_VMCNT0);
@@ -820,14 +830,14 @@ __global__ __launch_bounds__(64 * (WK * WP + LW), WPE) void igemm_sk_kernel(Igem
             if (it + 1 < nunits) {
                 const int t_prev = t_l;
                 advance(t_l, uu_l, it + 1);
-                if (t_l != t_prev) setup_load(t_l);
+                if (t_l != t_prev) setup_load(tile_of(t_l));
                 issue_loads(uu_l, (it + 1) & 1);
             }
         }
         return;
     }
     bool whole = segment_is_whole(t_c, uu_c);
-    setup_compute(t_c);
+    setup_compute(tile_of(t_c));
 
     for (int it = 0; it < nunits; ++it) {
         lds_barrier();      // unit it is in LDS (the fetching waves waited for it) and the other buffer is free; results
@@ -844,7 +854,7 @@ __global__ __launch_bounds__(64 * (WK * WP + LW), WPE) void igemm_sk_kernel(Igem
             if (!last) {
                 advance(t_c, uu_c, it + 1);
                 whole = segment_is_whole(t_c, uu_c);
-                setup_compute(t_c);
+                setup_compute(tile_of(t_c));
             }
         } else {
             ++uu_c;
