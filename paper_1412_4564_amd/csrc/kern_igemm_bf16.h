@@ -410,6 +410,14 @@ __global__ __launch_bounds__(64 * (WK * WP + LW), WPE) void igemm_bf16_kernel(Ig
         if (++uu == NU) { uu = 0; ++t; }
         return P.NTR == 1 || uu % P.NTR == 0;
     };
+    // the whole tiles of a block, dealt among the blocks of its XCD as in igemm_sk_kernel (neighbouring tiles are
+    // then in flight on one XCD together and share its L2)
+    auto tile_of = [&](int t) {
+        if (t >= tile_s0 || (P.nblocks & 7) != 0) return t;
+        const int b = t / P.own, j = t - b * P.own;
+        const int G = P.nblocks >> 3, x = b / G, i = b - x * G;
+        return (x * G) * P.own + j * G + i;
+    };
     int t_c = n_own ? vb * P.own : t_s;   // compute-side tile and unit
     int uu_c = n_own ? 0 : uu_s;
     int t_l = t_c, uu_l = uu_c;           // the load side runs one unit ahead
@@ -425,7 +433,7 @@ __global__ __launch_bounds__(64 * (WK * WP + LW), WPE) void igemm_bf16_kernel(Ig
         // Slab buffers are used in turn, one per group of channels: the buffer written for the next group was last
         // read by the group before the current one, whose units ended at an earlier barrier.
         int slab = 0;
-        setup_load(t_l);
+        setup_load(tile_of(t_l));
         issue_loads(uu_l, 0, true);
         write_slab(0);
         for (int it = 0; it < nunits; ++it) {
@@ -434,7 +442,7 @@ __global__ __launch_bounds__(64 * (WK * WP + LW), WPE) void igemm_bf16_kernel(Ig
             if (it + 1 < nunits) {
                 const int t_prev = t_l;
                 const bool fresh = advance(t_l, uu_l, it + 1);
-                if (t_l != t_prev) setup_load(t_l);
+                if (t_l != t_prev) setup_load(tile_of(t_l));
                 issue_loads(uu_l, (it + 1) & 1, fresh);
                 if (fresh) { slab ^= 1; write_slab(slab); }
             }
@@ -442,7 +450,7 @@ __global__ __launch_bounds__(64 * (WK * WP + LW), WPE) void igemm_bf16_kernel(Ig
         return;
     }
     bool whole = segment_is_whole(t_c, uu_c);
-    setup_compute(t_c);
+    setup_compute(tile_of(t_c));
 
     int slab_c = 0;                                // slab buffer of the current unit (see the staging waves)
     for (int it = 0; it < nunits; ++it) {
@@ -460,7 +468,7 @@ __global__ __launch_bounds__(64 * (WK * WP + LW), WPE) void igemm_bf16_kernel(Ig
                 advance(t_c, uu_c, it + 1);        // a new tile or the jump to the shared range: a new slab either way
                 slab_c ^= 1;
                 whole = segment_is_whole(t_c, uu_c);
-                setup_compute(t_c);
+                setup_compute(tile_of(t_c));
             }
         } else {
             ++uu_c;
